@@ -1,0 +1,224 @@
+"""Oracle scattering transforms (fp64, numpy) -- TEST INFRASTRUCTURE, not the product.
+
+Only tests, the smoke check and the benchmark's cpu_baseline leg may import this
+package; it shares no code with the HIP library.
+
+Two families of functions:
+
+* ``scattering2d`` / ``scattering1d`` -- the cascade as the paper's section 2
+  ("Implementation") describes it: every periodic convolution is a product in the
+  Fourier domain, every signal produced by filtering (and modulus) is downsampled.
+  The paper gives no schedule; the reading taken is: after a wavelet of octave j the
+  signal lives on the grid subsampled by 2^j (sample phase 0), after phi_J on the
+  grid subsampled by 2^J.  A filter applied to a signal that already lives at
+  resolution r is the full-resolution filter with its Fourier blocks summed
+  (``fold``), i.e. the spatial filter sampled at stride 2^r and rescaled.
+  This is an approximation of the definition for S1 and S2 (the modulus aliases a
+  little when subsampled) and exact for S0 and for the first wavelet-modulus layer.
+
+* ``scattering2d_plain`` / ``scattering1d_plain`` -- the paper's three equations of
+  section 2 ("Definition") taken literally: every convolution at full resolution,
+  the result sampled at multiples of 2^J.  Used as a loose cross-check only.
+
+Second-order index set: the "typical" choice of section 2, |lambda_2| > |lambda_1|,
+read as octave j2 strictly greater than octave j1, all orientations.
+
+Output channel order: S0; then S1 ordered by (j1, theta1) -- in 1-D by wavelet
+index k; then S2 ordered by (j1, theta1, j2, theta2) -- in 1-D by (k, j2).
+FFT convention: forward sum x[n] exp(-2 pi i k n / N), inverse carries 1/N per axis.
+"""
+import numpy as np
+
+from . import filters
+
+
+# ------------------------------------------------------------------ index tables
+
+def coeff_index_2d(J, L, max_order=2):
+    """Rows (order, j1, theta1, j2, theta2); unused fields are -1."""
+    rows = [(0, -1, -1, -1, -1)]
+    for j1 in range(J):
+        for t1 in range(L):
+            rows.append((1, j1, t1, -1, -1))
+    if max_order >= 2:
+        for j1 in range(J):
+            for t1 in range(L):
+                for j2 in range(j1 + 1, J):
+                    for t2 in range(L):
+                        rows.append((2, j1, t1, j2, t2))
+    return rows
+
+
+def coeff_index_1d(J, Q, max_order=2):
+    """Rows (order, j1, k1, j2, k2): k1 = first-order wavelet index (octave j1 =
+    k1 // Q), k2 = second-order wavelet index (= its octave j2).  Unused = -1."""
+    rows = [(0, -1, -1, -1, -1)]
+    for k in range(J * Q):
+        rows.append((1, k // Q, k, -1, -1))
+    if max_order >= 2:
+        for k in range(J * Q):
+            for j2 in range(k // Q + 1, J):
+                rows.append((2, k // Q, k, j2, j2))
+    return rows
+
+
+# ------------------------------------------------------------------ fold / sub
+
+def fold(F, r, axes):
+    """Sum the 2^r Fourier blocks along each of `axes` (the last len(axes) axes).
+
+    fold(F)[k] = sum_a F[k + a*M], M = N / 2^r.  No normalisation.
+    """
+    out = F
+    for ax in axes:
+        ax = ax % out.ndim
+        n = out.shape[ax]
+        shp = out.shape[:ax] + (1 << r, n >> r) + out.shape[ax + 1:]
+        out = out.reshape(shp).sum(axis=ax)
+    return out
+
+
+def sub(F, r, axes):
+    """Fourier transform of the signal subsampled by 2^r at phase 0 along `axes`."""
+    return fold(F, r, axes) / float(1 << (r * len(axes)))
+
+
+# ------------------------------------------------------------------ 2-D cascade
+
+def scattering2d(x, J, L, max_order=2, bank=None):
+    """Order-<=2 scattering of real images, Fourier-domain cascade with subsampling.
+
+    x: array (..., N_r, N_c), N_r and N_c multiples of 2^J.
+    Returns float64 array (..., K, N_r >> J, N_c >> J).
+    """
+    x = np.asarray(x, dtype=np.float64)
+    n_r, n_c = x.shape[-2:]
+    if bank is None:
+        bank = filters.bank_2d(n_r, n_c, J, L)
+    psi_hat, phi_hat = bank['psi_hat'], bank['phi_hat']
+    ax = (-2, -1)
+    lead = x.shape[:-2]
+    X = np.fft.fft2(x)
+    out = []
+    # S0 = (x conv phi_J) sampled at 2^J n
+    out.append(np.fft.ifft2(sub(X * phi_hat, J, ax)).real)
+    s2 = []
+    for j1 in range(J):
+        phi_j1 = fold(phi_hat, j1, ax)
+        for t1 in range(L):
+            U1 = np.abs(np.fft.ifft2(sub(X * psi_hat[j1, t1], j1, ax)))
+            U1h = np.fft.fft2(U1)
+            out.append(np.fft.ifft2(sub(U1h * phi_j1, J - j1, ax)).real)
+            if max_order < 2:
+                continue
+            for j2 in range(j1 + 1, J):
+                phi_j2 = fold(phi_hat, j2, ax)
+                for t2 in range(L):
+                    psi_r = fold(psi_hat[j2, t2], j1, ax)
+                    V = np.abs(np.fft.ifft2(sub(U1h * psi_r, j2 - j1, ax)))
+                    Vh = np.fft.fft2(V)
+                    s2.append(np.fft.ifft2(sub(Vh * phi_j2, J - j2, ax)).real)
+    out.extend(s2)
+    return np.stack(out, axis=len(lead))
+
+
+def scattering2d_plain(x, J, L, max_order=2, bank=None):
+    """The three defining equations at full resolution, sampled at 2^J n."""
+    x = np.asarray(x, dtype=np.float64)
+    n_r, n_c = x.shape[-2:]
+    if bank is None:
+        bank = filters.bank_2d(n_r, n_c, J, L)
+    psi_hat, phi_hat = bank['psi_hat'], bank['phi_hat']
+    lead = x.shape[:-2]
+    s = 1 << J
+    X = np.fft.fft2(x)
+    out = [np.fft.ifft2(X * phi_hat).real[..., ::s, ::s]]
+    s2 = []
+    for j1 in range(J):
+        for t1 in range(L):
+            U1 = np.abs(np.fft.ifft2(X * psi_hat[j1, t1]))
+            U1h = np.fft.fft2(U1)
+            out.append(np.fft.ifft2(U1h * phi_hat).real[..., ::s, ::s])
+            if max_order < 2:
+                continue
+            for j2 in range(j1 + 1, J):
+                for t2 in range(L):
+                    V = np.abs(np.fft.ifft2(U1h * psi_hat[j2, t2]))
+                    s2.append(np.fft.ifft2(np.fft.fft2(V) * phi_hat).real[..., ::s, ::s])
+    out.extend(s2)
+    return np.stack(out, axis=len(lead))
+
+
+# ------------------------------------------------------------------ 1-D cascade
+
+def scattering1d(x, J, Q, max_order=2, bank=None):
+    """Order-<=2 scattering of real 1-D signals, Fourier-domain cascade.
+
+    x: array (..., N), N a multiple of 2^J.  Returns float64 (..., K, N >> J).
+    """
+    x = np.asarray(x, dtype=np.float64)
+    n = x.shape[-1]
+    if bank is None:
+        bank = filters.bank_1d(n, J, Q)
+    psi1_hat, psi2_hat, phi_hat = bank['psi1_hat'], bank['psi2_hat'], bank['phi_hat']
+    ax = (-1,)
+    lead = x.shape[:-1]
+    X = np.fft.fft(x)
+    out = [np.fft.ifft(sub(X * phi_hat, J, ax)).real]
+    s2 = []
+    for k in range(J * Q):
+        j1 = bank['j1'][k]
+        U1 = np.abs(np.fft.ifft(sub(X * psi1_hat[k], j1, ax)))
+        U1h = np.fft.fft(U1)
+        out.append(np.fft.ifft(sub(U1h * fold(phi_hat, j1, ax), J - j1, ax)).real)
+        if max_order < 2:
+            continue
+        for j2 in range(j1 + 1, J):
+            psi_r = fold(psi2_hat[j2], j1, ax)
+            V = np.abs(np.fft.ifft(sub(U1h * psi_r, j2 - j1, ax)))
+            Vh = np.fft.fft(V)
+            s2.append(np.fft.ifft(sub(Vh * fold(phi_hat, j2, ax), J - j2, ax)).real)
+    out.extend(s2)
+    return np.stack(out, axis=len(lead))
+
+
+def scattering1d_plain(x, J, Q, max_order=2, bank=None):
+    """The three defining equations at full resolution, sampled at 2^J n (1-D)."""
+    x = np.asarray(x, dtype=np.float64)
+    n = x.shape[-1]
+    if bank is None:
+        bank = filters.bank_1d(n, J, Q)
+    psi1_hat, psi2_hat, phi_hat = bank['psi1_hat'], bank['psi2_hat'], bank['phi_hat']
+    lead = x.shape[:-1]
+    s = 1 << J
+    X = np.fft.fft(x)
+    out = [np.fft.ifft(X * phi_hat).real[..., ::s]]
+    s2 = []
+    for k in range(J * Q):
+        j1 = bank['j1'][k]
+        U1 = np.abs(np.fft.ifft(X * psi1_hat[k]))
+        U1h = np.fft.fft(U1)
+        out.append(np.fft.ifft(U1h * phi_hat).real[..., ::s])
+        if max_order < 2:
+            continue
+        for j2 in range(j1 + 1, J):
+            V = np.abs(np.fft.ifft(U1h * psi2_hat[j2]))
+            s2.append(np.fft.ifft(np.fft.fft(V) * phi_hat).real[..., ::s])
+    out.extend(s2)
+    return np.stack(out, axis=len(lead))
+
+
+def first_layer_2d(x, J, L, bank=None):
+    """U1[j1, theta1] = |x conv psi| on the grid subsampled by 2^j1 (exact, no
+    approximation involved).  Returns a list over j1 of arrays (..., L, M, M)."""
+    x = np.asarray(x, dtype=np.float64)
+    n_r, n_c = x.shape[-2:]
+    if bank is None:
+        bank = filters.bank_2d(n_r, n_c, J, L)
+    X = np.fft.fft2(x)
+    res = []
+    for j1 in range(J):
+        res.append(np.stack(
+            [np.abs(np.fft.ifft2(sub(X * bank['psi_hat'][j1, t], j1, (-2, -1))))
+             for t in range(L)], axis=x.ndim - 2))
+    return res
