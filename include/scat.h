@@ -1,0 +1,128 @@
+/*
+ * scat.h -- C ABI of the MI355X wavelet scattering library (order <= 2, 1-D and 2-D).
+ *
+ * The operation is the scattering transform of the Kymatio paper (arXiv 1812.11214),
+ * section 2: with a lowpass phi_J and wavelet banks psi_lambda on a periodic grid,
+ *
+ *     S0 x[n]                = (x (*) phi_J)[n]
+ *     S1 x[n, l1]            = (|x (*) psi_l1| (*) phi_J)[n]
+ *     S2 x[n, l1, l2]        = (||x (*) psi_l1| (*) psi_l2| (*) phi_J)[n],  |l2| > |l1|
+ *
+ * ((*) = periodic convolution), computed as that section's "Implementation" paragraph
+ * describes: products in the Fourier domain, every filtered signal downsampled, the
+ * tree walked one first-order branch after the other.  Downsampling schedule (the
+ * paper names none): a signal filtered by a wavelet of octave j lives on the grid
+ * subsampled by 2^j, the output on the grid subsampled by 2^J, sample phase 0.
+ *
+ * Filters (the paper names Morlet wavelets and gives no constants): sigma_j = 0.8*2^j,
+ * xi_j = (3 pi/4) 2^-j, 2-D slant 4/L and angles pi*l/L, phi_J a Gaussian with
+ * sigma = 0.8*2^J; 1-D first order has Q wavelets per octave, xi_k = (3 pi/4) 2^(-k/Q),
+ * sigma_k = 0.3 pi / (xi_k (1 - 2^(-1/Q))) (0.8*2^k when Q = 1), second order one
+ * wavelet per octave.
+ *
+ * All pointers named `in`/`out` are DEVICE pointers; everything else is host memory.
+ * Every function returns a status and never throws or aborts.  The library needs a
+ * GPU for scat_plan_create and scat_forward only.
+ */
+#ifndef SCAT_H
+#define SCAT_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct scat_plan scat_plan; /* opaque, owned by the library */
+
+typedef enum {
+  SCAT_OK = 0,
+  SCAT_ERR_ARG = 1,    /* bad dims / J / L / Q / max_order / batch / index */
+  SCAT_ERR_SHAPE = 2,  /* a side is not a power of two, or is smaller than 2^J */
+  SCAT_ERR_ALLOC = 3,  /* host or device allocation failed */
+  SCAT_ERR_DEVICE = 4, /* a HIP call failed (no device, launch error, ...) */
+  SCAT_ERR_NULL = 5    /* a required pointer is NULL */
+} scat_status;
+
+/*
+ * Build a plan: coefficient index table, filter bank (evaluated in fp64 from the
+ * analytic Fourier transforms, summed over 2 pi aliases, folded to every resolution the
+ * cascade uses, pre-scaled by the inverse-transform normalisation, stored as fp32) and
+ * FFT twiddle tables, uploaded to the current HIP device.
+ *
+ *   dims       1 or 2
+ *   shape      host array of `dims` ints; each a power of two and >= 2^J (2-D: rows, cols)
+ *   J          number of octaves, >= 1; the output grid is shape >> J
+ *   LQ         2-D: number of angles L >= 1;  1-D: first-order wavelets per octave Q >= 1
+ *   max_order  1 or 2
+ *
+ * On success *out_plan is a new plan the caller must release with scat_plan_destroy.
+ * On failure *out_plan is NULL and nothing is leaked.
+ */
+scat_status scat_plan_create(scat_plan **out_plan, int dims, const int *shape, int J, int LQ,
+                             int max_order);
+
+/*
+ * Same as scat_plan_create but touches no GPU: the plan holds the host copies of the
+ * tables only (for inspection with the scat_plan_* getters below); scat_forward on such a
+ * plan returns SCAT_ERR_DEVICE.
+ */
+scat_status scat_plan_create_host(scat_plan **out_plan, int dims, const int *shape, int J,
+                                  int LQ, int max_order);
+
+/*
+ * Enqueue the transform of `batch` planes on `stream` (a hipStream_t passed as void*,
+ * NULL = the default stream).  Does not synchronise.
+ *
+ *   in   device, float32, batch x shape[0] (x shape[1]), C-contiguous.  Read only.
+ *   out  device, float32, batch x K x (shape[0]>>J) (x (shape[1]>>J)), C-contiguous, where
+ *        K = scat_plan_num_coeffs: channel 0 is S0, then S1 in order (j1, theta1) [1-D: by
+ *        first-order wavelet index], then S2 in order (j1, theta1, j2, theta2) [1-D: (k1, j2)].
+ *
+ * Image channels are the caller's business: a (B, C, H, W) tensor is batch = B*C planes.
+ * `in` and `out` must not overlap and must stay valid until the stream has run the work.
+ * The plan owns a scratch buffer that is (re)allocated when a call needs a larger one, so
+ * at most one scat_forward per plan may be in flight at a time, and a call that grows
+ * the buffer synchronises the device first.  batch == 0 is a no-op.
+ */
+scat_status scat_forward(scat_plan *plan, const float *in, float *out, long batch,
+                         void *stream);
+
+/* Release a plan and its device memory.  NULL is a no-op returning SCAT_OK. */
+scat_status scat_plan_destroy(scat_plan *plan);
+
+/* ---- introspection: host only, never touches the GPU ------------------------------ */
+
+/* Number of output channels K (1 + J*L + L^2 J(J-1)/2 in 2-D at max_order 2); -1 on NULL. */
+int scat_plan_num_coeffs(const scat_plan *plan);
+
+/* Writes the `dims` output side lengths (shape >> J). */
+scat_status scat_plan_out_shape(const scat_plan *plan, int *shape_out);
+
+/* Row c of the index table: idx = {order, j1, t1, j2, t2}, unused fields -1.
+ * 2-D: t = angle index.  1-D: t1 = first-order wavelet index k (octave j1 = k / Q),
+ * t2 = second-order wavelet index (= j2). */
+scat_status scat_plan_coeff_index(const scat_plan *plan, int c, int idx[5]);
+
+/* Bytes of device scratch a scat_forward call with this batch size uses. */
+size_t scat_plan_workspace_bytes(const scat_plan *plan, long batch);
+
+/*
+ * Copy one filter's Fourier samples, as the kernels read them but WITHOUT the
+ * normalisation pre-scale, into host memory as float64, natural frequency order
+ * (2-D: rows x cols of the grid at resolution `res`, i.e. shape >> res; 1-D: length
+ * shape[0] >> res).
+ *   kind 0: lowpass phi_J folded to resolution res        (index ignored)
+ *   kind 1: first-order wavelet `index` (2-D: j*L + theta; 1-D: k), res must be 0
+ *   kind 2: second-order wavelet `index` (2-D: j*L + theta; 1-D: j) folded to res < j
+ * Returns SCAT_ERR_ARG if that table is not part of the plan.
+ */
+scat_status scat_plan_filter(const scat_plan *plan, int kind, int index, int res,
+                             double *out_host);
+
+const char *scat_status_string(scat_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SCAT_H */

@@ -1,0 +1,193 @@
+"""ctypes binding of libscat.so: argument marshalling only.
+
+The functions carry the names of the C entry points declared in include/scat.h.
+Every step of the transform runs in the library's HIP kernels; torch is used for
+device memory and streams only.  If the shared library has not been built the
+binding raises -- there is no CPU fallback.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libscat.so")
+
+SCAT_OK = 0
+_lib = None
+
+
+class ScatError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__("%s failed: %s (status %d)" % (where, scat_status_string(status), status))
+
+
+def lib():
+    """Load (once) and return the ctypes handle of libscat.so."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            "%s is missing: build it with `python -m paper_1812_11214_amd.build` "
+            "(there is no fallback implementation)" % LIB_PATH)
+    L = ctypes.CDLL(LIB_PATH)
+    vp, ci, cl = ctypes.c_void_p, ctypes.c_int, ctypes.c_long
+    pi = ctypes.POINTER(ctypes.c_int)
+    L.scat_plan_create.argtypes = [ctypes.POINTER(vp), ci, pi, ci, ci, ci]
+    L.scat_plan_create.restype = ci
+    L.scat_plan_create_host.argtypes = [ctypes.POINTER(vp), ci, pi, ci, ci, ci]
+    L.scat_plan_create_host.restype = ci
+    L.scat_forward.argtypes = [vp, vp, vp, cl, vp]
+    L.scat_forward.restype = ci
+    L.scat_plan_destroy.argtypes = [vp]
+    L.scat_plan_destroy.restype = ci
+    L.scat_plan_num_coeffs.argtypes = [vp]
+    L.scat_plan_num_coeffs.restype = ci
+    L.scat_plan_out_shape.argtypes = [vp, pi]
+    L.scat_plan_out_shape.restype = ci
+    L.scat_plan_coeff_index.argtypes = [vp, ci, pi]
+    L.scat_plan_coeff_index.restype = ci
+    L.scat_plan_workspace_bytes.argtypes = [vp, cl]
+    L.scat_plan_workspace_bytes.restype = ctypes.c_size_t
+    L.scat_plan_filter.argtypes = [vp, ci, ci, ci, ctypes.POINTER(ctypes.c_double)]
+    L.scat_plan_filter.restype = ci
+    L.scat_status_string.argtypes = [ci]
+    L.scat_status_string.restype = ctypes.c_char_p
+    _lib = L
+    return L
+
+
+EXPORTS = ("scat_plan_create", "scat_plan_create_host", "scat_forward", "scat_plan_destroy",
+           "scat_plan_num_coeffs", "scat_plan_out_shape", "scat_plan_coeff_index",
+           "scat_plan_workspace_bytes", "scat_plan_filter", "scat_status_string")
+
+
+def scat_status_string(status):
+    return lib().scat_status_string(int(status)).decode()
+
+
+def _create(fn, shape, J, LQ, max_order):
+    shape = tuple(int(s) for s in shape)
+    arr = (ctypes.c_int * len(shape))(*shape)
+    handle = ctypes.c_void_p()
+    st = fn(ctypes.byref(handle), len(shape), arr, int(J), int(LQ), int(max_order))
+    if st != SCAT_OK:
+        raise ScatError(st, fn.__name__)
+    return handle
+
+
+def scat_plan_create(shape, J, LQ, max_order=2):
+    """Plan for signals of `shape` (1 or 2 sides) on the current GPU; returns a handle."""
+    return _create(lib().scat_plan_create, shape, J, LQ, max_order)
+
+
+def scat_plan_create_host(shape, J, LQ, max_order=2):
+    """Plan with host tables only (no GPU touched)."""
+    return _create(lib().scat_plan_create_host, shape, J, LQ, max_order)
+
+
+def scat_plan_destroy(plan):
+    st = lib().scat_plan_destroy(plan)
+    if st != SCAT_OK:
+        raise ScatError(st, "scat_plan_destroy")
+
+
+def scat_plan_num_coeffs(plan):
+    return lib().scat_plan_num_coeffs(plan)
+
+
+def scat_plan_out_shape(plan, dims):
+    arr = (ctypes.c_int * dims)()
+    st = lib().scat_plan_out_shape(plan, arr)
+    if st != SCAT_OK:
+        raise ScatError(st, "scat_plan_out_shape")
+    return tuple(arr)
+
+
+def scat_plan_coeff_index(plan, c):
+    arr = (ctypes.c_int * 5)()
+    st = lib().scat_plan_coeff_index(plan, int(c), arr)
+    if st != SCAT_OK:
+        raise ScatError(st, "scat_plan_coeff_index")
+    return tuple(arr)
+
+
+def scat_plan_workspace_bytes(plan, batch):
+    return int(lib().scat_plan_workspace_bytes(plan, int(batch)))
+
+
+def scat_plan_filter(plan, kind, index, res, shape):
+    """Unscaled Fourier samples of one filter as a float64 array of `shape`."""
+    out = np.empty(shape, dtype=np.float64)
+    st = lib().scat_plan_filter(plan, int(kind), int(index), int(res),
+                                out.ctypes.data_as(ctypes.POINTER(ctypes.c_double)))
+    if st != SCAT_OK:
+        raise ScatError(st, "scat_plan_filter")
+    return out
+
+
+def scat_forward(plan, in_ptr, out_ptr, batch, stream_ptr=None):
+    """Raw call: device addresses as integers, stream as a hipStream_t integer or None."""
+    st = lib().scat_forward(plan, ctypes.c_void_p(in_ptr), ctypes.c_void_p(out_ptr), int(batch),
+                            ctypes.c_void_p(stream_ptr) if stream_ptr else None)
+    if st != SCAT_OK:
+        raise ScatError(st, "scat_forward")
+
+
+class Scattering:
+    """Owner of one plan.  `forward` takes a contiguous float32 CUDA tensor whose trailing
+    dims equal `shape`; all leading dims are independent planes."""
+
+    def __init__(self, shape, J, LQ, max_order=2, host_only=False):
+        self.shape = tuple(int(s) for s in shape)
+        self.dims = len(self.shape)
+        self.J, self.LQ, self.max_order = int(J), int(LQ), int(max_order)
+        self._plan = None
+        create = scat_plan_create_host if host_only else scat_plan_create
+        self._plan = create(self.shape, J, LQ, max_order)
+        self.K = scat_plan_num_coeffs(self._plan)
+        self.out_shape = scat_plan_out_shape(self._plan, self.dims)
+
+    def coeff_index(self):
+        return [scat_plan_coeff_index(self._plan, c) for c in range(self.K)]
+
+    def workspace_bytes(self, batch):
+        return scat_plan_workspace_bytes(self._plan, batch)
+
+    def filter(self, kind, index, res):
+        shp = tuple(s >> res for s in self.shape)
+        return scat_plan_filter(self._plan, kind, index, res, shp)
+
+    def forward(self, x, out=None):
+        import torch
+        if not (x.is_cuda and x.dtype == torch.float32 and x.is_contiguous()):
+            raise ValueError("input must be a contiguous float32 CUDA tensor")
+        if tuple(x.shape[x.dim() - self.dims:]) != self.shape:
+            raise ValueError("trailing dims %s do not match the plan's shape %s"
+                             % (tuple(x.shape), self.shape))
+        lead = tuple(x.shape[:x.dim() - self.dims])
+        batch = 1
+        for d in lead:
+            batch *= d
+        oshape = lead + (self.K,) + self.out_shape
+        if out is None:
+            out = torch.empty(oshape, dtype=torch.float32, device=x.device)
+        elif not (out.is_cuda and out.dtype == torch.float32 and out.is_contiguous()
+                  and tuple(out.shape) == oshape):
+            raise ValueError("out must be a contiguous float32 CUDA tensor of shape %s" % (oshape,))
+        stream = torch.cuda.current_stream(x.device).cuda_stream
+        scat_forward(self._plan, x.data_ptr(), out.data_ptr(), batch, stream)
+        return out
+
+    def close(self):
+        if self._plan is not None:
+            scat_plan_destroy(self._plan)
+            self._plan = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

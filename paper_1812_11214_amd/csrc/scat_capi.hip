@@ -1,0 +1,449 @@
+// C ABI of the scattering library: plan life cycle, table upload, and the schedule that
+// walks the scattering tree one first-order octave after the other (paper section 2,
+// "Implementation": depth-first traversal, downsampled intermediates).
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <map>
+#include <new>
+#include <utility>
+#include <vector>
+
+#include "../../include/scat.h"
+#include "scat_host.hpp"
+#include "scat_kernels.hpp"
+
+struct scat_plan {
+  scat::HostPlan host;
+  bool has_device = false;
+  int device = -1;
+  // Grid the kernels see: 2-D (rows, cols); 1-D the four-step factorisation N = n1 * n2,
+  // signal sample n1_index * n2 + n2_index.
+  int n1 = 1, n2 = 1;
+  float *d_tables = nullptr;
+  float2 *d_tw = nullptr;
+  int tw_n = 0;
+  void *d_scratch = nullptr;
+  size_t scratch_bytes = 0;
+  // offsets (in floats) into d_tables
+  std::vector<size_t> psi1_off;                    // per octave; LQ tables contiguous
+  std::map<std::pair<int, int>, size_t> psi2_off;  // (res, j2) -> tables (2-D: L contiguous)
+  std::vector<size_t> phi_rows_off, phi_cols_off;  // 2-D, per res
+  std::vector<size_t> phi_off;                     // 1-D, per res
+};
+
+namespace {
+
+using scat::ChanMap;
+using scat::FilterTable;
+
+constexpr size_t kScratchBudget = size_t(1) << 30;  // bytes of scratch one chunk may use
+
+struct Layout {
+  long chunk = 0;       // planes per chunk
+  size_t per_plane = 0; // scratch bytes per plane
+  // element offsets are expressed per plane; buffers are laid out chunk-major
+  size_t xh = 0, t = 0, u = 0, v = 0, w = 0;  // per-plane sizes in bytes
+};
+
+Layout make_layout(const scat_plan &p, long batch) {
+  Layout L;
+  const scat::HostPlan &h = p.host;
+  const size_t n = static_cast<size_t>(p.n1) * p.n2;
+  const bool second = h.max_order == 2 && h.J >= 2;
+  const size_t c8 = sizeof(float2);
+  if (h.dims == 2) {
+    const size_t l = h.LQ;
+    L.xh = n * c8;
+    size_t t1 = l * n, t2 = second ? l * l * (n / 4) : 0;
+    L.t = (t1 > t2 ? t1 : t2) * c8;
+    L.u = second ? l * n * c8 : 0;
+    L.v = 0;
+    const size_t m_r = p.n1 >> h.J;
+    size_t w0 = l * m_r * p.n2;                       // first order at octave 0
+    size_t w2 = second ? l * l * m_r * (p.n2 / 2) : 0;  // second order at octave 1
+    L.w = (w0 > w2 ? w0 : w2) * sizeof(float);
+  } else {
+    const size_t q = h.LQ;
+    L.xh = n * c8;
+    L.t = q * n * c8;
+    L.u = q * n * c8;
+    L.v = second ? q * (n / 2) * c8 : 0;
+    L.w = 0;
+  }
+  L.per_plane = L.xh + L.t + L.u + L.v + L.w;
+  long c = static_cast<long>(kScratchBudget / L.per_plane);
+  if (c < 1) c = 1;
+  if (c > batch) c = batch;
+  L.chunk = c;
+  return L;
+}
+
+void free_device(scat_plan *p) {
+  if (p->d_tables) (void)hipFree(p->d_tables);
+  if (p->d_tw) (void)hipFree(p->d_tw);
+  if (p->d_scratch) (void)hipFree(p->d_scratch);
+  p->d_tables = nullptr;
+  p->d_tw = nullptr;
+  p->d_scratch = nullptr;
+  p->scratch_bytes = 0;
+}
+
+// Append one table in the kernels' layout, scaled by 1 / (number of grid points).
+size_t append_table(std::vector<float> &pool, const FilterTable &t, int dims, int n1) {
+  const size_t off = pool.size();
+  const size_t cnt = t.v.size();
+  const double scale = 1.0 / static_cast<double>(cnt);
+  pool.resize(off + cnt);
+  if (dims == 2) {
+    for (size_t i = 0; i < cnt; ++i) pool[off + i] = static_cast<float>(t.v[i] * scale);
+  } else {
+    // four-step layout: [k1][k2] holds frequency k1 + n1 * k2
+    const size_t cols = cnt / n1;
+    for (size_t k1 = 0; k1 < static_cast<size_t>(n1); ++k1)
+      for (size_t k2 = 0; k2 < cols; ++k2)
+        pool[off + k1 * cols + k2] = static_cast<float>(t.v[k1 + n1 * k2] * scale);
+  }
+  return off;
+}
+
+size_t append_vec(std::vector<float> &pool, const std::vector<double> &v) {
+  const size_t off = pool.size();
+  const double scale = 1.0 / static_cast<double>(v.size());
+  for (double d : v) pool.push_back(static_cast<float>(d * scale));
+  return off;
+}
+
+scat_status upload(scat_plan *p) {
+  const scat::HostPlan &h = p->host;
+  std::vector<float> pool;
+  p->psi1_off.assign(h.J, 0);
+  for (int j = 0; j < h.J; ++j)
+    for (int l = 0; l < h.LQ; ++l) {
+      size_t off = append_table(pool, *h.find(1, j * h.LQ + l, 0), h.dims, p->n1);
+      if (l == 0) p->psi1_off[j] = off;
+    }
+  if (h.max_order == 2) {
+    for (int j2 = 1; j2 < h.J; ++j2)
+      for (int r = 0; r < j2; ++r) {
+        if (h.dims == 2) {
+          if (r == 0) {
+            p->psi2_off[{0, j2}] = p->psi1_off[j2];
+            continue;
+          }
+          for (int l = 0; l < h.LQ; ++l) {
+            size_t off = append_table(pool, *h.find(2, j2 * h.LQ + l, r), 2, p->n1);
+            if (l == 0) p->psi2_off[{r, j2}] = off;
+          }
+        } else {
+          p->psi2_off[{r, j2}] = append_table(pool, *h.find(2, j2, r), 1, p->n1);
+        }
+      }
+  }
+  if (h.dims == 2) {
+    for (int r = 0; r < h.J; ++r) {
+      p->phi_rows_off.push_back(append_vec(pool, h.phi_rows[r]));
+      p->phi_cols_off.push_back(append_vec(pool, h.phi_cols[r]));
+    }
+  } else {
+    for (int r = 0; r < h.J; ++r)
+      p->phi_off.push_back(append_table(pool, *h.find(0, 0, r), 1, p->n1));
+  }
+  // twiddles exp(-2 pi i j / tw_n), evaluated in double
+  p->tw_n = h.dims == 2 ? (p->n1 > p->n2 ? p->n1 : p->n2) : p->n1 * p->n2;
+  std::vector<float2> tw(p->tw_n);
+  const double two_pi = 6.283185307179586476925286766559;
+  for (int j = 0; j < p->tw_n; ++j) {
+    double a = -two_pi * j / p->tw_n;
+    tw[j] = make_float2(static_cast<float>(std::cos(a)), static_cast<float>(std::sin(a)));
+  }
+  if (hipGetDevice(&p->device) != hipSuccess) return SCAT_ERR_DEVICE;
+  if (hipMalloc(&p->d_tables, pool.size() * sizeof(float)) != hipSuccess) return SCAT_ERR_ALLOC;
+  if (hipMalloc(&p->d_tw, tw.size() * sizeof(float2)) != hipSuccess) return SCAT_ERR_ALLOC;
+  if (hipMemcpy(p->d_tables, pool.data(), pool.size() * sizeof(float), hipMemcpyHostToDevice) !=
+      hipSuccess)
+    return SCAT_ERR_DEVICE;
+  if (hipMemcpy(p->d_tw, tw.data(), tw.size() * sizeof(float2), hipMemcpyHostToDevice) !=
+      hipSuccess)
+    return SCAT_ERR_DEVICE;
+  p->has_device = true;
+  return SCAT_OK;
+}
+
+scat_status create_common(scat_plan **out_plan, int dims, const int *shape, int J, int LQ,
+                          int max_order, bool device) {
+  if (out_plan == nullptr) return SCAT_ERR_NULL;
+  *out_plan = nullptr;
+  if (shape == nullptr) return SCAT_ERR_NULL;
+  int v = scat::validate(dims, shape, J, LQ, max_order);
+  if (v != 0) return static_cast<scat_status>(v);
+  scat_plan *p = new (std::nothrow) scat_plan;
+  if (p == nullptr) return SCAT_ERR_ALLOC;
+  try {
+    scat::build_host_plan(p->host, dims, shape, J, LQ, max_order);
+  } catch (const std::bad_alloc &) {
+    delete p;
+    return SCAT_ERR_ALLOC;
+  }
+  if (dims == 2) {
+    p->n1 = shape[0];
+    p->n2 = shape[1];
+  } else {
+    // four-step split N = n1 * n2 with n2 >= 2^J (folds act on the n2 digit only) and
+    // both factors as close to sqrt(N) as that allows
+    int lg = 0;
+    while ((1 << lg) < shape[0]) ++lg;
+    int lg2 = (lg + 1) / 2;
+    if (lg2 < J) lg2 = J;
+    p->n2 = 1 << lg2;
+    p->n1 = shape[0] >> lg2;
+  }
+  if (device) {
+    scat_status s;
+    try {
+      s = upload(p);
+    } catch (const std::bad_alloc &) {
+      s = SCAT_ERR_ALLOC;
+    }
+    if (s != SCAT_OK) {
+      free_device(p);
+      delete p;
+      return s;
+    }
+  }
+  *out_plan = p;
+  return SCAT_OK;
+}
+
+#define SCAT_TRY(expr)                               \
+  do {                                               \
+    if ((expr) != hipSuccess) return SCAT_ERR_DEVICE; \
+  } while (0)
+
+// ---- 2-D schedule for one chunk of `pc` planes starting at plane p0
+scat_status forward_2d(scat_plan *p, const float *in, float *out, long p0, long pc,
+                       const Layout &lay, hipStream_t st) {
+  const scat::HostPlan &h = p->host;
+  const int J = h.J, L = h.LQ, K = h.K;
+  const int Nr = p->n1, Nc = p->n2;
+  const int m_r = Nr >> J, m_c = Nc >> J;
+  char *base = static_cast<char *>(p->d_scratch);
+  float2 *XH = reinterpret_cast<float2 *>(base);
+  float2 *T = reinterpret_cast<float2 *>(base + lay.xh * pc);
+  float2 *U = reinterpret_cast<float2 *>(base + (lay.xh + lay.t) * pc);
+  float *W = reinterpret_cast<float *>(base + (lay.xh + lay.t + lay.u + lay.v) * pc);
+  const float *tab = p->d_tables;
+  const float2 *tw = p->d_tw;
+  const int tw_n = p->tw_n;
+  const float *x = in + static_cast<size_t>(p0) * Nr * Nc;
+  float *o = out + static_cast<size_t>(p0) * K * m_r * m_c;
+  const ChanMap none{1, 1, 0, 0};
+
+  // x -> column spectra (+ column half of the lowpass for S0), then rows
+  SCAT_TRY(scat::launch_col(0, x, pc, Nr, Nc, XH, 0, tab + p->phi_rows_off[0], m_r, W, nullptr,
+                            none, K, tw, tw_n, st));
+  SCAT_TRY(scat::launch_row_lowpass(W, pc, m_r, Nc, m_c, tab + p->phi_cols_off[0], o,
+                                    ChanMap{1, 1, 0, 0}, K, tw, tw_n, st));
+  SCAT_TRY(scat::launch_row_fwd(XH, pc * Nr, Nc, tw, tw_n, st));
+
+  int s2_base = 1 + J * L;
+  for (int j1 = 0; j1 < J; ++j1) {
+    const int M1r = Nr >> j1, M1c = Nc >> j1;
+    const bool kids = h.max_order == 2 && j1 < J - 1;
+    SCAT_TRY(scat::launch_mulfold_invrow(XH, tab + p->psi1_off[j1], T, pc, L, Nr, Nc, j1, j1, 0,
+                                         tw, tw_n, st));
+    SCAT_TRY(scat::launch_col(1, T, pc * L, M1r, M1c, kids ? U : nullptr, 0,
+                              tab + p->phi_rows_off[j1], m_r, W, nullptr, none, K, tw, tw_n, st));
+    SCAT_TRY(scat::launch_row_lowpass(W, pc * L, m_r, M1c, m_c, tab + p->phi_cols_off[j1], o,
+                                      ChanMap{L, L, 0, 1 + j1 * L}, K, tw, tw_n, st));
+    if (!kids) continue;
+    SCAT_TRY(scat::launch_row_fwd(U, pc * L * M1r, M1c, tw, tw_n, st));
+    const int octs = J - 1 - j1;
+    for (int j2 = j1 + 1; j2 < J; ++j2) {
+      const int M2r = Nr >> j2, M2c = Nc >> j2;
+      SCAT_TRY(scat::launch_mulfold_invrow(U, tab + p->psi2_off[{j1, j2}], T, pc * L, L, M1r, M1c,
+                                           j2 - j1, j2 - j1, 0, tw, tw_n, st));
+      SCAT_TRY(scat::launch_col(1, T, pc * L * L, M2r, M2c, nullptr, 0, tab + p->phi_rows_off[j2],
+                                m_r, W, nullptr, none, K, tw, tw_n, st));
+      SCAT_TRY(scat::launch_row_lowpass(W, pc * L * L, m_r, M2c, m_c, tab + p->phi_cols_off[j2], o,
+                                        ChanMap{L * L, L, octs * L, s2_base + (j2 - j1 - 1) * L}, K,
+                                        tw, tw_n, st));
+    }
+    s2_base += L * L * octs;
+  }
+  return SCAT_OK;
+}
+
+// ---- 1-D schedule (four-step transforms: the signal is an n1 x n2 matrix)
+scat_status forward_1d(scat_plan *p, const float *in, float *out, long p0, long pc,
+                       const Layout &lay, hipStream_t st) {
+  const scat::HostPlan &h = p->host;
+  const int J = h.J, Q = h.LQ, K = h.K;
+  const int N1 = p->n1, N2 = p->n2;
+  const int N = N1 * N2;
+  const int mc_out = N2 >> J;
+  char *base = static_cast<char *>(p->d_scratch);
+  float2 *XH = reinterpret_cast<float2 *>(base);
+  float2 *T = reinterpret_cast<float2 *>(base + lay.xh * pc);
+  float2 *U = reinterpret_cast<float2 *>(base + (lay.xh + lay.t) * pc);
+  float2 *V = reinterpret_cast<float2 *>(base + (lay.xh + lay.t + lay.u) * pc);
+  const float *tab = p->d_tables;
+  const float2 *tw = p->d_tw;
+  const int tw_n = p->tw_n;
+  const float *x = in + static_cast<size_t>(p0) * N;
+  float *o = out + static_cast<size_t>(p0) * K * (N >> J);
+  const ChanMap none{1, 1, 0, 0};
+
+  SCAT_TRY(scat::launch_col(0, x, pc, N1, N2, XH, N, nullptr, 0, nullptr, nullptr, none, K, tw,
+                            tw_n, st));
+  SCAT_TRY(scat::launch_row_fwd(XH, pc * N1, N2, tw, tw_n, st));
+  // S0
+  SCAT_TRY(scat::launch_mulfold_invrow(XH, tab + p->phi_off[0], T, pc, 1, N1, N2, 0, J, N >> J, tw,
+                                       tw_n, st));
+  SCAT_TRY(scat::launch_col(2, T, pc, N1, mc_out, nullptr, 0, nullptr, 0, nullptr, o,
+                            ChanMap{1, 1, 0, 0}, K, tw, tw_n, st));
+  int s2_base = 1 + J * Q;
+  for (int j1 = 0; j1 < J; ++j1) {
+    const int Mc1 = N2 >> j1;
+    const int M1 = N >> j1;
+    const bool kids = h.max_order == 2 && j1 < J - 1;
+    SCAT_TRY(scat::launch_mulfold_invrow(XH, tab + p->psi1_off[j1], T, pc, Q, N1, N2, 0, j1, M1,
+                                         tw, tw_n, st));
+    SCAT_TRY(scat::launch_col(1, T, pc * Q, N1, Mc1, U, M1, nullptr, 0, nullptr, nullptr, none, K,
+                              tw, tw_n, st));
+    SCAT_TRY(scat::launch_row_fwd(U, pc * Q * N1, Mc1, tw, tw_n, st));
+    SCAT_TRY(scat::launch_mulfold_invrow(U, tab + p->phi_off[j1], T, pc * Q, 1, N1, Mc1, 0, J - j1,
+                                         N >> J, tw, tw_n, st));
+    SCAT_TRY(scat::launch_col(2, T, pc * Q, N1, mc_out, nullptr, 0, nullptr, 0, nullptr, o,
+                              ChanMap{Q, Q, 0, 1 + j1 * Q}, K, tw, tw_n, st));
+    if (!kids) continue;
+    const int octs = J - 1 - j1;
+    for (int j2 = j1 + 1; j2 < J; ++j2) {
+      const int Mc2 = N2 >> j2;
+      const int M2 = N >> j2;
+      SCAT_TRY(scat::launch_mulfold_invrow(U, tab + p->psi2_off[{j1, j2}], T, pc * Q, 1, N1, Mc1, 0,
+                                           j2 - j1, M2, tw, tw_n, st));
+      SCAT_TRY(scat::launch_col(1, T, pc * Q, N1, Mc2, V, M2, nullptr, 0, nullptr, nullptr, none, K,
+                                tw, tw_n, st));
+      SCAT_TRY(scat::launch_row_fwd(V, pc * Q * N1, Mc2, tw, tw_n, st));
+      SCAT_TRY(scat::launch_mulfold_invrow(V, tab + p->phi_off[j2], T, pc * Q, 1, N1, Mc2, 0,
+                                           J - j2, N >> J, tw, tw_n, st));
+      SCAT_TRY(scat::launch_col(2, T, pc * Q, N1, mc_out, nullptr, 0, nullptr, 0, nullptr, o,
+                                ChanMap{Q, 1, octs, s2_base + (j2 - j1 - 1)}, K, tw, tw_n, st));
+    }
+    s2_base += Q * octs;
+  }
+  return SCAT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+scat_status scat_plan_create(scat_plan **out_plan, int dims, const int *shape, int J, int LQ,
+                             int max_order) {
+  return create_common(out_plan, dims, shape, J, LQ, max_order, true);
+}
+
+scat_status scat_plan_create_host(scat_plan **out_plan, int dims, const int *shape, int J, int LQ,
+                                  int max_order) {
+  return create_common(out_plan, dims, shape, J, LQ, max_order, false);
+}
+
+scat_status scat_forward(scat_plan *plan, const float *in, float *out, long batch, void *stream) {
+  if (plan == nullptr) return SCAT_ERR_NULL;
+  if (batch < 0) return SCAT_ERR_ARG;
+  if (batch == 0) return SCAT_OK;
+  if (in == nullptr || out == nullptr) return SCAT_ERR_NULL;
+  if (!plan->has_device) return SCAT_ERR_DEVICE;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev != plan->device) return SCAT_ERR_DEVICE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const Layout lay = make_layout(*plan, batch);
+  const size_t need = lay.per_plane * static_cast<size_t>(lay.chunk);
+  if (need > plan->scratch_bytes) {
+    if (hipDeviceSynchronize() != hipSuccess) return SCAT_ERR_DEVICE;
+    if (plan->d_scratch) (void)hipFree(plan->d_scratch);
+    plan->d_scratch = nullptr;
+    plan->scratch_bytes = 0;
+    if (hipMalloc(&plan->d_scratch, need) != hipSuccess) return SCAT_ERR_ALLOC;
+    plan->scratch_bytes = need;
+  }
+  for (long p0 = 0; p0 < batch; p0 += lay.chunk) {
+    long pc = batch - p0 < lay.chunk ? batch - p0 : lay.chunk;
+    scat_status s = plan->host.dims == 2 ? forward_2d(plan, in, out, p0, pc, lay, st)
+                                         : forward_1d(plan, in, out, p0, pc, lay, st);
+    if (s != SCAT_OK) return s;
+  }
+  return SCAT_OK;
+}
+
+scat_status scat_plan_destroy(scat_plan *plan) {
+  if (plan == nullptr) return SCAT_OK;
+  if (plan->has_device) {
+    int cur = -1;
+    bool sw = hipGetDevice(&cur) == hipSuccess && cur != plan->device;
+    if (sw) (void)hipSetDevice(plan->device);
+    (void)hipDeviceSynchronize();
+    free_device(plan);
+    if (sw) (void)hipSetDevice(cur);
+  }
+  delete plan;
+  return SCAT_OK;
+}
+
+int scat_plan_num_coeffs(const scat_plan *plan) { return plan ? plan->host.K : -1; }
+
+scat_status scat_plan_out_shape(const scat_plan *plan, int *shape_out) {
+  if (plan == nullptr || shape_out == nullptr) return SCAT_ERR_NULL;
+  const scat::HostPlan &h = plan->host;
+  if (h.dims == 2) {
+    shape_out[0] = h.shape[0] >> h.J;
+    shape_out[1] = h.shape[1] >> h.J;
+  } else {
+    shape_out[0] = h.shape[1] >> h.J;
+  }
+  return SCAT_OK;
+}
+
+scat_status scat_plan_coeff_index(const scat_plan *plan, int c, int idx[5]) {
+  if (plan == nullptr || idx == nullptr) return SCAT_ERR_NULL;
+  if (c < 0 || c >= plan->host.K) return SCAT_ERR_ARG;
+  const scat::CoeffRow &r = plan->host.index[c];
+  idx[0] = r.order;
+  idx[1] = r.j1;
+  idx[2] = r.t1;
+  idx[3] = r.j2;
+  idx[4] = r.t2;
+  return SCAT_OK;
+}
+
+size_t scat_plan_workspace_bytes(const scat_plan *plan, long batch) {
+  if (plan == nullptr || batch <= 0) return 0;
+  const Layout lay = make_layout(*plan, batch);
+  return lay.per_plane * static_cast<size_t>(lay.chunk);
+}
+
+scat_status scat_plan_filter(const scat_plan *plan, int kind, int index, int res,
+                             double *out_host) {
+  if (plan == nullptr || out_host == nullptr) return SCAT_ERR_NULL;
+  const FilterTable *t = plan->host.find(kind, index, res);
+  if (t == nullptr) return SCAT_ERR_ARG;
+  std::memcpy(out_host, t->v.data(), t->v.size() * sizeof(double));
+  return SCAT_OK;
+}
+
+const char *scat_status_string(scat_status s) {
+  switch (s) {
+    case SCAT_OK: return "ok";
+    case SCAT_ERR_ARG: return "invalid argument";
+    case SCAT_ERR_SHAPE: return "shape must be powers of two, each at least 2^J";
+    case SCAT_ERR_ALLOC: return "allocation failed";
+    case SCAT_ERR_DEVICE: return "GPU error or plan has no device state";
+    case SCAT_ERR_NULL: return "null pointer";
+  }
+  return "unknown status";
+}
+
+}  // extern "C"
