@@ -120,6 +120,32 @@ size_t scat_plan_workspace_bytes(const scat_plan *plan, long batch);
 scat_status scat_plan_filter(const scat_plan *plan, int kind, int index, int res,
                              double *out_host);
 
+/* ---- per-kernel timing, for benchmarks ---------------------------------------------- */
+
+/*
+ * From now on scat_forward brackets kernel launches with HIP events on the stream it is
+ * given: every launch if kernel_name is NULL, else only launches of the kernel with that
+ * name (as a profiler prints it without namespaces and arguments, e.g.
+ * "k_rows_fused<256>").  Discards earlier records.  Costs two event records per timed
+ * launch; leave it off otherwise.
+ */
+scat_status scat_plan_timing_begin(scat_plan *plan, const char *kernel_name);
+
+/* Stops recording, waits for the recorded launches and sums them per kernel name.
+ * Returns the number of distinct kernels recorded, or -1 on error / if not recording. */
+int scat_plan_timing_end(scat_plan *plan);
+
+/*
+ * Row `row` of the last scat_plan_timing_end: kernel name (copied, NUL-terminated, into
+ * name[name_len]), number of launches, their summed duration in milliseconds, the bytes
+ * those launches had to move at the least (each input and filter table read once, each
+ * output written once) and their model flops (5 n log2 n per n-point transform plus
+ * 4 per filter multiply-accumulate and modulus).  Any out pointer may be NULL.
+ */
+scat_status scat_plan_timing_row(const scat_plan *plan, int row, char *name, size_t name_len,
+                                 long *launches, double *ms, double *alg_bytes,
+                                 double *model_flops);
+
 const char *scat_status_string(scat_status s);
 
 #ifdef __cplusplus

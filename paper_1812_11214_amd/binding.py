@@ -53,6 +53,15 @@ def lib():
     L.scat_plan_workspace_bytes.restype = ctypes.c_size_t
     L.scat_plan_filter.argtypes = [vp, ci, ci, ci, ctypes.POINTER(ctypes.c_double)]
     L.scat_plan_filter.restype = ci
+    L.scat_plan_timing_begin.argtypes = [vp, ctypes.c_char_p]
+    L.scat_plan_timing_begin.restype = ci
+    L.scat_plan_timing_end.argtypes = [vp]
+    L.scat_plan_timing_end.restype = ci
+    L.scat_plan_timing_row.argtypes = [vp, ci, ctypes.c_char_p, ctypes.c_size_t,
+                                       ctypes.POINTER(cl), ctypes.POINTER(ctypes.c_double),
+                                       ctypes.POINTER(ctypes.c_double),
+                                       ctypes.POINTER(ctypes.c_double)]
+    L.scat_plan_timing_row.restype = ci
     L.scat_status_string.argtypes = [ci]
     L.scat_status_string.restype = ctypes.c_char_p
     _lib = L
@@ -61,7 +70,8 @@ def lib():
 
 EXPORTS = ("scat_plan_create", "scat_plan_create_host", "scat_forward", "scat_plan_destroy",
            "scat_plan_num_coeffs", "scat_plan_out_shape", "scat_plan_coeff_index",
-           "scat_plan_workspace_bytes", "scat_plan_filter", "scat_status_string")
+           "scat_plan_workspace_bytes", "scat_plan_filter", "scat_status_string",
+           "scat_plan_timing_begin", "scat_plan_timing_end", "scat_plan_timing_row")
 
 
 def scat_status_string(status):
@@ -128,6 +138,43 @@ def scat_plan_filter(plan, kind, index, res, shape):
     return out
 
 
+def scat_plan_timing_begin(plan, kernel_name=None):
+    st = lib().scat_plan_timing_begin(plan, kernel_name.encode() if kernel_name else None)
+    if st != SCAT_OK:
+        raise ScatError(st, "scat_plan_timing_begin")
+
+
+def scat_plan_timing_end(plan):
+    """Stop recording; returns {kernel name: dict(launches, ms, alg_bytes, model_flops)}."""
+    n = lib().scat_plan_timing_end(plan)
+    if n < 0:
+        raise ScatError(4, "scat_plan_timing_end")
+    out = {}
+    for r in range(n):
+        name = ctypes.create_string_buffer(128)
+        launches = ctypes.c_long()
+        ms, by, fl = ctypes.c_double(), ctypes.c_double(), ctypes.c_double()
+        st = lib().scat_plan_timing_row(plan, r, name, 128, ctypes.byref(launches),
+                                        ctypes.byref(ms), ctypes.byref(by), ctypes.byref(fl))
+        if st != SCAT_OK:
+            raise ScatError(st, "scat_plan_timing_row")
+        out[name.value.decode()] = dict(launches=launches.value, ms=ms.value,
+                                        alg_bytes=by.value, model_flops=fl.value)
+    return out
+
+
+def scat_plan_timing_row(plan, row):
+    """One row of the last timing table as (name, launches, ms, alg_bytes, model_flops)."""
+    name = ctypes.create_string_buffer(128)
+    launches = ctypes.c_long()
+    ms, by, fl = ctypes.c_double(), ctypes.c_double(), ctypes.c_double()
+    st = lib().scat_plan_timing_row(plan, int(row), name, 128, ctypes.byref(launches),
+                                    ctypes.byref(ms), ctypes.byref(by), ctypes.byref(fl))
+    if st != SCAT_OK:
+        raise ScatError(st, "scat_plan_timing_row")
+    return name.value.decode(), launches.value, ms.value, by.value, fl.value
+
+
 def scat_forward(plan, in_ptr, out_ptr, batch, stream_ptr=None):
     """Raw call: device addresses as integers, stream as a hipStream_t integer or None."""
     st = lib().scat_forward(plan, ctypes.c_void_p(in_ptr), ctypes.c_void_p(out_ptr), int(batch),
@@ -180,6 +227,12 @@ class Scattering:
         stream = torch.cuda.current_stream(x.device).cuda_stream
         scat_forward(self._plan, x.data_ptr(), out.data_ptr(), batch, stream)
         return out
+
+    def timing_begin(self, kernel_name=None):
+        scat_plan_timing_begin(self._plan, kernel_name)
+
+    def timing_end(self):
+        return scat_plan_timing_end(self._plan)
 
     def close(self):
         if self._plan is not None:

@@ -1,0 +1,157 @@
+// Register-resident FFT building blocks for gfx950.
+//
+// A transform of N = E * T points is shared by T threads, each holding E points in
+// registers: thread t holds x[t + T*i] in v[i].  One radix-E butterfly in registers, a
+// twiddle multiply, one exchange through LDS, and E/T radix-T butterflies leave thread t
+// holding X[t + T*i] in v[i] -- the same layout, so transforms chain without reshuffling.
+// Sign convention: forward = exp(-2 pi i k n / N); INV = true conjugates every twiddle
+// (no 1/N scaling anywhere).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+namespace scat {
+
+__device__ __forceinline__ float2 c_mul(float2 a, float2 b) {
+  return make_float2(a.x * b.x - a.y * b.y, a.x * b.y + a.y * b.x);
+}
+__device__ __forceinline__ float2 c_add(float2 a, float2 b) { return make_float2(a.x + b.x, a.y + b.y); }
+__device__ __forceinline__ float2 c_sub(float2 a, float2 b) { return make_float2(a.x - b.x, a.y - b.y); }
+// multiply by -i (forward quarter turn) or +i (inverse)
+template <bool INV>
+__device__ __forceinline__ float2 c_rot(float2 a) {
+  return INV ? make_float2(-a.y, a.x) : make_float2(a.y, -a.x);
+}
+// multiply by the constant (wr, wi) with wi given for the forward direction
+template <bool INV>
+__device__ __forceinline__ float2 c_mulc(float2 a, float wr, float wi) {
+  const float s = INV ? -wi : wi;
+  return make_float2(a.x * wr - a.y * s, a.x * s + a.y * wr);
+}
+
+template <bool INV>
+__device__ __forceinline__ void dft4(float2 &x0, float2 &x1, float2 &x2, float2 &x3) {
+  float2 t0 = c_add(x0, x2), t1 = c_sub(x0, x2), t2 = c_add(x1, x3), t3 = c_rot<INV>(c_sub(x1, x3));
+  x0 = c_add(t0, t2);
+  x2 = c_sub(t0, t2);
+  x1 = c_add(t1, t3);
+  x3 = c_sub(t1, t3);
+}
+
+template <int E, bool INV>
+struct DftRegs;
+
+template <bool INV>
+struct DftRegs<1, INV> {
+  static __device__ __forceinline__ void run(float2 (&)[1]) {}
+};
+
+template <bool INV>
+struct DftRegs<2, INV> {
+  static __device__ __forceinline__ void run(float2 (&v)[2]) {
+    float2 a = v[0], b = v[1];
+    v[0] = c_add(a, b);
+    v[1] = c_sub(a, b);
+  }
+};
+
+template <bool INV>
+struct DftRegs<4, INV> {
+  static __device__ __forceinline__ void run(float2 (&v)[4]) { dft4<INV>(v[0], v[1], v[2], v[3]); }
+};
+
+template <bool INV>
+struct DftRegs<8, INV> {
+  // index i = 2a + b, frequency k = c + 4d
+  static __device__ __forceinline__ void run(float2 (&v)[8]) {
+    constexpr float h = 0.70710678118654752440f;
+    dft4<INV>(v[0], v[2], v[4], v[6]);  // b = 0: results Y[0][c] at v[2c]
+    dft4<INV>(v[1], v[3], v[5], v[7]);  // b = 1: results Y[1][c] at v[2c+1]
+    v[3] = c_mulc<INV>(v[3], h, -h);
+    v[5] = c_rot<INV>(v[5]);
+    v[7] = c_mulc<INV>(v[7], -h, -h);
+    float2 o[8];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      o[c] = c_add(v[2 * c], v[2 * c + 1]);
+      o[c + 4] = c_sub(v[2 * c], v[2 * c + 1]);
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] = o[k];
+  }
+};
+
+template <bool INV>
+struct DftRegs<16, INV> {
+  // index i = 4a + b, frequency k = c + 4d
+  static __device__ __forceinline__ void run(float2 (&v)[16]) {
+    constexpr float h = 0.70710678118654752440f;
+    constexpr float c1 = 0.92387953251128675613f;  // cos(pi/8)
+    constexpr float s1 = 0.38268343236508977173f;  // sin(pi/8)
+#pragma unroll
+    for (int b = 0; b < 4; ++b) dft4<INV>(v[b], v[4 + b], v[8 + b], v[12 + b]);  // Y[b][c] at v[4c+b]
+    // twiddles w16^(b*c)
+    v[4 * 1 + 1] = c_mulc<INV>(v[4 * 1 + 1], c1, -s1);  // w^1
+    v[4 * 1 + 2] = c_mulc<INV>(v[4 * 1 + 2], h, -h);    // w^2
+    v[4 * 1 + 3] = c_mulc<INV>(v[4 * 1 + 3], s1, -c1);  // w^3
+    v[4 * 2 + 1] = c_mulc<INV>(v[4 * 2 + 1], h, -h);    // w^2
+    v[4 * 2 + 2] = c_rot<INV>(v[4 * 2 + 2]);            // w^4
+    v[4 * 2 + 3] = c_mulc<INV>(v[4 * 2 + 3], -h, -h);   // w^6
+    v[4 * 3 + 1] = c_mulc<INV>(v[4 * 3 + 1], s1, -c1);  // w^3
+    v[4 * 3 + 2] = c_mulc<INV>(v[4 * 3 + 2], -h, -h);   // w^6
+    v[4 * 3 + 3] = c_mulc<INV>(v[4 * 3 + 3], -c1, s1);  // w^9
+    float2 o[16];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      dft4<INV>(v[4 * c], v[4 * c + 1], v[4 * c + 2], v[4 * c + 3]);  // X[c + 4d] at v[4c+d]
+#pragma unroll
+      for (int d = 0; d < 4; ++d) o[c + 4 * d] = v[4 * c + d];
+    }
+#pragma unroll
+    for (int k = 0; k < 16; ++k) v[k] = o[k];
+  }
+};
+
+// Twiddles of thread t for an N = E*T point transform: wt[k1] = exp(-2 pi i t k1 / N),
+// taken from the table tw[j] = exp(-2 pi i j / tw_n) (N divides tw_n).
+template <int E, int T>
+__device__ __forceinline__ void load_twiddles(float2 (&wt)[E], int t, const float2 *__restrict__ tw,
+                                              int tw_n) {
+  const int step = tw_n / (E * T);
+#pragma unroll
+  for (int k1 = 0; k1 < E; ++k1) wt[k1] = tw[t * k1 * step];
+}
+
+// The transform described at the top of this file.  xch points at this transform's
+// exchange area in LDS, already offset for anything but (k1, t): element (k1, t) lives at
+// xch[k1 * sk + t * st].  Contains two workgroup barriers when T > 1 (one before the
+// exchange buffer is read, one after), so every thread of the workgroup must call it.
+template <int E, int T, bool INV>
+__device__ __forceinline__ void fft_core(float2 (&v)[E], int t, float2 *xch, int sk, int st,
+                                         const float2 (&wt)[E]) {
+  DftRegs<E, INV>::run(v);
+  if (T == 1) return;
+#pragma unroll
+  for (int k1 = 1; k1 < E; ++k1) {
+    float2 w = wt[k1];
+    if (INV) w.y = -w.y;
+    v[k1] = c_mul(v[k1], w);
+  }
+#pragma unroll
+  for (int k1 = 0; k1 < E; ++k1) xch[k1 * sk + t * st] = v[k1];
+  __syncthreads();
+  constexpr int U = E / T;
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    float2 a[T];
+    const int k1 = t + T * u;
+#pragma unroll
+    for (int j = 0; j < T; ++j) a[j] = xch[k1 * sk + j * st];
+    DftRegs<T, INV>::run(a);
+#pragma unroll
+    for (int k2 = 0; k2 < T; ++k2) v[u + U * k2] = a[k2];
+  }
+  __syncthreads();
+}
+
+}  // namespace scat

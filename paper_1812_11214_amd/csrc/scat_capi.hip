@@ -7,6 +7,7 @@
 #include <cstring>
 #include <map>
 #include <new>
+#include <string>
 #include <utility>
 #include <vector>
 
@@ -14,8 +15,75 @@
 #include "scat_host.hpp"
 #include "scat_kernels.hpp"
 
+// Records a HIP event pair around launches (all, or those of one kernel name) and sums
+// their durations per kernel name.
+struct LaunchTimer : scat::LaunchObserver {
+  struct Row {
+    std::string name;
+    long launches = 0;
+    double ms = 0, bytes = 0, flops = 0;
+  };
+  bool enabled = false;
+  std::string only;  // empty = every kernel
+  std::vector<Row> rows;
+  std::vector<hipEvent_t> pool;  // pairs: 2*i = start, 2*i+1 = stop
+  std::vector<int> pair_row;     // row of each recorded pair
+  bool recording = false;
+  bool failed = false;
+
+  void before(const char *name, double bytes, double flops, hipStream_t st) override {
+    recording = false;
+    if (!enabled || (!only.empty() && only != name)) return;
+    size_t r = 0;
+    while (r < rows.size() && rows[r].name != name) ++r;
+    if (r == rows.size()) {
+      rows.emplace_back();
+      rows.back().name = name;
+    }
+    rows[r].launches += 1;
+    rows[r].bytes += bytes;
+    rows[r].flops += flops;
+    const size_t i = pair_row.size();
+    while (pool.size() < 2 * (i + 1)) {
+      hipEvent_t e;
+      if (hipEventCreate(&e) != hipSuccess) {
+        failed = true;
+        return;
+      }
+      pool.push_back(e);
+    }
+    if (hipEventRecord(pool[2 * i], st) != hipSuccess) failed = true;
+    pair_row.push_back(static_cast<int>(r));
+    recording = true;
+  }
+  void after(hipStream_t st) override {
+    if (!recording) return;
+    if (hipEventRecord(pool[2 * (pair_row.size() - 1) + 1], st) != hipSuccess) failed = true;
+    recording = false;
+  }
+  // Waits for every recorded pair and adds up the elapsed times.
+  bool collect() {
+    for (size_t i = 0; i < pair_row.size(); ++i) {
+      float ms = 0.f;
+      if (hipEventSynchronize(pool[2 * i + 1]) != hipSuccess ||
+          hipEventElapsedTime(&ms, pool[2 * i], pool[2 * i + 1]) != hipSuccess) {
+        failed = true;
+        continue;
+      }
+      rows[pair_row[i]].ms += ms;
+    }
+    pair_row.clear();
+    return !failed;
+  }
+  void release() {
+    for (hipEvent_t e : pool) (void)hipEventDestroy(e);
+    pool.clear();
+  }
+};
+
 struct scat_plan {
   scat::HostPlan host;
+  LaunchTimer timer;
   bool has_device = false;
   int device = -1;
   // Grid the kernels see: 2-D (rows, cols); 1-D the four-step factorisation N = n1 * n2,
@@ -31,6 +99,7 @@ struct scat_plan {
   std::map<std::pair<int, int>, size_t> psi2_off;  // (res, j2) -> tables (2-D: L contiguous)
   std::vector<size_t> phi_rows_off, phi_cols_off;  // 2-D, per res
   std::vector<size_t> phi_off;                     // 1-D, per res
+  bool fused = false;  // 2-D: the fused row pass can serve every level of this plan
 };
 
 namespace {
@@ -53,7 +122,24 @@ Layout make_layout(const scat_plan &p, long batch) {
   const size_t n = static_cast<size_t>(p.n1) * p.n2;
   const bool second = h.max_order == 2 && h.J >= 2;
   const size_t c8 = sizeof(float2);
-  if (h.dims == 2) {
+  if (h.dims == 2 && p.fused) {
+    // xh: column spectra of x; t: first-order row-pass outputs of all octaves at once
+    // (sum over j of L*n/4^j); u: column spectra of one octave's moduli; v: second-order
+    // row-pass outputs of all child octaves of one first-order octave
+    const size_t l = h.LQ;
+    L.xh = n * c8;
+    size_t t1 = 0;
+    for (int j = 0; j < h.J; ++j) t1 += l * (n >> (2 * j));
+    L.t = t1 * c8;
+    L.u = second ? l * n * c8 : 0;
+    size_t t2 = 0;
+    for (int j = 1; j < h.J; ++j) t2 += l * l * (n >> (2 * j));
+    L.v = second ? t2 * c8 : 0;
+    const size_t m_r = p.n1 >> h.J;
+    size_t w0 = l * m_r * p.n2;
+    size_t w2 = second ? l * l * m_r * (p.n2 / 2) : 0;
+    L.w = (w0 > w2 ? w0 : w2) * sizeof(float);
+  } else if (h.dims == 2) {
     const size_t l = h.LQ;
     L.xh = n * c8;
     size_t t1 = l * n, t2 = second ? l * l * (n / 4) : 0;
@@ -199,6 +285,7 @@ scat_status create_common(scat_plan **out_plan, int dims, const int *shape, int 
     p->n2 = 1 << lg2;
     p->n1 = shape[0] >> lg2;
   }
+  p->fused = dims == 2 && J <= 4 && scat::rows_fused_supported(p->n1, p->n2, J - 1);
   if (device) {
     scat_status s;
     try {
@@ -266,6 +353,78 @@ scat_status forward_2d(scat_plan *p, const float *in, float *out, long p0, long 
                                            j2 - j1, j2 - j1, 0, tw, tw_n, st));
       SCAT_TRY(scat::launch_col(1, T, pc * L * L, M2r, M2c, nullptr, 0, tab + p->phi_rows_off[j2],
                                 m_r, W, nullptr, none, K, tw, tw_n, st));
+      SCAT_TRY(scat::launch_row_lowpass(W, pc * L * L, m_r, M2c, m_c, tab + p->phi_cols_off[j2], o,
+                                        ChanMap{L * L, L, octs * L, s2_base + (j2 - j1 - 1) * L}, K,
+                                        tw, tw_n, st));
+    }
+    s2_base += L * L * octs;
+  }
+  return SCAT_OK;
+}
+
+
+// ---- 2-D schedule with the fused row pass (no full 2-D spectrum is ever stored)
+scat_status forward_2d_fused(scat_plan *p, const float *in, float *out, long p0, long pc,
+                             const Layout &lay, hipStream_t st) {
+  const scat::HostPlan &h = p->host;
+  const int J = h.J, L = h.LQ, K = h.K;
+  const int Nr = p->n1, Nc = p->n2;
+  const int m_r = Nr >> J, m_c = Nc >> J;
+  const size_t n = static_cast<size_t>(Nr) * Nc;
+  char *base = static_cast<char *>(p->d_scratch);
+  float2 *XC = reinterpret_cast<float2 *>(base);
+  float2 *T = reinterpret_cast<float2 *>(base + lay.xh * pc);
+  float2 *U = reinterpret_cast<float2 *>(base + (lay.xh + lay.t) * pc);
+  float2 *V = reinterpret_cast<float2 *>(base + (lay.xh + lay.t + lay.u) * pc);
+  float *W = reinterpret_cast<float *>(base + (lay.xh + lay.t + lay.u + lay.v) * pc);
+  const float *tab = p->d_tables;
+  const float2 *tw = p->d_tw;
+  const int tw_n = p->tw_n;
+  const float *x = in + static_cast<size_t>(p0) * n;
+  float *o = out + static_cast<size_t>(p0) * K * m_r * m_c;
+  const ChanMap none{1, 1, 0, 0};
+
+  SCAT_TRY(scat::launch_col(0, x, pc, Nr, Nc, XC, 0, tab + p->phi_rows_off[0], m_r, W, nullptr,
+                            none, K, tw, tw_n, st));
+  SCAT_TRY(scat::launch_row_lowpass(W, pc, m_r, Nc, m_c, tab + p->phi_cols_off[0], o,
+                                    ChanMap{1, 1, 0, 0}, K, tw, tw_n, st));
+  // every first-order octave in one row pass over x's column spectra
+  std::vector<float2 *> t1(J);
+  {
+    scat::FusedLevel lv[4];
+    size_t off = 0;
+    for (int j1 = 0; j1 < J; ++j1) {
+      t1[j1] = T + off;
+      lv[j1] = scat::FusedLevel{j1, L, tab + p->psi1_off[j1], t1[j1]};
+      off += static_cast<size_t>(pc) * L * (n >> (2 * j1));
+    }
+    SCAT_TRY(scat::launch_rows_fused(XC, pc, Nr, Nc, lv, J, tw, tw_n, st));
+  }
+  int s2_base = 1 + J * L;
+  for (int j1 = 0; j1 < J; ++j1) {
+    const int M1r = Nr >> j1, M1c = Nc >> j1;
+    const bool kids = h.max_order == 2 && j1 < J - 1;
+    SCAT_TRY(scat::launch_col(1, t1[j1], pc * L, M1r, M1c, kids ? U : nullptr, 0,
+                              tab + p->phi_rows_off[j1], m_r, W, nullptr, none, K, tw, tw_n, st));
+    SCAT_TRY(scat::launch_row_lowpass(W, pc * L, m_r, M1c, m_c, tab + p->phi_cols_off[j1], o,
+                                      ChanMap{L, L, 0, 1 + j1 * L}, K, tw, tw_n, st));
+    if (!kids) continue;
+    const int octs = J - 1 - j1;
+    std::vector<float2 *> t2(J);
+    {
+      scat::FusedLevel lv[4];
+      size_t off = 0;
+      for (int j2 = j1 + 1; j2 < J; ++j2) {
+        t2[j2] = V + off;
+        lv[j2 - j1 - 1] = scat::FusedLevel{j2 - j1, L, tab + p->psi2_off[{j1, j2}], t2[j2]};
+        off += static_cast<size_t>(pc) * L * L * (n >> (2 * j2));
+      }
+      SCAT_TRY(scat::launch_rows_fused(U, pc * L, M1r, M1c, lv, octs, tw, tw_n, st));
+    }
+    for (int j2 = j1 + 1; j2 < J; ++j2) {
+      const int M2r = Nr >> j2, M2c = Nc >> j2;
+      SCAT_TRY(scat::launch_col(1, t2[j2], pc * L * L, M2r, M2c, nullptr, 0,
+                                tab + p->phi_rows_off[j2], m_r, W, nullptr, none, K, tw, tw_n, st));
       SCAT_TRY(scat::launch_row_lowpass(W, pc * L * L, m_r, M2c, m_c, tab + p->phi_cols_off[j2], o,
                                         ChanMap{L * L, L, octs * L, s2_base + (j2 - j1 - 1) * L}, K,
                                         tw, tw_n, st));
@@ -370,10 +529,15 @@ scat_status scat_forward(scat_plan *plan, const float *in, float *out, long batc
     if (hipMalloc(&plan->d_scratch, need) != hipSuccess) return SCAT_ERR_ALLOC;
     plan->scratch_bytes = need;
   }
+  struct ObserverScope {
+    explicit ObserverScope(scat::LaunchObserver *o) { scat::set_launch_observer(o); }
+    ~ObserverScope() { scat::set_launch_observer(nullptr); }
+  } scope(plan->timer.enabled ? &plan->timer : nullptr);
   for (long p0 = 0; p0 < batch; p0 += lay.chunk) {
     long pc = batch - p0 < lay.chunk ? batch - p0 : lay.chunk;
-    scat_status s = plan->host.dims == 2 ? forward_2d(plan, in, out, p0, pc, lay, st)
-                                         : forward_1d(plan, in, out, p0, pc, lay, st);
+    scat_status s = plan->host.dims == 1 ? forward_1d(plan, in, out, p0, pc, lay, st)
+                    : plan->fused        ? forward_2d_fused(plan, in, out, p0, pc, lay, st)
+                                         : forward_2d(plan, in, out, p0, pc, lay, st);
     if (s != SCAT_OK) return s;
   }
   return SCAT_OK;
@@ -386,6 +550,7 @@ scat_status scat_plan_destroy(scat_plan *plan) {
     bool sw = hipGetDevice(&cur) == hipSuccess && cur != plan->device;
     if (sw) (void)hipSetDevice(plan->device);
     (void)hipDeviceSynchronize();
+    plan->timer.release();
     free_device(plan);
     if (sw) (void)hipSetDevice(cur);
   }
@@ -431,6 +596,42 @@ scat_status scat_plan_filter(const scat_plan *plan, int kind, int index, int res
   const FilterTable *t = plan->host.find(kind, index, res);
   if (t == nullptr) return SCAT_ERR_ARG;
   std::memcpy(out_host, t->v.data(), t->v.size() * sizeof(double));
+  return SCAT_OK;
+}
+
+scat_status scat_plan_timing_begin(scat_plan *plan, const char *kernel_name) {
+  if (plan == nullptr) return SCAT_ERR_NULL;
+  if (!plan->has_device) return SCAT_ERR_DEVICE;
+  LaunchTimer &t = plan->timer;
+  t.rows.clear();
+  t.pair_row.clear();
+  t.failed = false;
+  t.only = kernel_name ? kernel_name : "";
+  t.enabled = true;
+  return SCAT_OK;
+}
+
+int scat_plan_timing_end(scat_plan *plan) {
+  if (plan == nullptr || !plan->timer.enabled) return -1;
+  plan->timer.enabled = false;
+  if (!plan->timer.collect()) return -1;
+  return static_cast<int>(plan->timer.rows.size());
+}
+
+scat_status scat_plan_timing_row(const scat_plan *plan, int row, char *name, size_t name_len,
+                                 long *launches, double *ms, double *alg_bytes,
+                                 double *model_flops) {
+  if (plan == nullptr) return SCAT_ERR_NULL;
+  if (row < 0 || row >= static_cast<int>(plan->timer.rows.size())) return SCAT_ERR_ARG;
+  const LaunchTimer::Row &r = plan->timer.rows[row];
+  if (name != nullptr && name_len > 0) {
+    std::strncpy(name, r.name.c_str(), name_len - 1);
+    name[name_len - 1] = 0;
+  }
+  if (launches) *launches = r.launches;
+  if (ms) *ms = r.ms;
+  if (alg_bytes) *alg_bytes = r.bytes;
+  if (model_flops) *model_flops = r.flops;
   return SCAT_OK;
 }
 

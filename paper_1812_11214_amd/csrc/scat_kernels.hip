@@ -14,11 +14,32 @@
 // intermediates, modulus non-linearity.
 #include <hip/hip_runtime.h>
 
+#include <cmath>
+#include <string>
+
+#include "fft_regs.hpp"
 #include "scat_kernels.hpp"
 
 namespace scat {
 
 namespace {
+
+thread_local LaunchObserver *g_observer = nullptr;
+
+// 5 n log2 n, the usual flop model of one complex transform of n points
+double fft_flops(double n) { return n > 1 ? 5.0 * n * std::log2(n) : 0.0; }
+
+struct Observe {
+  hipStream_t st;
+  bool on;
+  Observe(const char *name, double bytes, double flops, hipStream_t s) : st(s), on(g_observer != nullptr) {
+    if (on) g_observer->before(name, bytes, flops, st);
+  }
+  ~Observe() {
+    if (on) g_observer->after(st);
+  }
+};
+
 
 __device__ __forceinline__ float2 cmul(float2 a, float2 b) {
   return make_float2(a.x * b.x - a.y * b.y, a.x * b.y + a.y * b.x);
@@ -299,6 +320,240 @@ __global__ void k_row_lowpass(const float *__restrict__ w, int m_r, int Mc, int 
   for (int t = threadIdx.x; t < RB * m_c; t += blockDim.x) op[t] = low[t].x;
 }
 
+
+// ------------------------------------------------------------------------------------
+// Column pass with register-resident transforms (column length MR = 16 * T, compile
+// time).  Same contract as k_col<0> / k_col<1>; T threads share one column, TC columns
+// per workgroup (blockDim = T * TC, thread = c + TC * t so that global accesses run
+// along rows).  LDS: 16 * (T*TC + 16) complex for the exchanges, then m_r * TC complex
+// for the small lowpass transform.
+template <int MR, int MODE>
+__global__ __launch_bounds__(256) void k_col_fast(const void *__restrict__ src_v, int Mc, int TC,
+                           float2 *__restrict__ uc, const float *__restrict__ phi_rows, int m_r,
+                           float *__restrict__ w_out, const float2 *__restrict__ tw, int tw_n) {
+  constexpr int E = 16, T = MR / 16;
+  extern __shared__ float2 lds[];
+  const int KS = T * TC + 16;
+  const int c = threadIdx.x % TC, t = threadIdx.x / TC;
+  const int tiles = Mc / TC;
+  const int node = blockIdx.x / tiles;
+  const int c0 = (blockIdx.x % tiles) * TC;
+  const size_t plane = static_cast<size_t>(node) * MR * Mc;
+  float2 wt[E];
+  load_twiddles<E, T>(wt, t, tw, tw_n);
+  float2 v[E];
+  if (MODE == 0) {
+    const float *sp = static_cast<const float *>(src_v) + plane + c0 + c;
+#pragma unroll
+    for (int i = 0; i < E; ++i) v[i] = make_float2(sp[static_cast<size_t>(t + T * i) * Mc], 0.f);
+  } else {
+    const float2 *sp = static_cast<const float2 *>(src_v) + plane + c0 + c;
+#pragma unroll
+    for (int i = 0; i < E; ++i) v[i] = sp[static_cast<size_t>(t + T * i) * Mc];
+    fft_core<E, T, true>(v, t, lds + c, KS, TC, wt);
+#pragma unroll
+    for (int i = 0; i < E; ++i) v[i] = make_float2(sqrtf(v[i].x * v[i].x + v[i].y * v[i].y), 0.f);
+  }
+  fft_core<E, T, false>(v, t, lds + c, KS, TC, wt);
+  if (uc != nullptr) {
+    float2 *up = uc + plane + c0 + c;
+#pragma unroll
+    for (int i = 0; i < E; ++i) up[static_cast<size_t>(t + T * i) * Mc] = v[i];
+  }
+  if (w_out != nullptr) {
+    // spectrum * phi in natural row order, then fold and a small inverse transform
+#pragma unroll
+    for (int i = 0; i < E; ++i) {
+      const int r = t + T * i;
+      const float f = phi_rows[r];
+      lds[r * TC + c] = make_float2(v[i].x * f, v[i].y * f);
+    }
+    __syncthreads();
+    float2 *low = lds + E * KS;
+    const int log2m = ilog2(m_r);
+    const int nf = MR / m_r;
+    for (int idx = threadIdx.x; idx < m_r * TC; idx += blockDim.x) {
+      int m = idx / TC, cc = idx % TC;
+      float2 acc = make_float2(0.f, 0.f);
+      for (int a = 0; a < nf; ++a) acc = cadd(acc, lds[(m + a * m_r) * TC + cc]);
+      low[bitrev(m, log2m) * TC + cc] = acc;
+    }
+    lds_fft<true, true>(low, log2m, TC, 1, TC, tw, tw_n);
+    float *wp = w_out + static_cast<size_t>(node) * m_r * Mc;
+    for (int idx = threadIdx.x; idx < m_r * TC; idx += blockDim.x) {
+      int m = idx / TC, cc = idx % TC;
+      wp[static_cast<size_t>(m) * Mc + c0 + cc] = low[idx].x;
+    }
+  }
+}
+
+template <int MR>
+hipError_t launch_col_fast_t(int mode, const void *src, long nodes, int Mc, float2 *uc,
+                             const float *phi_rows, int m_r, float *w_out, const float2 *tw,
+                             int tw_n, hipStream_t st) {
+  constexpr int T = MR / 16;
+  int TC = 256 / T;
+  if (TC < 16) TC = 16;
+  if (TC > Mc) TC = Mc;
+  long blocks = nodes * (Mc / TC);
+  if (blocks <= 0 || blocks > 0x7fffffffL) return hipErrorInvalidValue;
+  size_t lds = (static_cast<size_t>(16) * (T * TC + 16) + (w_out ? static_cast<size_t>(m_r) * TC : 0)) *
+               sizeof(float2);
+  dim3 g(static_cast<unsigned>(blocks)), b(T * TC);
+  static const std::string names[2] = {"k_col_fast<" + std::to_string(MR) + ", 0>",
+                                       "k_col_fast<" + std::to_string(MR) + ", 1>"};
+  const double pts = static_cast<double>(nodes) * MR * Mc;
+  const double cols = static_cast<double>(nodes) * Mc;
+  Observe ob(names[mode ? 1 : 0].c_str(),
+             pts * (mode == 0 ? 4 : 8) + (uc ? pts * 8 : 0) + (w_out ? cols * m_r * 4 + MR * 4.0 : 0),
+             cols * ((mode ? 2 : 1) * fft_flops(MR) + (w_out ? fft_flops(m_r) + 2.0 * MR : 0)) +
+                 (mode ? 4.0 * pts : 0),
+             st);
+  if (mode == 0)
+    hipLaunchKernelGGL((k_col_fast<MR, 0>), g, b, lds, st, src, Mc, TC, uc, phi_rows, m_r, w_out, tw,
+                       tw_n);
+  else
+    hipLaunchKernelGGL((k_col_fast<MR, 1>), g, b, lds, st, src, Mc, TC, uc, phi_rows, m_r, w_out, tw,
+                       tw_n);
+  return hipGetLastError();
+}
+
+
+// ------------------------------------------------------------------------------------
+// Fused row pass: forward row FFT of column-transformed sources, then for every level
+// (one octave of wavelets applied at fold 2^f) filter multiply + fold + inverse row FFT.
+// The full 2-D spectrum of the source therefore never goes to memory.
+//
+// src : [NS][Sr][SC] complex, rows already transformed along columns (k_r, c).
+// Rows are processed in groups {q + (Sr/G) a, a < G}, G = 2^fmax, which are closed under
+// every level's row fold.  A workgroup takes NGRP consecutive groups of two consecutive
+// sources; the two sources share every filter value that is loaded.
+// Level output: dst[(src * F + theta)][q_r][.] for q_r < Sr >> f, row length SC >> f.
+struct FusedLevelDev {
+  int f, F;
+  const float *filt;  // [F][Sr][SC], carries the 1/(Sr*SC) normalisation
+  float2 *dst;        // [NS*F][Sr>>f][SC>>f]
+};
+struct FusedArgsDev {
+  FusedLevelDev lv[4];
+  int nlev;
+};
+
+template <int TP>
+__device__ __forceinline__ void fused_level(const FusedLevelDev &L, int Sr, int SC, int G, int NGRP,
+                                            int n_src, long src0, int grp0, const float2 *xr,
+                                            int RS, float2 *xch, const float2 *__restrict__ tw,
+                                            int tw_n) {
+  constexpr int M = 16 * TP;
+  const int f = L.f, nf = 1 << f, Gf = G >> f;
+  const int Mr = Sr >> f;
+  const int slots = blockDim.x / TP;
+  const int slot = threadIdx.x / TP, t = threadIdx.x % TP;
+  const int items = L.F * Gf * NGRP;
+  const int rows_per_group_stride = Sr / G;
+  float2 wt[16];
+  load_twiddles<16, TP>(wt, t, tw, tw_n);
+  float2 *my_xch = xch + slot * 16 * (TP + 1);
+  for (int it0 = 0; it0 < items; it0 += slots) {
+    const int item = it0 + slot;
+    const bool active = item < items;
+    const int theta = active ? item / (Gf * NGRP) : 0;
+    const int rem = active ? item % (Gf * NGRP) : 0;
+    const int g = rem / Gf, ap = rem % Gf;
+    const int qr = grp0 + g + rows_per_group_stride * ap;
+    // the two sources are taken one after the other; the second pass finds the filter
+    // values of the first in the vector L1 cache
+    for (int s = 0; s < 2; ++s) {
+      float2 acc[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[i] = make_float2(0.f, 0.f);
+      for (int a = 0; a < nf; ++a) {
+        const int ag = ap + a * Gf;
+        const float2 *r0 = xr + static_cast<size_t>((s * NGRP + g) * G + ag) * RS;
+        const float *fp = L.filt + (static_cast<size_t>(theta) * Sr + qr + a * Mr) * SC;
+        for (int b = 0; b < nf; ++b) {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const int col = t + TP * i + b * M;
+            const float fv = fp[col];
+            const float2 u0 = r0[col];
+            acc[i].x += u0.x * fv;
+            acc[i].y += u0.y * fv;
+          }
+        }
+      }
+      fft_core<16, TP, true>(acc, t, my_xch, TP + 1, 1, wt);
+      if (active && s < n_src) {
+        float2 *dp = L.dst + ((static_cast<size_t>(src0 + s) * L.F + theta) * Mr + qr) * M + t;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) dp[TP * i] = acc[i];
+      }
+    }
+  }
+}
+
+template <int SC>
+__global__ __launch_bounds__(256) void k_rows_fused(const float2 *__restrict__ src, long NS, int Sr,
+                                                    int G, int NGRP, FusedArgsDev args,
+                                                    const float2 *__restrict__ tw, int tw_n) {
+  constexpr int T = SC / 16;
+  constexpr int RS = 16 * (T + 1);
+  extern __shared__ float2 lds[];
+  const int groups = Sr / G;
+  const int wg_per_pair = groups / NGRP;
+  const long pair = blockIdx.x / wg_per_pair;
+  const int grp0 = (blockIdx.x % wg_per_pair) * NGRP;
+  const long src0 = 2 * pair;
+  const int n_src = (NS - src0) >= 2 ? 2 : 1;
+  const int nrows = 2 * NGRP * G;
+  float2 *xr = lds;
+  float2 *xch = lds + static_cast<size_t>(nrows) * RS;
+  // ---- phase 1: forward row FFT of the group rows, kept in LDS in natural order
+  {
+    float2 wt[16];
+    const int t = threadIdx.x % T;
+    load_twiddles<16, T>(wt, t, tw, tw_n);
+    const int per_pass = blockDim.x / T;
+    for (int r0 = 0; r0 < nrows; r0 += per_pass) {
+      const int rho = r0 + threadIdx.x / T;
+      const bool live = rho < nrows;
+      const int rr = live ? rho : 0;
+      const int s = rr / (NGRP * G), g = (rr / G) % NGRP, ag = rr % G;
+      float2 v[16];
+      if (live && s < n_src) {
+        const float2 *sp = src + ((src0 + s) * Sr + (grp0 + g + groups * ag)) * SC + t;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) v[i] = sp[T * i];
+      } else {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) v[i] = make_float2(0.f, 0.f);
+      }
+      float2 *row = xr + static_cast<size_t>(rr) * RS;
+      // rows past nrows (block larger than the row count) run the transform on zeros in
+      // the exchange area that follows the row storage, to keep the barriers uniform
+      float2 *ex = live ? row : xch + static_cast<size_t>(threadIdx.x / T) * RS;
+      fft_core<16, T, false>(v, t, ex, T + 1, 1, wt);
+      if (live) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) row[t + T * i] = v[i];
+      }
+    }
+    __syncthreads();
+  }
+  // ---- phase 2: every level
+  for (int l = 0; l < args.nlev; ++l) {
+    const FusedLevelDev &L = args.lv[l];
+    switch ((SC >> L.f) / 16) {
+      case 16: fused_level<16>(L, Sr, SC, G, NGRP, n_src, src0, grp0, xr, RS, xch, tw, tw_n); break;
+      case 8: fused_level<8>(L, Sr, SC, G, NGRP, n_src, src0, grp0, xr, RS, xch, tw, tw_n); break;
+      case 4: fused_level<4>(L, Sr, SC, G, NGRP, n_src, src0, grp0, xr, RS, xch, tw, tw_n); break;
+      case 2: fused_level<2>(L, Sr, SC, G, NGRP, n_src, src0, grp0, xr, RS, xch, tw, tw_n); break;
+      case 1: fused_level<1>(L, Sr, SC, G, NGRP, n_src, src0, grp0, xr, RS, xch, tw, tw_n); break;
+      default: break;
+    }
+  }
+}
+
 constexpr int kThreads = 256;
 constexpr int kTileElems = 4096;  // complex elements of one workgroup's LDS tile (32 KB)
 
@@ -312,6 +567,8 @@ int pow2_floor(int v) {
 
 // ----------------------------------------------------------------------------- launchers
 
+void set_launch_observer(LaunchObserver *o) { g_observer = o; }
+
 hipError_t launch_mulfold_invrow(const float2 *src, const float *filt, float2 *dst, long S, int F,
                                  int Sr, int Sc, int fr, int fc, int post_tw_m, const float2 *tw,
                                  int tw_n, hipStream_t st) {
@@ -322,6 +579,9 @@ hipError_t launch_mulfold_invrow(const float2 *src, const float *filt, float2 *d
   long blocks = S * F * (Mr / RB);
   if (blocks <= 0 || blocks > 0x7fffffffL) return hipErrorInvalidValue;
   size_t lds = static_cast<size_t>(RB) * Mc * sizeof(float2);
+  const double spts = static_cast<double>(S) * Sr * Sc, opts = static_cast<double>(S) * F * Mr * Mc;
+  Observe ob("k_mulfold_invrow", spts * 8 + static_cast<double>(F) * Sr * Sc * 4 + opts * 8,
+             static_cast<double>(S) * F * Mr * fft_flops(Mc) + 4.0 * spts * F, st);
   hipLaunchKernelGGL(k_mulfold_invrow, dim3(static_cast<unsigned>(blocks)), dim3(kThreads), lds, st,
                      src, filt, dst, F, Sr, Sc, fr, fc, RB, post_tw_m, tw, tw_n);
   return hipGetLastError();
@@ -330,6 +590,17 @@ hipError_t launch_mulfold_invrow(const float2 *src, const float *filt, float2 *d
 hipError_t launch_col(int mode, const void *src, long nodes, int Mr, int Mc, float2 *uc,
                       int post_tw_m, const float *phi_rows, int m_r, float *w_out, float *out,
                       ChanMap cm, int K, const float2 *tw, int tw_n, hipStream_t st) {
+  // register-resident variant: modes 0/1, no four-step twiddle, column length 16*T with
+  // T | 16, at least 16 columns, lowpass length dividing the column length
+  if (mode != 2 && post_tw_m == 0 && Mc >= 16 && (w_out == nullptr || (m_r >= 1 && m_r <= Mr))) {
+    switch (Mr) {
+      case 32: return launch_col_fast_t<32>(mode, src, nodes, Mc, uc, phi_rows, m_r, w_out, tw, tw_n, st);
+      case 64: return launch_col_fast_t<64>(mode, src, nodes, Mc, uc, phi_rows, m_r, w_out, tw, tw_n, st);
+      case 128: return launch_col_fast_t<128>(mode, src, nodes, Mc, uc, phi_rows, m_r, w_out, tw, tw_n, st);
+      case 256: return launch_col_fast_t<256>(mode, src, nodes, Mc, uc, phi_rows, m_r, w_out, tw, tw_n, st);
+      default: break;
+    }
+  }
   int TC = pow2_floor(kTileElems / Mr);
   if (TC > 16) TC = 16;
   if (TC > Mc) TC = Mc;
@@ -338,6 +609,15 @@ hipError_t launch_col(int mode, const void *src, long nodes, int Mr, int Mc, flo
   if (blocks <= 0 || blocks > 0x7fffffffL) return hipErrorInvalidValue;
   size_t lds = (static_cast<size_t>(Mr) + (w_out ? m_r : 0)) * TC * sizeof(float2);
   dim3 g(static_cast<unsigned>(blocks)), b(kThreads);
+  static const char *const names[3] = {"k_col<0>", "k_col<1>", "k_col<2>"};
+  const double pts = static_cast<double>(nodes) * Mr * Mc;
+  const double cols = static_cast<double>(nodes) * Mc;
+  Observe ob(names[mode < 0 || mode > 2 ? 0 : mode],
+             pts * (mode == 0 ? 4 : 8) + (uc ? pts * 8 : 0) + (w_out ? cols * m_r * 4 : 0) +
+                 (mode == 2 ? pts * 4 : 0),
+             cols * ((mode == 1 ? 2 : 1) * fft_flops(Mr) + (w_out ? fft_flops(m_r) + 2.0 * Mr : 0)) +
+                 (mode == 1 ? 4.0 * pts : 0),
+             st);
   switch (mode) {
     case 0:
       hipLaunchKernelGGL(k_col<0>, g, b, lds, st, src, Mr, Mc, TC, uc, post_tw_m, phi_rows, m_r,
@@ -365,6 +645,7 @@ hipError_t launch_row_fwd(float2 *data, long rows, int Mc, const float2 *tw, int
   long blocks = rows / RB;
   if (blocks <= 0 || blocks > 0x7fffffffL) return hipErrorInvalidValue;
   size_t lds = static_cast<size_t>(RB) * Mc * sizeof(float2);
+  Observe ob("k_row_fwd", static_cast<double>(rows) * Mc * 16, static_cast<double>(rows) * fft_flops(Mc), st);
   hipLaunchKernelGGL(k_row_fwd, dim3(static_cast<unsigned>(blocks)), dim3(kThreads), lds, st, data,
                      Mc, RB, tw, tw_n);
   return hipGetLastError();
@@ -379,8 +660,78 @@ hipError_t launch_row_lowpass(const float *w, long nodes, int m_r, int Mc, int m
   long blocks = nodes * (m_r / RB);
   if (blocks <= 0 || blocks > 0x7fffffffL) return hipErrorInvalidValue;
   size_t lds = static_cast<size_t>(RB) * (Mc + m_c) * sizeof(float2);
+  const double rws = static_cast<double>(nodes) * m_r;
+  Observe ob("k_row_lowpass", rws * (Mc + m_c) * 4, rws * (fft_flops(Mc) + fft_flops(m_c) + 2.0 * Mc), st);
   hipLaunchKernelGGL(k_row_lowpass, dim3(static_cast<unsigned>(blocks)), dim3(kThreads), lds, st, w,
                      m_r, Mc, m_c, RB, phi_cols, out, cm, K, tw, tw_n);
+  return hipGetLastError();
+}
+
+
+bool rows_fused_supported(int Sr, int Sc, int fmax) {
+  if (Sc != 32 && Sc != 64 && Sc != 128 && Sc != 256) return false;
+  if (fmax < 0 || fmax > 3) return false;
+  if ((Sc >> fmax) < 16) return false;
+  if ((Sr >> fmax) < 1) return false;
+  return true;
+}
+
+hipError_t launch_rows_fused(const float2 *src, long NS, int Sr, int Sc, const FusedLevel *levels,
+                             int nlev, const float2 *tw, int tw_n, hipStream_t st) {
+  if (nlev < 1 || nlev > 4) return hipErrorInvalidValue;
+  int fmax = 0;
+  FusedArgsDev args;
+  args.nlev = nlev;
+  for (int l = 0; l < nlev; ++l) {
+    args.lv[l].f = levels[l].f;
+    args.lv[l].F = levels[l].F;
+    args.lv[l].filt = levels[l].filt;
+    args.lv[l].dst = levels[l].dst;
+    if (levels[l].f > fmax) fmax = levels[l].f;
+  }
+  if (!rows_fused_supported(Sr, Sc, fmax)) return hipErrorInvalidValue;
+  const int G = 1 << fmax;
+  const int T = Sc / 16;
+  const int groups = Sr / G;
+  // threads per workgroup: 128 keeps the LDS footprint of one workgroup under 48 KB
+  const int BS = 128;
+  int NGRP = BS / (2 * G * T);
+  if (NGRP < 1) NGRP = 1;
+  if (NGRP > groups) NGRP = groups;
+  const int nrows = 2 * NGRP * G;
+  const int RS = 16 * (T + 1);
+  // exchange area of phase 2: the widest level decides; it also backs phase 1's idle rows
+  size_t xch = 0;
+  for (int l = 0; l < nlev; ++l) {
+    int TP = (Sc >> levels[l].f) / 16;
+    size_t need = static_cast<size_t>(BS / TP) * 16 * (TP + 1);
+    if (need > xch) xch = need;
+  }
+  size_t idle = static_cast<size_t>(BS / T) * RS;
+  if (idle > xch) xch = idle;
+  size_t lds = (static_cast<size_t>(nrows) * RS + xch) * sizeof(float2);
+  if (lds > 65536) return hipErrorInvalidValue;
+  long blocks = ((NS + 1) / 2) * (groups / NGRP);
+  if (blocks <= 0 || blocks > 0x7fffffffL) return hipErrorInvalidValue;
+  dim3 g(static_cast<unsigned>(blocks)), b(BS);
+  static const std::string names[4] = {"k_rows_fused<32>", "k_rows_fused<64>", "k_rows_fused<128>",
+                                       "k_rows_fused<256>"};
+  const double spts = static_cast<double>(NS) * Sr * Sc;
+  double bytes = spts * 8, flops = static_cast<double>(NS) * Sr * fft_flops(Sc);
+  for (int l = 0; l < nlev; ++l) {
+    const int f = levels[l].f, F = levels[l].F;
+    const double opts = static_cast<double>(NS) * F * (Sr >> f) * (Sc >> f);
+    bytes += opts * 8 + static_cast<double>(F) * Sr * Sc * 4;
+    flops += static_cast<double>(NS) * F * (Sr >> f) * fft_flops(Sc >> f) + 4.0 * spts * F;
+  }
+  Observe ob(names[Sc == 32 ? 0 : Sc == 64 ? 1 : Sc == 128 ? 2 : 3].c_str(), bytes, flops, st);
+  switch (Sc) {
+    case 32: hipLaunchKernelGGL(k_rows_fused<32>, g, b, lds, st, src, NS, Sr, G, NGRP, args, tw, tw_n); break;
+    case 64: hipLaunchKernelGGL(k_rows_fused<64>, g, b, lds, st, src, NS, Sr, G, NGRP, args, tw, tw_n); break;
+    case 128: hipLaunchKernelGGL(k_rows_fused<128>, g, b, lds, st, src, NS, Sr, G, NGRP, args, tw, tw_n); break;
+    case 256: hipLaunchKernelGGL(k_rows_fused<256>, g, b, lds, st, src, NS, Sr, G, NGRP, args, tw, tw_n); break;
+    default: return hipErrorInvalidValue;
+  }
   return hipGetLastError();
 }
 

@@ -5,6 +5,17 @@
 
 namespace scat {
 
+// Optional per-thread hook called around every kernel launch of this file: `before` gets
+// the kernel's name as a profiler prints it, the bytes the launch must move at the least
+// (inputs and filter tables read once, outputs written once) and its model flops
+// (5 n log2 n per transform plus the pointwise work).
+struct LaunchObserver {
+  virtual void before(const char *name, double bytes, double flops, hipStream_t st) = 0;
+  virtual void after(hipStream_t st) = 0;
+  virtual ~LaunchObserver() = default;
+};
+void set_launch_observer(LaunchObserver *o);
+
 // Where a kernel's node number g (within one input plane p) lands in the output:
 // channel = base + (g / inner) * outer_stride + (g % inner), node = p * G + g.
 struct ChanMap {
@@ -25,5 +36,21 @@ hipError_t launch_row_fwd(float2 *data, long rows, int Mc, const float2 *tw, int
 hipError_t launch_row_lowpass(const float *w, long nodes, int m_r, int Mc, int m_c,
                               const float *phi_cols, float *out, ChanMap cm, int K,
                               const float2 *tw, int tw_n, hipStream_t st);
+
+// One level of the fused row pass: wavelets `filt` ([F][Sr][Sc] real, pre-scaled) applied
+// with fold 2^f on both axes, outputs to dst [NS*F][Sr>>f][Sc>>f].
+struct FusedLevel {
+  int f, F;
+  const float *filt;
+  float2 *dst;
+};
+
+// True if launch_rows_fused can handle sources of Sr x Sc with largest fold 2^fmax.
+bool rows_fused_supported(int Sr, int Sc, int fmax);
+
+// Forward row FFT of column-transformed sources [NS][Sr][Sc], then every level's filter
+// multiply + fold + inverse row FFT (see k_rows_fused).
+hipError_t launch_rows_fused(const float2 *src, long NS, int Sr, int Sc, const FusedLevel *levels,
+                             int nlev, const float2 *tw, int tw_n, hipStream_t st);
 
 }  // namespace scat
