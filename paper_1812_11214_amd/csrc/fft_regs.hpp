@@ -122,11 +122,30 @@ __device__ __forceinline__ void load_twiddles(float2 (&wt)[E], int t, const floa
   for (int k1 = 0; k1 < E; ++k1) wt[k1] = tw[t * k1 * step];
 }
 
+// Orders LDS accesses of the lanes of one wavefront: everything written before is visible
+// to every lane after.  (LDS operations of one wave complete in issue order; the fences
+// keep the compiler from moving accesses across.)
+__device__ __forceinline__ void wave_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <bool WAVE>
+__device__ __forceinline__ void group_sync() {
+  if (WAVE)
+    wave_sync();
+  else
+    __syncthreads();
+}
+
 // The transform described at the top of this file.  xch points at this transform's
 // exchange area in LDS, already offset for anything but (k1, t): element (k1, t) lives at
-// xch[k1 * sk + t * st].  Contains two workgroup barriers when T > 1 (one before the
-// exchange buffer is read, one after), so every thread of the workgroup must call it.
-template <int E, int T, bool INV>
+// xch[k1 * sk + t * st].  When T > 1 it synchronises twice (before the exchange buffer is
+// read, and after): with WAVE = false by workgroup barriers, so every thread of the
+// workgroup must call it; with WAVE = true only within the wavefront, which requires the T
+// threads of a transform to be lanes of one wave.
+template <int E, int T, bool INV, bool WAVE = false>
 __device__ __forceinline__ void fft_core(float2 (&v)[E], int t, float2 *xch, int sk, int st,
                                          const float2 (&wt)[E]) {
   DftRegs<E, INV>::run(v);
@@ -139,7 +158,7 @@ __device__ __forceinline__ void fft_core(float2 (&v)[E], int t, float2 *xch, int
   }
 #pragma unroll
   for (int k1 = 0; k1 < E; ++k1) xch[k1 * sk + t * st] = v[k1];
-  __syncthreads();
+  group_sync<WAVE>();
   constexpr int U = E / T;
 #pragma unroll
   for (int u = 0; u < U; ++u) {
@@ -151,7 +170,7 @@ __device__ __forceinline__ void fft_core(float2 (&v)[E], int t, float2 *xch, int
 #pragma unroll
     for (int k2 = 0; k2 < T; ++k2) v[u + U * k2] = a[k2];
   }
-  __syncthreads();
+  group_sync<WAVE>();
 }
 
 }  // namespace scat

@@ -439,116 +439,180 @@ struct FusedArgsDev {
   int nlev;
 };
 
-template <int TP>
-__device__ __forceinline__ void fused_level(const FusedLevelDev &L, int Sr, int SC, int G, int NGRP,
-                                            int n_src, long src0, int grp0, const float2 *xr,
-                                            int RS, float2 *xch, const float2 *__restrict__ tw,
-                                            int tw_n) {
+// Filter values of CPL consecutive columns, and the multiply-accumulate of CPL complex
+// points by them.
+template <int CPL>
+struct FiltVec;
+template <>
+struct FiltVec<1> {
+  float f;
+  __device__ __forceinline__ void load(const float *p) { f = *p; }
+  __device__ __forceinline__ void fma(float2 (&acc)[1], const float2 *r) const {
+    const float2 u = r[0];
+    acc[0].x += u.x * f;
+    acc[0].y += u.y * f;
+  }
+};
+template <>
+struct FiltVec<2> {
+  float2 f;
+  __device__ __forceinline__ void load(const float *p) { f = *reinterpret_cast<const float2 *>(p); }
+  __device__ __forceinline__ void fma(float2 (&acc)[2], const float2 *r) const {
+    const float4 u = *reinterpret_cast<const float4 *>(r);
+    acc[0].x += u.x * f.x;
+    acc[0].y += u.y * f.x;
+    acc[1].x += u.z * f.y;
+    acc[1].y += u.w * f.y;
+  }
+};
+template <>
+struct FiltVec<4> {
+  float4 f;
+  __device__ __forceinline__ void load(const float *p) { f = *reinterpret_cast<const float4 *>(p); }
+  __device__ __forceinline__ void fma(float2 (&acc)[4], const float2 *r) const {
+    const float4 u = *reinterpret_cast<const float4 *>(r);
+    const float4 w = *reinterpret_cast<const float4 *>(r + 2);
+    acc[0].x += u.x * f.x;
+    acc[0].y += u.y * f.x;
+    acc[1].x += u.z * f.y;
+    acc[1].y += u.w * f.y;
+    acc[2].x += w.x * f.z;
+    acc[2].y += w.y * f.z;
+    acc[3].x += w.z * f.w;
+    acc[3].y += w.w * f.w;
+  }
+};
+
+// One level of the fused row pass for one wavefront.  The wave owns the LDS rows R
+// (rows of SC points, natural order) of its source.  Items = (filter, output row);
+// 64/TP of them form a batch: first every item's folded product row is accumulated by the
+// whole wave (lane l owns M/64 consecutive output columns, so filter and LDS reads are
+// contiguous across the wave) into B, then each group of TP lanes transforms one row.
+// The accumulation is unrolled over IC items so that about 32 filter loads are in flight.
+// lgGf, lgNGRP: log2 of the output rows per group at this level and of the groups per wave.
+template <int SC, int FL>
+__device__ __forceinline__ void fused_level_w(const FusedLevelDev &L, int Sr, int lgG, int lgNGRP,
+                                              long src_idx, int grp0, const float2 *R, float2 *B,
+                                              int lane, const float2 *__restrict__ tw, int tw_n) {
+  constexpr int TP = (SC / 16) >> FL;
   constexpr int M = 16 * TP;
-  const int f = L.f, nf = 1 << f, Gf = G >> f;
-  const int Mr = Sr >> f;
-  const int slots = blockDim.x / TP;
-  const int slot = threadIdx.x / TP, t = threadIdx.x % TP;
-  const int items = L.F * Gf * NGRP;
-  const int rows_per_group_stride = Sr / G;
+  constexpr int SLOTS = 64 / TP;
+  constexpr int CPL = M >= 64 ? M / 64 : 1;  // output columns per lane
+  constexpr int SLOT_STRIDE = TP > 1 ? 16 * (TP + 1) : 16;
+  constexpr int NF = 1 << FL, TERMS = NF * NF;
+  constexpr int IC0 = 32 / TERMS < 1 ? 1 : 32 / TERMS;
+  constexpr int IC = IC0 > SLOTS ? SLOTS : IC0;
+  const int lgGf = lgG - FL;
+  const int Gf = 1 << lgGf;
+  const int Mr = Sr >> FL;
+  const int items = L.F << (lgGf + lgNGRP);
+  const int rows_step = Sr >> lgG;
+  const int slot = lane / TP, t = lane % TP;
+  const int lcol = (lane * CPL) % M;  // lanes past M (only when M < 64) repeat valid columns
   float2 wt[16];
   load_twiddles<16, TP>(wt, t, tw, tw_n);
-  float2 *my_xch = xch + slot * 16 * (TP + 1);
-  for (int it0 = 0; it0 < items; it0 += slots) {
+  for (int it0 = 0; it0 < items; it0 += SLOTS) {
+#pragma unroll 1
+    for (int s0 = 0; s0 < SLOTS; s0 += IC) {
+      FiltVec<CPL> fv[IC][TERMS];
+      const float2 *rb[IC];
+#pragma unroll
+      for (int s = 0; s < IC; ++s) {
+        int item = it0 + s0 + s;
+        item = item < items ? item : items - 1;  // surplus slots recompute the last item
+        const int theta = item >> (lgGf + lgNGRP);
+        const int rem = item & ((1 << (lgGf + lgNGRP)) - 1);
+        const int g = rem >> lgGf, ap = rem & (Gf - 1);
+        const int qr = grp0 + g + rows_step * ap;
+        const float *fp = L.filt + (static_cast<size_t>(theta) * Sr + qr) * SC + lcol;
+        rb[s] = R + static_cast<size_t>((g << lgG) + ap) * SC + lcol;
+#pragma unroll
+        for (int a = 0; a < NF; ++a)
+#pragma unroll
+          for (int b = 0; b < NF; ++b)
+            fv[s][a * NF + b].load(fp + static_cast<size_t>(a) * Mr * SC + b * M);
+      }
+#pragma unroll
+      for (int s = 0; s < IC; ++s) {
+        float2 acc[CPL];
+#pragma unroll
+        for (int e = 0; e < CPL; ++e) acc[e] = make_float2(0.f, 0.f);
+#pragma unroll
+        for (int a = 0; a < NF; ++a)
+#pragma unroll
+          for (int b = 0; b < NF; ++b)
+            fv[s][a * NF + b].fma(acc, rb[s] + static_cast<size_t>(a * Gf) * SC + b * M);
+#pragma unroll
+        for (int e = 0; e < CPL; ++e) B[(s0 + s) * SLOT_STRIDE + lcol + e] = acc[e];
+      }
+    }
+    wave_sync();
     const int item = it0 + slot;
     const bool active = item < items;
-    const int theta = active ? item / (Gf * NGRP) : 0;
-    const int rem = active ? item % (Gf * NGRP) : 0;
-    const int g = rem / Gf, ap = rem % Gf;
-    const int qr = grp0 + g + rows_per_group_stride * ap;
-    // the two sources are taken one after the other; the second pass finds the filter
-    // values of the first in the vector L1 cache
-    for (int s = 0; s < 2; ++s) {
-      float2 acc[16];
+    float2 v[16];
 #pragma unroll
-      for (int i = 0; i < 16; ++i) acc[i] = make_float2(0.f, 0.f);
-      for (int a = 0; a < nf; ++a) {
-        const int ag = ap + a * Gf;
-        const float2 *r0 = xr + static_cast<size_t>((s * NGRP + g) * G + ag) * RS;
-        const float *fp = L.filt + (static_cast<size_t>(theta) * Sr + qr + a * Mr) * SC;
-        for (int b = 0; b < nf; ++b) {
+    for (int i = 0; i < 16; ++i) v[i] = B[slot * SLOT_STRIDE + t + TP * i];
+    wave_sync();
+    fft_core<16, TP, true, true>(v, t, B + slot * SLOT_STRIDE, TP + 1, 1, wt);
+    if (TP == 1) wave_sync();
+    if (active) {
+      const int theta = item >> (lgGf + lgNGRP);
+      const int rem = item & ((1 << (lgGf + lgNGRP)) - 1);
+      const int g = rem >> lgGf, ap = rem & (Gf - 1);
+      const int qr = grp0 + g + rows_step * ap;
+      float2 *dp = L.dst + ((static_cast<size_t>(src_idx) * L.F + theta) * Mr + qr) * M + t;
 #pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const int col = t + TP * i + b * M;
-            const float fv = fp[col];
-            const float2 u0 = r0[col];
-            acc[i].x += u0.x * fv;
-            acc[i].y += u0.y * fv;
-          }
-        }
-      }
-      fft_core<16, TP, true>(acc, t, my_xch, TP + 1, 1, wt);
-      if (active && s < n_src) {
-        float2 *dp = L.dst + ((static_cast<size_t>(src0 + s) * L.F + theta) * Mr + qr) * M + t;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) dp[TP * i] = acc[i];
-      }
+      for (int i = 0; i < 16; ++i) dp[TP * i] = v[i];
     }
   }
 }
 
+// Workgroup = 4 wavefronts; wave w handles source 4*(block / per_src) + w and NGRP row
+// groups starting at grp0, entirely on its own (no workgroup barrier anywhere; the four
+// waves only share the filter rows they read through the L1 cache).
+// LDS per wave: rows_w * SC (rows) + b_words (product rows / exchange), in float2.
 template <int SC>
-__global__ __launch_bounds__(256) void k_rows_fused(const float2 *__restrict__ src, long NS, int Sr,
-                                                    int G, int NGRP, FusedArgsDev args,
+__global__ __launch_bounds__(256, 2) void k_rows_fused(const float2 *__restrict__ src, long NS, int Sr,
+                                                    int G, int b_words, FusedArgsDev args,
                                                     const float2 *__restrict__ tw, int tw_n) {
   constexpr int T = SC / 16;
-  constexpr int RS = 16 * (T + 1);
+  constexpr int RPW = 64 / T;  // rows one wave transforms at a time
   extern __shared__ float2 lds[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int rows_w = RPW > G ? RPW : G;
+  const int NGRP = rows_w / G;
   const int groups = Sr / G;
-  const int wg_per_pair = groups / NGRP;
-  const long pair = blockIdx.x / wg_per_pair;
-  const int grp0 = (blockIdx.x % wg_per_pair) * NGRP;
-  const long src0 = 2 * pair;
-  const int n_src = (NS - src0) >= 2 ? 2 : 1;
-  const int nrows = 2 * NGRP * G;
-  float2 *xr = lds;
-  float2 *xch = lds + static_cast<size_t>(nrows) * RS;
-  // ---- phase 1: forward row FFT of the group rows, kept in LDS in natural order
+  const int per_src = groups / NGRP;
+  const long src_idx = 4 * static_cast<long>(blockIdx.x / per_src) + wave;
+  const int grp0 = (blockIdx.x % per_src) * NGRP;
+  if (src_idx >= NS) return;
+  float2 *R = lds + static_cast<size_t>(wave) * (static_cast<size_t>(rows_w) * SC + b_words);
+  float2 *B = R + static_cast<size_t>(rows_w) * SC;
   {
+    const int t = lane % T, rl = lane / T;
     float2 wt[16];
-    const int t = threadIdx.x % T;
     load_twiddles<16, T>(wt, t, tw, tw_n);
-    const int per_pass = blockDim.x / T;
-    for (int r0 = 0; r0 < nrows; r0 += per_pass) {
-      const int rho = r0 + threadIdx.x / T;
-      const bool live = rho < nrows;
-      const int rr = live ? rho : 0;
-      const int s = rr / (NGRP * G), g = (rr / G) % NGRP, ag = rr % G;
+    for (int pass = 0; pass < rows_w / RPW; ++pass) {
+      const int rr = pass * RPW + rl;
+      const int g = rr / G, ag = rr % G;
+      const float2 *sp = src + (static_cast<size_t>(src_idx) * Sr + grp0 + g + groups * ag) * SC + t;
       float2 v[16];
-      if (live && s < n_src) {
-        const float2 *sp = src + ((src0 + s) * Sr + (grp0 + g + groups * ag)) * SC + t;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) v[i] = sp[T * i];
-      } else {
+      for (int i = 0; i < 16; ++i) v[i] = sp[T * i];
+      fft_core<16, T, false, true>(v, t, B + rl * 16 * (T + 1), T + 1, 1, wt);
 #pragma unroll
-        for (int i = 0; i < 16; ++i) v[i] = make_float2(0.f, 0.f);
-      }
-      float2 *row = xr + static_cast<size_t>(rr) * RS;
-      // rows past nrows (block larger than the row count) run the transform on zeros in
-      // the exchange area that follows the row storage, to keep the barriers uniform
-      float2 *ex = live ? row : xch + static_cast<size_t>(threadIdx.x / T) * RS;
-      fft_core<16, T, false>(v, t, ex, T + 1, 1, wt);
-      if (live) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) row[t + T * i] = v[i];
-      }
+      for (int i = 0; i < 16; ++i) R[rr * SC + t + T * i] = v[i];
     }
-    __syncthreads();
+    wave_sync();
   }
-  // ---- phase 2: every level
+  const int lgG = ilog2(G), lgNGRP = ilog2(NGRP);
   for (int l = 0; l < args.nlev; ++l) {
     const FusedLevelDev &L = args.lv[l];
-    switch ((SC >> L.f) / 16) {
-      case 16: fused_level<16>(L, Sr, SC, G, NGRP, n_src, src0, grp0, xr, RS, xch, tw, tw_n); break;
-      case 8: fused_level<8>(L, Sr, SC, G, NGRP, n_src, src0, grp0, xr, RS, xch, tw, tw_n); break;
-      case 4: fused_level<4>(L, Sr, SC, G, NGRP, n_src, src0, grp0, xr, RS, xch, tw, tw_n); break;
-      case 2: fused_level<2>(L, Sr, SC, G, NGRP, n_src, src0, grp0, xr, RS, xch, tw, tw_n); break;
-      case 1: fused_level<1>(L, Sr, SC, G, NGRP, n_src, src0, grp0, xr, RS, xch, tw, tw_n); break;
+    switch (L.f) {
+      case 0: fused_level_w<SC, 0>(L, Sr, lgG, lgNGRP, src_idx, grp0, R, B, lane, tw, tw_n); break;
+      case 1: fused_level_w<SC, 1>(L, Sr, lgG, lgNGRP, src_idx, grp0, R, B, lane, tw, tw_n); break;
+      case 2: if (SC >= 64) fused_level_w<(SC >= 64 ? SC : 64), 2>(L, Sr, lgG, lgNGRP, src_idx, grp0, R, B, lane, tw, tw_n); break;
+      case 3: if (SC >= 128) fused_level_w<(SC >= 128 ? SC : 128), 3>(L, Sr, lgG, lgNGRP, src_idx, grp0, R, B, lane, tw, tw_n); break;
       default: break;
     }
   }
@@ -692,28 +756,24 @@ hipError_t launch_rows_fused(const float2 *src, long NS, int Sr, int Sc, const F
   if (!rows_fused_supported(Sr, Sc, fmax)) return hipErrorInvalidValue;
   const int G = 1 << fmax;
   const int T = Sc / 16;
+  const int RPW = 64 / T;
+  const int rows_w = RPW > G ? RPW : G;
+  const int NGRP = rows_w / G;
   const int groups = Sr / G;
-  // threads per workgroup: 128 keeps the LDS footprint of one workgroup under 48 KB
-  const int BS = 128;
-  int NGRP = BS / (2 * G * T);
-  if (NGRP < 1) NGRP = 1;
-  if (NGRP > groups) NGRP = groups;
-  const int nrows = 2 * NGRP * G;
-  const int RS = 16 * (T + 1);
-  // exchange area of phase 2: the widest level decides; it also backs phase 1's idle rows
-  size_t xch = 0;
+  if (groups % NGRP != 0) return hipErrorInvalidValue;
+  // per-wave product/exchange area: phase 1 needs RPW transforms of 16*(T+1), a level
+  // with TP lanes per transform needs (64/TP) slots of 16*(TP+1) (16 if TP == 1)
+  size_t b_words = static_cast<size_t>(RPW) * 16 * (T + 1);
   for (int l = 0; l < nlev; ++l) {
     int TP = (Sc >> levels[l].f) / 16;
-    size_t need = static_cast<size_t>(BS / TP) * 16 * (TP + 1);
-    if (need > xch) xch = need;
+    size_t need = static_cast<size_t>(64 / TP) * (TP > 1 ? 16 * (TP + 1) : 16);
+    if (need > b_words) b_words = need;
   }
-  size_t idle = static_cast<size_t>(BS / T) * RS;
-  if (idle > xch) xch = idle;
-  size_t lds = (static_cast<size_t>(nrows) * RS + xch) * sizeof(float2);
-  if (lds > 65536) return hipErrorInvalidValue;
-  long blocks = ((NS + 1) / 2) * (groups / NGRP);
+  size_t lds = 4 * (static_cast<size_t>(rows_w) * Sc + b_words) * sizeof(float2);
+  if (lds > 160 * 1024) return hipErrorInvalidValue;
+  long blocks = ((NS + 3) / 4) * (groups / NGRP);
   if (blocks <= 0 || blocks > 0x7fffffffL) return hipErrorInvalidValue;
-  dim3 g(static_cast<unsigned>(blocks)), b(BS);
+  dim3 g(static_cast<unsigned>(blocks)), b(256);
   static const std::string names[4] = {"k_rows_fused<32>", "k_rows_fused<64>", "k_rows_fused<128>",
                                        "k_rows_fused<256>"};
   const double spts = static_cast<double>(NS) * Sr * Sc;
@@ -724,12 +784,24 @@ hipError_t launch_rows_fused(const float2 *src, long NS, int Sr, int Sc, const F
     bytes += opts * 8 + static_cast<double>(F) * Sr * Sc * 4;
     flops += static_cast<double>(NS) * F * (Sr >> f) * fft_flops(Sc >> f) + 4.0 * spts * F;
   }
-  Observe ob(names[Sc == 32 ? 0 : Sc == 64 ? 1 : Sc == 128 ? 2 : 3].c_str(), bytes, flops, st);
+  // workgroups may use more than the default 64 KB of LDS
+  static bool attr_set[4] = {false, false, false, false};
+  const int which = Sc == 32 ? 0 : Sc == 64 ? 1 : Sc == 128 ? 2 : 3;
+  if (!attr_set[which]) {
+    const void *fn = which == 0   ? reinterpret_cast<const void *>(k_rows_fused<32>)
+                     : which == 1 ? reinterpret_cast<const void *>(k_rows_fused<64>)
+                     : which == 2 ? reinterpret_cast<const void *>(k_rows_fused<128>)
+                                  : reinterpret_cast<const void *>(k_rows_fused<256>);
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e != hipSuccess) return e;
+    attr_set[which] = true;
+  }
+  Observe ob(names[which].c_str(), bytes, flops, st);
   switch (Sc) {
-    case 32: hipLaunchKernelGGL(k_rows_fused<32>, g, b, lds, st, src, NS, Sr, G, NGRP, args, tw, tw_n); break;
-    case 64: hipLaunchKernelGGL(k_rows_fused<64>, g, b, lds, st, src, NS, Sr, G, NGRP, args, tw, tw_n); break;
-    case 128: hipLaunchKernelGGL(k_rows_fused<128>, g, b, lds, st, src, NS, Sr, G, NGRP, args, tw, tw_n); break;
-    case 256: hipLaunchKernelGGL(k_rows_fused<256>, g, b, lds, st, src, NS, Sr, G, NGRP, args, tw, tw_n); break;
+    case 32: hipLaunchKernelGGL(k_rows_fused<32>, g, b, lds, st, src, NS, Sr, G, static_cast<int>(b_words), args, tw, tw_n); break;
+    case 64: hipLaunchKernelGGL(k_rows_fused<64>, g, b, lds, st, src, NS, Sr, G, static_cast<int>(b_words), args, tw, tw_n); break;
+    case 128: hipLaunchKernelGGL(k_rows_fused<128>, g, b, lds, st, src, NS, Sr, G, static_cast<int>(b_words), args, tw, tw_n); break;
+    case 256: hipLaunchKernelGGL(k_rows_fused<256>, g, b, lds, st, src, NS, Sr, G, static_cast<int>(b_words), args, tw, tw_n); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
