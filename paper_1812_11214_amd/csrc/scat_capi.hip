@@ -107,7 +107,7 @@ namespace {
 using scat::ChanMap;
 using scat::FilterTable;
 
-constexpr size_t kScratchBudget = size_t(1) << 30;  // bytes of scratch one chunk may use
+constexpr size_t kScratchBudget = size_t(12) << 30;  // bytes of scratch one chunk may use
 
 struct Layout {
   long chunk = 0;       // planes per chunk

@@ -618,6 +618,89 @@ __global__ __launch_bounds__(256, 2) void k_rows_fused(const float2 *__restrict_
   }
 }
 
+
+// ------------------------------------------------------------------------------------
+// Row half of the separable lowpass with register-resident transforms (row length
+// MC = 16 * T).  Two consecutive rows of a node travel as the real and imaginary part of
+// one complex signal: the lowpass is a real linear map, so the real part of the result
+// belongs to the first row and the imaginary part to the second.  Same contract as
+// k_row_lowpass; m_r must be even.  256 / T row pairs per workgroup.
+template <int MC>
+__global__ __launch_bounds__(256) void k_row_lowpass_fast(const float *__restrict__ w, long pairs,
+                                                          int m_r, int m_c,
+                                                          const float *__restrict__ phi_cols,
+                                                          float *__restrict__ out, ChanMap cm, int K,
+                                                          const float2 *__restrict__ tw, int tw_n) {
+  constexpr int E = 16, T = MC / 16, RP = 256 / T, XS = 16 * (T + 1);
+  extern __shared__ float2 lds[];
+  const int pr = threadIdx.x / T, t = threadIdx.x % T;
+  const long gp0 = static_cast<long>(blockIdx.x) * RP;
+  const long gp = gp0 + pr;
+  const bool valid = gp < pairs;
+  float2 wt[E];
+  load_twiddles<E, T>(wt, t, tw, tw_n);
+  float2 v[E];
+  if (valid) {
+    const float *wp = w + static_cast<size_t>(2 * gp) * MC + t;
+#pragma unroll
+    for (int i = 0; i < E; ++i) v[i] = make_float2(wp[T * i], wp[MC + T * i]);
+  } else {
+#pragma unroll
+    for (int i = 0; i < E; ++i) v[i] = make_float2(0.f, 0.f);
+  }
+  float2 *xch = lds + pr * XS;
+  fft_core<E, T, false>(v, t, xch, T + 1, 1, wt);
+#pragma unroll
+  for (int i = 0; i < E; ++i) {
+    const int k = t + T * i;
+    const float f = phi_cols[k];
+    xch[k] = make_float2(v[i].x * f, v[i].y * f);
+  }
+  __syncthreads();
+  float2 *low = lds + RP * XS;
+  const int log2m = ilog2(m_c);
+  const int nf = MC / m_c;
+  for (int idx = threadIdx.x; idx < RP * m_c; idx += blockDim.x) {
+    const int q = idx / m_c, m = idx % m_c;
+    float2 acc = make_float2(0.f, 0.f);
+    for (int b = 0; b < nf; ++b) acc = cadd(acc, lds[q * XS + m + b * m_c]);
+    low[q * m_c + bitrev(m, log2m)] = acc;
+  }
+  lds_fft<true, false>(low, log2m, RP, m_c, 1, tw, tw_n);
+  for (int idx = threadIdx.x; idx < RP * m_c; idx += blockDim.x) {
+    const int q = idx / m_c, m = idx % m_c;
+    const long g2 = gp0 + q;
+    if (g2 >= pairs) continue;
+    const long row = 2 * g2;
+    const long node = row / m_r;
+    const int r = static_cast<int>(row % m_r);
+    const long pl = node / cm.G;
+    const int g = static_cast<int>(node % cm.G);
+    float *op = out + ((static_cast<size_t>(pl) * K + chan_of(cm, g)) * m_r + r) * m_c + m;
+    const float2 val = low[idx];
+    op[0] = val.x;
+    op[m_c] = val.y;
+  }
+}
+
+template <int MC>
+hipError_t launch_row_lowpass_fast_t(const float *w, long nodes, int m_r, int m_c,
+                                     const float *phi_cols, float *out, ChanMap cm, int K,
+                                     const float2 *tw, int tw_n, hipStream_t st) {
+  constexpr int T = MC / 16, RP = 256 / T, XS = 16 * (T + 1);
+  const long pairs = nodes * m_r / 2;
+  long blocks = (pairs + RP - 1) / RP;
+  if (blocks <= 0 || blocks > 0x7fffffffL) return hipErrorInvalidValue;
+  size_t lds = (static_cast<size_t>(RP) * XS + static_cast<size_t>(RP) * m_c) * sizeof(float2);
+  const double rws = static_cast<double>(nodes) * m_r;
+  static const std::string name = "k_row_lowpass_fast<" + std::to_string(MC) + ">";
+  Observe ob(name.c_str(), rws * (MC + m_c) * 4,
+             rws * 0.5 * (fft_flops(MC) + fft_flops(m_c) + 2.0 * MC), st);
+  hipLaunchKernelGGL(k_row_lowpass_fast<MC>, dim3(static_cast<unsigned>(blocks)), dim3(256), lds, st,
+                     w, pairs, m_r, m_c, phi_cols, out, cm, K, tw, tw_n);
+  return hipGetLastError();
+}
+
 constexpr int kThreads = 256;
 constexpr int kTileElems = 4096;  // complex elements of one workgroup's LDS tile (32 KB)
 
@@ -718,6 +801,15 @@ hipError_t launch_row_fwd(float2 *data, long rows, int Mc, const float2 *tw, int
 hipError_t launch_row_lowpass(const float *w, long nodes, int m_r, int Mc, int m_c,
                               const float *phi_cols, float *out, ChanMap cm, int K,
                               const float2 *tw, int tw_n, hipStream_t st) {
+  if (m_r % 2 == 0 && m_c <= Mc) {
+    switch (Mc) {
+      case 32: return launch_row_lowpass_fast_t<32>(w, nodes, m_r, m_c, phi_cols, out, cm, K, tw, tw_n, st);
+      case 64: return launch_row_lowpass_fast_t<64>(w, nodes, m_r, m_c, phi_cols, out, cm, K, tw, tw_n, st);
+      case 128: return launch_row_lowpass_fast_t<128>(w, nodes, m_r, m_c, phi_cols, out, cm, K, tw, tw_n, st);
+      case 256: return launch_row_lowpass_fast_t<256>(w, nodes, m_r, m_c, phi_cols, out, cm, K, tw, tw_n, st);
+      default: break;
+    }
+  }
   int RB = pow2_floor(kTileElems / Mc);
   if (RB > m_r) RB = m_r;
   if (RB < 1) return hipErrorInvalidValue;
