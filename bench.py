@@ -21,6 +21,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 WORKLOAD = 2                   # index into workloads.CONFIGS: 2-D J=3 L=8 256x256, 128x3 planes
+TRAFFIC_TAG = "2d_J3_L8_256x256_b384"
 
 
 def cpu_baseline(planes, J, L, channels, budget_s=20.0):
@@ -48,6 +49,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--cpu-seconds", type=float, default=20.0,
                     help="CPU time budget of the oracle baseline (0 disables it)")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy (a kernel of known "
+                         "traffic, to calibrate profiler byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (planes are independent, so more GPUs would "
@@ -75,6 +79,13 @@ def main():
     for _ in range(max(args.warmup, 1)):
         plan.forward(x, out=out)
     torch.cuda.synchronize()
+
+    if args.copy_probe:
+        a = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        b = torch.empty_like(a)
+        b.copy_(a)                    # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del a, b
 
     # which kernel takes the most time? (one untimed forward with every launch bracketed)
     plan.timing_begin(None)
@@ -105,11 +116,16 @@ def main():
     bytes_per_launch = dom["alg_bytes"] / dom["launches"]
     flops_per_launch = dom["model_flops"] / dom["launches"]
     achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9
+    # HBM bytes per launch of that kernel from the committed rocprofv3 counter summary
+    # (FETCH_SIZE and WRITE_SIZE runs of this same command, scaled by a plain copy)
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % TRAFFIC_TAG)
     if os.path.exists(tpath):
         with open(tpath) as f:
-            traffic = json.load(f).get(dominant)
+            for line in f:
+                cols = line.rstrip("\n").split("\t")
+                if not line.startswith("#") and len(cols) == 5 and cols[0] == dominant:
+                    traffic = float(cols[4])
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                 "avg_launch_ms": avg_ms, "launches_timed": dom["launches"],

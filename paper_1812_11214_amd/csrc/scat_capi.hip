@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 #include <map>
 #include <new>
@@ -107,7 +108,16 @@ namespace {
 using scat::ChanMap;
 using scat::FilterTable;
 
-constexpr size_t kScratchBudget = size_t(12) << 30;  // bytes of scratch one chunk may use
+// Bytes of scratch one chunk of planes may use (a forward call walks the batch in chunks).
+// SCAT_SCRATCH_MB in the environment overrides the default of 12 GiB.
+size_t scratch_budget() {
+  static const size_t v = [] {
+    const char *e = std::getenv("SCAT_SCRATCH_MB");
+    long mb = e ? std::atol(e) : 0;
+    return mb > 0 ? static_cast<size_t>(mb) << 20 : size_t(12) << 30;
+  }();
+  return v;
+}
 
 struct Layout {
   long chunk = 0;       // planes per chunk
@@ -159,7 +169,7 @@ Layout make_layout(const scat_plan &p, long batch) {
     L.w = 0;
   }
   L.per_plane = L.xh + L.t + L.u + L.v + L.w;
-  long c = static_cast<long>(kScratchBudget / L.per_plane);
+  long c = static_cast<long>(scratch_budget() / L.per_plane);
   if (c < 1) c = 1;
   if (c > batch) c = batch;
   L.chunk = c;
