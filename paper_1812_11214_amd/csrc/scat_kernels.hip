@@ -325,12 +325,15 @@ __global__ void k_row_lowpass(const float *__restrict__ w, int m_r, int Mc, int 
 // Column pass with register-resident transforms (column length MR = 16 * T, compile
 // time).  Same contract as k_col<0> / k_col<1>; T threads share one column, TC columns
 // per workgroup (blockDim = T * TC, thread = c + TC * t so that global accesses run
-// along rows).  LDS: 16 * (T*TC + 16) complex for the exchanges, then m_r * TC complex
-// for the small lowpass transform.
-template <int MR, int MODE>
+// along rows).  LM_R = compile-time lowpass length (8 or 32: the fold is done in registers
+// and the small inverse transform by 1 or 2 lanes per column) or 0 = any length (generic
+// tail through lds_fft).
+template <int MR, int MODE, int LM_R>
 __global__ __launch_bounds__(256) void k_col_fast(const void *__restrict__ src_v, int Mc, int TC,
-                           float2 *__restrict__ uc, const float *__restrict__ phi_rows, int m_r,
-                           float *__restrict__ w_out, const float2 *__restrict__ tw, int tw_n) {
+                                                  float2 *__restrict__ uc,
+                                                  const float *__restrict__ phi_rows, int m_r,
+                                                  float *__restrict__ w_out,
+                                                  const float2 *__restrict__ tw, int tw_n) {
   constexpr int E = 16, T = MR / 16;
   extern __shared__ float2 lds[];
   const int KS = T * TC + 16;
@@ -339,28 +342,71 @@ __global__ __launch_bounds__(256) void k_col_fast(const void *__restrict__ src_v
   const int node = blockIdx.x / tiles;
   const int c0 = (blockIdx.x % tiles) * TC;
   const size_t plane = static_cast<size_t>(node) * MR * Mc;
+  const int off0 = t * Mc + c0 + c;  // offset of this thread's first element in the plane
+  const int step = T * Mc;
   float2 wt[E];
   load_twiddles<E, T>(wt, t, tw, tw_n);
   float2 v[E];
   if (MODE == 0) {
-    const float *sp = static_cast<const float *>(src_v) + plane + c0 + c;
+    const float *sp = static_cast<const float *>(src_v) + plane + off0;
 #pragma unroll
-    for (int i = 0; i < E; ++i) v[i] = make_float2(sp[static_cast<size_t>(t + T * i) * Mc], 0.f);
+    for (int i = 0; i < E; ++i) v[i] = make_float2(sp[i * step], 0.f);
   } else {
-    const float2 *sp = static_cast<const float2 *>(src_v) + plane + c0 + c;
+    const float2 *sp = static_cast<const float2 *>(src_v) + plane + off0;
 #pragma unroll
-    for (int i = 0; i < E; ++i) v[i] = sp[static_cast<size_t>(t + T * i) * Mc];
+    for (int i = 0; i < E; ++i) v[i] = sp[i * step];
     fft_core<E, T, true>(v, t, lds + c, KS, TC, wt);
 #pragma unroll
-    for (int i = 0; i < E; ++i) v[i] = make_float2(sqrtf(v[i].x * v[i].x + v[i].y * v[i].y), 0.f);
+    for (int i = 0; i < E; ++i)
+      v[i] = make_float2(__builtin_amdgcn_sqrtf(v[i].x * v[i].x + v[i].y * v[i].y), 0.f);
   }
   fft_core<E, T, false>(v, t, lds + c, KS, TC, wt);
   if (uc != nullptr) {
-    float2 *up = uc + plane + c0 + c;
+    float2 *up = uc + plane + off0;
 #pragma unroll
-    for (int i = 0; i < E; ++i) up[static_cast<size_t>(t + T * i) * Mc] = v[i];
+    for (int i = 0; i < E; ++i) up[i * step] = v[i];
   }
-  if (w_out != nullptr) {
+  if (w_out == nullptr) return;
+  float *wp = w_out + static_cast<size_t>(node) * m_r * Mc + c0;
+  if (LM_R > 0) {
+    // fold in registers: row t + T*i lands on lowpass frequency t + T*(i mod JT)
+    constexpr int JT = LM_R / T > 0 ? LM_R / T : 1;
+    float2 fm[JT];
+#pragma unroll
+    for (int j = 0; j < JT; ++j) fm[j] = make_float2(0.f, 0.f);
+    const float *ph = phi_rows + t;
+#pragma unroll
+    for (int i = 0; i < E; ++i) {
+      const float f = ph[T * i];
+      fm[i % JT].x += v[i].x * f;
+      fm[i % JT].y += v[i].y * f;
+    }
+#pragma unroll
+    for (int j = 0; j < JT; ++j) lds[(t + T * j) * TC + c] = fm[j];
+    __syncthreads();
+    if (LM_R == 32) {
+      if (static_cast<int>(threadIdx.x) < 2 * TC) {
+        const int tp = threadIdx.x & 1, cc = threadIdx.x >> 1;
+        float2 y[16], w2[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) y[i] = lds[(tp + 2 * i) * TC + cc];
+        load_twiddles<16, 2>(w2, tp, tw, tw_n);
+        fft_core<16, 2, true, true>(y, tp, lds + LM_R * TC + cc * 48, 3, 1, w2);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) wp[(tp + 2 * i) * Mc + cc] = y[i].x;
+      }
+    } else {
+      if (static_cast<int>(threadIdx.x) < TC) {
+        const int cc = threadIdx.x;
+        float2 y[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) y[i] = lds[i * TC + cc];
+        DftRegs<8, true>::run(y);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) wp[i * Mc + cc] = y[i].x;
+      }
+    }
+  } else {
     // spectrum * phi in natural row order, then fold and a small inverse transform
 #pragma unroll
     for (int i = 0; i < E; ++i) {
@@ -379,10 +425,9 @@ __global__ __launch_bounds__(256) void k_col_fast(const void *__restrict__ src_v
       low[bitrev(m, log2m) * TC + cc] = acc;
     }
     lds_fft<true, true>(low, log2m, TC, 1, TC, tw, tw_n);
-    float *wp = w_out + static_cast<size_t>(node) * m_r * Mc;
     for (int idx = threadIdx.x; idx < m_r * TC; idx += blockDim.x) {
       int m = idx / TC, cc = idx % TC;
-      wp[static_cast<size_t>(m) * Mc + c0 + cc] = low[idx].x;
+      wp[static_cast<size_t>(m) * Mc + cc] = low[idx].x;
     }
   }
 }
@@ -397,27 +442,38 @@ hipError_t launch_col_fast_t(int mode, const void *src, long nodes, int Mc, floa
   if (TC > Mc) TC = Mc;
   long blocks = nodes * (Mc / TC);
   if (blocks <= 0 || blocks > 0x7fffffffL) return hipErrorInvalidValue;
-  size_t lds = (static_cast<size_t>(16) * (T * TC + 16) + (w_out ? static_cast<size_t>(m_r) * TC : 0)) *
-               sizeof(float2);
+  // lowpass tail variant: registers when the lowpass length is 32 or 8 and a multiple of T
+  const int lm = (w_out && m_r == 32 && T <= 32 && tw_n >= 32) ? 32 : (w_out && m_r == 8 && T <= 8) ? 8 : 0;
+  size_t words = static_cast<size_t>(16) * (T * TC + 16);
+  if (lm == 0 && w_out) words += static_cast<size_t>(m_r) * TC;
+  if (lm == 32 && static_cast<size_t>(80) * TC > words) words = static_cast<size_t>(80) * TC;
+  size_t lds = words * sizeof(float2);
   dim3 g(static_cast<unsigned>(blocks)), b(T * TC);
-  static const std::string names[2] = {"k_col_fast<" + std::to_string(MR) + ", 0>",
-                                       "k_col_fast<" + std::to_string(MR) + ", 1>"};
+  const int lm_t = (lm == 8 && MR > 128) ? 0 : lm;  // the template argument actually used
+  const std::string name = "k_col_fast<" + std::to_string(MR) + ", " + (mode ? "1" : "0") + ", " +
+                           std::to_string(lm_t) + ">";
   const double pts = static_cast<double>(nodes) * MR * Mc;
   const double cols = static_cast<double>(nodes) * Mc;
-  Observe ob(names[mode ? 1 : 0].c_str(),
+  Observe ob(name.c_str(),
              pts * (mode == 0 ? 4 : 8) + (uc ? pts * 8 : 0) + (w_out ? cols * m_r * 4 + MR * 4.0 : 0),
              cols * ((mode ? 2 : 1) * fft_flops(MR) + (w_out ? fft_flops(m_r) + 2.0 * MR : 0)) +
                  (mode ? 4.0 * pts : 0),
              st);
-  if (mode == 0)
-    hipLaunchKernelGGL((k_col_fast<MR, 0>), g, b, lds, st, src, Mc, TC, uc, phi_rows, m_r, w_out, tw,
-                       tw_n);
-  else
-    hipLaunchKernelGGL((k_col_fast<MR, 1>), g, b, lds, st, src, Mc, TC, uc, phi_rows, m_r, w_out, tw,
-                       tw_n);
+#define SCAT_COL_LAUNCH(MODE_, LM_)                                                               \
+  hipLaunchKernelGGL((k_col_fast<MR, MODE_, LM_>), g, b, lds, st, src, Mc, TC, uc, phi_rows, m_r, \
+                     w_out, tw, tw_n)
+  if (mode == 0) {
+    if (lm == 32) SCAT_COL_LAUNCH(0, 32);
+    else if (lm == 8) SCAT_COL_LAUNCH(0, (MR <= 128 ? 8 : 0));
+    else SCAT_COL_LAUNCH(0, 0);
+  } else {
+    if (lm == 32) SCAT_COL_LAUNCH(1, 32);
+    else if (lm == 8) SCAT_COL_LAUNCH(1, (MR <= 128 ? 8 : 0));
+    else SCAT_COL_LAUNCH(1, 0);
+  }
+#undef SCAT_COL_LAUNCH
   return hipGetLastError();
 }
-
 
 // ------------------------------------------------------------------------------------
 // Fused row pass: forward row FFT of column-transformed sources, then for every level
@@ -483,13 +539,23 @@ struct FiltVec<4> {
   }
 };
 
+// LDS strides (in float2) chosen so that the lanes of half a wavefront fall on distinct
+// banks: row stride of the source rows, and slot stride of the product/exchange area for
+// transforms shared by TP lanes (at least 16*(TP+1) for the exchange layout).
+__host__ __device__ constexpr int fused_row_stride(int SC) { return SC + 16; }
+__host__ __device__ constexpr int fused_slot_stride(int TP) {
+  return TP == 16 ? 272 : TP == 8 ? 152 : TP == 4 ? 84 : TP == 2 ? 50 : 16;
+}
+
 // One level of the fused row pass for one wavefront.  The wave owns the LDS rows R
-// (rows of SC points, natural order) of its source.  Items = (filter, output row);
-// 64/TP of them form a batch: first every item's folded product row is accumulated by the
-// whole wave (lane l owns M/64 consecutive output columns, so filter and LDS reads are
-// contiguous across the wave) into B, then each group of TP lanes transforms one row.
-// The accumulation is unrolled over IC items so that about 32 filter loads are in flight.
-// lgGf, lgNGRP: log2 of the output rows per group at this level and of the groups per wave.
+// (rows of SC points, natural order, stride fused_row_stride) of its source.  Items =
+// (filter, output row); 64/TP of them form a batch: first every item's folded product row
+// is accumulated by the whole wave (lane l owns M/64 consecutive output columns, so filter
+// and LDS reads are contiguous across the wave) into B, then each group of TP lanes
+// transforms one row.  The accumulation runs in chunks of IC items (about 32 filter loads
+// per lane); the loads of the next chunk are issued before the transforms of the current
+// batch so that they are in flight behind the arithmetic.
+// lgG, lgNGRP: log2 of the rows per group and of the groups per wave.
 template <int SC, int FL>
 __device__ __forceinline__ void fused_level_w(const FusedLevelDev &L, int Sr, int lgG, int lgNGRP,
                                               long src_idx, int grp0, const float2 *R, float2 *B,
@@ -498,10 +564,12 @@ __device__ __forceinline__ void fused_level_w(const FusedLevelDev &L, int Sr, in
   constexpr int M = 16 * TP;
   constexpr int SLOTS = 64 / TP;
   constexpr int CPL = M >= 64 ? M / 64 : 1;  // output columns per lane
-  constexpr int SLOT_STRIDE = TP > 1 ? 16 * (TP + 1) : 16;
+  constexpr int SS = fused_slot_stride(TP);
+  constexpr int RS = fused_row_stride(SC);
   constexpr int NF = 1 << FL, TERMS = NF * NF;
   constexpr int IC0 = 32 / TERMS < 1 ? 1 : 32 / TERMS;
   constexpr int IC = IC0 > SLOTS ? SLOTS : IC0;
+  constexpr int CPB = SLOTS / IC;  // chunks per batch
   const int lgGf = lgG - FL;
   const int Gf = 1 << lgGf;
   const int Mr = Sr >> FL;
@@ -509,51 +577,58 @@ __device__ __forceinline__ void fused_level_w(const FusedLevelDev &L, int Sr, in
   const int rows_step = Sr >> lgG;
   const int slot = lane / TP, t = lane % TP;
   const int lcol = (lane * CPL) % M;  // lanes past M (only when M < 64) repeat valid columns
-  float2 wt[16];
-  load_twiddles<16, TP>(wt, t, tw, tw_n);
-  for (int it0 = 0; it0 < items; it0 += SLOTS) {
-#pragma unroll 1
-    for (int s0 = 0; s0 < SLOTS; s0 += IC) {
-      FiltVec<CPL> fv[IC][TERMS];
-      const float2 *rb[IC];
+  const int nchunks = (items + IC - 1) / IC;
+
+  FiltVec<CPL> fv[IC][TERMS];
+  const float2 *rb[IC];
+  auto issue = [&](int c) {
 #pragma unroll
-      for (int s = 0; s < IC; ++s) {
-        int item = it0 + s0 + s;
-        item = item < items ? item : items - 1;  // surplus slots recompute the last item
-        const int theta = item >> (lgGf + lgNGRP);
-        const int rem = item & ((1 << (lgGf + lgNGRP)) - 1);
-        const int g = rem >> lgGf, ap = rem & (Gf - 1);
-        const int qr = grp0 + g + rows_step * ap;
-        const float *fp = L.filt + (static_cast<size_t>(theta) * Sr + qr) * SC + lcol;
-        rb[s] = R + static_cast<size_t>((g << lgG) + ap) * SC + lcol;
+    for (int s = 0; s < IC; ++s) {
+      int item = c * IC + s;
+      item = item < items ? item : items - 1;  // surplus slots recompute the last item
+      const int theta = item >> (lgGf + lgNGRP);
+      const int rem = item & ((1 << (lgGf + lgNGRP)) - 1);
+      const int g = rem >> lgGf, ap = rem & (Gf - 1);
+      const int qr = grp0 + g + rows_step * ap;
+      const float *fp = L.filt + (static_cast<size_t>(theta) * Sr + qr) * SC + lcol;
+      rb[s] = R + static_cast<size_t>((g << lgG) + ap) * RS + lcol;
 #pragma unroll
-        for (int a = 0; a < NF; ++a)
+      for (int a = 0; a < NF; ++a)
 #pragma unroll
-          for (int b = 0; b < NF; ++b)
-            fv[s][a * NF + b].load(fp + static_cast<size_t>(a) * Mr * SC + b * M);
-      }
-#pragma unroll
-      for (int s = 0; s < IC; ++s) {
-        float2 acc[CPL];
-#pragma unroll
-        for (int e = 0; e < CPL; ++e) acc[e] = make_float2(0.f, 0.f);
-#pragma unroll
-        for (int a = 0; a < NF; ++a)
-#pragma unroll
-          for (int b = 0; b < NF; ++b)
-            fv[s][a * NF + b].fma(acc, rb[s] + static_cast<size_t>(a * Gf) * SC + b * M);
-#pragma unroll
-        for (int e = 0; e < CPL; ++e) B[(s0 + s) * SLOT_STRIDE + lcol + e] = acc[e];
-      }
+        for (int b = 0; b < NF; ++b)
+          fv[s][a * NF + b].load(fp + static_cast<size_t>(a) * Mr * SC + b * M);
     }
+  };
+  issue(0);
+  for (int c = 0; c < nchunks; ++c) {
+    const int s0 = (c % CPB) * IC;
+#pragma unroll
+    for (int s = 0; s < IC; ++s) {
+      float2 acc[CPL];
+#pragma unroll
+      for (int e = 0; e < CPL; ++e) acc[e] = make_float2(0.f, 0.f);
+#pragma unroll
+      for (int a = 0; a < NF; ++a)
+#pragma unroll
+        for (int b = 0; b < NF; ++b)
+          fv[s][a * NF + b].fma(acc, rb[s] + static_cast<size_t>(a * Gf) * RS + b * M);
+#pragma unroll
+      for (int e = 0; e < CPL; ++e) B[(s0 + s) * SS + lcol + e] = acc[e];
+    }
+    if (c + 1 < nchunks) issue(c + 1);
+    if ((c + 1) % CPB != 0 && c + 1 != nchunks) continue;
+    // ---- a batch of product rows is complete: transform and store it
+    const int it0 = (c / CPB) * SLOTS;
     wave_sync();
     const int item = it0 + slot;
     const bool active = item < items;
     float2 v[16];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) v[i] = B[slot * SLOT_STRIDE + t + TP * i];
+    for (int i = 0; i < 16; ++i) v[i] = B[slot * SS + t + TP * i];
     wave_sync();
-    fft_core<16, TP, true, true>(v, t, B + slot * SLOT_STRIDE, TP + 1, 1, wt);
+    float2 wt[16];  // (re)loaded per batch from the cached table to keep registers free
+    load_twiddles<16, TP>(wt, t, tw, tw_n);
+    fft_core<16, TP, true, true>(v, t, B + slot * SS, TP + 1, 1, wt);
     if (TP == 1) wave_sync();
     if (active) {
       const int theta = item >> (lgGf + lgNGRP);
@@ -586,8 +661,9 @@ __global__ __launch_bounds__(256, 2) void k_rows_fused(const float2 *__restrict_
   const long src_idx = 4 * static_cast<long>(blockIdx.x / per_src) + wave;
   const int grp0 = (blockIdx.x % per_src) * NGRP;
   if (src_idx >= NS) return;
-  float2 *R = lds + static_cast<size_t>(wave) * (static_cast<size_t>(rows_w) * SC + b_words);
-  float2 *B = R + static_cast<size_t>(rows_w) * SC;
+  constexpr int RS = fused_row_stride(SC);
+  float2 *R = lds + static_cast<size_t>(wave) * (static_cast<size_t>(rows_w) * RS + b_words);
+  float2 *B = R + static_cast<size_t>(rows_w) * RS;
   {
     const int t = lane % T, rl = lane / T;
     float2 wt[16];
@@ -599,9 +675,9 @@ __global__ __launch_bounds__(256, 2) void k_rows_fused(const float2 *__restrict_
       float2 v[16];
 #pragma unroll
       for (int i = 0; i < 16; ++i) v[i] = sp[T * i];
-      fft_core<16, T, false, true>(v, t, B + rl * 16 * (T + 1), T + 1, 1, wt);
+      fft_core<16, T, false, true>(v, t, B + rl * fused_slot_stride(T), T + 1, 1, wt);
 #pragma unroll
-      for (int i = 0; i < 16; ++i) R[rr * SC + t + T * i] = v[i];
+      for (int i = 0; i < 16; ++i) R[rr * RS + t + T * i] = v[i];
     }
     wave_sync();
   }
@@ -855,13 +931,13 @@ hipError_t launch_rows_fused(const float2 *src, long NS, int Sr, int Sc, const F
   if (groups % NGRP != 0) return hipErrorInvalidValue;
   // per-wave product/exchange area: phase 1 needs RPW transforms of 16*(T+1), a level
   // with TP lanes per transform needs (64/TP) slots of 16*(TP+1) (16 if TP == 1)
-  size_t b_words = static_cast<size_t>(RPW) * 16 * (T + 1);
+  size_t b_words = static_cast<size_t>(RPW) * fused_slot_stride(T);
   for (int l = 0; l < nlev; ++l) {
     int TP = (Sc >> levels[l].f) / 16;
-    size_t need = static_cast<size_t>(64 / TP) * (TP > 1 ? 16 * (TP + 1) : 16);
+    size_t need = static_cast<size_t>(64 / TP) * fused_slot_stride(TP);
     if (need > b_words) b_words = need;
   }
-  size_t lds = 4 * (static_cast<size_t>(rows_w) * Sc + b_words) * sizeof(float2);
+  size_t lds = 4 * (static_cast<size_t>(rows_w) * fused_row_stride(Sc) + b_words) * sizeof(float2);
   if (lds > 160 * 1024) return hipErrorInvalidValue;
   long blocks = ((NS + 3) / 4) * (groups / NGRP);
   if (blocks <= 0 || blocks > 0x7fffffffL) return hipErrorInvalidValue;
