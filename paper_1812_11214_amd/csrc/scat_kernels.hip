@@ -495,149 +495,182 @@ struct FusedArgsDev {
   int nlev;
 };
 
-// Filter values of CPL consecutive columns, and the multiply-accumulate of CPL complex
-// points by them.
+// Filter values of CPL consecutive columns.
 template <int CPL>
 struct FiltVec;
 template <>
 struct FiltVec<1> {
-  float f;
-  __device__ __forceinline__ void load(const float *p) { f = *p; }
-  __device__ __forceinline__ void fma(float2 (&acc)[1], const float2 *r) const {
-    const float2 u = r[0];
-    acc[0].x += u.x * f;
-    acc[0].y += u.y * f;
-  }
+  float f[1];
+  __device__ __forceinline__ void load(const float *p) { f[0] = *p; }
 };
 template <>
 struct FiltVec<2> {
-  float2 f;
-  __device__ __forceinline__ void load(const float *p) { f = *reinterpret_cast<const float2 *>(p); }
-  __device__ __forceinline__ void fma(float2 (&acc)[2], const float2 *r) const {
-    const float4 u = *reinterpret_cast<const float4 *>(r);
-    acc[0].x += u.x * f.x;
-    acc[0].y += u.y * f.x;
-    acc[1].x += u.z * f.y;
-    acc[1].y += u.w * f.y;
+  float f[2];
+  __device__ __forceinline__ void load(const float *p) {
+    const float2 v = *reinterpret_cast<const float2 *>(p);
+    f[0] = v.x;
+    f[1] = v.y;
   }
 };
 template <>
 struct FiltVec<4> {
-  float4 f;
-  __device__ __forceinline__ void load(const float *p) { f = *reinterpret_cast<const float4 *>(p); }
-  __device__ __forceinline__ void fma(float2 (&acc)[4], const float2 *r) const {
-    const float4 u = *reinterpret_cast<const float4 *>(r);
-    const float4 w = *reinterpret_cast<const float4 *>(r + 2);
-    acc[0].x += u.x * f.x;
-    acc[0].y += u.y * f.x;
-    acc[1].x += u.z * f.y;
-    acc[1].y += u.w * f.y;
-    acc[2].x += w.x * f.z;
-    acc[2].y += w.y * f.z;
-    acc[3].x += w.z * f.w;
-    acc[3].y += w.w * f.w;
+  float f[4];
+  __device__ __forceinline__ void load(const float *p) {
+    const float4 v = *reinterpret_cast<const float4 *>(p);
+    f[0] = v.x;
+    f[1] = v.y;
+    f[2] = v.z;
+    f[3] = v.w;
   }
 };
 
+// CPL consecutive complex values from LDS (16-byte reads where possible).
+template <int CPL>
+__device__ __forceinline__ void lds_read_cols(float2 (&d)[CPL], const float2 *p) {
+  if (CPL == 1) {
+    d[0] = p[0];
+  } else {
+#pragma unroll
+    for (int e = 0; e < CPL; e += 2) {
+      const float4 u = *reinterpret_cast<const float4 *>(p + e);
+      d[e] = make_float2(u.x, u.y);
+      d[(e + 1) % CPL] = make_float2(u.z, u.w);
+    }
+  }
+}
+
 // LDS strides (in float2) chosen so that the lanes of half a wavefront fall on distinct
 // banks: row stride of the source rows, and slot stride of the product/exchange area for
-// transforms shared by TP lanes (at least 16*(TP+1) for the exchange layout).
+// transforms of EL points per lane shared by TP lanes (at least EL*(TP+1) for the exchange).
 __host__ __device__ constexpr int fused_row_stride(int SC) { return SC + 16; }
-__host__ __device__ constexpr int fused_slot_stride(int TP) {
-  return TP == 16 ? 272 : TP == 8 ? 152 : TP == 4 ? 84 : TP == 2 ? 50 : 16;
+__host__ __device__ constexpr int fused_slot_stride(int EL, int TP) {
+  return TP == 1 ? EL
+         : EL == 8 ? 72  /* TP == 8 */
+         : TP == 16 ? 272 : TP == 8 ? 152 : TP == 4 ? 84 : 50;
 }
+// Transform shape used for an output row of M points: 64 points go as 8 lanes x 8 points so
+// that a wave's 8 items fill all lanes; everything else as 16 points per lane.
+__host__ __device__ constexpr int fused_el(int M) { return M == 64 ? 8 : 16; }
 
 // One level of the fused row pass for one wavefront.  The wave owns the LDS rows R
 // (rows of SC points, natural order, stride fused_row_stride) of its source.  Items =
-// (filter, output row); 64/TP of them form a batch: first every item's folded product row
-// is accumulated by the whole wave (lane l owns M/64 consecutive output columns, so filter
-// and LDS reads are contiguous across the wave) into B, then each group of TP lanes
-// transforms one row.  The accumulation runs in chunks of IC items (about 32 filter loads
-// per lane); the loads of the next chunk are issued before the transforms of the current
-// batch so that they are in flight behind the arithmetic.
+// (output row, filter), filter index fastest; 64/TP of them form a batch: first every
+// item's folded product row is accumulated by the whole wave (lane l owns M/64 consecutive
+// output columns, so filter and LDS reads are contiguous across the wave) into B, then each
+// group of TP lanes transforms one row.  The source values an output row needs are read
+// from LDS once and kept in registers for all filters of that row.  The accumulation runs
+// in chunks of IC items (about 32 filter loads per lane); the loads of the next chunk are
+// issued before the transforms of the current batch.
 // lgG, lgNGRP: log2 of the rows per group and of the groups per wave.
 template <int SC, int FL>
 __device__ __forceinline__ void fused_level_w(const FusedLevelDev &L, int Sr, int lgG, int lgNGRP,
                                               long src_idx, int grp0, const float2 *R, float2 *B,
                                               int lane, const float2 *__restrict__ tw, int tw_n) {
-  constexpr int TP = (SC / 16) >> FL;
-  constexpr int M = 16 * TP;
+  constexpr int M = SC >> FL;
+  constexpr int EL = fused_el(M);
+  constexpr int TP = M / EL;
   constexpr int SLOTS = 64 / TP;
   constexpr int CPL = M >= 64 ? M / 64 : 1;  // output columns per lane
-  constexpr int SS = fused_slot_stride(TP);
+  constexpr int SS = fused_slot_stride(EL, TP);
   constexpr int RS = fused_row_stride(SC);
   constexpr int NF = 1 << FL, TERMS = NF * NF;
   constexpr int IC0 = 32 / TERMS < 1 ? 1 : 32 / TERMS;
   constexpr int IC = IC0 > SLOTS ? SLOTS : IC0;
-  constexpr int CPB = SLOTS / IC;  // chunks per batch
+  constexpr int CPB = SLOTS / IC;                // chunks per batch
+  constexpr bool CACHE = TERMS * CPL <= 16;      // keep a row set's source values in registers
+  constexpr int NRT = CACHE ? TERMS : 1;
   const int lgGf = lgG - FL;
   const int Gf = 1 << lgGf;
   const int Mr = Sr >> FL;
-  const int items = L.F << (lgGf + lgNGRP);
+  const int F = L.F;
+  const int items = F << (lgGf + lgNGRP);
   const int rows_step = Sr >> lgG;
   const int slot = lane / TP, t = lane % TP;
   const int lcol = (lane * CPL) % M;  // lanes past M (only when M < 64) repeat valid columns
   const int nchunks = (items + IC - 1) / IC;
 
   FiltVec<CPL> fv[IC][TERMS];
-  const float2 *rb[IC];
-  auto issue = [&](int c) {
+  int rs_of[IC];            // row set (g, ap) of each item of the chunk in flight
+  int nx_theta = 0, nx_rs = 0;  // next item to issue
+  auto issue = [&]() {
 #pragma unroll
     for (int s = 0; s < IC; ++s) {
-      int item = c * IC + s;
-      item = item < items ? item : items - 1;  // surplus slots recompute the last item
-      const int theta = item >> (lgGf + lgNGRP);
-      const int rem = item & ((1 << (lgGf + lgNGRP)) - 1);
-      const int g = rem >> lgGf, ap = rem & (Gf - 1);
+      const int g = nx_rs >> lgGf, ap = nx_rs & (Gf - 1);
       const int qr = grp0 + g + rows_step * ap;
-      const float *fp = L.filt + (static_cast<size_t>(theta) * Sr + qr) * SC + lcol;
-      rb[s] = R + static_cast<size_t>((g << lgG) + ap) * RS + lcol;
+      const float *fp = L.filt + (static_cast<size_t>(nx_theta) * Sr + qr) * SC + lcol;
+      rs_of[s] = nx_rs;
 #pragma unroll
       for (int a = 0; a < NF; ++a)
 #pragma unroll
         for (int b = 0; b < NF; ++b)
           fv[s][a * NF + b].load(fp + static_cast<size_t>(a) * Mr * SC + b * M);
+      // advance; past the last item the last one is recomputed (harmless)
+      if (nx_theta + 1 < F) {
+        ++nx_theta;
+      } else if (nx_rs + 1 < (1 << (lgGf + lgNGRP))) {
+        nx_theta = 0;
+        ++nx_rs;
+      }
     }
   };
-  issue(0);
+  float2 rt[NRT][CPL];
+  int cur_rs = -1;
+  issue();
   for (int c = 0; c < nchunks; ++c) {
     const int s0 = (c % CPB) * IC;
 #pragma unroll
     for (int s = 0; s < IC; ++s) {
+      const int rs = rs_of[s];
+      const int g = rs >> lgGf, ap = rs & (Gf - 1);
+      const float2 *rb = R + static_cast<size_t>((g << lgG) + ap) * RS + lcol;
+      if (CACHE && rs != cur_rs) {
+        cur_rs = rs;
+#pragma unroll
+        for (int a = 0; a < NF; ++a)
+#pragma unroll
+          for (int b = 0; b < NF; ++b)
+            lds_read_cols<CPL>(rt[(a * NF + b) % NRT], rb + static_cast<size_t>(a * Gf) * RS + b * M);
+      }
       float2 acc[CPL];
 #pragma unroll
       for (int e = 0; e < CPL; ++e) acc[e] = make_float2(0.f, 0.f);
 #pragma unroll
       for (int a = 0; a < NF; ++a)
 #pragma unroll
-        for (int b = 0; b < NF; ++b)
-          fv[s][a * NF + b].fma(acc, rb[s] + static_cast<size_t>(a * Gf) * RS + b * M);
+        for (int b = 0; b < NF; ++b) {
+          if (!CACHE) lds_read_cols<CPL>(rt[0], rb + static_cast<size_t>(a * Gf) * RS + b * M);
+          const int k = CACHE ? a * NF + b : 0;
+#pragma unroll
+          for (int e = 0; e < CPL; ++e) {
+            acc[e].x += rt[k][e].x * fv[s][a * NF + b].f[e];
+            acc[e].y += rt[k][e].y * fv[s][a * NF + b].f[e];
+          }
+        }
 #pragma unroll
       for (int e = 0; e < CPL; ++e) B[(s0 + s) * SS + lcol + e] = acc[e];
     }
-    if (c + 1 < nchunks) issue(c + 1);
+    if (c + 1 < nchunks) issue();
     if ((c + 1) % CPB != 0 && c + 1 != nchunks) continue;
     // ---- a batch of product rows is complete: transform and store it
     const int it0 = (c / CPB) * SLOTS;
     wave_sync();
     const int item = it0 + slot;
     const bool active = item < items;
-    float2 v[16];
+    float2 v[EL];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) v[i] = B[slot * SS + t + TP * i];
+    for (int i = 0; i < EL; ++i) v[i] = B[slot * SS + t + TP * i];
     wave_sync();
-    float2 wt[16];  // (re)loaded per batch from the cached table to keep registers free
-    load_twiddles<16, TP>(wt, t, tw, tw_n);
-    fft_core<16, TP, true, true>(v, t, B + slot * SS, TP + 1, 1, wt);
+    float2 wt[EL];  // (re)loaded per batch from the cached table to keep registers free
+    load_twiddles<EL, TP>(wt, t, tw, tw_n);
+    fft_core<EL, TP, true, true>(v, t, B + slot * SS, TP + 1, 1, wt);
     if (TP == 1) wave_sync();
     if (active) {
-      const int theta = item >> (lgGf + lgNGRP);
-      const int rem = item & ((1 << (lgGf + lgNGRP)) - 1);
-      const int g = rem >> lgGf, ap = rem & (Gf - 1);
+      const int rs = item / F, theta = item - rs * F;
+      const int g = rs >> lgGf, ap = rs & (Gf - 1);
       const int qr = grp0 + g + rows_step * ap;
-      float2 *dp = L.dst + ((static_cast<size_t>(src_idx) * L.F + theta) * Mr + qr) * M + t;
+      float2 *dp = L.dst + ((static_cast<size_t>(src_idx) * F + theta) * Mr + qr) * M + t;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) dp[TP * i] = v[i];
+      for (int i = 0; i < EL; ++i) dp[TP * i] = v[i];
     }
   }
 }
@@ -675,7 +708,7 @@ __global__ __launch_bounds__(256, 2) void k_rows_fused(const float2 *__restrict_
       float2 v[16];
 #pragma unroll
       for (int i = 0; i < 16; ++i) v[i] = sp[T * i];
-      fft_core<16, T, false, true>(v, t, B + rl * fused_slot_stride(T), T + 1, 1, wt);
+      fft_core<16, T, false, true>(v, t, B + rl * fused_slot_stride(16, T), T + 1, 1, wt);
 #pragma unroll
       for (int i = 0; i < 16; ++i) R[rr * RS + t + T * i] = v[i];
     }
@@ -931,10 +964,11 @@ hipError_t launch_rows_fused(const float2 *src, long NS, int Sr, int Sc, const F
   if (groups % NGRP != 0) return hipErrorInvalidValue;
   // per-wave product/exchange area: phase 1 needs RPW transforms of 16*(T+1), a level
   // with TP lanes per transform needs (64/TP) slots of 16*(TP+1) (16 if TP == 1)
-  size_t b_words = static_cast<size_t>(RPW) * fused_slot_stride(T);
+  size_t b_words = static_cast<size_t>(RPW) * fused_slot_stride(16, T);
   for (int l = 0; l < nlev; ++l) {
-    int TP = (Sc >> levels[l].f) / 16;
-    size_t need = static_cast<size_t>(64 / TP) * fused_slot_stride(TP);
+    const int M = Sc >> levels[l].f;
+    const int EL = fused_el(M), TP = M / EL;
+    size_t need = static_cast<size_t>(64 / TP) * fused_slot_stride(EL, TP);
     if (need > b_words) b_words = need;
   }
   size_t lds = 4 * (static_cast<size_t>(rows_w) * fused_row_stride(Sc) + b_words) * sizeof(float2);
