@@ -733,14 +733,18 @@ __global__ __launch_bounds__(256, 2) void k_rows_fused(const float2 *__restrict_
 // MC = 16 * T).  Two consecutive rows of a node travel as the real and imaginary part of
 // one complex signal: the lowpass is a real linear map, so the real part of the result
 // belongs to the first row and the imaginary part to the second.  Same contract as
-// k_row_lowpass; m_r must be even.  256 / T row pairs per workgroup.
-template <int MC>
+// k_row_lowpass; m_r must be even.  256 / T row pairs per workgroup; the T lanes of a pair
+// sit in one wavefront, so only wave-level synchronisation is used.
+// LM_C = compile-time output length (32 or 8: fold in registers, small inverse transform by
+// 2 lanes or 1 lane of the pair) or 0 = any length (generic tail through lds_fft).
+template <int MC, int LM_C>
 __global__ __launch_bounds__(256) void k_row_lowpass_fast(const float *__restrict__ w, long pairs,
                                                           int m_r, int m_c,
                                                           const float *__restrict__ phi_cols,
                                                           float *__restrict__ out, ChanMap cm, int K,
                                                           const float2 *__restrict__ tw, int tw_n) {
-  constexpr int E = 16, T = MC / 16, RP = 256 / T, XS = 16 * (T + 1);
+  constexpr int E = 16, T = MC / 16, RP = 256 / T;
+  constexpr int XS = 16 * (T + 1) + (LM_C > 0 ? 48 : 0);
   extern __shared__ float2 lds[];
   const int pr = threadIdx.x / T, t = threadIdx.x % T;
   const long gp0 = static_cast<long>(blockIdx.x) * RP;
@@ -758,6 +762,57 @@ __global__ __launch_bounds__(256) void k_row_lowpass_fast(const float *__restric
     for (int i = 0; i < E; ++i) v[i] = make_float2(0.f, 0.f);
   }
   float2 *xch = lds + pr * XS;
+  if (LM_C > 0) {
+    fft_core<E, T, false, true>(v, t, xch, T + 1, 1, wt);
+    constexpr int JT = LM_C / T > 0 ? LM_C / T : 1;
+    float2 fm[JT];
+#pragma unroll
+    for (int j = 0; j < JT; ++j) fm[j] = make_float2(0.f, 0.f);
+    const float *ph = phi_cols + t;
+#pragma unroll
+    for (int i = 0; i < E; ++i) {
+      const float f = ph[T * i];
+      fm[i % JT].x += v[i].x * f;
+      fm[i % JT].y += v[i].y * f;
+    }
+#pragma unroll
+    for (int j = 0; j < JT; ++j) xch[t + T * j] = fm[j];
+    wave_sync();
+    if (!valid) return;
+    const long row = 2 * gp;
+    const long node = row / m_r;
+    const int r = static_cast<int>(row % m_r);
+    const long pl = node / cm.G;
+    const int g = static_cast<int>(node % cm.G);
+    float *op = out + ((static_cast<size_t>(pl) * K + chan_of(cm, g)) * m_r + r) * LM_C;
+    if (LM_C == 32) {
+      if (t < 2) {
+        float2 y[16], w2[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) y[i] = xch[t + 2 * i];
+        load_twiddles<16, 2>(w2, t, tw, tw_n);
+        fft_core<16, 2, true, true>(y, t, xch + 16 * (T + 1), 3, 1, w2);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          op[t + 2 * i] = y[i].x;
+          op[LM_C + t + 2 * i] = y[i].y;
+        }
+      }
+    } else {
+      if (t == 0) {
+        float2 y[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) y[i] = xch[i];
+        DftRegs<8, true>::run(y);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          op[i] = y[i].x;
+          op[LM_C + i] = y[i].y;
+        }
+      }
+    }
+    return;
+  }
   fft_core<E, T, false>(v, t, xch, T + 1, 1, wt);
 #pragma unroll
   for (int i = 0; i < E; ++i) {
@@ -796,17 +851,28 @@ template <int MC>
 hipError_t launch_row_lowpass_fast_t(const float *w, long nodes, int m_r, int m_c,
                                      const float *phi_cols, float *out, ChanMap cm, int K,
                                      const float2 *tw, int tw_n, hipStream_t st) {
-  constexpr int T = MC / 16, RP = 256 / T, XS = 16 * (T + 1);
+  constexpr int T = MC / 16, RP = 256 / T;
   const long pairs = nodes * m_r / 2;
   long blocks = (pairs + RP - 1) / RP;
   if (blocks <= 0 || blocks > 0x7fffffffL) return hipErrorInvalidValue;
-  size_t lds = (static_cast<size_t>(RP) * XS + static_cast<size_t>(RP) * m_c) * sizeof(float2);
+  // tail variant: registers when the output length is 32 (needs T >= 2 lanes) or 8
+  const int lm = (m_c == 32 && T >= 2 && T <= 32 && tw_n >= 32) ? 32 : (m_c == 8 && T <= 8) ? 8 : 0;
+  const int XS = 16 * (T + 1) + (lm > 0 ? 48 : 0);
+  size_t lds = (static_cast<size_t>(RP) * XS + (lm > 0 ? 0 : static_cast<size_t>(RP) * m_c)) * sizeof(float2);
   const double rws = static_cast<double>(nodes) * m_r;
-  static const std::string name = "k_row_lowpass_fast<" + std::to_string(MC) + ">";
+  const std::string name = "k_row_lowpass_fast<" + std::to_string(MC) + ", " + std::to_string(lm) + ">";
   Observe ob(name.c_str(), rws * (MC + m_c) * 4,
              rws * 0.5 * (fft_flops(MC) + fft_flops(m_c) + 2.0 * MC), st);
-  hipLaunchKernelGGL(k_row_lowpass_fast<MC>, dim3(static_cast<unsigned>(blocks)), dim3(256), lds, st,
-                     w, pairs, m_r, m_c, phi_cols, out, cm, K, tw, tw_n);
+  dim3 g(static_cast<unsigned>(blocks)), b(256);
+  if (lm == 32)
+    hipLaunchKernelGGL((k_row_lowpass_fast<MC, (MC >= 32 ? 32 : 0)>), g, b, lds, st, w, pairs, m_r, m_c,
+                       phi_cols, out, cm, K, tw, tw_n);
+  else if (lm == 8)
+    hipLaunchKernelGGL((k_row_lowpass_fast<MC, (MC <= 128 ? 8 : 0)>), g, b, lds, st, w, pairs, m_r, m_c,
+                       phi_cols, out, cm, K, tw, tw_n);
+  else
+    hipLaunchKernelGGL((k_row_lowpass_fast<MC, 0>), g, b, lds, st, w, pairs, m_r, m_c, phi_cols, out,
+                       cm, K, tw, tw_n);
   return hipGetLastError();
 }
 
