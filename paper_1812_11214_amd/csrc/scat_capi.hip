@@ -394,8 +394,9 @@ scat_status forward_2d_fused(scat_plan *p, const float *in, float *out, long p0,
   float *o = out + static_cast<size_t>(p0) * K * m_r * m_c;
   const ChanMap none{1, 1, 0, 0};
 
+  // column spectra of real signals are stored as their non-redundant half (rows 0..M/2)
   SCAT_TRY(scat::launch_col(0, x, pc, Nr, Nc, XC, 0, tab + p->phi_rows_off[0], m_r, W, nullptr,
-                            none, K, tw, tw_n, st));
+                            none, K, tw, tw_n, st, true));
   SCAT_TRY(scat::launch_row_lowpass(W, pc, m_r, Nc, m_c, tab + p->phi_cols_off[0], o,
                                     ChanMap{1, 1, 0, 0}, K, tw, tw_n, st));
   // every first-order octave in one row pass over x's column spectra
@@ -408,14 +409,15 @@ scat_status forward_2d_fused(scat_plan *p, const float *in, float *out, long p0,
       lv[j1] = scat::FusedLevel{j1, L, tab + p->psi1_off[j1], t1[j1]};
       off += static_cast<size_t>(pc) * L * (n >> (2 * j1));
     }
-    SCAT_TRY(scat::launch_rows_fused(XC, pc, Nr, Nc, lv, J, tw, tw_n, st));
+    SCAT_TRY(scat::launch_rows_fused(XC, true, pc, Nr, Nc, lv, J, tw, tw_n, st));
   }
   int s2_base = 1 + J * L;
   for (int j1 = 0; j1 < J; ++j1) {
     const int M1r = Nr >> j1, M1c = Nc >> j1;
     const bool kids = h.max_order == 2 && j1 < J - 1;
     SCAT_TRY(scat::launch_col(1, t1[j1], pc * L, M1r, M1c, kids ? U : nullptr, 0,
-                              tab + p->phi_rows_off[j1], m_r, W, nullptr, none, K, tw, tw_n, st));
+                              tab + p->phi_rows_off[j1], m_r, W, nullptr, none, K, tw, tw_n, st,
+                              true));
     SCAT_TRY(scat::launch_row_lowpass(W, pc * L, m_r, M1c, m_c, tab + p->phi_cols_off[j1], o,
                                       ChanMap{L, L, 0, 1 + j1 * L}, K, tw, tw_n, st));
     if (!kids) continue;
@@ -429,7 +431,7 @@ scat_status forward_2d_fused(scat_plan *p, const float *in, float *out, long p0,
         lv[j2 - j1 - 1] = scat::FusedLevel{j2 - j1, L, tab + p->psi2_off[{j1, j2}], t2[j2]};
         off += static_cast<size_t>(pc) * L * L * (n >> (2 * j2));
       }
-      SCAT_TRY(scat::launch_rows_fused(U, pc * L, M1r, M1c, lv, octs, tw, tw_n, st));
+      SCAT_TRY(scat::launch_rows_fused(U, true, pc * L, M1r, M1c, lv, octs, tw, tw_n, st));
     }
     for (int j2 = j1 + 1; j2 < J; ++j2) {
       const int M2r = Nr >> j2, M2c = Nc >> j2;

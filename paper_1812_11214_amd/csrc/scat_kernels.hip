@@ -182,7 +182,8 @@ __global__ void k_mulfold_invrow(const float2 *__restrict__ src, const float *__
 //   IFFT_{m_r}( fold_{Mr -> m_r}( spectrum[k_r] * phi_rows[k_r] ) ), real, [node][m_r][Mc].
 template <int MODE>
 __global__ void k_col(const void *__restrict__ src_v, int Mr, int Mc, int TC,
-                      float2 *__restrict__ uc, int post_tw_m, const float *__restrict__ phi_rows,
+                      float2 *__restrict__ uc, int uc_half, int post_tw_m,
+                      const float *__restrict__ phi_rows,
                       int m_r, float *__restrict__ w_out, float *__restrict__ out, ChanMap cm,
                       int K, const float2 *__restrict__ tw, int tw_n) {
   extern __shared__ float2 lds[];
@@ -232,14 +233,18 @@ __global__ void k_col(const void *__restrict__ src_v, int Mr, int Mc, int TC,
   }
   lds_fft<false, true>(lds, log2mr, TC, 1, TC, tw, tw_n);
   if (uc != nullptr) {
-    for (int t = threadIdx.x; t < total; t += blockDim.x) {
+    // uc_half: the input was real, so rows Mr/2+1.. are conjugates of rows Mr/2-1..1 and
+    // only rows 0..Mr/2 are stored, compactly
+    const int rows_kept = uc_half ? Mr / 2 + 1 : Mr;
+    float2 *ucp = uc + static_cast<size_t>(node) * rows_kept * Mc;
+    for (int t = threadIdx.x; t < rows_kept * TC; t += blockDim.x) {
       int i = t / TC, c = t % TC;
       float2 v = lds[t];
       if (post_tw_m > 0) {
         int e = static_cast<int>((static_cast<long long>(i) * (c0 + c)) % post_tw_m);
         v = cmul(v, twiddle<false>(tw, tw_n, e, post_tw_m));
       }
-      uc[plane + static_cast<size_t>(i) * Mc + c0 + c] = v;
+      ucp[static_cast<size_t>(i) * Mc + c0 + c] = v;
     }
   }
   if (w_out != nullptr) {
@@ -330,7 +335,7 @@ __global__ void k_row_lowpass(const float *__restrict__ w, int m_r, int Mc, int 
 // tail through lds_fft).
 template <int MR, int MODE, int LM_R>
 __global__ __launch_bounds__(256) void k_col_fast(const void *__restrict__ src_v, int Mc, int TC,
-                                                  float2 *__restrict__ uc,
+                                                  float2 *__restrict__ uc, int uc_half,
                                                   const float *__restrict__ phi_rows, int m_r,
                                                   float *__restrict__ w_out,
                                                   const float2 *__restrict__ tw, int tw_n) {
@@ -362,9 +367,17 @@ __global__ __launch_bounds__(256) void k_col_fast(const void *__restrict__ src_v
   }
   fft_core<E, T, false>(v, t, lds + c, KS, TC, wt);
   if (uc != nullptr) {
-    float2 *up = uc + plane + off0;
+    if (uc_half) {
+      // real input: rows above MR/2 are conjugates of stored ones; keep rows 0..MR/2 compactly
+      float2 *up = uc + static_cast<size_t>(node) * (MR / 2 + 1) * Mc + off0;
 #pragma unroll
-    for (int i = 0; i < E; ++i) up[i * step] = v[i];
+      for (int i = 0; i < E; ++i)
+        if (t + T * i <= MR / 2) up[i * step] = v[i];
+    } else {
+      float2 *up = uc + plane + off0;
+#pragma unroll
+      for (int i = 0; i < E; ++i) up[i * step] = v[i];
+    }
   }
   if (w_out == nullptr) return;
   float *wp = w_out + static_cast<size_t>(node) * m_r * Mc + c0;
@@ -433,7 +446,7 @@ __global__ __launch_bounds__(256) void k_col_fast(const void *__restrict__ src_v
 }
 
 template <int MR>
-hipError_t launch_col_fast_t(int mode, const void *src, long nodes, int Mc, float2 *uc,
+hipError_t launch_col_fast_t(int mode, const void *src, long nodes, int Mc, float2 *uc, bool uc_half,
                              const float *phi_rows, int m_r, float *w_out, const float2 *tw,
                              int tw_n, hipStream_t st) {
   constexpr int T = MR / 16;
@@ -455,13 +468,14 @@ hipError_t launch_col_fast_t(int mode, const void *src, long nodes, int Mc, floa
   const double pts = static_cast<double>(nodes) * MR * Mc;
   const double cols = static_cast<double>(nodes) * Mc;
   Observe ob(name.c_str(),
-             pts * (mode == 0 ? 4 : 8) + (uc ? pts * 8 : 0) + (w_out ? cols * m_r * 4 + MR * 4.0 : 0),
+             pts * (mode == 0 ? 4 : 8) + (uc ? (uc_half ? cols * (MR / 2 + 1) : pts) * 8 : 0) +
+                 (w_out ? cols * m_r * 4 + MR * 4.0 : 0),
              cols * ((mode ? 2 : 1) * fft_flops(MR) + (w_out ? fft_flops(m_r) + 2.0 * MR : 0)) +
                  (mode ? 4.0 * pts : 0),
              st);
 #define SCAT_COL_LAUNCH(MODE_, LM_)                                                               \
-  hipLaunchKernelGGL((k_col_fast<MR, MODE_, LM_>), g, b, lds, st, src, Mc, TC, uc, phi_rows, m_r, \
-                     w_out, tw, tw_n)
+  hipLaunchKernelGGL((k_col_fast<MR, MODE_, LM_>), g, b, lds, st, src, Mc, TC, uc,                \
+                     static_cast<int>(uc_half), phi_rows, m_r, w_out, tw, tw_n)
   if (mode == 0) {
     if (lm == 32) SCAT_COL_LAUNCH(0, 32);
     else if (lm == 8) SCAT_COL_LAUNCH(0, (MR <= 128 ? 8 : 0));
@@ -680,8 +694,9 @@ __device__ __forceinline__ void fused_level_w(const FusedLevelDev &L, int Sr, in
 // waves only share the filter rows they read through the L1 cache).
 // LDS per wave: rows_w * SC (rows) + b_words (product rows / exchange), in float2.
 template <int SC>
-__global__ __launch_bounds__(256, 2) void k_rows_fused(const float2 *__restrict__ src, long NS, int Sr,
-                                                    int G, int b_words, FusedArgsDev args,
+__global__ __launch_bounds__(256, 2) void k_rows_fused(const float2 *__restrict__ src, int src_half,
+                                                    long NS, int Sr, int G, int b_words,
+                                                    FusedArgsDev args,
                                                     const float2 *__restrict__ tw, int tw_n) {
   constexpr int T = SC / 16;
   constexpr int RPW = 64 / T;  // rows one wave transforms at a time
@@ -704,10 +719,20 @@ __global__ __launch_bounds__(256, 2) void k_rows_fused(const float2 *__restrict_
     for (int pass = 0; pass < rows_w / RPW; ++pass) {
       const int rr = pass * RPW + rl;
       const int g = rr / G, ag = rr % G;
-      const float2 *sp = src + (static_cast<size_t>(src_idx) * Sr + grp0 + g + groups * ag) * SC + t;
+      // src_half: the source holds rows 0..Sr/2 only (column spectra of a real signal);
+      // row r > Sr/2 is the conjugate of row Sr - r
+      const int r = grp0 + g + groups * ag;
+      const bool mirror = src_half && r > Sr / 2;
+      const int r_st = mirror ? Sr - r : r;
+      const int rows_st = src_half ? Sr / 2 + 1 : Sr;
+      const float2 *sp = src + (static_cast<size_t>(src_idx) * rows_st + r_st) * SC + t;
       float2 v[16];
 #pragma unroll
       for (int i = 0; i < 16; ++i) v[i] = sp[T * i];
+      if (mirror) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) v[i].y = -v[i].y;
+      }
       fft_core<16, T, false, true>(v, t, B + rl * fused_slot_stride(16, T), T + 1, 1, wt);
 #pragma unroll
       for (int i = 0; i < 16; ++i) R[rr * RS + t + T * i] = v[i];
@@ -911,15 +936,16 @@ hipError_t launch_mulfold_invrow(const float2 *src, const float *filt, float2 *d
 
 hipError_t launch_col(int mode, const void *src, long nodes, int Mr, int Mc, float2 *uc,
                       int post_tw_m, const float *phi_rows, int m_r, float *w_out, float *out,
-                      ChanMap cm, int K, const float2 *tw, int tw_n, hipStream_t st) {
+                      ChanMap cm, int K, const float2 *tw, int tw_n, hipStream_t st, bool uc_half) {
+  if (uc_half && (mode == 2 || post_tw_m != 0 || Mr < 2)) return hipErrorInvalidValue;
   // register-resident variant: modes 0/1, no four-step twiddle, column length 16*T with
   // T | 16, at least 16 columns, lowpass length dividing the column length
   if (mode != 2 && post_tw_m == 0 && Mc >= 16 && (w_out == nullptr || (m_r >= 1 && m_r <= Mr))) {
     switch (Mr) {
-      case 32: return launch_col_fast_t<32>(mode, src, nodes, Mc, uc, phi_rows, m_r, w_out, tw, tw_n, st);
-      case 64: return launch_col_fast_t<64>(mode, src, nodes, Mc, uc, phi_rows, m_r, w_out, tw, tw_n, st);
-      case 128: return launch_col_fast_t<128>(mode, src, nodes, Mc, uc, phi_rows, m_r, w_out, tw, tw_n, st);
-      case 256: return launch_col_fast_t<256>(mode, src, nodes, Mc, uc, phi_rows, m_r, w_out, tw, tw_n, st);
+      case 32: return launch_col_fast_t<32>(mode, src, nodes, Mc, uc, uc_half, phi_rows, m_r, w_out, tw, tw_n, st);
+      case 64: return launch_col_fast_t<64>(mode, src, nodes, Mc, uc, uc_half, phi_rows, m_r, w_out, tw, tw_n, st);
+      case 128: return launch_col_fast_t<128>(mode, src, nodes, Mc, uc, uc_half, phi_rows, m_r, w_out, tw, tw_n, st);
+      case 256: return launch_col_fast_t<256>(mode, src, nodes, Mc, uc, uc_half, phi_rows, m_r, w_out, tw, tw_n, st);
       default: break;
     }
   }
@@ -935,22 +961,23 @@ hipError_t launch_col(int mode, const void *src, long nodes, int Mr, int Mc, flo
   const double pts = static_cast<double>(nodes) * Mr * Mc;
   const double cols = static_cast<double>(nodes) * Mc;
   Observe ob(names[mode < 0 || mode > 2 ? 0 : mode],
-             pts * (mode == 0 ? 4 : 8) + (uc ? pts * 8 : 0) + (w_out ? cols * m_r * 4 : 0) +
+             pts * (mode == 0 ? 4 : 8) + (uc ? (uc_half ? cols * (Mr / 2 + 1) : pts) * 8 : 0) +
+                 (w_out ? cols * m_r * 4 : 0) +
                  (mode == 2 ? pts * 4 : 0),
              cols * ((mode == 1 ? 2 : 1) * fft_flops(Mr) + (w_out ? fft_flops(m_r) + 2.0 * Mr : 0)) +
                  (mode == 1 ? 4.0 * pts : 0),
              st);
   switch (mode) {
     case 0:
-      hipLaunchKernelGGL(k_col<0>, g, b, lds, st, src, Mr, Mc, TC, uc, post_tw_m, phi_rows, m_r,
+      hipLaunchKernelGGL(k_col<0>, g, b, lds, st, src, Mr, Mc, TC, uc, static_cast<int>(uc_half), post_tw_m, phi_rows, m_r,
                          w_out, out, cm, K, tw, tw_n);
       break;
     case 1:
-      hipLaunchKernelGGL(k_col<1>, g, b, lds, st, src, Mr, Mc, TC, uc, post_tw_m, phi_rows, m_r,
+      hipLaunchKernelGGL(k_col<1>, g, b, lds, st, src, Mr, Mc, TC, uc, static_cast<int>(uc_half), post_tw_m, phi_rows, m_r,
                          w_out, out, cm, K, tw, tw_n);
       break;
     case 2:
-      hipLaunchKernelGGL(k_col<2>, g, b, lds, st, src, Mr, Mc, TC, uc, post_tw_m, phi_rows, m_r,
+      hipLaunchKernelGGL(k_col<2>, g, b, lds, st, src, Mr, Mc, TC, uc, static_cast<int>(uc_half), post_tw_m, phi_rows, m_r,
                          w_out, out, cm, K, tw, tw_n);
       break;
     default:
@@ -1007,8 +1034,9 @@ bool rows_fused_supported(int Sr, int Sc, int fmax) {
   return true;
 }
 
-hipError_t launch_rows_fused(const float2 *src, long NS, int Sr, int Sc, const FusedLevel *levels,
-                             int nlev, const float2 *tw, int tw_n, hipStream_t st) {
+hipError_t launch_rows_fused(const float2 *src, bool src_half, long NS, int Sr, int Sc,
+                             const FusedLevel *levels, int nlev, const float2 *tw, int tw_n,
+                             hipStream_t st) {
   if (nlev < 1 || nlev > 4) return hipErrorInvalidValue;
   int fmax = 0;
   FusedArgsDev args;
@@ -1045,7 +1073,8 @@ hipError_t launch_rows_fused(const float2 *src, long NS, int Sr, int Sc, const F
   static const std::string names[4] = {"k_rows_fused<32>", "k_rows_fused<64>", "k_rows_fused<128>",
                                        "k_rows_fused<256>"};
   const double spts = static_cast<double>(NS) * Sr * Sc;
-  double bytes = spts * 8, flops = static_cast<double>(NS) * Sr * fft_flops(Sc);
+  double bytes = static_cast<double>(NS) * (src_half ? Sr / 2 + 1 : Sr) * Sc * 8;
+  double flops = static_cast<double>(NS) * Sr * fft_flops(Sc);
   for (int l = 0; l < nlev; ++l) {
     const int f = levels[l].f, F = levels[l].F;
     const double opts = static_cast<double>(NS) * F * (Sr >> f) * (Sc >> f);
@@ -1066,10 +1095,10 @@ hipError_t launch_rows_fused(const float2 *src, long NS, int Sr, int Sc, const F
   }
   Observe ob(names[which].c_str(), bytes, flops, st);
   switch (Sc) {
-    case 32: hipLaunchKernelGGL(k_rows_fused<32>, g, b, lds, st, src, NS, Sr, G, static_cast<int>(b_words), args, tw, tw_n); break;
-    case 64: hipLaunchKernelGGL(k_rows_fused<64>, g, b, lds, st, src, NS, Sr, G, static_cast<int>(b_words), args, tw, tw_n); break;
-    case 128: hipLaunchKernelGGL(k_rows_fused<128>, g, b, lds, st, src, NS, Sr, G, static_cast<int>(b_words), args, tw, tw_n); break;
-    case 256: hipLaunchKernelGGL(k_rows_fused<256>, g, b, lds, st, src, NS, Sr, G, static_cast<int>(b_words), args, tw, tw_n); break;
+    case 32: hipLaunchKernelGGL(k_rows_fused<32>, g, b, lds, st, src, static_cast<int>(src_half), NS, Sr, G, static_cast<int>(b_words), args, tw, tw_n); break;
+    case 64: hipLaunchKernelGGL(k_rows_fused<64>, g, b, lds, st, src, static_cast<int>(src_half), NS, Sr, G, static_cast<int>(b_words), args, tw, tw_n); break;
+    case 128: hipLaunchKernelGGL(k_rows_fused<128>, g, b, lds, st, src, static_cast<int>(src_half), NS, Sr, G, static_cast<int>(b_words), args, tw, tw_n); break;
+    case 256: hipLaunchKernelGGL(k_rows_fused<256>, g, b, lds, st, src, static_cast<int>(src_half), NS, Sr, G, static_cast<int>(b_words), args, tw, tw_n); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();

@@ -28,7 +28,8 @@ hipError_t launch_mulfold_invrow(const float2 *src, const float *filt, float2 *d
 
 hipError_t launch_col(int mode, const void *src, long nodes, int Mr, int Mc, float2 *uc,
                       int post_tw_m, const float *phi_rows, int m_r, float *w_out, float *out,
-                      ChanMap cm, int K, const float2 *tw, int tw_n, hipStream_t st);
+                      ChanMap cm, int K, const float2 *tw, int tw_n, hipStream_t st,
+                      bool uc_half = false);
 
 hipError_t launch_row_fwd(float2 *data, long rows, int Mc, const float2 *tw, int tw_n,
                           hipStream_t st);
@@ -48,9 +49,12 @@ struct FusedLevel {
 // True if launch_rows_fused can handle sources of Sr x Sc with largest fold 2^fmax.
 bool rows_fused_supported(int Sr, int Sc, int fmax);
 
-// Forward row FFT of column-transformed sources [NS][Sr][Sc], then every level's filter
+// Forward row FFT of column-transformed sources [NS][Sr][Sc] (or half, see below), then every level's filter
 // multiply + fold + inverse row FFT (see k_rows_fused).
-hipError_t launch_rows_fused(const float2 *src, long NS, int Sr, int Sc, const FusedLevel *levels,
-                             int nlev, const float2 *tw, int tw_n, hipStream_t st);
+// src_half: the sources hold rows 0..Sr/2 only ([NS][Sr/2+1][Sc], column spectra of real
+// signals as written by launch_col with uc_half); the other rows are their conjugates.
+hipError_t launch_rows_fused(const float2 *src, bool src_half, long NS, int Sr, int Sc,
+                             const FusedLevel *levels, int nlev, const float2 *tw, int tw_n,
+                             hipStream_t st);
 
 }  // namespace scat
