@@ -611,13 +611,13 @@ __device__ __forceinline__ void fused_level_w(const FusedLevelDev &L, int Sr, in
     for (int s = 0; s < IC; ++s) {
       const int g = nx_rs >> lgGf, ap = nx_rs & (Gf - 1);
       const int qr = grp0 + g + rows_step * ap;
-      const float *fp = L.filt + (static_cast<size_t>(nx_theta) * Sr + qr) * SC + lcol;
+      const float *fp = L.filt + (static_cast<size_t>(nx_theta) * Sr + qr) * SC;  // wave-uniform
       rs_of[s] = nx_rs;
 #pragma unroll
       for (int a = 0; a < NF; ++a)
 #pragma unroll
         for (int b = 0; b < NF; ++b)
-          fv[s][a * NF + b].load(fp + static_cast<size_t>(a) * Mr * SC + b * M);
+          fv[s][a * NF + b].load(fp + static_cast<size_t>(a) * Mr * SC + b * M + lcol);
       // advance; past the last item the last one is recomputed (harmless)
       if (nx_theta + 1 < F) {
         ++nx_theta;
@@ -692,8 +692,10 @@ __device__ __forceinline__ void fused_level_w(const FusedLevelDev &L, int Sr, in
 // Workgroup = 4 wavefronts; wave w handles source 4*(block / per_src) + w and NGRP row
 // groups starting at grp0, entirely on its own (no workgroup barrier anywhere; the four
 // waves only share the filter rows they read through the L1 cache).
-// LDS per wave: rows_w * SC (rows) + b_words (product rows / exchange), in float2.
-template <int SC>
+// LDS per wave: rows_w * fused_row_stride(SC) (rows) + b_words (product rows / exchange),
+// in float2.  MASK: bit f set = a level with fold 2^f may occur (only those variants are
+// compiled in, which keeps the kernel's register allocation at that of its heaviest level).
+template <int SC, int MASK>
 __global__ __launch_bounds__(256, 2) void k_rows_fused(const float2 *__restrict__ src, int src_half,
                                                     long NS, int Sr, int G, int b_words,
                                                     FusedArgsDev args,
@@ -701,7 +703,9 @@ __global__ __launch_bounds__(256, 2) void k_rows_fused(const float2 *__restrict_
   constexpr int T = SC / 16;
   constexpr int RPW = 64 / T;  // rows one wave transforms at a time
   extern __shared__ float2 lds[];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  // the wave number is the same in all lanes: keep it (and all that derives from it) scalar
+  const int wave = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));
   const int rows_w = RPW > G ? RPW : G;
   const int NGRP = rows_w / G;
   const int groups = Sr / G;
@@ -743,10 +747,10 @@ __global__ __launch_bounds__(256, 2) void k_rows_fused(const float2 *__restrict_
   for (int l = 0; l < args.nlev; ++l) {
     const FusedLevelDev &L = args.lv[l];
     switch (L.f) {
-      case 0: fused_level_w<SC, 0>(L, Sr, lgG, lgNGRP, src_idx, grp0, R, B, lane, tw, tw_n); break;
-      case 1: fused_level_w<SC, 1>(L, Sr, lgG, lgNGRP, src_idx, grp0, R, B, lane, tw, tw_n); break;
-      case 2: if (SC >= 64) fused_level_w<(SC >= 64 ? SC : 64), 2>(L, Sr, lgG, lgNGRP, src_idx, grp0, R, B, lane, tw, tw_n); break;
-      case 3: if (SC >= 128) fused_level_w<(SC >= 128 ? SC : 128), 3>(L, Sr, lgG, lgNGRP, src_idx, grp0, R, B, lane, tw, tw_n); break;
+      case 0: if (MASK & 1) fused_level_w<SC, 0>(L, Sr, lgG, lgNGRP, src_idx, grp0, R, B, lane, tw, tw_n); break;
+      case 1: if (MASK & 2) fused_level_w<SC, 1>(L, Sr, lgG, lgNGRP, src_idx, grp0, R, B, lane, tw, tw_n); break;
+      case 2: if ((MASK & 4) && SC >= 64) fused_level_w<(SC >= 64 ? SC : 64), 2>(L, Sr, lgG, lgNGRP, src_idx, grp0, R, B, lane, tw, tw_n); break;
+      case 3: if ((MASK & 8) && SC >= 128) fused_level_w<(SC >= 128 ? SC : 128), 3>(L, Sr, lgG, lgNGRP, src_idx, grp0, R, B, lane, tw, tw_n); break;
       default: break;
     }
   }
@@ -1081,26 +1085,47 @@ hipError_t launch_rows_fused(const float2 *src, bool src_half, long NS, int Sr, 
     bytes += opts * 8 + static_cast<double>(F) * Sr * Sc * 4;
     flops += static_cast<double>(NS) * F * (Sr >> f) * fft_flops(Sc >> f) + 4.0 * spts * F;
   }
-  // workgroups may use more than the default 64 KB of LDS
-  static bool attr_set[4] = {false, false, false, false};
+  int mask = 0;
+  for (int l = 0; l < nlev; ++l) mask |= 1 << levels[l].f;
   const int which = Sc == 32 ? 0 : Sc == 64 ? 1 : Sc == 128 ? 2 : 3;
-  if (!attr_set[which]) {
-    const void *fn = which == 0   ? reinterpret_cast<const void *>(k_rows_fused<32>)
-                     : which == 1 ? reinterpret_cast<const void *>(k_rows_fused<64>)
-                     : which == 2 ? reinterpret_cast<const void *>(k_rows_fused<128>)
-                                  : reinterpret_cast<const void *>(k_rows_fused<256>);
-    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) return e;
-    attr_set[which] = true;
-  }
+  const int hf = static_cast<int>(src_half), bw = static_cast<int>(b_words);
   Observe ob(names[which].c_str(), bytes, flops, st);
+  // one instantiation per (row length, set of fold levels); workgroups may use more than
+  // the default 64 KB of LDS, which has to be allowed once per kernel
+#define SCAT_RF_LAUNCH(SC_, MASK_)                                                                \
+  {                                                                                               \
+    static bool attr_done = false;                                                                \
+    if (!attr_done) {                                                                             \
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_rows_fused<SC_, MASK_>), \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024); \
+      if (e != hipSuccess) return e;                                                              \
+      attr_done = true;                                                                           \
+    }                                                                                             \
+    hipLaunchKernelGGL((k_rows_fused<SC_, MASK_>), g, b, lds, st, src, hf, NS, Sr, G, bw, args,   \
+                       tw, tw_n);                                                                 \
+  }
+#define SCAT_RF_MASKS(SC_)                                    \
+  switch (mask) {                                             \
+    case 1: SCAT_RF_LAUNCH(SC_, 1) break;                     \
+    case 2: SCAT_RF_LAUNCH(SC_, 2) break;                     \
+    case 3: SCAT_RF_LAUNCH(SC_, 3) break;                     \
+    case 4: SCAT_RF_LAUNCH(SC_, 4) break;                     \
+    case 6: SCAT_RF_LAUNCH(SC_, 6) break;                     \
+    case 7: SCAT_RF_LAUNCH(SC_, 7) break;                     \
+    case 8: SCAT_RF_LAUNCH(SC_, 8) break;                     \
+    case 12: SCAT_RF_LAUNCH(SC_, 12) break;                   \
+    case 14: SCAT_RF_LAUNCH(SC_, 14) break;                   \
+    default: SCAT_RF_LAUNCH(SC_, 15) break;                   \
+  }
   switch (Sc) {
-    case 32: hipLaunchKernelGGL(k_rows_fused<32>, g, b, lds, st, src, static_cast<int>(src_half), NS, Sr, G, static_cast<int>(b_words), args, tw, tw_n); break;
-    case 64: hipLaunchKernelGGL(k_rows_fused<64>, g, b, lds, st, src, static_cast<int>(src_half), NS, Sr, G, static_cast<int>(b_words), args, tw, tw_n); break;
-    case 128: hipLaunchKernelGGL(k_rows_fused<128>, g, b, lds, st, src, static_cast<int>(src_half), NS, Sr, G, static_cast<int>(b_words), args, tw, tw_n); break;
-    case 256: hipLaunchKernelGGL(k_rows_fused<256>, g, b, lds, st, src, static_cast<int>(src_half), NS, Sr, G, static_cast<int>(b_words), args, tw, tw_n); break;
+    case 32: SCAT_RF_MASKS(32) break;
+    case 64: SCAT_RF_MASKS(64) break;
+    case 128: SCAT_RF_MASKS(128) break;
+    case 256: SCAT_RF_MASKS(256) break;
     default: return hipErrorInvalidValue;
   }
+#undef SCAT_RF_MASKS
+#undef SCAT_RF_LAUNCH
   return hipGetLastError();
 }
 
