@@ -47,6 +47,17 @@ __device__ __forceinline__ float2 cmul(float2 a, float2 b) {
 __device__ __forceinline__ float2 cadd(float2 a, float2 b) { return make_float2(a.x + b.x, a.y + b.y); }
 __device__ __forceinline__ float2 csub(float2 a, float2 b) { return make_float2(a.x - b.x, a.y - b.y); }
 
+// Streaming store: the value is written once and read much later by another kernel.
+__device__ __forceinline__ void nt_store(float2 *p, float2 v) {
+  __builtin_nontemporal_store(v.x, &p->x);
+  __builtin_nontemporal_store(v.y, &p->y);
+}
+
+// Streaming load: the value is read exactly once.
+__device__ __forceinline__ float2 nt_load(const float2 *p) {
+  return make_float2(__builtin_nontemporal_load(&p->x), __builtin_nontemporal_load(&p->y));
+}
+
 __device__ __forceinline__ int bitrev(int i, int log2n) {
   return log2n == 0 ? 0 : static_cast<int>(__brev(static_cast<unsigned>(i)) >> (32 - log2n));
 }
@@ -359,7 +370,7 @@ __global__ __launch_bounds__(256) void k_col_fast(const void *__restrict__ src_v
   } else {
     const float2 *sp = static_cast<const float2 *>(src_v) + plane + off0;
 #pragma unroll
-    for (int i = 0; i < E; ++i) v[i] = sp[i * step];
+    for (int i = 0; i < E; ++i) v[i] = nt_load(sp + i * step);
     fft_core<E, T, true>(v, t, lds + c, KS, TC, wt);
 #pragma unroll
     for (int i = 0; i < E; ++i)
@@ -372,7 +383,7 @@ __global__ __launch_bounds__(256) void k_col_fast(const void *__restrict__ src_v
       float2 *up = uc + static_cast<size_t>(node) * (MR / 2 + 1) * Mc + off0;
 #pragma unroll
       for (int i = 0; i < E; ++i)
-        if (t + T * i <= MR / 2) up[i * step] = v[i];
+        if (t + T * i <= MR / 2) nt_store(up + i * step, v[i]);
     } else {
       float2 *up = uc + plane + off0;
 #pragma unroll
@@ -684,7 +695,7 @@ __device__ __forceinline__ void fused_level_w(const FusedLevelDev &L, int Sr, in
       const int qr = grp0 + g + rows_step * ap;
       float2 *dp = L.dst + ((static_cast<size_t>(src_idx) * F + theta) * Mr + qr) * M + t;
 #pragma unroll
-      for (int i = 0; i < EL; ++i) dp[TP * i] = v[i];
+      for (int i = 0; i < EL; ++i) nt_store(dp + TP * i, v[i]);
     }
   }
 }
