@@ -100,6 +100,119 @@ def test_config4_1d_sample():
     _check_1d(x, c["J"], c["LQ"])
 
 
+def test_config2_full_batch_sampled():
+    """The benchmark's launch configuration (all 384 planes in one call); planes sampled
+    across the batch are compared with the oracle one by one."""
+    c = workloads.config(2)
+    P = workloads.num_planes(2)
+    x = workloads.planes(2)
+    plan = scat.Scattering(c["shape"], c["J"], c["LQ"])
+    try:
+        got = gpu_forward(plan, x)
+        rows = plan.coeff_index()
+    finally:
+        plan.close()
+    assert got.shape == (P, 217, 32, 32) and np.isfinite(got).all()
+    bank = oracle.bank_2d(256, 256, c["J"], c["LQ"])
+    sample = [0, 1, 95, 190, 191, 257, 383]
+    want = oracle.scattering2d(x[sample], c["J"], c["LQ"], bank=bank)
+    errs = per_order_errors(got[sample], want, order_of_channels(rows), x[sample])
+    print("config2 full batch, planes", sample, errs, flush=True)
+    assert max(errs.values()) <= TOL, errs
+    # every plane's S0 must equal the lowpassed mean structure: cheap whole-batch property
+    # (zero-mean input => S0 averages to ~0; S1, S2 non-negative up to rounding)
+    order = order_of_channels(rows)
+    assert np.abs(got[:, order == 0].mean(axis=(1, 2, 3))).max() < 1e-3
+    assert got[:, order > 0].min() > -1e-4
+
+
+@pytest.mark.parametrize("shape,J,L,batch", [((64, 64), 2, 3, 7), ((64, 128), 3, 5, 3),
+                                             ((256, 64), 3, 1, 2), ((32, 32), 1, 8, 5),
+                                             ((256, 256), 4, 2, 1), ((128, 64), 4, 3, 2)])
+def test_2d_ragged(shape, J, L, batch):
+    """Odd numbers of angles and planes (partially filled workgroups and batches), one
+    octave only, four octaves on the fast path, rectangular grids."""
+    rng = np.random.default_rng(sum(shape) * 31 + J * 7 + L)
+    x = rng.standard_normal((batch,) + shape).astype(np.float32)
+    _check_2d(x, J, L)
+
+
+def test_chunked_equals_single_call():
+    """A small scratch budget forces the batch to be walked in chunks; results must be
+    bit-identical to the single-chunk call."""
+    x = workloads.planes(1, 40)
+    plan = scat.Scattering((32, 32), 2, 8)
+    try:
+        a = gpu_forward(plan, x)
+    finally:
+        plan.close()
+    import subprocess, sys, os, tempfile
+    code = (
+        "import sys, numpy as np, torch\n"
+        "sys.path.insert(0, %r)\n"
+        "import paper_1812_11214_amd as scat\n"
+        "from paper_1812_11214_amd import workloads\n"
+        "x = workloads.planes(1, 40)\n"
+        "p = scat.Scattering((32, 32), 2, 8)\n"
+        "assert p.workspace_bytes(40) <= (2 << 20)\n"
+        "y = p.forward(torch.from_numpy(x).cuda()); torch.cuda.synchronize()\n"
+        "np.save(sys.argv[1], y.cpu().numpy()); p.close()\n"
+    ) % os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    with tempfile.TemporaryDirectory() as d:
+        out = os.path.join(d, "y.npy")
+        env = dict(os.environ, SCAT_SCRATCH_MB="2")
+        subprocess.run([sys.executable, "-c", code, out], check=True, env=env, timeout=240)
+        b = np.load(out)
+    assert np.array_equal(a, b)
+
+
+def test_stream_and_plan_independence():
+    """Two plans on two streams in flight at once give the same results as alone."""
+    import torch
+    xa = workloads.planes(0, 4)
+    xb = np.random.default_rng(9).standard_normal((6, 64, 64)).astype(np.float32)
+    pa, pb = scat.Scattering((32, 32), 2, 8), scat.Scattering((64, 64), 3, 4)
+    try:
+        ra, rb = gpu_forward(pa, xa), gpu_forward(pb, xb)
+        sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+        ta, tb = torch.from_numpy(xa).cuda(), torch.from_numpy(xb).cuda()
+        torch.cuda.synchronize()
+        for _ in range(3):
+            with torch.cuda.stream(sa):
+                ya = pa.forward(ta)
+            with torch.cuda.stream(sb):
+                yb = pb.forward(tb)
+        torch.cuda.synchronize()
+        assert np.array_equal(ya.cpu().numpy(), ra) and np.array_equal(yb.cpu().numpy(), rb)
+    finally:
+        pa.close()
+        pb.close()
+
+
+def test_timing_api():
+    import torch
+    x = torch.from_numpy(workloads.planes(0, 4)).cuda()
+    plan = scat.Scattering((32, 32), 2, 8)
+    try:
+        plan.forward(x)
+        plan.timing_begin(None)
+        y1 = plan.forward(x)
+        table = plan.timing_end()
+        assert len(table) >= 3
+        for name, row in table.items():
+            assert name.startswith("k_") and row["launches"] >= 1 and row["ms"] > 0
+            assert row["alg_bytes"] > 0 and row["model_flops"] > 0
+        one = max(table, key=lambda k: table[k]["ms"])
+        plan.timing_begin(one)
+        y2 = plan.forward(x)
+        t2 = plan.timing_end()
+        assert list(t2) == [one] and t2[one]["launches"] == table[one]["launches"]
+        torch.cuda.synchronize()
+        assert torch.equal(y1, y2)
+    finally:
+        plan.close()
+
+
 def test_batch_and_repeatability():
     """Results do not depend on batch size or call order; leading dims are planes."""
     import torch
