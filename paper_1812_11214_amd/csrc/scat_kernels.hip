@@ -1085,8 +1085,6 @@ hipError_t launch_rows_fused(const float2 *src, bool src_half, long NS, int Sr, 
   long blocks = ((NS + 3) / 4) * (groups / NGRP);
   if (blocks <= 0 || blocks > 0x7fffffffL) return hipErrorInvalidValue;
   dim3 g(static_cast<unsigned>(blocks)), b(256);
-  static const std::string names[4] = {"k_rows_fused<32>", "k_rows_fused<64>", "k_rows_fused<128>",
-                                       "k_rows_fused<256>"};
   const double spts = static_cast<double>(NS) * Sr * Sc;
   double bytes = static_cast<double>(NS) * (src_half ? Sr / 2 + 1 : Sr) * Sc * 8;
   double flops = static_cast<double>(NS) * Sr * fft_flops(Sc);
@@ -1098,9 +1096,12 @@ hipError_t launch_rows_fused(const float2 *src, bool src_half, long NS, int Sr, 
   }
   int mask = 0;
   for (int l = 0; l < nlev; ++l) mask |= 1 << levels[l].f;
-  const int which = Sc == 32 ? 0 : Sc == 64 ? 1 : Sc == 128 ? 2 : 3;
   const int hf = static_cast<int>(src_half), bw = static_cast<int>(b_words);
-  Observe ob(names[which].c_str(), bytes, flops, st);
+  const bool known_mask = mask == 1 || mask == 2 || mask == 3 || mask == 4 || mask == 6 ||
+                          mask == 7 || mask == 8 || mask == 12 || mask == 14;
+  const std::string name = "k_rows_fused<" + std::to_string(Sc) + ", " +
+                           std::to_string(known_mask ? mask : 15) + ">";
+  Observe ob(name.c_str(), bytes, flops, st);
   // one instantiation per (row length, set of fold levels); workgroups may use more than
   // the default 64 KB of LDS, which has to be allowed once per kernel
 #define SCAT_RF_LAUNCH(SC_, MASK_)                                                                \
