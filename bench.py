@@ -116,16 +116,25 @@ def main():
     bytes_per_launch = dom["alg_bytes"] / dom["launches"]
     flops_per_launch = dom["model_flops"] / dom["launches"]
     achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9
-    # HBM bytes per launch of that kernel from the committed rocprofv3 counter summary
+    # HBM bytes per launch of every kernel from the committed rocprofv3 counter summary
     # (FETCH_SIZE and WRITE_SIZE runs of this same command, scaled by a plain copy)
-    traffic = None
+    per_kernel = {}
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % TRAFFIC_TAG)
     if os.path.exists(tpath):
         with open(tpath) as f:
             for line in f:
                 cols = line.rstrip("\n").split("\t")
-                if not line.startswith("#") and len(cols) == 5 and cols[0] == dominant:
-                    traffic = float(cols[4])
+                if not line.startswith("#") and len(cols) == 5:
+                    per_kernel[cols[0]] = float(cols[4])
+    traffic = per_kernel.get(dominant)
+    # whole step: measured HBM bytes of all its launches over the measured step time
+    pipeline = None
+    if per_kernel and all(k in per_kernel for k in table):
+        step_bytes = sum(per_kernel[k] * table[k]["launches"] for k in table)
+        rate = step_bytes / (ms_per_step * 1e-3) / 1e9
+        pipeline = {"hbm_bytes_per_step": step_bytes, "achieved": rate, "unit": "GB/s",
+                    "frac": rate / HBM_PEAK_GBS,
+                    "alg_bytes_per_step": sum(v["alg_bytes"] for v in table.values())}
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                 "avg_launch_ms": avg_ms, "launches_timed": dom["launches"],
@@ -145,6 +154,7 @@ def main():
         "planes_per_s": P / (ms_per_step * 1e-3),
         "wall_ms_per_step": wall / args.steps * 1e3,
         "roofline": roofline,
+        "pipeline_hbm": pipeline,
         "kernel_table_ms": {k: round(v["ms"], 4) for k, v in table.items()},
     }
     plan.close()

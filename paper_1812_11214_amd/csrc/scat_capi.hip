@@ -393,12 +393,23 @@ scat_status forward_2d_fused(scat_plan *p, const float *in, float *out, long p0,
   const float *x = in + static_cast<size_t>(p0) * n;
   float *o = out + static_cast<size_t>(p0) * K * m_r * m_c;
   const ChanMap none{1, 1, 0, 0};
+  // Column pass (+ modulus) of `nodes` planes of Mr x Mc at resolution `res`, then the
+  // lowpass to the output channels `cm`: one kernel when the whole-node variant applies,
+  // else the column pass followed by the row half of the lowpass.  Column spectra of the
+  // real signals go to `uc` (may be null) as their non-redundant half (rows 0..Mr/2).
+  auto col_and_lowpass = [&](int mode, const void *src, long nodes, int Mr, int Mc, int res,
+                             float2 *uc, ChanMap cm) -> hipError_t {
+    const float *pr = tab + p->phi_rows_off[res], *pcs = tab + p->phi_cols_off[res];
+    if (scat::col_node_supported(Mr, Mc, m_r, m_c, tw_n))
+      return scat::launch_col_node(mode, src, nodes, Mr, m_r, uc, true, pr, pcs, o, cm, K, tw, tw_n,
+                                   st);
+    hipError_t e = scat::launch_col(mode, src, nodes, Mr, Mc, uc, 0, pr, m_r, W, nullptr, none, K,
+                                    tw, tw_n, st, true);
+    if (e != hipSuccess) return e;
+    return scat::launch_row_lowpass(W, nodes, m_r, Mc, m_c, pcs, o, cm, K, tw, tw_n, st);
+  };
 
-  // column spectra of real signals are stored as their non-redundant half (rows 0..M/2)
-  SCAT_TRY(scat::launch_col(0, x, pc, Nr, Nc, XC, 0, tab + p->phi_rows_off[0], m_r, W, nullptr,
-                            none, K, tw, tw_n, st, true));
-  SCAT_TRY(scat::launch_row_lowpass(W, pc, m_r, Nc, m_c, tab + p->phi_cols_off[0], o,
-                                    ChanMap{1, 1, 0, 0}, K, tw, tw_n, st));
+  SCAT_TRY(col_and_lowpass(0, x, pc, Nr, Nc, 0, XC, ChanMap{1, 1, 0, 0}));
   // every first-order octave in one row pass over x's column spectra
   std::vector<float2 *> t1(J);
   {
@@ -415,11 +426,8 @@ scat_status forward_2d_fused(scat_plan *p, const float *in, float *out, long p0,
   for (int j1 = 0; j1 < J; ++j1) {
     const int M1r = Nr >> j1, M1c = Nc >> j1;
     const bool kids = h.max_order == 2 && j1 < J - 1;
-    SCAT_TRY(scat::launch_col(1, t1[j1], pc * L, M1r, M1c, kids ? U : nullptr, 0,
-                              tab + p->phi_rows_off[j1], m_r, W, nullptr, none, K, tw, tw_n, st,
-                              true));
-    SCAT_TRY(scat::launch_row_lowpass(W, pc * L, m_r, M1c, m_c, tab + p->phi_cols_off[j1], o,
-                                      ChanMap{L, L, 0, 1 + j1 * L}, K, tw, tw_n, st));
+    SCAT_TRY(col_and_lowpass(1, t1[j1], pc * L, M1r, M1c, j1, kids ? U : nullptr,
+                             ChanMap{L, L, 0, 1 + j1 * L}));
     if (!kids) continue;
     const int octs = J - 1 - j1;
     std::vector<float2 *> t2(J);
@@ -435,11 +443,8 @@ scat_status forward_2d_fused(scat_plan *p, const float *in, float *out, long p0,
     }
     for (int j2 = j1 + 1; j2 < J; ++j2) {
       const int M2r = Nr >> j2, M2c = Nc >> j2;
-      SCAT_TRY(scat::launch_col(1, t2[j2], pc * L * L, M2r, M2c, nullptr, 0,
-                                tab + p->phi_rows_off[j2], m_r, W, nullptr, none, K, tw, tw_n, st));
-      SCAT_TRY(scat::launch_row_lowpass(W, pc * L * L, m_r, M2c, m_c, tab + p->phi_cols_off[j2], o,
-                                        ChanMap{L * L, L, octs * L, s2_base + (j2 - j1 - 1) * L}, K,
-                                        tw, tw_n, st));
+      SCAT_TRY(col_and_lowpass(1, t2[j2], pc * L * L, M2r, M2c, j2, nullptr,
+                               ChanMap{L * L, L, octs * L, s2_base + (j2 - j1 - 1) * L}));
     }
     s2_base += L * L * octs;
   }

@@ -501,6 +501,210 @@ hipError_t launch_col_fast_t(int mode, const void *src, long nodes, int Mc, floa
 }
 
 // ------------------------------------------------------------------------------------
+// Column pass of a whole square node with the row half of the lowpass fused in: one
+// workgroup walks the node's column tiles (each tile as in k_col_fast), keeps the
+// column-lowpassed rows W (LM rows of MR reals) in LDS, and finishes with the row half
+// (k_row_lowpass_fast's arithmetic) so that S goes straight to `out` and W never to memory.
+// LM = lowpass length on both axes: 32 (needs MR >= 64) or 8 (MR <= 128); instantiated for
+// MR >= 128 only.
+template <int MR, int MODE, int LM>
+__global__ __launch_bounds__(256) void k_col_node(const void *__restrict__ src_v,
+                                                  float2 *__restrict__ uc, int uc_half,
+                                                  const float *__restrict__ phi_rows,
+                                                  const float *__restrict__ phi_cols,
+                                                  float *__restrict__ out, ChanMap cm, int K,
+                                                  const float2 *__restrict__ tw, int tw_n) {
+  constexpr int E = 16, T = MR / 16;
+  constexpr int TC = (256 / T) < MR ? (256 / T) : MR;
+  constexpr int KS = T * TC + 16;
+  constexpr int XW = (16 * KS > 80 * TC) ? 16 * KS : 80 * TC;  // float2 words of scratch
+  constexpr int WS = MR + 4;                                   // floats per W row
+  constexpr int Mc = MR;
+  constexpr int JT = LM / T > 0 ? LM / T : 1;
+  extern __shared__ float2 lds[];
+  float *Wl = reinterpret_cast<float *>(lds + XW);
+  const int c = threadIdx.x % TC, t = threadIdx.x / TC;
+  const int node = blockIdx.x;
+  const size_t plane = static_cast<size_t>(node) * MR * Mc;
+  const int step = T * Mc;
+  float2 wt[E];
+  load_twiddles<E, T>(wt, t, tw, tw_n);
+  float phr[E];
+#pragma unroll
+  for (int i = 0; i < E; ++i) phr[i] = phi_rows[t + T * i];
+#pragma unroll 1
+  for (int c0 = 0; c0 < Mc; c0 += TC) {
+    const int off0 = t * Mc + c0 + c;
+    float2 v[E];
+    if (MODE == 0) {
+      const float *sp = static_cast<const float *>(src_v) + plane + off0;
+#pragma unroll
+      for (int i = 0; i < E; ++i) v[i] = make_float2(sp[i * step], 0.f);
+    } else {
+      const float2 *sp = static_cast<const float2 *>(src_v) + plane + off0;
+#pragma unroll
+      for (int i = 0; i < E; ++i) v[i] = nt_load(sp + i * step);
+      fft_core<E, T, true>(v, t, lds + c, KS, TC, wt);
+#pragma unroll
+      for (int i = 0; i < E; ++i)
+        v[i] = make_float2(__builtin_amdgcn_sqrtf(v[i].x * v[i].x + v[i].y * v[i].y), 0.f);
+    }
+    fft_core<E, T, false>(v, t, lds + c, KS, TC, wt);
+    if (uc != nullptr) {
+      if (uc_half) {
+        float2 *up = uc + static_cast<size_t>(node) * (MR / 2 + 1) * Mc + off0;
+#pragma unroll
+        for (int i = 0; i < E; ++i)
+          if (t + T * i <= MR / 2) nt_store(up + i * step, v[i]);
+      } else {
+        float2 *up = uc + plane + off0;
+#pragma unroll
+        for (int i = 0; i < E; ++i) up[i * step] = v[i];
+      }
+    }
+    // column half of the lowpass: fold in registers, small inverse transform, W tile to LDS
+    float2 fm[JT];
+#pragma unroll
+    for (int j = 0; j < JT; ++j) fm[j] = make_float2(0.f, 0.f);
+#pragma unroll
+    for (int i = 0; i < E; ++i) {
+      fm[i % JT].x += v[i].x * phr[i];
+      fm[i % JT].y += v[i].y * phr[i];
+    }
+#pragma unroll
+    for (int j = 0; j < JT; ++j) lds[(t + T * j) * TC + c] = fm[j];
+    __syncthreads();
+    if (LM == 32) {
+      if (static_cast<int>(threadIdx.x) < 2 * TC) {
+        const int tp = threadIdx.x & 1, cc = threadIdx.x >> 1;
+        float2 y[16], w2[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) y[i] = lds[(tp + 2 * i) * TC + cc];
+        load_twiddles<16, 2>(w2, tp, tw, tw_n);
+        fft_core<16, 2, true, true>(y, tp, lds + LM * TC + cc * 48, 3, 1, w2);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) Wl[(tp + 2 * i) * WS + c0 + cc] = y[i].x;
+      }
+    } else {
+      if (static_cast<int>(threadIdx.x) < TC) {
+        const int cc = threadIdx.x;
+        float2 y[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) y[i] = lds[i * TC + cc];
+        DftRegs<8, true>::run(y);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) Wl[i * WS + c0 + cc] = y[i].x;
+      }
+    }
+    __syncthreads();
+  }
+  // ---- row half of the lowpass on W (LM rows, two rows per complex transform)
+  constexpr int NP = LM / 2;  // row pairs
+  if (static_cast<int>(threadIdx.x) >= NP * T) return;
+  {
+    const int pr = threadIdx.x / T, tr = threadIdx.x % T;
+    float2 wr[E];
+    load_twiddles<E, T>(wr, tr, tw, tw_n);
+    float2 v[E];
+    const float *w0 = Wl + (2 * pr) * WS + tr;
+#pragma unroll
+    for (int i = 0; i < E; ++i) v[i] = make_float2(w0[T * i], w0[WS + T * i]);
+    float2 *xr = lds + pr * (16 * (T + 1));
+    fft_core<E, T, false, true>(v, tr, xr, T + 1, 1, wr);
+    float2 fm[JT];
+#pragma unroll
+    for (int j = 0; j < JT; ++j) fm[j] = make_float2(0.f, 0.f);
+    const float *ph = phi_cols + tr;
+#pragma unroll
+    for (int i = 0; i < E; ++i) {
+      const float f = ph[T * i];
+      fm[i % JT].x += v[i].x * f;
+      fm[i % JT].y += v[i].y * f;
+    }
+#pragma unroll
+    for (int j = 0; j < JT; ++j) xr[tr + T * j] = fm[j];
+    wave_sync();
+    const int pl = node / cm.G, g = node % cm.G;
+    float *op = out + ((static_cast<size_t>(pl) * K + chan_of(cm, g)) * LM + 2 * pr) * LM;
+    if (LM == 32) {
+      if (tr < 2) {
+        float2 y[16], w2[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) y[i] = xr[tr + 2 * i];
+        load_twiddles<16, 2>(w2, tr, tw, tw_n);
+        fft_core<16, 2, true, true>(y, tr, xr + 32, 3, 1, w2);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          op[tr + 2 * i] = y[i].x;
+          op[LM + tr + 2 * i] = y[i].y;
+        }
+      }
+    } else {
+      if (tr == 0) {
+        float2 y[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) y[i] = xr[i];
+        DftRegs<8, true>::run(y);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          op[i] = y[i].x;
+          op[LM + i] = y[i].y;
+        }
+      }
+    }
+  }
+}
+
+// True if launch_col_node handles nodes of MR x MR with lowpass length lm on both axes.
+bool col_node_supported_impl(int Mr, int Mc, int m_r, int m_c, int tw_n) {
+  if (Mr != Mc || m_r != m_c) return false;
+  // (measured: the whole-node kernel wins from 128 x 128 up; smaller nodes leave too few
+  // lanes busy in its final stage and keep the two-kernel path)
+  if (m_r == 32) return (Mr == 128 || Mr == 256) && tw_n >= 32;
+  if (m_r == 8) return Mr == 128;
+  return false;
+}
+
+template <int MR, int LM>
+hipError_t launch_col_node_t(int mode, const void *src, long nodes, float2 *uc, bool uc_half,
+                             const float *phi_rows, const float *phi_cols, float *out, ChanMap cm,
+                             int K, const float2 *tw, int tw_n, hipStream_t st) {
+  constexpr int T = MR / 16;
+  constexpr int TC = (256 / T) < MR ? (256 / T) : MR;
+  constexpr int KS = T * TC + 16;
+  constexpr int XW = (16 * KS > 80 * TC) ? 16 * KS : 80 * TC;
+  constexpr int WS = MR + 4;
+  if (nodes <= 0 || nodes > 0x7fffffffL) return hipErrorInvalidValue;
+  size_t lds = static_cast<size_t>(XW) * sizeof(float2) + static_cast<size_t>(LM) * WS * sizeof(float);
+  const std::string name = "k_col_node<" + std::to_string(MR) + ", " + (mode ? "1" : "0") + ", " +
+                           std::to_string(LM) + ">";
+  const double pts = static_cast<double>(nodes) * MR * MR;
+  const double cols = static_cast<double>(nodes) * MR;
+  Observe ob(name.c_str(),
+             pts * (mode == 0 ? 4 : 8) + (uc ? (uc_half ? cols * (MR / 2 + 1) : pts) * 8 : 0) +
+                 static_cast<double>(nodes) * LM * LM * 4,
+             cols * ((mode ? 2 : 1) * fft_flops(MR) + fft_flops(LM) + 2.0 * MR) + (mode ? 4.0 * pts : 0) +
+                 static_cast<double>(nodes) * LM * 0.5 * (fft_flops(MR) + fft_flops(LM) + 2.0 * MR),
+             st);
+  static bool attr_done[2] = {false, false};
+  if (lds > 65536 && !attr_done[mode ? 1 : 0]) {
+    const void *fn = mode ? reinterpret_cast<const void *>(k_col_node<MR, 1, LM>)
+                          : reinterpret_cast<const void *>(k_col_node<MR, 0, LM>);
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e != hipSuccess) return e;
+    attr_done[mode ? 1 : 0] = true;
+  }
+  dim3 g(static_cast<unsigned>(nodes)), b(T * TC);
+  if (mode == 0)
+    hipLaunchKernelGGL((k_col_node<MR, 0, LM>), g, b, lds, st, src, uc, static_cast<int>(uc_half),
+                       phi_rows, phi_cols, out, cm, K, tw, tw_n);
+  else
+    hipLaunchKernelGGL((k_col_node<MR, 1, LM>), g, b, lds, st, src, uc, static_cast<int>(uc_half),
+                       phi_rows, phi_cols, out, cm, K, tw, tw_n);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------
 // Fused row pass: forward row FFT of column-transformed sources, then for every level
 // (one octave of wavelets applied at fold 2^f) filter multiply + fold + inverse row FFT.
 // The full 2-D spectrum of the source therefore never goes to memory.
@@ -1040,6 +1244,29 @@ hipError_t launch_row_lowpass(const float *w, long nodes, int m_r, int Mc, int m
   return hipGetLastError();
 }
 
+
+bool col_node_supported(int Mr, int Mc, int m_r, int m_c, int tw_n) {
+  return col_node_supported_impl(Mr, Mc, m_r, m_c, tw_n);
+}
+
+hipError_t launch_col_node(int mode, const void *src, long nodes, int Mr, int m, float2 *uc,
+                           bool uc_half, const float *phi_rows, const float *phi_cols, float *out,
+                           ChanMap cm, int K, const float2 *tw, int tw_n, hipStream_t st) {
+  if (!col_node_supported_impl(Mr, Mr, m, m, tw_n) || (mode != 0 && mode != 1)) return hipErrorInvalidValue;
+#define SCAT_CN(MR_, LM_) \
+  return launch_col_node_t<MR_, LM_>(mode, src, nodes, uc, uc_half, phi_rows, phi_cols, out, cm, K, tw, tw_n, st)
+  if (m == 32) {
+    switch (Mr) {
+      case 128: SCAT_CN(128, 32);
+      case 256: SCAT_CN(256, 32);
+      default: break;
+    }
+  } else {
+    if (Mr == 128) SCAT_CN(128, 8);
+  }
+#undef SCAT_CN
+  return hipErrorInvalidValue;
+}
 
 bool rows_fused_supported(int Sr, int Sc, int fmax) {
   if (Sc != 32 && Sc != 64 && Sc != 128 && Sc != 256) return false;

@@ -38,6 +38,14 @@ hipError_t launch_row_lowpass(const float *w, long nodes, int m_r, int Mc, int m
                               const float *phi_cols, float *out, ChanMap cm, int K,
                               const float2 *tw, int tw_n, hipStream_t st);
 
+// Column pass of whole square nodes (Mr x Mr) with both halves of the lowpass (length m on
+// both axes) fused: like launch_col mode 0/1 followed by launch_row_lowpass, but S goes
+// straight to `out` and the intermediate W never to memory.
+bool col_node_supported(int Mr, int Mc, int m_r, int m_c, int tw_n);
+hipError_t launch_col_node(int mode, const void *src, long nodes, int Mr, int m, float2 *uc,
+                           bool uc_half, const float *phi_rows, const float *phi_cols, float *out,
+                           ChanMap cm, int K, const float2 *tw, int tw_n, hipStream_t st);
+
 // One level of the fused row pass: wavelets `filt` ([F][Sr][Sc] real, pre-scaled) applied
 // with fold 2^f on both axes, outputs to dst [NS*F][Sr>>f][Sc>>f].
 struct FusedLevel {
