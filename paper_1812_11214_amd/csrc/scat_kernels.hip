@@ -794,7 +794,7 @@ __host__ __device__ constexpr int fused_el(int M) { return M == 64 ? 8 : 16; }
 template <int SC, int FL>
 __device__ __forceinline__ void fused_level_w(const FusedLevelDev &L, int Sr, int lgG, int lgNGRP,
                                               long src_idx, int grp0, const float2 *R, float2 *B,
-                                              int lane, const float2 *__restrict__ tw, int tw_n) {
+                                              int lane, const float2 *twl) {
   constexpr int M = SC >> FL;
   constexpr int EL = fused_el(M);
   constexpr int TP = M / EL;
@@ -889,8 +889,11 @@ __device__ __forceinline__ void fused_level_w(const FusedLevelDev &L, int Sr, in
 #pragma unroll
     for (int i = 0; i < EL; ++i) v[i] = B[slot * SS + t + TP * i];
     wave_sync();
-    float2 wt[EL];  // (re)loaded per batch from the cached table to keep registers free
-    load_twiddles<EL, TP>(wt, t, tw, tw_n);
+    // twiddles come from the workgroup's LDS copy of the table: a global load here would
+    // queue behind the filter prefetch and the previous batch's stores
+    float2 wt[EL];
+#pragma unroll
+    for (int k1 = 0; k1 < EL; ++k1) wt[k1] = twl[t * k1 * (SC / M)];
     fft_core<EL, TP, true, true>(v, t, B + slot * SS, TP + 1, 1, wt);
     if (TP == 1) wave_sync();
     if (active) {
@@ -907,8 +910,8 @@ __device__ __forceinline__ void fused_level_w(const FusedLevelDev &L, int Sr, in
 // Workgroup = 4 wavefronts; wave w handles source 4*(block / per_src) + w and NGRP row
 // groups starting at grp0, entirely on its own (no workgroup barrier anywhere; the four
 // waves only share the filter rows they read through the L1 cache).
-// LDS per wave: rows_w * fused_row_stride(SC) (rows) + b_words (product rows / exchange),
-// in float2.  MASK: bit f set = a level with fold 2^f may occur (only those variants are
+// LDS: SC twiddles shared by the workgroup, then per wave rows_w * fused_row_stride(SC)
+// (rows) + b_words (product rows / exchange), in float2.  MASK: bit f set = a level with fold 2^f may occur (only those variants are
 // compiled in, which keeps the kernel's register allocation at that of its heaviest level).
 template <int SC, int MASK>
 __global__ __launch_bounds__(256, 2) void k_rows_fused(const float2 *__restrict__ src, int src_half,
@@ -927,14 +930,19 @@ __global__ __launch_bounds__(256, 2) void k_rows_fused(const float2 *__restrict_
   const int per_src = groups / NGRP;
   const long src_idx = 4 * static_cast<long>(blockIdx.x / per_src) + wave;
   const int grp0 = (blockIdx.x % per_src) * NGRP;
+  // LDS copy of the SC-point twiddle table, shared by the workgroup
+  float2 *twl = lds;
+  for (int j = threadIdx.x; j < SC; j += blockDim.x) twl[j] = tw[j * (tw_n / SC)];
+  __syncthreads();
   if (src_idx >= NS) return;
   constexpr int RS = fused_row_stride(SC);
-  float2 *R = lds + static_cast<size_t>(wave) * (static_cast<size_t>(rows_w) * RS + b_words);
+  float2 *R = lds + SC + static_cast<size_t>(wave) * (static_cast<size_t>(rows_w) * RS + b_words);
   float2 *B = R + static_cast<size_t>(rows_w) * RS;
   {
     const int t = lane % T, rl = lane / T;
     float2 wt[16];
-    load_twiddles<16, T>(wt, t, tw, tw_n);
+#pragma unroll
+    for (int k1 = 0; k1 < 16; ++k1) wt[k1] = twl[t * k1];
     for (int pass = 0; pass < rows_w / RPW; ++pass) {
       const int rr = pass * RPW + rl;
       const int g = rr / G, ag = rr % G;
@@ -962,10 +970,10 @@ __global__ __launch_bounds__(256, 2) void k_rows_fused(const float2 *__restrict_
   for (int l = 0; l < args.nlev; ++l) {
     const FusedLevelDev &L = args.lv[l];
     switch (L.f) {
-      case 0: if (MASK & 1) fused_level_w<SC, 0>(L, Sr, lgG, lgNGRP, src_idx, grp0, R, B, lane, tw, tw_n); break;
-      case 1: if (MASK & 2) fused_level_w<SC, 1>(L, Sr, lgG, lgNGRP, src_idx, grp0, R, B, lane, tw, tw_n); break;
-      case 2: if ((MASK & 4) && SC >= 64) fused_level_w<(SC >= 64 ? SC : 64), 2>(L, Sr, lgG, lgNGRP, src_idx, grp0, R, B, lane, tw, tw_n); break;
-      case 3: if ((MASK & 8) && SC >= 128) fused_level_w<(SC >= 128 ? SC : 128), 3>(L, Sr, lgG, lgNGRP, src_idx, grp0, R, B, lane, tw, tw_n); break;
+      case 0: if (MASK & 1) fused_level_w<SC, 0>(L, Sr, lgG, lgNGRP, src_idx, grp0, R, B, lane, twl); break;
+      case 1: if (MASK & 2) fused_level_w<SC, 1>(L, Sr, lgG, lgNGRP, src_idx, grp0, R, B, lane, twl); break;
+      case 2: if ((MASK & 4) && SC >= 64) fused_level_w<(SC >= 64 ? SC : 64), 2>(L, Sr, lgG, lgNGRP, src_idx, grp0, R, B, lane, twl); break;
+      case 3: if ((MASK & 8) && SC >= 128) fused_level_w<(SC >= 128 ? SC : 128), 3>(L, Sr, lgG, lgNGRP, src_idx, grp0, R, B, lane, twl); break;
       default: break;
     }
   }
@@ -1307,7 +1315,7 @@ hipError_t launch_rows_fused(const float2 *src, bool src_half, long NS, int Sr, 
     size_t need = static_cast<size_t>(64 / TP) * fused_slot_stride(EL, TP);
     if (need > b_words) b_words = need;
   }
-  size_t lds = 4 * (static_cast<size_t>(rows_w) * fused_row_stride(Sc) + b_words) * sizeof(float2);
+  size_t lds = (Sc + 4 * (static_cast<size_t>(rows_w) * fused_row_stride(Sc) + b_words)) * sizeof(float2);
   if (lds > 160 * 1024) return hipErrorInvalidValue;
   long blocks = ((NS + 3) / 4) * (groups / NGRP);
   if (blocks <= 0 || blocks > 0x7fffffffL) return hipErrorInvalidValue;
