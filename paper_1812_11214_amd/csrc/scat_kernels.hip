@@ -507,7 +507,7 @@ hipError_t launch_col_fast_t(int mode, const void *src, long nodes, int Mc, floa
 // (k_row_lowpass_fast's arithmetic) so that S goes straight to `out` and W never to memory.
 // LM = lowpass length on both axes: 32 (needs MR >= 64) or 8 (MR <= 128); instantiated for
 // MR >= 128 only.
-template <int MR, int MODE, int LM>
+template <int MR, int MODE, int LM, bool PF>
 __global__ __launch_bounds__(256) void k_col_node(const void *__restrict__ src_v,
                                                   float2 *__restrict__ uc, int uc_half,
                                                   const float *__restrict__ phi_rows,
@@ -532,24 +532,38 @@ __global__ __launch_bounds__(256) void k_col_node(const void *__restrict__ src_v
   float phr[E];
 #pragma unroll
   for (int i = 0; i < E; ++i) phr[i] = phi_rows[t + T * i];
-#pragma unroll 1
-  for (int c0 = 0; c0 < Mc; c0 += TC) {
+  // PF (used when the node stores its column spectra): the loads of the next tile are
+  // issued before the stores of the current one, so that waiting for them never means
+  // waiting for those stores to drain (memory operations of a wave retire in order).
+  float2 vn[E];
+  auto fetch = [&](int c0) {
     const int off0 = t * Mc + c0 + c;
-    float2 v[E];
     if (MODE == 0) {
       const float *sp = static_cast<const float *>(src_v) + plane + off0;
 #pragma unroll
-      for (int i = 0; i < E; ++i) v[i] = make_float2(sp[i * step], 0.f);
+      for (int i = 0; i < E; ++i) vn[i] = make_float2(sp[i * step], 0.f);
     } else {
       const float2 *sp = static_cast<const float2 *>(src_v) + plane + off0;
 #pragma unroll
-      for (int i = 0; i < E; ++i) v[i] = nt_load(sp + i * step);
+      for (int i = 0; i < E; ++i) vn[i] = nt_load(sp + i * step);
+    }
+  };
+  if (PF) fetch(0);
+#pragma unroll 1
+  for (int c0 = 0; c0 < Mc; c0 += TC) {
+    const int off0 = t * Mc + c0 + c;
+    if (!PF) fetch(c0);
+    float2 v[E];
+#pragma unroll
+    for (int i = 0; i < E; ++i) v[i] = vn[i];
+    if (MODE != 0) {
       fft_core<E, T, true>(v, t, lds + c, KS, TC, wt);
 #pragma unroll
       for (int i = 0; i < E; ++i)
         v[i] = make_float2(__builtin_amdgcn_sqrtf(v[i].x * v[i].x + v[i].y * v[i].y), 0.f);
     }
     fft_core<E, T, false>(v, t, lds + c, KS, TC, wt);
+    if (PF && c0 + TC < Mc) fetch(c0 + TC);
     if (uc != nullptr) {
       if (uc_half) {
         float2 *up = uc + static_cast<size_t>(node) * (MR / 2 + 1) * Mc + off0;
@@ -677,7 +691,7 @@ hipError_t launch_col_node_t(int mode, const void *src, long nodes, float2 *uc, 
   if (nodes <= 0 || nodes > 0x7fffffffL) return hipErrorInvalidValue;
   size_t lds = static_cast<size_t>(XW) * sizeof(float2) + static_cast<size_t>(LM) * WS * sizeof(float);
   const std::string name = "k_col_node<" + std::to_string(MR) + ", " + (mode ? "1" : "0") + ", " +
-                           std::to_string(LM) + ">";
+                           std::to_string(LM) + ((uc != nullptr && MR >= 256) ? ", true>" : ", false>");
   const double pts = static_cast<double>(nodes) * MR * MR;
   const double cols = static_cast<double>(nodes) * MR;
   Observe ob(name.c_str(),
@@ -686,21 +700,27 @@ hipError_t launch_col_node_t(int mode, const void *src, long nodes, float2 *uc, 
              cols * ((mode ? 2 : 1) * fft_flops(MR) + fft_flops(LM) + 2.0 * MR) + (mode ? 4.0 * pts : 0) +
                  static_cast<double>(nodes) * LM * 0.5 * (fft_flops(MR) + fft_flops(LM) + 2.0 * MR),
              st);
-  static bool attr_done[2] = {false, false};
-  if (lds > 65536 && !attr_done[mode ? 1 : 0]) {
-    const void *fn = mode ? reinterpret_cast<const void *>(k_col_node<MR, 1, LM>)
-                          : reinterpret_cast<const void *>(k_col_node<MR, 0, LM>);
-    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) return e;
-    attr_done[mode ? 1 : 0] = true;
-  }
   dim3 g(static_cast<unsigned>(nodes)), b(T * TC);
-  if (mode == 0)
-    hipLaunchKernelGGL((k_col_node<MR, 0, LM>), g, b, lds, st, src, uc, static_cast<int>(uc_half),
-                       phi_rows, phi_cols, out, cm, K, tw, tw_n);
-  else
-    hipLaunchKernelGGL((k_col_node<MR, 1, LM>), g, b, lds, st, src, uc, static_cast<int>(uc_half),
-                       phi_rows, phi_cols, out, cm, K, tw, tw_n);
+#define SCAT_CN_LAUNCH(MODE_, PF_)                                                                 \
+  {                                                                                                \
+    static bool attr_done = false;                                                                 \
+    if (lds > 65536 && !attr_done) {                                                               \
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_col_node<MR, MODE_, LM, PF_>), \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);  \
+      if (e != hipSuccess) return e;                                                               \
+      attr_done = true;                                                                            \
+    }                                                                                              \
+    hipLaunchKernelGGL((k_col_node<MR, MODE_, LM, PF_>), g, b, lds, st, src, uc,                   \
+                       static_cast<int>(uc_half), phi_rows, phi_cols, out, cm, K, tw, tw_n);       \
+  }
+  // (measured: the prefetch pays for 256-row nodes only; it costs 32 registers)
+  const bool pf = uc != nullptr && MR >= 256;
+  if (mode == 0) {
+    if (pf) SCAT_CN_LAUNCH(0, (MR >= 256)) else SCAT_CN_LAUNCH(0, false)
+  } else {
+    if (pf) SCAT_CN_LAUNCH(1, (MR >= 256)) else SCAT_CN_LAUNCH(1, false)
+  }
+#undef SCAT_CN_LAUNCH
   return hipGetLastError();
 }
 
