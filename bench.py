@@ -24,18 +24,23 @@ WORKLOAD = 2                   # index into workloads.CONFIGS: 2-D J=3 L=8 256x2
 TRAFFIC_TAG = "2d_J3_L8_256x256_b384"
 
 
-def cpu_baseline(planes, J, L, channels, budget_s=20.0):
+def cpu_baseline(planes, dims, J, LQ, channels, budget_s=20.0):
     """Time the oracle (single process, numpy FFTs are single threaded) on as many planes
     of the workload as fit in about budget_s seconds."""
     import oracle
-    n_r, n_c = planes.shape[-2:]
-    bank = oracle.bank_2d(n_r, n_c, J, L)          # built once, like the GPU plan; not timed
+    if dims == 2:
+        n_r, n_c = planes.shape[-2:]
+        bank = oracle.bank_2d(n_r, n_c, J, LQ)     # built once, like the GPU plan; not timed
+        run = lambda x: oracle.scattering2d(x, J, LQ, bank=bank)
+    else:
+        bank = oracle.bank_1d(planes.shape[-1], J, LQ)
+        run = lambda x: oracle.scattering1d(x, J, LQ, bank=bank)
     t0 = time.perf_counter()
-    oracle.scattering2d(planes[:1], J, L, bank=bank)
+    run(planes[:1])
     one = time.perf_counter() - t0
-    n = int(max(2, min(len(planes), budget_s / max(one, 1e-6))))
+    n = int(max(1, min(len(planes), budget_s / max(one, 1e-6))))
     t0 = time.perf_counter()
-    oracle.scattering2d(planes[:n], J, L, bank=bank)
+    run(planes[:n])
     dt = time.perf_counter() - t0
     return {"value": n / dt / channels, "unit": "images/s", "cores": 1, "kind": "oracle",
             "sample": "%d of %d planes (%d-channel images), fp64 numpy cascade, filter bank "
@@ -49,6 +54,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--cpu-seconds", type=float, default=20.0,
                     help="CPU time budget of the oracle baseline (0 disables it)")
+    ap.add_argument("--workload", type=int, default=WORKLOAD,
+                    help="index of the configuration to run (default 2 = the headline one; "
+                         "0, 1, 3, 4 are the other parity configurations)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (a kernel of known "
                          "traffic, to calibrate profiler byte counters)")
@@ -63,10 +71,11 @@ def main():
     import paper_1812_11214_amd as scat
     from paper_1812_11214_amd import workloads
 
-    cfg = workloads.config(WORKLOAD)
-    P = workloads.num_planes(WORKLOAD)
+    wl = args.workload
+    cfg = workloads.config(wl)
+    P = workloads.num_planes(wl)
     C = cfg["channels"]
-    x_host = workloads.planes(WORKLOAD)
+    x_host = workloads.planes(wl)
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -120,7 +129,7 @@ def main():
     # (FETCH_SIZE and WRITE_SIZE runs of this same command, scaled by a plain copy)
     per_kernel = {}
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % TRAFFIC_TAG)
-    if os.path.exists(tpath):
+    if wl == WORKLOAD and os.path.exists(tpath):
         with open(tpath) as f:
             for line in f:
                 cols = line.rstrip("\n").split("\t")
@@ -144,12 +153,13 @@ def main():
 
     images_per_s = (P / C) / (ms_per_step * 1e-3)
     result = {
-        "metric": "Scattering2D J=3 L=8 256x256 images/sec on 1 MI355X; % HBM roofline",
+        "metric": ("Scattering2D J=3 L=8 256x256 images/sec on 1 MI355X; % HBM roofline"
+                   if wl == WORKLOAD else "scattering images/sec on 1 MI355X (%s)" % cfg["name"]),
         "value": images_per_s, "unit": "images/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": cfg["name"], "planes_per_step": P, "channels": C,
-                   "J": cfg["J"], "L": cfg["LQ"], "shape": list(cfg["shape"]), "max_order": 2,
+                   "J": cfg["J"], "LQ": cfg["LQ"], "shape": list(cfg["shape"]), "max_order": 2,
                    "coefficients": plan.K},
         "planes_per_s": P / (ms_per_step * 1e-3),
         "wall_ms_per_step": wall / args.steps * 1e3,
@@ -159,7 +169,8 @@ def main():
     }
     plan.close()
     if args.cpu_seconds > 0:
-        result["cpu_baseline"] = cpu_baseline(x_host, cfg["J"], cfg["LQ"], C, args.cpu_seconds)
+        result["cpu_baseline"] = cpu_baseline(x_host, cfg["dims"], cfg["J"], cfg["LQ"], C,
+                                              args.cpu_seconds)
     print(json.dumps(result))
 
 
