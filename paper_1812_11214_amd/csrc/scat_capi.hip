@@ -101,6 +101,7 @@ struct scat_plan {
   std::vector<size_t> phi_rows_off, phi_cols_off;  // 2-D, per res
   std::vector<size_t> phi_off;                     // 1-D, per res
   bool fused = false;  // 2-D: the fused row pass can serve every level of this plan
+  bool tree = false;   // 2-D: planes small enough for the whole-tree-in-LDS kernel
 };
 
 namespace {
@@ -132,7 +133,11 @@ Layout make_layout(const scat_plan &p, long batch) {
   const size_t n = static_cast<size_t>(p.n1) * p.n2;
   const bool second = h.max_order == 2 && h.J >= 2;
   const size_t c8 = sizeof(float2);
-  if (h.dims == 2 && p.fused) {
+  if (h.dims == 2 && p.tree) {
+    // xh: spectra of x; w: half-lowpassed x for S0; everything else stays in LDS
+    L.xh = n * c8;
+    L.w = static_cast<size_t>(p.n1 >> h.J) * p.n2 * sizeof(float);
+  } else if (h.dims == 2 && p.fused) {
     // xh: column spectra of x; t: first-order row-pass outputs of all octaves at once
     // (sum over j of L*n/4^j); u: column spectra of one octave's moduli; v: second-order
     // row-pass outputs of all child octaves of one first-order octave
@@ -296,6 +301,7 @@ scat_status create_common(scat_plan **out_plan, int dims, const int *shape, int 
     p->n1 = shape[0] >> lg2;
   }
   p->fused = dims == 2 && J <= 4 && scat::rows_fused_supported(p->n1, p->n2, J - 1);
+  p->tree = dims == 2 && scat::tree_supported(p->n1, p->n2, J);
   if (device) {
     scat_status s;
     try {
@@ -451,6 +457,32 @@ scat_status forward_2d_fused(scat_plan *p, const float *in, float *out, long p0,
   return SCAT_OK;
 }
 
+// ---- 2-D schedule for planes whose whole tree fits in LDS: x -> X^ and S0 by the pass
+// kernels, then one kernel for everything below
+scat_status forward_2d_tree(scat_plan *p, const float *in, float *out, long p0, long pc,
+                            const Layout &lay, hipStream_t st) {
+  const scat::HostPlan &h = p->host;
+  const int J = h.J, L = h.LQ, K = h.K;
+  const int Nr = p->n1, Nc = p->n2;
+  const int m_r = Nr >> J, m_c = Nc >> J;
+  char *base = static_cast<char *>(p->d_scratch);
+  float2 *XH = reinterpret_cast<float2 *>(base);
+  float *W = reinterpret_cast<float *>(base + lay.xh * pc);
+  const float *tab = p->d_tables;
+  const float *x = in + static_cast<size_t>(p0) * Nr * Nc;
+  float *o = out + static_cast<size_t>(p0) * K * m_r * m_c;
+  const ChanMap one{1, 1, 0, 0};
+  SCAT_TRY(scat::launch_col(0, x, pc, Nr, Nc, XH, 0, tab + p->phi_rows_off[0], m_r, W, nullptr,
+                            one, K, p->d_tw, p->tw_n, st));
+  SCAT_TRY(scat::launch_row_lowpass(W, pc, m_r, Nc, m_c, tab + p->phi_cols_off[0], o, one, K,
+                                    p->d_tw, p->tw_n, st));
+  SCAT_TRY(scat::launch_row_fwd(XH, pc * Nr, Nc, p->d_tw, p->tw_n, st));
+  SCAT_TRY(scat::launch_tree32(XH, pc, L, h.max_order, tab + p->psi1_off[0], tab + p->psi1_off[1],
+                               tab + p->phi_rows_off[0], tab + p->phi_cols_off[0],
+                               tab + p->phi_rows_off[1], tab + p->phi_cols_off[1], o, K, st));
+  return SCAT_OK;
+}
+
 // ---- 1-D schedule (four-step transforms: the signal is an n1 x n2 matrix)
 scat_status forward_1d(scat_plan *p, const float *in, float *out, long p0, long pc,
                        const Layout &lay, hipStream_t st) {
@@ -553,6 +585,7 @@ scat_status scat_forward(scat_plan *plan, const float *in, float *out, long batc
   for (long p0 = 0; p0 < batch; p0 += lay.chunk) {
     long pc = batch - p0 < lay.chunk ? batch - p0 : lay.chunk;
     scat_status s = plan->host.dims == 1 ? forward_1d(plan, in, out, p0, pc, lay, st)
+                    : plan->tree         ? forward_2d_tree(plan, in, out, p0, pc, lay, st)
                     : plan->fused        ? forward_2d_fused(plan, in, out, p0, pc, lay, st)
                                          : forward_2d(plan, in, out, p0, pc, lay, st);
     if (s != SCAT_OK) return s;

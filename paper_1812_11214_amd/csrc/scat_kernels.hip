@@ -41,6 +41,18 @@ struct Observe {
 };
 
 
+}  // namespace
+
+LaunchScope::LaunchScope(const char *name, double bytes, double flops, hipStream_t st)
+    : st_(st), on_(g_observer != nullptr) {
+  if (on_) g_observer->before(name, bytes, flops, st_);
+}
+LaunchScope::~LaunchScope() {
+  if (on_) g_observer->after(st_);
+}
+
+namespace {
+
 __device__ __forceinline__ float2 cmul(float2 a, float2 b) {
   return make_float2(a.x * b.x - a.y * b.y, a.x * b.y + a.y * b.x);
 }

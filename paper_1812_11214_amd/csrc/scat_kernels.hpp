@@ -16,6 +16,19 @@ struct LaunchObserver {
 };
 void set_launch_observer(LaunchObserver *o);
 
+// Reports one launch to the installed observer: construct right before the launch,
+// destroy right after it.
+struct LaunchScope {
+  LaunchScope(const char *name, double bytes, double flops, hipStream_t st);
+  ~LaunchScope();
+  LaunchScope(const LaunchScope &) = delete;
+  LaunchScope &operator=(const LaunchScope &) = delete;
+
+ private:
+  hipStream_t st_;
+  bool on_;
+};
+
 // Where a kernel's node number g (within one input plane p) lands in the output:
 // channel = base + (g / inner) * outer_stride + (g % inner), node = p * G + g.
 struct ChanMap {
@@ -64,5 +77,19 @@ bool rows_fused_supported(int Sr, int Sc, int fmax);
 hipError_t launch_rows_fused(const float2 *src, bool src_half, long NS, int Sr, int Sc,
                              const FusedLevel *levels, int nlev, const float2 *tw, int tw_n,
                              hipStream_t st);
+
+// Whole scattering tree of 32 x 32 planes at J = 2 below the input spectrum: one wavefront
+// per first-order node keeps the node, the spectrum of its modulus and its second-order
+// children in LDS and writes only S1 and S2 (see scat_tree.hip).
+//   xh        [planes][32][32] spectra of the inputs (forward 2-D FFT, unnormalised)
+//   psi_j0/1  [L][32][32] first-order wavelets of octaves 0 and 1, pre-scaled by 1/1024
+//   phi_*     lowpass factors along rows / columns at resolutions 0 (32) and 1 (16),
+//             pre-scaled by 1/length
+//   out       [planes][K][8][8]; channel 0 (S0) is not written here
+bool tree_supported(int n_r, int n_c, int J);
+hipError_t launch_tree32(const float2 *xh, long planes, int L, int max_order, const float *psi_j0,
+                         const float *psi_j1, const float *phi_rows0, const float *phi_cols0,
+                         const float *phi_rows1, const float *phi_cols1, float *out, int K,
+                         hipStream_t st);
 
 }  // namespace scat
