@@ -20,8 +20,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
+ALU_PEAK_TFLOPS = 157.3        # MI355X fp32 vector peak (256 CUs x 4 SIMD x 16 lanes x 2 x 2.4 GHz)
 WORKLOAD = 2                   # index into workloads.CONFIGS: 2-D J=3 L=8 256x256, 128x3 planes
-TRAFFIC_TAG = "2d_J3_L8_256x256_b384"
+# committed rocprofv3 counter summaries, profiles/hbm_traffic_<tag>.txt, per workload index
+TRAFFIC_TAGS = {1: "2d_J2_L8_32x32_b3072", 2: "2d_J3_L8_256x256_b384"}
 
 
 def cpu_baseline(planes, dims, J, LQ, channels, budget_s=20.0):
@@ -128,8 +130,8 @@ def main():
     # HBM bytes per launch of every kernel from the committed rocprofv3 counter summary
     # (FETCH_SIZE and WRITE_SIZE runs of this same command, scaled by a plain copy)
     per_kernel = {}
-    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % TRAFFIC_TAG)
-    if wl == WORKLOAD and os.path.exists(tpath):
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % TRAFFIC_TAGS.get(wl, "none"))
+    if os.path.exists(tpath):
         with open(tpath) as f:
             for line in f:
                 cols = line.rstrip("\n").split("\t")
@@ -144,12 +146,28 @@ def main():
         pipeline = {"hbm_bytes_per_step": step_bytes, "achieved": rate, "unit": "GB/s",
                     "frac": rate / HBM_PEAK_GBS,
                     "alg_bytes_per_step": sum(v["alg_bytes"] for v in table.values())}
-    roofline = {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                "avg_launch_ms": avg_ms, "launches_timed": dom["launches"],
-                "alg_bytes_per_launch": bytes_per_launch,
-                "model_tflops": flops_per_launch / (avg_ms * 1e-3) / 1e12,
-                "share_of_step": dom["ms"] / args.steps / ms_per_step}
+    model_tflops = flops_per_launch / (avg_ms * 1e-3) / 1e12
+    # the roofline that bounds this kernel: the larger of the time its least traffic needs
+    # at the HBM peak and the time its model flops need at the fp32 vector peak
+    hbm_bound = bytes_per_launch / (HBM_PEAK_GBS * 1e9) >= flops_per_launch / (ALU_PEAK_TFLOPS * 1e12)
+    if hbm_bound:
+        roofline = {"bound": "hbm", "kernel": dominant, "achieved": achieved,
+                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS}
+    else:
+        roofline = {"bound": "alu", "kernel": dominant, "achieved": model_tflops,
+                    "peak": ALU_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": model_tflops / ALU_PEAK_TFLOPS}
+    roofline.update({"traffic": traffic, "avg_launch_ms": avg_ms,
+                     "launches_timed": dom["launches"],
+                     "alg_bytes_per_launch": bytes_per_launch, "alg_gbs": achieved,
+                     "model_tflops": model_tflops,
+                     "share_of_step": dom["ms"] / args.steps / ms_per_step})
+    # whole step against the fp32 vector peak with the 5 n log2 n flop model
+    step_flops = sum(v["model_flops"] for v in table.values())
+    step_tflops = step_flops / (ms_per_step * 1e-3) / 1e12
+    pipeline_alu = {"model_flops_per_step": step_flops, "achieved": step_tflops,
+                    "unit": "TFLOP/s", "peak": ALU_PEAK_TFLOPS,
+                    "frac": step_tflops / ALU_PEAK_TFLOPS}
 
     images_per_s = (P / C) / (ms_per_step * 1e-3)
     result = {
@@ -165,6 +183,7 @@ def main():
         "wall_ms_per_step": wall / args.steps * 1e3,
         "roofline": roofline,
         "pipeline_hbm": pipeline,
+        "pipeline_alu": pipeline_alu,
         "kernel_table_ms": {k: round(v["ms"], 4) for k, v in table.items()},
     }
     plan.close()

@@ -102,6 +102,7 @@ struct scat_plan {
   std::vector<size_t> phi_off;                     // 1-D, per res
   bool fused = false;  // 2-D: the fused row pass can serve every level of this plan
   bool tree = false;   // 2-D: planes small enough for the whole-tree-in-LDS kernel
+  std::vector<size_t> taps_off;  // tree: spatial taps of the lowpass along a column, per res
 };
 
 namespace {
@@ -250,6 +251,21 @@ scat_status upload(scat_plan *p) {
   } else {
     for (int r = 0; r < h.J; ++r)
       p->phi_off.push_back(append_table(pool, *h.find(0, 0, r), 1, p->n1));
+  }
+  if (p->tree) {
+    // the lowpass along a column as spatial taps: g[m] = sum_k phi[k] / len * cos(2 pi k m / len)
+    // (phi is even, so the inverse transform is real)
+    const double two_pi_ = 6.283185307179586476925286766559;
+    for (int r = 0; r < h.J; ++r) {
+      const std::vector<double> &ph = h.phi_rows[r];
+      const size_t len = ph.size();
+      p->taps_off.push_back(pool.size());
+      for (size_t m = 0; m < len; ++m) {
+        double acc = 0.0;
+        for (size_t k = 0; k < len; ++k) acc += ph[k] * std::cos(two_pi_ * static_cast<double>((k * m) % len) / len);
+        pool.push_back(static_cast<float>(acc / static_cast<double>(len)));
+      }
+    }
   }
   // twiddles exp(-2 pi i j / tw_n), evaluated in double
   p->tw_n = h.dims == 2 ? (p->n1 > p->n2 ? p->n1 : p->n2) : p->n1 * p->n2;
@@ -478,8 +494,8 @@ scat_status forward_2d_tree(scat_plan *p, const float *in, float *out, long p0, 
                                     p->d_tw, p->tw_n, st));
   SCAT_TRY(scat::launch_row_fwd(XH, pc * Nr, Nc, p->d_tw, p->tw_n, st));
   SCAT_TRY(scat::launch_tree32(XH, pc, L, h.max_order, tab + p->psi1_off[0], tab + p->psi1_off[1],
-                               tab + p->phi_rows_off[0], tab + p->phi_cols_off[0],
-                               tab + p->phi_rows_off[1], tab + p->phi_cols_off[1], o, K, st));
+                               tab + p->phi_cols_off[0], tab + p->phi_cols_off[1],
+                               tab + p->taps_off[0], tab + p->taps_off[1], o, K, st));
   return SCAT_OK;
 }
 

@@ -83,13 +83,15 @@ hipError_t launch_rows_fused(const float2 *src, bool src_half, long NS, int Sr, 
 // children in LDS and writes only S1 and S2 (see scat_tree.hip).
 //   xh        [planes][32][32] spectra of the inputs (forward 2-D FFT, unnormalised)
 //   psi_j0/1  [L][32][32] first-order wavelets of octaves 0 and 1, pre-scaled by 1/1024
-//   phi_*     lowpass factors along rows / columns at resolutions 0 (32) and 1 (16),
-//             pre-scaled by 1/length
+//   phi_cols* lowpass along a row (the column frequency axis) at resolutions 0 (32 samples)
+//             and 1 (16 samples), Fourier domain, pre-scaled by 1/length
+//   taps*     lowpass along a column at the same resolutions as spatial taps: the inverse
+//             DFT (unnormalised) of the pre-scaled Fourier samples, 32 and 16 values
 //   out       [planes][K][8][8]; channel 0 (S0) is not written here
 bool tree_supported(int n_r, int n_c, int J);
 hipError_t launch_tree32(const float2 *xh, long planes, int L, int max_order, const float *psi_j0,
-                         const float *psi_j1, const float *phi_rows0, const float *phi_cols0,
-                         const float *phi_rows1, const float *phi_cols1, float *out, int K,
+                         const float *psi_j1, const float *phi_cols0, const float *phi_cols1,
+                         const float *taps0, const float *taps1, float *out, int K,
                          hipStream_t st);
 
 }  // namespace scat

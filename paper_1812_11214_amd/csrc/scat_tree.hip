@@ -38,12 +38,13 @@ __device__ __forceinline__ float2 pair_swap(float2 a) {
 }
 __device__ __forceinline__ float2 sel(bool c, float2 a, float2 b) { return c ? a : b; }
 
-// 32-point transform over a lane pair: lane tp (0 or 1) holds x[tp + 2 i] in v[i] and ends
-// with X[tp + 2 i] in v[i].  Radix 16 in registers, twiddle w32^(tp k1), then the radix-2
-// butterflies between the two lanes: lane tp keeps the odd/even k1 = tp + 2 j it owns and
-// receives the partner's value for the same k1.
-template <bool INV>
-__device__ __forceinline__ void fft32_pair(float2 (&v)[16], int tp) {
+// Twiddles of a lane for the 32-point lane-pair transform: w[k1] = exp(-2 pi i tp k1 / 32)
+// (all ones in the even lane), and the sign bit that negates a float in the odd lane.
+struct PairTw {
+  float2 w[16];
+  unsigned flip;
+};
+__device__ __forceinline__ void pair_twiddles(PairTw &pw, int tp) {
   // cos and sin of 2 pi k / 32
   constexpr float C[16] = {1.f,
                            0.98078528040323044913f,
@@ -77,13 +78,30 @@ __device__ __forceinline__ void fft32_pair(float2 (&v)[16], int tp) {
                            0.55557023301960222474f,
                            0.38268343236508977173f,
                            0.19509032201612826785f};
+  const bool odd = tp != 0;
+#pragma unroll
+  for (int k = 0; k < 16; ++k) pw.w[k] = make_float2(odd ? C[k] : 1.f, odd ? -S[k] : 0.f);
+  pw.flip = odd ? 0x80000000u : 0u;
+}
+__device__ __forceinline__ float flip_sign(float x, unsigned flip) {
+  return __uint_as_float(__float_as_uint(x) ^ flip);
+}
+
+// 32-point transform over a lane pair: lane tp (0 or 1) holds x[tp + 2 i] in v[i] and ends
+// with X[tp + 2 i] in v[i].  Radix 16 in registers, twiddle w32^(tp k1), then the radix-2
+// butterflies between the two lanes: lane tp keeps the k1 = tp + 2 j it owns, receives the
+// partner's value for the same k1 and forms sum and difference (the difference is
+// even-lane minus odd-lane value, hence the sign flip in the odd lane).
+template <bool INV>
+__device__ __forceinline__ void fft32_pair(float2 (&v)[16], int tp, const PairTw &pw) {
   DftRegs<16, INV>::run(v);
   const bool odd = tp != 0;
 #pragma unroll
   for (int k1 = 1; k1 < 16; ++k1) {
-    const float wr = odd ? C[k1] : 1.f;
-    const float wi = odd ? (INV ? S[k1] : -S[k1]) : 0.f;
-    v[k1] = c_mul(v[k1], make_float2(wr, wi));
+    const float2 w = pw.w[k1];
+    // multiply by w (forward) or its conjugate (inverse)
+    v[k1] = INV ? make_float2(v[k1].x * w.x + v[k1].y * w.y, v[k1].y * w.x - v[k1].x * w.y)
+                : make_float2(v[k1].x * w.x - v[k1].y * w.y, v[k1].y * w.x + v[k1].x * w.y);
   }
   float2 o[16];
 #pragma unroll
@@ -91,9 +109,9 @@ __device__ __forceinline__ void fft32_pair(float2 (&v)[16], int tp) {
     const float2 mine = sel(odd, v[2 * j + 1], v[2 * j]);
     const float2 send = sel(odd, v[2 * j], v[2 * j + 1]);
     const float2 recv = pair_swap(send);
-    const float2 a0 = sel(odd, recv, mine), a1 = sel(odd, mine, recv);
-    o[j] = c_add(a0, a1);
-    o[j + 8] = c_sub(a0, a1);
+    o[j] = c_add(mine, recv);
+    const float2 d = c_sub(mine, recv);
+    o[j + 8] = make_float2(flip_sign(d.x, pw.flip), flip_sign(d.y, pw.flip));
   }
 #pragma unroll
   for (int i = 0; i < 16; ++i) v[i] = o[i];
@@ -143,7 +161,8 @@ struct TreeArgs {
   long planes;
   int L, max_order, K;
   const float *psi_j0, *psi_j1;
-  const float *phi_rows0, *phi_cols0, *phi_rows1, *phi_cols1;
+  const float *phi_cols0, *phi_cols1;  // lowpass along a row, Fourier samples (32 and 16)
+  const float *taps0, *taps1;          // lowpass along a column, spatial taps (32 and 16)
   float *out;
 };
 
@@ -151,10 +170,11 @@ struct TreeArgs {
 // c): node g of the batch is filtered by psi_j1[first + g] out of the 32 x 32 spectrum
 // `src` (fold 2 on both axes) and its lowpass goes to channel chan0 + g.  SRC_LDS: src is
 // the wave's P1 plane (row stride P1_STRIDE), else global memory (row stride 32).
+// tp1[r] = taps1[(2 n - r) mod 16] for this lane's output row n = (lane % 16) / 2.
 template <bool SRC_LDS>
 __device__ __forceinline__ void small_nodes(const TreeArgs &a, const float2 *src, int first,
                                             int chan0, float2 *P2, float *Wl, float *out,
-                                            int lane) {
+                                            int lane, const float (&tp1)[16]) {
   const int g = lane >> 4, c = lane & 15;
   const bool live = first + g < a.L;
   const int th = live ? first + g : a.L - 1;
@@ -200,23 +220,30 @@ __device__ __forceinline__ void small_nodes(const TreeArgs &a, const float2 *src
 #pragma unroll
   for (int n = 0; n < 8; ++n) wl[c * 8 + n] = f8[n].x;
   wave_sync();
-  // lowpass along the columns of that 16 x 8 plane, two real columns per transform
-  const int pr = c & 3;
+  // lowpass along the columns of that 16 x 8 plane, straight from its definition: output
+  // row n is the circular correlation with the spatial taps at stride 2.  Lane c forms the
+  // four outputs (n = c / 2, columns 4 (c % 2) ...).
+  {
+    const int n = c >> 1, c4 = 4 * (c & 1);
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-  for (int i = 0; i < 16; ++i) v[i] = make_float2(wl[i * 8 + 2 * pr], wl[i * 8 + 2 * pr + 1]);
-  DftRegs<16, false>::run(v);
-#pragma unroll
-  for (int m = 0; m < 8; ++m) {
-    const float p0 = a.phi_rows1[m], p1 = a.phi_rows1[m + 8];
-    f8[m] = make_float2(v[m].x * p0 + v[m + 8].x * p1, v[m].y * p0 + v[m + 8].y * p1);
-  }
-  DftRegs<8, true>::run(f8);
-  if (live && c < 4) {
-    float *o = out + static_cast<size_t>(chan0 + g) * 64 + 2 * pr;
-#pragma unroll
-    for (int n = 0; n < 8; ++n) *reinterpret_cast<float2 *>(o + n * 8) = f8[n];
+    for (int r = 0; r < 16; ++r) {
+      const float t = tp1[r];
+      const float4 w = *reinterpret_cast<const float4 *>(wl + r * 8 + c4);
+      acc.x += t * w.x;
+      acc.y += t * w.y;
+      acc.z += t * w.z;
+      acc.w += t * w.w;
+    }
+    if (live) *reinterpret_cast<float4 *>(out + static_cast<size_t>(chan0 + g) * 64 + n * 8 + c4) = acc;
   }
   wave_sync();  // P2 and Wl are free again
+}
+
+__device__ __forceinline__ void load_taps1(float (&tp1)[16], const float *taps1, int lane) {
+  const int n = (lane & 15) >> 1;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) tp1[r] = taps1[(2 * n - r) & 15];
 }
 
 // One first-order node of octave 0 with all its children.
@@ -226,6 +253,8 @@ __device__ __forceinline__ void node_octave0(const TreeArgs &a, const float2 *xh
   const int tp = lane & 1, q = lane >> 1;
   const bool kids = a.max_order == 2;
   const float *ps = a.psi_j0 + static_cast<size_t>(th1) * 1024;
+  PairTw pw;
+  pair_twiddles(pw, tp);
   float2 v[16];
   // columns: lane pair q owns column q, rows tp + 2 i
 #pragma unroll
@@ -235,17 +264,17 @@ __device__ __forceinline__ void node_octave0(const TreeArgs &a, const float2 *xh
     const float f = ps[r * 32 + q];
     v[i] = make_float2(x.x * f, x.y * f);
   }
-  fft32_pair<true>(v, tp);
+  fft32_pair<true>(v, tp, pw);
 #pragma unroll
   for (int i = 0; i < 16; ++i) P1[(tp + 2 * i) * P1_STRIDE + q] = v[i];
   wave_sync();
   // rows: lane pair q owns row q
 #pragma unroll
   for (int i = 0; i < 16; ++i) v[i] = P1[q * P1_STRIDE + tp + 2 * i];
-  fft32_pair<true>(v, tp);
+  fft32_pair<true>(v, tp, pw);
 #pragma unroll
   for (int i = 0; i < 16; ++i) v[i] = modulus(v[i]);
-  fft32_pair<false>(v, tp);
+  fft32_pair<false>(v, tp, pw);
   if (kids) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) P1[q * P1_STRIDE + tp + 2 * i] = v[i];
@@ -263,41 +292,28 @@ __device__ __forceinline__ void node_octave0(const TreeArgs &a, const float2 *xh
 #pragma unroll
   for (int j = 0; j < 4; ++j) Wl[q * 9 + tp + 2 * j] = f4[j].x;  // [row 32][col 8], stride 9
   wave_sync();
-  // S1: lowpass along the columns of that 32 x 8 plane, two real columns per lane pair
+  // S1: lowpass along the columns of that 32 x 8 plane from its definition (circular
+  // correlation with the spatial taps at stride 4), one output sample per lane
   {
-    const int pr = q & 3;
+    const int n = lane >> 3, nc = lane & 7;
+    float acc = 0.f;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int r = tp + 2 * i;
-      v[i] = make_float2(Wl[r * 9 + 2 * pr], Wl[r * 9 + 2 * pr + 1]);
-    }
-    fft32_pair<false>(v, tp);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) f4[j] = make_float2(0.f, 0.f);
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const float p = a.phi_rows0[tp + 2 * i];
-      f4[i & 3].x += v[i].x * p;
-      f4[i & 3].y += v[i].y * p;
-    }
-    idft8_pair(f4, tp);
-    if (q < 4) {
-      float *o = out + static_cast<size_t>(1 + th1) * 64 + 2 * pr;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) *reinterpret_cast<float2 *>(o + (tp + 2 * j) * 8) = f4[j];
-    }
+    for (int r = 0; r < 32; ++r) acc += a.taps0[(4 * n - r) & 31] * Wl[r * 9 + nc];
+    out[static_cast<size_t>(1 + th1) * 64 + lane] = acc;
   }
   if (!kids) return;
   // columns of the row spectra: P1 becomes the 2-D spectrum of the modulus
 #pragma unroll
   for (int i = 0; i < 16; ++i) v[i] = P1[(tp + 2 * i) * P1_STRIDE + q];
-  fft32_pair<false>(v, tp);
+  fft32_pair<false>(v, tp, pw);
 #pragma unroll
   for (int i = 0; i < 16; ++i) P1[(tp + 2 * i) * P1_STRIDE + q] = v[i];
   wave_sync();
   const int chan0 = 1 + 2 * a.L + th1 * a.L;
+  float tp1[16];
+  load_taps1(tp1, a.taps1, lane);
   for (int first = 0; first < a.L; first += 4)
-    small_nodes<true>(a, P1, first, chan0 + first, P2, Wl, out, lane);
+    small_nodes<true>(a, P1, first, chan0 + first, P2, Wl, out, lane, tp1);
 }
 
 __global__ __launch_bounds__(64 * TREE_WAVES) void k_tree32(TreeArgs a) {
@@ -317,8 +333,11 @@ __global__ __launch_bounds__(64 * TREE_WAVES) void k_tree32(TreeArgs a) {
   float *out = a.out + p * a.K * 64;
   if (it < a.L)
     node_octave0(a, xh, it, P1, P2, Wl, out, lane);
-  else
-    small_nodes<false>(a, xh, 4 * (it - a.L), 1 + a.L + 4 * (it - a.L), P2, Wl, out, lane);
+  else {
+    float tp1[16];
+    load_taps1(tp1, a.taps1, lane);
+    small_nodes<false>(a, xh, 4 * (it - a.L), 1 + a.L + 4 * (it - a.L), P2, Wl, out, lane, tp1);
+  }
 }
 
 }  // namespace
@@ -326,8 +345,8 @@ __global__ __launch_bounds__(64 * TREE_WAVES) void k_tree32(TreeArgs a) {
 bool tree_supported(int n_r, int n_c, int J) { return n_r == 32 && n_c == 32 && J == 2; }
 
 hipError_t launch_tree32(const float2 *xh, long planes, int L, int max_order, const float *psi_j0,
-                         const float *psi_j1, const float *phi_rows0, const float *phi_cols0,
-                         const float *phi_rows1, const float *phi_cols1, float *out, int K,
+                         const float *psi_j1, const float *phi_cols0, const float *phi_cols1,
+                         const float *taps0, const float *taps1, float *out, int K,
                          hipStream_t st) {
   if (planes <= 0) return hipSuccess;
   if (L < 1 || (max_order != 1 && max_order != 2)) return hipErrorInvalidValue;
@@ -343,8 +362,7 @@ hipError_t launch_tree32(const float2 *xh, long planes, int L, int max_order, co
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  TreeArgs a{xh,     planes,    L,         max_order, K,         psi_j0,
-             psi_j1, phi_rows0, phi_cols0, phi_rows1, phi_cols1, out};
+  TreeArgs a{xh, planes, L, max_order, K, psi_j0, psi_j1, phi_cols0, phi_cols1, taps0, taps1, out};
   // least traffic: spectra in, S1 and S2 out, the 2 L wavelet tables once
   const double kids = max_order == 2 ? static_cast<double>(L) * L : 0.0;
   const double bytes = planes * (1024.0 * 8 + (2.0 * L + kids) * 64 * 4) + 2.0 * L * 1024 * 4;
