@@ -135,9 +135,8 @@ Layout make_layout(const scat_plan &p, long batch) {
   const bool second = h.max_order == 2 && h.J >= 2;
   const size_t c8 = sizeof(float2);
   if (h.dims == 2 && p.tree) {
-    // xh: spectra of x; w: half-lowpassed x for S0; everything else stays in LDS
+    // xh: spectra of x; everything else stays in LDS
     L.xh = n * c8;
-    L.w = static_cast<size_t>(p.n1 >> h.J) * p.n2 * sizeof(float);
   } else if (h.dims == 2 && p.fused) {
     // xh: column spectra of x; t: first-order row-pass outputs of all octaves at once
     // (sum over j of L*n/4^j); u: column spectra of one octave's moduli; v: second-order
@@ -483,16 +482,12 @@ scat_status forward_2d_tree(scat_plan *p, const float *in, float *out, long p0, 
   const int m_r = Nr >> J, m_c = Nc >> J;
   char *base = static_cast<char *>(p->d_scratch);
   float2 *XH = reinterpret_cast<float2 *>(base);
-  float *W = reinterpret_cast<float *>(base + lay.xh * pc);
+  (void)lay;
   const float *tab = p->d_tables;
   const float *x = in + static_cast<size_t>(p0) * Nr * Nc;
   float *o = out + static_cast<size_t>(p0) * K * m_r * m_c;
-  const ChanMap one{1, 1, 0, 0};
-  SCAT_TRY(scat::launch_col(0, x, pc, Nr, Nc, XH, 0, tab + p->phi_rows_off[0], m_r, W, nullptr,
-                            one, K, p->d_tw, p->tw_n, st));
-  SCAT_TRY(scat::launch_row_lowpass(W, pc, m_r, Nc, m_c, tab + p->phi_cols_off[0], o, one, K,
-                                    p->d_tw, p->tw_n, st));
-  SCAT_TRY(scat::launch_row_fwd(XH, pc * Nr, Nc, p->d_tw, p->tw_n, st));
+  SCAT_TRY(scat::launch_tree32_input(x, pc, XH, tab + p->phi_cols_off[0], tab + p->taps_off[0], o,
+                                     K, st));
   SCAT_TRY(scat::launch_tree32(XH, pc, L, h.max_order, tab + p->psi1_off[0], tab + p->psi1_off[1],
                                tab + p->phi_cols_off[0], tab + p->phi_cols_off[1],
                                tab + p->taps_off[0], tab + p->taps_off[1], o, K, st));

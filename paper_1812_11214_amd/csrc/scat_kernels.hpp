@@ -89,6 +89,9 @@ hipError_t launch_rows_fused(const float2 *src, bool src_half, long NS, int Sr, 
 //             DFT (unnormalised) of the pre-scaled Fourier samples, 32 and 16 values
 //   out       [planes][K][8][8]; channel 0 (S0) is not written here
 bool tree_supported(int n_r, int n_c, int J);
+// x [planes][32][32] real -> xh (its unnormalised 2-D spectrum) and S0 (channel 0 of out)
+hipError_t launch_tree32_input(const float *x, long planes, float2 *xh, const float *phi_cols0,
+                               const float *taps0, float *out, int K, hipStream_t st);
 hipError_t launch_tree32(const float2 *xh, long planes, int L, int max_order, const float *psi_j0,
                          const float *psi_j1, const float *phi_cols0, const float *phi_cols1,
                          const float *taps0, const float *taps1, float *out, int K,

@@ -316,6 +316,58 @@ __device__ __forceinline__ void node_octave0(const TreeArgs &a, const float2 *xh
     small_nodes<true>(a, P1, first, chan0 + first, P2, Wl, out, lane, tp1);
 }
 
+// Spectrum and S0 of the inputs: one wavefront per plane.  Rows first (so that the
+// row-lowpassed plane is still spatial along the columns for the tap correlation), then
+// columns; writes xh [32][32] and channel 0 of the output.
+constexpr int INPUT_WAVE_LDS_BYTES = P1_ELEMS * 8 + 32 * 9 * 4;
+__global__ __launch_bounds__(64 * TREE_WAVES) void k_tree32_input(const float *__restrict__ x,
+                                                                  long planes, float2 *xh,
+                                                                  TreeArgs a) {
+  extern __shared__ float2 smem[];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));
+  const long p = static_cast<long>(blockIdx.x) * TREE_WAVES + wave;
+  if (p >= planes) return;
+  float2 *P1 = smem + static_cast<size_t>(wave) * (INPUT_WAVE_LDS_BYTES / 8);
+  float *Wl = reinterpret_cast<float *>(P1 + P1_ELEMS);
+  const int tp = lane & 1, q = lane >> 1;
+  PairTw pw;
+  pair_twiddles(pw, tp);
+  const float *xp = x + p * 1024;
+  float2 v[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) v[i] = make_float2(xp[q * 32 + tp + 2 * i], 0.f);
+  fft32_pair<false>(v, tp, pw);
+#pragma unroll
+  for (int i = 0; i < 16; ++i) P1[q * P1_STRIDE + tp + 2 * i] = v[i];
+  float2 f4[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) f4[j] = make_float2(0.f, 0.f);
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const float ph = a.phi_cols0[tp + 2 * i];
+    f4[i & 3].x += v[i].x * ph;
+    f4[i & 3].y += v[i].y * ph;
+  }
+  idft8_pair(f4, tp);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) Wl[q * 9 + tp + 2 * j] = f4[j].x;
+  wave_sync();
+  {
+    const int n = lane >> 3, nc = lane & 7;
+    float acc = 0.f;
+#pragma unroll
+    for (int r = 0; r < 32; ++r) acc += a.taps0[(4 * n - r) & 31] * Wl[r * 9 + nc];
+    a.out[p * a.K * 64 + lane] = acc;
+  }
+#pragma unroll
+  for (int i = 0; i < 16; ++i) v[i] = P1[(tp + 2 * i) * P1_STRIDE + q];
+  fft32_pair<false>(v, tp, pw);
+  float2 *xo = xh + p * 1024;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) xo[(tp + 2 * i) * 32 + q] = v[i];
+}
+
 __global__ __launch_bounds__(64 * TREE_WAVES) void k_tree32(TreeArgs a) {
   extern __shared__ float2 smem[];
   const int lane = threadIdx.x & 63;
@@ -343,6 +395,20 @@ __global__ __launch_bounds__(64 * TREE_WAVES) void k_tree32(TreeArgs a) {
 }  // namespace
 
 bool tree_supported(int n_r, int n_c, int J) { return n_r == 32 && n_c == 32 && J == 2; }
+
+hipError_t launch_tree32_input(const float *x, long planes, float2 *xh, const float *phi_cols0,
+                               const float *taps0, float *out, int K, hipStream_t st) {
+  if (planes <= 0) return hipSuccess;
+  const long blocks = (planes + TREE_WAVES - 1) / TREE_WAVES;
+  if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
+  TreeArgs a{xh, planes, 0, 1, K, nullptr, nullptr, phi_cols0, nullptr, taps0, nullptr, out};
+  const double bytes = planes * (1024.0 * 4 + 1024.0 * 8 + 64.0 * 4);
+  const double flops = planes * 64.0 * 5.0 * 32 * 5;
+  LaunchScope obs("k_tree32_input", bytes, flops, st);
+  hipLaunchKernelGGL(k_tree32_input, dim3(static_cast<unsigned>(blocks)), dim3(64 * TREE_WAVES),
+                     static_cast<size_t>(INPUT_WAVE_LDS_BYTES) * TREE_WAVES, st, x, planes, xh, a);
+  return hipGetLastError();
+}
 
 hipError_t launch_tree32(const float2 *xh, long planes, int L, int max_order, const float *psi_j0,
                          const float *psi_j1, const float *phi_cols0, const float *phi_cols1,
