@@ -192,8 +192,9 @@ def test_stream_and_plan_independence():
 
 def test_timing_api():
     import torch
-    x = torch.from_numpy(workloads.planes(0, 4)).cuda()
-    plan = scat.Scattering((32, 32), 2, 8)
+    rng = np.random.default_rng(11)
+    x = torch.from_numpy(rng.standard_normal((4, 64, 64)).astype(np.float32)).cuda()
+    plan = scat.Scattering((64, 64), 3, 4)
     try:
         plan.forward(x)
         plan.timing_begin(None)
