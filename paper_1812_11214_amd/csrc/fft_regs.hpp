@@ -112,6 +112,30 @@ struct DftRegs<16, INV> {
   }
 };
 
+template <bool INV>
+struct DftRegs<32, INV> {
+  // even and odd samples as two 16-point transforms: X[k] = E[k] + w32^k O[k],
+  // X[k + 16] = E[k] - w32^k O[k]
+  static __device__ __forceinline__ void run(float2 (&v)[32]) {
+    constexpr float C[16] = {1.00000000000000000000f, 0.98078528040323043058f, 0.92387953251128673848f, 0.83146961230254523567f, 0.70710678118654757274f, 0.55557023301960228867f, 0.38268343236508983729f, 0.19509032201612833135f, 0.00000000000000006123f, -0.19509032201612819257f, -0.38268343236508972627f, -0.55557023301960195560f, -0.70710678118654746172f, -0.83146961230254534669f, -0.92387953251128673848f, -0.98078528040323043058f};
+    constexpr float S[16] = {0.00000000000000000000f, 0.19509032201612824808f, 0.38268343236508978178f, 0.55557023301960217765f, 0.70710678118654746172f, 0.83146961230254523567f, 0.92387953251128673848f, 0.98078528040323043058f, 1.00000000000000000000f, 0.98078528040323043058f, 0.92387953251128673848f, 0.83146961230254545772f, 0.70710678118654757274f, 0.55557023301960217765f, 0.38268343236508989280f, 0.19509032201612860891f};
+    float2 e[16], o[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      e[i] = v[2 * i];
+      o[i] = v[2 * i + 1];
+    }
+    DftRegs<16, INV>::run(e);
+    DftRegs<16, INV>::run(o);
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      const float2 t = k == 0 ? o[0] : c_mulc<INV>(o[k], C[k], -S[k]);
+      v[k] = c_add(e[k], t);
+      v[k + 16] = c_sub(e[k], t);
+    }
+  }
+};
+
 // Twiddles of thread t for an N = E*T point transform: wt[k1] = exp(-2 pi i t k1 / N),
 // taken from the table tw[j] = exp(-2 pi i j / tw_n) (N divides tw_n).
 template <int E, int T>

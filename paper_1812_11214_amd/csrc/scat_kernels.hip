@@ -195,6 +195,169 @@ __global__ void k_mulfold_invrow(const float2 *__restrict__ src, const float *__
 }
 
 // ------------------------------------------------------------------------------------
+// Forward row FFT in place, transform in registers (rows of E*T points, T lanes per row).
+template <int E, int T>
+__global__ __launch_bounds__(E == 32 ? 128 : 256) void k_row_fwd_reg(float2 *__restrict__ data,
+                                                                     long rows,
+                                                                     const float2 *__restrict__ tw,
+                                                                     int tw_n) {
+  constexpr int NT = E == 32 ? 128 : 256;
+  constexpr int RPB = NT / T, M = E * T;
+  extern __shared__ float2 lds[];
+  const int rl = threadIdx.x / T, t = threadIdx.x % T;
+  const long row = static_cast<long>(blockIdx.x) * RPB + rl;
+  const bool valid = row < rows;
+  float2 *p = data + static_cast<size_t>(valid ? row : 0) * M + t;
+  float2 v[E];
+#pragma unroll
+  for (int i = 0; i < E; ++i) v[i] = valid ? p[T * i] : make_float2(0.f, 0.f);
+  float2 wt[E];
+  load_twiddles<E, T>(wt, t, tw, tw_n);
+  fft_core<E, T, false, true>(v, t, lds + rl * (E * (T + 1)), T + 1, 1, wt);
+  if (!valid) return;
+#pragma unroll
+  for (int i = 0; i < E; ++i) p[T * i] = v[i];
+}
+
+// ------------------------------------------------------------------------------------
+// k_mulfold_invrow with the transform in registers (output rows of E*T points, T lanes per
+// row, only wave-level synchronisation).  Same contract; `rows` is the number of output rows
+// per XCD (see below), lgMr = log2(Mr).
+template <int E, int T, bool MULTI>
+__global__ __launch_bounds__(E == 32 ? 128 : 256) void k_mulfold_reg(
+    const float2 *__restrict__ src, const float *__restrict__ filt, float2 *__restrict__ dst,
+    long rows, int F, int Sr, int Sc, int fr, int fc, int lgMr, int post_tw_m,
+    const float2 *__restrict__ tw, int tw_n) {
+  constexpr int NT = E == 32 ? 128 : 256;
+  constexpr int RPB = NT / T, M = E * T;
+  extern __shared__ float2 lds[];
+  const int rl = threadIdx.x / T, t = threadIdx.x % T;
+  // Workgroups go round-robin to the 8 XCDs, each with its own L2.  XCD x takes the output
+  // rows qr in [x Mr/8, (x+1) Mr/8) of every source, so it only ever reads its own eighth of
+  // the filter tables (which then stays in its L2) and of every source.  Within an XCD rows
+  // are numbered filter-fastest: the lane groups of a wave that work on the same output row
+  // of different filters load the same source addresses (one fetch per wave).
+  // `rows` = rows per XCD = S * (Mr/8) * F when lgMr >= 3, else all rows (no split).
+  const bool split = lgMr >= 3;
+  const int xcd = split ? static_cast<int>(blockIdx.x & 7) : 0;
+  const long blk = split ? static_cast<long>(blockIdx.x >> 3) : static_cast<long>(blockIdx.x);
+  const int lgQ = split ? lgMr - 3 : lgMr;
+  const long row_raw = blk * RPB + rl;
+  const bool valid = row_raw < rows;
+  const long row = valid ? row_raw : rows - 1;  // idle groups redo the last row, unstored
+  const int Mr = 1 << lgMr;
+  const long sq = row / F;  // source * (rows of this XCD) + output row within the XCD's range
+  const int f_idx = static_cast<int>(row - sq * F);
+  const long s_idx = sq >> lgQ;
+  const int qr = (xcd << lgQ) + static_cast<int>(sq & ((1 << lgQ) - 1));
+  float2 v[E];
+  const int nfr = 1 << fr, nfc = 1 << fc;
+  if (M >= 64) {
+    // Rows of 64 points and more: the whole wave accumulates one row at a time (a lane owns
+    // M/64 consecutive columns, so source and filter reads are contiguous across the wave),
+    // parks it in the row's exchange area, and the T lanes of the row pick it up from there.
+    constexpr int CPL = M >= 64 ? M / 64 : 1;
+    constexpr int RW = 64 / T;  // rows per wave
+    constexpr int XS = E * (T + 1);
+    const int lane = threadIdx.x & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));
+    float2 *xw = lds + wv * RW * XS;
+    const long row0 = blk * RPB + wv * RW;
+    // Rows are numbered filter-fastest, so a run of consecutive rows shares its source
+    // row: with MULTI up to FB filters are accumulated at once from one read of the source
+    // values (pays off for rows of 128 points and more and several filters; measured).
+    constexpr int FB = !MULTI ? 1 : CPL == 1 ? 4 : CPL == 2 ? 8 : CPL == 4 ? 4 : 2;
+    for (int r = 0; r < RW;) {
+      long rr = row0 + r;
+      if (rr >= rows) rr = rows - 1;
+      const long sq_r = rr / F;
+      const int f_r = static_cast<int>(rr - sq_r * F);
+      int n = F - f_r;
+      if (n > RW - r) n = RW - r;
+      if (n > FB) n = FB;
+      const long s_r = sq_r >> lgQ;
+      const int q_r = (xcd << lgQ) + static_cast<int>(sq_r & ((1 << lgQ) - 1));
+      const float2 *sp = src + static_cast<size_t>(s_r) * Sr * Sc + lane * CPL;
+      const size_t fstride = static_cast<size_t>(Sr) * Sc;
+      const float *fp = filt + static_cast<size_t>(f_r) * fstride + lane * CPL;
+      float2 acc[FB][CPL];
+#pragma unroll
+      for (int j = 0; j < FB; ++j)
+#pragma unroll
+        for (int e = 0; e < CPL; ++e) acc[j][e] = make_float2(0.f, 0.f);
+      for (int a = 0; a < nfr; ++a) {
+        const size_t ro = static_cast<size_t>(q_r + a * Mr) * Sc;
+#pragma unroll 2
+        for (int b = 0; b < nfc; ++b) {
+          const size_t o = ro + static_cast<size_t>(b) * M;
+          float2 x[CPL];
+#pragma unroll
+          for (int e = 0; e < CPL; ++e) x[e] = sp[o + e];
+#pragma unroll
+          for (int j = 0; j < FB; ++j) {
+            // filters past the run repeat its last one (loaded, not stored)
+            const float *fj = fp + static_cast<size_t>(j < n ? j : n - 1) * fstride;
+#pragma unroll
+            for (int e = 0; e < CPL; ++e) {
+              const float f = fj[o + e];
+              acc[j][e].x += x[e].x * f;
+              acc[j][e].y += x[e].y * f;
+            }
+          }
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < FB; ++j)
+        if (j < n) {
+#pragma unroll
+          for (int e = 0; e < CPL; ++e) xw[(r + j) * XS + lane * CPL + e] = acc[j][e];
+        }
+      r += n;
+    }
+    wave_sync();
+#pragma unroll
+    for (int i = 0; i < E; ++i) v[i] = xw[(lane / T) * XS + t + T * i];
+    wave_sync();
+  } else {
+    const float2 *sp = src + static_cast<size_t>(s_idx) * Sr * Sc + t;
+    const float *fp = filt + static_cast<size_t>(f_idx) * Sr * Sc + t;
+#pragma unroll
+    for (int i = 0; i < E; ++i) v[i] = make_float2(0.f, 0.f);
+    for (int a = 0; a < nfr; ++a) {
+      const size_t ro = static_cast<size_t>(qr + a * Mr) * Sc;
+      for (int b = 0; b < nfc; ++b) {
+        const size_t o = ro + static_cast<size_t>(b) * M;
+#pragma unroll
+        for (int i = 0; i < E; ++i) {
+          const float2 x = sp[o + T * i];
+          const float f = fp[o + T * i];
+          v[i].x += x.x * f;
+          v[i].y += x.y * f;
+        }
+      }
+    }
+  }
+  float2 wt[E];
+  load_twiddles<E, T>(wt, t, tw, tw_n);
+  fft_core<E, T, true, true>(v, t, lds + rl * (E * (T + 1)), T + 1, 1, wt);
+  if (!valid) return;
+  float2 *dp = dst + ((static_cast<size_t>(s_idx) * F + f_idx) * Mr + qr) * M + t;
+  if (post_tw_m > 0) {
+    const int step = tw_n / post_tw_m;
+#pragma unroll
+    for (int i = 0; i < E; ++i) {
+      const int e = static_cast<int>((static_cast<long long>(qr) * (t + T * i)) & (post_tw_m - 1));
+      float2 w = tw[e * step];
+      w.y = -w.y;
+      dp[T * i] = cmul(v[i], w);
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < E; ++i) dp[T * i] = v[i];
+  }
+}
+
+// ------------------------------------------------------------------------------------
 // Column pass on a tile of TC columns of one node ([Mr][Mc] plane).
 // MODE 0: src real; forward column FFT.
 // MODE 1: src complex; inverse column FFT, modulus, forward column FFT.
@@ -1169,6 +1332,52 @@ int pow2_floor(int v) {
   return p;
 }
 
+template <int E, int T>
+hipError_t launch_mulfold_reg_t(const float2 *src, const float *filt, float2 *dst, long S, int F,
+                                int Sr, int Sc, int fr, int fc, int post_tw_m, const float2 *tw,
+                                int tw_n, hipStream_t st) {
+  constexpr int NT = E == 32 ? 128 : 256, RPB = NT / T;
+  const int Mr = Sr >> fr, Mc = Sc >> fc;
+  int lgMr = 0;
+  while ((1 << lgMr) < Mr) ++lgMr;
+  const bool split = lgMr >= 3;  // one eighth of the output rows per XCD (see the kernel)
+  const long rows = split ? S * F * (Mr / 8) : S * F * Mr;
+  const long blocks = ((rows + RPB - 1) / RPB) * (split ? 8 : 1);
+  if (rows <= 0 || blocks > 0x7fffffffL || tw_n % (E * T) != 0) return hipErrorInvalidValue;
+  if (post_tw_m > 0 && (tw_n % post_tw_m != 0 || (post_tw_m & (post_tw_m - 1)) != 0))
+    return hipErrorInvalidValue;
+  const size_t lds = T == 1 ? 0 : static_cast<size_t>(RPB) * E * (T + 1) * sizeof(float2);
+  const double spts = static_cast<double>(S) * Sr * Sc, opts = static_cast<double>(S) * F * Mr * Mc;
+  const bool multi = F >= 2 && E * T >= 64;
+  const std::string name = "k_mulfold_reg<" + std::to_string(E) + ", " + std::to_string(T) +
+                           (multi ? ", true>" : ", false>");
+  Observe ob(name.c_str(), spts * 8 + static_cast<double>(F) * Sr * Sc * 4 + opts * 8,
+             static_cast<double>(S) * F * Mr * fft_flops(Mc) + 4.0 * spts * F, st);
+  if (multi)
+    hipLaunchKernelGGL((k_mulfold_reg<E, T, (E * T >= 64)>), dim3(static_cast<unsigned>(blocks)),
+                       dim3(NT), lds, st, src, filt, dst, rows, F, Sr, Sc, fr, fc, lgMr, post_tw_m,
+                       tw, tw_n);
+  else
+    hipLaunchKernelGGL((k_mulfold_reg<E, T, false>), dim3(static_cast<unsigned>(blocks)), dim3(NT),
+                       lds, st, src, filt, dst, rows, F, Sr, Sc, fr, fc, lgMr, post_tw_m, tw, tw_n);
+  return hipGetLastError();
+}
+
+template <int E, int T>
+hipError_t launch_row_fwd_reg_t(float2 *data, long rows, const float2 *tw, int tw_n,
+                                hipStream_t st) {
+  constexpr int NT = E == 32 ? 128 : 256, RPB = NT / T;
+  const long blocks = (rows + RPB - 1) / RPB;
+  if (rows <= 0 || blocks > 0x7fffffffL || tw_n % (E * T) != 0) return hipErrorInvalidValue;
+  const size_t lds = T == 1 ? 0 : static_cast<size_t>(RPB) * E * (T + 1) * sizeof(float2);
+  const std::string name = "k_row_fwd_reg<" + std::to_string(E) + ", " + std::to_string(T) + ">";
+  Observe ob(name.c_str(), static_cast<double>(rows) * E * T * 16,
+             static_cast<double>(rows) * fft_flops(E * T), st);
+  hipLaunchKernelGGL((k_row_fwd_reg<E, T>), dim3(static_cast<unsigned>(blocks)), dim3(NT), lds, st,
+                     data, rows, tw, tw_n);
+  return hipGetLastError();
+}
+
 }  // namespace
 
 // ----------------------------------------------------------------------------- launchers
@@ -1179,6 +1388,22 @@ hipError_t launch_mulfold_invrow(const float2 *src, const float *filt, float2 *d
                                  int Sr, int Sc, int fr, int fc, int post_tw_m, const float2 *tw,
                                  int tw_n, hipStream_t st) {
   const int Mr = Sr >> fr, Mc = Sc >> fc;
+#define SCAT_MF(E_, T_) \
+  return launch_mulfold_reg_t<E_, T_>(src, filt, dst, S, F, Sr, Sc, fr, fc, post_tw_m, tw, tw_n, st)
+  if (S > 0 && F > 0 && Mr >= 1) {
+    switch (Mc) {
+      case 4: SCAT_MF(4, 1);
+      case 8: SCAT_MF(8, 1);
+      case 16: SCAT_MF(16, 1);
+      case 32: SCAT_MF(16, 2);
+      case 64: SCAT_MF(16, 4);
+      case 128: SCAT_MF(16, 8);
+      case 256: SCAT_MF(16, 16);
+      case 512: SCAT_MF(32, 16);
+      default: break;
+    }
+  }
+#undef SCAT_MF
   int RB = pow2_floor(kTileElems / Mc);
   if (RB > Mr) RB = Mr;
   if (RB < 1) return hipErrorInvalidValue;
@@ -1247,6 +1472,15 @@ hipError_t launch_col(int mode, const void *src, long nodes, int Mr, int Mc, flo
 
 hipError_t launch_row_fwd(float2 *data, long rows, int Mc, const float2 *tw, int tw_n,
                           hipStream_t st) {
+  switch (Mc) {
+    case 16: return launch_row_fwd_reg_t<16, 1>(data, rows, tw, tw_n, st);
+    case 32: return launch_row_fwd_reg_t<16, 2>(data, rows, tw, tw_n, st);
+    case 64: return launch_row_fwd_reg_t<16, 4>(data, rows, tw, tw_n, st);
+    case 128: return launch_row_fwd_reg_t<16, 8>(data, rows, tw, tw_n, st);
+    case 256: return launch_row_fwd_reg_t<16, 16>(data, rows, tw, tw_n, st);
+    case 512: return launch_row_fwd_reg_t<32, 16>(data, rows, tw, tw_n, st);
+    default: break;
+  }
   int RB = pow2_floor(kTileElems / Mc);
   while (RB > 1 && rows % RB != 0) RB >>= 1;
   if (RB < 1) return hipErrorInvalidValue;
