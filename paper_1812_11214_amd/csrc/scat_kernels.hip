@@ -252,13 +252,17 @@ __global__ __launch_bounds__(E == 32 ? 128 : 256) void k_mulfold_reg(
   const int qr = (xcd << lgQ) + static_cast<int>(sq & ((1 << lgQ) - 1));
   float2 v[E];
   const int nfr = 1 << fr, nfc = 1 << fc;
-  if (M >= 64) {
-    // Rows of 64 points and more: the whole wave accumulates one row at a time (a lane owns
-    // M/64 consecutive columns, so source and filter reads are contiguous across the wave),
-    // parks it in the row's exchange area, and the T lanes of the row pick it up from there.
+  if (M >= 64 || (M >= 32 && Sc >= 64)) {
+    // The whole wave accumulates one row at a time, reading the source row W = max(M, 64)
+    // contiguous columns per step (a lane owns M/64 consecutive columns, or one column when
+    // M < 64; then the 64/M lanes that hold the same output column are summed by lane
+    // exchange).  So source and filter reads are contiguous across the wave.  The row is
+    // parked in its exchange area, where the T lanes of the row pick it up.
     constexpr int CPL = M >= 64 ? M / 64 : 1;
+    constexpr int W = M >= 64 ? M : 64;
     constexpr int RW = 64 / T;  // rows per wave
-    constexpr int XS = E * (T + 1);
+    constexpr int XS = T == 1 ? E : E * (T + 1);
+    const int nsteps = Sc / W;
     const int lane = threadIdx.x & 63;
     const int wv = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));
     float2 *xw = lds + wv * RW * XS;
@@ -288,8 +292,8 @@ __global__ __launch_bounds__(E == 32 ? 128 : 256) void k_mulfold_reg(
       for (int a = 0; a < nfr; ++a) {
         const size_t ro = static_cast<size_t>(q_r + a * Mr) * Sc;
 #pragma unroll 2
-        for (int b = 0; b < nfc; ++b) {
-          const size_t o = ro + static_cast<size_t>(b) * M;
+        for (int b = 0; b < nsteps; ++b) {
+          const size_t o = ro + static_cast<size_t>(b) * W;
           float2 x[CPL];
 #pragma unroll
           for (int e = 0; e < CPL; ++e) x[e] = sp[o + e];
@@ -306,12 +310,23 @@ __global__ __launch_bounds__(E == 32 ? 128 : 256) void k_mulfold_reg(
           }
         }
       }
+      if (M < 64) {
 #pragma unroll
-      for (int j = 0; j < FB; ++j)
-        if (j < n) {
+        for (int j = 0; j < FB; ++j)
 #pragma unroll
-          for (int e = 0; e < CPL; ++e) xw[(r + j) * XS + lane * CPL + e] = acc[j][e];
-        }
+          for (int d = M; d < 64; d <<= 1) {
+            acc[j][0].x += __shfl_xor(acc[j][0].x, d);
+            acc[j][0].y += __shfl_xor(acc[j][0].y, d);
+          }
+      }
+      if (lane * CPL < M) {
+#pragma unroll
+        for (int j = 0; j < FB; ++j)
+          if (j < n) {
+#pragma unroll
+            for (int e = 0; e < CPL; ++e) xw[(r + j) * XS + lane * CPL + e] = acc[j][e];
+          }
+      }
       r += n;
     }
     wave_sync();
@@ -319,6 +334,8 @@ __global__ __launch_bounds__(E == 32 ? 128 : 256) void k_mulfold_reg(
     for (int i = 0; i < E; ++i) v[i] = xw[(lane / T) * XS + t + T * i];
     wave_sync();
   } else {
+    // short rows (the per-row cost of the wave-wide scheme outweighs its coalescing;
+    // measured) or sources narrower than a wave: the T lanes of a row gather directly
     const float2 *sp = src + static_cast<size_t>(s_idx) * Sr * Sc + t;
     const float *fp = filt + static_cast<size_t>(f_idx) * Sr * Sc + t;
 #pragma unroll
@@ -339,7 +356,7 @@ __global__ __launch_bounds__(E == 32 ? 128 : 256) void k_mulfold_reg(
   }
   float2 wt[E];
   load_twiddles<E, T>(wt, t, tw, tw_n);
-  fft_core<E, T, true, true>(v, t, lds + rl * (E * (T + 1)), T + 1, 1, wt);
+  fft_core<E, T, true, true>(v, t, lds + rl * (T == 1 ? E : E * (T + 1)), T + 1, 1, wt);
   if (!valid) return;
   float2 *dp = dst + ((static_cast<size_t>(s_idx) * F + f_idx) * Mr + qr) * M + t;
   if (post_tw_m > 0) {
@@ -522,10 +539,11 @@ __global__ void k_row_lowpass(const float *__restrict__ w, int m_r, int Mc, int 
 template <int MR, int MODE, int LM_R>
 __global__ __launch_bounds__(256) void k_col_fast(const void *__restrict__ src_v, int Mc, int TC,
                                                   float2 *__restrict__ uc, int uc_half,
+                                                  int post_tw_m,
                                                   const float *__restrict__ phi_rows, int m_r,
                                                   float *__restrict__ w_out,
                                                   const float2 *__restrict__ tw, int tw_n) {
-  constexpr int E = 16, T = MR / 16;
+  constexpr int E = MR > 256 ? 32 : 16, T = MR / E;
   extern __shared__ float2 lds[];
   const int KS = T * TC + 16;
   const int c = threadIdx.x % TC, t = threadIdx.x / TC;
@@ -559,6 +577,15 @@ __global__ __launch_bounds__(256) void k_col_fast(const void *__restrict__ src_v
 #pragma unroll
       for (int i = 0; i < E; ++i)
         if (t + T * i <= MR / 2) nt_store(up + i * step, v[i]);
+    } else if (post_tw_m > 0) {
+      // four-step forward: times exp(-2 pi i k_r c / post_tw_m), k_r = t + T i, c the column
+      float2 *up = uc + plane + off0;
+      const int tstep = tw_n / post_tw_m;
+#pragma unroll
+      for (int i = 0; i < E; ++i) {
+        const int e = static_cast<int>((static_cast<long long>(t + T * i) * (c0 + c)) & (post_tw_m - 1));
+        up[i * step] = cmul(v[i], tw[e * tstep]);
+      }
     } else {
       float2 *up = uc + plane + off0;
 #pragma unroll
@@ -633,9 +660,11 @@ __global__ __launch_bounds__(256) void k_col_fast(const void *__restrict__ src_v
 
 template <int MR>
 hipError_t launch_col_fast_t(int mode, const void *src, long nodes, int Mc, float2 *uc, bool uc_half,
-                             const float *phi_rows, int m_r, float *w_out, const float2 *tw,
-                             int tw_n, hipStream_t st) {
-  constexpr int T = MR / 16;
+                             int post_tw_m, const float *phi_rows, int m_r, float *w_out,
+                             const float2 *tw, int tw_n, hipStream_t st) {
+  constexpr int E = MR > 256 ? 32 : 16, T = MR / E;
+  if (post_tw_m > 0 && (uc_half || tw_n % post_tw_m != 0 || (post_tw_m & (post_tw_m - 1)) != 0))
+    return hipErrorInvalidValue;
   int TC = 256 / T;
   if (TC < 16) TC = 16;
   if (TC > Mc) TC = Mc;
@@ -643,7 +672,7 @@ hipError_t launch_col_fast_t(int mode, const void *src, long nodes, int Mc, floa
   if (blocks <= 0 || blocks > 0x7fffffffL) return hipErrorInvalidValue;
   // lowpass tail variant: registers when the lowpass length is 32 or 8 and a multiple of T
   const int lm = (w_out && m_r == 32 && T <= 32 && tw_n >= 32) ? 32 : (w_out && m_r == 8 && T <= 8) ? 8 : 0;
-  size_t words = static_cast<size_t>(16) * (T * TC + 16);
+  size_t words = static_cast<size_t>(E) * (T * TC + 16);
   if (lm == 0 && w_out) words += static_cast<size_t>(m_r) * TC;
   if (lm == 32 && static_cast<size_t>(80) * TC > words) words = static_cast<size_t>(80) * TC;
   size_t lds = words * sizeof(float2);
@@ -660,16 +689,25 @@ hipError_t launch_col_fast_t(int mode, const void *src, long nodes, int Mc, floa
                  (mode ? 4.0 * pts : 0),
              st);
 #define SCAT_COL_LAUNCH(MODE_, LM_)                                                               \
-  hipLaunchKernelGGL((k_col_fast<MR, MODE_, LM_>), g, b, lds, st, src, Mc, TC, uc,                \
-                     static_cast<int>(uc_half), phi_rows, m_r, w_out, tw, tw_n)
+  {                                                                                               \
+    static bool attr_done = false;                                                                \
+    if (lds > 65536 && !attr_done) {                                                              \
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_col_fast<MR, MODE_, LM_>), \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024); \
+      if (e != hipSuccess) return e;                                                              \
+      attr_done = true;                                                                           \
+    }                                                                                             \
+    hipLaunchKernelGGL((k_col_fast<MR, MODE_, LM_>), g, b, lds, st, src, Mc, TC, uc,              \
+                       static_cast<int>(uc_half), post_tw_m, phi_rows, m_r, w_out, tw, tw_n);     \
+  }
   if (mode == 0) {
-    if (lm == 32) SCAT_COL_LAUNCH(0, 32);
-    else if (lm == 8) SCAT_COL_LAUNCH(0, (MR <= 128 ? 8 : 0));
-    else SCAT_COL_LAUNCH(0, 0);
+    if (lm == 32) SCAT_COL_LAUNCH(0, 32)
+    else if (lm == 8) SCAT_COL_LAUNCH(0, (MR <= 128 ? 8 : 0))
+    else SCAT_COL_LAUNCH(0, 0)
   } else {
-    if (lm == 32) SCAT_COL_LAUNCH(1, 32);
-    else if (lm == 8) SCAT_COL_LAUNCH(1, (MR <= 128 ? 8 : 0));
-    else SCAT_COL_LAUNCH(1, 0);
+    if (lm == 32) SCAT_COL_LAUNCH(1, 32)
+    else if (lm == 8) SCAT_COL_LAUNCH(1, (MR <= 128 ? 8 : 0))
+    else SCAT_COL_LAUNCH(1, 0)
   }
 #undef SCAT_COL_LAUNCH
   return hipGetLastError();
@@ -1346,15 +1384,15 @@ hipError_t launch_mulfold_reg_t(const float2 *src, const float *filt, float2 *ds
   if (rows <= 0 || blocks > 0x7fffffffL || tw_n % (E * T) != 0) return hipErrorInvalidValue;
   if (post_tw_m > 0 && (tw_n % post_tw_m != 0 || (post_tw_m & (post_tw_m - 1)) != 0))
     return hipErrorInvalidValue;
-  const size_t lds = T == 1 ? 0 : static_cast<size_t>(RPB) * E * (T + 1) * sizeof(float2);
+  const size_t lds = static_cast<size_t>(RPB) * (T == 1 ? E : E * (T + 1)) * sizeof(float2);
   const double spts = static_cast<double>(S) * Sr * Sc, opts = static_cast<double>(S) * F * Mr * Mc;
-  const bool multi = F >= 2 && E * T >= 64;
+  const bool multi = F >= 2 && (E * T >= 64 || (E * T >= 32 && Sc >= 64));
   const std::string name = "k_mulfold_reg<" + std::to_string(E) + ", " + std::to_string(T) +
                            (multi ? ", true>" : ", false>");
   Observe ob(name.c_str(), spts * 8 + static_cast<double>(F) * Sr * Sc * 4 + opts * 8,
              static_cast<double>(S) * F * Mr * fft_flops(Mc) + 4.0 * spts * F, st);
   if (multi)
-    hipLaunchKernelGGL((k_mulfold_reg<E, T, (E * T >= 64)>), dim3(static_cast<unsigned>(blocks)),
+    hipLaunchKernelGGL((k_mulfold_reg<E, T, true>), dim3(static_cast<unsigned>(blocks)),
                        dim3(NT), lds, st, src, filt, dst, rows, F, Sr, Sc, fr, fc, lgMr, post_tw_m,
                        tw, tw_n);
   else
@@ -1424,12 +1462,14 @@ hipError_t launch_col(int mode, const void *src, long nodes, int Mr, int Mc, flo
   if (uc_half && (mode == 2 || post_tw_m != 0 || Mr < 2)) return hipErrorInvalidValue;
   // register-resident variant: modes 0/1, no four-step twiddle, column length 16*T with
   // T | 16, at least 16 columns, lowpass length dividing the column length
-  if (mode != 2 && post_tw_m == 0 && Mc >= 16 && (w_out == nullptr || (m_r >= 1 && m_r <= Mr))) {
+  if (mode != 2 && Mc >= 16 && tw_n % Mr == 0 && (post_tw_m == 0 || !uc_half) &&
+      (w_out == nullptr || (m_r >= 1 && m_r <= Mr))) {
     switch (Mr) {
-      case 32: return launch_col_fast_t<32>(mode, src, nodes, Mc, uc, uc_half, phi_rows, m_r, w_out, tw, tw_n, st);
-      case 64: return launch_col_fast_t<64>(mode, src, nodes, Mc, uc, uc_half, phi_rows, m_r, w_out, tw, tw_n, st);
-      case 128: return launch_col_fast_t<128>(mode, src, nodes, Mc, uc, uc_half, phi_rows, m_r, w_out, tw, tw_n, st);
-      case 256: return launch_col_fast_t<256>(mode, src, nodes, Mc, uc, uc_half, phi_rows, m_r, w_out, tw, tw_n, st);
+      case 32: return launch_col_fast_t<32>(mode, src, nodes, Mc, uc, uc_half, post_tw_m, phi_rows, m_r, w_out, tw, tw_n, st);
+      case 64: return launch_col_fast_t<64>(mode, src, nodes, Mc, uc, uc_half, post_tw_m, phi_rows, m_r, w_out, tw, tw_n, st);
+      case 128: return launch_col_fast_t<128>(mode, src, nodes, Mc, uc, uc_half, post_tw_m, phi_rows, m_r, w_out, tw, tw_n, st);
+      case 256: return launch_col_fast_t<256>(mode, src, nodes, Mc, uc, uc_half, post_tw_m, phi_rows, m_r, w_out, tw, tw_n, st);
+      case 512: return launch_col_fast_t<512>(mode, src, nodes, Mc, uc, uc_half, post_tw_m, phi_rows, m_r, w_out, tw, tw_n, st);
       default: break;
     }
   }
