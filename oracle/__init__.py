@@ -7,4 +7,5 @@ product.
 """
 from .filters import bank_1d, bank_2d  # noqa: F401
 from .scattering import (coeff_index_1d, coeff_index_2d, scattering1d,  # noqa: F401
-                         scattering1d_plain, scattering2d, scattering2d_plain)
+                         scattering1d_plain, scattering2d, scattering2d_backward,
+                         scattering2d_plain)

@@ -122,6 +122,75 @@ def scattering2d(x, J, L, max_order=2, bank=None):
     return np.stack(out, axis=len(lead))
 
 
+def tile(G, r, axes):
+    """Adjoint of ``fold``: repeat G 2^r times along each of `axes` (periodic extension of
+    a spectrum of M points to N = 2^r M points)."""
+    reps = [1] * G.ndim
+    for ax in axes:
+        reps[ax % G.ndim] = 1 << r
+    return np.tile(G, reps)
+
+
+def scattering2d_backward(x, g, J, L, max_order=2, bank=None):
+    """Gradient of sum(g * scattering2d(x)) with respect to x (vector-Jacobian product).
+
+    The cascade is a chain of real-linear maps and complex moduli, so its transpose is the
+    chain of adjoints in reverse order (section 3 of the paper relies on this chain being
+    differentiable; it gives no formulas).  With the real inner product Re<a, b>:
+    adjoint of fft2 = n * ifft2, of ifft2 = fft2 / n (n = number of grid points), of
+    ``fold`` = ``tile``, of the product with a real filter = the same product, of taking
+    the real part = inclusion, and d|y| = Re(conj(y) dy) / |y|, hence g_y = g_U * y / |y|
+    (taken as 0 where y = 0).
+
+    x: (..., N_r, N_c) real; g: (..., K, N_r >> J, N_c >> J) real.  Returns (..., N_r, N_c).
+    """
+    x = np.asarray(x, dtype=np.float64)
+    g = np.asarray(g, dtype=np.float64)
+    n_r, n_c = x.shape[-2:]
+    if bank is None:
+        bank = filters.bank_2d(n_r, n_c, J, L)
+    psi_hat, phi_hat = bank['psi_hat'], bank['phi_hat']
+    ax = (-2, -1)
+    m_pts = float((n_r >> J) * (n_c >> J))
+
+    def unit(y):
+        a = np.abs(y)
+        return np.where(a > 0, y / np.where(a > 0, a, 1.0), 0.0)
+
+    def lowpass_adjoint(gs, phi_r, r):
+        # S = Re ifft2(sub(Z^ * phi, r)):  g_Z^ = tile(fft2(g_S) / m) / 4^r * phi
+        return tile(np.fft.fft2(gs) / m_pts, r, ax) / float(4 ** r) * phi_r
+
+    X = np.fft.fft2(x)
+    gX = lowpass_adjoint(g[..., 0, :, :], phi_hat, J)
+    c1 = 1
+    c2 = 1 + J * L
+    for j1 in range(J):
+        phi_j1 = fold(phi_hat, j1, ax)
+        n1 = float((n_r >> j1) * (n_c >> j1))
+        for t1 in range(L):
+            y1 = np.fft.ifft2(sub(X * psi_hat[j1, t1], j1, ax))
+            U1h = np.fft.fft2(np.abs(y1))
+            gU1h = lowpass_adjoint(g[..., c1, :, :], phi_j1, J - j1)
+            c1 += 1
+            if max_order >= 2:
+                for j2 in range(j1 + 1, J):
+                    phi_j2 = fold(phi_hat, j2, ax)
+                    n2 = float((n_r >> j2) * (n_c >> j2))
+                    for t2 in range(L):
+                        psi_r = fold(psi_hat[j2, t2], j1, ax)
+                        y2 = np.fft.ifft2(sub(U1h * psi_r, j2 - j1, ax))
+                        gVh = lowpass_adjoint(g[..., c2, :, :], phi_j2, J - j2)
+                        c2 += 1
+                        gV = (np.fft.ifft2(gVh) * n2).real
+                        gY2 = np.fft.fft2(gV * unit(y2)) / n2
+                        gU1h = gU1h + tile(gY2, j2 - j1, ax) / float(4 ** (j2 - j1)) * psi_r
+            gU1 = (np.fft.ifft2(gU1h) * n1).real
+            gY1 = np.fft.fft2(gU1 * unit(y1)) / n1
+            gX = gX + tile(gY1, j1, ax) / float(4 ** j1) * psi_hat[j1, t1]
+    return (np.fft.ifft2(gX) * float(n_r * n_c)).real
+
+
 def scattering2d_plain(x, J, L, max_order=2, bank=None):
     """The three defining equations at full resolution, sampled at 2^J n."""
     x = np.asarray(x, dtype=np.float64)
