@@ -88,6 +88,32 @@ scat_status scat_plan_create_host(scat_plan **out_plan, int dims, const int *sha
 scat_status scat_forward(scat_plan *plan, const float *in, float *out, long batch,
                          void *stream);
 
+/*
+ * Backward pass (2-D plans): the gradient of  sum(grad_out * S(in))  with respect to `in`,
+ * i.e. the transposed Jacobian of scat_forward applied to grad_out.  The paper lists
+ * differentiability as a feature of its package (section 3, "Relation to previous
+ * software") without formulas; the cascade is a chain of real-linear maps and complex
+ * moduli, and this call applies the adjoints in reverse order, with d|y| = Re(conj(y) dy)/|y|
+ * and the convention that the modulus passes no gradient where y = 0.
+ *
+ *   in        device, float32, batch x shape, as given to scat_forward.  Read only.
+ *   grad_out  device, float32, batch x K x out_shape (the layout of scat_forward's `out`).
+ *             Read only.
+ *   grad_in   device, float32, batch x shape.  Overwritten with the gradient.
+ *
+ * The forward cascade is recomputed inside the call (its outputs S are not formed) and the
+ * complex signals before every modulus are kept in the plan's scratch buffer until the
+ * call's work has run; the same one-call-in-flight rule as scat_forward applies, and the
+ * two share the scratch buffer.  Enqueues on `stream`, does not synchronise.
+ * Errors: SCAT_ERR_ARG for a 1-D plan or batch < 0; SCAT_ERR_SHAPE unless every side and
+ * every side >> (J-1) lies in 4...512 and the output grid has at most 1024 points.
+ */
+scat_status scat_backward(scat_plan *plan, const float *in, const float *grad_out,
+                          float *grad_in, long batch, void *stream);
+
+/* Bytes of device scratch a scat_backward call with this batch size uses (0 for 1-D). */
+size_t scat_plan_backward_workspace_bytes(const scat_plan *plan, long batch);
+
 /* Release a plan and its device memory.  NULL is a no-op returning SCAT_OK. */
 scat_status scat_plan_destroy(scat_plan *plan);
 

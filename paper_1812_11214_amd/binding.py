@@ -41,6 +41,10 @@ def lib():
     L.scat_plan_create_host.restype = ci
     L.scat_forward.argtypes = [vp, vp, vp, cl, vp]
     L.scat_forward.restype = ci
+    L.scat_backward.argtypes = [vp, vp, vp, vp, cl, vp]
+    L.scat_backward.restype = ci
+    L.scat_plan_backward_workspace_bytes.argtypes = [vp, cl]
+    L.scat_plan_backward_workspace_bytes.restype = ctypes.c_size_t
     L.scat_plan_destroy.argtypes = [vp]
     L.scat_plan_destroy.restype = ci
     L.scat_plan_num_coeffs.argtypes = [vp]
@@ -71,7 +75,8 @@ def lib():
 EXPORTS = ("scat_plan_create", "scat_plan_create_host", "scat_forward", "scat_plan_destroy",
            "scat_plan_num_coeffs", "scat_plan_out_shape", "scat_plan_coeff_index",
            "scat_plan_workspace_bytes", "scat_plan_filter", "scat_status_string",
-           "scat_plan_timing_begin", "scat_plan_timing_end", "scat_plan_timing_row")
+           "scat_plan_timing_begin", "scat_plan_timing_end", "scat_plan_timing_row",
+           "scat_backward", "scat_plan_backward_workspace_bytes")
 
 
 def scat_status_string(status):
@@ -126,6 +131,19 @@ def scat_plan_coeff_index(plan, c):
 
 def scat_plan_workspace_bytes(plan, batch):
     return int(lib().scat_plan_workspace_bytes(plan, int(batch)))
+
+
+def scat_plan_backward_workspace_bytes(plan, batch):
+    return int(lib().scat_plan_backward_workspace_bytes(plan, int(batch)))
+
+
+def scat_backward(plan, in_ptr, grad_out_ptr, grad_in_ptr, batch, stream_ptr=None):
+    """Enqueue the backward pass; the pointers are device addresses (ints)."""
+    st = lib().scat_backward(plan, ctypes.c_void_p(in_ptr), ctypes.c_void_p(grad_out_ptr),
+                             ctypes.c_void_p(grad_in_ptr), int(batch),
+                             ctypes.c_void_p(stream_ptr) if stream_ptr else None)
+    if st != SCAT_OK:
+        raise ScatError(st, "scat_backward")
 
 
 def scat_plan_filter(plan, kind, index, res, shape):
@@ -227,6 +245,34 @@ class Scattering:
         stream = torch.cuda.current_stream(x.device).cuda_stream
         scat_forward(self._plan, x.data_ptr(), out.data_ptr(), batch, stream)
         return out
+
+    def backward(self, x, grad_out, grad_in=None):
+        """Gradient of sum(grad_out * forward(x)) with respect to x (2-D plans)."""
+        import torch
+        for t, nm in ((x, "x"), (grad_out, "grad_out")):
+            if not (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()):
+                raise ValueError("%s must be a contiguous float32 CUDA tensor" % nm)
+        if tuple(x.shape[x.dim() - self.dims:]) != self.shape:
+            raise ValueError("trailing dims %s do not match the plan's shape %s"
+                             % (tuple(x.shape), self.shape))
+        lead = tuple(x.shape[:x.dim() - self.dims])
+        batch = 1
+        for d in lead:
+            batch *= d
+        if tuple(grad_out.shape) != lead + (self.K,) + self.out_shape:
+            raise ValueError("grad_out must have shape %s" % (lead + (self.K,) + self.out_shape,))
+        if grad_in is None:
+            grad_in = torch.empty_like(x)
+        elif not (grad_in.is_cuda and grad_in.dtype == torch.float32 and grad_in.is_contiguous()
+                  and grad_in.shape == x.shape):
+            raise ValueError("grad_in must be a contiguous float32 CUDA tensor shaped like x")
+        stream = torch.cuda.current_stream(x.device).cuda_stream
+        scat_backward(self._plan, x.data_ptr(), grad_out.data_ptr(), grad_in.data_ptr(), batch,
+                      stream)
+        return grad_in
+
+    def backward_workspace_bytes(self, batch):
+        return scat_plan_backward_workspace_bytes(self._plan, batch)
 
     def timing_begin(self, kernel_name=None):
         scat_plan_timing_begin(self._plan, kernel_name)

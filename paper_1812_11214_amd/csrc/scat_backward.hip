@@ -1,0 +1,309 @@
+// Kernels of the backward pass (gradient of <g, S(x)> with respect to x) of the 2-D
+// cascade.  The paper lists differentiability as a feature of its package (section 3,
+// "Relation to previous software") and gives no formulas; the forward cascade is a chain of
+// real-linear maps and complex moduli, so its transpose is the chain of adjoints in
+// reverse order:
+//   S = Re IFFT_m(fold(Z^ phi))   ->  g_Z^ = tile(FFT_m(g_S)) phi        (k_lowpass_adj)
+//   Z^ = FFT(Z), Z real           ->  g_Z  = Re IFFT(g_Z^)               (k_fft_* + k_modback)
+//   Z = |y|                       ->  g_y  = g_Z y / |y|  (0 at y = 0)   (k_modback)
+//   y = IFFT(fold(A^ psi))        ->  g_A^ += tile(FFT(g_y)) psi         (k_fft_* + k_tile_accum)
+// with unnormalised transforms throughout: the filter tables already carry the 1/n of the
+// forward pass, and the adjoint of a product with a real table is the same product.
+#include <hip/hip_runtime.h>
+
+#include <string>
+
+#include "fft_regs.hpp"
+#include "scat_kernels.hpp"
+
+namespace scat {
+
+namespace {
+
+__device__ __forceinline__ int chan(const ChanMap &cm, int g) {
+  return cm.base + (g / cm.inner) * cm.outer_stride + (g % cm.inner);
+}
+
+// Adjoint of the lowpass + subsampling: g_out [planes][K][m_r][m_c] real (node g of plane p
+// at channel chan(cm, g)) -> dst [node][Mr][Mc] = FFT2_m(g)[k_r mod m_r][k_c mod m_c] *
+// phi_rows[k_r] * phi_cols[k_c].  One workgroup per node; the m_r x m_c transform is two
+// dense stages in LDS (it is tiny next to the Mr x Mc plane written afterwards).
+__global__ __launch_bounds__(256) void k_lowpass_adj(const float *__restrict__ gout, ChanMap cm,
+                                                     int K, int m_r, int m_c, int lgMr, int lgMc,
+                                                     const float *__restrict__ phi_rows,
+                                                     const float *__restrict__ phi_cols,
+                                                     float2 *__restrict__ dst,
+                                                     const float2 *__restrict__ tw, int tw_n) {
+  extern __shared__ float2 lds[];
+  const int mm = m_r * m_c;
+  float2 *s1 = lds, *s2 = lds + mm;
+  float *a = reinterpret_cast<float *>(lds + 2 * mm);
+  const long node = blockIdx.x;
+  const long p = node / cm.G;
+  const int g = static_cast<int>(node - p * cm.G);
+  const float *gp = gout + (static_cast<size_t>(p) * K + chan(cm, g)) * mm;
+  for (int i = threadIdx.x; i < mm; i += blockDim.x) a[i] = gp[i];
+  __syncthreads();
+  const int sc = tw_n / m_c, sr = tw_n / m_r;
+  for (int i = threadIdx.x; i < mm; i += blockDim.x) {
+    const int r = i / m_c, kc = i - r * m_c;
+    float2 acc = make_float2(0.f, 0.f);
+    for (int b = 0; b < m_c; ++b) {
+      const float2 w = tw[((b * kc) & (m_c - 1)) * sc];
+      const float x = a[r * m_c + b];
+      acc.x += x * w.x;
+      acc.y += x * w.y;
+    }
+    s1[i] = acc;
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < mm; i += blockDim.x) {
+    const int kr = i / m_c, kc = i - kr * m_c;
+    float2 acc = make_float2(0.f, 0.f);
+    for (int r = 0; r < m_r; ++r) acc = c_add(acc, c_mul(s1[r * m_c + kc], tw[((r * kr) & (m_r - 1)) * sr]));
+    s2[i] = acc;
+  }
+  __syncthreads();
+  const int Mc = 1 << lgMc;
+  const int total = 1 << (lgMr + lgMc);
+  float2 *dp = dst + (static_cast<size_t>(node) << (lgMr + lgMc));
+  for (int i = threadIdx.x; i < total; i += blockDim.x) {
+    const int kr = i >> lgMc, kc = i & (Mc - 1);
+    const float f = phi_rows[kr] * phi_cols[kc];
+    const float2 v = s2[(kr & (m_r - 1)) * m_c + (kc & (m_c - 1))];
+    dp[i] = make_float2(v.x * f, v.y * f);
+  }
+}
+
+// a[i] = Re(a[i]) * y[i] / |y[i]|  (0 where y = 0)
+__global__ __launch_bounds__(256) void k_modback(float2 *__restrict__ a,
+                                                 const float2 *__restrict__ y, long count) {
+  const long stride = static_cast<long>(gridDim.x) * blockDim.x;
+  for (long i = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x; i < count; i += stride) {
+    const float2 v = y[i];
+    const float m2 = v.x * v.x + v.y * v.y;
+    const float s = m2 > 0.f ? a[i].x / __builtin_amdgcn_sqrtf(m2) : 0.f;
+    a[i] = make_float2(v.x * s, v.y * s);
+  }
+}
+
+__global__ __launch_bounds__(256) void k_take_real(const float2 *__restrict__ a,
+                                                   float *__restrict__ out, long count) {
+  const long stride = static_cast<long>(gridDim.x) * blockDim.x;
+  for (long i = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x; i < count; i += stride)
+    out[i] = a[i].x;
+}
+
+// dst [S][Sr][Sc] += sum_f filt[f][k_r][k_c] * G[s F + f][k_r mod Mr][k_c mod Mc]
+// (adjoint of: multiply by the F filters, fold to Mr x Mc).  One thread per element of dst.
+__global__ __launch_bounds__(256) void k_tile_accum(float2 *__restrict__ dst,
+                                                    const float *__restrict__ filt,
+                                                    const float2 *__restrict__ G, long count,
+                                                    int F, int lgSr, int lgSc, int lgMr, int lgMc) {
+  const long i = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (i >= count) return;
+  const int lgS = lgSr + lgSc;
+  const long s = i >> lgS;
+  const int e = static_cast<int>(i & ((1L << lgS) - 1));
+  const int kr = e >> lgSc, kc = e & ((1 << lgSc) - 1);
+  const int ge = ((kr & ((1 << lgMr) - 1)) << lgMc) + (kc & ((1 << lgMc) - 1));
+  const float2 *gp = G + ((static_cast<size_t>(s) * F) << (lgMr + lgMc)) + ge;
+  const float *fp = filt + e;
+  float2 acc = dst[i];
+  for (int f = 0; f < F; ++f) {
+    const float w = fp[static_cast<size_t>(f) << lgS];
+    const float2 v = gp[static_cast<size_t>(f) << (lgMr + lgMc)];
+    acc.x += v.x * w;
+    acc.y += v.y * w;
+  }
+  dst[i] = acc;
+}
+
+// In-place transform of every row of [rows][E*T] (T lanes per row, wave-level sync only).
+template <int E, int T, bool INV>
+__global__ __launch_bounds__(E == 32 ? 128 : 256) void k_fft_rows(float2 *__restrict__ data,
+                                                                  long rows,
+                                                                  const float2 *__restrict__ tw,
+                                                                  int tw_n) {
+  constexpr int NT = E == 32 ? 128 : 256;
+  constexpr int RPB = NT / T, M = E * T;
+  extern __shared__ float2 lds[];
+  const int rl = threadIdx.x / T, t = threadIdx.x % T;
+  const long row = static_cast<long>(blockIdx.x) * RPB + rl;
+  const bool valid = row < rows;
+  float2 *p = data + static_cast<size_t>(valid ? row : 0) * M + t;
+  float2 v[E];
+#pragma unroll
+  for (int i = 0; i < E; ++i) v[i] = valid ? p[T * i] : make_float2(0.f, 0.f);
+  float2 wt[E];
+  load_twiddles<E, T>(wt, t, tw, tw_n);
+  fft_core<E, T, INV, true>(v, t, lds + rl * (E * (T + 1)), T + 1, 1, wt);
+  if (!valid) return;
+#pragma unroll
+  for (int i = 0; i < E; ++i) p[T * i] = v[i];
+}
+
+// In-place transform of every column of [nodes][E*T][Mc]: a workgroup takes TC columns of
+// one node, thread (t, c) holds rows t + T i of column c.
+template <int E, int T, bool INV>
+__global__ __launch_bounds__(256) void k_fft_cols(float2 *__restrict__ data, int Mc, int TC,
+                                                  const float2 *__restrict__ tw, int tw_n) {
+  constexpr int M = E * T;
+  extern __shared__ float2 lds[];
+  const int KS = T * TC + (E == 32 ? 0 : 1);
+  const int c = threadIdx.x % TC, t = threadIdx.x / TC;
+  const int tiles = Mc / TC;
+  const long node = blockIdx.x / tiles;
+  const int c0 = static_cast<int>(blockIdx.x % tiles) * TC;
+  float2 *p = data + static_cast<size_t>(node) * M * Mc + static_cast<size_t>(t) * Mc + c0 + c;
+  const size_t step = static_cast<size_t>(T) * Mc;
+  float2 v[E];
+#pragma unroll
+  for (int i = 0; i < E; ++i) v[i] = p[i * step];
+  float2 wt[E];
+  load_twiddles<E, T>(wt, t, tw, tw_n);
+  fft_core<E, T, INV, false>(v, t, lds + c, KS, TC, wt);
+#pragma unroll
+  for (int i = 0; i < E; ++i) p[i * step] = v[i];
+}
+
+int ilog2h(int v) {
+  int l = 0;
+  while ((1 << l) < v) ++l;
+  return l;
+}
+
+bool pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
+
+template <int E, int T>
+hipError_t rows_t(float2 *data, long rows, bool inverse, const float2 *tw, int tw_n,
+                  hipStream_t st) {
+  constexpr int NT = E == 32 ? 128 : 256, RPB = NT / T;
+  const long blocks = (rows + RPB - 1) / RPB;
+  if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
+  const size_t lds = T == 1 ? 0 : static_cast<size_t>(RPB) * E * (T + 1) * sizeof(float2);
+  const std::string name = std::string("k_fft_rows<") + std::to_string(E) + ", " +
+                           std::to_string(T) + (inverse ? ", true>" : ", false>");
+  const double n = static_cast<double>(E) * T;
+  LaunchScope obs(name.c_str(), rows * n * 16, rows * 5.0 * n * ilog2h(E * T), st);
+  if (inverse)
+    hipLaunchKernelGGL((k_fft_rows<E, T, true>), dim3(static_cast<unsigned>(blocks)), dim3(NT), lds,
+                       st, data, rows, tw, tw_n);
+  else
+    hipLaunchKernelGGL((k_fft_rows<E, T, false>), dim3(static_cast<unsigned>(blocks)), dim3(NT), lds,
+                       st, data, rows, tw, tw_n);
+  return hipGetLastError();
+}
+
+template <int E, int T>
+hipError_t cols_t(float2 *data, long nodes, int Mc, bool inverse, const float2 *tw, int tw_n,
+                  hipStream_t st) {
+  int TC = 256 / T;
+  if (TC > Mc) TC = Mc;
+  const long blocks = nodes * (Mc / TC);
+  if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
+  const size_t lds = T == 1 ? 0 : static_cast<size_t>(E) * (T * TC + (E == 32 ? 0 : 1)) * sizeof(float2);
+  if (lds > 65536) return hipErrorInvalidValue;
+  const std::string name = std::string("k_fft_cols<") + std::to_string(E) + ", " +
+                           std::to_string(T) + (inverse ? ", true>" : ", false>");
+  const double n = static_cast<double>(E) * T;
+  LaunchScope obs(name.c_str(), nodes * n * Mc * 16, nodes * Mc * 5.0 * n * ilog2h(E * T), st);
+  if (inverse)
+    hipLaunchKernelGGL((k_fft_cols<E, T, true>), dim3(static_cast<unsigned>(blocks)), dim3(T * TC),
+                       lds, st, data, Mc, TC, tw, tw_n);
+  else
+    hipLaunchKernelGGL((k_fft_cols<E, T, false>), dim3(static_cast<unsigned>(blocks)),
+                       dim3(T * TC), lds, st, data, Mc, TC, tw, tw_n);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool backward_side_supported(int m) { return pow2(m) && m >= 4 && m <= 512; }
+
+hipError_t launch_fft2_inplace(float2 *data, long nodes, int Mr, int Mc, bool inverse,
+                               const float2 *tw, int tw_n, hipStream_t st) {
+  if (nodes <= 0) return hipSuccess;
+  if (!backward_side_supported(Mr) || !backward_side_supported(Mc) || tw_n % Mr != 0 ||
+      tw_n % Mc != 0)
+    return hipErrorInvalidValue;
+  const long rows = nodes * Mr;
+  hipError_t e;
+#define SCAT_ROWS(E_, T_) e = rows_t<E_, T_>(data, rows, inverse, tw, tw_n, st)
+  switch (Mc) {
+    case 4: SCAT_ROWS(4, 1); break;
+    case 8: SCAT_ROWS(8, 1); break;
+    case 16: SCAT_ROWS(16, 1); break;
+    case 32: SCAT_ROWS(16, 2); break;
+    case 64: SCAT_ROWS(16, 4); break;
+    case 128: SCAT_ROWS(16, 8); break;
+    case 256: SCAT_ROWS(16, 16); break;
+    default: SCAT_ROWS(32, 16); break;
+  }
+#undef SCAT_ROWS
+  if (e != hipSuccess) return e;
+#define SCAT_COLS(E_, T_) return cols_t<E_, T_>(data, nodes, Mc, inverse, tw, tw_n, st)
+  switch (Mr) {
+    case 4: SCAT_COLS(4, 1);
+    case 8: SCAT_COLS(8, 1);
+    case 16: SCAT_COLS(16, 1);
+    case 32: SCAT_COLS(16, 2);
+    case 64: SCAT_COLS(16, 4);
+    case 128: SCAT_COLS(16, 8);
+    case 256: SCAT_COLS(16, 16);
+    default: SCAT_COLS(32, 16);
+  }
+#undef SCAT_COLS
+}
+
+hipError_t launch_lowpass_adj(const float *gout, long nodes, ChanMap cm, int K, int m_r, int m_c,
+                              int Mr, int Mc, const float *phi_rows, const float *phi_cols,
+                              float2 *dst, const float2 *tw, int tw_n, hipStream_t st) {
+  if (nodes <= 0) return hipSuccess;
+  if (!pow2(m_r) || !pow2(m_c) || !pow2(Mr) || !pow2(Mc) || m_r > Mr || m_c > Mc ||
+      m_r * m_c > 1024 || tw_n % m_r != 0 || tw_n % m_c != 0 || nodes > 0x7fffffffL)
+    return hipErrorInvalidValue;
+  const size_t lds = static_cast<size_t>(m_r) * m_c * (2 * sizeof(float2) + sizeof(float));
+  LaunchScope obs("k_lowpass_adj", nodes * (m_r * m_c * 4.0 + Mr * 8.0 * Mc),
+                  nodes * (8.0 * m_r * m_c * (m_r + m_c) + 3.0 * Mr * Mc), st);
+  hipLaunchKernelGGL(k_lowpass_adj, dim3(static_cast<unsigned>(nodes)), dim3(256), lds, st, gout, cm,
+                     K, m_r, m_c, ilog2h(Mr), ilog2h(Mc), phi_rows, phi_cols, dst, tw, tw_n);
+  return hipGetLastError();
+}
+
+hipError_t launch_modback(float2 *a, const float2 *y, long count, hipStream_t st) {
+  if (count <= 0) return hipSuccess;
+  long blocks = (count + 255) / 256;
+  if (blocks > 65536 * 16) blocks = 65536 * 16;
+  LaunchScope obs("k_modback", count * 24.0, count * 8.0, st);
+  hipLaunchKernelGGL(k_modback, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st, a, y, count);
+  return hipGetLastError();
+}
+
+hipError_t launch_take_real(const float2 *a, float *out, long count, hipStream_t st) {
+  if (count <= 0) return hipSuccess;
+  long blocks = (count + 255) / 256;
+  if (blocks > 65536 * 16) blocks = 65536 * 16;
+  LaunchScope obs("k_take_real", count * 12.0, 0.0, st);
+  hipLaunchKernelGGL(k_take_real, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st, a, out,
+                     count);
+  return hipGetLastError();
+}
+
+hipError_t launch_tile_accum(float2 *dst, const float *filt, const float2 *G, long S, int F, int Sr,
+                             int Sc, int Mr, int Mc, hipStream_t st) {
+  if (S <= 0 || F <= 0) return hipSuccess;
+  if (!pow2(Sr) || !pow2(Sc) || !pow2(Mr) || !pow2(Mc) || Mr > Sr || Mc > Sc)
+    return hipErrorInvalidValue;
+  const long count = S * Sr * Sc;
+  const long blocks = (count + 255) / 256;
+  if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
+  LaunchScope obs("k_tile_accum",
+                  count * 16.0 + static_cast<double>(F) * Sr * Sc * 4 + S * F * 8.0 * Mr * Mc,
+                  count * 4.0 * F, st);
+  hipLaunchKernelGGL(k_tile_accum, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st, dst, filt,
+                     G, count, F, ilog2h(Sr), ilog2h(Sc), ilog2h(Mr), ilog2h(Mc));
+  return hipGetLastError();
+}
+
+}  // namespace scat

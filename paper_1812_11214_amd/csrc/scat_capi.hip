@@ -339,9 +339,39 @@ scat_status create_common(scat_plan **out_plan, int dims, const int *shape, int 
     if ((expr) != hipSuccess) return SCAT_ERR_DEVICE; \
   } while (0)
 
-// ---- 2-D schedule for one chunk of `pc` planes starting at plane p0
+// Where the backward pass keeps the complex signals before every modulus: per-plane element
+// offsets into one array (chunk-major like all scratch: array of octave j1 starts at
+// y1_off[j1] * planes_in_chunk).
+struct Tape {
+  float2 *base = nullptr;
+  std::vector<size_t> y1_off;                     // per j1: [planes*L][M1r][M1c]
+  std::map<std::pair<int, int>, size_t> y2_off;   // per (j1, j2): [planes*L*L][M2r][M2c]
+  size_t total = 0;                               // elements per plane
+};
+
+Tape make_tape(const scat_plan &p) {
+  Tape t;
+  const scat::HostPlan &h = p.host;
+  const size_t n = static_cast<size_t>(p.n1) * p.n2, l = h.LQ;
+  size_t off = 0;
+  for (int j1 = 0; j1 < h.J; ++j1) {
+    t.y1_off.push_back(off);
+    off += l * (n >> (2 * j1));
+  }
+  if (h.max_order == 2)
+    for (int j1 = 0; j1 < h.J; ++j1)
+      for (int j2 = j1 + 1; j2 < h.J; ++j2) {
+        t.y2_off[{j1, j2}] = off;
+        off += l * l * (n >> (2 * j2));
+      }
+  t.total = off;
+  return t;
+}
+
+// ---- 2-D schedule for one chunk of `pc` planes starting at plane p0.  With a tape the
+// signals before each modulus are kept and the outputs S are not formed (`out` unused).
 scat_status forward_2d(scat_plan *p, const float *in, float *out, long p0, long pc,
-                       const Layout &lay, hipStream_t st) {
+                       const Layout &lay, hipStream_t st, const Tape *tape = nullptr) {
   const scat::HostPlan &h = p->host;
   const int J = h.J, L = h.LQ, K = h.K;
   const int Nr = p->n1, Nc = p->n2;
@@ -355,14 +385,16 @@ scat_status forward_2d(scat_plan *p, const float *in, float *out, long p0, long 
   const float2 *tw = p->d_tw;
   const int tw_n = p->tw_n;
   const float *x = in + static_cast<size_t>(p0) * Nr * Nc;
-  float *o = out + static_cast<size_t>(p0) * K * m_r * m_c;
+  float *o = out ? out + static_cast<size_t>(p0) * K * m_r * m_c : nullptr;
   const ChanMap none{1, 1, 0, 0};
 
+  const bool lp = tape == nullptr;  // form the lowpassed outputs
   // x -> column spectra (+ column half of the lowpass for S0), then rows
-  SCAT_TRY(scat::launch_col(0, x, pc, Nr, Nc, XH, 0, tab + p->phi_rows_off[0], m_r, W, nullptr,
-                            none, K, tw, tw_n, st));
-  SCAT_TRY(scat::launch_row_lowpass(W, pc, m_r, Nc, m_c, tab + p->phi_cols_off[0], o,
-                                    ChanMap{1, 1, 0, 0}, K, tw, tw_n, st));
+  SCAT_TRY(scat::launch_col(0, x, pc, Nr, Nc, XH, 0, tab + p->phi_rows_off[0], m_r,
+                            lp ? W : nullptr, nullptr, none, K, tw, tw_n, st));
+  if (lp)
+    SCAT_TRY(scat::launch_row_lowpass(W, pc, m_r, Nc, m_c, tab + p->phi_cols_off[0], o,
+                                      ChanMap{1, 1, 0, 0}, K, tw, tw_n, st));
   SCAT_TRY(scat::launch_row_fwd(XH, pc * Nr, Nc, tw, tw_n, st));
 
   int s2_base = 1 + J * L;
@@ -372,9 +404,12 @@ scat_status forward_2d(scat_plan *p, const float *in, float *out, long p0, long 
     SCAT_TRY(scat::launch_mulfold_invrow(XH, tab + p->psi1_off[j1], T, pc, L, Nr, Nc, j1, j1, 0,
                                          tw, tw_n, st));
     SCAT_TRY(scat::launch_col(1, T, pc * L, M1r, M1c, kids ? U : nullptr, 0,
-                              tab + p->phi_rows_off[j1], m_r, W, nullptr, none, K, tw, tw_n, st));
-    SCAT_TRY(scat::launch_row_lowpass(W, pc * L, m_r, M1c, m_c, tab + p->phi_cols_off[j1], o,
-                                      ChanMap{L, L, 0, 1 + j1 * L}, K, tw, tw_n, st));
+                              tab + p->phi_rows_off[j1], m_r, lp ? W : nullptr, nullptr, none, K,
+                              tw, tw_n, st, false,
+                              tape ? tape->base + tape->y1_off[j1] * pc : nullptr));
+    if (lp)
+      SCAT_TRY(scat::launch_row_lowpass(W, pc * L, m_r, M1c, m_c, tab + p->phi_cols_off[j1], o,
+                                        ChanMap{L, L, 0, 1 + j1 * L}, K, tw, tw_n, st));
     if (!kids) continue;
     SCAT_TRY(scat::launch_row_fwd(U, pc * L * M1r, M1c, tw, tw_n, st));
     const int octs = J - 1 - j1;
@@ -383,10 +418,12 @@ scat_status forward_2d(scat_plan *p, const float *in, float *out, long p0, long 
       SCAT_TRY(scat::launch_mulfold_invrow(U, tab + p->psi2_off[{j1, j2}], T, pc * L, L, M1r, M1c,
                                            j2 - j1, j2 - j1, 0, tw, tw_n, st));
       SCAT_TRY(scat::launch_col(1, T, pc * L * L, M2r, M2c, nullptr, 0, tab + p->phi_rows_off[j2],
-                                m_r, W, nullptr, none, K, tw, tw_n, st));
-      SCAT_TRY(scat::launch_row_lowpass(W, pc * L * L, m_r, M2c, m_c, tab + p->phi_cols_off[j2], o,
-                                        ChanMap{L * L, L, octs * L, s2_base + (j2 - j1 - 1) * L}, K,
-                                        tw, tw_n, st));
+                                m_r, lp ? W : nullptr, nullptr, none, K, tw, tw_n, st, false,
+                                tape ? tape->base + tape->y2_off.at({j1, j2}) * pc : nullptr));
+      if (lp)
+        SCAT_TRY(scat::launch_row_lowpass(W, pc * L * L, m_r, M2c, m_c, tab + p->phi_cols_off[j2],
+                                          o, ChanMap{L * L, L, octs * L, s2_base + (j2 - j1 - 1) * L},
+                                          K, tw, tw_n, st));
     }
     s2_base += L * L * octs;
   }
@@ -491,6 +528,103 @@ scat_status forward_2d_tree(scat_plan *p, const float *in, float *out, long p0, 
   SCAT_TRY(scat::launch_tree32(XH, pc, L, h.max_order, tab + p->psi1_off[0], tab + p->psi1_off[1],
                                tab + p->phi_cols_off[0], tab + p->phi_cols_off[1],
                                tab + p->taps_off[0], tab + p->taps_off[1], o, K, st));
+  return SCAT_OK;
+}
+
+// ---- backward pass of the 2-D cascade for one chunk: forward with a tape, then the chain
+// of adjoints from the leaves to x (see scat_backward.hip)
+struct BwdLayout {
+  long chunk = 0;
+  size_t per_plane = 0;         // bytes
+  Layout fwd;                   // xh, t, u of the taped forward pass
+  Tape tape;
+  size_t gx = 0, gu = 0, ga = 0;  // elements per plane
+};
+
+BwdLayout make_bwd_layout(const scat_plan &p, long batch) {
+  BwdLayout b;
+  const scat::HostPlan &h = p.host;
+  const size_t n = static_cast<size_t>(p.n1) * p.n2, l = h.LQ, c8 = sizeof(float2);
+  const bool second = h.max_order == 2 && h.J >= 2;
+  const size_t t1 = l * n, t2 = second ? l * l * (n / 4) : 0;
+  b.fwd.xh = n * c8;
+  b.fwd.t = (t1 > t2 ? t1 : t2) * c8;
+  b.fwd.u = second ? l * n * c8 : 0;
+  b.tape = make_tape(p);
+  b.gx = n;
+  b.gu = l * n;
+  b.ga = t2;
+  b.per_plane = b.fwd.xh + b.fwd.t + b.fwd.u + (b.tape.total + b.gx + b.gu + b.ga) * c8;
+  long c = static_cast<long>(scratch_budget() / b.per_plane);
+  if (c < 1) c = 1;
+  if (c > batch) c = batch;
+  b.chunk = c;
+  b.fwd.chunk = c;
+  b.fwd.per_plane = b.per_plane;
+  return b;
+}
+
+scat_status backward_2d(scat_plan *p, const float *in, const float *gout, float *gin, long p0,
+                        long pc, BwdLayout &bl, hipStream_t st) {
+  const scat::HostPlan &h = p->host;
+  const int J = h.J, L = h.LQ, K = h.K;
+  const int Nr = p->n1, Nc = p->n2;
+  const int m_r = Nr >> J, m_c = Nc >> J;
+  const size_t n = static_cast<size_t>(Nr) * Nc;
+  char *base = static_cast<char *>(p->d_scratch);
+  float2 *after_fwd = reinterpret_cast<float2 *>(base + (bl.fwd.xh + bl.fwd.t + bl.fwd.u) * pc);
+  bl.tape.base = after_fwd;
+  float2 *GX = after_fwd + bl.tape.total * pc;
+  float2 *GU = GX + bl.gx * pc;
+  float2 *GA = GU + bl.gu * pc;
+  const float *tab = p->d_tables;
+  const float2 *tw = p->d_tw;
+  const int tw_n = p->tw_n;
+  const float *go = gout + static_cast<size_t>(p0) * K * m_r * m_c;
+  float *gi = gin + static_cast<size_t>(p0) * n;
+
+  scat_status fs = forward_2d(p, in, nullptr, p0, pc, bl.fwd, st, &bl.tape);
+  if (fs != SCAT_OK) return fs;
+
+  // order 0: g_X^ = adjoint lowpass of g_S0
+  SCAT_TRY(scat::launch_lowpass_adj(go, pc, ChanMap{1, 1, 0, 0}, K, m_r, m_c, Nr, Nc,
+                                    tab + p->phi_rows_off[0], tab + p->phi_cols_off[0], GX, tw, tw_n,
+                                    st));
+  int s2_base = 1 + J * L;
+  for (int j1 = 0; j1 < J; ++j1) {
+    const int M1r = Nr >> j1, M1c = Nc >> j1;
+    const size_t n1 = static_cast<size_t>(M1r) * M1c;
+    const bool kids = h.max_order == 2 && j1 < J - 1;
+    // g_U1^ starts as the adjoint lowpass of g_S1, then collects its children
+    SCAT_TRY(scat::launch_lowpass_adj(go, pc * L, ChanMap{L, L, 0, 1 + j1 * L}, K, m_r, m_c, M1r,
+                                      M1c, tab + p->phi_rows_off[j1], tab + p->phi_cols_off[j1], GU,
+                                      tw, tw_n, st));
+    if (kids) {
+      const int octs = J - 1 - j1;
+      for (int j2 = j1 + 1; j2 < J; ++j2) {
+        const int M2r = Nr >> j2, M2c = Nc >> j2;
+        const long nodes = pc * L * L;
+        const size_t n2 = static_cast<size_t>(M2r) * M2c;
+        SCAT_TRY(scat::launch_lowpass_adj(
+            go, nodes, ChanMap{L * L, L, octs * L, s2_base + (j2 - j1 - 1) * L}, K, m_r, m_c, M2r, M2c,
+            tab + p->phi_rows_off[j2], tab + p->phi_cols_off[j2], GA, tw, tw_n, st));
+        SCAT_TRY(scat::launch_fft2_inplace(GA, nodes, M2r, M2c, true, tw, tw_n, st));
+        SCAT_TRY(scat::launch_modback(GA, bl.tape.base + bl.tape.y2_off.at({j1, j2}) * pc,
+                                      nodes * static_cast<long>(n2), st));
+        SCAT_TRY(scat::launch_fft2_inplace(GA, nodes, M2r, M2c, false, tw, tw_n, st));
+        SCAT_TRY(scat::launch_tile_accum(GU, tab + p->psi2_off[{j1, j2}], GA, pc * L, L, M1r, M1c,
+                                         M2r, M2c, st));
+      }
+      s2_base += L * L * octs;
+    }
+    SCAT_TRY(scat::launch_fft2_inplace(GU, pc * L, M1r, M1c, true, tw, tw_n, st));
+    SCAT_TRY(scat::launch_modback(GU, bl.tape.base + bl.tape.y1_off[j1] * pc,
+                                  pc * L * static_cast<long>(n1), st));
+    SCAT_TRY(scat::launch_fft2_inplace(GU, pc * L, M1r, M1c, false, tw, tw_n, st));
+    SCAT_TRY(scat::launch_tile_accum(GX, tab + p->psi1_off[j1], GU, pc, L, Nr, Nc, M1r, M1c, st));
+  }
+  SCAT_TRY(scat::launch_fft2_inplace(GX, pc, Nr, Nc, true, tw, tw_n, st));
+  SCAT_TRY(scat::launch_take_real(GX, gi, pc * static_cast<long>(n), st));
   return SCAT_OK;
 }
 
@@ -602,6 +736,53 @@ scat_status scat_forward(scat_plan *plan, const float *in, float *out, long batc
     if (s != SCAT_OK) return s;
   }
   return SCAT_OK;
+}
+
+scat_status scat_backward(scat_plan *plan, const float *in, const float *grad_out, float *grad_in,
+                          long batch, void *stream) {
+  if (plan == nullptr) return SCAT_ERR_NULL;
+  if (batch < 0) return SCAT_ERR_ARG;
+  const scat::HostPlan &h = plan->host;
+  if (h.dims != 2) return SCAT_ERR_ARG;
+  // every grid of the cascade must have sides the plain transforms handle, and the output
+  // grid must fit the adjoint lowpass kernel's LDS stage
+  const int small_r = plan->n1 >> (h.J - 1), small_c = plan->n2 >> (h.J - 1);
+  if (!scat::backward_side_supported(plan->n1) || !scat::backward_side_supported(plan->n2) ||
+      !scat::backward_side_supported(small_r) || !scat::backward_side_supported(small_c) ||
+      static_cast<long>(plan->n1 >> h.J) * (plan->n2 >> h.J) > 1024)
+    return SCAT_ERR_SHAPE;
+  if (batch == 0) return SCAT_OK;
+  if (in == nullptr || grad_out == nullptr || grad_in == nullptr) return SCAT_ERR_NULL;
+  if (!plan->has_device) return SCAT_ERR_DEVICE;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev != plan->device) return SCAT_ERR_DEVICE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  BwdLayout bl = make_bwd_layout(*plan, batch);
+  const size_t need = bl.per_plane * static_cast<size_t>(bl.chunk);
+  if (need > plan->scratch_bytes) {
+    if (hipDeviceSynchronize() != hipSuccess) return SCAT_ERR_DEVICE;
+    if (plan->d_scratch) (void)hipFree(plan->d_scratch);
+    plan->d_scratch = nullptr;
+    plan->scratch_bytes = 0;
+    if (hipMalloc(&plan->d_scratch, need) != hipSuccess) return SCAT_ERR_ALLOC;
+    plan->scratch_bytes = need;
+  }
+  struct ObserverScope {
+    explicit ObserverScope(scat::LaunchObserver *o) { scat::set_launch_observer(o); }
+    ~ObserverScope() { scat::set_launch_observer(nullptr); }
+  } scope(plan->timer.enabled ? &plan->timer : nullptr);
+  for (long p0 = 0; p0 < batch; p0 += bl.chunk) {
+    long pc = batch - p0 < bl.chunk ? batch - p0 : bl.chunk;
+    scat_status s = backward_2d(plan, in, grad_out, grad_in, p0, pc, bl, st);
+    if (s != SCAT_OK) return s;
+  }
+  return SCAT_OK;
+}
+
+size_t scat_plan_backward_workspace_bytes(const scat_plan *plan, long batch) {
+  if (plan == nullptr || batch <= 0 || plan->host.dims != 2) return 0;
+  const BwdLayout bl = make_bwd_layout(*plan, batch);
+  return bl.per_plane * static_cast<size_t>(bl.chunk);
 }
 
 scat_status scat_plan_destroy(scat_plan *plan) {

@@ -42,7 +42,7 @@ hipError_t launch_mulfold_invrow(const float2 *src, const float *filt, float2 *d
 hipError_t launch_col(int mode, const void *src, long nodes, int Mr, int Mc, float2 *uc,
                       int post_tw_m, const float *phi_rows, int m_r, float *w_out, float *out,
                       ChanMap cm, int K, const float2 *tw, int tw_n, hipStream_t st,
-                      bool uc_half = false);
+                      bool uc_half = false, float2 *y_out = nullptr);
 
 hipError_t launch_row_fwd(float2 *data, long rows, int Mc, const float2 *tw, int tw_n,
                           hipStream_t st);
@@ -96,5 +96,23 @@ hipError_t launch_tree32(const float2 *xh, long planes, int L, int max_order, co
                          const float *psi_j1, const float *phi_cols0, const float *phi_cols1,
                          const float *taps0, const float *taps1, float *out, int K,
                          hipStream_t st);
+
+// ---- backward pass (scat_backward.hip): plain 2-D transforms in place and the adjoints of
+// the lowpass, the modulus and the filter-multiply-fold step.  Sides 4...512.
+bool backward_side_supported(int m);
+// data [nodes][Mr][Mc] complex, unnormalised forward or inverse 2-D transform in place
+hipError_t launch_fft2_inplace(float2 *data, long nodes, int Mr, int Mc, bool inverse,
+                               const float2 *tw, int tw_n, hipStream_t st);
+// dst [nodes][Mr][Mc] = FFT2(g_out node)[k mod m] * phi_rows[k_r] * phi_cols[k_c]; node g of
+// plane p is channel chan(cm, g) of g_out [planes][K][m_r][m_c]; m_r * m_c <= 1024
+hipError_t launch_lowpass_adj(const float *gout, long nodes, ChanMap cm, int K, int m_r, int m_c,
+                              int Mr, int Mc, const float *phi_rows, const float *phi_cols,
+                              float2 *dst, const float2 *tw, int tw_n, hipStream_t st);
+// a[i] = Re(a[i]) * y[i] / |y[i]| (0 where y = 0)
+hipError_t launch_modback(float2 *a, const float2 *y, long count, hipStream_t st);
+hipError_t launch_take_real(const float2 *a, float *out, long count, hipStream_t st);
+// dst [S][Sr][Sc] += sum_f filt[f] * G[s F + f][k_r mod Mr][k_c mod Mc]
+hipError_t launch_tile_accum(float2 *dst, const float *filt, const float2 *G, long S, int F, int Sr,
+                             int Sc, int Mr, int Mc, hipStream_t st);
 
 }  // namespace scat

@@ -1,0 +1,126 @@
+"""Parity of the HIP backward pass with the fp64 oracle's chain of adjoints.
+
+Tolerance.  The gradient passes through y / |y| at every modulus; where |y| is within
+fp32 rounding of zero the phase of the fp32 y is noise, so isolated samples of g_y can
+differ from fp64 by O(|g_U|).  Their effect on the final gradient is damped by the
+filters that follow: measured errors are 1e-7 ... 8e-6 of the gradient's largest entry.
+The bar is the forward pass's: 1e-4 of max |grad| per plane (and 1e-5 in relative L2
+norm); any structural mistake (wrong channel, missing term, wrong sign or scale) gives
+errors of order 1.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import paper_1812_11214_amd as scat
+from paper_1812_11214_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+TOL_MAX = 1e-4
+TOL_L2 = 1e-5
+
+
+def _backward(shape, J, L, max_order, x, g):
+    import torch
+    plan = scat.Scattering(shape, J, L, max_order)
+    try:
+        gi = plan.backward(torch.from_numpy(x).cuda(), torch.from_numpy(g).cuda())
+        torch.cuda.synchronize()
+        return gi.cpu().numpy()
+    finally:
+        plan.close()
+
+
+def _check(shape, J, L, max_order, x, g):
+    got = _backward(shape, J, L, max_order, x, g)
+    bank = oracle.bank_2d(shape[0], shape[1], J, L)
+    want = oracle.scattering2d_backward(x.astype(np.float64), g.astype(np.float64), J, L,
+                                        max_order, bank=bank)
+    worst_max, worst_l2 = 0.0, 0.0
+    for p in range(x.shape[0]):
+        d = got[p].astype(np.float64) - want[p]
+        worst_max = max(worst_max, np.abs(d).max() / np.abs(want[p]).max())
+        worst_l2 = max(worst_l2, np.linalg.norm(d) / np.linalg.norm(want[p]))
+    print("backward", shape, J, L, max_order, "max-rel %.2e l2-rel %.2e" % (worst_max, worst_l2),
+          flush=True)
+    assert worst_max <= TOL_MAX and worst_l2 <= TOL_L2, (worst_max, worst_l2)
+    return got, want
+
+
+@pytest.mark.parametrize("shape,J,L,max_order,batch", [
+    ((32, 32), 2, 8, 2, 5), ((16, 16), 2, 3, 2, 3), ((64, 64), 3, 4, 2, 3),
+    ((32, 64), 2, 3, 1, 2), ((64, 32), 3, 2, 2, 2), ((128, 128), 3, 2, 2, 2),
+    ((8, 8), 1, 4, 2, 3), ((128, 128), 4, 3, 2, 1),
+])
+def test_backward_shapes(shape, J, L, max_order, batch):
+    rng = np.random.default_rng(hash((shape, J, L, max_order)) % 2**32)
+    x = rng.standard_normal((batch,) + shape).astype(np.float32)
+    K = 1 + J * L + (L * L * J * (J - 1) // 2 if max_order == 2 else 0)
+    g = rng.standard_normal((batch, K, shape[0] >> J, shape[1] >> J)).astype(np.float32)
+    _check(shape, J, L, max_order, x, g)
+
+
+def test_backward_headline_shape():
+    """256 x 256, J = 3, L = 8 on two planes of the headline workload."""
+    c = workloads.config(2)
+    x = workloads.planes(2, 2)
+    rng = np.random.default_rng(21)
+    g = rng.standard_normal((2, 217, 32, 32)).astype(np.float32)
+    _check(tuple(c["shape"]), c["J"], c["LQ"], 2, x, g)
+
+
+def test_backward_order0_only_is_linear_and_exact():
+    """With g on channel 0 only the gradient does not depend on x and equals the
+    transposed lowpass; fp32 reproduces it to rounding."""
+    rng = np.random.default_rng(8)
+    shape, J, L = (64, 64), 2, 4
+    K = 1 + J * L + L * L
+    g = np.zeros((2, K, 16, 16), dtype=np.float32)
+    g[:, 0] = rng.standard_normal((2, 16, 16))
+    x1 = rng.standard_normal((2,) + shape).astype(np.float32)
+    x2 = rng.standard_normal((2,) + shape).astype(np.float32)
+    a = _backward(shape, J, L, 2, x1, g)
+    b = _backward(shape, J, L, 2, x2, g)
+    assert np.array_equal(a, b)
+    want = oracle.scattering2d_backward(x1.astype(np.float64), g.astype(np.float64), J, L)
+    assert np.abs(a - want).max() <= 1e-5 * np.abs(want).max()
+
+
+def test_backward_chunked_and_repeatable():
+    """Same gradient whether the batch runs in one chunk or several, and on a second call;
+    a forward call in between (shared scratch) does not disturb it."""
+    import torch
+    rng = np.random.default_rng(12)
+    shape, J, L = (64, 64), 3, 4
+    K = 1 + J * L + L * L * 3
+    x = torch.from_numpy(rng.standard_normal((9,) + shape).astype(np.float32)).cuda()
+    g = torch.from_numpy(rng.standard_normal((9, K, 8, 8)).astype(np.float32)).cuda()
+    plan = scat.Scattering(shape, J, L)
+    try:
+        a = plan.backward(x, g).clone()
+        plan.forward(x)
+        b = plan.backward(x, g).clone()
+        parts = torch.cat([plan.backward(x[:4].contiguous(), g[:4].contiguous()),
+                           plan.backward(x[4:].contiguous(), g[4:].contiguous())])
+        torch.cuda.synchronize()
+        assert torch.equal(a, b) and torch.equal(a, parts)
+        assert plan.backward_workspace_bytes(9) > plan.workspace_bytes(9)
+    finally:
+        plan.close()
+
+
+def test_backward_zero_input_and_zero_gradient():
+    import torch
+    shape, J, L = (32, 32), 2, 8
+    K = 1 + J * L + L * L
+    rng = np.random.default_rng(2)
+    g = rng.standard_normal((2, K, 8, 8)).astype(np.float32)
+    x0 = np.zeros((2,) + shape, dtype=np.float32)
+    got = _backward(shape, J, L, 2, x0, g)
+    g0 = np.zeros_like(g)
+    g0[:, 0] = g[:, 0]
+    only0 = _backward(shape, J, L, 2, x0, g0)
+    assert np.array_equal(got, only0) and np.abs(got).max() > 0
+    x = rng.standard_normal((2,) + shape).astype(np.float32)
+    assert np.all(_backward(shape, J, L, 2, x, np.zeros_like(g)) == 0)

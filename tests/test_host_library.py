@@ -113,3 +113,28 @@ def test_filter_bank_1d_matches_oracle():
     for r in range(J):
         assert np.abs(p.filter(0, 0, r) - oscat.fold(bank['phi_hat'], r, (-1,)).real).max() < 1e-13
     p.close()
+
+
+def test_backward_argument_errors_need_no_gpu():
+    """scat_backward rejects 1-D plans, unsupported grids and bad arguments before it
+    touches the GPU (host-only plans are enough to see it)."""
+    import paper_1812_11214_amd as scat
+    from paper_1812_11214_amd import binding
+    L = binding.lib()
+    one_d = scat.scat_plan_create_host((1024,), 4, 2)
+    tiny = scat.scat_plan_create_host((4, 4), 2, 2)
+    big = scat.scat_plan_create_host((1024, 64), 2, 2)
+    ok = scat.scat_plan_create_host((64, 64), 2, 2)
+    try:
+        assert L.scat_backward(one_d, None, None, None, 1, None) == 1      # SCAT_ERR_ARG
+        assert L.scat_backward(tiny, None, None, None, 1, None) == 2       # SCAT_ERR_SHAPE
+        assert L.scat_backward(big, None, None, None, 1, None) == 2
+        assert L.scat_backward(ok, None, None, None, -1, None) == 1
+        assert L.scat_backward(ok, None, None, None, 0, None) == 0         # no-op
+        assert L.scat_backward(ok, None, None, None, 1, None) == 5         # SCAT_ERR_NULL
+        assert L.scat_backward(None, None, None, None, 1, None) == 5
+        assert scat.scat_plan_backward_workspace_bytes(one_d, 4) == 0
+        assert scat.scat_plan_backward_workspace_bytes(ok, 4) > scat.scat_plan_workspace_bytes(ok, 4)
+    finally:
+        for p in (one_d, tiny, big, ok):
+            scat.scat_plan_destroy(p)
