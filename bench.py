@@ -26,11 +26,16 @@ WORKLOAD = 2                   # index into workloads.CONFIGS: 2-D J=3 L=8 256x2
 TRAFFIC_TAGS = {1: "2d_J2_L8_32x32_b3072", 2: "2d_J3_L8_256x256_b384"}
 
 
-def cpu_baseline(planes, dims, J, LQ, channels, budget_s=20.0):
+def cpu_baseline(planes, dims, J, LQ, channels, budget_s=20.0, grad=None):
     """Time the oracle (single process, numpy FFTs are single threaded) on as many planes
-    of the workload as fit in about budget_s seconds."""
+    of the workload as fit in about budget_s seconds.  With `grad` (dL/dS for every plane)
+    the oracle's backward pass is timed instead of its forward pass."""
     import oracle
-    if dims == 2:
+    if dims == 2 and grad is not None:
+        n_r, n_c = planes.shape[-2:]
+        bank = oracle.bank_2d(n_r, n_c, J, LQ)
+        run = lambda x: oracle.scattering2d_backward(x, grad[:len(x)], J, LQ, bank=bank)
+    elif dims == 2:
         n_r, n_c = planes.shape[-2:]
         bank = oracle.bank_2d(n_r, n_c, J, LQ)     # built once, like the GPU plan; not timed
         run = lambda x: oracle.scattering2d(x, J, LQ, bank=bank)
@@ -45,8 +50,10 @@ def cpu_baseline(planes, dims, J, LQ, channels, budget_s=20.0):
     run(planes[:n])
     dt = time.perf_counter() - t0
     return {"value": n / dt / channels, "unit": "images/s", "cores": 1, "kind": "oracle",
-            "sample": "%d of %d planes (%d-channel images), fp64 numpy cascade, filter bank "
-                      "prebuilt, %.1f s" % (n, len(planes), channels, dt)}
+            "sample": "%d of %d planes (%d-channel images), fp64 numpy %s, filter bank "
+                      "prebuilt, %.1f s" % (n, len(planes), channels,
+                                            "backward pass (forward recomputed inside)"
+                                            if grad is not None else "cascade", dt)}
 
 
 def main():
@@ -59,6 +66,10 @@ def main():
     ap.add_argument("--workload", type=int, default=WORKLOAD,
                     help="index of the configuration to run (default 2 = the headline one; "
                          "0, 1, 3, 4 are the other parity configurations)")
+    ap.add_argument("--backward", action="store_true",
+                    help="time the backward pass (gradient with respect to the input of a "
+                         "seeded random dL/dS; recomputes the forward cascade inside) instead "
+                         "of the forward transform; 2-D workloads only")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (a kernel of known "
                          "traffic, to calibrate profiler byte counters)")
@@ -86,9 +97,21 @@ def main():
     x = torch.from_numpy(x_host).cuda()
     plan = scat.Scattering(cfg["shape"], cfg["J"], cfg["LQ"])
     out = torch.empty((P, plan.K) + plan.out_shape, dtype=torch.float32, device="cuda")
+    g_host = None
+    if args.backward:
+        if cfg["dims"] != 2:
+            print("bench.py: --backward needs a 2-D workload", file=sys.stderr)
+            sys.exit(2)
+        g_host = np.random.default_rng(181211214).standard_normal(
+            tuple(out.shape), dtype=np.float32)
+        g = torch.from_numpy(g_host).cuda()
+        gin = torch.empty_like(x)
+        step = lambda: plan.backward(x, g, grad_in=gin)
+    else:
+        step = lambda: plan.forward(x, out=out)
 
     for _ in range(max(args.warmup, 1)):
-        plan.forward(x, out=out)
+        step()
     torch.cuda.synchronize()
 
     if args.copy_probe:
@@ -100,7 +123,7 @@ def main():
 
     # which kernel takes the most time? (one untimed forward with every launch bracketed)
     plan.timing_begin(None)
-    plan.forward(x, out=out)
+    step()
     torch.cuda.synchronize()
     table = plan.timing_end()
     dominant = max(table, key=lambda k: table[k]["ms"])
@@ -112,7 +135,7 @@ def main():
     t0 = time.perf_counter()
     start.record()
     for _ in range(args.steps):
-        plan.forward(x, out=out)
+        step()
     stop.record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
@@ -120,7 +143,7 @@ def main():
     ms_per_step = start.elapsed_time(stop) / args.steps
 
     # sanity: the output is finite and S0 of a zero-mean unit-variance field is small
-    chk = out[:2].float().cpu().numpy()
+    chk = (gin if args.backward else out)[:2].float().cpu().numpy()
     assert np.isfinite(chk).all()
 
     avg_ms = dom["ms"] / dom["launches"]
@@ -130,7 +153,8 @@ def main():
     # HBM bytes per launch of every kernel from the committed rocprofv3 counter summary
     # (FETCH_SIZE and WRITE_SIZE runs of this same command, scaled by a plain copy)
     per_kernel = {}
-    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % TRAFFIC_TAGS.get(wl, "none"))
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_%s%s.txt"
+                         % (TRAFFIC_TAGS.get(wl, "none"), "_backward" if args.backward else ""))
     if os.path.exists(tpath):
         with open(tpath) as f:
             for line in f:
@@ -171,7 +195,9 @@ def main():
 
     images_per_s = (P / C) / (ms_per_step * 1e-3)
     result = {
-        "metric": ("Scattering2D J=3 L=8 256x256 images/sec on 1 MI355X; % HBM roofline"
+        "metric": ("scattering backward pass (gradient wrt the input, forward recomputed) "
+                   "images/sec on 1 MI355X (%s)" % cfg["name"] if args.backward else
+                   "Scattering2D J=3 L=8 256x256 images/sec on 1 MI355X; % HBM roofline"
                    if wl == WORKLOAD else "scattering images/sec on 1 MI355X (%s)" % cfg["name"]),
         "value": images_per_s, "unit": "images/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
@@ -189,7 +215,7 @@ def main():
     plan.close()
     if args.cpu_seconds > 0:
         result["cpu_baseline"] = cpu_baseline(x_host, cfg["dims"], cfg["J"], cfg["LQ"], C,
-                                              args.cpu_seconds)
+                                              args.cpu_seconds, grad=g_host)
     print(json.dumps(result))
 
 

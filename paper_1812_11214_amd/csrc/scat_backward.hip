@@ -37,19 +37,22 @@ __global__ __launch_bounds__(256) void k_lowpass_adj(const float *__restrict__ g
   extern __shared__ float2 lds[];
   const int mm = m_r * m_c;
   float2 *s1 = lds, *s2 = lds + mm;
-  float *a = reinterpret_cast<float *>(lds + 2 * mm);
+  float2 *twc = lds + 2 * mm, *twr = twc + m_c;  // exp(-2 pi i j / m_c), exp(-2 pi i j / m_r)
+  float *a = reinterpret_cast<float *>(twr + m_r);
   const long node = blockIdx.x;
   const long p = node / cm.G;
   const int g = static_cast<int>(node - p * cm.G);
   const float *gp = gout + (static_cast<size_t>(p) * K + chan(cm, g)) * mm;
   for (int i = threadIdx.x; i < mm; i += blockDim.x) a[i] = gp[i];
-  __syncthreads();
   const int sc = tw_n / m_c, sr = tw_n / m_r;
+  for (int i = threadIdx.x; i < m_c; i += blockDim.x) twc[i] = tw[i * sc];
+  for (int i = threadIdx.x; i < m_r; i += blockDim.x) twr[i] = tw[i * sr];
+  __syncthreads();
   for (int i = threadIdx.x; i < mm; i += blockDim.x) {
     const int r = i / m_c, kc = i - r * m_c;
     float2 acc = make_float2(0.f, 0.f);
     for (int b = 0; b < m_c; ++b) {
-      const float2 w = tw[((b * kc) & (m_c - 1)) * sc];
+      const float2 w = twc[(b * kc) & (m_c - 1)];
       const float x = a[r * m_c + b];
       acc.x += x * w.x;
       acc.y += x * w.y;
@@ -60,7 +63,7 @@ __global__ __launch_bounds__(256) void k_lowpass_adj(const float *__restrict__ g
   for (int i = threadIdx.x; i < mm; i += blockDim.x) {
     const int kr = i / m_c, kc = i - kr * m_c;
     float2 acc = make_float2(0.f, 0.f);
-    for (int r = 0; r < m_r; ++r) acc = c_add(acc, c_mul(s1[r * m_c + kc], tw[((r * kr) & (m_r - 1)) * sr]));
+    for (int r = 0; r < m_r; ++r) acc = c_add(acc, c_mul(s1[r * m_c + kc], twr[(r * kr) & (m_r - 1)]));
     s2[i] = acc;
   }
   __syncthreads();
@@ -95,28 +98,42 @@ __global__ __launch_bounds__(256) void k_take_real(const float2 *__restrict__ a,
 }
 
 // dst [S][Sr][Sc] += sum_f filt[f][k_r][k_c] * G[s F + f][k_r mod Mr][k_c mod Mc]
-// (adjoint of: multiply by the F filters, fold to Mr x Mc).  One thread per element of dst.
+// (adjoint of: multiply by the F filters, fold to Mr x Mc).  One thread per element
+// (s, q_r, q_c) of the folded grid: it reads its F values of G once (FB at a time) and
+// updates every copy (q_r + a Mr, q_c + b Mc) of dst, so nothing is read twice.
+template <int FB>
 __global__ __launch_bounds__(256) void k_tile_accum(float2 *__restrict__ dst,
                                                     const float *__restrict__ filt,
                                                     const float2 *__restrict__ G, long count,
                                                     int F, int lgSr, int lgSc, int lgMr, int lgMc) {
   const long i = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x;
   if (i >= count) return;
-  const int lgS = lgSr + lgSc;
-  const long s = i >> lgS;
-  const int e = static_cast<int>(i & ((1L << lgS) - 1));
-  const int kr = e >> lgSc, kc = e & ((1 << lgSc) - 1);
-  const int ge = ((kr & ((1 << lgMr) - 1)) << lgMc) + (kc & ((1 << lgMc) - 1));
-  const float2 *gp = G + ((static_cast<size_t>(s) * F) << (lgMr + lgMc)) + ge;
-  const float *fp = filt + e;
-  float2 acc = dst[i];
-  for (int f = 0; f < F; ++f) {
-    const float w = fp[static_cast<size_t>(f) << lgS];
-    const float2 v = gp[static_cast<size_t>(f) << (lgMr + lgMc)];
-    acc.x += v.x * w;
-    acc.y += v.y * w;
+  const int lgM = lgMr + lgMc, lgS = lgSr + lgSc;
+  const long s = i >> lgM;
+  const int e = static_cast<int>(i & ((1L << lgM) - 1));
+  const int qr = e >> lgMc, qc = e & ((1 << lgMc) - 1);
+  const float2 *gp = G + ((static_cast<size_t>(s) * F) << lgM) + e;
+  float2 *dp = dst + (static_cast<size_t>(s) << lgS);
+  const int nr = 1 << (lgSr - lgMr), nc = 1 << (lgSc - lgMc);
+  for (int f0 = 0; f0 < F; f0 += FB) {
+    float2 g[FB];
+#pragma unroll
+    for (int j = 0; j < FB; ++j)
+      g[j] = f0 + j < F ? gp[static_cast<size_t>(f0 + j) << lgM] : make_float2(0.f, 0.f);
+    for (int a = 0; a < nr; ++a)
+      for (int b = 0; b < nc; ++b) {
+        const int o = ((qr + (a << lgMr)) << lgSc) + qc + (b << lgMc);
+        float2 acc = dp[o];
+#pragma unroll
+        for (int j = 0; j < FB; ++j) {
+          const int f = f0 + j < F ? f0 + j : F - 1;
+          const float w = filt[(static_cast<size_t>(f) << lgS) + o];
+          acc.x += g[j].x * w;
+          acc.y += g[j].y * w;
+        }
+        dp[o] = acc;
+      }
   }
-  dst[i] = acc;
 }
 
 // In-place transform of every row of [rows][E*T] (T lanes per row, wave-level sync only).
@@ -163,6 +180,41 @@ __global__ __launch_bounds__(256) void k_fft_cols(float2 *__restrict__ data, int
   float2 wt[E];
   load_twiddles<E, T>(wt, t, tw, tw_n);
   fft_core<E, T, INV, false>(v, t, lds + c, KS, TC, wt);
+#pragma unroll
+  for (int i = 0; i < E; ++i) p[i * step] = v[i];
+}
+
+// Column pass of the modulus backward step: inverse transform of every column, then
+// a = Re(a) y / |y| against the taped signal y (same layout), then forward transform.
+template <int E, int T>
+__global__ __launch_bounds__(256) void k_cols_modback(float2 *__restrict__ data,
+                                                      const float2 *__restrict__ y, int Mc, int TC,
+                                                      const float2 *__restrict__ tw, int tw_n) {
+  constexpr int M = E * T;
+  extern __shared__ float2 lds[];
+  const int KS = T * TC + (E == 32 ? 0 : 1);
+  const int c = threadIdx.x % TC, t = threadIdx.x / TC;
+  const int tiles = Mc / TC;
+  const long node = blockIdx.x / tiles;
+  const int c0 = static_cast<int>(blockIdx.x % tiles) * TC;
+  const size_t off = static_cast<size_t>(node) * M * Mc + static_cast<size_t>(t) * Mc + c0 + c;
+  float2 *p = data + off;
+  const float2 *yp = y + off;
+  const size_t step = static_cast<size_t>(T) * Mc;
+  float2 v[E];
+#pragma unroll
+  for (int i = 0; i < E; ++i) v[i] = p[i * step];
+  float2 wt[E];
+  load_twiddles<E, T>(wt, t, tw, tw_n);
+  fft_core<E, T, true, false>(v, t, lds + c, KS, TC, wt);
+#pragma unroll
+  for (int i = 0; i < E; ++i) {
+    const float2 u = yp[i * step];
+    const float m2 = u.x * u.x + u.y * u.y;
+    const float sgn = m2 > 0.f ? v[i].x / __builtin_amdgcn_sqrtf(m2) : 0.f;
+    v[i] = make_float2(u.x * sgn, u.y * sgn);
+  }
+  fft_core<E, T, false, false>(v, t, lds + c, KS, TC, wt);
 #pragma unroll
   for (int i = 0; i < E; ++i) p[i * step] = v[i];
 }
@@ -217,9 +269,65 @@ hipError_t cols_t(float2 *data, long nodes, int Mc, bool inverse, const float2 *
   return hipGetLastError();
 }
 
+template <int E, int T>
+hipError_t cols_modback_t(float2 *data, const float2 *y, long nodes, int Mc, const float2 *tw,
+                          int tw_n, hipStream_t st) {
+  int TC = 256 / T;
+  if (TC > Mc) TC = Mc;
+  const long blocks = nodes * (Mc / TC);
+  if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
+  const size_t lds = T == 1 ? 0 : static_cast<size_t>(E) * (T * TC + (E == 32 ? 0 : 1)) * sizeof(float2);
+  if (lds > 65536) return hipErrorInvalidValue;
+  const std::string name = std::string("k_cols_modback<") + std::to_string(E) + ", " +
+                           std::to_string(T) + ">";
+  const double n = static_cast<double>(E) * T;
+  LaunchScope obs(name.c_str(), nodes * n * Mc * 24,
+                  nodes * Mc * (10.0 * n * ilog2h(E * T) + 8.0 * n), st);
+  hipLaunchKernelGGL((k_cols_modback<E, T>), dim3(static_cast<unsigned>(blocks)), dim3(T * TC), lds,
+                     st, data, y, Mc, TC, tw, tw_n);
+  return hipGetLastError();
+}
+
 }  // namespace
 
 bool backward_side_supported(int m) { return pow2(m) && m >= 4 && m <= 512; }
+
+hipError_t launch_fft_rows_inplace(float2 *data, long rows, int Mc, bool inverse, const float2 *tw,
+                                   int tw_n, hipStream_t st) {
+  if (rows <= 0) return hipSuccess;
+  if (!backward_side_supported(Mc) || tw_n % Mc != 0) return hipErrorInvalidValue;
+#define SCAT_ROWS(E_, T_) return rows_t<E_, T_>(data, rows, inverse, tw, tw_n, st)
+  switch (Mc) {
+    case 4: SCAT_ROWS(4, 1);
+    case 8: SCAT_ROWS(8, 1);
+    case 16: SCAT_ROWS(16, 1);
+    case 32: SCAT_ROWS(16, 2);
+    case 64: SCAT_ROWS(16, 4);
+    case 128: SCAT_ROWS(16, 8);
+    case 256: SCAT_ROWS(16, 16);
+    default: SCAT_ROWS(32, 16);
+  }
+#undef SCAT_ROWS
+}
+
+hipError_t launch_cols_modback(float2 *data, const float2 *y, long nodes, int Mr, int Mc,
+                               const float2 *tw, int tw_n, hipStream_t st) {
+  if (nodes <= 0) return hipSuccess;
+  if (!backward_side_supported(Mr) || !backward_side_supported(Mc) || tw_n % Mr != 0)
+    return hipErrorInvalidValue;
+#define SCAT_CM(E_, T_) return cols_modback_t<E_, T_>(data, y, nodes, Mc, tw, tw_n, st)
+  switch (Mr) {
+    case 4: SCAT_CM(4, 1);
+    case 8: SCAT_CM(8, 1);
+    case 16: SCAT_CM(16, 1);
+    case 32: SCAT_CM(16, 2);
+    case 64: SCAT_CM(16, 4);
+    case 128: SCAT_CM(16, 8);
+    case 256: SCAT_CM(16, 16);
+    default: SCAT_CM(32, 16);
+  }
+#undef SCAT_CM
+}
 
 hipError_t launch_fft2_inplace(float2 *data, long nodes, int Mr, int Mc, bool inverse,
                                const float2 *tw, int tw_n, hipStream_t st) {
@@ -263,7 +371,8 @@ hipError_t launch_lowpass_adj(const float *gout, long nodes, ChanMap cm, int K, 
   if (!pow2(m_r) || !pow2(m_c) || !pow2(Mr) || !pow2(Mc) || m_r > Mr || m_c > Mc ||
       m_r * m_c > 1024 || tw_n % m_r != 0 || tw_n % m_c != 0 || nodes > 0x7fffffffL)
     return hipErrorInvalidValue;
-  const size_t lds = static_cast<size_t>(m_r) * m_c * (2 * sizeof(float2) + sizeof(float));
+  const size_t lds = static_cast<size_t>(m_r) * m_c * (2 * sizeof(float2) + sizeof(float)) +
+                     static_cast<size_t>(m_r + m_c) * sizeof(float2);
   LaunchScope obs("k_lowpass_adj", nodes * (m_r * m_c * 4.0 + Mr * 8.0 * Mc),
                   nodes * (8.0 * m_r * m_c * (m_r + m_c) + 3.0 * Mr * Mc), st);
   hipLaunchKernelGGL(k_lowpass_adj, dim3(static_cast<unsigned>(nodes)), dim3(256), lds, st, gout, cm,
@@ -295,14 +404,14 @@ hipError_t launch_tile_accum(float2 *dst, const float *filt, const float2 *G, lo
   if (S <= 0 || F <= 0) return hipSuccess;
   if (!pow2(Sr) || !pow2(Sc) || !pow2(Mr) || !pow2(Mc) || Mr > Sr || Mc > Sc)
     return hipErrorInvalidValue;
-  const long count = S * Sr * Sc;
+  const long count = S * Mr * Mc;
   const long blocks = (count + 255) / 256;
   if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
   LaunchScope obs("k_tile_accum",
-                  count * 16.0 + static_cast<double>(F) * Sr * Sc * 4 + S * F * 8.0 * Mr * Mc,
-                  count * 4.0 * F, st);
-  hipLaunchKernelGGL(k_tile_accum, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st, dst, filt,
-                     G, count, F, ilog2h(Sr), ilog2h(Sc), ilog2h(Mr), ilog2h(Mc));
+                  S * 16.0 * Sr * Sc + static_cast<double>(F) * Sr * Sc * 4 + S * F * 8.0 * Mr * Mc,
+                  S * 4.0 * F * Sr * Sc, st);
+  hipLaunchKernelGGL((k_tile_accum<8>), dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st, dst,
+                     filt, G, count, F, ilog2h(Sr), ilog2h(Sc), ilog2h(Mr), ilog2h(Mc));
   return hipGetLastError();
 }
 

@@ -593,7 +593,6 @@ scat_status backward_2d(scat_plan *p, const float *in, const float *gout, float 
   int s2_base = 1 + J * L;
   for (int j1 = 0; j1 < J; ++j1) {
     const int M1r = Nr >> j1, M1c = Nc >> j1;
-    const size_t n1 = static_cast<size_t>(M1r) * M1c;
     const bool kids = h.max_order == 2 && j1 < J - 1;
     // g_U1^ starts as the adjoint lowpass of g_S1, then collects its children
     SCAT_TRY(scat::launch_lowpass_adj(go, pc * L, ChanMap{L, L, 0, 1 + j1 * L}, K, m_r, m_c, M1r,
@@ -604,23 +603,24 @@ scat_status backward_2d(scat_plan *p, const float *in, const float *gout, float 
       for (int j2 = j1 + 1; j2 < J; ++j2) {
         const int M2r = Nr >> j2, M2c = Nc >> j2;
         const long nodes = pc * L * L;
-        const size_t n2 = static_cast<size_t>(M2r) * M2c;
         SCAT_TRY(scat::launch_lowpass_adj(
             go, nodes, ChanMap{L * L, L, octs * L, s2_base + (j2 - j1 - 1) * L}, K, m_r, m_c, M2r, M2c,
             tab + p->phi_rows_off[j2], tab + p->phi_cols_off[j2], GA, tw, tw_n, st));
-        SCAT_TRY(scat::launch_fft2_inplace(GA, nodes, M2r, M2c, true, tw, tw_n, st));
-        SCAT_TRY(scat::launch_modback(GA, bl.tape.base + bl.tape.y2_off.at({j1, j2}) * pc,
-                                      nodes * static_cast<long>(n2), st));
-        SCAT_TRY(scat::launch_fft2_inplace(GA, nodes, M2r, M2c, false, tw, tw_n, st));
+        // inverse 2-D transform, modulus backward, forward 2-D transform: rows, then one
+        // column pass that does all three column steps, then rows
+        SCAT_TRY(scat::launch_fft_rows_inplace(GA, nodes * M2r, M2c, true, tw, tw_n, st));
+        SCAT_TRY(scat::launch_cols_modback(GA, bl.tape.base + bl.tape.y2_off.at({j1, j2}) * pc, nodes,
+                                           M2r, M2c, tw, tw_n, st));
+        SCAT_TRY(scat::launch_fft_rows_inplace(GA, nodes * M2r, M2c, false, tw, tw_n, st));
         SCAT_TRY(scat::launch_tile_accum(GU, tab + p->psi2_off[{j1, j2}], GA, pc * L, L, M1r, M1c,
                                          M2r, M2c, st));
       }
       s2_base += L * L * octs;
     }
-    SCAT_TRY(scat::launch_fft2_inplace(GU, pc * L, M1r, M1c, true, tw, tw_n, st));
-    SCAT_TRY(scat::launch_modback(GU, bl.tape.base + bl.tape.y1_off[j1] * pc,
-                                  pc * L * static_cast<long>(n1), st));
-    SCAT_TRY(scat::launch_fft2_inplace(GU, pc * L, M1r, M1c, false, tw, tw_n, st));
+    SCAT_TRY(scat::launch_fft_rows_inplace(GU, pc * L * M1r, M1c, true, tw, tw_n, st));
+    SCAT_TRY(scat::launch_cols_modback(GU, bl.tape.base + bl.tape.y1_off[j1] * pc, pc * L, M1r, M1c,
+                                       tw, tw_n, st));
+    SCAT_TRY(scat::launch_fft_rows_inplace(GU, pc * L * M1r, M1c, false, tw, tw_n, st));
     SCAT_TRY(scat::launch_tile_accum(GX, tab + p->psi1_off[j1], GU, pc, L, Nr, Nc, M1r, M1c, st));
   }
   SCAT_TRY(scat::launch_fft2_inplace(GX, pc, Nr, Nc, true, tw, tw_n, st));

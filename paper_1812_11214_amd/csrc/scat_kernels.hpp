@@ -103,6 +103,13 @@ bool backward_side_supported(int m);
 // data [nodes][Mr][Mc] complex, unnormalised forward or inverse 2-D transform in place
 hipError_t launch_fft2_inplace(float2 *data, long nodes, int Mr, int Mc, bool inverse,
                                const float2 *tw, int tw_n, hipStream_t st);
+// rows only: data [rows][Mc]
+hipError_t launch_fft_rows_inplace(float2 *data, long rows, int Mc, bool inverse, const float2 *tw,
+                                   int tw_n, hipStream_t st);
+// columns of data [nodes][Mr][Mc]: inverse transform, a = Re(a) y / |y| (0 where y = 0)
+// against y of the same layout, forward transform
+hipError_t launch_cols_modback(float2 *data, const float2 *y, long nodes, int Mr, int Mc,
+                               const float2 *tw, int tw_n, hipStream_t st);
 // dst [nodes][Mr][Mc] = FFT2(g_out node)[k mod m] * phi_rows[k_r] * phi_cols[k_c]; node g of
 // plane p is channel chan(cm, g) of g_out [planes][K][m_r][m_c]; m_r * m_c <= 1024
 hipError_t launch_lowpass_adj(const float *gout, long nodes, ChanMap cm, int K, int m_r, int m_c,
