@@ -431,9 +431,10 @@ scat_status forward_2d(scat_plan *p, const float *in, float *out, long p0, long 
 }
 
 
-// ---- 2-D schedule with the fused row pass (no full 2-D spectrum is ever stored)
+// ---- 2-D schedule with the fused row pass (no full 2-D spectrum is ever stored).  With a
+// tape the signals before each modulus are kept and the outputs S are not formed.
 scat_status forward_2d_fused(scat_plan *p, const float *in, float *out, long p0, long pc,
-                             const Layout &lay, hipStream_t st) {
+                             const Layout &lay, hipStream_t st, const Tape *tape = nullptr) {
   const scat::HostPlan &h = p->host;
   const int J = h.J, L = h.LQ, K = h.K;
   const int Nr = p->n1, Nc = p->n2;
@@ -449,15 +450,18 @@ scat_status forward_2d_fused(scat_plan *p, const float *in, float *out, long p0,
   const float2 *tw = p->d_tw;
   const int tw_n = p->tw_n;
   const float *x = in + static_cast<size_t>(p0) * n;
-  float *o = out + static_cast<size_t>(p0) * K * m_r * m_c;
+  float *o = out ? out + static_cast<size_t>(p0) * K * m_r * m_c : nullptr;
   const ChanMap none{1, 1, 0, 0};
   // Column pass (+ modulus) of `nodes` planes of Mr x Mc at resolution `res`, then the
   // lowpass to the output channels `cm`: one kernel when the whole-node variant applies,
   // else the column pass followed by the row half of the lowpass.  Column spectra of the
   // real signals go to `uc` (may be null) as their non-redundant half (rows 0..Mr/2).
   auto col_and_lowpass = [&](int mode, const void *src, long nodes, int Mr, int Mc, int res,
-                             float2 *uc, ChanMap cm) -> hipError_t {
+                             float2 *uc, ChanMap cm, float2 *y_out = nullptr) -> hipError_t {
     const float *pr = tab + p->phi_rows_off[res], *pcs = tab + p->phi_cols_off[res];
+    if (tape != nullptr)  // column pass only, keeping the signal before the modulus
+      return scat::launch_col(mode, src, nodes, Mr, Mc, uc, 0, pr, m_r, nullptr, nullptr, none, K,
+                              tw, tw_n, st, true, y_out);
     if (scat::col_node_supported(Mr, Mc, m_r, m_c, tw_n))
       return scat::launch_col_node(mode, src, nodes, Mr, m_r, uc, true, pr, pcs, o, cm, K, tw, tw_n,
                                    st);
@@ -485,7 +489,8 @@ scat_status forward_2d_fused(scat_plan *p, const float *in, float *out, long p0,
     const int M1r = Nr >> j1, M1c = Nc >> j1;
     const bool kids = h.max_order == 2 && j1 < J - 1;
     SCAT_TRY(col_and_lowpass(1, t1[j1], pc * L, M1r, M1c, j1, kids ? U : nullptr,
-                             ChanMap{L, L, 0, 1 + j1 * L}));
+                             ChanMap{L, L, 0, 1 + j1 * L},
+                             tape ? tape->base + tape->y1_off[j1] * pc : nullptr));
     if (!kids) continue;
     const int octs = J - 1 - j1;
     std::vector<float2 *> t2(J);
@@ -502,7 +507,8 @@ scat_status forward_2d_fused(scat_plan *p, const float *in, float *out, long p0,
     for (int j2 = j1 + 1; j2 < J; ++j2) {
       const int M2r = Nr >> j2, M2c = Nc >> j2;
       SCAT_TRY(col_and_lowpass(1, t2[j2], pc * L * L, M2r, M2c, j2, nullptr,
-                               ChanMap{L * L, L, octs * L, s2_base + (j2 - j1 - 1) * L}));
+                               ChanMap{L * L, L, octs * L, s2_base + (j2 - j1 - 1) * L},
+                               tape ? tape->base + tape->y2_off.at({j1, j2}) * pc : nullptr));
     }
     s2_base += L * L * octs;
   }
@@ -547,14 +553,25 @@ BwdLayout make_bwd_layout(const scat_plan &p, long batch) {
   const size_t n = static_cast<size_t>(p.n1) * p.n2, l = h.LQ, c8 = sizeof(float2);
   const bool second = h.max_order == 2 && h.J >= 2;
   const size_t t1 = l * n, t2 = second ? l * l * (n / 4) : 0;
-  b.fwd.xh = n * c8;
-  b.fwd.t = (t1 > t2 ? t1 : t2) * c8;
-  b.fwd.u = second ? l * n * c8 : 0;
+  if (p.fused) {
+    // buffers of the fused forward schedule (see make_layout)
+    size_t ft1 = 0, ft2 = 0;
+    for (int j = 0; j < h.J; ++j) ft1 += l * (n >> (2 * j));
+    for (int j = 1; j < h.J; ++j) ft2 += l * l * (n >> (2 * j));
+    b.fwd.xh = n * c8;
+    b.fwd.t = ft1 * c8;
+    b.fwd.u = second ? l * n * c8 : 0;
+    b.fwd.v = second ? ft2 * c8 : 0;
+  } else {
+    b.fwd.xh = n * c8;
+    b.fwd.t = (t1 > t2 ? t1 : t2) * c8;
+    b.fwd.u = second ? l * n * c8 : 0;
+  }
   b.tape = make_tape(p);
   b.gx = n;
   b.gu = l * n;
   b.ga = t2;
-  b.per_plane = b.fwd.xh + b.fwd.t + b.fwd.u + (b.tape.total + b.gx + b.gu + b.ga) * c8;
+  b.per_plane = b.fwd.xh + b.fwd.t + b.fwd.u + b.fwd.v + (b.tape.total + b.gx + b.gu + b.ga) * c8;
   long c = static_cast<long>(scratch_budget() / b.per_plane);
   if (c < 1) c = 1;
   if (c > batch) c = batch;
@@ -572,7 +589,8 @@ scat_status backward_2d(scat_plan *p, const float *in, const float *gout, float 
   const int m_r = Nr >> J, m_c = Nc >> J;
   const size_t n = static_cast<size_t>(Nr) * Nc;
   char *base = static_cast<char *>(p->d_scratch);
-  float2 *after_fwd = reinterpret_cast<float2 *>(base + (bl.fwd.xh + bl.fwd.t + bl.fwd.u) * pc);
+  float2 *after_fwd =
+      reinterpret_cast<float2 *>(base + (bl.fwd.xh + bl.fwd.t + bl.fwd.u + bl.fwd.v) * pc);
   bl.tape.base = after_fwd;
   float2 *GX = after_fwd + bl.tape.total * pc;
   float2 *GU = GX + bl.gx * pc;
@@ -583,7 +601,8 @@ scat_status backward_2d(scat_plan *p, const float *in, const float *gout, float 
   const float *go = gout + static_cast<size_t>(p0) * K * m_r * m_c;
   float *gi = gin + static_cast<size_t>(p0) * n;
 
-  scat_status fs = forward_2d(p, in, nullptr, p0, pc, bl.fwd, st, &bl.tape);
+  scat_status fs = p->fused ? forward_2d_fused(p, in, nullptr, p0, pc, bl.fwd, st, &bl.tape)
+                            : forward_2d(p, in, nullptr, p0, pc, bl.fwd, st, &bl.tape);
   if (fs != SCAT_OK) return fs;
 
   // order 0: g_X^ = adjoint lowpass of g_S0
