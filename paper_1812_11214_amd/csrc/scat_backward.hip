@@ -407,7 +407,7 @@ hipError_t launch_tile_accum(float2 *dst, const float *filt, const float2 *G, lo
   const long count = S * Mr * Mc;
   const long blocks = (count + 255) / 256;
   if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
-  LaunchScope obs("k_tile_accum",
+  LaunchScope obs("k_tile_accum<8>",
                   S * 16.0 * Sr * Sc + static_cast<double>(F) * Sr * Sc * 4 + S * F * 8.0 * Mr * Mc,
                   S * 4.0 * F * Sr * Sc, st);
   hipLaunchKernelGGL((k_tile_accum<8>), dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st, dst,
