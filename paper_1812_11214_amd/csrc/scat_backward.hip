@@ -78,6 +78,83 @@ __global__ __launch_bounds__(256) void k_lowpass_adj(const float *__restrict__ g
   }
 }
 
+// First half of the adjoint lowpass: Ghat [node][m_r][m_c] = FFT2 of the node's gradient
+// plane (two dense stages in LDS; the planes are tiny).
+__global__ __launch_bounds__(256) void k_small_fft2(const float *__restrict__ gout, ChanMap cm,
+                                                    int K, int m_r, int m_c,
+                                                    float2 *__restrict__ ghat,
+                                                    const float2 *__restrict__ tw, int tw_n) {
+  extern __shared__ float2 lds[];
+  const int mm = m_r * m_c;
+  float2 *s1 = lds;
+  float2 *twc = lds + mm, *twr = twc + m_c;
+  float *a = reinterpret_cast<float *>(twr + m_r);
+  const long node = blockIdx.x;
+  const long p = node / cm.G;
+  const int g = static_cast<int>(node - p * cm.G);
+  const float *gp = gout + (static_cast<size_t>(p) * K + chan(cm, g)) * mm;
+  for (int i = threadIdx.x; i < mm; i += blockDim.x) a[i] = gp[i];
+  const int sc = tw_n / m_c, sr = tw_n / m_r;
+  for (int i = threadIdx.x; i < m_c; i += blockDim.x) twc[i] = tw[i * sc];
+  for (int i = threadIdx.x; i < m_r; i += blockDim.x) twr[i] = tw[i * sr];
+  __syncthreads();
+  for (int i = threadIdx.x; i < mm; i += blockDim.x) {
+    const int r = i / m_c, kc = i - r * m_c;
+    float2 acc = make_float2(0.f, 0.f);
+    for (int b = 0; b < m_c; ++b) {
+      const float2 w = twc[(b * kc) & (m_c - 1)];
+      const float x = a[r * m_c + b];
+      acc.x += x * w.x;
+      acc.y += x * w.y;
+    }
+    s1[i] = acc;
+  }
+  __syncthreads();
+  float2 *op = ghat + static_cast<size_t>(node) * mm;
+  for (int i = threadIdx.x; i < mm; i += blockDim.x) {
+    const int kr = i / m_c, kc = i - kr * m_c;
+    float2 acc = make_float2(0.f, 0.f);
+    for (int r = 0; r < m_r; ++r) acc = c_add(acc, c_mul(s1[r * m_c + kc], twr[(r * kr) & (m_r - 1)]));
+    op[i] = acc;
+  }
+}
+
+// Second half fused with the inverse row transform that follows it: row (node, k_r) of the
+// M x M gradient spectrum is Ghat[node][k_r mod m_r][k_c mod m_c] phi_rows[k_r] phi_cols[k_c];
+// it is formed in registers, transformed along the row and written once.
+template <int E, int T>
+__global__ __launch_bounds__(E == 32 ? 128 : 256) void k_rows_lowpass_adj(
+    const float2 *__restrict__ ghat, int m_r, int m_c, int lgMr, const float *__restrict__ phi_rows,
+    const float *__restrict__ phi_cols, float2 *__restrict__ dst, long rows,
+    const float2 *__restrict__ tw, int tw_n) {
+  constexpr int NT = E == 32 ? 128 : 256;
+  constexpr int RPB = NT / T, M = E * T;
+  extern __shared__ float2 lds[];
+  const int rl = threadIdx.x / T, t = threadIdx.x % T;
+  const long row_raw = static_cast<long>(blockIdx.x) * RPB + rl;
+  const bool valid = row_raw < rows;
+  const long row = valid ? row_raw : rows - 1;
+  const long node = row >> lgMr;
+  const int kr = static_cast<int>(row & ((1 << lgMr) - 1));
+  const float2 *gp = ghat + (static_cast<size_t>(node) * m_r + (kr & (m_r - 1))) * m_c;
+  const float fr = phi_rows[kr];
+  float2 v[E];
+#pragma unroll
+  for (int i = 0; i < E; ++i) {
+    const int kc = t + T * i;
+    const float f = fr * phi_cols[kc];
+    const float2 x = gp[kc & (m_c - 1)];
+    v[i] = make_float2(x.x * f, x.y * f);
+  }
+  float2 wt[E];
+  load_twiddles<E, T>(wt, t, tw, tw_n);
+  fft_core<E, T, true, true>(v, t, lds + rl * (E * (T + 1)), T + 1, 1, wt);
+  if (!valid) return;
+  float2 *p = dst + static_cast<size_t>(row) * M + t;
+#pragma unroll
+  for (int i = 0; i < E; ++i) p[T * i] = v[i];
+}
+
 // a[i] = Re(a[i]) * y[i] / |y[i]|  (0 where y = 0)
 __global__ __launch_bounds__(256) void k_modback(float2 *__restrict__ a,
                                                  const float2 *__restrict__ y, long count) {
@@ -99,39 +176,51 @@ __global__ __launch_bounds__(256) void k_take_real(const float2 *__restrict__ a,
 
 // dst [S][Sr][Sc] += sum_f filt[f][k_r][k_c] * G[s F + f][k_r mod Mr][k_c mod Mc]
 // (adjoint of: multiply by the F filters, fold to Mr x Mc).  One thread per element
-// (s, q_r, q_c) of the folded grid: it reads its F values of G once (FB at a time) and
-// updates every copy (q_r + a Mr, q_c + b Mc) of dst, so nothing is read twice.
-template <int FB>
+// (q_r, q_c) of the folded grid and group of SB sources: it reads its F values of G once per
+// source (FB at a time) and updates every copy (q_r + a Mr, q_c + b Mc) of dst, loading
+// each filter value once for the SB sources -- nothing is read twice, nothing is shared.
+template <int FB, int SB>
 __global__ __launch_bounds__(256) void k_tile_accum(float2 *__restrict__ dst,
                                                     const float *__restrict__ filt,
                                                     const float2 *__restrict__ G, long count,
-                                                    int F, int lgSr, int lgSc, int lgMr, int lgMc) {
+                                                    long S, int F, int lgSr, int lgSc, int lgMr,
+                                                    int lgMc) {
   const long i = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x;
   if (i >= count) return;
   const int lgM = lgMr + lgMc, lgS = lgSr + lgSc;
-  const long s = i >> lgM;
+  const long s0 = (i >> lgM) * SB;
   const int e = static_cast<int>(i & ((1L << lgM) - 1));
   const int qr = e >> lgMc, qc = e & ((1 << lgMc) - 1);
-  const float2 *gp = G + ((static_cast<size_t>(s) * F) << lgM) + e;
-  float2 *dp = dst + (static_cast<size_t>(s) << lgS);
   const int nr = 1 << (lgSr - lgMr), nc = 1 << (lgSc - lgMc);
   for (int f0 = 0; f0 < F; f0 += FB) {
-    float2 g[FB];
+    float2 g[SB][FB];
 #pragma unroll
-    for (int j = 0; j < FB; ++j)
-      g[j] = f0 + j < F ? gp[static_cast<size_t>(f0 + j) << lgM] : make_float2(0.f, 0.f);
+    for (int k = 0; k < SB; ++k) {
+      const long s = s0 + k < S ? s0 + k : S - 1;  // sources past the end repeat the last, unstored
+#pragma unroll
+      for (int j = 0; j < FB; ++j)
+        g[k][j] = f0 + j < F ? G[((static_cast<size_t>(s) * F + f0 + j) << lgM) + e]
+                             : make_float2(0.f, 0.f);
+    }
     for (int a = 0; a < nr; ++a)
       for (int b = 0; b < nc; ++b) {
         const int o = ((qr + (a << lgMr)) << lgSc) + qc + (b << lgMc);
-        float2 acc = dp[o];
+        float w[FB];
 #pragma unroll
-        for (int j = 0; j < FB; ++j) {
-          const int f = f0 + j < F ? f0 + j : F - 1;
-          const float w = filt[(static_cast<size_t>(f) << lgS) + o];
-          acc.x += g[j].x * w;
-          acc.y += g[j].y * w;
+        for (int j = 0; j < FB; ++j)
+          w[j] = filt[(static_cast<size_t>(f0 + j < F ? f0 + j : F - 1) << lgS) + o];
+#pragma unroll
+        for (int k = 0; k < SB; ++k) {
+          if (s0 + k >= S) break;
+          float2 *dp = dst + (static_cast<size_t>(s0 + k) << lgS) + o;
+          float2 acc = *dp;
+#pragma unroll
+          for (int j = 0; j < FB; ++j) {
+            acc.x += g[k][j].x * w[j];
+            acc.y += g[k][j].y * w[j];
+          }
+          *dp = acc;
         }
-        dp[o] = acc;
       }
   }
 }
@@ -288,6 +377,25 @@ hipError_t cols_modback_t(float2 *data, const float2 *y, long nodes, int Mc, con
   return hipGetLastError();
 }
 
+template <int E, int T>
+hipError_t rows_lowpass_adj_t(const float2 *ghat, long nodes, int m_r, int m_c, int Mr,
+                              const float *phi_rows, const float *phi_cols, float2 *dst,
+                              const float2 *tw, int tw_n, hipStream_t st) {
+  constexpr int NT = E == 32 ? 128 : 256, RPB = NT / T;
+  const long rows = nodes * Mr;
+  const long blocks = (rows + RPB - 1) / RPB;
+  if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
+  const size_t lds = T == 1 ? 0 : static_cast<size_t>(RPB) * E * (T + 1) * sizeof(float2);
+  const std::string name = std::string("k_rows_lowpass_adj<") + std::to_string(E) + ", " +
+                           std::to_string(T) + ">";
+  const double n = static_cast<double>(E) * T;
+  LaunchScope obs(name.c_str(), nodes * 8.0 * m_r * m_c + rows * n * 8,
+                  rows * (5.0 * n * ilog2h(E * T) + 3.0 * n), st);
+  hipLaunchKernelGGL((k_rows_lowpass_adj<E, T>), dim3(static_cast<unsigned>(blocks)), dim3(NT), lds,
+                     st, ghat, m_r, m_c, ilog2h(Mr), phi_rows, phi_cols, dst, rows, tw, tw_n);
+  return hipGetLastError();
+}
+
 }  // namespace
 
 bool backward_side_supported(int m) { return pow2(m) && m >= 4 && m <= 512; }
@@ -380,6 +488,43 @@ hipError_t launch_lowpass_adj(const float *gout, long nodes, ChanMap cm, int K, 
   return hipGetLastError();
 }
 
+// Adjoint lowpass fused with the inverse row transform: dst [nodes][Mr][Mc] = inverse row
+// FFT of ( FFT2(g_out node)[k mod m] phi_rows[k_r] phi_cols[k_c] ); `ghat` is scratch for
+// the small transforms, nodes * m_r * m_c elements.
+hipError_t launch_lowpass_adj_rows(const float *gout, long nodes, ChanMap cm, int K, int m_r,
+                                   int m_c, int Mr, int Mc, const float *phi_rows,
+                                   const float *phi_cols, float2 *ghat, float2 *dst,
+                                   const float2 *tw, int tw_n, hipStream_t st) {
+  if (nodes <= 0) return hipSuccess;
+  if (!pow2(m_r) || !pow2(m_c) || !backward_side_supported(Mr) || !backward_side_supported(Mc) ||
+      m_r > Mr || m_c > Mc || m_r * m_c > 1024 || tw_n % Mc != 0 || tw_n % m_r != 0 ||
+      tw_n % m_c != 0 || nodes > 0x7fffffffL)
+    return hipErrorInvalidValue;
+  {
+    const size_t lds = static_cast<size_t>(m_r) * m_c * (sizeof(float2) + sizeof(float)) +
+                       static_cast<size_t>(m_r + m_c) * sizeof(float2);
+    LaunchScope obs("k_small_fft2", nodes * 12.0 * m_r * m_c, nodes * 8.0 * m_r * m_c * (m_r + m_c),
+                    st);
+    hipLaunchKernelGGL(k_small_fft2, dim3(static_cast<unsigned>(nodes)), dim3(256), lds, st, gout, cm,
+                       K, m_r, m_c, ghat, tw, tw_n);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+#define SCAT_RLA(E_, T_) \
+  return rows_lowpass_adj_t<E_, T_>(ghat, nodes, m_r, m_c, Mr, phi_rows, phi_cols, dst, tw, tw_n, st)
+  switch (Mc) {
+    case 4: SCAT_RLA(4, 1);
+    case 8: SCAT_RLA(8, 1);
+    case 16: SCAT_RLA(16, 1);
+    case 32: SCAT_RLA(16, 2);
+    case 64: SCAT_RLA(16, 4);
+    case 128: SCAT_RLA(16, 8);
+    case 256: SCAT_RLA(16, 16);
+    default: SCAT_RLA(32, 16);
+  }
+#undef SCAT_RLA
+}
+
 hipError_t launch_modback(float2 *a, const float2 *y, long count, hipStream_t st) {
   if (count <= 0) return hipSuccess;
   long blocks = (count + 255) / 256;
@@ -404,14 +549,15 @@ hipError_t launch_tile_accum(float2 *dst, const float *filt, const float2 *G, lo
   if (S <= 0 || F <= 0) return hipSuccess;
   if (!pow2(Sr) || !pow2(Sc) || !pow2(Mr) || !pow2(Mc) || Mr > Sr || Mc > Sc)
     return hipErrorInvalidValue;
-  const long count = S * Mr * Mc;
+  constexpr int SB = 4;
+  const long count = ((S + SB - 1) / SB) * Mr * Mc;
   const long blocks = (count + 255) / 256;
   if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
-  LaunchScope obs("k_tile_accum<8>",
+  LaunchScope obs("k_tile_accum<8, 4>",
                   S * 16.0 * Sr * Sc + static_cast<double>(F) * Sr * Sc * 4 + S * F * 8.0 * Mr * Mc,
                   S * 4.0 * F * Sr * Sc, st);
-  hipLaunchKernelGGL((k_tile_accum<8>), dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st, dst,
-                     filt, G, count, F, ilog2h(Sr), ilog2h(Sc), ilog2h(Mr), ilog2h(Mc));
+  hipLaunchKernelGGL((k_tile_accum<8, SB>), dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st,
+                     dst, filt, G, count, S, F, ilog2h(Sr), ilog2h(Sc), ilog2h(Mr), ilog2h(Mc));
   return hipGetLastError();
 }
 

@@ -544,7 +544,7 @@ struct BwdLayout {
   size_t per_plane = 0;         // bytes
   Layout fwd;                   // xh, t, u of the taped forward pass
   Tape tape;
-  size_t gx = 0, gu = 0, ga = 0;  // elements per plane
+  size_t gx = 0, gu = 0, ga = 0, gh = 0;  // elements per plane
 };
 
 BwdLayout make_bwd_layout(const scat_plan &p, long batch) {
@@ -571,7 +571,10 @@ BwdLayout make_bwd_layout(const scat_plan &p, long batch) {
   b.gx = n;
   b.gu = l * n;
   b.ga = t2;
-  b.per_plane = b.fwd.xh + b.fwd.t + b.fwd.u + b.fwd.v + (b.tape.total + b.gx + b.gu + b.ga) * c8;
+  // spectra of the output-grid gradient planes of one launch (at most L*L, or L, nodes)
+  b.gh = (second ? l * l : l) * static_cast<size_t>(p.n1 >> h.J) * (p.n2 >> h.J);
+  b.per_plane = b.fwd.xh + b.fwd.t + b.fwd.u + b.fwd.v +
+                (b.tape.total + b.gx + b.gu + b.ga + b.gh) * c8;
   long c = static_cast<long>(scratch_budget() / b.per_plane);
   if (c < 1) c = 1;
   if (c > batch) c = batch;
@@ -595,6 +598,7 @@ scat_status backward_2d(scat_plan *p, const float *in, const float *gout, float 
   float2 *GX = after_fwd + bl.tape.total * pc;
   float2 *GU = GX + bl.gx * pc;
   float2 *GA = GU + bl.gu * pc;
+  float2 *GH = GA + bl.ga * pc;
   const float *tab = p->d_tables;
   const float2 *tw = p->d_tw;
   const int tw_n = p->tw_n;
@@ -613,21 +617,29 @@ scat_status backward_2d(scat_plan *p, const float *in, const float *gout, float 
   for (int j1 = 0; j1 < J; ++j1) {
     const int M1r = Nr >> j1, M1c = Nc >> j1;
     const bool kids = h.max_order == 2 && j1 < J - 1;
-    // g_U1^ starts as the adjoint lowpass of g_S1, then collects its children
-    SCAT_TRY(scat::launch_lowpass_adj(go, pc * L, ChanMap{L, L, 0, 1 + j1 * L}, K, m_r, m_c, M1r,
-                                      M1c, tab + p->phi_rows_off[j1], tab + p->phi_cols_off[j1], GU,
-                                      tw, tw_n, st));
+    // g_U1^ starts as the adjoint lowpass of g_S1, then collects its children; without
+    // children the inverse row transform can follow in the same pass
+    if (kids) {
+      SCAT_TRY(scat::launch_lowpass_adj(go, pc * L, ChanMap{L, L, 0, 1 + j1 * L}, K, m_r, m_c, M1r,
+                                        M1c, tab + p->phi_rows_off[j1], tab + p->phi_cols_off[j1],
+                                        GU, tw, tw_n, st));
+    } else {
+      SCAT_TRY(scat::launch_lowpass_adj_rows(go, pc * L, ChanMap{L, L, 0, 1 + j1 * L}, K, m_r, m_c,
+                                             M1r, M1c, tab + p->phi_rows_off[j1],
+                                             tab + p->phi_cols_off[j1], GH, GU, tw, tw_n, st));
+    }
     if (kids) {
       const int octs = J - 1 - j1;
       for (int j2 = j1 + 1; j2 < J; ++j2) {
         const int M2r = Nr >> j2, M2c = Nc >> j2;
         const long nodes = pc * L * L;
-        SCAT_TRY(scat::launch_lowpass_adj(
+        // adjoint lowpass and inverse rows in one pass; then one column pass (inverse,
+        // modulus backward against the tape, forward); then forward rows and the
+        // accumulation into the parent's gradient spectrum (fusing those two was measured
+        // and is not faster: the accumulate is bound by its filter reads)
+        SCAT_TRY(scat::launch_lowpass_adj_rows(
             go, nodes, ChanMap{L * L, L, octs * L, s2_base + (j2 - j1 - 1) * L}, K, m_r, m_c, M2r, M2c,
-            tab + p->phi_rows_off[j2], tab + p->phi_cols_off[j2], GA, tw, tw_n, st));
-        // inverse 2-D transform, modulus backward, forward 2-D transform: rows, then one
-        // column pass that does all three column steps, then rows
-        SCAT_TRY(scat::launch_fft_rows_inplace(GA, nodes * M2r, M2c, true, tw, tw_n, st));
+            tab + p->phi_rows_off[j2], tab + p->phi_cols_off[j2], GH, GA, tw, tw_n, st));
         SCAT_TRY(scat::launch_cols_modback(GA, bl.tape.base + bl.tape.y2_off.at({j1, j2}) * pc, nodes,
                                            M2r, M2c, tw, tw_n, st));
         SCAT_TRY(scat::launch_fft_rows_inplace(GA, nodes * M2r, M2c, false, tw, tw_n, st));
@@ -636,7 +648,7 @@ scat_status backward_2d(scat_plan *p, const float *in, const float *gout, float 
       }
       s2_base += L * L * octs;
     }
-    SCAT_TRY(scat::launch_fft_rows_inplace(GU, pc * L * M1r, M1c, true, tw, tw_n, st));
+    if (kids) SCAT_TRY(scat::launch_fft_rows_inplace(GU, pc * L * M1r, M1c, true, tw, tw_n, st));
     SCAT_TRY(scat::launch_cols_modback(GU, bl.tape.base + bl.tape.y1_off[j1] * pc, pc * L, M1r, M1c,
                                        tw, tw_n, st));
     SCAT_TRY(scat::launch_fft_rows_inplace(GU, pc * L * M1r, M1c, false, tw, tw_n, st));

@@ -115,6 +115,12 @@ hipError_t launch_cols_modback(float2 *data, const float2 *y, long nodes, int Mr
 hipError_t launch_lowpass_adj(const float *gout, long nodes, ChanMap cm, int K, int m_r, int m_c,
                               int Mr, int Mc, const float *phi_rows, const float *phi_cols,
                               float2 *dst, const float2 *tw, int tw_n, hipStream_t st);
+// the same followed by the inverse row transform, in one pass over dst; `ghat` is scratch
+// of nodes * m_r * m_c elements
+hipError_t launch_lowpass_adj_rows(const float *gout, long nodes, ChanMap cm, int K, int m_r,
+                                   int m_c, int Mr, int Mc, const float *phi_rows,
+                                   const float *phi_cols, float2 *ghat, float2 *dst,
+                                   const float2 *tw, int tw_n, hipStream_t st);
 // a[i] = Re(a[i]) * y[i] / |y[i]| (0 where y = 0)
 hipError_t launch_modback(float2 *a, const float2 *y, long count, hipStream_t st);
 hipError_t launch_take_real(const float2 *a, float *out, long count, hipStream_t st);
