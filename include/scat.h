@@ -71,6 +71,28 @@ scat_status scat_plan_create_host(scat_plan **out_plan, int dims, const int *sha
                                   int LQ, int max_order);
 
 /*
+ * Plans for signals of ANY size (each side >= 1).  The paper's usage example (section 4,
+ * "Interface") applies the transform to a 28 x 28 array without saying how the boundary is
+ * handled; the reading taken here: every signal is extended symmetrically to the periodic
+ * grid whose sides are the smallest powers of two >= side + 2^J (the margin's first half
+ * mirrors the far edge, x[n-1], x[n-2], ..., the second half leads up to the near edge of
+ * the next period, ..., x[1], x[0]; reflections repeat with period 2n), the periodic
+ * transform runs on that grid, and the output keeps the samples 2^J k that lie inside the
+ * signal: side ceil(n / 2^J).  scat_forward then takes inputs of `shape` and writes outputs
+ * of scat_plan_out_shape; scat_plan_grid_shape tells the periodic grid; scat_plan_filter
+ * refers to that grid.  scat_backward does not support these plans (SCAT_ERR_ARG).
+ * SCAT_ERR_SHAPE if the periodic grid exceeds what scat_plan_create accepts.
+ */
+scat_status scat_plan_create_padded(scat_plan **out_plan, int dims, const int *shape, int J,
+                                    int LQ, int max_order);
+scat_status scat_plan_create_padded_host(scat_plan **out_plan, int dims, const int *shape, int J,
+                                         int LQ, int max_order);
+
+/* Writes the `dims` side lengths of the periodic grid the plan transforms on (equal to
+ * `shape` for plans made by scat_plan_create). */
+scat_status scat_plan_grid_shape(const scat_plan *plan, int *shape_out);
+
+/*
  * Enqueue the transform of `batch` planes on `stream` (a hipStream_t passed as void*,
  * NULL = the default stream).  Does not synchronise.
  *
@@ -122,7 +144,7 @@ scat_status scat_plan_destroy(scat_plan *plan);
 /* Number of output channels K (1 + J*L + L^2 J(J-1)/2 in 2-D at max_order 2); -1 on NULL. */
 int scat_plan_num_coeffs(const scat_plan *plan);
 
-/* Writes the `dims` output side lengths (shape >> J). */
+/* Writes the `dims` output side lengths (shape >> J; ceil(shape / 2^J) for padded plans). */
 scat_status scat_plan_out_shape(const scat_plan *plan, int *shape_out);
 
 /* Row c of the index table: idx = {order, j1, t1, j2, t2}, unused fields -1.

@@ -191,6 +191,54 @@ def scattering2d_backward(x, g, J, L, max_order=2, bank=None):
     return (np.fft.ifft2(gX) * float(n_r * n_c)).real
 
 
+# ------------------------------------------------------------------ signals of any size
+
+def padded_size(n, J):
+    """Smallest power of two >= n + 2^J: the periodic grid a signal of n samples is
+    extended to (at least 2^J samples of margin in total)."""
+    p = 1
+    while p < n + (1 << J):
+        p *= 2
+    return p
+
+
+def pad_index(n, P):
+    """Source index of every sample of the period-P symmetric extension of n samples.
+
+    The signal sits at 0..n-1.  The margin n..P-1 is filled by half-sample-symmetric
+    reflection: its first ceil((P-n)/2) samples continue past the right edge
+    (x[n-1], x[n-2], ...), the rest lead up to the left edge of the next period
+    (..., x[1], x[0]), so the periodic signal has no jump at either edge.  Reflection
+    repeats with period 2n when the margin is longer than the signal."""
+    h = (P - n + 1) // 2
+    i = np.arange(P)
+    v = np.where(i < n + h, i, i - P)          # virtual position on the infinite extension
+    v = np.mod(v, 2 * n)
+    return np.where(v < n, v, 2 * n - 1 - v)
+
+
+def scattering2d_padded(x, J, L, max_order=2):
+    """Scattering of images of any size (the paper's usage example applies the transform
+    to a 28 x 28 array and does not say how; reading taken): extend symmetrically to the
+    periodic grid of ``padded_size`` per axis, run the periodic cascade there, keep the
+    output samples 2^J n that lie inside the image, n < ceil(N / 2^J) per axis."""
+    x = np.asarray(x, dtype=np.float64)
+    n_r, n_c = x.shape[-2:]
+    P_r, P_c = padded_size(n_r, J), padded_size(n_c, J)
+    xp = x[..., pad_index(n_r, P_r), :][..., :, pad_index(n_c, P_c)]
+    S = scattering2d(xp, J, L, max_order)
+    return S[..., :-(-n_r >> J), :-(-n_c >> J)]
+
+
+def scattering1d_padded(x, J, Q, max_order=2):
+    """1-D counterpart of ``scattering2d_padded``."""
+    x = np.asarray(x, dtype=np.float64)
+    n = x.shape[-1]
+    P = padded_size(n, J)
+    S = scattering1d(x[..., pad_index(n, P)], J, Q, max_order)
+    return S[..., :-(-n >> J)]
+
+
 def scattering2d_plain(x, J, L, max_order=2, bank=None):
     """The three defining equations at full resolution, sampled at 2^J n."""
     x = np.asarray(x, dtype=np.float64)

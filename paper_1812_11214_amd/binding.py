@@ -39,6 +39,12 @@ def lib():
     L.scat_plan_create.restype = ci
     L.scat_plan_create_host.argtypes = [ctypes.POINTER(vp), ci, pi, ci, ci, ci]
     L.scat_plan_create_host.restype = ci
+    L.scat_plan_create_padded.argtypes = [ctypes.POINTER(vp), ci, pi, ci, ci, ci]
+    L.scat_plan_create_padded.restype = ci
+    L.scat_plan_create_padded_host.argtypes = [ctypes.POINTER(vp), ci, pi, ci, ci, ci]
+    L.scat_plan_create_padded_host.restype = ci
+    L.scat_plan_grid_shape.argtypes = [vp, pi]
+    L.scat_plan_grid_shape.restype = ci
     L.scat_forward.argtypes = [vp, vp, vp, cl, vp]
     L.scat_forward.restype = ci
     L.scat_backward.argtypes = [vp, vp, vp, vp, cl, vp]
@@ -76,7 +82,8 @@ EXPORTS = ("scat_plan_create", "scat_plan_create_host", "scat_forward", "scat_pl
            "scat_plan_num_coeffs", "scat_plan_out_shape", "scat_plan_coeff_index",
            "scat_plan_workspace_bytes", "scat_plan_filter", "scat_status_string",
            "scat_plan_timing_begin", "scat_plan_timing_end", "scat_plan_timing_row",
-           "scat_backward", "scat_plan_backward_workspace_bytes")
+           "scat_backward", "scat_plan_backward_workspace_bytes", "scat_plan_create_padded",
+           "scat_plan_create_padded_host", "scat_plan_grid_shape")
 
 
 def scat_status_string(status):
@@ -96,6 +103,23 @@ def _create(fn, shape, J, LQ, max_order):
 def scat_plan_create(shape, J, LQ, max_order=2):
     """Plan for signals of `shape` (1 or 2 sides) on the current GPU; returns a handle."""
     return _create(lib().scat_plan_create, shape, J, LQ, max_order)
+
+
+def scat_plan_create_padded(shape, J, LQ, max_order=2):
+    """Plan for signals of any `shape` (symmetric extension to a periodic grid)."""
+    return _create(lib().scat_plan_create_padded, shape, J, LQ, max_order)
+
+
+def scat_plan_create_padded_host(shape, J, LQ, max_order=2):
+    return _create(lib().scat_plan_create_padded_host, shape, J, LQ, max_order)
+
+
+def scat_plan_grid_shape(plan, dims):
+    arr = (ctypes.c_int * dims)()
+    st = lib().scat_plan_grid_shape(plan, arr)
+    if st != SCAT_OK:
+        raise ScatError(st, "scat_plan_grid_shape")
+    return tuple(arr)
 
 
 def scat_plan_create_host(shape, J, LQ, max_order=2):
@@ -205,15 +229,22 @@ class Scattering:
     """Owner of one plan.  `forward` takes a contiguous float32 CUDA tensor whose trailing
     dims equal `shape`; all leading dims are independent planes."""
 
-    def __init__(self, shape, J, LQ, max_order=2, host_only=False):
+    def __init__(self, shape, J, LQ, max_order=2, host_only=False, padded=False):
+        """padded=True: signals of any size, extended symmetrically to a periodic grid of
+        power-of-two sides (scat_plan_create_padded); else `shape` is that periodic grid."""
         self.shape = tuple(int(s) for s in shape)
         self.dims = len(self.shape)
         self.J, self.LQ, self.max_order = int(J), int(LQ), int(max_order)
+        self.padded = bool(padded)
         self._plan = None
-        create = scat_plan_create_host if host_only else scat_plan_create
+        if padded:
+            create = scat_plan_create_padded_host if host_only else scat_plan_create_padded
+        else:
+            create = scat_plan_create_host if host_only else scat_plan_create
         self._plan = create(self.shape, J, LQ, max_order)
         self.K = scat_plan_num_coeffs(self._plan)
         self.out_shape = scat_plan_out_shape(self._plan, self.dims)
+        self.grid_shape = scat_plan_grid_shape(self._plan, self.dims)
 
     def coeff_index(self):
         return [scat_plan_coeff_index(self._plan, c) for c in range(self.K)]
@@ -222,7 +253,7 @@ class Scattering:
         return scat_plan_workspace_bytes(self._plan, batch)
 
     def filter(self, kind, index, res):
-        shp = tuple(s >> res for s in self.shape)
+        shp = tuple(s >> res for s in self.grid_shape)
         return scat_plan_filter(self._plan, kind, index, res, shp)
 
     def forward(self, x, out=None):

@@ -4,8 +4,8 @@
 // real-linear maps and complex moduli, so its transpose is the chain of adjoints in
 // reverse order:
 //   S = Re IFFT_m(fold(Z^ phi))   ->  g_Z^ = tile(FFT_m(g_S)) phi        (k_lowpass_adj)
-//   Z^ = FFT(Z), Z real           ->  g_Z  = Re IFFT(g_Z^)               (k_fft_* + k_modback)
-//   Z = |y|                       ->  g_y  = g_Z y / |y|  (0 at y = 0)   (k_modback)
+//   Z^ = FFT(Z), Z real           ->  g_Z  = Re IFFT(g_Z^)               (k_fft_rows, k_cols_modback)
+//   Z = |y|                       ->  g_y  = g_Z y / |y|  (0 at y = 0)   (k_cols_modback)
 //   y = IFFT(fold(A^ psi))        ->  g_A^ += tile(FFT(g_y)) psi         (k_fft_* + k_tile_accum)
 // with unnormalised transforms throughout: the filter tables already carry the 1/n of the
 // forward pass, and the adjoint of a product with a real table is the same product.
@@ -153,18 +153,6 @@ __global__ __launch_bounds__(E == 32 ? 128 : 256) void k_rows_lowpass_adj(
   float2 *p = dst + static_cast<size_t>(row) * M + t;
 #pragma unroll
   for (int i = 0; i < E; ++i) p[T * i] = v[i];
-}
-
-// a[i] = Re(a[i]) * y[i] / |y[i]|  (0 where y = 0)
-__global__ __launch_bounds__(256) void k_modback(float2 *__restrict__ a,
-                                                 const float2 *__restrict__ y, long count) {
-  const long stride = static_cast<long>(gridDim.x) * blockDim.x;
-  for (long i = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x; i < count; i += stride) {
-    const float2 v = y[i];
-    const float m2 = v.x * v.x + v.y * v.y;
-    const float s = m2 > 0.f ? a[i].x / __builtin_amdgcn_sqrtf(m2) : 0.f;
-    a[i] = make_float2(v.x * s, v.y * s);
-  }
 }
 
 __global__ __launch_bounds__(256) void k_take_real(const float2 *__restrict__ a,
@@ -523,15 +511,6 @@ hipError_t launch_lowpass_adj_rows(const float *gout, long nodes, ChanMap cm, in
     default: SCAT_RLA(32, 16);
   }
 #undef SCAT_RLA
-}
-
-hipError_t launch_modback(float2 *a, const float2 *y, long count, hipStream_t st) {
-  if (count <= 0) return hipSuccess;
-  long blocks = (count + 255) / 256;
-  if (blocks > 65536 * 16) blocks = 65536 * 16;
-  LaunchScope obs("k_modback", count * 24.0, count * 8.0, st);
-  hipLaunchKernelGGL(k_modback, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st, a, y, count);
-  return hipGetLastError();
 }
 
 hipError_t launch_take_real(const float2 *a, float *out, long count, hipStream_t st) {

@@ -102,6 +102,11 @@ struct scat_plan {
   std::vector<size_t> phi_off;                     // 1-D, per res
   bool fused = false;  // 2-D: the fused row pass can serve every level of this plan
   bool tree = false;   // 2-D: planes small enough for the whole-tree-in-LDS kernel
+  // signals of any size: the caller's shape, symmetrically extended to the plan's periodic
+  // grid before the transform; the output is cropped to user_out
+  bool padded = false;
+  int user_shape[2] = {1, 1};  // 2-D (rows, cols); 1-D (1, n)
+  int user_out[2] = {1, 1};
   std::vector<size_t> taps_off;  // tree: spatial taps of the lowpass along a column, per res
 };
 
@@ -126,6 +131,7 @@ struct Layout {
   size_t per_plane = 0; // scratch bytes per plane
   // element offsets are expressed per plane; buffers are laid out chunk-major
   size_t xh = 0, t = 0, u = 0, v = 0, w = 0;  // per-plane sizes in bytes
+  size_t pad_in = 0, pad_out = 0;             // padded plans: extended input, uncropped output
 };
 
 Layout make_layout(const scat_plan &p, long batch) {
@@ -173,7 +179,12 @@ Layout make_layout(const scat_plan &p, long batch) {
     L.v = second ? q * (n / 2) * c8 : 0;
     L.w = 0;
   }
-  L.per_plane = L.xh + L.t + L.u + L.v + L.w;
+  if (p.padded) {
+    L.pad_in = n * sizeof(float);
+    const size_t m_r = h.dims == 2 ? h.shape[0] >> h.J : 1;
+    L.pad_out = static_cast<size_t>(h.K) * m_r * (h.shape[1] >> h.J) * sizeof(float);
+  }
+  L.per_plane = L.xh + L.t + L.u + L.v + L.w + L.pad_in + L.pad_out;
   long c = static_cast<long>(scratch_budget() / L.per_plane);
   if (c < 1) c = 1;
   if (c > batch) c = batch;
@@ -287,11 +298,25 @@ scat_status upload(scat_plan *p) {
   return SCAT_OK;
 }
 
-scat_status create_common(scat_plan **out_plan, int dims, const int *shape, int J, int LQ,
-                          int max_order, bool device) {
+scat_status create_common(scat_plan **out_plan, int dims, const int *user_shape, int J, int LQ,
+                          int max_order, bool device, bool padded = false) {
   if (out_plan == nullptr) return SCAT_ERR_NULL;
   *out_plan = nullptr;
-  if (shape == nullptr) return SCAT_ERR_NULL;
+  if (user_shape == nullptr) return SCAT_ERR_NULL;
+  int grid[2] = {1, 1};
+  const int *shape = user_shape;
+  if (padded) {
+    // periodic grid: smallest power of two >= n + 2^J per axis
+    if ((dims != 1 && dims != 2) || J < 1 || J > 24) return SCAT_ERR_ARG;
+    for (int d = 0; d < dims; ++d) {
+      if (user_shape[d] < 1 || user_shape[d] > (1 << 24)) return SCAT_ERR_SHAPE;
+      long need = static_cast<long>(user_shape[d]) + (1L << J), g = 1;
+      while (g < need) g *= 2;
+      if (g > (1L << 24)) return SCAT_ERR_SHAPE;
+      grid[d] = static_cast<int>(g);
+    }
+    shape = grid;
+  }
   int v = scat::validate(dims, shape, J, LQ, max_order);
   if (v != 0) return static_cast<scat_status>(v);
   scat_plan *p = new (std::nothrow) scat_plan;
@@ -317,6 +342,14 @@ scat_status create_common(scat_plan **out_plan, int dims, const int *shape, int 
   }
   p->fused = dims == 2 && J <= 4 && scat::rows_fused_supported(p->n1, p->n2, J - 1);
   p->tree = dims == 2 && scat::tree_supported(p->n1, p->n2, J);
+  if (padded) {
+    p->padded = true;
+    for (int d = 0; d < dims; ++d) {
+      const int k = dims == 2 ? d : 1;
+      p->user_shape[k] = user_shape[d];
+      p->user_out[k] = (user_shape[d] + (1 << J) - 1) >> J;
+    }
+  }
   if (device) {
     scat_status s;
     try {
@@ -332,6 +365,51 @@ scat_status create_common(scat_plan **out_plan, int dims, const int *shape, int 
   }
   *out_plan = p;
   return SCAT_OK;
+}
+
+// Symmetric periodic extension of `planes` signals of n_r x n_c to P_r x P_c: the margin's
+// first half mirrors the right/bottom edge, the rest mirrors the left/top edge of the next
+// period, so the periodic signal has no jump; reflections repeat with period 2n.
+__device__ __forceinline__ int pad_source(int i, int n, int P) {
+  const int h = (P - n + 1) / 2;
+  int v = i < n + h ? i : i - P;
+  v %= 2 * n;
+  if (v < 0) v += 2 * n;
+  return v < n ? v : 2 * n - 1 - v;
+}
+
+__global__ __launch_bounds__(256) void k_pad_symmetric(const float *__restrict__ in,
+                                                       float *__restrict__ out, long planes,
+                                                       int n_r, int n_c, int P_r, int P_c) {
+  const long total = planes * P_r * P_c;
+  const long stride = static_cast<long>(gridDim.x) * blockDim.x;
+  for (long i = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x; i < total; i += stride) {
+    const int c = static_cast<int>(i % P_c);
+    const long t = i / P_c;
+    const int r = static_cast<int>(t % P_r);
+    const long p = t / P_r;
+    out[i] = in[(p * n_r + pad_source(r, n_r, P_r)) * n_c + pad_source(c, n_c, P_c)];
+  }
+}
+
+// out [planes*K][o_r][o_c] = in [planes*K][m_r][m_c] restricted to the top-left corner
+__global__ __launch_bounds__(256) void k_crop(const float *__restrict__ in, float *__restrict__ out,
+                                              long maps, int m_r, int m_c, int o_r, int o_c) {
+  const long total = maps * o_r * o_c;
+  const long stride = static_cast<long>(gridDim.x) * blockDim.x;
+  for (long i = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x; i < total; i += stride) {
+    const int c = static_cast<int>(i % o_c);
+    const long t = i / o_c;
+    const int r = static_cast<int>(t % o_r);
+    const long m = t / o_r;
+    out[i] = in[(m * m_r + r) * m_c + c];
+  }
+}
+
+unsigned stream_blocks(long total) {
+  long b = (total + 255) / 256;
+  if (b > 65536 * 16) b = 65536 * 16;
+  return static_cast<unsigned>(b < 1 ? 1 : b);
 }
 
 #define SCAT_TRY(expr)                               \
@@ -730,6 +808,24 @@ scat_status scat_plan_create(scat_plan **out_plan, int dims, const int *shape, i
   return create_common(out_plan, dims, shape, J, LQ, max_order, true);
 }
 
+scat_status scat_plan_create_padded(scat_plan **out_plan, int dims, const int *shape, int J,
+                                    int LQ, int max_order) {
+  return create_common(out_plan, dims, shape, J, LQ, max_order, true, true);
+}
+
+scat_status scat_plan_create_padded_host(scat_plan **out_plan, int dims, const int *shape, int J,
+                                         int LQ, int max_order) {
+  return create_common(out_plan, dims, shape, J, LQ, max_order, false, true);
+}
+
+scat_status scat_plan_grid_shape(const scat_plan *plan, int *shape_out) {
+  if (plan == nullptr || shape_out == nullptr) return SCAT_ERR_NULL;
+  const scat::HostPlan &h = plan->host;
+  if (h.dims == 2) shape_out[0] = h.shape[0];
+  shape_out[h.dims == 2 ? 1 : 0] = h.shape[1];
+  return SCAT_OK;
+}
+
 scat_status scat_plan_create_host(scat_plan **out_plan, int dims, const int *shape, int J, int LQ,
                                   int max_order) {
   return create_common(out_plan, dims, shape, J, LQ, max_order, false);
@@ -758,13 +854,41 @@ scat_status scat_forward(scat_plan *plan, const float *in, float *out, long batc
     explicit ObserverScope(scat::LaunchObserver *o) { scat::set_launch_observer(o); }
     ~ObserverScope() { scat::set_launch_observer(nullptr); }
   } scope(plan->timer.enabled ? &plan->timer : nullptr);
+  const scat::HostPlan &h = plan->host;
   for (long p0 = 0; p0 < batch; p0 += lay.chunk) {
     long pc = batch - p0 < lay.chunk ? batch - p0 : lay.chunk;
-    scat_status s = plan->host.dims == 1 ? forward_1d(plan, in, out, p0, pc, lay, st)
-                    : plan->tree         ? forward_2d_tree(plan, in, out, p0, pc, lay, st)
-                    : plan->fused        ? forward_2d_fused(plan, in, out, p0, pc, lay, st)
-                                         : forward_2d(plan, in, out, p0, pc, lay, st);
+    const float *cin = in;
+    float *cout = out;
+    long cp0 = p0;
+    float *xp = nullptr, *op = nullptr;
+    if (plan->padded) {
+      // extend this chunk's signals into scratch and transform them as planes 0..pc-1
+      char *tail = static_cast<char *>(plan->d_scratch) +
+                   (lay.xh + lay.t + lay.u + lay.v + lay.w) * static_cast<size_t>(lay.chunk);
+      xp = reinterpret_cast<float *>(tail);
+      op = reinterpret_cast<float *>(tail + lay.pad_in * static_cast<size_t>(lay.chunk));
+      const int ur = plan->user_shape[0], uc = plan->user_shape[1];
+      hipLaunchKernelGGL(k_pad_symmetric, dim3(stream_blocks(pc * h.shape[0] * h.shape[1])),
+                         dim3(256), 0, st, in + static_cast<size_t>(p0) * ur * uc, xp, pc, ur, uc,
+                         h.shape[0], h.shape[1]);
+      if (hipGetLastError() != hipSuccess) return SCAT_ERR_DEVICE;
+      cin = xp;
+      cout = op;
+      cp0 = 0;
+    }
+    scat_status s = h.dims == 1 ? forward_1d(plan, cin, cout, cp0, pc, lay, st)
+                    : plan->tree  ? forward_2d_tree(plan, cin, cout, cp0, pc, lay, st)
+                    : plan->fused ? forward_2d_fused(plan, cin, cout, cp0, pc, lay, st)
+                                  : forward_2d(plan, cin, cout, cp0, pc, lay, st);
     if (s != SCAT_OK) return s;
+    if (plan->padded) {
+      const int m_r = h.dims == 2 ? h.shape[0] >> h.J : 1, m_c = h.shape[1] >> h.J;
+      const int o_r = plan->user_out[0], o_c = plan->user_out[1];
+      hipLaunchKernelGGL(k_crop, dim3(stream_blocks(pc * h.K * o_r * o_c)), dim3(256), 0, st, op,
+                         out + static_cast<size_t>(p0) * h.K * o_r * o_c, pc * h.K, m_r, m_c, o_r,
+                         o_c);
+      if (hipGetLastError() != hipSuccess) return SCAT_ERR_DEVICE;
+    }
   }
   return SCAT_OK;
 }
@@ -774,7 +898,7 @@ scat_status scat_backward(scat_plan *plan, const float *in, const float *grad_ou
   if (plan == nullptr) return SCAT_ERR_NULL;
   if (batch < 0) return SCAT_ERR_ARG;
   const scat::HostPlan &h = plan->host;
-  if (h.dims != 2) return SCAT_ERR_ARG;
+  if (h.dims != 2 || plan->padded) return SCAT_ERR_ARG;
   // every grid of the cascade must have sides the plain transforms handle, and the output
   // grid must fit the adjoint lowpass kernel's LDS stage
   const int small_r = plan->n1 >> (h.J - 1), small_c = plan->n2 >> (h.J - 1);
@@ -811,7 +935,7 @@ scat_status scat_backward(scat_plan *plan, const float *in, const float *grad_ou
 }
 
 size_t scat_plan_backward_workspace_bytes(const scat_plan *plan, long batch) {
-  if (plan == nullptr || batch <= 0 || plan->host.dims != 2) return 0;
+  if (plan == nullptr || batch <= 0 || plan->host.dims != 2 || plan->padded) return 0;
   const BwdLayout bl = make_bwd_layout(*plan, batch);
   return bl.per_plane * static_cast<size_t>(bl.chunk);
 }
@@ -836,7 +960,10 @@ int scat_plan_num_coeffs(const scat_plan *plan) { return plan ? plan->host.K : -
 scat_status scat_plan_out_shape(const scat_plan *plan, int *shape_out) {
   if (plan == nullptr || shape_out == nullptr) return SCAT_ERR_NULL;
   const scat::HostPlan &h = plan->host;
-  if (h.dims == 2) {
+  if (plan->padded) {
+    if (h.dims == 2) shape_out[0] = plan->user_out[0];
+    shape_out[h.dims == 2 ? 1 : 0] = plan->user_out[1];
+  } else if (h.dims == 2) {
     shape_out[0] = h.shape[0] >> h.J;
     shape_out[1] = h.shape[1] >> h.J;
   } else {

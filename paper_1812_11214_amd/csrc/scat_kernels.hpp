@@ -121,8 +121,6 @@ hipError_t launch_lowpass_adj_rows(const float *gout, long nodes, ChanMap cm, in
                                    int m_c, int Mr, int Mc, const float *phi_rows,
                                    const float *phi_cols, float2 *ghat, float2 *dst,
                                    const float2 *tw, int tw_n, hipStream_t st);
-// a[i] = Re(a[i]) * y[i] / |y[i]| (0 where y = 0)
-hipError_t launch_modback(float2 *a, const float2 *y, long count, hipStream_t st);
 hipError_t launch_take_real(const float2 *a, float *out, long count, hipStream_t st);
 // dst [S][Sr][Sc] += sum_f filt[f] * G[s F + f][k_r mod Mr][k_c mod Mc]
 hipError_t launch_tile_accum(float2 *dst, const float *filt, const float2 *G, long S, int F, int Sr,

@@ -1,0 +1,111 @@
+"""Signals of any size: symmetric extension to a periodic power-of-two grid.
+
+The paper applies the transform to a 28 x 28 array (section 4, "Interface") without
+describing the boundary handling, so the extension rule is this build's reading --
+"parity unpinned by the paper".  What is pinned here: the oracle's extension against
+numpy's own symmetric padding, the grid and output sizes, exactness for constant signals,
+and (GPU) the library against the oracle through the C ABI.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import paper_1812_11214_amd as scat
+from oracle.scattering import pad_index, padded_size
+
+
+@pytest.mark.parametrize("n,J", [(28, 2), (5, 3), (100, 4), (32, 2), (1, 2), (3, 1), (1000, 6)])
+def test_extension_matches_numpy_symmetric_pad(n, J):
+    P = padded_size(n, J)
+    assert P & (P - 1) == 0 and P >= n + (1 << J) and P // 2 < n + (1 << J)
+    h = (P - n + 1) // 2
+    lo = P - n - h
+    x = np.arange(n) * 1.5 + 0.25
+    want = np.roll(np.pad(x, (lo, h), mode="symmetric"), -lo)
+    assert np.array_equal(x[pad_index(n, P)], want)
+    # the periodic extension has no jump at either edge of the signal
+    xe = x[pad_index(n, P)]
+    assert xe[n] == x[n - 1] and xe[P - 1] == x[0]
+
+
+def test_oracle_padded_shapes_and_constant_signal():
+    S = oracle.scattering2d_padded(np.zeros((3, 28, 28)), 2, 8)
+    assert S.shape == (3, 81, 7, 7)
+    S1 = oracle.scattering1d_padded(np.zeros((2, 1000)), 4, 2)
+    assert S1.shape[-1] == 63
+    c = oracle.scattering2d_padded(np.full((30, 50), 2.5), 3, 4)
+    assert c.shape[-2:] == (4, 7)
+    assert np.abs(c[0] - 2.5).max() < 1e-12 and np.abs(c[1:]).max() < 1e-12
+
+
+def test_oracle_padded_equals_periodic_transform_of_the_extension():
+    rng = np.random.default_rng(0)
+    x = rng.standard_normal((2, 20, 28))
+    J, L = 2, 3
+    Pr, Pc = padded_size(20, J), padded_size(28, J)
+    xp = x[:, pad_index(20, Pr), :][:, :, pad_index(28, Pc)]
+    want = oracle.scattering2d(xp, J, L)[..., :5, :7]
+    assert np.array_equal(oracle.scattering2d_padded(x, J, L), want)
+
+
+def test_host_plan_sizes():
+    for shape, J, grid, out in [((28, 28), 2, (32, 32), (7, 7)), ((30, 50), 3, (64, 64), (4, 7)),
+                                ((1000,), 4, (1024,), (63,)), ((256, 256), 3, (512, 512), (32, 32)),
+                                ((1, 9), 1, (4, 16), (1, 5))]:
+        p = scat.Scattering(shape, J, 2, host_only=True, padded=True)
+        try:
+            assert p.grid_shape == grid and p.out_shape == out
+        finally:
+            p.close()
+    with pytest.raises(scat.ScatError):
+        scat.Scattering((5000, 8), 2, 2, host_only=True, padded=True)   # grid 8192 > 4096
+    with pytest.raises(scat.ScatError):
+        scat.Scattering((0, 8), 2, 2, host_only=True, padded=True)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("shape,J,LQ,batch", [((28, 28), 2, 8, 6), ((30, 50), 3, 4, 3),
+                                              ((200, 120), 3, 3, 2), ((5, 7), 2, 2, 4),
+                                              ((256, 256), 3, 8, 1), ((1000,), 4, 2, 3),
+                                              ((4000,), 6, 8, 2)])
+def test_padded_parity_gpu(shape, J, LQ, batch):
+    import torch
+    rng = np.random.default_rng(sum(shape) + J)
+    x = rng.standard_normal((batch,) + shape).astype(np.float32)
+    plan = scat.Scattering(shape, J, LQ, padded=True)
+    try:
+        y = plan.forward(torch.from_numpy(x).cuda())
+        torch.cuda.synchronize()
+        got = y.cpu().numpy().astype(np.float64)
+        assert got.shape[1:] == (plan.K,) + plan.out_shape
+        rows = plan.coeff_index()
+    finally:
+        plan.close()
+    if len(shape) == 2:
+        want = oracle.scattering2d_padded(x.astype(np.float64), J, LQ)
+    else:
+        want = oracle.scattering1d_padded(x.astype(np.float64), J, LQ)
+    order = np.array([r[0] for r in rows])
+    for p in range(batch):
+        for o in (0, 1, 2):
+            sel = order == o
+            err = np.abs(got[p][sel] - want[p][sel]).max() / np.abs(want[p][sel]).max()
+            assert err <= 1e-4, (p, o, err)
+
+
+@pytest.mark.gpu
+def test_padded_chunks_and_backward_refusal():
+    import torch
+    rng = np.random.default_rng(5)
+    x = torch.from_numpy(rng.standard_normal((7, 28, 28)).astype(np.float32)).cuda()
+    plan = scat.Scattering((28, 28), 2, 8, padded=True)
+    try:
+        a = plan.forward(x)
+        b = torch.cat([plan.forward(x[:3].contiguous()), plan.forward(x[3:].contiguous())])
+        torch.cuda.synchronize()
+        assert torch.equal(a, b)
+        g = torch.zeros_like(a)
+        with pytest.raises(scat.ScatError):
+            plan.backward(x, g)
+    finally:
+        plan.close()
