@@ -64,6 +64,19 @@ def test_2d_shapes(shape, J, L, max_order):
     _check_2d(x, J, L, max_order)
 
 
+@pytest.mark.parametrize("shape,J,L,max_order,batch", [
+    ((512, 64), 3, 3, 2, 2), ((64, 512), 2, 5, 2, 2), ((256, 256), 5, 2, 2, 1),
+    ((1024, 32), 2, 5, 2, 1), ((512, 512), 2, 6, 1, 1), ((128, 128), 6, 3, 2, 2),
+])
+def test_2d_stored_spectrum_path(shape, J, L, max_order, batch):
+    """Shapes the fused row pass does not take (a side of 512 or more, or more than four
+    octaves): full spectra are stored and re-read per level; numbers of angles that are
+    not multiples of the filters-per-read of that kernel; rectangular grids."""
+    rng = np.random.default_rng(sum(shape) * 13 + J * 5 + L)
+    x = rng.standard_normal((batch,) + shape).astype(np.float32)
+    _check_2d(x, J, L, max_order)
+
+
 def test_2d_edge_inputs():
     rng = np.random.default_rng(5)
     x = np.zeros((4, 32, 32), dtype=np.float32)
