@@ -80,7 +80,9 @@ scat_status scat_plan_create_host(scat_plan **out_plan, int dims, const int *sha
  * transform runs on that grid, and the output keeps the samples 2^J k that lie inside the
  * signal: side ceil(n / 2^J).  scat_forward then takes inputs of `shape` and writes outputs
  * of scat_plan_out_shape; scat_plan_grid_shape tells the periodic grid; scat_plan_filter
- * refers to that grid.  scat_backward does not support these plans (SCAT_ERR_ARG).
+ * refers to that grid.  scat_backward works on these plans too (2-D): it applies the
+ * adjoints of the crop (zero extension) and of the symmetric extension (every sample
+ * collects the gradients of its mirror images) around the periodic backward pass.
  * SCAT_ERR_SHAPE if the periodic grid exceeds what scat_plan_create accepts.
  */
 scat_status scat_plan_create_padded(scat_plan **out_plan, int dims, const int *shape, int J,

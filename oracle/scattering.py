@@ -230,6 +230,27 @@ def scattering2d_padded(x, J, L, max_order=2):
     return S[..., :-(-n_r >> J), :-(-n_c >> J)]
 
 
+def scattering2d_padded_backward(x, g, J, L, max_order=2):
+    """Gradient of sum(g * scattering2d_padded(x)) with respect to x: zero-extend g to the
+    periodic grid's output (adjoint of the crop), run the periodic backward pass on the
+    extended image, and add every extended sample's gradient to the pixel it mirrors
+    (adjoint of the symmetric extension)."""
+    x = np.asarray(x, dtype=np.float64)
+    g = np.asarray(g, dtype=np.float64)
+    n_r, n_c = x.shape[-2:]
+    P_r, P_c = padded_size(n_r, J), padded_size(n_c, J)
+    ir, ic = pad_index(n_r, P_r), pad_index(n_c, P_c)
+    xp = x[..., ir, :][..., :, ic]
+    gp = np.zeros(g.shape[:-2] + (P_r >> J, P_c >> J))
+    gp[..., :g.shape[-2], :g.shape[-1]] = g
+    gxp = scattering2d_backward(xp, gp, J, L, max_order)
+    rows = np.zeros(x.shape[:-2] + (n_r, P_c))
+    np.add.at(rows, (Ellipsis, ir, slice(None)), gxp)
+    out = np.zeros(x.shape)
+    np.add.at(out, (Ellipsis, ic), rows)
+    return out
+
+
 def scattering1d_padded(x, J, Q, max_order=2):
     """1-D counterpart of ``scattering2d_padded``."""
     x = np.asarray(x, dtype=np.float64)

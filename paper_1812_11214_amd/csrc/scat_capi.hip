@@ -406,6 +406,54 @@ __global__ __launch_bounds__(256) void k_crop(const float *__restrict__ in, floa
   }
 }
 
+// Adjoint of k_crop: out [maps][m_r][m_c] = in [maps][o_r][o_c] in the top-left corner, 0 elsewhere
+__global__ __launch_bounds__(256) void k_uncrop(const float *__restrict__ in, float *__restrict__ out,
+                                                long maps, int m_r, int m_c, int o_r, int o_c) {
+  const long total = maps * m_r * m_c;
+  const long stride = static_cast<long>(gridDim.x) * blockDim.x;
+  for (long i = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x; i < total; i += stride) {
+    const int c = static_cast<int>(i % m_c);
+    const long t = i / m_c;
+    const int r = static_cast<int>(t % m_r);
+    const long m = t / m_r;
+    out[i] = (r < o_r && c < o_c) ? in[(m * o_r + r) * o_c + c] : 0.f;
+  }
+}
+
+// Positions of the period-P extension that mirror sample r of n (see pad_source): virtual
+// positions v = r + 2 n t and v = 2 n - 1 - r + 2 n t inside [-(P - n - h), n + h), stored
+// at v (v >= 0) or v + P.  Calls f(position) for each.
+template <class Fn>
+__device__ __forceinline__ void for_each_image(int r, int n, int P, Fn f) {
+  const int h = (P - n + 1) / 2, lo = P - n - h;
+  const int reps = P / (2 * n) + 1;
+  for (int t = -reps; t <= reps; ++t) {
+    const int v0 = r + 2 * n * t, v1 = 2 * n - 1 - r + 2 * n * t;
+    if (v0 >= -lo && v0 < n + h) f(v0 >= 0 ? v0 : v0 + P);
+    if (v1 >= -lo && v1 < n + h) f(v1 >= 0 ? v1 : v1 + P);
+  }
+}
+
+// Adjoint of k_pad_symmetric: every sample collects the gradients of all its mirror images.
+__global__ __launch_bounds__(256) void k_unpad_symmetric(const float *__restrict__ gp,
+                                                         float *__restrict__ gx, long planes,
+                                                         int n_r, int n_c, int P_r, int P_c) {
+  const long total = planes * n_r * n_c;
+  const long stride = static_cast<long>(gridDim.x) * blockDim.x;
+  for (long i = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x; i < total; i += stride) {
+    const int c = static_cast<int>(i % n_c);
+    const long t = i / n_c;
+    const int r = static_cast<int>(t % n_r);
+    const long p = t / n_r;
+    const float *plane = gp + p * P_r * P_c;
+    float acc = 0.f;
+    for_each_image(r, n_r, P_r, [&](int ir) {
+      for_each_image(c, n_c, P_c, [&](int ic) { acc += plane[static_cast<size_t>(ir) * P_c + ic]; });
+    });
+    gx[i] = acc;
+  }
+}
+
 unsigned stream_blocks(long total) {
   long b = (total + 255) / 256;
   if (b > 65536 * 16) b = 65536 * 16;
@@ -623,6 +671,7 @@ struct BwdLayout {
   Layout fwd;                   // xh, t, u of the taped forward pass
   Tape tape;
   size_t gx = 0, gu = 0, ga = 0, gh = 0;  // elements per plane
+  size_t pad_floats = 0;  // padded plans: extended input + extended gradients, floats per plane
 };
 
 BwdLayout make_bwd_layout(const scat_plan &p, long batch) {
@@ -651,8 +700,10 @@ BwdLayout make_bwd_layout(const scat_plan &p, long batch) {
   b.ga = t2;
   // spectra of the output-grid gradient planes of one launch (at most L*L, or L, nodes)
   b.gh = (second ? l * l : l) * static_cast<size_t>(p.n1 >> h.J) * (p.n2 >> h.J);
+  if (p.padded)
+    b.pad_floats = 2 * n + static_cast<size_t>(h.K) * (p.n1 >> h.J) * (p.n2 >> h.J);
   b.per_plane = b.fwd.xh + b.fwd.t + b.fwd.u + b.fwd.v +
-                (b.tape.total + b.gx + b.gu + b.ga + b.gh) * c8;
+                (b.tape.total + b.gx + b.gu + b.ga + b.gh) * c8 + b.pad_floats * sizeof(float);
   long c = static_cast<long>(scratch_budget() / b.per_plane);
   if (c < 1) c = 1;
   if (c > batch) c = batch;
@@ -898,7 +949,7 @@ scat_status scat_backward(scat_plan *plan, const float *in, const float *grad_ou
   if (plan == nullptr) return SCAT_ERR_NULL;
   if (batch < 0) return SCAT_ERR_ARG;
   const scat::HostPlan &h = plan->host;
-  if (h.dims != 2 || plan->padded) return SCAT_ERR_ARG;
+  if (h.dims != 2) return SCAT_ERR_ARG;
   // every grid of the cascade must have sides the plain transforms handle, and the output
   // grid must fit the adjoint lowpass kernel's LDS stage
   const int small_r = plan->n1 >> (h.J - 1), small_c = plan->n2 >> (h.J - 1);
@@ -928,14 +979,39 @@ scat_status scat_backward(scat_plan *plan, const float *in, const float *grad_ou
   } scope(plan->timer.enabled ? &plan->timer : nullptr);
   for (long p0 = 0; p0 < batch; p0 += bl.chunk) {
     long pc = batch - p0 < bl.chunk ? batch - p0 : bl.chunk;
-    scat_status s = backward_2d(plan, in, grad_out, grad_in, p0, pc, bl, st);
+    if (!plan->padded) {
+      scat_status s = backward_2d(plan, in, grad_out, grad_in, p0, pc, bl, st);
+      if (s != SCAT_OK) return s;
+      continue;
+    }
+    // padded plan: extend the input and (with zeros) the output gradient to the periodic
+    // grid, run the periodic backward pass there, fold the extended gradient back
+    const size_t n = static_cast<size_t>(plan->n1) * plan->n2;
+    const int m_r = plan->n1 >> h.J, m_c = plan->n2 >> h.J;
+    const int ur = plan->user_shape[0], uc = plan->user_shape[1];
+    const int o_r = plan->user_out[0], o_c = plan->user_out[1];
+    float *xp = reinterpret_cast<float *>(static_cast<char *>(plan->d_scratch) +
+                                          (bl.per_plane - bl.pad_floats * sizeof(float)) *
+                                              static_cast<size_t>(bl.chunk));
+    float *gxp = xp + n * bl.chunk;
+    float *gop = gxp + n * bl.chunk;
+    hipLaunchKernelGGL(k_pad_symmetric, dim3(stream_blocks(pc * static_cast<long>(n))), dim3(256), 0,
+                       st, in + static_cast<size_t>(p0) * ur * uc, xp, pc, ur, uc, plan->n1, plan->n2);
+    hipLaunchKernelGGL(k_uncrop, dim3(stream_blocks(pc * h.K * m_r * m_c)), dim3(256), 0, st,
+                       grad_out + static_cast<size_t>(p0) * h.K * o_r * o_c, gop, pc * h.K, m_r, m_c,
+                       o_r, o_c);
+    if (hipGetLastError() != hipSuccess) return SCAT_ERR_DEVICE;
+    scat_status s = backward_2d(plan, xp, gop, gxp, 0, pc, bl, st);
     if (s != SCAT_OK) return s;
+    hipLaunchKernelGGL(k_unpad_symmetric, dim3(stream_blocks(pc * ur * uc)), dim3(256), 0, st, gxp,
+                       grad_in + static_cast<size_t>(p0) * ur * uc, pc, ur, uc, plan->n1, plan->n2);
+    if (hipGetLastError() != hipSuccess) return SCAT_ERR_DEVICE;
   }
   return SCAT_OK;
 }
 
 size_t scat_plan_backward_workspace_bytes(const scat_plan *plan, long batch) {
-  if (plan == nullptr || batch <= 0 || plan->host.dims != 2 || plan->padded) return 0;
+  if (plan == nullptr || batch <= 0 || plan->host.dims != 2) return 0;
   const BwdLayout bl = make_bwd_layout(*plan, batch);
   return bl.per_plane * static_cast<size_t>(bl.chunk);
 }

@@ -94,7 +94,7 @@ def test_padded_parity_gpu(shape, J, LQ, batch):
 
 
 @pytest.mark.gpu
-def test_padded_chunks_and_backward_refusal():
+def test_padded_chunks():
     import torch
     rng = np.random.default_rng(5)
     x = torch.from_numpy(rng.standard_normal((7, 28, 28)).astype(np.float32)).cuda()
@@ -104,8 +104,52 @@ def test_padded_chunks_and_backward_refusal():
         b = torch.cat([plan.forward(x[:3].contiguous()), plan.forward(x[3:].contiguous())])
         torch.cuda.synchronize()
         assert torch.equal(a, b)
-        g = torch.zeros_like(a)
-        with pytest.raises(scat.ScatError):
-            plan.backward(x, g)
     finally:
         plan.close()
+
+
+def test_oracle_padded_backward_matches_finite_differences():
+    rng = np.random.default_rng(1)
+    for shape, J, L in [((14, 10), 2, 3), ((5, 7), 1, 2)]:
+        x = rng.standard_normal((2,) + shape)
+        S = oracle.scattering2d_padded(x, J, L)
+        g = rng.standard_normal(S.shape)
+        gx = oracle.scattering2d_padded_backward(x, g, J, L)
+        d = rng.standard_normal(x.shape)
+        eps = 1e-6
+        f = lambda z: float(np.sum(g * oracle.scattering2d_padded(z, J, L)))
+        fd = (f(x + eps * d) - f(x - eps * d)) / (2 * eps)
+        assert abs(fd - np.sum(gx * d)) <= 1e-6 * max(abs(fd), 1e-3)
+
+
+def test_extension_adjoint_identity():
+    """<pad(x), y> = <x, pad^T(y)> with pad^T as used by the oracle's backward pass."""
+    rng = np.random.default_rng(2)
+    for n, J in [(28, 2), (5, 3), (3, 4)]:
+        P = padded_size(n, J)
+        idx = pad_index(n, P)
+        x, y = rng.standard_normal(n), rng.standard_normal(P)
+        yt = np.zeros(n)
+        np.add.at(yt, idx, y)
+        assert abs(np.dot(x[idx], y) - np.dot(x, yt)) < 1e-12
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("shape,J,L,batch", [((28, 28), 2, 8, 4), ((30, 50), 3, 4, 2),
+                                             ((5, 7), 2, 2, 3), ((100, 36), 3, 3, 2)])
+def test_padded_backward_parity_gpu(shape, J, L, batch):
+    import torch
+    rng = np.random.default_rng(sum(shape) * 3 + J)
+    x = rng.standard_normal((batch,) + shape).astype(np.float32)
+    plan = scat.Scattering(shape, J, L, padded=True)
+    try:
+        g = rng.standard_normal((batch, plan.K) + plan.out_shape).astype(np.float32)
+        gi = plan.backward(torch.from_numpy(x).cuda(), torch.from_numpy(g).cuda())
+        torch.cuda.synchronize()
+        got = gi.cpu().numpy().astype(np.float64)
+    finally:
+        plan.close()
+    want = oracle.scattering2d_padded_backward(x.astype(np.float64), g.astype(np.float64), J, L)
+    for p in range(batch):
+        err = np.abs(got[p] - want[p]).max() / np.abs(want[p]).max()
+        assert err <= 1e-4, (p, err)
