@@ -90,6 +90,22 @@ scat_status scat_plan_create_padded(scat_plan **out_plan, int dims, const int *s
 scat_status scat_plan_create_padded_host(scat_plan **out_plan, int dims, const int *shape, int J,
                                          int LQ, int max_order);
 
+/*
+ * General form of plan creation.  `oversampling` = o >= 0 keeps every signal 2^o times finer
+ * than the default schedule (the paper, section 2 "Implementation", only says that
+ * intermediate signals are downsampled; o is the knob for how much): after a wavelet of
+ * octave j the grid is subsampled by 2^max(j-o, 0) and the output by 2^max(J-o, 0), so the
+ * output has sides shape >> max(J-o, 0).  With o >= J nothing is subsampled and the output,
+ * read at the samples 2^J k, is the section-2 definition itself.  flags: bitwise OR of
+ * SCAT_PLAN_PADDED (signals of any size, see scat_plan_create_padded) and
+ * SCAT_PLAN_HOST_ONLY (no GPU, see scat_plan_create_host).  scat_backward needs an output
+ * grid of at most 1024 points, which limits o there.
+ */
+#define SCAT_PLAN_PADDED 1
+#define SCAT_PLAN_HOST_ONLY 2
+scat_status scat_plan_create_ex(scat_plan **out_plan, int dims, const int *shape, int J, int LQ,
+                                int max_order, int oversampling, int flags);
+
 /* Writes the `dims` side lengths of the periodic grid the plan transforms on (equal to
  * `shape` for plans made by scat_plan_create). */
 scat_status scat_plan_grid_shape(const scat_plan *plan, int *shape_out);
@@ -146,7 +162,8 @@ scat_status scat_plan_destroy(scat_plan *plan);
 /* Number of output channels K (1 + J*L + L^2 J(J-1)/2 in 2-D at max_order 2); -1 on NULL. */
 int scat_plan_num_coeffs(const scat_plan *plan);
 
-/* Writes the `dims` output side lengths (shape >> J; ceil(shape / 2^J) for padded plans). */
+/* Writes the `dims` output side lengths: shape >> max(J - oversampling, 0), rounded up for
+ * padded plans. */
 scat_status scat_plan_out_shape(const scat_plan *plan, int *shape_out);
 
 /* Row c of the index table: idx = {order, j1, t1, j2, t2}, unused fields -1.

@@ -85,11 +85,16 @@ def sub(F, r, axes):
 
 # ------------------------------------------------------------------ 2-D cascade
 
-def scattering2d(x, J, L, max_order=2, bank=None):
+def scattering2d(x, J, L, max_order=2, bank=None, oversampling=0):
     """Order-<=2 scattering of real images, Fourier-domain cascade with subsampling.
 
     x: array (..., N_r, N_c), N_r and N_c multiples of 2^J.
-    Returns float64 array (..., K, N_r >> J, N_c >> J).
+    Returns float64 array (..., K, N_r >> rJ, N_c >> rJ), rJ = max(J - oversampling, 0).
+
+    oversampling = o keeps every signal 2^o times finer than the default schedule: after
+    a wavelet of octave j the grid is subsampled by 2^max(j - o, 0), the output by
+    2^max(J - o, 0).  With o >= J nothing is subsampled and the result, read at the
+    samples 2^J n, is the paper's definition itself (``scattering2d_plain``).
     """
     x = np.asarray(x, dtype=np.float64)
     n_r, n_c = x.shape[-2:]
@@ -98,26 +103,30 @@ def scattering2d(x, J, L, max_order=2, bank=None):
     psi_hat, phi_hat = bank['psi_hat'], bank['phi_hat']
     ax = (-2, -1)
     lead = x.shape[:-2]
+    res = lambda j: max(j - oversampling, 0)   # log2 of the subsampling after octave j
+    rJ = res(J)
     X = np.fft.fft2(x)
     out = []
-    # S0 = (x conv phi_J) sampled at 2^J n
-    out.append(np.fft.ifft2(sub(X * phi_hat, J, ax)).real)
+    # S0 = (x conv phi_J) sampled at 2^rJ n
+    out.append(np.fft.ifft2(sub(X * phi_hat, rJ, ax)).real)
     s2 = []
     for j1 in range(J):
-        phi_j1 = fold(phi_hat, j1, ax)
+        r1 = res(j1)
+        phi_r1 = fold(phi_hat, r1, ax)
         for t1 in range(L):
-            U1 = np.abs(np.fft.ifft2(sub(X * psi_hat[j1, t1], j1, ax)))
+            U1 = np.abs(np.fft.ifft2(sub(X * psi_hat[j1, t1], r1, ax)))
             U1h = np.fft.fft2(U1)
-            out.append(np.fft.ifft2(sub(U1h * phi_j1, J - j1, ax)).real)
+            out.append(np.fft.ifft2(sub(U1h * phi_r1, rJ - r1, ax)).real)
             if max_order < 2:
                 continue
             for j2 in range(j1 + 1, J):
-                phi_j2 = fold(phi_hat, j2, ax)
+                r2 = res(j2)
+                phi_r2 = fold(phi_hat, r2, ax)
                 for t2 in range(L):
-                    psi_r = fold(psi_hat[j2, t2], j1, ax)
-                    V = np.abs(np.fft.ifft2(sub(U1h * psi_r, j2 - j1, ax)))
+                    psi_r = fold(psi_hat[j2, t2], r1, ax)
+                    V = np.abs(np.fft.ifft2(sub(U1h * psi_r, r2 - r1, ax)))
                     Vh = np.fft.fft2(V)
-                    s2.append(np.fft.ifft2(sub(Vh * phi_j2, J - j2, ax)).real)
+                    s2.append(np.fft.ifft2(sub(Vh * phi_r2, rJ - r2, ax)).real)
     out.extend(s2)
     return np.stack(out, axis=len(lead))
 
@@ -131,7 +140,7 @@ def tile(G, r, axes):
     return np.tile(G, reps)
 
 
-def scattering2d_backward(x, g, J, L, max_order=2, bank=None):
+def scattering2d_backward(x, g, J, L, max_order=2, bank=None, oversampling=0):
     """Gradient of sum(g * scattering2d(x)) with respect to x (vector-Jacobian product).
 
     The cascade is a chain of real-linear maps and complex moduli, so its transpose is the
@@ -142,7 +151,8 @@ def scattering2d_backward(x, g, J, L, max_order=2, bank=None):
     the real part = inclusion, and d|y| = Re(conj(y) dy) / |y|, hence g_y = g_U * y / |y|
     (taken as 0 where y = 0).
 
-    x: (..., N_r, N_c) real; g: (..., K, N_r >> J, N_c >> J) real.  Returns (..., N_r, N_c).
+    x: (..., N_r, N_c) real; g: (..., K, N_r >> rJ, N_c >> rJ) real with rJ = max(J -
+    oversampling, 0) as in ``scattering2d``.  Returns (..., N_r, N_c).
     """
     x = np.asarray(x, dtype=np.float64)
     g = np.asarray(g, dtype=np.float64)
@@ -151,7 +161,9 @@ def scattering2d_backward(x, g, J, L, max_order=2, bank=None):
         bank = filters.bank_2d(n_r, n_c, J, L)
     psi_hat, phi_hat = bank['psi_hat'], bank['phi_hat']
     ax = (-2, -1)
-    m_pts = float((n_r >> J) * (n_c >> J))
+    res = lambda j: max(j - oversampling, 0)
+    rJ = res(J)
+    m_pts = float((n_r >> rJ) * (n_c >> rJ))
 
     def unit(y):
         a = np.abs(y)
@@ -162,32 +174,34 @@ def scattering2d_backward(x, g, J, L, max_order=2, bank=None):
         return tile(np.fft.fft2(gs) / m_pts, r, ax) / float(4 ** r) * phi_r
 
     X = np.fft.fft2(x)
-    gX = lowpass_adjoint(g[..., 0, :, :], phi_hat, J)
+    gX = lowpass_adjoint(g[..., 0, :, :], phi_hat, rJ)
     c1 = 1
     c2 = 1 + J * L
     for j1 in range(J):
-        phi_j1 = fold(phi_hat, j1, ax)
-        n1 = float((n_r >> j1) * (n_c >> j1))
+        r1 = res(j1)
+        phi_j1 = fold(phi_hat, r1, ax)
+        n1 = float((n_r >> r1) * (n_c >> r1))
         for t1 in range(L):
-            y1 = np.fft.ifft2(sub(X * psi_hat[j1, t1], j1, ax))
+            y1 = np.fft.ifft2(sub(X * psi_hat[j1, t1], r1, ax))
             U1h = np.fft.fft2(np.abs(y1))
-            gU1h = lowpass_adjoint(g[..., c1, :, :], phi_j1, J - j1)
+            gU1h = lowpass_adjoint(g[..., c1, :, :], phi_j1, rJ - r1)
             c1 += 1
             if max_order >= 2:
                 for j2 in range(j1 + 1, J):
-                    phi_j2 = fold(phi_hat, j2, ax)
-                    n2 = float((n_r >> j2) * (n_c >> j2))
+                    r2 = res(j2)
+                    phi_j2 = fold(phi_hat, r2, ax)
+                    n2 = float((n_r >> r2) * (n_c >> r2))
                     for t2 in range(L):
-                        psi_r = fold(psi_hat[j2, t2], j1, ax)
-                        y2 = np.fft.ifft2(sub(U1h * psi_r, j2 - j1, ax))
-                        gVh = lowpass_adjoint(g[..., c2, :, :], phi_j2, J - j2)
+                        psi_r = fold(psi_hat[j2, t2], r1, ax)
+                        y2 = np.fft.ifft2(sub(U1h * psi_r, r2 - r1, ax))
+                        gVh = lowpass_adjoint(g[..., c2, :, :], phi_j2, rJ - r2)
                         c2 += 1
                         gV = (np.fft.ifft2(gVh) * n2).real
                         gY2 = np.fft.fft2(gV * unit(y2)) / n2
-                        gU1h = gU1h + tile(gY2, j2 - j1, ax) / float(4 ** (j2 - j1)) * psi_r
+                        gU1h = gU1h + tile(gY2, r2 - r1, ax) / float(4 ** (r2 - r1)) * psi_r
             gU1 = (np.fft.ifft2(gU1h) * n1).real
             gY1 = np.fft.fft2(gU1 * unit(y1)) / n1
-            gX = gX + tile(gY1, j1, ax) / float(4 ** j1) * psi_hat[j1, t1]
+            gX = gX + tile(gY1, r1, ax) / float(4 ** r1) * psi_hat[j1, t1]
     return (np.fft.ifft2(gX) * float(n_r * n_c)).real
 
 
@@ -289,10 +303,11 @@ def scattering2d_plain(x, J, L, max_order=2, bank=None):
 
 # ------------------------------------------------------------------ 1-D cascade
 
-def scattering1d(x, J, Q, max_order=2, bank=None):
+def scattering1d(x, J, Q, max_order=2, bank=None, oversampling=0):
     """Order-<=2 scattering of real 1-D signals, Fourier-domain cascade.
 
-    x: array (..., N), N a multiple of 2^J.  Returns float64 (..., K, N >> J).
+    x: array (..., N), N a multiple of 2^J.  Returns float64 (..., K, N >> rJ) with
+    rJ = max(J - oversampling, 0); see ``scattering2d`` for `oversampling`.
     """
     x = np.asarray(x, dtype=np.float64)
     n = x.shape[-1]
@@ -301,21 +316,25 @@ def scattering1d(x, J, Q, max_order=2, bank=None):
     psi1_hat, psi2_hat, phi_hat = bank['psi1_hat'], bank['psi2_hat'], bank['phi_hat']
     ax = (-1,)
     lead = x.shape[:-1]
+    res = lambda j: max(j - oversampling, 0)
+    rJ = res(J)
     X = np.fft.fft(x)
-    out = [np.fft.ifft(sub(X * phi_hat, J, ax)).real]
+    out = [np.fft.ifft(sub(X * phi_hat, rJ, ax)).real]
     s2 = []
     for k in range(J * Q):
         j1 = bank['j1'][k]
-        U1 = np.abs(np.fft.ifft(sub(X * psi1_hat[k], j1, ax)))
+        r1 = res(j1)
+        U1 = np.abs(np.fft.ifft(sub(X * psi1_hat[k], r1, ax)))
         U1h = np.fft.fft(U1)
-        out.append(np.fft.ifft(sub(U1h * fold(phi_hat, j1, ax), J - j1, ax)).real)
+        out.append(np.fft.ifft(sub(U1h * fold(phi_hat, r1, ax), rJ - r1, ax)).real)
         if max_order < 2:
             continue
         for j2 in range(j1 + 1, J):
-            psi_r = fold(psi2_hat[j2], j1, ax)
-            V = np.abs(np.fft.ifft(sub(U1h * psi_r, j2 - j1, ax)))
+            r2 = res(j2)
+            psi_r = fold(psi2_hat[j2], r1, ax)
+            V = np.abs(np.fft.ifft(sub(U1h * psi_r, r2 - r1, ax)))
             Vh = np.fft.fft(V)
-            s2.append(np.fft.ifft(sub(Vh * fold(phi_hat, j2, ax), J - j2, ax)).real)
+            s2.append(np.fft.ifft(sub(Vh * fold(phi_hat, r2, ax), rJ - r2, ax)).real)
     out.extend(s2)
     return np.stack(out, axis=len(lead))
 

@@ -43,6 +43,8 @@ def lib():
     L.scat_plan_create_padded.restype = ci
     L.scat_plan_create_padded_host.argtypes = [ctypes.POINTER(vp), ci, pi, ci, ci, ci]
     L.scat_plan_create_padded_host.restype = ci
+    L.scat_plan_create_ex.argtypes = [ctypes.POINTER(vp), ci, pi, ci, ci, ci, ci, ci]
+    L.scat_plan_create_ex.restype = ci
     L.scat_plan_grid_shape.argtypes = [vp, pi]
     L.scat_plan_grid_shape.restype = ci
     L.scat_forward.argtypes = [vp, vp, vp, cl, vp]
@@ -83,7 +85,7 @@ EXPORTS = ("scat_plan_create", "scat_plan_create_host", "scat_forward", "scat_pl
            "scat_plan_workspace_bytes", "scat_plan_filter", "scat_status_string",
            "scat_plan_timing_begin", "scat_plan_timing_end", "scat_plan_timing_row",
            "scat_backward", "scat_plan_backward_workspace_bytes", "scat_plan_create_padded",
-           "scat_plan_create_padded_host", "scat_plan_grid_shape")
+           "scat_plan_create_padded_host", "scat_plan_grid_shape", "scat_plan_create_ex")
 
 
 def scat_status_string(status):
@@ -103,6 +105,22 @@ def _create(fn, shape, J, LQ, max_order):
 def scat_plan_create(shape, J, LQ, max_order=2):
     """Plan for signals of `shape` (1 or 2 sides) on the current GPU; returns a handle."""
     return _create(lib().scat_plan_create, shape, J, LQ, max_order)
+
+
+SCAT_PLAN_PADDED = 1
+SCAT_PLAN_HOST_ONLY = 2
+
+
+def scat_plan_create_ex(shape, J, LQ, max_order=2, oversampling=0, flags=0):
+    """General plan creation: oversampling >= 0, flags = SCAT_PLAN_PADDED | SCAT_PLAN_HOST_ONLY."""
+    shape = tuple(int(s) for s in shape)
+    arr = (ctypes.c_int * len(shape))(*shape)
+    handle = ctypes.c_void_p()
+    st = lib().scat_plan_create_ex(ctypes.byref(handle), len(shape), arr, int(J), int(LQ),
+                                   int(max_order), int(oversampling), int(flags))
+    if st != SCAT_OK:
+        raise ScatError(st, "scat_plan_create_ex")
+    return handle
 
 
 def scat_plan_create_padded(shape, J, LQ, max_order=2):
@@ -229,19 +247,18 @@ class Scattering:
     """Owner of one plan.  `forward` takes a contiguous float32 CUDA tensor whose trailing
     dims equal `shape`; all leading dims are independent planes."""
 
-    def __init__(self, shape, J, LQ, max_order=2, host_only=False, padded=False):
+    def __init__(self, shape, J, LQ, max_order=2, host_only=False, padded=False, oversampling=0):
         """padded=True: signals of any size, extended symmetrically to a periodic grid of
-        power-of-two sides (scat_plan_create_padded); else `shape` is that periodic grid."""
+        power-of-two sides (scat_plan_create_padded); else `shape` is that periodic grid.
+        oversampling=o: every signal 2^o times finer than the default schedule."""
         self.shape = tuple(int(s) for s in shape)
         self.dims = len(self.shape)
         self.J, self.LQ, self.max_order = int(J), int(LQ), int(max_order)
         self.padded = bool(padded)
         self._plan = None
-        if padded:
-            create = scat_plan_create_padded_host if host_only else scat_plan_create_padded
-        else:
-            create = scat_plan_create_host if host_only else scat_plan_create
-        self._plan = create(self.shape, J, LQ, max_order)
+        self.oversampling = int(oversampling)
+        flags = (SCAT_PLAN_PADDED if padded else 0) | (SCAT_PLAN_HOST_ONLY if host_only else 0)
+        self._plan = scat_plan_create_ex(self.shape, J, LQ, max_order, oversampling, flags)
         self.K = scat_plan_num_coeffs(self._plan)
         self.out_shape = scat_plan_out_shape(self._plan, self.dims)
         self.grid_shape = scat_plan_grid_shape(self._plan, self.dims)

@@ -150,39 +150,39 @@ Layout make_layout(const scat_plan &p, long batch) {
     const size_t l = h.LQ;
     L.xh = n * c8;
     size_t t1 = 0;
-    for (int j = 0; j < h.J; ++j) t1 += l * (n >> (2 * j));
+    for (int j = 0; j < h.J; ++j) t1 += l * (n >> (2 * h.res(j)));
     L.t = t1 * c8;
     L.u = second ? l * n * c8 : 0;
     size_t t2 = 0;
-    for (int j = 1; j < h.J; ++j) t2 += l * l * (n >> (2 * j));
+    for (int j = 1; j < h.J; ++j) t2 += l * l * (n >> (2 * h.res(j)));
     L.v = second ? t2 * c8 : 0;
-    const size_t m_r = p.n1 >> h.J;
+    const size_t m_r = p.n1 >> h.res(h.J);
     size_t w0 = l * m_r * p.n2;
-    size_t w2 = second ? l * l * m_r * (p.n2 / 2) : 0;
+    size_t w2 = second ? l * l * m_r * (p.n2 >> h.res(1)) : 0;
     L.w = (w0 > w2 ? w0 : w2) * sizeof(float);
   } else if (h.dims == 2) {
     const size_t l = h.LQ;
     L.xh = n * c8;
-    size_t t1 = l * n, t2 = second ? l * l * (n / 4) : 0;
+    size_t t1 = l * n, t2 = second ? l * l * (n >> (2 * h.res(1))) : 0;
     L.t = (t1 > t2 ? t1 : t2) * c8;
     L.u = second ? l * n * c8 : 0;
     L.v = 0;
-    const size_t m_r = p.n1 >> h.J;
+    const size_t m_r = p.n1 >> h.res(h.J);
     size_t w0 = l * m_r * p.n2;                       // first order at octave 0
-    size_t w2 = second ? l * l * m_r * (p.n2 / 2) : 0;  // second order at octave 1
+    size_t w2 = second ? l * l * m_r * (p.n2 >> h.res(1)) : 0;  // second order at octave 1
     L.w = (w0 > w2 ? w0 : w2) * sizeof(float);
   } else {
     const size_t q = h.LQ;
     L.xh = n * c8;
     L.t = q * n * c8;
     L.u = q * n * c8;
-    L.v = second ? q * (n / 2) * c8 : 0;
+    L.v = second ? q * (n >> h.res(1)) * c8 : 0;
     L.w = 0;
   }
   if (p.padded) {
     L.pad_in = n * sizeof(float);
-    const size_t m_r = h.dims == 2 ? h.shape[0] >> h.J : 1;
-    L.pad_out = static_cast<size_t>(h.K) * m_r * (h.shape[1] >> h.J) * sizeof(float);
+    const size_t m_r = h.dims == 2 ? h.shape[0] >> h.res(h.J) : 1;
+    L.pad_out = static_cast<size_t>(h.K) * m_r * (h.shape[1] >> h.res(h.J)) * sizeof(float);
   }
   L.per_plane = L.xh + L.t + L.u + L.v + L.w + L.pad_in + L.pad_out;
   long c = static_cast<long>(scratch_budget() / L.per_plane);
@@ -299,10 +299,11 @@ scat_status upload(scat_plan *p) {
 }
 
 scat_status create_common(scat_plan **out_plan, int dims, const int *user_shape, int J, int LQ,
-                          int max_order, bool device, bool padded = false) {
+                          int max_order, bool device, bool padded = false, int oversampling = 0) {
   if (out_plan == nullptr) return SCAT_ERR_NULL;
   *out_plan = nullptr;
   if (user_shape == nullptr) return SCAT_ERR_NULL;
+  if (oversampling < 0 || oversampling > 24) return SCAT_ERR_ARG;
   int grid[2] = {1, 1};
   const int *shape = user_shape;
   if (padded) {
@@ -323,6 +324,7 @@ scat_status create_common(scat_plan **out_plan, int dims, const int *user_shape,
   if (p == nullptr) return SCAT_ERR_ALLOC;
   try {
     scat::build_host_plan(p->host, dims, shape, J, LQ, max_order);
+    p->host.oversampling = oversampling;
   } catch (const std::bad_alloc &) {
     delete p;
     return SCAT_ERR_ALLOC;
@@ -340,14 +342,15 @@ scat_status create_common(scat_plan **out_plan, int dims, const int *user_shape,
     p->n2 = 1 << lg2;
     p->n1 = shape[0] >> lg2;
   }
-  p->fused = dims == 2 && J <= 4 && scat::rows_fused_supported(p->n1, p->n2, J - 1);
-  p->tree = dims == 2 && scat::tree_supported(p->n1, p->n2, J);
+  p->fused = dims == 2 && J <= 4 && scat::rows_fused_supported(p->n1, p->n2, p->host.res(J - 1));
+  p->tree = dims == 2 && oversampling == 0 && scat::tree_supported(p->n1, p->n2, J);
   if (padded) {
     p->padded = true;
     for (int d = 0; d < dims; ++d) {
       const int k = dims == 2 ? d : 1;
       p->user_shape[k] = user_shape[d];
-      p->user_out[k] = (user_shape[d] + (1 << J) - 1) >> J;
+      const int rj = p->host.res(J);
+      p->user_out[k] = (user_shape[d] + (1 << rj) - 1) >> rj;
     }
   }
   if (device) {
@@ -482,13 +485,13 @@ Tape make_tape(const scat_plan &p) {
   size_t off = 0;
   for (int j1 = 0; j1 < h.J; ++j1) {
     t.y1_off.push_back(off);
-    off += l * (n >> (2 * j1));
+    off += l * (n >> (2 * h.res(j1)));
   }
   if (h.max_order == 2)
     for (int j1 = 0; j1 < h.J; ++j1)
       for (int j2 = j1 + 1; j2 < h.J; ++j2) {
         t.y2_off[{j1, j2}] = off;
-        off += l * l * (n >> (2 * j2));
+        off += l * l * (n >> (2 * h.res(j2)));
       }
   t.total = off;
   return t;
@@ -501,7 +504,8 @@ scat_status forward_2d(scat_plan *p, const float *in, float *out, long p0, long 
   const scat::HostPlan &h = p->host;
   const int J = h.J, L = h.LQ, K = h.K;
   const int Nr = p->n1, Nc = p->n2;
-  const int m_r = Nr >> J, m_c = Nc >> J;
+  const int rJ = h.res(J);
+  const int m_r = Nr >> rJ, m_c = Nc >> rJ;
   char *base = static_cast<char *>(p->d_scratch);
   float2 *XH = reinterpret_cast<float2 *>(base);
   float2 *T = reinterpret_cast<float2 *>(base + lay.xh * pc);
@@ -525,29 +529,31 @@ scat_status forward_2d(scat_plan *p, const float *in, float *out, long p0, long 
 
   int s2_base = 1 + J * L;
   for (int j1 = 0; j1 < J; ++j1) {
-    const int M1r = Nr >> j1, M1c = Nc >> j1;
+    const int r1 = h.res(j1);
+    const int M1r = Nr >> r1, M1c = Nc >> r1;
     const bool kids = h.max_order == 2 && j1 < J - 1;
-    SCAT_TRY(scat::launch_mulfold_invrow(XH, tab + p->psi1_off[j1], T, pc, L, Nr, Nc, j1, j1, 0,
+    SCAT_TRY(scat::launch_mulfold_invrow(XH, tab + p->psi1_off[j1], T, pc, L, Nr, Nc, r1, r1, 0,
                                          tw, tw_n, st));
     SCAT_TRY(scat::launch_col(1, T, pc * L, M1r, M1c, kids ? U : nullptr, 0,
-                              tab + p->phi_rows_off[j1], m_r, lp ? W : nullptr, nullptr, none, K,
+                              tab + p->phi_rows_off[r1], m_r, lp ? W : nullptr, nullptr, none, K,
                               tw, tw_n, st, false,
                               tape ? tape->base + tape->y1_off[j1] * pc : nullptr));
     if (lp)
-      SCAT_TRY(scat::launch_row_lowpass(W, pc * L, m_r, M1c, m_c, tab + p->phi_cols_off[j1], o,
+      SCAT_TRY(scat::launch_row_lowpass(W, pc * L, m_r, M1c, m_c, tab + p->phi_cols_off[r1], o,
                                         ChanMap{L, L, 0, 1 + j1 * L}, K, tw, tw_n, st));
     if (!kids) continue;
     SCAT_TRY(scat::launch_row_fwd(U, pc * L * M1r, M1c, tw, tw_n, st));
     const int octs = J - 1 - j1;
     for (int j2 = j1 + 1; j2 < J; ++j2) {
-      const int M2r = Nr >> j2, M2c = Nc >> j2;
-      SCAT_TRY(scat::launch_mulfold_invrow(U, tab + p->psi2_off[{j1, j2}], T, pc * L, L, M1r, M1c,
-                                           j2 - j1, j2 - j1, 0, tw, tw_n, st));
-      SCAT_TRY(scat::launch_col(1, T, pc * L * L, M2r, M2c, nullptr, 0, tab + p->phi_rows_off[j2],
+      const int r2 = h.res(j2);
+      const int M2r = Nr >> r2, M2c = Nc >> r2;
+      SCAT_TRY(scat::launch_mulfold_invrow(U, tab + p->psi2_off[{r1, j2}], T, pc * L, L, M1r, M1c,
+                                           r2 - r1, r2 - r1, 0, tw, tw_n, st));
+      SCAT_TRY(scat::launch_col(1, T, pc * L * L, M2r, M2c, nullptr, 0, tab + p->phi_rows_off[r2],
                                 m_r, lp ? W : nullptr, nullptr, none, K, tw, tw_n, st, false,
                                 tape ? tape->base + tape->y2_off.at({j1, j2}) * pc : nullptr));
       if (lp)
-        SCAT_TRY(scat::launch_row_lowpass(W, pc * L * L, m_r, M2c, m_c, tab + p->phi_cols_off[j2],
+        SCAT_TRY(scat::launch_row_lowpass(W, pc * L * L, m_r, M2c, m_c, tab + p->phi_cols_off[r2],
                                           o, ChanMap{L * L, L, octs * L, s2_base + (j2 - j1 - 1) * L},
                                           K, tw, tw_n, st));
     }
@@ -564,7 +570,8 @@ scat_status forward_2d_fused(scat_plan *p, const float *in, float *out, long p0,
   const scat::HostPlan &h = p->host;
   const int J = h.J, L = h.LQ, K = h.K;
   const int Nr = p->n1, Nc = p->n2;
-  const int m_r = Nr >> J, m_c = Nc >> J;
+  const int rJ = h.res(J);
+  const int m_r = Nr >> rJ, m_c = Nc >> rJ;
   const size_t n = static_cast<size_t>(Nr) * Nc;
   char *base = static_cast<char *>(p->d_scratch);
   float2 *XC = reinterpret_cast<float2 *>(base);
@@ -605,16 +612,17 @@ scat_status forward_2d_fused(scat_plan *p, const float *in, float *out, long p0,
     size_t off = 0;
     for (int j1 = 0; j1 < J; ++j1) {
       t1[j1] = T + off;
-      lv[j1] = scat::FusedLevel{j1, L, tab + p->psi1_off[j1], t1[j1]};
-      off += static_cast<size_t>(pc) * L * (n >> (2 * j1));
+      lv[j1] = scat::FusedLevel{h.res(j1), L, tab + p->psi1_off[j1], t1[j1]};
+      off += static_cast<size_t>(pc) * L * (n >> (2 * h.res(j1)));
     }
     SCAT_TRY(scat::launch_rows_fused(XC, true, pc, Nr, Nc, lv, J, tw, tw_n, st));
   }
   int s2_base = 1 + J * L;
   for (int j1 = 0; j1 < J; ++j1) {
-    const int M1r = Nr >> j1, M1c = Nc >> j1;
+    const int r1 = h.res(j1);
+    const int M1r = Nr >> r1, M1c = Nc >> r1;
     const bool kids = h.max_order == 2 && j1 < J - 1;
-    SCAT_TRY(col_and_lowpass(1, t1[j1], pc * L, M1r, M1c, j1, kids ? U : nullptr,
+    SCAT_TRY(col_and_lowpass(1, t1[j1], pc * L, M1r, M1c, r1, kids ? U : nullptr,
                              ChanMap{L, L, 0, 1 + j1 * L},
                              tape ? tape->base + tape->y1_off[j1] * pc : nullptr));
     if (!kids) continue;
@@ -625,14 +633,15 @@ scat_status forward_2d_fused(scat_plan *p, const float *in, float *out, long p0,
       size_t off = 0;
       for (int j2 = j1 + 1; j2 < J; ++j2) {
         t2[j2] = V + off;
-        lv[j2 - j1 - 1] = scat::FusedLevel{j2 - j1, L, tab + p->psi2_off[{j1, j2}], t2[j2]};
-        off += static_cast<size_t>(pc) * L * L * (n >> (2 * j2));
+        lv[j2 - j1 - 1] = scat::FusedLevel{h.res(j2) - r1, L, tab + p->psi2_off[{r1, j2}], t2[j2]};
+        off += static_cast<size_t>(pc) * L * L * (n >> (2 * h.res(j2)));
       }
       SCAT_TRY(scat::launch_rows_fused(U, true, pc * L, M1r, M1c, lv, octs, tw, tw_n, st));
     }
     for (int j2 = j1 + 1; j2 < J; ++j2) {
-      const int M2r = Nr >> j2, M2c = Nc >> j2;
-      SCAT_TRY(col_and_lowpass(1, t2[j2], pc * L * L, M2r, M2c, j2, nullptr,
+      const int r2 = h.res(j2);
+      const int M2r = Nr >> r2, M2c = Nc >> r2;
+      SCAT_TRY(col_and_lowpass(1, t2[j2], pc * L * L, M2r, M2c, r2, nullptr,
                                ChanMap{L * L, L, octs * L, s2_base + (j2 - j1 - 1) * L},
                                tape ? tape->base + tape->y2_off.at({j1, j2}) * pc : nullptr));
     }
@@ -679,12 +688,12 @@ BwdLayout make_bwd_layout(const scat_plan &p, long batch) {
   const scat::HostPlan &h = p.host;
   const size_t n = static_cast<size_t>(p.n1) * p.n2, l = h.LQ, c8 = sizeof(float2);
   const bool second = h.max_order == 2 && h.J >= 2;
-  const size_t t1 = l * n, t2 = second ? l * l * (n / 4) : 0;
+  const size_t t1 = l * n, t2 = second ? l * l * (n >> (2 * h.res(1))) : 0;
   if (p.fused) {
     // buffers of the fused forward schedule (see make_layout)
     size_t ft1 = 0, ft2 = 0;
-    for (int j = 0; j < h.J; ++j) ft1 += l * (n >> (2 * j));
-    for (int j = 1; j < h.J; ++j) ft2 += l * l * (n >> (2 * j));
+    for (int j = 0; j < h.J; ++j) ft1 += l * (n >> (2 * h.res(j)));
+    for (int j = 1; j < h.J; ++j) ft2 += l * l * (n >> (2 * h.res(j)));
     b.fwd.xh = n * c8;
     b.fwd.t = ft1 * c8;
     b.fwd.u = second ? l * n * c8 : 0;
@@ -699,9 +708,9 @@ BwdLayout make_bwd_layout(const scat_plan &p, long batch) {
   b.gu = l * n;
   b.ga = t2;
   // spectra of the output-grid gradient planes of one launch (at most L*L, or L, nodes)
-  b.gh = (second ? l * l : l) * static_cast<size_t>(p.n1 >> h.J) * (p.n2 >> h.J);
+  b.gh = (second ? l * l : l) * static_cast<size_t>(p.n1 >> h.res(h.J)) * (p.n2 >> h.res(h.J));
   if (p.padded)
-    b.pad_floats = 2 * n + static_cast<size_t>(h.K) * (p.n1 >> h.J) * (p.n2 >> h.J);
+    b.pad_floats = 2 * n + static_cast<size_t>(h.K) * (p.n1 >> h.res(h.J)) * (p.n2 >> h.res(h.J));
   b.per_plane = b.fwd.xh + b.fwd.t + b.fwd.u + b.fwd.v +
                 (b.tape.total + b.gx + b.gu + b.ga + b.gh) * c8 + b.pad_floats * sizeof(float);
   long c = static_cast<long>(scratch_budget() / b.per_plane);
@@ -718,7 +727,8 @@ scat_status backward_2d(scat_plan *p, const float *in, const float *gout, float 
   const scat::HostPlan &h = p->host;
   const int J = h.J, L = h.LQ, K = h.K;
   const int Nr = p->n1, Nc = p->n2;
-  const int m_r = Nr >> J, m_c = Nc >> J;
+  const int rJ = h.res(J);
+  const int m_r = Nr >> rJ, m_c = Nc >> rJ;
   const size_t n = static_cast<size_t>(Nr) * Nc;
   char *base = static_cast<char *>(p->d_scratch);
   float2 *after_fwd =
@@ -744,23 +754,25 @@ scat_status backward_2d(scat_plan *p, const float *in, const float *gout, float 
                                     st));
   int s2_base = 1 + J * L;
   for (int j1 = 0; j1 < J; ++j1) {
-    const int M1r = Nr >> j1, M1c = Nc >> j1;
+    const int r1 = h.res(j1);
+    const int M1r = Nr >> r1, M1c = Nc >> r1;
     const bool kids = h.max_order == 2 && j1 < J - 1;
     // g_U1^ starts as the adjoint lowpass of g_S1, then collects its children; without
     // children the inverse row transform can follow in the same pass
     if (kids) {
       SCAT_TRY(scat::launch_lowpass_adj(go, pc * L, ChanMap{L, L, 0, 1 + j1 * L}, K, m_r, m_c, M1r,
-                                        M1c, tab + p->phi_rows_off[j1], tab + p->phi_cols_off[j1],
+                                        M1c, tab + p->phi_rows_off[r1], tab + p->phi_cols_off[r1],
                                         GU, tw, tw_n, st));
     } else {
       SCAT_TRY(scat::launch_lowpass_adj_rows(go, pc * L, ChanMap{L, L, 0, 1 + j1 * L}, K, m_r, m_c,
-                                             M1r, M1c, tab + p->phi_rows_off[j1],
-                                             tab + p->phi_cols_off[j1], GH, GU, tw, tw_n, st));
+                                             M1r, M1c, tab + p->phi_rows_off[r1],
+                                             tab + p->phi_cols_off[r1], GH, GU, tw, tw_n, st));
     }
     if (kids) {
       const int octs = J - 1 - j1;
       for (int j2 = j1 + 1; j2 < J; ++j2) {
-        const int M2r = Nr >> j2, M2c = Nc >> j2;
+        const int r2 = h.res(j2);
+        const int M2r = Nr >> r2, M2c = Nc >> r2;
         const long nodes = pc * L * L;
         // adjoint lowpass and inverse rows in one pass; then one column pass (inverse,
         // modulus backward against the tape, forward); then forward rows and the
@@ -768,11 +780,11 @@ scat_status backward_2d(scat_plan *p, const float *in, const float *gout, float 
         // and is not faster: the accumulate is bound by its filter reads)
         SCAT_TRY(scat::launch_lowpass_adj_rows(
             go, nodes, ChanMap{L * L, L, octs * L, s2_base + (j2 - j1 - 1) * L}, K, m_r, m_c, M2r, M2c,
-            tab + p->phi_rows_off[j2], tab + p->phi_cols_off[j2], GH, GA, tw, tw_n, st));
+            tab + p->phi_rows_off[r2], tab + p->phi_cols_off[r2], GH, GA, tw, tw_n, st));
         SCAT_TRY(scat::launch_cols_modback(GA, bl.tape.base + bl.tape.y2_off.at({j1, j2}) * pc, nodes,
                                            M2r, M2c, tw, tw_n, st));
         SCAT_TRY(scat::launch_fft_rows_inplace(GA, nodes * M2r, M2c, false, tw, tw_n, st));
-        SCAT_TRY(scat::launch_tile_accum(GU, tab + p->psi2_off[{j1, j2}], GA, pc * L, L, M1r, M1c,
+        SCAT_TRY(scat::launch_tile_accum(GU, tab + p->psi2_off[{r1, j2}], GA, pc * L, L, M1r, M1c,
                                          M2r, M2c, st));
       }
       s2_base += L * L * octs;
@@ -795,7 +807,8 @@ scat_status forward_1d(scat_plan *p, const float *in, float *out, long p0, long 
   const int J = h.J, Q = h.LQ, K = h.K;
   const int N1 = p->n1, N2 = p->n2;
   const int N = N1 * N2;
-  const int mc_out = N2 >> J;
+  const int rJ = h.res(J);
+  const int mc_out = N2 >> rJ;
   char *base = static_cast<char *>(p->d_scratch);
   float2 *XH = reinterpret_cast<float2 *>(base);
   float2 *T = reinterpret_cast<float2 *>(base + lay.xh * pc);
@@ -805,43 +818,45 @@ scat_status forward_1d(scat_plan *p, const float *in, float *out, long p0, long 
   const float2 *tw = p->d_tw;
   const int tw_n = p->tw_n;
   const float *x = in + static_cast<size_t>(p0) * N;
-  float *o = out + static_cast<size_t>(p0) * K * (N >> J);
+  float *o = out + static_cast<size_t>(p0) * K * (N >> rJ);
   const ChanMap none{1, 1, 0, 0};
 
   SCAT_TRY(scat::launch_col(0, x, pc, N1, N2, XH, N, nullptr, 0, nullptr, nullptr, none, K, tw,
                             tw_n, st));
   SCAT_TRY(scat::launch_row_fwd(XH, pc * N1, N2, tw, tw_n, st));
   // S0
-  SCAT_TRY(scat::launch_mulfold_invrow(XH, tab + p->phi_off[0], T, pc, 1, N1, N2, 0, J, N >> J, tw,
+  SCAT_TRY(scat::launch_mulfold_invrow(XH, tab + p->phi_off[0], T, pc, 1, N1, N2, 0, rJ, N >> rJ, tw,
                                        tw_n, st));
   SCAT_TRY(scat::launch_col(2, T, pc, N1, mc_out, nullptr, 0, nullptr, 0, nullptr, o,
                             ChanMap{1, 1, 0, 0}, K, tw, tw_n, st));
   int s2_base = 1 + J * Q;
   for (int j1 = 0; j1 < J; ++j1) {
-    const int Mc1 = N2 >> j1;
-    const int M1 = N >> j1;
+    const int r1 = h.res(j1);
+    const int Mc1 = N2 >> r1;
+    const int M1 = N >> r1;
     const bool kids = h.max_order == 2 && j1 < J - 1;
-    SCAT_TRY(scat::launch_mulfold_invrow(XH, tab + p->psi1_off[j1], T, pc, Q, N1, N2, 0, j1, M1,
+    SCAT_TRY(scat::launch_mulfold_invrow(XH, tab + p->psi1_off[j1], T, pc, Q, N1, N2, 0, r1, M1,
                                          tw, tw_n, st));
     SCAT_TRY(scat::launch_col(1, T, pc * Q, N1, Mc1, U, M1, nullptr, 0, nullptr, nullptr, none, K,
                               tw, tw_n, st));
     SCAT_TRY(scat::launch_row_fwd(U, pc * Q * N1, Mc1, tw, tw_n, st));
-    SCAT_TRY(scat::launch_mulfold_invrow(U, tab + p->phi_off[j1], T, pc * Q, 1, N1, Mc1, 0, J - j1,
-                                         N >> J, tw, tw_n, st));
+    SCAT_TRY(scat::launch_mulfold_invrow(U, tab + p->phi_off[r1], T, pc * Q, 1, N1, Mc1, 0, rJ - r1,
+                                         N >> rJ, tw, tw_n, st));
     SCAT_TRY(scat::launch_col(2, T, pc * Q, N1, mc_out, nullptr, 0, nullptr, 0, nullptr, o,
                               ChanMap{Q, Q, 0, 1 + j1 * Q}, K, tw, tw_n, st));
     if (!kids) continue;
     const int octs = J - 1 - j1;
     for (int j2 = j1 + 1; j2 < J; ++j2) {
-      const int Mc2 = N2 >> j2;
-      const int M2 = N >> j2;
-      SCAT_TRY(scat::launch_mulfold_invrow(U, tab + p->psi2_off[{j1, j2}], T, pc * Q, 1, N1, Mc1, 0,
-                                           j2 - j1, M2, tw, tw_n, st));
+      const int r2 = h.res(j2);
+      const int Mc2 = N2 >> r2;
+      const int M2 = N >> r2;
+      SCAT_TRY(scat::launch_mulfold_invrow(U, tab + p->psi2_off[{r1, j2}], T, pc * Q, 1, N1, Mc1, 0,
+                                           r2 - r1, M2, tw, tw_n, st));
       SCAT_TRY(scat::launch_col(1, T, pc * Q, N1, Mc2, V, M2, nullptr, 0, nullptr, nullptr, none, K,
                                 tw, tw_n, st));
       SCAT_TRY(scat::launch_row_fwd(V, pc * Q * N1, Mc2, tw, tw_n, st));
-      SCAT_TRY(scat::launch_mulfold_invrow(V, tab + p->phi_off[j2], T, pc * Q, 1, N1, Mc2, 0,
-                                           J - j2, N >> J, tw, tw_n, st));
+      SCAT_TRY(scat::launch_mulfold_invrow(V, tab + p->phi_off[r2], T, pc * Q, 1, N1, Mc2, 0,
+                                           rJ - r2, N >> rJ, tw, tw_n, st));
       SCAT_TRY(scat::launch_col(2, T, pc * Q, N1, mc_out, nullptr, 0, nullptr, 0, nullptr, o,
                                 ChanMap{Q, 1, octs, s2_base + (j2 - j1 - 1)}, K, tw, tw_n, st));
     }
@@ -867,6 +882,16 @@ scat_status scat_plan_create_padded(scat_plan **out_plan, int dims, const int *s
 scat_status scat_plan_create_padded_host(scat_plan **out_plan, int dims, const int *shape, int J,
                                          int LQ, int max_order) {
   return create_common(out_plan, dims, shape, J, LQ, max_order, false, true);
+}
+
+scat_status scat_plan_create_ex(scat_plan **out_plan, int dims, const int *shape, int J, int LQ,
+                                int max_order, int oversampling, int flags) {
+  if (flags & ~3) {
+    if (out_plan != nullptr) *out_plan = nullptr;
+    return SCAT_ERR_ARG;
+  }
+  return create_common(out_plan, dims, shape, J, LQ, max_order, (flags & SCAT_PLAN_HOST_ONLY) == 0,
+                       (flags & SCAT_PLAN_PADDED) != 0, oversampling);
 }
 
 scat_status scat_plan_grid_shape(const scat_plan *plan, int *shape_out) {
@@ -933,7 +958,7 @@ scat_status scat_forward(scat_plan *plan, const float *in, float *out, long batc
                                   : forward_2d(plan, cin, cout, cp0, pc, lay, st);
     if (s != SCAT_OK) return s;
     if (plan->padded) {
-      const int m_r = h.dims == 2 ? h.shape[0] >> h.J : 1, m_c = h.shape[1] >> h.J;
+      const int m_r = h.dims == 2 ? h.shape[0] >> h.res(h.J) : 1, m_c = h.shape[1] >> h.res(h.J);
       const int o_r = plan->user_out[0], o_c = plan->user_out[1];
       hipLaunchKernelGGL(k_crop, dim3(stream_blocks(pc * h.K * o_r * o_c)), dim3(256), 0, st, op,
                          out + static_cast<size_t>(p0) * h.K * o_r * o_c, pc * h.K, m_r, m_c, o_r,
@@ -952,10 +977,10 @@ scat_status scat_backward(scat_plan *plan, const float *in, const float *grad_ou
   if (h.dims != 2) return SCAT_ERR_ARG;
   // every grid of the cascade must have sides the plain transforms handle, and the output
   // grid must fit the adjoint lowpass kernel's LDS stage
-  const int small_r = plan->n1 >> (h.J - 1), small_c = plan->n2 >> (h.J - 1);
+  const int small_r = plan->n1 >> h.res(h.J - 1), small_c = plan->n2 >> h.res(h.J - 1);
   if (!scat::backward_side_supported(plan->n1) || !scat::backward_side_supported(plan->n2) ||
       !scat::backward_side_supported(small_r) || !scat::backward_side_supported(small_c) ||
-      static_cast<long>(plan->n1 >> h.J) * (plan->n2 >> h.J) > 1024)
+      static_cast<long>(plan->n1 >> h.res(h.J)) * (plan->n2 >> h.res(h.J)) > 1024)
     return SCAT_ERR_SHAPE;
   if (batch == 0) return SCAT_OK;
   if (in == nullptr || grad_out == nullptr || grad_in == nullptr) return SCAT_ERR_NULL;
@@ -987,7 +1012,7 @@ scat_status scat_backward(scat_plan *plan, const float *in, const float *grad_ou
     // padded plan: extend the input and (with zeros) the output gradient to the periodic
     // grid, run the periodic backward pass there, fold the extended gradient back
     const size_t n = static_cast<size_t>(plan->n1) * plan->n2;
-    const int m_r = plan->n1 >> h.J, m_c = plan->n2 >> h.J;
+    const int m_r = plan->n1 >> h.res(h.J), m_c = plan->n2 >> h.res(h.J);
     const int ur = plan->user_shape[0], uc = plan->user_shape[1];
     const int o_r = plan->user_out[0], o_c = plan->user_out[1];
     float *xp = reinterpret_cast<float *>(static_cast<char *>(plan->d_scratch) +
@@ -1040,10 +1065,10 @@ scat_status scat_plan_out_shape(const scat_plan *plan, int *shape_out) {
     if (h.dims == 2) shape_out[0] = plan->user_out[0];
     shape_out[h.dims == 2 ? 1 : 0] = plan->user_out[1];
   } else if (h.dims == 2) {
-    shape_out[0] = h.shape[0] >> h.J;
-    shape_out[1] = h.shape[1] >> h.J;
+    shape_out[0] = h.shape[0] >> h.res(h.J);
+    shape_out[1] = h.shape[1] >> h.res(h.J);
   } else {
-    shape_out[0] = h.shape[1] >> h.J;
+    shape_out[0] = h.shape[1] >> h.res(h.J);
   }
   return SCAT_OK;
 }

@@ -26,6 +26,10 @@ struct HostPlan {
   int dims = 0;
   int shape[2] = {1, 1};  // 1-D: shape[0] = 1 rows, shape[1] = N
   int J = 0, LQ = 0, max_order = 0;
+  // Oversampling o: after a wavelet of octave j the grid is shape >> res(j) with
+  // res(j) = max(j - o, 0); the output grid is shape >> res(J).  o = 0: critical schedule.
+  int oversampling = 0;
+  int res(int j) const { return j > oversampling ? j - oversampling : 0; }
   int K = 0;
   std::vector<CoeffRow> index;
   std::vector<FilterTable> filters;

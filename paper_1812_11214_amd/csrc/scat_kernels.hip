@@ -688,12 +688,13 @@ hipError_t launch_col_fast_t(int mode, const void *src, long nodes, int Mc, floa
   if (blocks <= 0 || blocks > 0x7fffffffL) return hipErrorInvalidValue;
   // lowpass tail variant: registers when the lowpass length is 32 or 8 and a multiple of T
   const int lm = (w_out && m_r == 32 && T <= 32 && tw_n >= 32) ? 32 : (w_out && m_r == 8 && T <= 8) ? 8 : 0;
-  size_t words = static_cast<size_t>(E) * (T * TC + 16);
-  if (lm == 0 && w_out) words += static_cast<size_t>(m_r) * TC;
-  if (lm == 32 && static_cast<size_t>(80) * TC > words) words = static_cast<size_t>(80) * TC;
-  size_t lds = words * sizeof(float2);
-  dim3 g(static_cast<unsigned>(blocks)), b(T * TC);
   const int lm_t = (lm == 8 && MR > 128) ? 0 : lm;  // the template argument actually used
+  size_t words = static_cast<size_t>(E) * (T * TC + 16);
+  if (lm_t == 0 && w_out) words += static_cast<size_t>(m_r) * TC;  // the generic tail's own area
+  if (lm_t == 32 && static_cast<size_t>(80) * TC > words) words = static_cast<size_t>(80) * TC;
+  size_t lds = words * sizeof(float2);
+  if (lds > 160 * 1024) return hipErrorInvalidValue;
+  dim3 g(static_cast<unsigned>(blocks)), b(T * TC);
   const std::string name = "k_col_fast<" + std::to_string(MR) + ", " + (mode ? "1" : "0") + ", " +
                            std::to_string(lm_t) + ">";
   const double pts = static_cast<double>(nodes) * MR * Mc;
@@ -1366,15 +1367,23 @@ hipError_t launch_row_lowpass_fast_t(const float *w, long nodes, int m_r, int m_
   Observe ob(name.c_str(), rws * (MC + m_c) * 4,
              rws * 0.5 * (fft_flops(MC) + fft_flops(m_c) + 2.0 * MC), st);
   dim3 g(static_cast<unsigned>(blocks)), b(256);
-  if (lm == 32)
-    hipLaunchKernelGGL((k_row_lowpass_fast<MC, (MC >= 32 ? 32 : 0)>), g, b, lds, st, w, pairs, m_r, m_c,
-                       phi_cols, out, cm, K, tw, tw_n);
-  else if (lm == 8)
-    hipLaunchKernelGGL((k_row_lowpass_fast<MC, (MC <= 128 ? 8 : 0)>), g, b, lds, st, w, pairs, m_r, m_c,
-                       phi_cols, out, cm, K, tw, tw_n);
-  else
-    hipLaunchKernelGGL((k_row_lowpass_fast<MC, 0>), g, b, lds, st, w, pairs, m_r, m_c, phi_cols, out,
-                       cm, K, tw, tw_n);
+  if (lds > 160 * 1024) return hipErrorInvalidValue;
+#define SCAT_RLP_LAUNCH(LM_)                                                                       \
+  {                                                                                                \
+    static bool attr_done = false;                                                                 \
+    if (lds > 65536 && !attr_done) {                                                               \
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_row_lowpass_fast<MC, LM_>), \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);  \
+      if (e != hipSuccess) return e;                                                               \
+      attr_done = true;                                                                            \
+    }                                                                                              \
+    hipLaunchKernelGGL((k_row_lowpass_fast<MC, LM_>), g, b, lds, st, w, pairs, m_r, m_c, phi_cols, \
+                       out, cm, K, tw, tw_n);                                                      \
+  }
+  if (lm == 32) SCAT_RLP_LAUNCH((MC >= 32 ? 32 : 0))
+  else if (lm == 8) SCAT_RLP_LAUNCH((MC <= 128 ? 8 : 0))
+  else SCAT_RLP_LAUNCH(0)
+#undef SCAT_RLP_LAUNCH
   return hipGetLastError();
 }
 
