@@ -23,7 +23,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 ALU_PEAK_TFLOPS = 157.3        # MI355X fp32 vector peak (256 CUs x 4 SIMD x 16 lanes x 2 x 2.4 GHz)
 WORKLOAD = 2                   # index into workloads.CONFIGS: 2-D J=3 L=8 256x256, 128x3 planes
 # committed rocprofv3 counter summaries, profiles/hbm_traffic_<tag>.txt, per workload index
-TRAFFIC_TAGS = {1: "2d_J2_L8_32x32_b3072", 2: "2d_J3_L8_256x256_b384"}
+TRAFFIC_TAGS = {0: "2d_J2_L8_32x32_b4", 1: "2d_J2_L8_32x32_b3072", 2: "2d_J3_L8_256x256_b384",
+                3: "2d_J4_L8_512x512_b32", 4: "1d_J6_Q8_65536_b64"}
 
 
 def cpu_baseline(planes, dims, J, LQ, channels, budget_s=20.0, grad=None):
