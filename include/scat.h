@@ -20,9 +20,10 @@
  * sigma_k = 0.3 pi / (xi_k (1 - 2^(-1/Q))) (0.8*2^k when Q = 1), second order one
  * wavelet per octave.
  *
- * All pointers named `in`/`out` are DEVICE pointers; everything else is host memory.
- * Every function returns a status and never throws or aborts.  The library needs a
- * GPU for scat_plan_create and scat_forward only.
+ * All pointers named `in`/`out`/`grad_*` are DEVICE pointers; everything else is host
+ * memory.  Every function returns a status and never throws or aborts.  The library needs
+ * a GPU for the plan constructors without "host" in their name (or flag), scat_forward and
+ * scat_backward only.
  */
 #ifndef SCAT_H
 #define SCAT_H
@@ -38,7 +39,8 @@ typedef struct scat_plan scat_plan; /* opaque, owned by the library */
 typedef enum {
   SCAT_OK = 0,
   SCAT_ERR_ARG = 1,    /* bad dims / J / L / Q / max_order / batch / index */
-  SCAT_ERR_SHAPE = 2,  /* a side is not a power of two, or is smaller than 2^J */
+  SCAT_ERR_SHAPE = 2,  /* a side is not a power of two, is smaller than 2^J, or is outside the
+                          range the called function supports */
   SCAT_ERR_ALLOC = 3,  /* host or device allocation failed */
   SCAT_ERR_DEVICE = 4, /* a HIP call failed (no device, launch error, ...) */
   SCAT_ERR_NULL = 5    /* a required pointer is NULL */
