@@ -707,13 +707,11 @@ hipError_t launch_col_fast_t(int mode, const void *src, long nodes, int Mc, floa
              st);
 #define SCAT_COL_LAUNCH(MODE_, LM_)                                                               \
   {                                                                                               \
-    static bool attr_done = false;                                                                \
-    if (lds > 65536 && !attr_done) {                                                              \
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_col_fast<MR, MODE_, LM_>), \
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024); \
-      if (e != hipSuccess) return e;                                                              \
-      attr_done = true;                                                                           \
-    }                                                                                             \
+    static unsigned long long lds_ok = 0;                                        \
+    if (lds > 65536) {                                                            \
+      hipError_t e = allow_large_lds(reinterpret_cast<const void *>(k_col_fast<MR, MODE_, LM_>), lds_ok); \
+      if (e != hipSuccess) return e;                                        \
+    }                                                                      \
     hipLaunchKernelGGL((k_col_fast<MR, MODE_, LM_>), g, b, lds, st, src, Mc, TC, uc,              \
                        static_cast<int>(uc_half), post_tw_m, phi_rows, m_r, w_out, tw, tw_n,      \
                        y_out);                                                                    \
@@ -934,13 +932,11 @@ hipError_t launch_col_node_t(int mode, const void *src, long nodes, float2 *uc, 
   dim3 g(static_cast<unsigned>(nodes)), b(T * TC);
 #define SCAT_CN_LAUNCH(MODE_, PF_)                                                                 \
   {                                                                                                \
-    static bool attr_done = false;                                                                 \
-    if (lds > 65536 && !attr_done) {                                                               \
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_col_node<MR, MODE_, LM, PF_>), \
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);  \
-      if (e != hipSuccess) return e;                                                               \
-      attr_done = true;                                                                            \
-    }                                                                                              \
+    static unsigned long long lds_ok = 0;                                        \
+    if (lds > 65536) {                                                            \
+      hipError_t e = allow_large_lds(reinterpret_cast<const void *>(k_col_node<MR, MODE_, LM, PF_>), lds_ok); \
+      if (e != hipSuccess) return e;                                        \
+    }                                                                      \
     hipLaunchKernelGGL((k_col_node<MR, MODE_, LM, PF_>), g, b, lds, st, src, uc,                   \
                        static_cast<int>(uc_half), phi_rows, phi_cols, out, cm, K, tw, tw_n);       \
   }
@@ -1370,13 +1366,11 @@ hipError_t launch_row_lowpass_fast_t(const float *w, long nodes, int m_r, int m_
   if (lds > 160 * 1024) return hipErrorInvalidValue;
 #define SCAT_RLP_LAUNCH(LM_)                                                                       \
   {                                                                                                \
-    static bool attr_done = false;                                                                 \
-    if (lds > 65536 && !attr_done) {                                                               \
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_row_lowpass_fast<MC, LM_>), \
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);  \
-      if (e != hipSuccess) return e;                                                               \
-      attr_done = true;                                                                            \
-    }                                                                                              \
+    static unsigned long long lds_ok = 0;                                        \
+    if (lds > 65536) {                                                            \
+      hipError_t e = allow_large_lds(reinterpret_cast<const void *>(k_row_lowpass_fast<MC, LM_>), lds_ok); \
+      if (e != hipSuccess) return e;                                        \
+    }                                                                      \
     hipLaunchKernelGGL((k_row_lowpass_fast<MC, LM_>), g, b, lds, st, w, pairs, m_r, m_c, phi_cols, \
                        out, cm, K, tw, tw_n);                                                      \
   }
@@ -1675,12 +1669,11 @@ hipError_t launch_rows_fused(const float2 *src, bool src_half, long NS, int Sr, 
   // the default 64 KB of LDS, which has to be allowed once per kernel
 #define SCAT_RF_LAUNCH(SC_, MASK_)                                                                \
   {                                                                                               \
-    static bool attr_done = false;                                                                \
-    if (!attr_done) {                                                                             \
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_rows_fused<SC_, MASK_>), \
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024); \
+    static unsigned long long lds_ok = 0;                                                         \
+    {                                                                                             \
+      hipError_t e =                                                                              \
+          allow_large_lds(reinterpret_cast<const void *>(k_rows_fused<SC_, MASK_>), lds_ok);      \
       if (e != hipSuccess) return e;                                                              \
-      attr_done = true;                                                                           \
     }                                                                                             \
     hipLaunchKernelGGL((k_rows_fused<SC_, MASK_>), g, b, lds, st, src, hf, NS, Sr, G, bw, args,   \
                        tw, tw_n);                                                                 \

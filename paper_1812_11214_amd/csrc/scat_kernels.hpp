@@ -29,6 +29,19 @@ struct LaunchScope {
   bool on_;
 };
 
+// Lets kernel `fn` use up to 160 KB of dynamic LDS on the current device.  The attribute is
+// per device; `done` (one static per kernel at the call site) remembers the devices served.
+inline hipError_t allow_large_lds(const void *fn, unsigned long long &done) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const unsigned long long bit = 1ull << (dev & 63);
+  if (done & bit) return hipSuccess;
+  e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+  if (e == hipSuccess) done |= bit;
+  return e;
+}
+
 // Where a kernel's node number g (within one input plane p) lands in the output:
 // channel = base + (g / inner) * outer_stride + (g % inner), node = p * G + g.
 struct ChanMap {

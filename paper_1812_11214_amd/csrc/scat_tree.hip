@@ -421,12 +421,10 @@ hipError_t launch_tree32(const float2 *xh, long planes, int L, int max_order, co
   const long blocks = (waves + TREE_WAVES - 1) / TREE_WAVES;
   if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
   const size_t lds = static_cast<size_t>(WAVE_LDS_BYTES) * TREE_WAVES;
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_tree32),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+  static unsigned long long lds_ok = 0;
+  {
+    hipError_t e = allow_large_lds(reinterpret_cast<const void *>(k_tree32), lds_ok);
     if (e != hipSuccess) return e;
-    attr_done = true;
   }
   TreeArgs a{xh, planes, L, max_order, K, psi_j0, psi_j1, phi_cols0, phi_cols1, taps0, taps1, out};
   // least traffic: spectra in, S1 and S2 out, the 2 L wavelet tables once
