@@ -36,6 +36,9 @@ def cpu_baseline(planes, dims, J, LQ, channels, budget_s=20.0, grad=None):
         n_r, n_c = planes.shape[-2:]
         bank = oracle.bank_2d(n_r, n_c, J, LQ)
         run = lambda x: oracle.scattering2d_backward(x, grad[:len(x)], J, LQ, bank=bank)
+    elif grad is not None:
+        bank = oracle.bank_1d(planes.shape[-1], J, LQ)
+        run = lambda x: oracle.scattering1d_backward(x, grad[:len(x)], J, LQ, bank=bank)
     elif dims == 2:
         n_r, n_c = planes.shape[-2:]
         bank = oracle.bank_2d(n_r, n_c, J, LQ)     # built once, like the GPU plan; not timed
@@ -70,7 +73,7 @@ def main():
     ap.add_argument("--backward", action="store_true",
                     help="time the backward pass (gradient with respect to the input of a "
                          "seeded random dL/dS; recomputes the forward cascade inside) instead "
-                         "of the forward transform; 2-D workloads only")
+                         "of the forward transform")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (a kernel of known "
                          "traffic, to calibrate profiler byte counters)")
@@ -100,9 +103,6 @@ def main():
     out = torch.empty((P, plan.K) + plan.out_shape, dtype=torch.float32, device="cuda")
     g_host = None
     if args.backward:
-        if cfg["dims"] != 2:
-            print("bench.py: --backward needs a 2-D workload", file=sys.stderr)
-            sys.exit(2)
         g_host = np.random.default_rng(181211214).standard_normal(
             tuple(out.shape), dtype=np.float32)
         g = torch.from_numpy(g_host).cuda()

@@ -131,7 +131,7 @@ scat_status scat_forward(scat_plan *plan, const float *in, float *out, long batc
                          void *stream);
 
 /*
- * Backward pass (2-D plans): the gradient of  sum(grad_out * S(in))  with respect to `in`,
+ * Backward pass: the gradient of  sum(grad_out * S(in))  with respect to `in`,
  * i.e. the transposed Jacobian of scat_forward applied to grad_out.  The paper lists
  * differentiability as a feature of its package (section 3, "Relation to previous
  * software") without formulas; the cascade is a chain of real-linear maps and complex
@@ -147,13 +147,16 @@ scat_status scat_forward(scat_plan *plan, const float *in, float *out, long batc
  * complex signals before every modulus are kept in the plan's scratch buffer until the
  * call's work has run; the same one-call-in-flight rule as scat_forward applies, and the
  * two share the scratch buffer.  Enqueues on `stream`, does not synchronise.
- * Errors: SCAT_ERR_ARG for a 1-D plan or batch < 0; SCAT_ERR_SHAPE unless every side and
- * every side >> (J-1) lies in 4...512 and the output grid has at most 1024 points.
+ * Errors: SCAT_ERR_ARG for a padded 1-D plan or batch < 0.  SCAT_ERR_SHAPE, 2-D: unless every
+ * side and every side subsampled for the last octave lies in 4...512 and the output grid
+ * has at most 1024 points; 1-D: unless the signal, seen as the n1 x n2 matrix of the
+ * four-step transform (n2 = 2^max(ceil(log2(n)/2), J), n1 = n / n2), has n1 in 4...512 and
+ * n2 <= 512 (so n <= 2^18 at most).
  */
 scat_status scat_backward(scat_plan *plan, const float *in, const float *grad_out,
                           float *grad_in, long batch, void *stream);
 
-/* Bytes of device scratch a scat_backward call with this batch size uses (0 for 1-D). */
+/* Bytes of device scratch a scat_backward call with this batch size uses (0 if unsupported). */
 size_t scat_plan_backward_workspace_bytes(const scat_plan *plan, long batch);
 
 /* Release a plan and its device memory.  NULL is a no-op returning SCAT_OK. */

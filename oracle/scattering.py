@@ -339,6 +339,58 @@ def scattering1d(x, J, Q, max_order=2, bank=None, oversampling=0):
     return np.stack(out, axis=len(lead))
 
 
+def scattering1d_backward(x, g, J, Q, max_order=2, bank=None, oversampling=0):
+    """Gradient of sum(g * scattering1d(x)) with respect to x; the 1-D counterpart of
+    ``scattering2d_backward`` (same adjoints, one axis).
+
+    x: (..., N) real; g: (..., K, N >> rJ) real.  Returns (..., N)."""
+    x = np.asarray(x, dtype=np.float64)
+    g = np.asarray(g, dtype=np.float64)
+    n = x.shape[-1]
+    if bank is None:
+        bank = filters.bank_1d(n, J, Q)
+    psi1_hat, psi2_hat, phi_hat = bank['psi1_hat'], bank['psi2_hat'], bank['phi_hat']
+    ax = (-1,)
+    res = lambda j: max(j - oversampling, 0)
+    rJ = res(J)
+    m_pts = float(n >> rJ)
+
+    def unit(y):
+        a = np.abs(y)
+        return np.where(a > 0, y / np.where(a > 0, a, 1.0), 0.0)
+
+    def lowpass_adjoint(gs, phi_r, r):
+        return tile(np.fft.fft(gs) / m_pts, r, ax) / float(2 ** r) * phi_r
+
+    X = np.fft.fft(x)
+    gX = lowpass_adjoint(g[..., 0, :], phi_hat, rJ)
+    c1 = 1
+    c2 = 1 + J * Q
+    for k in range(J * Q):
+        j1 = bank['j1'][k]
+        r1 = res(j1)
+        n1 = float(n >> r1)
+        y1 = np.fft.ifft(sub(X * psi1_hat[k], r1, ax))
+        U1h = np.fft.fft(np.abs(y1))
+        gU1h = lowpass_adjoint(g[..., c1, :], fold(phi_hat, r1, ax), rJ - r1)
+        c1 += 1
+        if max_order >= 2:
+            for j2 in range(j1 + 1, J):
+                r2 = res(j2)
+                n2 = float(n >> r2)
+                psi_r = fold(psi2_hat[j2], r1, ax)
+                y2 = np.fft.ifft(sub(U1h * psi_r, r2 - r1, ax))
+                gVh = lowpass_adjoint(g[..., c2, :], fold(phi_hat, r2, ax), rJ - r2)
+                c2 += 1
+                gV = (np.fft.ifft(gVh) * n2).real
+                gY2 = np.fft.fft(gV * unit(y2)) / n2
+                gU1h = gU1h + tile(gY2, r2 - r1, ax) / float(2 ** (r2 - r1)) * psi_r
+        gU1 = (np.fft.ifft(gU1h) * n1).real
+        gY1 = np.fft.fft(gU1 * unit(y1)) / n1
+        gX = gX + tile(gY1, r1, ax) / float(2 ** r1) * psi1_hat[k]
+    return (np.fft.ifft(gX) * float(n)).real
+
+
 def scattering1d_plain(x, J, Q, max_order=2, bank=None):
     """The three defining equations at full resolution, sampled at 2^J n (1-D)."""
     x = np.asarray(x, dtype=np.float64)

@@ -263,10 +263,14 @@ __global__ __launch_bounds__(256) void k_fft_cols(float2 *__restrict__ data, int
 
 // Column pass of the modulus backward step: inverse transform of every column, then
 // a = Re(a) y / |y| against the taped signal y (same layout), then forward transform.
+// tw_m > 0 (1-D signals as an E*T x Mc matrix, tw_m = E*T*Mc): the data are multiplied by
+// exp(+2 pi i k1 b / tw_m) before the inverse column transform and by its conjugate after
+// the forward one (the twiddle step of the four-step transform; k1 = row, b = column).
 template <int E, int T>
 __global__ __launch_bounds__(256) void k_cols_modback(float2 *__restrict__ data,
                                                       const float2 *__restrict__ y, int Mc, int TC,
-                                                      const float2 *__restrict__ tw, int tw_n) {
+                                                      int tw_m, const float2 *__restrict__ tw,
+                                                      int tw_n) {
   constexpr int M = E * T;
   extern __shared__ float2 lds[];
   const int KS = T * TC + (E == 32 ? 0 : 1);
@@ -281,6 +285,16 @@ __global__ __launch_bounds__(256) void k_cols_modback(float2 *__restrict__ data,
   float2 v[E];
 #pragma unroll
   for (int i = 0; i < E; ++i) v[i] = p[i * step];
+  float2 fs[E];  // four-step twiddles exp(-2 pi i k1 b / tw_m) of this thread's elements
+  if (tw_m > 0) {
+    const int tstep = tw_n / tw_m;
+#pragma unroll
+    for (int i = 0; i < E; ++i) {
+      const int e = static_cast<int>((static_cast<long long>(t + T * i) * (c0 + c)) & (tw_m - 1));
+      fs[i] = tw[e * tstep];
+      v[i] = c_mul(v[i], make_float2(fs[i].x, -fs[i].y));
+    }
+  }
   float2 wt[E];
   load_twiddles<E, T>(wt, t, tw, tw_n);
   fft_core<E, T, true, false>(v, t, lds + c, KS, TC, wt);
@@ -292,8 +306,61 @@ __global__ __launch_bounds__(256) void k_cols_modback(float2 *__restrict__ data,
     v[i] = make_float2(u.x * sgn, u.y * sgn);
   }
   fft_core<E, T, false, false>(v, t, lds + c, KS, TC, wt);
+  if (tw_m > 0) {
+#pragma unroll
+    for (int i = 0; i < E; ++i) v[i] = c_mul(v[i], fs[i]);
+  }
 #pragma unroll
   for (int i = 0; i < E; ++i) p[i * step] = v[i];
+}
+
+// ---- 1-D signals (four-step layout: an n1 x Mc matrix, sample a Mc + b, frequency
+// k1 + n1 k2 stored at [k1][k2])
+
+// data[node][k1][b] *= exp(-+ 2 pi i k1 b / m): the twiddle step between the column and
+// the row pass of a four-step transform (conj = inverse direction)
+__global__ __launch_bounds__(256) void k_twiddle(float2 *__restrict__ data, long count, int lgMc,
+                                                 int lgN1, int m, int conj,
+                                                 const float2 *__restrict__ tw, int tw_n) {
+  const long stride = static_cast<long>(gridDim.x) * blockDim.x;
+  const int tstep = tw_n / m;
+  for (long i = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x; i < count; i += stride) {
+    const int b = static_cast<int>(i & ((1 << lgMc) - 1));
+    const int k1 = static_cast<int>((i >> lgMc) & ((1 << lgN1) - 1));
+    float2 w = tw[static_cast<int>((static_cast<long long>(k1) * b) & (m - 1)) * tstep];
+    if (conj) w.y = -w.y;
+    data[i] = c_mul(data[i], w);
+  }
+}
+
+// dst[node][i] = (g_out[plane][chan(cm, g)][i], 0), i < m: one gradient signal per node
+__global__ __launch_bounds__(256) void k_gather_real(const float *__restrict__ gout, ChanMap cm,
+                                                     int K, int m, float2 *__restrict__ dst,
+                                                     long count) {
+  const long stride = static_cast<long>(gridDim.x) * blockDim.x;
+  for (long i = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x; i < count; i += stride) {
+    const long node = i / m;
+    const int e = static_cast<int>(i - node * m);
+    const long p = node / cm.G;
+    const int g = static_cast<int>(node - p * cm.G);
+    dst[i] = make_float2(gout[(static_cast<size_t>(p) * K + chan(cm, g)) * m + e], 0.f);
+  }
+}
+
+// dst[node][k1][k2] = ghat[node][k1][k2 mod mc] * filt[k1][k2]   (tile along k2, one table)
+__global__ __launch_bounds__(256) void k_tile_filter(const float2 *__restrict__ ghat,
+                                                     const float *__restrict__ filt,
+                                                     float2 *__restrict__ dst, long count, int lgN1,
+                                                     int lgMc, int lgmc) {
+  const long stride = static_cast<long>(gridDim.x) * blockDim.x;
+  for (long i = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x; i < count; i += stride) {
+    const int k2 = static_cast<int>(i & ((1 << lgMc) - 1));
+    const long r = i >> lgMc;  // node * n1 + k1
+    const int k1 = static_cast<int>(r & ((1 << lgN1) - 1));
+    const float f = filt[(static_cast<size_t>(k1) << lgMc) + k2];
+    const float2 v = ghat[(static_cast<size_t>(r) << lgmc) + (k2 & ((1 << lgmc) - 1))];
+    dst[i] = make_float2(v.x * f, v.y * f);
+  }
 }
 
 int ilog2h(int v) {
@@ -347,8 +414,8 @@ hipError_t cols_t(float2 *data, long nodes, int Mc, bool inverse, const float2 *
 }
 
 template <int E, int T>
-hipError_t cols_modback_t(float2 *data, const float2 *y, long nodes, int Mc, const float2 *tw,
-                          int tw_n, hipStream_t st) {
+hipError_t cols_modback_t(float2 *data, const float2 *y, long nodes, int Mc, int tw_m,
+                          const float2 *tw, int tw_n, hipStream_t st) {
   int TC = 256 / T;
   if (TC > Mc) TC = Mc;
   const long blocks = nodes * (Mc / TC);
@@ -361,7 +428,7 @@ hipError_t cols_modback_t(float2 *data, const float2 *y, long nodes, int Mc, con
   LaunchScope obs(name.c_str(), nodes * n * Mc * 24,
                   nodes * Mc * (10.0 * n * ilog2h(E * T) + 8.0 * n), st);
   hipLaunchKernelGGL((k_cols_modback<E, T>), dim3(static_cast<unsigned>(blocks)), dim3(T * TC), lds,
-                     st, data, y, Mc, TC, tw, tw_n);
+                     st, data, y, Mc, TC, tw_m, tw, tw_n);
   return hipGetLastError();
 }
 
@@ -390,10 +457,11 @@ bool backward_side_supported(int m) { return pow2(m) && m >= 4 && m <= 512; }
 
 hipError_t launch_fft_rows_inplace(float2 *data, long rows, int Mc, bool inverse, const float2 *tw,
                                    int tw_n, hipStream_t st) {
-  if (rows <= 0) return hipSuccess;
-  if (!backward_side_supported(Mc) || tw_n % Mc != 0) return hipErrorInvalidValue;
+  if (rows <= 0 || Mc == 1) return hipSuccess;
+  if (!pow2(Mc) || Mc > 512 || tw_n % Mc != 0) return hipErrorInvalidValue;
 #define SCAT_ROWS(E_, T_) return rows_t<E_, T_>(data, rows, inverse, tw, tw_n, st)
   switch (Mc) {
+    case 2: SCAT_ROWS(2, 1);
     case 4: SCAT_ROWS(4, 1);
     case 8: SCAT_ROWS(8, 1);
     case 16: SCAT_ROWS(16, 1);
@@ -407,11 +475,12 @@ hipError_t launch_fft_rows_inplace(float2 *data, long rows, int Mc, bool inverse
 }
 
 hipError_t launch_cols_modback(float2 *data, const float2 *y, long nodes, int Mr, int Mc,
-                               const float2 *tw, int tw_n, hipStream_t st) {
+                               const float2 *tw, int tw_n, hipStream_t st, int tw_m) {
   if (nodes <= 0) return hipSuccess;
-  if (!backward_side_supported(Mr) || !backward_side_supported(Mc) || tw_n % Mr != 0)
+  if (!backward_side_supported(Mr) || !pow2(Mc) || Mc > 512 || tw_n % Mr != 0 ||
+      (tw_m > 0 && (!pow2(tw_m) || tw_n % tw_m != 0)))
     return hipErrorInvalidValue;
-#define SCAT_CM(E_, T_) return cols_modback_t<E_, T_>(data, y, nodes, Mc, tw, tw_n, st)
+#define SCAT_CM(E_, T_) return cols_modback_t<E_, T_>(data, y, nodes, Mc, tw_m, tw, tw_n, st)
   switch (Mr) {
     case 4: SCAT_CM(4, 1);
     case 8: SCAT_CM(8, 1);
@@ -423,6 +492,65 @@ hipError_t launch_cols_modback(float2 *data, const float2 *y, long nodes, int Mr
     default: SCAT_CM(32, 16);
   }
 #undef SCAT_CM
+}
+
+hipError_t launch_fft_cols_inplace(float2 *data, long nodes, int Mr, int Mc, bool inverse,
+                                   const float2 *tw, int tw_n, hipStream_t st) {
+  if (nodes <= 0) return hipSuccess;
+  if (!backward_side_supported(Mr) || !pow2(Mc) || Mc > 512 || tw_n % Mr != 0)
+    return hipErrorInvalidValue;
+#define SCAT_COLS1(E_, T_) return cols_t<E_, T_>(data, nodes, Mc, inverse, tw, tw_n, st)
+  switch (Mr) {
+    case 4: SCAT_COLS1(4, 1);
+    case 8: SCAT_COLS1(8, 1);
+    case 16: SCAT_COLS1(16, 1);
+    case 32: SCAT_COLS1(16, 2);
+    case 64: SCAT_COLS1(16, 4);
+    case 128: SCAT_COLS1(16, 8);
+    case 256: SCAT_COLS1(16, 16);
+    default: SCAT_COLS1(32, 16);
+  }
+#undef SCAT_COLS1
+}
+
+unsigned grid_for(long count) {
+  long b = (count + 255) / 256;
+  if (b > 65536 * 16) b = 65536 * 16;
+  return static_cast<unsigned>(b < 1 ? 1 : b);
+}
+
+hipError_t launch_twiddle(float2 *data, long nodes, int n1, int Mc, bool conj, const float2 *tw,
+                          int tw_n, hipStream_t st) {
+  const long count = nodes * n1 * Mc;
+  const long m = static_cast<long>(n1) * Mc;
+  if (count <= 0 || Mc == 1) return hipSuccess;  // k1 * 0 = 0: no twiddle with one column
+  if (!pow2(n1) || !pow2(Mc) || m > tw_n || tw_n % m != 0) return hipErrorInvalidValue;
+  LaunchScope obs("k_twiddle", count * 16.0, count * 6.0, st);
+  hipLaunchKernelGGL(k_twiddle, dim3(grid_for(count)), dim3(256), 0, st, data, count, ilog2h(Mc),
+                     ilog2h(n1), static_cast<int>(m), conj ? 1 : 0, tw, tw_n);
+  return hipGetLastError();
+}
+
+hipError_t launch_gather_real(const float *gout, long nodes, ChanMap cm, int K, int m, float2 *dst,
+                              hipStream_t st) {
+  const long count = nodes * m;
+  if (count <= 0) return hipSuccess;
+  LaunchScope obs("k_gather_real", count * 12.0, 0.0, st);
+  hipLaunchKernelGGL(k_gather_real, dim3(grid_for(count)), dim3(256), 0, st, gout, cm, K, m, dst,
+                     count);
+  return hipGetLastError();
+}
+
+hipError_t launch_tile_filter(const float2 *ghat, const float *filt, float2 *dst, long nodes, int n1,
+                              int Mc, int mc, hipStream_t st) {
+  const long count = nodes * n1 * Mc;
+  if (count <= 0) return hipSuccess;
+  if (!pow2(n1) || !pow2(Mc) || !pow2(mc) || mc > Mc) return hipErrorInvalidValue;
+  LaunchScope obs("k_tile_filter", count * 8.0 + nodes * 8.0 * n1 * mc + 4.0 * n1 * Mc, count * 2.0,
+                  st);
+  hipLaunchKernelGGL(k_tile_filter, dim3(grid_for(count)), dim3(256), 0, st, ghat, filt, dst, count,
+                     ilog2h(n1), ilog2h(Mc), ilog2h(mc));
+  return hipGetLastError();
 }
 
 hipError_t launch_fft2_inplace(float2 *data, long nodes, int Mr, int Mc, bool inverse,

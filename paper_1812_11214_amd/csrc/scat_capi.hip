@@ -482,16 +482,18 @@ Tape make_tape(const scat_plan &p) {
   Tape t;
   const scat::HostPlan &h = p.host;
   const size_t n = static_cast<size_t>(p.n1) * p.n2, l = h.LQ;
+  const int d = h.dims;  // grid points at resolution r: n >> (d r)
   size_t off = 0;
   for (int j1 = 0; j1 < h.J; ++j1) {
     t.y1_off.push_back(off);
-    off += l * (n >> (2 * h.res(j1)));
+    off += l * (n >> (d * h.res(j1)));
   }
   if (h.max_order == 2)
     for (int j1 = 0; j1 < h.J; ++j1)
       for (int j2 = j1 + 1; j2 < h.J; ++j2) {
         t.y2_off[{j1, j2}] = off;
-        off += l * l * (n >> (2 * h.res(j2)));
+        // 2-D: L*L children per (j1, j2); 1-D: one second-order wavelet per octave, Q parents
+        off += (d == 2 ? l * l : l) * (n >> (d * h.res(j2)));
       }
   t.total = off;
   return t;
@@ -688,31 +690,46 @@ BwdLayout make_bwd_layout(const scat_plan &p, long batch) {
   const scat::HostPlan &h = p.host;
   const size_t n = static_cast<size_t>(p.n1) * p.n2, l = h.LQ, c8 = sizeof(float2);
   const bool second = h.max_order == 2 && h.J >= 2;
-  const size_t t1 = l * n, t2 = second ? l * l * (n >> (2 * h.res(1))) : 0;
-  if (p.fused) {
-    // buffers of the fused forward schedule (see make_layout)
-    size_t ft1 = 0, ft2 = 0;
-    for (int j = 0; j < h.J; ++j) ft1 += l * (n >> (2 * h.res(j)));
-    for (int j = 1; j < h.J; ++j) ft2 += l * l * (n >> (2 * h.res(j)));
+  if (h.dims == 1) {
+    // forward buffers as in make_layout; gradients: x spectrum, one octave's first-order
+    // spectra, one (j1, j2) level's second-order spectra, output-grid spectra
     b.fwd.xh = n * c8;
-    b.fwd.t = ft1 * c8;
-    b.fwd.u = second ? l * n * c8 : 0;
-    b.fwd.v = second ? ft2 * c8 : 0;
+    b.fwd.t = l * n * c8;
+    b.fwd.u = l * n * c8;
+    b.fwd.v = 0;
+    b.tape = make_tape(p);
+    b.gx = n;
+    b.gu = l * n;
+    b.ga = second ? l * (n >> h.res(1)) : 0;
+    b.gh = l * (n >> h.res(h.J));
+    b.per_plane = b.fwd.xh + b.fwd.t + b.fwd.u + (b.tape.total + b.gx + b.gu + b.ga + b.gh) * c8;
   } else {
-    b.fwd.xh = n * c8;
-    b.fwd.t = (t1 > t2 ? t1 : t2) * c8;
-    b.fwd.u = second ? l * n * c8 : 0;
+    const size_t t1 = l * n, t2 = second ? l * l * (n >> (2 * h.res(1))) : 0;
+    if (p.fused) {
+      // buffers of the fused forward schedule (see make_layout)
+      size_t ft1 = 0, ft2 = 0;
+      for (int j = 0; j < h.J; ++j) ft1 += l * (n >> (2 * h.res(j)));
+      for (int j = 1; j < h.J; ++j) ft2 += l * l * (n >> (2 * h.res(j)));
+      b.fwd.xh = n * c8;
+      b.fwd.t = ft1 * c8;
+      b.fwd.u = second ? l * n * c8 : 0;
+      b.fwd.v = second ? ft2 * c8 : 0;
+    } else {
+      b.fwd.xh = n * c8;
+      b.fwd.t = (t1 > t2 ? t1 : t2) * c8;
+      b.fwd.u = second ? l * n * c8 : 0;
+    }
+    b.tape = make_tape(p);
+    b.gx = n;
+    b.gu = l * n;
+    b.ga = t2;
+    // spectra of the output-grid gradient planes of one launch (at most L*L, or L, nodes)
+    b.gh = (second ? l * l : l) * static_cast<size_t>(p.n1 >> h.res(h.J)) * (p.n2 >> h.res(h.J));
+    if (p.padded)
+      b.pad_floats = 2 * n + static_cast<size_t>(h.K) * (p.n1 >> h.res(h.J)) * (p.n2 >> h.res(h.J));
+    b.per_plane = b.fwd.xh + b.fwd.t + b.fwd.u + b.fwd.v +
+                  (b.tape.total + b.gx + b.gu + b.ga + b.gh) * c8 + b.pad_floats * sizeof(float);
   }
-  b.tape = make_tape(p);
-  b.gx = n;
-  b.gu = l * n;
-  b.ga = t2;
-  // spectra of the output-grid gradient planes of one launch (at most L*L, or L, nodes)
-  b.gh = (second ? l * l : l) * static_cast<size_t>(p.n1 >> h.res(h.J)) * (p.n2 >> h.res(h.J));
-  if (p.padded)
-    b.pad_floats = 2 * n + static_cast<size_t>(h.K) * (p.n1 >> h.res(h.J)) * (p.n2 >> h.res(h.J));
-  b.per_plane = b.fwd.xh + b.fwd.t + b.fwd.u + b.fwd.v +
-                (b.tape.total + b.gx + b.gu + b.ga + b.gh) * c8 + b.pad_floats * sizeof(float);
   long c = static_cast<long>(scratch_budget() / b.per_plane);
   if (c < 1) c = 1;
   if (c > batch) c = batch;
@@ -800,9 +817,89 @@ scat_status backward_2d(scat_plan *p, const float *in, const float *gout, float 
   return SCAT_OK;
 }
 
+scat_status forward_1d(scat_plan *p, const float *in, float *out, long p0, long pc,
+                       const Layout &lay, hipStream_t st, const Tape *tape = nullptr);
+
+// ---- backward pass of the 1-D cascade for one chunk (signals as n1 x n2 matrices, spectra
+// in four-step order): the same chain of adjoints as backward_2d with four-step transforms
+// (row pass, twiddle, column pass) and folds / tiles along the second digit only.
+scat_status backward_1d(scat_plan *p, const float *in, const float *gout, float *gin, long p0,
+                        long pc, BwdLayout &bl, hipStream_t st) {
+  const scat::HostPlan &h = p->host;
+  const int J = h.J, Q = h.LQ, K = h.K;
+  const int N1 = p->n1, N2 = p->n2;
+  const int N = N1 * N2;
+  const int rJ = h.res(J);
+  const int mc_out = N2 >> rJ, m = N >> rJ;
+  char *base = static_cast<char *>(p->d_scratch);
+  float2 *after_fwd = reinterpret_cast<float2 *>(base + (bl.fwd.xh + bl.fwd.t + bl.fwd.u) * pc);
+  bl.tape.base = after_fwd;
+  float2 *GX = after_fwd + bl.tape.total * pc;
+  float2 *GU = GX + bl.gx * pc;
+  float2 *GA = GU + bl.gu * pc;
+  float2 *GH = GA + bl.ga * pc;
+  const float *tab = p->d_tables;
+  const float2 *tw = p->d_tw;
+  const int tw_n = p->tw_n;
+  const float *go = gout + static_cast<size_t>(p0) * K * m;
+  float *gi = gin + static_cast<size_t>(p0) * N;
+
+  scat_status fs = forward_1d(p, in, nullptr, p0, pc, bl.fwd, st, &bl.tape);
+  if (fs != SCAT_OK) return fs;
+
+  // dst [nodes][N1][Mc] = adjoint lowpass of the nodes' output gradients: forward four-step
+  // transform of the m-sample gradient, tiled along k2, times phi^ at resolution `res`
+  auto lowpass_adj = [&](long nodes, ChanMap cm, int res, int Mc, float2 *dst) -> hipError_t {
+    hipError_t e = scat::launch_gather_real(go, nodes, cm, K, m, GH, st);
+    if (e != hipSuccess) return e;
+    e = scat::launch_fft_cols_inplace(GH, nodes, N1, mc_out, false, tw, tw_n, st);
+    if (e != hipSuccess) return e;
+    e = scat::launch_twiddle(GH, nodes, N1, mc_out, false, tw, tw_n, st);
+    if (e != hipSuccess) return e;
+    e = scat::launch_fft_rows_inplace(GH, nodes * N1, mc_out, false, tw, tw_n, st);
+    if (e != hipSuccess) return e;
+    return scat::launch_tile_filter(GH, tab + p->phi_off[res], dst, nodes, N1, Mc, mc_out, st);
+  };
+  // spectrum -> signal, modulus backward against the taped y, signal -> spectrum
+  auto through_modulus = [&](float2 *g, const float2 *y, long nodes, int Mc) -> hipError_t {
+    hipError_t e = scat::launch_fft_rows_inplace(g, nodes * N1, Mc, true, tw, tw_n, st);
+    if (e != hipSuccess) return e;
+    e = scat::launch_cols_modback(g, y, nodes, N1, Mc, tw, tw_n, st, Mc > 1 ? N1 * Mc : 0);
+    if (e != hipSuccess) return e;
+    return scat::launch_fft_rows_inplace(g, nodes * N1, Mc, false, tw, tw_n, st);
+  };
+
+  SCAT_TRY(lowpass_adj(pc, ChanMap{1, 1, 0, 0}, 0, N2, GX));
+  int s2_base = 1 + J * Q;
+  for (int j1 = 0; j1 < J; ++j1) {
+    const int r1 = h.res(j1);
+    const int Mc1 = N2 >> r1;
+    const bool kids = h.max_order == 2 && j1 < J - 1;
+    const int octs = J - 1 - j1;
+    SCAT_TRY(lowpass_adj(pc * Q, ChanMap{Q, Q, 0, 1 + j1 * Q}, r1, Mc1, GU));
+    for (int j2 = j1 + 1; kids && j2 < J; ++j2) {
+      const int r2 = h.res(j2);
+      const int Mc2 = N2 >> r2;
+      SCAT_TRY(lowpass_adj(pc * Q, ChanMap{Q, 1, octs, s2_base + (j2 - j1 - 1)}, r2, Mc2, GA));
+      SCAT_TRY(through_modulus(GA, bl.tape.base + bl.tape.y2_off.at({j1, j2}) * pc, pc * Q, Mc2));
+      SCAT_TRY(scat::launch_tile_accum(GU, tab + p->psi2_off[{r1, j2}], GA, pc * Q, 1, N1, Mc1, N1,
+                                       Mc2, st));
+    }
+    if (kids) s2_base += Q * octs;
+    SCAT_TRY(through_modulus(GU, bl.tape.base + bl.tape.y1_off[j1] * pc, pc * Q, Mc1));
+    SCAT_TRY(scat::launch_tile_accum(GX, tab + p->psi1_off[j1], GU, pc, Q, N1, N2, N1, Mc1, st));
+  }
+  // g_x = Re(inverse four-step transform of g_X^)
+  SCAT_TRY(scat::launch_fft_rows_inplace(GX, pc * N1, N2, true, tw, tw_n, st));
+  SCAT_TRY(scat::launch_twiddle(GX, pc, N1, N2, true, tw, tw_n, st));
+  SCAT_TRY(scat::launch_fft_cols_inplace(GX, pc, N1, N2, true, tw, tw_n, st));
+  SCAT_TRY(scat::launch_take_real(GX, gi, pc * static_cast<long>(N), st));
+  return SCAT_OK;
+}
+
 // ---- 1-D schedule (four-step transforms: the signal is an n1 x n2 matrix)
 scat_status forward_1d(scat_plan *p, const float *in, float *out, long p0, long pc,
-                       const Layout &lay, hipStream_t st) {
+                       const Layout &lay, hipStream_t st, const Tape *tape) {
   const scat::HostPlan &h = p->host;
   const int J = h.J, Q = h.LQ, K = h.K;
   const int N1 = p->n1, N2 = p->n2;
@@ -818,17 +915,20 @@ scat_status forward_1d(scat_plan *p, const float *in, float *out, long p0, long 
   const float2 *tw = p->d_tw;
   const int tw_n = p->tw_n;
   const float *x = in + static_cast<size_t>(p0) * N;
-  float *o = out + static_cast<size_t>(p0) * K * (N >> rJ);
+  float *o = out ? out + static_cast<size_t>(p0) * K * (N >> rJ) : nullptr;
+  const bool lp = tape == nullptr;  // form the lowpassed outputs
   const ChanMap none{1, 1, 0, 0};
 
   SCAT_TRY(scat::launch_col(0, x, pc, N1, N2, XH, N, nullptr, 0, nullptr, nullptr, none, K, tw,
                             tw_n, st));
   SCAT_TRY(scat::launch_row_fwd(XH, pc * N1, N2, tw, tw_n, st));
   // S0
-  SCAT_TRY(scat::launch_mulfold_invrow(XH, tab + p->phi_off[0], T, pc, 1, N1, N2, 0, rJ, N >> rJ, tw,
-                                       tw_n, st));
-  SCAT_TRY(scat::launch_col(2, T, pc, N1, mc_out, nullptr, 0, nullptr, 0, nullptr, o,
-                            ChanMap{1, 1, 0, 0}, K, tw, tw_n, st));
+  if (lp) {
+    SCAT_TRY(scat::launch_mulfold_invrow(XH, tab + p->phi_off[0], T, pc, 1, N1, N2, 0, rJ, N >> rJ,
+                                         tw, tw_n, st));
+    SCAT_TRY(scat::launch_col(2, T, pc, N1, mc_out, nullptr, 0, nullptr, 0, nullptr, o,
+                              ChanMap{1, 1, 0, 0}, K, tw, tw_n, st));
+  }
   int s2_base = 1 + J * Q;
   for (int j1 = 0; j1 < J; ++j1) {
     const int r1 = h.res(j1);
@@ -838,12 +938,15 @@ scat_status forward_1d(scat_plan *p, const float *in, float *out, long p0, long 
     SCAT_TRY(scat::launch_mulfold_invrow(XH, tab + p->psi1_off[j1], T, pc, Q, N1, N2, 0, r1, M1,
                                          tw, tw_n, st));
     SCAT_TRY(scat::launch_col(1, T, pc * Q, N1, Mc1, U, M1, nullptr, 0, nullptr, nullptr, none, K,
-                              tw, tw_n, st));
-    SCAT_TRY(scat::launch_row_fwd(U, pc * Q * N1, Mc1, tw, tw_n, st));
-    SCAT_TRY(scat::launch_mulfold_invrow(U, tab + p->phi_off[r1], T, pc * Q, 1, N1, Mc1, 0, rJ - r1,
-                                         N >> rJ, tw, tw_n, st));
-    SCAT_TRY(scat::launch_col(2, T, pc * Q, N1, mc_out, nullptr, 0, nullptr, 0, nullptr, o,
-                              ChanMap{Q, Q, 0, 1 + j1 * Q}, K, tw, tw_n, st));
+                              tw, tw_n, st, false,
+                              tape ? tape->base + tape->y1_off[j1] * pc : nullptr));
+    if (lp || kids) SCAT_TRY(scat::launch_row_fwd(U, pc * Q * N1, Mc1, tw, tw_n, st));
+    if (lp) {
+      SCAT_TRY(scat::launch_mulfold_invrow(U, tab + p->phi_off[r1], T, pc * Q, 1, N1, Mc1, 0,
+                                           rJ - r1, N >> rJ, tw, tw_n, st));
+      SCAT_TRY(scat::launch_col(2, T, pc * Q, N1, mc_out, nullptr, 0, nullptr, 0, nullptr, o,
+                                ChanMap{Q, Q, 0, 1 + j1 * Q}, K, tw, tw_n, st));
+    }
     if (!kids) continue;
     const int octs = J - 1 - j1;
     for (int j2 = j1 + 1; j2 < J; ++j2) {
@@ -852,8 +955,10 @@ scat_status forward_1d(scat_plan *p, const float *in, float *out, long p0, long 
       const int M2 = N >> r2;
       SCAT_TRY(scat::launch_mulfold_invrow(U, tab + p->psi2_off[{r1, j2}], T, pc * Q, 1, N1, Mc1, 0,
                                            r2 - r1, M2, tw, tw_n, st));
-      SCAT_TRY(scat::launch_col(1, T, pc * Q, N1, Mc2, V, M2, nullptr, 0, nullptr, nullptr, none, K,
-                                tw, tw_n, st));
+      SCAT_TRY(scat::launch_col(1, T, pc * Q, N1, Mc2, lp ? V : nullptr, M2, nullptr, 0, nullptr,
+                                nullptr, none, K, tw, tw_n, st, false,
+                                tape ? tape->base + tape->y2_off.at({j1, j2}) * pc : nullptr));
+      if (!lp) continue;
       SCAT_TRY(scat::launch_row_fwd(V, pc * Q * N1, Mc2, tw, tw_n, st));
       SCAT_TRY(scat::launch_mulfold_invrow(V, tab + p->phi_off[r2], T, pc * Q, 1, N1, Mc2, 0,
                                            rJ - r2, N >> rJ, tw, tw_n, st));
@@ -974,14 +1079,19 @@ scat_status scat_backward(scat_plan *plan, const float *in, const float *grad_ou
   if (plan == nullptr) return SCAT_ERR_NULL;
   if (batch < 0) return SCAT_ERR_ARG;
   const scat::HostPlan &h = plan->host;
-  if (h.dims != 2) return SCAT_ERR_ARG;
-  // every grid of the cascade must have sides the plain transforms handle, and the output
-  // grid must fit the adjoint lowpass kernel's LDS stage
-  const int small_r = plan->n1 >> h.res(h.J - 1), small_c = plan->n2 >> h.res(h.J - 1);
-  if (!scat::backward_side_supported(plan->n1) || !scat::backward_side_supported(plan->n2) ||
-      !scat::backward_side_supported(small_r) || !scat::backward_side_supported(small_c) ||
-      static_cast<long>(plan->n1 >> h.res(h.J)) * (plan->n2 >> h.res(h.J)) > 1024)
-    return SCAT_ERR_SHAPE;
+  if (h.dims == 1) {
+    // signals are n1 x n2 matrices: n1-point column transforms, row transforms of n2 >> r
+    if (plan->padded) return SCAT_ERR_ARG;
+    if (!scat::backward_side_supported(plan->n1) || plan->n2 > 512) return SCAT_ERR_SHAPE;
+  } else {
+    // every grid of the cascade must have sides the plain transforms handle, and the
+    // output grid must fit the adjoint lowpass kernel's LDS stage
+    const int small_r = plan->n1 >> h.res(h.J - 1), small_c = plan->n2 >> h.res(h.J - 1);
+    if (!scat::backward_side_supported(plan->n1) || !scat::backward_side_supported(plan->n2) ||
+        !scat::backward_side_supported(small_r) || !scat::backward_side_supported(small_c) ||
+        static_cast<long>(plan->n1 >> h.res(h.J)) * (plan->n2 >> h.res(h.J)) > 1024)
+      return SCAT_ERR_SHAPE;
+  }
   if (batch == 0) return SCAT_OK;
   if (in == nullptr || grad_out == nullptr || grad_in == nullptr) return SCAT_ERR_NULL;
   if (!plan->has_device) return SCAT_ERR_DEVICE;
@@ -1005,7 +1115,8 @@ scat_status scat_backward(scat_plan *plan, const float *in, const float *grad_ou
   for (long p0 = 0; p0 < batch; p0 += bl.chunk) {
     long pc = batch - p0 < bl.chunk ? batch - p0 : bl.chunk;
     if (!plan->padded) {
-      scat_status s = backward_2d(plan, in, grad_out, grad_in, p0, pc, bl, st);
+      scat_status s = h.dims == 1 ? backward_1d(plan, in, grad_out, grad_in, p0, pc, bl, st)
+                                  : backward_2d(plan, in, grad_out, grad_in, p0, pc, bl, st);
       if (s != SCAT_OK) return s;
       continue;
     }
@@ -1036,7 +1147,7 @@ scat_status scat_backward(scat_plan *plan, const float *in, const float *grad_ou
 }
 
 size_t scat_plan_backward_workspace_bytes(const scat_plan *plan, long batch) {
-  if (plan == nullptr || batch <= 0 || plan->host.dims != 2) return 0;
+  if (plan == nullptr || batch <= 0 || (plan->host.dims == 1 && plan->padded)) return 0;
   const BwdLayout bl = make_bwd_layout(*plan, batch);
   return bl.per_plane * static_cast<size_t>(bl.chunk);
 }

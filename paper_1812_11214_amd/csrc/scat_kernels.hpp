@@ -121,8 +121,21 @@ hipError_t launch_fft_rows_inplace(float2 *data, long rows, int Mc, bool inverse
                                    int tw_n, hipStream_t st);
 // columns of data [nodes][Mr][Mc]: inverse transform, a = Re(a) y / |y| (0 where y = 0)
 // against y of the same layout, forward transform
+// tw_m > 0: with the four-step twiddles exp(+-2 pi i k1 b / tw_m) around the column passes
 hipError_t launch_cols_modback(float2 *data, const float2 *y, long nodes, int Mr, int Mc,
-                               const float2 *tw, int tw_n, hipStream_t st);
+                               const float2 *tw, int tw_n, hipStream_t st, int tw_m = 0);
+// columns only (any power-of-two number of columns up to 512)
+hipError_t launch_fft_cols_inplace(float2 *data, long nodes, int Mr, int Mc, bool inverse,
+                                   const float2 *tw, int tw_n, hipStream_t st);
+// 1-D signals as n1 x Mc matrices: data[node][k1][b] *= exp(-+2 pi i k1 b / (n1 Mc))
+hipError_t launch_twiddle(float2 *data, long nodes, int n1, int Mc, bool conj, const float2 *tw,
+                          int tw_n, hipStream_t st);
+// dst[node][i] = (g_out[plane][chan(cm, g)][i], 0) for i < m
+hipError_t launch_gather_real(const float *gout, long nodes, ChanMap cm, int K, int m, float2 *dst,
+                              hipStream_t st);
+// dst[node][k1][k2] = ghat[node][k1][k2 mod mc] * filt[k1][k2]
+hipError_t launch_tile_filter(const float2 *ghat, const float *filt, float2 *dst, long nodes, int n1,
+                              int Mc, int mc, hipStream_t st);
 // dst [nodes][Mr][Mc] = FFT2(g_out node)[k mod m] * phi_rows[k_r] * phi_cols[k_c]; node g of
 // plane p is channel chan(cm, g) of g_out [planes][K][m_r][m_c]; m_r * m_c <= 1024
 hipError_t launch_lowpass_adj(const float *gout, long nodes, ChanMap cm, int K, int m_r, int m_c,

@@ -124,3 +124,31 @@ def test_backward_zero_input_and_zero_gradient():
     assert np.array_equal(got, only0) and np.abs(got).max() > 0
     x = rng.standard_normal((2,) + shape).astype(np.float32)
     assert np.all(_backward(shape, J, L, 2, x, np.zeros_like(g)) == 0)
+
+
+@pytest.mark.parametrize("n,J,Q,max_order,o,batch", [
+    (64, 3, 2, 2, 0, 3), (256, 4, 1, 2, 0, 2), (1024, 5, 8, 2, 0, 2), (4096, 6, 8, 1, 0, 2),
+    (2048, 2, 3, 2, 0, 2), (1024, 5, 2, 2, 2, 3), (65536, 6, 8, 2, 0, 1),
+])
+def test_backward_1d(n, J, Q, max_order, o, batch):
+    import torch
+    rng = np.random.default_rng(n + 3 * J + Q + o)
+    x = rng.standard_normal((batch, n)).astype(np.float32)
+    plan = scat.Scattering((n,), J, Q, max_order, oversampling=o)
+    try:
+        g = rng.standard_normal((batch, plan.K) + plan.out_shape).astype(np.float32)
+        gi = plan.backward(torch.from_numpy(x).cuda(), torch.from_numpy(g).cuda())
+        torch.cuda.synchronize()
+        got = gi.cpu().numpy().astype(np.float64)
+    finally:
+        plan.close()
+    want = oracle.scattering1d_backward(x.astype(np.float64), g.astype(np.float64), J, Q,
+                                        max_order, oversampling=o)
+    worst_max, worst_l2 = 0.0, 0.0
+    for p in range(batch):
+        d = got[p] - want[p]
+        worst_max = max(worst_max, np.abs(d).max() / np.abs(want[p]).max())
+        worst_l2 = max(worst_l2, np.linalg.norm(d) / np.linalg.norm(want[p]))
+    print("backward 1d", n, J, Q, max_order, o, "max-rel %.2e l2-rel %.2e" % (worst_max, worst_l2),
+          flush=True)
+    assert worst_max <= TOL_MAX and worst_l2 <= TOL_L2, (worst_max, worst_l2)

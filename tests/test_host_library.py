@@ -116,8 +116,8 @@ def test_filter_bank_1d_matches_oracle():
 
 
 def test_backward_argument_errors_need_no_gpu():
-    """scat_backward rejects 1-D plans, unsupported grids and bad arguments before it
-    touches the GPU (host-only plans are enough to see it)."""
+    """scat_backward rejects padded 1-D plans, unsupported grids and bad arguments before
+    it touches the GPU (host-only plans are enough to see it)."""
     import paper_1812_11214_amd as scat
     from paper_1812_11214_amd import binding
     L = binding.lib()
@@ -126,14 +126,21 @@ def test_backward_argument_errors_need_no_gpu():
     big = scat.scat_plan_create_host((1024, 64), 2, 2)
     ok = scat.scat_plan_create_host((64, 64), 2, 2)
     try:
-        assert L.scat_backward(one_d, None, None, None, 1, None) == 1      # SCAT_ERR_ARG
+        assert L.scat_backward(one_d, None, None, None, 1, None) == 5      # supported: NULL args
+        pad_1d = scat.scat_plan_create_padded_host((1000,), 4, 2)
+        assert L.scat_backward(pad_1d, None, None, None, 1, None) == 1     # SCAT_ERR_ARG
+        assert scat.scat_plan_backward_workspace_bytes(pad_1d, 4) == 0
+        scat.scat_plan_destroy(pad_1d)
+        long_1d = scat.scat_plan_create_host((1 << 20,), 4, 2)             # 1024 x 1024 matrix
+        assert L.scat_backward(long_1d, None, None, None, 1, None) == 2    # SCAT_ERR_SHAPE
+        scat.scat_plan_destroy(long_1d)
         assert L.scat_backward(tiny, None, None, None, 1, None) == 2       # SCAT_ERR_SHAPE
         assert L.scat_backward(big, None, None, None, 1, None) == 2
         assert L.scat_backward(ok, None, None, None, -1, None) == 1
         assert L.scat_backward(ok, None, None, None, 0, None) == 0         # no-op
         assert L.scat_backward(ok, None, None, None, 1, None) == 5         # SCAT_ERR_NULL
         assert L.scat_backward(None, None, None, None, 1, None) == 5
-        assert scat.scat_plan_backward_workspace_bytes(one_d, 4) == 0
+        assert scat.scat_plan_backward_workspace_bytes(one_d, 4) > scat.scat_plan_workspace_bytes(one_d, 4)
         assert scat.scat_plan_backward_workspace_bytes(ok, 4) > scat.scat_plan_workspace_bytes(ok, 4)
     finally:
         for p in (one_d, tiny, big, ok):

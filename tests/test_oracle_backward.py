@@ -108,3 +108,20 @@ def test_zero_input_leaves_only_the_order0_term():
     only0 = oracle.scattering2d_backward(x, g0, J, L, bank=bank)
     assert np.array_equal(full, only0)
     assert np.abs(full).max() > 0
+
+
+@pytest.mark.parametrize("n,J,Q,mo,o", [(64, 3, 2, 2, 0), (256, 4, 1, 2, 0), (128, 3, 3, 1, 0),
+                                        (64, 3, 2, 2, 1)])
+def test_1d_directional_derivative_matches_finite_differences(n, J, Q, mo, o):
+    rng = np.random.default_rng(n + J + Q + o)
+    bank = oracle.bank_1d(n, J, Q)
+    x = rng.standard_normal((2, n))
+    S = oracle.scattering1d(x, J, Q, mo, bank=bank, oversampling=o)
+    g = rng.standard_normal(S.shape)
+    gx = oracle.scattering1d_backward(x, g, J, Q, mo, bank=bank, oversampling=o)
+    f = lambda z: float(np.sum(g * oracle.scattering1d(z, J, Q, mo, bank=bank, oversampling=o)))
+    for _ in range(3):
+        d = rng.standard_normal(x.shape)
+        eps = 1e-6
+        fd = (f(x + eps * d) - f(x - eps * d)) / (2 * eps)
+        assert abs(fd - np.sum(gx * d)) <= 1e-6 * max(abs(fd), 1e-3)
