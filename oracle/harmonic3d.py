@@ -1,0 +1,128 @@
+"""Oracle for the 3-D solid harmonic scattering transform (fp64, numpy + scipy) -- TEST
+INFRASTRUCTURE, not the product; it shares no code with the HIP library.
+
+Section 2 of the paper: the 3-D transform uses solid harmonic wavelets psi_{j,l,m} (j the
+scale, l and m the azimuthal and magnetic quantum numbers) and the non-linearity
+rho(x conv psi_{j,l}) = sqrt(sum_m |x conv psi_{j,l,m}|^2); with a lowpass phi_J the three
+defining equations are S0 = x conv phi_J, S1 = rho(x conv psi_l1) conv phi_J,
+S2 = rho(rho(x conv psi_l1) conv psi_l2) conv phi_J, all convolutions periodic.
+
+The paper prints no wavelet formula, constants, index set or sampling for 3-D -- readings
+taken here ("parity unpinned by the paper"; the pins are mathematical identities):
+
+* wavelet: psi_{l,m}(u) = (2 pi)^(-3/2) exp(-|u|^2 / 2) |u|^l Y_l^m(u / |u|) (the solid
+  harmonic wavelet of the work the paper cites for it), dilated as
+  psi_{j,l,m}(u) = 2^(-3j) psi_{l,m}(2^-j u), j = 0 .. J-1, l = 0 .. L, m = -l .. l;
+* lowpass: phi_J a Gaussian of standard deviation 2^J and unit mass;
+* both sampled at the integers and periodised (summed over all grid shifts);
+* second order: same l, scales j2 > j1 (the "typical" |lambda_2| > |lambda_1| read on
+  the scale index); K = 1 + J (L+1) + (L+1) J (J-1) / 2 channels ordered S0, S1 by (j, l),
+  S2 by (j1, l, j2);
+* everything is evaluated at full resolution and the outputs are read at the samples
+  2^J n (the definition taken literally; no intermediate subsampling).
+"""
+import numpy as np
+from scipy import special
+
+
+def _grid(shape):
+    """Signed integer coordinates of the periodic grid, shape (3, N0, N1, N2)."""
+    ax = [np.fft.fftfreq(n, d=1.0 / n) for n in shape]
+    return np.stack(np.meshgrid(*ax, indexing='ij'))
+
+
+def solid_harmonic_wavelet(shape, j, l, m, shifts=2):
+    """psi_{j,l,m} sampled on the grid and periodised: sum over grid shifts of
+    2^(-3j) (2 pi)^(-3/2) exp(-|v|^2 / 2) |v|^l Y_l^m(v / |v|), v = 2^-j u."""
+    base = _grid(shape).astype(np.float64)
+    out = np.zeros(shape, dtype=np.complex128)
+    rng = range(-shifts, shifts + 1)
+    for s0 in rng:
+        for s1 in rng:
+            for s2 in rng:
+                u = base + np.array([s0 * shape[0], s1 * shape[1], s2 * shape[2]],
+                                    dtype=np.float64)[:, None, None, None]
+                v = u / float(2 ** j)
+                r = np.sqrt((v ** 2).sum(axis=0))
+                safe = np.where(r > 0, r, 1.0)
+                polar = np.arccos(np.clip(v[2] / safe, -1.0, 1.0))   # angle from the last axis
+                azim = np.arctan2(v[1], v[0])
+                Y = special.sph_harm_y(l, m, polar, azim)
+                if l > 0:
+                    Y = np.where(r > 0, Y, 0.0)      # |v|^l vanishes at the origin anyway
+                out += np.exp(-0.5 * r ** 2) * r ** l * Y
+    return out * (2.0 * np.pi) ** -1.5 / float(8 ** j)
+
+
+def gaussian_lowpass(shape, J, shifts=2):
+    sigma = float(2 ** J)
+    base = _grid(shape).astype(np.float64)
+    out = np.zeros(shape)
+    rng = range(-shifts, shifts + 1)
+    for s0 in rng:
+        for s1 in rng:
+            for s2 in rng:
+                u = base + np.array([s0 * shape[0], s1 * shape[1], s2 * shape[2]],
+                                    dtype=np.float64)[:, None, None, None]
+                out += np.exp(-0.5 * (u ** 2).sum(axis=0) / sigma ** 2)
+    return out / ((2.0 * np.pi) ** 1.5 * sigma ** 3)
+
+
+def bank_3d(shape, J, L):
+    """Spatial filters and their DFTs: psi[j][l] has shape (2l+1, N0, N1, N2)."""
+    psi = [[np.stack([solid_harmonic_wavelet(shape, j, l, m) for m in range(-l, l + 1)])
+            for l in range(L + 1)] for j in range(J)]
+    phi = gaussian_lowpass(shape, J)
+    return {'psi': psi, 'phi': phi,
+            'psi_hat': [[np.fft.fftn(p, axes=(-3, -2, -1)) for p in row] for row in psi],
+            'phi_hat': np.fft.fftn(phi)}
+
+
+def coeff_index_3d(J, L, max_order=2):
+    """Rows (order, j1, l, j2); unused fields are -1."""
+    rows = [(0, -1, -1, -1)]
+    for j in range(J):
+        for l in range(L + 1):
+            rows.append((1, j, l, -1))
+    if max_order >= 2:
+        for j1 in range(J):
+            for l in range(L + 1):
+                for j2 in range(j1 + 1, J):
+                    rows.append((2, j1, l, j2))
+    return rows
+
+
+def harmonic_scattering3d(x, J, L, max_order=2, bank=None):
+    """x: (..., N0, N1, N2) real, sides multiples of 2^J.
+    Returns (..., K, N0 >> J, N1 >> J, N2 >> J)."""
+    x = np.asarray(x, dtype=np.float64)
+    shape = x.shape[-3:]
+    if bank is None:
+        bank = bank_3d(shape, J, L)
+    psi_hat, phi_hat = bank['psi_hat'], bank['phi_hat']
+    ax = (-3, -2, -1)
+    s = 1 << J
+    lead = x.shape[:-3]
+
+    def rho(Fh, wav_hat):
+        # sqrt of the sum over m of |F conv psi_m|^2, F given by its DFT
+        y = np.fft.ifftn(Fh[..., None, :, :, :] * wav_hat, axes=ax)
+        return np.sqrt((np.abs(y) ** 2).sum(axis=-4))
+
+    def lowpass(F):
+        return np.fft.ifftn(np.fft.fftn(F, axes=ax) * phi_hat, axes=ax).real[..., ::s, ::s, ::s]
+
+    X = np.fft.fftn(x, axes=ax)
+    out = [lowpass(x)]
+    s2 = []
+    for j1 in range(J):
+        for l in range(L + 1):
+            U1 = rho(X, psi_hat[j1][l])
+            out.append(lowpass(U1))
+            if max_order < 2:
+                continue
+            U1h = np.fft.fftn(U1, axes=ax)
+            for j2 in range(j1 + 1, J):
+                s2.append(lowpass(rho(U1h, psi_hat[j2][l])))
+    out.extend(s2)
+    return np.stack(out, axis=len(lead))
