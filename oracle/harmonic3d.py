@@ -31,9 +31,17 @@ def _grid(shape):
     return np.stack(np.meshgrid(*ax, indexing='ij'))
 
 
-def solid_harmonic_wavelet(shape, j, l, m, shifts=2):
+def _shifts(shape, sigma):
+    """Grid shifts per side that reach 10 standard deviations on every axis (beyond that
+    the Gaussian factor is below 2e-22 of its peak, whatever the polynomial factor here)."""
+    return int(np.ceil(10.0 * sigma / min(shape))) + 1
+
+
+def solid_harmonic_wavelet(shape, j, l, m, shifts=None):
     """psi_{j,l,m} sampled on the grid and periodised: sum over grid shifts of
     2^(-3j) (2 pi)^(-3/2) exp(-|v|^2 / 2) |v|^l Y_l^m(v / |v|), v = 2^-j u."""
+    if shifts is None:
+        shifts = _shifts(shape, float(2 ** j))
     base = _grid(shape).astype(np.float64)
     out = np.zeros(shape, dtype=np.complex128)
     rng = range(-shifts, shifts + 1)
@@ -54,8 +62,10 @@ def solid_harmonic_wavelet(shape, j, l, m, shifts=2):
     return out * (2.0 * np.pi) ** -1.5 / float(8 ** j)
 
 
-def gaussian_lowpass(shape, J, shifts=2):
+def gaussian_lowpass(shape, J, shifts=None):
     sigma = float(2 ** J)
+    if shifts is None:
+        shifts = _shifts(shape, sigma)
     base = _grid(shape).astype(np.float64)
     out = np.zeros(shape)
     rng = range(-shifts, shifts + 1)
