@@ -24,7 +24,7 @@ ALU_PEAK_TFLOPS = 157.3        # MI355X fp32 vector peak (256 CUs x 4 SIMD x 16 
 WORKLOAD = 2                   # index into workloads.CONFIGS: 2-D J=3 L=8 256x256, 128x3 planes
 # committed rocprofv3 counter summaries, profiles/hbm_traffic_<tag>.txt, per workload index
 TRAFFIC_TAGS = {0: "2d_J2_L8_32x32_b4", 1: "2d_J2_L8_32x32_b3072", 2: "2d_J3_L8_256x256_b384",
-                3: "2d_J4_L8_512x512_b32", 4: "1d_J6_Q8_65536_b64"}
+                3: "2d_J4_L8_512x512_b32", 4: "1d_J6_Q8_65536_b64", 5: "3d_J2_L3_64x64x64_b16"}
 
 
 def cpu_baseline(planes, dims, J, LQ, channels, budget_s=20.0, grad=None):
@@ -32,7 +32,11 @@ def cpu_baseline(planes, dims, J, LQ, channels, budget_s=20.0, grad=None):
     of the workload as fit in about budget_s seconds.  With `grad` (dL/dS for every plane)
     the oracle's backward pass is timed instead of its forward pass."""
     import oracle
-    if dims == 2 and grad is not None:
+    if dims == 3:
+        from oracle import harmonic3d
+        bank = harmonic3d.bank_3d(planes.shape[-3:], J, LQ)
+        run = lambda x: harmonic3d.harmonic_scattering3d(x, J, LQ, bank=bank)
+    elif dims == 2 and grad is not None:
         n_r, n_c = planes.shape[-2:]
         bank = oracle.bank_2d(n_r, n_c, J, LQ)
         run = lambda x: oracle.scattering2d_backward(x, grad[:len(x)], J, LQ, bank=bank)
@@ -69,7 +73,8 @@ def main():
                     help="CPU time budget of the oracle baseline (0 disables it)")
     ap.add_argument("--workload", type=int, default=WORKLOAD,
                     help="index of the configuration to run (default 2 = the headline one; "
-                         "0, 1, 3, 4 are the other parity configurations)")
+                         "0, 1, 3, 4 are the other parity configurations, 5 the 3-D solid "
+                         "harmonic transform of 16 volumes of 64^3, J=2, L=3)")
     ap.add_argument("--backward", action="store_true",
                     help="time the backward pass (gradient with respect to the input of a "
                          "seeded random dL/dS; recomputes the forward cascade inside) instead "
@@ -90,6 +95,9 @@ def main():
 
     wl = args.workload
     cfg = workloads.config(wl)
+    if cfg["dims"] == 3 and args.backward:
+        print("bench.py: 3-D plans have no backward pass", file=sys.stderr)
+        sys.exit(2)
     P = workloads.num_planes(wl)
     C = cfg["channels"]
     x_host = workloads.planes(wl)

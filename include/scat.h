@@ -1,5 +1,6 @@
 /*
- * scat.h -- C ABI of the MI355X wavelet scattering library (order <= 2, 1-D and 2-D).
+ * scat.h -- C ABI of the MI355X wavelet scattering library (order <= 2; 1-D and 2-D Morlet
+ * cascades, 3-D solid harmonic scattering).
  *
  * The operation is the scattering transform of the Kymatio paper (arXiv 1812.11214),
  * section 2: with a lowpass phi_J and wavelet banks psi_lambda on a periodic grid,
@@ -57,6 +58,22 @@ typedef enum {
  *   J          number of octaves, >= 1; the output grid is shape >> J
  *   LQ         2-D: number of angles L >= 1;  1-D: first-order wavelets per octave Q >= 1
  *   max_order  1 or 2
+ *
+ * dims = 3 makes a plan for the paper's 3-D transform (section 2: solid harmonic wavelets
+ * psi_{j,l,m}, non-linearity rho(x (*) psi_{j,l}) = sqrt(sum_m |x (*) psi_{j,l,m}|^2) in
+ * place of the modulus):
+ *
+ *   shape      3 ints (slowest axis first), each a power of two in 4...256 and >= 2^J
+ *   J          number of scales 1...8, j = 0...J-1;  LQ = L, the largest degree, 0...8
+ *   channels   K = 1 + J(L+1) + (L+1) J(J-1)/2: S0; S1 by (j, l); S2 by (j1, l, j2) with the
+ *              same degree l in both layers and j2 > j1
+ *
+ * The paper prints no 3-D formulas; the reading: psi_{l,m}(u) = (2 pi)^(-3/2) e^(-|u|^2/2)
+ * |u|^l Y_l^m(u/|u|) dilated by 2^j with unit L1 scaling, phi_J a unit-mass Gaussian of
+ * standard deviation 2^J, both sampled at the integers and periodised; every convolution is
+ * evaluated on the full grid and the lowpassed result read at the samples 2^J n.  Since rho
+ * does not depend on the orthonormal basis of the degree-l harmonics, the tables hold the
+ * real harmonics.  No padded plans, oversampling or scat_backward in 3-D (SCAT_ERR_ARG).
  *
  * On success *out_plan is a new plan the caller must release with scat_plan_destroy.
  * On failure *out_plan is NULL and nothing is leaked.
@@ -116,10 +133,11 @@ scat_status scat_plan_grid_shape(const scat_plan *plan, int *shape_out);
  * Enqueue the transform of `batch` planes on `stream` (a hipStream_t passed as void*,
  * NULL = the default stream).  Does not synchronise.
  *
- *   in   device, float32, batch x shape[0] (x shape[1]), C-contiguous.  Read only.
- *   out  device, float32, batch x K x (shape[0]>>J) (x (shape[1]>>J)), C-contiguous, where
+ *   in   device, float32, batch x shape[0] (x shape[1] (x shape[2])), C-contiguous.  Read only.
+ *   out  device, float32, batch x K x (shape[0]>>J) (x (shape[1]>>J) ...), C-contiguous, where
  *        K = scat_plan_num_coeffs: channel 0 is S0, then S1 in order (j1, theta1) [1-D: by
- *        first-order wavelet index], then S2 in order (j1, theta1, j2, theta2) [1-D: (k1, j2)].
+ *        first-order wavelet index], then S2 in order (j1, theta1, j2, theta2) [1-D: (k1, j2)];
+ *        3-D: S0, then S1 by (j, l), then S2 by (j1, l, j2).
  *
  * Image channels are the caller's business: a (B, C, H, W) tensor is batch = B*C planes.
  * `in` and `out` must not overlap and must stay valid until the stream has run the work.
@@ -147,7 +165,7 @@ scat_status scat_forward(scat_plan *plan, const float *in, float *out, long batc
  * complex signals before every modulus are kept in the plan's scratch buffer until the
  * call's work has run; the same one-call-in-flight rule as scat_forward applies, and the
  * two share the scratch buffer.  Enqueues on `stream`, does not synchronise.
- * Errors: SCAT_ERR_ARG for a padded 1-D plan or batch < 0.  SCAT_ERR_SHAPE, 2-D: unless every
+ * Errors: SCAT_ERR_ARG for a padded 1-D plan, a 3-D plan or batch < 0.  SCAT_ERR_SHAPE, 2-D: unless every
  * side and every side subsampled for the last octave lies in 4...512 and the output grid
  * has at most 1024 points; 1-D: unless the signal, seen as the n1 x n2 matrix of the
  * four-step transform (n2 = 2^max(ceil(log2(n)/2), J), n1 = n / n2), has n1 in 4...512 and
@@ -173,7 +191,7 @@ scat_status scat_plan_out_shape(const scat_plan *plan, int *shape_out);
 
 /* Row c of the index table: idx = {order, j1, t1, j2, t2}, unused fields -1.
  * 2-D: t = angle index.  1-D: t1 = first-order wavelet index k (octave j1 = k / Q),
- * t2 = second-order wavelet index (= j2). */
+ * t2 = second-order wavelet index (= j2).  3-D: t1 = degree l, t2 unused. */
 scat_status scat_plan_coeff_index(const scat_plan *plan, int c, int idx[5]);
 
 /* Bytes of device scratch a scat_forward call with this batch size uses. */
@@ -187,6 +205,11 @@ size_t scat_plan_workspace_bytes(const scat_plan *plan, long batch);
  *   kind 0: lowpass phi_J folded to resolution res        (index ignored)
  *   kind 1: first-order wavelet `index` (2-D: j*L + theta; 1-D: k), res must be 0
  *   kind 2: second-order wavelet `index` (2-D: j*L + theta; 1-D: j) folded to res < j
+ * 3-D plans (res must be 0): kind 0 index 0 is the lowpass (shape[0] x shape[1] x shape[2]);
+ * kind 1 with index j*(L+1) + l gives the 2l+1 real tables of that scale and degree,
+ * (2l+1) x shape: r^l e^(-r^2/2) times the real orthonormal harmonics of degree l at
+ * w = 2^j (omega + 2 pi a), r = |w|, summed over the aliases a (the factor (-i)^l of the
+ * Fourier transform has modulus 1 and is dropped).
  * Returns SCAT_ERR_ARG if that table is not part of the plan.
  */
 scat_status scat_plan_filter(const scat_plan *plan, int kind, int index, int res,

@@ -32,9 +32,10 @@ def _grid(shape):
 
 
 def _shifts(shape, sigma):
-    """Grid shifts per side that reach 10 standard deviations on every axis (beyond that
-    the Gaussian factor is below 2e-22 of its peak, whatever the polynomial factor here)."""
-    return int(np.ceil(10.0 * sigma / min(shape))) + 1
+    """Grid shifts per side s such that the summed copies cover 10 standard deviations on
+    every axis, (s + 1/2) n >= 10 sigma (beyond that the Gaussian factor is below 2e-22 of
+    its peak, whatever the polynomial factor here)."""
+    return max(0, int(np.ceil(10.0 * sigma / min(shape) - 0.5)))
 
 
 def solid_harmonic_wavelet(shape, j, l, m, shifts=None):

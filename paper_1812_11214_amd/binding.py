@@ -103,7 +103,8 @@ def _create(fn, shape, J, LQ, max_order):
 
 
 def scat_plan_create(shape, J, LQ, max_order=2):
-    """Plan for signals of `shape` (1 or 2 sides) on the current GPU; returns a handle."""
+    """Plan for signals of `shape` on the current GPU; returns a handle.  1 or 2 sides: the
+    Morlet cascade; 3 sides: solid harmonic scattering, LQ = the largest degree L."""
     return _create(lib().scat_plan_create, shape, J, LQ, max_order)
 
 
@@ -269,8 +270,12 @@ class Scattering:
     def workspace_bytes(self, batch):
         return scat_plan_workspace_bytes(self._plan, batch)
 
-    def filter(self, kind, index, res):
+    def filter(self, kind, index, res=0):
+        """Unscaled Fourier samples of one filter.  3-D plans: kind 0 is the lowpass, kind 1
+        with index j (L+1) + l the 2l+1 real solid harmonic tables of that scale and degree."""
         shp = tuple(s >> res for s in self.grid_shape)
+        if self.dims == 3 and kind == 1:
+            shp = (2 * (int(index) % (self.LQ + 1)) + 1,) + shp
         return scat_plan_filter(self._plan, kind, index, res, shp)
 
     def forward(self, x, out=None):

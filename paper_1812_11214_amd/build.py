@@ -5,7 +5,8 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libscat.so")
-SOURCES = ("scat_host.cpp", "scat_kernels.hip", "scat_tree.hip", "scat_backward.hip", "scat_capi.hip")
+SOURCES = ("scat_host.cpp", "scat_host3d.cpp", "scat_kernels.hip", "scat_tree.hip",
+           "scat_backward.hip", "scat_3d.hip", "scat_capi.hip")
 
 
 def build(verbose=False):

@@ -14,6 +14,7 @@
 
 #include "../../include/scat.h"
 #include "scat_host.hpp"
+#include "scat_host3d.hpp"
 #include "scat_kernels.hpp"
 
 // Records a HIP event pair around launches (all, or those of one kernel name) and sums
@@ -102,6 +103,10 @@ struct scat_plan {
   std::vector<size_t> phi_off;                     // 1-D, per res
   bool fused = false;  // 2-D: the fused row pass can serve every level of this plan
   bool tree = false;   // 2-D: planes small enough for the whole-tree-in-LDS kernel
+  // 3-D solid harmonic plans (host.dims == 3; host carries J, LQ = L, max_order, K only)
+  scat::HostPlan3D h3;
+  std::vector<size_t> psi3_off;  // per (j, l): its 2l+1 tables, contiguous
+  size_t phi3_off = 0;
   // signals of any size: the caller's shape, symmetrically extended to the plan's periodic
   // grid before the transform; the output is cropped to user_out
   bool padded = false;
@@ -134,9 +139,18 @@ struct Layout {
   size_t pad_in = 0, pad_out = 0;             // padded plans: extended input, uncropped output
 };
 
+size_t bytes_per_volume_3d(const scat_plan &p);
+
 Layout make_layout(const scat_plan &p, long batch) {
   Layout L;
   const scat::HostPlan &h = p.host;
+  if (h.dims == 3) {
+    L.per_plane = bytes_per_volume_3d(p);
+    long c = static_cast<long>(scratch_budget() / L.per_plane);
+    if (c < 1) c = 1;
+    L.chunk = c > batch ? batch : c;
+    return L;
+  }
   const size_t n = static_cast<size_t>(p.n1) * p.n2;
   const bool second = h.max_order == 2 && h.J >= 2;
   const size_t c8 = sizeof(float2);
@@ -298,12 +312,51 @@ scat_status upload(scat_plan *p) {
   return SCAT_OK;
 }
 
+scat_status upload_3d(scat_plan *p);
+
+// 3-D solid harmonic plan: LQ is the largest degree L (degrees 0 .. L).
+scat_status create_3d(scat_plan **out_plan, const int *shape, int J, int L, int max_order,
+                      bool device, bool padded, int oversampling) {
+  if (padded || oversampling != 0) return SCAT_ERR_ARG;
+  int v = scat::validate_3d(shape, J, L, max_order);
+  if (v != 0) return static_cast<scat_status>(v);
+  scat_plan *p = new (std::nothrow) scat_plan;
+  if (p == nullptr) return SCAT_ERR_ALLOC;
+  try {
+    scat::build_host_plan_3d(p->h3, shape, J, L, max_order);
+  } catch (const std::bad_alloc &) {
+    delete p;
+    return SCAT_ERR_ALLOC;
+  }
+  p->host.dims = 3;
+  p->host.J = J;
+  p->host.LQ = L;
+  p->host.max_order = max_order;
+  p->host.K = p->h3.K;
+  if (device) {
+    scat_status s;
+    try {
+      s = upload_3d(p);
+    } catch (const std::bad_alloc &) {
+      s = SCAT_ERR_ALLOC;
+    }
+    if (s != SCAT_OK) {
+      free_device(p);
+      delete p;
+      return s;
+    }
+  }
+  *out_plan = p;
+  return SCAT_OK;
+}
+
 scat_status create_common(scat_plan **out_plan, int dims, const int *user_shape, int J, int LQ,
                           int max_order, bool device, bool padded = false, int oversampling = 0) {
   if (out_plan == nullptr) return SCAT_ERR_NULL;
   *out_plan = nullptr;
   if (user_shape == nullptr) return SCAT_ERR_NULL;
   if (oversampling < 0 || oversampling > 24) return SCAT_ERR_ARG;
+  if (dims == 3) return create_3d(out_plan, user_shape, J, LQ, max_order, device, padded, oversampling);
   int grid[2] = {1, 1};
   const int *shape = user_shape;
   if (padded) {
@@ -897,6 +950,107 @@ scat_status backward_1d(scat_plan *p, const float *in, const float *gout, float 
   return SCAT_OK;
 }
 
+// ---- 3-D solid harmonic plans: tables (pre-scaled by 1/n for the unnormalised inverse
+// transforms), twiddles, and the schedule of the definition at full resolution
+scat_status upload_3d(scat_plan *p) {
+  const scat::HostPlan3D &h = p->h3;
+  const size_t n = h.points();
+  const double scale = 1.0 / static_cast<double>(n);
+  std::vector<float> pool;
+  p->psi3_off.clear();
+  for (const std::vector<double> &tab : h.psi) {
+    p->psi3_off.push_back(pool.size());
+    for (double d : tab) pool.push_back(static_cast<float>(d * scale));
+  }
+  p->phi3_off = pool.size();
+  for (double d : h.phi) pool.push_back(static_cast<float>(d * scale));
+  int side = h.shape[0];
+  if (h.shape[1] > side) side = h.shape[1];
+  if (h.shape[2] > side) side = h.shape[2];
+  p->tw_n = side;
+  std::vector<float2> tw(p->tw_n);
+  const double two_pi = 6.283185307179586476925286766559;
+  for (int j = 0; j < p->tw_n; ++j) {
+    double a = -two_pi * j / p->tw_n;
+    tw[j] = make_float2(static_cast<float>(std::cos(a)), static_cast<float>(std::sin(a)));
+  }
+  if (hipGetDevice(&p->device) != hipSuccess) return SCAT_ERR_DEVICE;
+  if (hipMalloc(&p->d_tables, pool.size() * sizeof(float)) != hipSuccess) return SCAT_ERR_ALLOC;
+  if (hipMalloc(&p->d_tw, tw.size() * sizeof(float2)) != hipSuccess) return SCAT_ERR_ALLOC;
+  if (hipMemcpy(p->d_tables, pool.data(), pool.size() * sizeof(float), hipMemcpyHostToDevice) !=
+      hipSuccess)
+    return SCAT_ERR_DEVICE;
+  if (hipMemcpy(p->d_tw, tw.data(), tw.size() * sizeof(float2), hipMemcpyHostToDevice) != hipSuccess)
+    return SCAT_ERR_DEVICE;
+  p->has_device = true;
+  return SCAT_OK;
+}
+
+// scratch per volume: X^, U^ (and V^ at order 2), work buffer, all complex; |.|^2 sums, real
+size_t bytes_per_volume_3d(const scat_plan &p) {
+  const size_t n = p.h3.points();
+  return n * sizeof(float2) * (p.host.max_order == 2 && p.host.J >= 2 ? 4 : 3) + n * sizeof(float);
+}
+
+scat_status forward_3d(scat_plan *p, const float *in, float *out, long p0, long pc, hipStream_t st) {
+  const scat::HostPlan3D &h = p->h3;
+  const int n0 = h.shape[0], n1 = h.shape[1], n2 = h.shape[2];
+  const int J = h.J, L = h.L, K = h.K;
+  const size_t n = h.points();
+  const long tot = pc * static_cast<long>(n);
+  const bool second = h.max_order == 2 && J >= 2;
+  float2 *XH = static_cast<float2 *>(p->d_scratch);
+  float2 *UH = XH + tot;
+  float2 *Wk = UH + tot;
+  float2 *VH = second ? Wk + tot : nullptr;
+  float *acc = reinterpret_cast<float *>((second ? VH : Wk) + tot);
+  const float *tab = p->d_tables;
+  const float2 *tw = p->d_tw;
+  const int tw_n = p->tw_n;
+  const float *x = in + static_cast<size_t>(p0) * n;
+  const size_t mout = static_cast<size_t>(n0 >> J) * (n1 >> J) * (n2 >> J);
+  float *o = out + static_cast<size_t>(p0) * K * mout;
+  // lowpass of the signal with spectrum Fh, read at the samples 2^J n, to channel c
+  auto lowpass = [&](const float2 *Fh, int c) -> hipError_t {
+    hipError_t e = scat::launch3_mul_table(Fh, tab + p->phi3_off, Wk, pc, static_cast<long>(n), st);
+    if (e != hipSuccess) return e;
+    e = scat::launch3_fft(Wk, pc, n0, n1, n2, true, tw, tw_n, st);
+    if (e != hipSuccess) return e;
+    return scat::launch3_sample(Wk, o, pc, K, c, n0, n1, n2, J, st);
+  };
+  // dst^ = FFT3( sqrt( sum_m |IFFT3(Fh psi_{j,l,m})|^2 ) )
+  auto rho = [&](const float2 *Fh, int j, int l, float2 *dst) -> hipError_t {
+    const float *ps = tab + p->psi3_off[static_cast<size_t>(j) * (L + 1) + l];
+    for (int m = 0; m < 2 * l + 1; ++m) {
+      hipError_t e = scat::launch3_mul_table(Fh, ps + static_cast<size_t>(m) * n, Wk, pc,
+                                             static_cast<long>(n), st);
+      if (e != hipSuccess) return e;
+      e = scat::launch3_fft(Wk, pc, n0, n1, n2, true, tw, tw_n, st);
+      if (e != hipSuccess) return e;
+      e = scat::launch3_accum_abs2(Wk, acc, tot, m == 0, st);
+      if (e != hipSuccess) return e;
+    }
+    hipError_t e = scat::launch3_sqrt(acc, dst, tot, st);
+    if (e != hipSuccess) return e;
+    return scat::launch3_fft(dst, pc, n0, n1, n2, false, tw, tw_n, st);
+  };
+  SCAT_TRY(scat::launch3_real_to_complex(x, XH, tot, st));
+  SCAT_TRY(scat::launch3_fft(XH, pc, n0, n1, n2, false, tw, tw_n, st));
+  SCAT_TRY(lowpass(XH, 0));
+  int c1 = 1, c2 = 1 + J * (L + 1);
+  for (int j1 = 0; j1 < J; ++j1)
+    for (int l = 0; l <= L; ++l) {
+      SCAT_TRY(rho(XH, j1, l, UH));
+      SCAT_TRY(lowpass(UH, c1++));
+      if (!second) continue;
+      for (int j2 = j1 + 1; j2 < J; ++j2) {
+        SCAT_TRY(rho(UH, j2, l, VH));
+        SCAT_TRY(lowpass(VH, c2++));
+      }
+    }
+  return SCAT_OK;
+}
+
 // ---- 1-D schedule (four-step transforms: the signal is an n1 x n2 matrix)
 scat_status forward_1d(scat_plan *p, const float *in, float *out, long p0, long pc,
                        const Layout &lay, hipStream_t st, const Tape *tape) {
@@ -1002,6 +1156,10 @@ scat_status scat_plan_create_ex(scat_plan **out_plan, int dims, const int *shape
 scat_status scat_plan_grid_shape(const scat_plan *plan, int *shape_out) {
   if (plan == nullptr || shape_out == nullptr) return SCAT_ERR_NULL;
   const scat::HostPlan &h = plan->host;
+  if (h.dims == 3) {
+    for (int d = 0; d < 3; ++d) shape_out[d] = plan->h3.shape[d];
+    return SCAT_OK;
+  }
   if (h.dims == 2) shape_out[0] = h.shape[0];
   shape_out[h.dims == 2 ? 1 : 0] = h.shape[1];
   return SCAT_OK;
@@ -1057,7 +1215,8 @@ scat_status scat_forward(scat_plan *plan, const float *in, float *out, long batc
       cout = op;
       cp0 = 0;
     }
-    scat_status s = h.dims == 1 ? forward_1d(plan, cin, cout, cp0, pc, lay, st)
+    scat_status s = h.dims == 3   ? forward_3d(plan, cin, cout, cp0, pc, st)
+                    : h.dims == 1 ? forward_1d(plan, cin, cout, cp0, pc, lay, st)
                     : plan->tree  ? forward_2d_tree(plan, cin, cout, cp0, pc, lay, st)
                     : plan->fused ? forward_2d_fused(plan, cin, cout, cp0, pc, lay, st)
                                   : forward_2d(plan, cin, cout, cp0, pc, lay, st);
@@ -1079,6 +1238,7 @@ scat_status scat_backward(scat_plan *plan, const float *in, const float *grad_ou
   if (plan == nullptr) return SCAT_ERR_NULL;
   if (batch < 0) return SCAT_ERR_ARG;
   const scat::HostPlan &h = plan->host;
+  if (h.dims == 3) return SCAT_ERR_ARG;  // no backward pass for 3-D plans
   if (h.dims == 1) {
     // signals are n1 x n2 matrices: n1-point column transforms, row transforms of n2 >> r
     if (plan->padded) return SCAT_ERR_ARG;
@@ -1147,7 +1307,9 @@ scat_status scat_backward(scat_plan *plan, const float *in, const float *grad_ou
 }
 
 size_t scat_plan_backward_workspace_bytes(const scat_plan *plan, long batch) {
-  if (plan == nullptr || batch <= 0 || (plan->host.dims == 1 && plan->padded)) return 0;
+  if (plan == nullptr || batch <= 0 || (plan->host.dims == 1 && plan->padded) ||
+      plan->host.dims == 3)
+    return 0;
   const BwdLayout bl = make_bwd_layout(*plan, batch);
   return bl.per_plane * static_cast<size_t>(bl.chunk);
 }
@@ -1172,6 +1334,10 @@ int scat_plan_num_coeffs(const scat_plan *plan) { return plan ? plan->host.K : -
 scat_status scat_plan_out_shape(const scat_plan *plan, int *shape_out) {
   if (plan == nullptr || shape_out == nullptr) return SCAT_ERR_NULL;
   const scat::HostPlan &h = plan->host;
+  if (h.dims == 3) {
+    for (int d = 0; d < 3; ++d) shape_out[d] = plan->h3.shape[d] >> h.J;
+    return SCAT_OK;
+  }
   if (plan->padded) {
     if (h.dims == 2) shape_out[0] = plan->user_out[0];
     shape_out[h.dims == 2 ? 1 : 0] = plan->user_out[1];
@@ -1187,6 +1353,15 @@ scat_status scat_plan_out_shape(const scat_plan *plan, int *shape_out) {
 scat_status scat_plan_coeff_index(const scat_plan *plan, int c, int idx[5]) {
   if (plan == nullptr || idx == nullptr) return SCAT_ERR_NULL;
   if (c < 0 || c >= plan->host.K) return SCAT_ERR_ARG;
+  if (plan->host.dims == 3) {
+    const scat::Coeff3D &r3 = plan->h3.index[c];
+    idx[0] = r3.order;
+    idx[1] = r3.j1;
+    idx[2] = r3.l;
+    idx[3] = r3.j2;
+    idx[4] = -1;
+    return SCAT_OK;
+  }
   const scat::CoeffRow &r = plan->host.index[c];
   idx[0] = r.order;
   idx[1] = r.j1;
@@ -1205,6 +1380,17 @@ size_t scat_plan_workspace_bytes(const scat_plan *plan, long batch) {
 scat_status scat_plan_filter(const scat_plan *plan, int kind, int index, int res,
                              double *out_host) {
   if (plan == nullptr || out_host == nullptr) return SCAT_ERR_NULL;
+  if (plan->host.dims == 3) {
+    // kind 0: the lowpass; kind 1: index = j (L+1) + l gives that pair's 2l+1 real tables
+    const scat::HostPlan3D &h3 = plan->h3;
+    if (res != 0) return SCAT_ERR_ARG;
+    const std::vector<double> *v = nullptr;
+    if (kind == 0 && index == 0) v = &h3.phi;
+    if (kind == 1 && index >= 0 && index < static_cast<int>(h3.psi.size())) v = &h3.psi[index];
+    if (v == nullptr) return SCAT_ERR_ARG;
+    std::memcpy(out_host, v->data(), v->size() * sizeof(double));
+    return SCAT_OK;
+  }
   const FilterTable *t = plan->host.find(kind, index, res);
   if (t == nullptr) return SCAT_ERR_ARG;
   std::memcpy(out_host, t->v.data(), t->v.size() * sizeof(double));

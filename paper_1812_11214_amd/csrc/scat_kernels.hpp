@@ -152,4 +152,20 @@ hipError_t launch_take_real(const float2 *a, float *out, long count, hipStream_t
 hipError_t launch_tile_accum(float2 *dst, const float *filt, const float2 *G, long S, int F, int Sr,
                              int Sc, int Mr, int Mc, hipStream_t st);
 
+// ---- 3-D solid harmonic scattering (scat_3d.hip): a 3-D transform in place over
+// [volumes][n0][n1][n2] (sides 4...256) and the pointwise steps of the cascade
+hipError_t launch3_fft(float2 *data, long volumes, int n0, int n1, int n2, bool inverse,
+                       const float2 *tw, int tw_n, hipStream_t st);
+hipError_t launch3_real_to_complex(const float *x, float2 *out, long total, hipStream_t st);
+// dst[v][e] = src[v][e] * filt[e], e < n
+hipError_t launch3_mul_table(const float2 *src, const float *filt, float2 *dst, long volumes, long n,
+                             hipStream_t st);
+// acc[i] = |y[i]|^2 (first) or acc[i] + |y[i]|^2
+hipError_t launch3_accum_abs2(const float2 *y, float *acc, long total, bool first, hipStream_t st);
+// out[i] = (sqrt(acc[i]), 0)
+hipError_t launch3_sqrt(const float *acc, float2 *out, long total, hipStream_t st);
+// out[v][chan][a][b][c] = Re src[v][a 2^J][b 2^J][c 2^J], out has K channels per volume
+hipError_t launch3_sample(const float2 *src, float *out, long volumes, int K, int chan, int n0,
+                          int n1, int n2, int J, hipStream_t st);
+
 }  // namespace scat

@@ -120,12 +120,12 @@ _GENERATORS = (_white, _blobs, _pink_field, _gratings_edges, _chirps)
 
 
 def config(i):
-    """The dictionary describing configuration i (0-based)."""
-    return dict(CONFIGS[i])
+    """The dictionary describing configuration i (0-based); 5 is the 3-D volume case."""
+    return dict(VOLUME_CONFIG if i == len(CONFIGS) else CONFIGS[i])
 
 
 def num_planes(i):
-    c = CONFIGS[i]
+    c = config(i)
     return c["batch"] * c["channels"]
 
 
@@ -134,11 +134,46 @@ def planes(i, count=None, start=0):
 
     Planes are numbered batch-major (plane = image * channels + channel).
     """
-    c = CONFIGS[i]
+    c = config(i)
     if count is None:
         count = num_planes(i) - start
+    if c["dims"] == 3:
+        return volumes(c["shape"], count, start)
     out = np.empty((count,) + tuple(c["shape"]), dtype=np.float32)
     gen = _GENERATORS[i]
     for p in range(count):
         out[p] = gen(_rng(i, start + p), c["shape"]).astype(np.float32)
+    return out
+
+
+# 3-D stand-in (the paper applies the solid harmonic transform to electronic densities of
+# small molecules, section 2 and its 3-D example; no such data set is available): a sum of
+# 6 to 20 isotropic Gaussian "atoms" with integer weights 1 .. 8 and widths of 1 to 2.5
+# voxels, placed in the central half of a periodic box.
+VOLUME_CONFIG = dict(name="3d_J2_L3_64x64x64_b16", dims=3, shape=(64, 64, 64), J=2, LQ=3, batch=16,
+                     channels=1)
+_VOLUME_STREAM = 5
+
+
+def _atoms(rng, shape):
+    ax = [np.arange(n, dtype=np.float64) for n in shape]
+    vol = np.zeros(shape)
+    for _ in range(int(rng.integers(6, 21))):
+        pos = [rng.uniform(0.25 * n, 0.75 * n) for n in shape]
+        w = float(rng.integers(1, 9))
+        s = rng.uniform(1.0, 2.5)
+        g = []
+        for a, p, n in zip(ax, pos, shape):
+            d = np.abs(a - p)
+            d = np.minimum(d, n - d)                       # periodic distance
+            g.append(np.exp(-0.5 * (d / s) ** 2))
+        vol += w * g[0][:, None, None] * g[1][None, :, None] * g[2][None, None, :]
+    return vol
+
+
+def volumes(shape, count, start=0):
+    """float32 array (count, *shape) of synthetic densities, one random stream per volume."""
+    out = np.empty((count,) + tuple(shape), dtype=np.float32)
+    for p in range(count):
+        out[p] = _atoms(_rng(_VOLUME_STREAM, start + p), tuple(shape)).astype(np.float32)
     return out

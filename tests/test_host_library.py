@@ -31,7 +31,7 @@ def test_status_strings():
 @pytest.mark.parametrize("shape,J,LQ,mo,status", [
     ((32, 32), 0, 8, 2, 1), ((32, 32), 2, 0, 2, 1), ((32, 32), 2, 8, 3, 1), ((32, 32), 2, 8, 0, 1),
     ((24, 32), 2, 8, 2, 2), ((32, 2), 2, 8, 2, 2), ((8192, 32), 2, 8, 2, 2), ((100,), 2, 1, 2, 2),
-    ((32,), 6, 1, 2, 2), ((32, 32, 32), 2, 8, 2, 1),
+    ((32,), 6, 1, 2, 2), ((8, 8, 8, 8), 2, 1, 2, 1),
 ])
 def test_bad_arguments(shape, J, LQ, mo, status):
     with pytest.raises(scat.ScatError) as e:
