@@ -6,11 +6,20 @@
 // are the small kernels below.
 #include <hip/hip_runtime.h>
 
+#include <string>
+
+#include "fft_regs.hpp"
 #include "scat_kernels.hpp"
 
 namespace scat {
 
 namespace {
+
+int ilog2h(int v) {
+  int l = 0;
+  while ((1 << l) < v) ++l;
+  return l;
+}
 
 unsigned blocks_for(long total) {
   long b = (total + 255) / 256;
@@ -78,7 +87,368 @@ __global__ __launch_bounds__(256) void k3_sample(const float2 *__restrict__ src,
   }
 }
 
+
+// ---- fused passes for volumes whose (axis 1, axis 2) slabs fit a workgroup's LDS --------
+//
+// A 3-D transform is split into the two slab axes (one workgroup holds whole N1 x N2
+// slabs: rows through registers, a transposition through LDS, columns through registers)
+// and axis 0 (columns of stride N1*N2).  Around them:
+//   k3_slab_mul_inv   W_m = inverse transform over the slab axes of F^ psi^_m, all m of one
+//                     (j, l) in one launch (the slab of F^ is read once)
+//   k3_axis0_rho      inverse transform along axis 0 of every W_m, sum of squared moduli in
+//                     registers, square root, forward transform along axis 0
+//   k3_slab_fwd_low   forward transform over the slab axes (giving U^), product with the
+//                     lowpass and the sum over the aliases of the slab axes (periodic
+//                     subsampling by 2^J seen from the Fourier side)
+//   k3_fold0          the aliases of axis 0; the small inverse transforms then give S
+
+// row stride of a slab in LDS: room for the row exchange of fft_core (16 (T2 + 1) elements)
+// plus a skew that spreads the rows of one wavefront over the banks
+__host__ __device__ constexpr int slab_row_stride(int N2) {
+  return N2 == 16 ? 17 : N2 == 256 ? N2 + 48 : N2 + 16 + N2 / 16;
+}
+
+template <int N1, int N2>
+struct Slab {
+  static constexpr int T1 = N1 / 16, T2 = N2 / 16;
+  static constexpr int TS = N1 * N2 / 16;  // threads per slab, 16 points each
+  static constexpr int SPW = 256 / TS;     // slabs per workgroup
+  static constexpr int RS = slab_row_stride(N2);
+  static constexpr size_t lds_bytes = static_cast<size_t>(SPW) * N1 * RS * sizeof(float2);
+  static_assert(N1 >= 16 && N2 >= 16 && TS <= 256 && TS >= 16, "slab shape");
+
+  // v: this thread's 16 points of row r (columns t + T2 i) -> after the call its 16 points
+  // of column c (rows t1 + T1 i) of the slab transformed along both axes
+  template <bool INV>
+  static __device__ __forceinline__ void transform(float2 (&v)[16], float2 *area, int r, int t, int c,
+                                                   int t1, const float2 (&wr)[16],
+                                                   const float2 (&wc)[16]) {
+    fft_core<16, T2, INV, false>(v, t, area + r * RS, T2 + 1, 1, wr);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) area[r * RS + t + T2 * i] = v[i];
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 16; ++i) v[i] = area[(t1 + T1 * i) * RS + c];
+    __syncthreads();
+    fft_core<16, T1, INV, false>(v, t1, area + c, T1 * RS, RS, wc);
+  }
+};
+
+template <int N1, int N2>
+__global__ __launch_bounds__(256) void k3_slab_mul_inv(const float2 *__restrict__ Fh,
+                                                       const float *__restrict__ tab,
+                                                       float2 *__restrict__ W, long slabs, int n0,
+                                                       int M, size_t mstride,
+                                                       const float2 *__restrict__ tw, int tw_n) {
+  using S = Slab<N1, N2>;
+  extern __shared__ float2 lds[];
+  const int s = threadIdx.x / S::TS, q = threadIdx.x % S::TS;
+  const long slab = static_cast<long>(blockIdx.x) * S::SPW + s;
+  const bool live = slab < slabs;
+  const long sl = live ? slab : slabs - 1;  // idle threads shadow the last slab, store nothing
+  float2 *area = lds + s * N1 * S::RS;
+  const int r = q / S::T2, t = q % S::T2;
+  const int c = q % N2, t1 = q / N2;
+  const int k0 = static_cast<int>(sl % n0);
+  const size_t base = static_cast<size_t>(sl) * N1 * N2;
+  const float2 *src = Fh + base + r * N2 + t;
+  float2 f[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) f[i] = src[S::T2 * i];
+  float2 wr[16], wc[16];
+  load_twiddles<16, S::T2>(wr, t, tw, tw_n);
+  load_twiddles<16, S::T1>(wc, t1, tw, tw_n);
+  for (int m = 0; m < M; ++m) {
+    const float *tb = tab + (static_cast<size_t>(m) * n0 + k0) * N1 * N2 + r * N2 + t;
+    float2 v[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const float g = tb[S::T2 * i];
+      v[i] = make_float2(f[i].x * g, f[i].y * g);
+    }
+    S::template transform<true>(v, area, r, t, c, t1, wr, wc);
+    if (live) {
+      float2 *dst = W + static_cast<size_t>(m) * mstride + base + c;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) dst[(t1 + S::T1 * i) * N2] = v[i];
+    }
+    __syncthreads();  // the slab area is reused by the next filter
+  }
+}
+
+template <int N1, int N2>
+__global__ __launch_bounds__(256) void k3_slab_fwd_low(const float2 *__restrict__ Tin,
+                                                       float2 *__restrict__ Uout,
+                                                       const float *__restrict__ phi,
+                                                       float2 *__restrict__ P, long slabs, int n0,
+                                                       int J, size_t p_vol_stride, size_t chan_off,
+                                                       const float2 *__restrict__ tw, int tw_n) {
+  using S = Slab<N1, N2>;
+  extern __shared__ float2 lds[];
+  const int s = threadIdx.x / S::TS, q = threadIdx.x % S::TS;
+  const long slab = static_cast<long>(blockIdx.x) * S::SPW + s;
+  const bool live = slab < slabs;
+  const long sl = live ? slab : slabs - 1;
+  float2 *area = lds + s * N1 * S::RS;
+  const int r = q / S::T2, t = q % S::T2;
+  const int c = q % N2, t1 = q / N2;
+  const int k0 = static_cast<int>(sl % n0);
+  const long vol = sl / n0;
+  const size_t base = static_cast<size_t>(sl) * N1 * N2;
+  const float2 *src = Tin + base + r * N2 + t;
+  float2 v[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) v[i] = src[S::T2 * i];
+  float2 wr[16], wc[16];
+  load_twiddles<16, S::T2>(wr, t, tw, tw_n);
+  load_twiddles<16, S::T1>(wc, t1, tw, tw_n);
+  S::template transform<false>(v, area, r, t, c, t1, wr, wc);
+  if (Uout != nullptr && live) {
+    float2 *dst = Uout + base + c;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) dst[(t1 + S::T1 * i) * N2] = v[i];
+  }
+  // lowpass product, then the sum over the 4^J aliases of the slab axes
+  const float *ph = phi + static_cast<size_t>(k0) * N1 * N2 + c;
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const float g = ph[(t1 + S::T1 * i) * N2];
+    area[(t1 + S::T1 * i) * S::RS + c] = make_float2(v[i].x * g, v[i].y * g);
+  }
+  __syncthreads();
+  const int m1 = N1 >> J, m2 = N2 >> J, al = 1 << J;
+  if (!live) return;
+  float2 *dst = P + static_cast<size_t>(vol) * p_vol_stride + chan_off +
+                static_cast<size_t>(k0) * m1 * m2;
+  for (int o = q; o < m1 * m2; o += S::TS) {
+    const int a = o / m2, b = o - a * m2;
+    float2 acc = make_float2(0.f, 0.f);
+    for (int p1 = 0; p1 < al; ++p1)
+      for (int p2 = 0; p2 < al; ++p2) {
+        const float2 e = area[(a + m1 * p1) * S::RS + b + m2 * p2];
+        acc.x += e.x;
+        acc.y += e.y;
+      }
+    dst[o] = acc;
+  }
+}
+
+// Axis 0 of [volumes][E*T][Mc]: a workgroup takes TC columns of one volume, thread (t, c)
+// holds rows t + T i.  xreal != nullptr: forward transform of the real input.  Else: inverse
+// transform of the M signals W_m, root of the sum of their squared moduli, forward transform.
+template <int E, int T>
+__global__ __launch_bounds__(256) void k3_axis0_rho(const float2 *__restrict__ W,
+                                                    const float *__restrict__ xreal,
+                                                    float2 *__restrict__ dst, int Mc, int TC, int M,
+                                                    size_t mstride, const float2 *__restrict__ tw,
+                                                    int tw_n) {
+  constexpr int N0 = E * T;
+  extern __shared__ float2 lds[];
+  const int KS = T * TC + (E == 32 ? 0 : 1);
+  const int c = threadIdx.x % TC, t = threadIdx.x / TC;
+  const int tiles = Mc / TC;
+  const long vol = blockIdx.x / tiles;
+  const int c0 = static_cast<int>(blockIdx.x % tiles) * TC;
+  const size_t off = static_cast<size_t>(vol) * N0 * Mc + static_cast<size_t>(t) * Mc + c0 + c;
+  const size_t step = static_cast<size_t>(T) * Mc;
+  float2 wt[E];
+  load_twiddles<E, T>(wt, t, tw, tw_n);
+  float2 v[E];
+  if (xreal != nullptr) {
+#pragma unroll
+    for (int i = 0; i < E; ++i) v[i] = make_float2(xreal[off + i * step], 0.f);
+  } else {
+    float acc[E];
+#pragma unroll
+    for (int i = 0; i < E; ++i) acc[i] = 0.f;
+    for (int m = 0; m < M; ++m) {
+      const float2 *p = W + static_cast<size_t>(m) * mstride + off;
+#pragma unroll
+      for (int i = 0; i < E; ++i) v[i] = p[i * step];
+      fft_core<E, T, true, false>(v, t, lds + c, KS, TC, wt);
+#pragma unroll
+      for (int i = 0; i < E; ++i) acc[i] += v[i].x * v[i].x + v[i].y * v[i].y;
+    }
+#pragma unroll
+    for (int i = 0; i < E; ++i) v[i] = make_float2(__builtin_amdgcn_sqrtf(acc[i]), 0.f);
+  }
+  fft_core<E, T, false, false>(v, t, lds + c, KS, TC, wt);
+  float2 *o = dst + off;
+#pragma unroll
+  for (int i = 0; i < E; ++i) o[i * step] = v[i];
+}
+
+// Q[g][a0][e] = sum_p P[g][a0 + m0 p][e]: g over volumes x channels, e over the m1*m2
+// folded slab points
+__global__ __launch_bounds__(256) void k3_fold0(const float2 *__restrict__ P,
+                                                float2 *__restrict__ Q, long groups, int n0, int m0,
+                                                int slab) {
+  const long per = static_cast<long>(m0) * slab;
+  const long total = groups * per;
+  const long stride = static_cast<long>(gridDim.x) * blockDim.x;
+  for (long i = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x; i < total; i += stride) {
+    const long g = i / per;
+    const long e = i - g * per;  // a0 * slab + point
+    const float2 *src = P + static_cast<size_t>(g) * n0 * slab + e;
+    float2 acc = make_float2(0.f, 0.f);
+    for (int a = 0; a < n0; a += m0) {
+      const float2 u = src[static_cast<size_t>(a) * slab];
+      acc.x += u.x;
+      acc.y += u.y;
+    }
+    Q[i] = acc;
+  }
+}
+
+__global__ __launch_bounds__(256) void k3_real_part(const float2 *__restrict__ src,
+                                                    float *__restrict__ out, long total) {
+  const long stride = static_cast<long>(gridDim.x) * blockDim.x;
+  for (long i = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x; i < total; i += stride)
+    out[i] = src[i].x;
+}
+
+template <int N1, int N2>
+hipError_t slab_mul_inv_t(const float2 *Fh, const float *tab, float2 *W, long volumes, int n0, int M,
+                          const float2 *tw, int tw_n, hipStream_t st) {
+  using S = Slab<N1, N2>;
+  const long slabs = volumes * n0;
+  const long blocks = (slabs + S::SPW - 1) / S::SPW;
+  if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
+  const std::string name =
+      "k3_slab_mul_inv<" + std::to_string(N1) + ", " + std::to_string(N2) + ">";
+  const double pts = static_cast<double>(slabs) * N1 * N2;
+  LaunchScope obs(name.c_str(), pts * 8.0 * (1 + M) + 4.0 * M * n0 * N1 * N2,
+                  pts * M * (5.0 * (ilog2h(N1) + ilog2h(N2)) + 2.0), st);
+  hipLaunchKernelGGL((k3_slab_mul_inv<N1, N2>), dim3(static_cast<unsigned>(blocks)), dim3(256),
+                     S::lds_bytes, st, Fh, tab, W, slabs, n0, M,
+                     static_cast<size_t>(slabs) * N1 * N2, tw, tw_n);
+  return hipGetLastError();
+}
+
+template <int N1, int N2>
+hipError_t slab_fwd_low_t(const float2 *Tin, float2 *Uout, const float *phi, float2 *P,
+                          long volumes, int n0, int J, int K, int chan, const float2 *tw, int tw_n,
+                          hipStream_t st) {
+  using S = Slab<N1, N2>;
+  const long slabs = volumes * n0;
+  const long blocks = (slabs + S::SPW - 1) / S::SPW;
+  if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
+  const size_t folded = static_cast<size_t>(n0) * (N1 >> J) * (N2 >> J);
+  const std::string name =
+      "k3_slab_fwd_low<" + std::to_string(N1) + ", " + std::to_string(N2) + ">";
+  const double pts = static_cast<double>(slabs) * N1 * N2;
+  LaunchScope obs(name.c_str(),
+                  pts * 8.0 * (Uout ? 2 : 1) + 4.0 * n0 * N1 * N2 + 8.0 * volumes * folded,
+                  pts * (5.0 * (ilog2h(N1) + ilog2h(N2)) + 4.0), st);
+  hipLaunchKernelGGL((k3_slab_fwd_low<N1, N2>), dim3(static_cast<unsigned>(blocks)), dim3(256),
+                     S::lds_bytes, st, Tin, Uout, phi, P, slabs, n0, J, folded * K, folded * chan,
+                     tw, tw_n);
+  return hipGetLastError();
+}
+
+template <int E, int T>
+hipError_t axis0_t(const float2 *W, const float *xreal, float2 *dst, long volumes, int Mc, int M,
+                   const float2 *tw, int tw_n, hipStream_t st) {
+  int TC = 256 / T;
+  if (TC > Mc) TC = Mc;
+  const long blocks = volumes * (Mc / TC);
+  if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
+  const size_t lds =
+      T == 1 ? 0 : static_cast<size_t>(E) * (T * TC + (E == 32 ? 0 : 1)) * sizeof(float2);
+  const std::string name = "k3_axis0_rho<" + std::to_string(E) + ", " + std::to_string(T) + ">";
+  const double pts = static_cast<double>(volumes) * E * T * Mc;
+  const int passes = xreal ? 1 : M + 1;
+  LaunchScope obs(name.c_str(), pts * (xreal ? 12.0 : 8.0 * (M + 1)),
+                  pts * (passes * 5.0 * ilog2h(E * T) + (xreal ? 0.0 : 4.0 * M)), st);
+  hipLaunchKernelGGL((k3_axis0_rho<E, T>), dim3(static_cast<unsigned>(blocks)), dim3(T * TC), lds, st,
+                     W, xreal, dst, Mc, TC, M, static_cast<size_t>(volumes) * E * T * Mc, tw, tw_n);
+  return hipGetLastError();
+}
+
 }  // namespace
+
+bool fused3_supported(int n0, int n1, int n2, int J) {
+  auto p2 = [](int v) { return v > 0 && (v & (v - 1)) == 0; };
+  return p2(n0) && p2(n1) && p2(n2) && n0 >= 4 && n0 <= 256 && n1 >= 16 && n2 >= 16 &&
+         n1 * n2 <= 4096 && J >= 1 && J <= 4 && (n1 >> J) >= 1 && (n2 >> J) >= 1;
+}
+
+#define SCAT3_SLAB_DISPATCH(CALL)                  \
+  switch ((n1 << 12) | n2) {                       \
+    case (16 << 12) | 16: CALL(16, 16);            \
+    case (16 << 12) | 32: CALL(16, 32);            \
+    case (16 << 12) | 64: CALL(16, 64);            \
+    case (16 << 12) | 128: CALL(16, 128);          \
+    case (16 << 12) | 256: CALL(16, 256);          \
+    case (32 << 12) | 16: CALL(32, 16);            \
+    case (32 << 12) | 32: CALL(32, 32);            \
+    case (32 << 12) | 64: CALL(32, 64);            \
+    case (32 << 12) | 128: CALL(32, 128);          \
+    case (64 << 12) | 16: CALL(64, 16);            \
+    case (64 << 12) | 32: CALL(64, 32);            \
+    case (64 << 12) | 64: CALL(64, 64);            \
+    case (128 << 12) | 16: CALL(128, 16);          \
+    case (128 << 12) | 32: CALL(128, 32);          \
+    case (256 << 12) | 16: CALL(256, 16);          \
+    default: return hipErrorInvalidValue;          \
+  }
+
+hipError_t launch3_slab_mul_inv(const float2 *Fh, const float *tab, float2 *W, long volumes, int n0,
+                                int n1, int n2, int M, const float2 *tw, int tw_n, hipStream_t st) {
+  if (volumes <= 0 || M <= 0) return hipSuccess;
+  if (tw_n % n1 != 0 || tw_n % n2 != 0) return hipErrorInvalidValue;
+#define SCAT3_A(A_, B_) return slab_mul_inv_t<A_, B_>(Fh, tab, W, volumes, n0, M, tw, tw_n, st)
+  SCAT3_SLAB_DISPATCH(SCAT3_A)
+#undef SCAT3_A
+}
+
+hipError_t launch3_slab_fwd_low(const float2 *Tin, float2 *Uout, const float *phi, float2 *P,
+                                long volumes, int n0, int n1, int n2, int J, int K, int chan,
+                                const float2 *tw, int tw_n, hipStream_t st) {
+  if (volumes <= 0) return hipSuccess;
+  if (tw_n % n1 != 0 || tw_n % n2 != 0 || J < 1 || J > 4 || (n1 >> J) < 1 || (n2 >> J) < 1)
+    return hipErrorInvalidValue;
+#define SCAT3_C(A_, B_) \
+  return slab_fwd_low_t<A_, B_>(Tin, Uout, phi, P, volumes, n0, J, K, chan, tw, tw_n, st)
+  SCAT3_SLAB_DISPATCH(SCAT3_C)
+#undef SCAT3_C
+}
+
+hipError_t launch3_axis0_rho(const float2 *W, const float *xreal, float2 *dst, long volumes, int n0,
+                             int Mc, int M, const float2 *tw, int tw_n, hipStream_t st) {
+  if (volumes <= 0) return hipSuccess;
+  if (tw_n % n0 != 0 || Mc < 256 || (Mc & (Mc - 1)) != 0 || (xreal == nullptr && M <= 0))
+    return hipErrorInvalidValue;
+#define SCAT3_B(E_, T_) return axis0_t<E_, T_>(W, xreal, dst, volumes, Mc, M, tw, tw_n, st)
+  switch (n0) {
+    case 4: SCAT3_B(4, 1);
+    case 8: SCAT3_B(8, 1);
+    case 16: SCAT3_B(16, 1);
+    case 32: SCAT3_B(16, 2);
+    case 64: SCAT3_B(16, 4);
+    case 128: SCAT3_B(16, 8);
+    case 256: SCAT3_B(16, 16);
+    default: return hipErrorInvalidValue;
+  }
+#undef SCAT3_B
+}
+
+hipError_t launch3_fold0(const float2 *P, float2 *Q, long groups, int n0, int m0, int slab,
+                         hipStream_t st) {
+  const long total = groups * m0 * slab;
+  if (total <= 0) return hipSuccess;
+  LaunchScope obs("k3_fold0", groups * 8.0 * slab * (n0 + m0), groups * 2.0 * slab * n0, st);
+  hipLaunchKernelGGL(k3_fold0, dim3(blocks_for(total)), dim3(256), 0, st, P, Q, groups, n0, m0, slab);
+  return hipGetLastError();
+}
+
+hipError_t launch3_real_part(const float2 *src, float *out, long total, hipStream_t st) {
+  if (total <= 0) return hipSuccess;
+  LaunchScope obs("k3_real_part", total * 12.0, 0.0, st);
+  hipLaunchKernelGGL(k3_real_part, dim3(blocks_for(total)), dim3(256), 0, st, src, out, total);
+  return hipGetLastError();
+}
 
 hipError_t launch3_fft(float2 *data, long volumes, int n0, int n1, int n2, bool inverse,
                        const float2 *tw, int tw_n, hipStream_t st) {

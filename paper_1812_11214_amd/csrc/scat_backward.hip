@@ -496,10 +496,11 @@ hipError_t launch_cols_modback(float2 *data, const float2 *y, long nodes, int Mr
 
 hipError_t launch_fft_cols_inplace(float2 *data, long nodes, int Mr, int Mc, bool inverse,
                                    const float2 *tw, int tw_n, hipStream_t st) {
-  if (nodes <= 0) return hipSuccess;
-  if (!backward_side_supported(Mr) || !pow2(Mc) || tw_n % Mr != 0) return hipErrorInvalidValue;
+  if (nodes <= 0 || Mr == 1) return hipSuccess;
+  if (!pow2(Mr) || Mr > 512 || !pow2(Mc) || tw_n % Mr != 0) return hipErrorInvalidValue;
 #define SCAT_COLS1(E_, T_) return cols_t<E_, T_>(data, nodes, Mc, inverse, tw, tw_n, st)
   switch (Mr) {
+    case 2: SCAT_COLS1(2, 1);
     case 4: SCAT_COLS1(4, 1);
     case 8: SCAT_COLS1(8, 1);
     case 16: SCAT_COLS1(16, 1);

@@ -107,6 +107,7 @@ struct scat_plan {
   scat::HostPlan3D h3;
   std::vector<size_t> psi3_off;  // per (j, l): its 2l+1 tables, contiguous
   size_t phi3_off = 0;
+  bool fused3 = false;  // 3-D: slabs of the two fast axes fit a workgroup (fused passes)
   // signals of any size: the caller's shape, symmetrically extended to the plan's periodic
   // grid before the transform; the output is cropped to user_out
   bool padded = false;
@@ -333,6 +334,7 @@ scat_status create_3d(scat_plan **out_plan, const int *shape, int J, int L, int 
   p->host.LQ = L;
   p->host.max_order = max_order;
   p->host.K = p->h3.K;
+  p->fused3 = scat::fused3_supported(shape[0], shape[1], shape[2], J);
   if (device) {
     scat_status s;
     try {
@@ -986,10 +988,65 @@ scat_status upload_3d(scat_plan *p) {
   return SCAT_OK;
 }
 
-// scratch per volume: X^, U^ (and V^ at order 2), work buffer, all complex; |.|^2 sums, real
+// scratch per volume.  General path: X^, U^ (and V^ at order 2), work buffer, all complex;
+// |.|^2 sums, real.  Fused path: X^, U^, the axis-0 stage T, the 2L+1 filtered signals W_m,
+// the slab-folded lowpass spectra P of all K channels and their fully folded form Q.
 size_t bytes_per_volume_3d(const scat_plan &p) {
-  const size_t n = p.h3.points();
-  return n * sizeof(float2) * (p.host.max_order == 2 && p.host.J >= 2 ? 4 : 3) + n * sizeof(float);
+  const scat::HostPlan3D &h = p.h3;
+  const size_t n = h.points();
+  if (!p.fused3)
+    return n * sizeof(float2) * (p.host.max_order == 2 && p.host.J >= 2 ? 4 : 3) + n * sizeof(float);
+  const size_t folded12 = static_cast<size_t>(h.shape[0]) * (h.shape[1] >> h.J) * (h.shape[2] >> h.J);
+  return (n * (3 + 2 * h.L + 1) + static_cast<size_t>(h.K) * (folded12 + (n >> (3 * h.J)))) *
+         sizeof(float2);
+}
+
+scat_status forward_3d_fused(scat_plan *p, const float *in, float *out, long p0, long pc,
+                             hipStream_t st) {
+  const scat::HostPlan3D &h = p->h3;
+  const int n0 = h.shape[0], n1 = h.shape[1], n2 = h.shape[2];
+  const int J = h.J, L = h.L, K = h.K;
+  const size_t n = h.points();
+  const size_t tot = static_cast<size_t>(pc) * n;
+  const bool second = h.max_order == 2 && J >= 2;
+  const int m0 = n0 >> J, m1 = n1 >> J, m2 = n2 >> J;
+  float2 *XH = static_cast<float2 *>(p->d_scratch);
+  float2 *UH = XH + tot;
+  float2 *T = UH + tot;
+  float2 *W = T + tot;
+  float2 *P = W + tot * (2 * L + 1);
+  float2 *Q = P + static_cast<size_t>(pc) * K * n0 * m1 * m2;
+  const float *tab = p->d_tables;
+  const float2 *tw = p->d_tw;
+  const int tw_n = p->tw_n;
+  const float *x = in + static_cast<size_t>(p0) * n;
+  const size_t mout = static_cast<size_t>(m0) * m1 * m2;
+  float *o = out + static_cast<size_t>(p0) * K * mout;
+  const float *phi = tab + p->phi3_off;
+  // dst^ (may be null) and channel c from the signal whose 2l+1 filtered versions come from Fh
+  auto node = [&](const float2 *Fh, int j, int l, float2 *dst, int c) -> hipError_t {
+    const float *ps = tab + p->psi3_off[static_cast<size_t>(j) * (L + 1) + l];
+    hipError_t e = scat::launch3_slab_mul_inv(Fh, ps, W, pc, n0, n1, n2, 2 * l + 1, tw, tw_n, st);
+    if (e != hipSuccess) return e;
+    e = scat::launch3_axis0_rho(W, nullptr, T, pc, n0, n1 * n2, 2 * l + 1, tw, tw_n, st);
+    if (e != hipSuccess) return e;
+    return scat::launch3_slab_fwd_low(T, dst, phi, P, pc, n0, n1, n2, J, K, c, tw, tw_n, st);
+  };
+  SCAT_TRY(scat::launch3_axis0_rho(nullptr, x, T, pc, n0, n1 * n2, 0, tw, tw_n, st));
+  SCAT_TRY(scat::launch3_slab_fwd_low(T, XH, phi, P, pc, n0, n1, n2, J, K, 0, tw, tw_n, st));
+  int c1 = 1, c2 = 1 + J * (L + 1);
+  for (int j1 = 0; j1 < J; ++j1)
+    for (int l = 0; l <= L; ++l) {
+      const bool kids = second && j1 < J - 1;
+      SCAT_TRY(node(XH, j1, l, kids ? UH : nullptr, c1++));
+      if (!kids) continue;
+      for (int j2 = j1 + 1; j2 < J; ++j2) SCAT_TRY(node(UH, j2, l, nullptr, c2++));
+    }
+  // aliases of axis 0, small inverse transforms, real parts: all channels at once
+  SCAT_TRY(scat::launch3_fold0(P, Q, pc * K, n0, m0, m1 * m2, st));
+  SCAT_TRY(scat::launch3_fft(Q, pc * K, m0, m1, m2, true, tw, tw_n, st));
+  SCAT_TRY(scat::launch3_real_part(Q, o, pc * K * static_cast<long>(mout), st));
+  return SCAT_OK;
 }
 
 scat_status forward_3d(scat_plan *p, const float *in, float *out, long p0, long pc, hipStream_t st) {
@@ -1215,7 +1272,8 @@ scat_status scat_forward(scat_plan *plan, const float *in, float *out, long batc
       cout = op;
       cp0 = 0;
     }
-    scat_status s = h.dims == 3   ? forward_3d(plan, cin, cout, cp0, pc, st)
+    scat_status s = h.dims == 3   ? (plan->fused3 ? forward_3d_fused(plan, cin, cout, cp0, pc, st)
+                                                  : forward_3d(plan, cin, cout, cp0, pc, st))
                     : h.dims == 1 ? forward_1d(plan, cin, cout, cp0, pc, lay, st)
                     : plan->tree  ? forward_2d_tree(plan, cin, cout, cp0, pc, lay, st)
                     : plan->fused ? forward_2d_fused(plan, cin, cout, cp0, pc, lay, st)

@@ -94,6 +94,10 @@ def _check(x, J, L, max_order=2):
 @pytest.mark.parametrize("shape,J,L,mo", [
     ((16, 16, 16), 2, 2, 2), ((32, 32, 32), 2, 3, 2), ((8, 16, 32), 1, 1, 2),
     ((16, 16, 16), 3, 1, 2), ((32, 16, 8), 2, 2, 1), ((4, 4, 4), 1, 0, 2), ((16, 8, 64), 2, 4, 2),
+    # shapes of the fused passes (both fast axes >= 16, slabs of at most 4096 points)
+    ((4, 16, 16), 2, 1, 2), ((8, 64, 16), 3, 2, 2), ((16, 16, 256), 2, 1, 2),
+    ((8, 256, 16), 1, 1, 2), ((32, 32, 128), 2, 1, 2), ((16, 128, 32), 4, 1, 2),
+    ((16, 32, 16), 2, 8, 1), ((128, 16, 64), 2, 0, 2),
 ])
 def test_parity_density_volumes(shape, J, L, mo):
     _check(workloads.volumes(shape, 3), J, L, mo)
