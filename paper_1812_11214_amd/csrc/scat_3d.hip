@@ -93,8 +93,12 @@ __global__ __launch_bounds__(256) void k3_sample(const float2 *__restrict__ src,
 // A 3-D transform is split into the two slab axes (one workgroup holds whole N1 x N2
 // slabs: rows through registers, a transposition through LDS, columns through registers)
 // and axis 0 (columns of stride N1*N2).  Around them:
-//   k3_slab_mul_inv   W_m = inverse transform over the slab axes of F^ psi^_m, all m of one
-//                     (j, l) in one launch (the slab of F^ is read once)
+//   k3_slab_mul_inv   W_p = inverse transform over the slab axes of F^ (g_2p + i g_2p+1), all
+//                     pairs of one (j, l) in one launch (the slab of F^ is read once).  The
+//                     signal F is real and the tables g_m are real with the parity of l, so
+//                     F conv g_m is real (l even) or imaginary (l odd) and one complex
+//                     transform carries two of them: |W_p|^2 = |F conv g_2p|^2 +
+//                     |F conv g_2p+1|^2, which is all the non-linearity needs
 //   k3_axis0_rho      inverse transform along axis 0 of every W_m, sum of squared moduli in
 //                     registers, square root, forward transform along axis 0
 //   k3_slab_fwd_low   forward transform over the slab axes (giving U^), product with the
@@ -136,7 +140,7 @@ struct Slab {
 
 template <int N1, int N2>
 __global__ __launch_bounds__(256) void k3_slab_mul_inv(const float2 *__restrict__ Fh,
-                                                       const float *__restrict__ tab,
+                                                       const float2 *__restrict__ tab,
                                                        float2 *__restrict__ W, long slabs, int n0,
                                                        int M, size_t mstride,
                                                        const float2 *__restrict__ tw, int tw_n) {
@@ -159,13 +163,10 @@ __global__ __launch_bounds__(256) void k3_slab_mul_inv(const float2 *__restrict_
   load_twiddles<16, S::T2>(wr, t, tw, tw_n);
   load_twiddles<16, S::T1>(wc, t1, tw, tw_n);
   for (int m = 0; m < M; ++m) {
-    const float *tb = tab + (static_cast<size_t>(m) * n0 + k0) * N1 * N2 + r * N2 + t;
+    const float2 *tb = tab + (static_cast<size_t>(m) * n0 + k0) * N1 * N2 + r * N2 + t;
     float2 v[16];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const float g = tb[S::T2 * i];
-      v[i] = make_float2(f[i].x * g, f[i].y * g);
-    }
+    for (int i = 0; i < 16; ++i) v[i] = c_mul(f[i], tb[S::T2 * i]);
     S::template transform<true>(v, area, r, t, c, t1, wr, wc);
     if (live) {
       float2 *dst = W + static_cast<size_t>(m) * mstride + base + c;
@@ -309,7 +310,7 @@ __global__ __launch_bounds__(256) void k3_real_part(const float2 *__restrict__ s
 }
 
 template <int N1, int N2>
-hipError_t slab_mul_inv_t(const float2 *Fh, const float *tab, float2 *W, long volumes, int n0, int M,
+hipError_t slab_mul_inv_t(const float2 *Fh, const float2 *tab, float2 *W, long volumes, int n0, int M,
                           const float2 *tw, int tw_n, hipStream_t st) {
   using S = Slab<N1, N2>;
   const long slabs = volumes * n0;
@@ -318,8 +319,8 @@ hipError_t slab_mul_inv_t(const float2 *Fh, const float *tab, float2 *W, long vo
   const std::string name =
       "k3_slab_mul_inv<" + std::to_string(N1) + ", " + std::to_string(N2) + ">";
   const double pts = static_cast<double>(slabs) * N1 * N2;
-  LaunchScope obs(name.c_str(), pts * 8.0 * (1 + M) + 4.0 * M * n0 * N1 * N2,
-                  pts * M * (5.0 * (ilog2h(N1) + ilog2h(N2)) + 2.0), st);
+  LaunchScope obs(name.c_str(), pts * 8.0 * (1 + M) + 8.0 * M * n0 * N1 * N2,
+                  pts * M * (5.0 * (ilog2h(N1) + ilog2h(N2)) + 6.0), st);
   hipLaunchKernelGGL((k3_slab_mul_inv<N1, N2>), dim3(static_cast<unsigned>(blocks)), dim3(256),
                      S::lds_bytes, st, Fh, tab, W, slabs, n0, M,
                      static_cast<size_t>(slabs) * N1 * N2, tw, tw_n);
@@ -394,7 +395,7 @@ bool fused3_supported(int n0, int n1, int n2, int J) {
     default: return hipErrorInvalidValue;          \
   }
 
-hipError_t launch3_slab_mul_inv(const float2 *Fh, const float *tab, float2 *W, long volumes, int n0,
+hipError_t launch3_slab_mul_inv(const float2 *Fh, const float2 *tab, float2 *W, long volumes, int n0,
                                 int n1, int n2, int M, const float2 *tw, int tw_n, hipStream_t st) {
   if (volumes <= 0 || M <= 0) return hipSuccess;
   if (tw_n % n1 != 0 || tw_n % n2 != 0) return hipErrorInvalidValue;

@@ -960,9 +960,21 @@ scat_status upload_3d(scat_plan *p) {
   const double scale = 1.0 / static_cast<double>(n);
   std::vector<float> pool;
   p->psi3_off.clear();
-  for (const std::vector<double> &tab : h.psi) {
+  for (size_t jl = 0; jl < h.psi.size(); ++jl) {
+    const std::vector<double> &tab = h.psi[jl];
     p->psi3_off.push_back(pool.size());
-    for (double d : tab) pool.push_back(static_cast<float>(d * scale));
+    if (!p->fused3) {
+      for (double d : tab) pool.push_back(static_cast<float>(d * scale));
+      continue;
+    }
+    // fused passes: tables interleaved in pairs (g_2p, g_2p+1) as complex numbers, the
+    // unpaired last one with a zero partner (pool.size() stays even: 8-byte aligned)
+    const int M = static_cast<int>(tab.size() / n);
+    for (int m = 0; m < M; m += 2)
+      for (size_t e = 0; e < n; ++e) {
+        pool.push_back(static_cast<float>(tab[m * n + e] * scale));
+        pool.push_back(m + 1 < M ? static_cast<float>(tab[(m + 1) * n + e] * scale) : 0.f);
+      }
   }
   p->phi3_off = pool.size();
   for (double d : h.phi) pool.push_back(static_cast<float>(d * scale));
@@ -997,7 +1009,7 @@ size_t bytes_per_volume_3d(const scat_plan &p) {
   if (!p.fused3)
     return n * sizeof(float2) * (p.host.max_order == 2 && p.host.J >= 2 ? 4 : 3) + n * sizeof(float);
   const size_t folded12 = static_cast<size_t>(h.shape[0]) * (h.shape[1] >> h.J) * (h.shape[2] >> h.J);
-  return (n * (3 + 2 * h.L + 1) + static_cast<size_t>(h.K) * (folded12 + (n >> (3 * h.J)))) *
+  return (n * (3 + h.L + 1) + static_cast<size_t>(h.K) * (folded12 + (n >> (3 * h.J)))) *
          sizeof(float2);
 }
 
@@ -1014,7 +1026,7 @@ scat_status forward_3d_fused(scat_plan *p, const float *in, float *out, long p0,
   float2 *UH = XH + tot;
   float2 *T = UH + tot;
   float2 *W = T + tot;
-  float2 *P = W + tot * (2 * L + 1);
+  float2 *P = W + tot * (L + 1);
   float2 *Q = P + static_cast<size_t>(pc) * K * n0 * m1 * m2;
   const float *tab = p->d_tables;
   const float2 *tw = p->d_tw;
@@ -1023,12 +1035,14 @@ scat_status forward_3d_fused(scat_plan *p, const float *in, float *out, long p0,
   const size_t mout = static_cast<size_t>(m0) * m1 * m2;
   float *o = out + static_cast<size_t>(p0) * K * mout;
   const float *phi = tab + p->phi3_off;
-  // dst^ (may be null) and channel c from the signal whose 2l+1 filtered versions come from Fh
+  // dst^ (may be null) and channel c from the real signal with spectrum Fh; its 2l+1
+  // filtered versions travel as l+1 complex signals
   auto node = [&](const float2 *Fh, int j, int l, float2 *dst, int c) -> hipError_t {
-    const float *ps = tab + p->psi3_off[static_cast<size_t>(j) * (L + 1) + l];
-    hipError_t e = scat::launch3_slab_mul_inv(Fh, ps, W, pc, n0, n1, n2, 2 * l + 1, tw, tw_n, st);
+    const float2 *ps = reinterpret_cast<const float2 *>(
+        tab + p->psi3_off[static_cast<size_t>(j) * (L + 1) + l]);
+    hipError_t e = scat::launch3_slab_mul_inv(Fh, ps, W, pc, n0, n1, n2, l + 1, tw, tw_n, st);
     if (e != hipSuccess) return e;
-    e = scat::launch3_axis0_rho(W, nullptr, T, pc, n0, n1 * n2, 2 * l + 1, tw, tw_n, st);
+    e = scat::launch3_axis0_rho(W, nullptr, T, pc, n0, n1 * n2, l + 1, tw, tw_n, st);
     if (e != hipSuccess) return e;
     return scat::launch3_slab_fwd_low(T, dst, phi, P, pc, n0, n1, n2, J, K, c, tw, tw_n, st);
   };

@@ -156,7 +156,7 @@ hipError_t launch_tile_accum(float2 *dst, const float *filt, const float2 *G, lo
 // [volumes][n0][n1][n2] (sides 4...256) and the pointwise steps of the cascade
 // fused 3-D passes (slabs of axes 1 and 2 held by one workgroup); see scat_3d.hip
 bool fused3_supported(int n0, int n1, int n2, int J);
-hipError_t launch3_slab_mul_inv(const float2 *Fh, const float *tab, float2 *W, long volumes, int n0,
+hipError_t launch3_slab_mul_inv(const float2 *Fh, const float2 *tab, float2 *W, long volumes, int n0,
                                 int n1, int n2, int M, const float2 *tw, int tw_n, hipStream_t st);
 hipError_t launch3_slab_fwd_low(const float2 *Tin, float2 *Uout, const float *phi, float2 *P,
                                 long volumes, int n0, int n1, int n2, int J, int K, int chan,
