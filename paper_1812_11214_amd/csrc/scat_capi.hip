@@ -3,6 +3,7 @@
 // "Implementation": depth-first traversal, downsampled intermediates).
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
@@ -142,6 +143,20 @@ struct Layout {
 
 size_t bytes_per_volume_3d(const scat_plan &p);
 
+// 1-D: elements per signal of the row-pass output buffer T.  It first holds one octave's Q
+// first-order signals (consumed by the column pass) and then, at once, that octave's
+// second-order row-pass outputs of all coarser octaves.
+size_t t_elems_1d(const scat::HostPlan &h, size_t n) {
+  size_t most = 0;
+  for (int j1 = 0; j1 < h.J; ++j1) {
+    size_t first = n >> h.res(j1), kids = 0;
+    if (h.max_order == 2)
+      for (int j2 = j1 + 1; j2 < h.J; ++j2) kids += n >> h.res(j2);
+    most = std::max(most, std::max(first, kids));
+  }
+  return most * static_cast<size_t>(h.LQ);
+}
+
 Layout make_layout(const scat_plan &p, long batch) {
   Layout L;
   const scat::HostPlan &h = p.host;
@@ -187,12 +202,14 @@ Layout make_layout(const scat_plan &p, long batch) {
     size_t w2 = second ? l * l * m_r * (p.n2 >> h.res(1)) : 0;  // second order at octave 1
     L.w = (w0 > w2 ? w0 : w2) * sizeof(float);
   } else {
+    // t: see t_elems_1d; u: one octave's moduli (column spectra); v: one second-order
+    // level's; w: row-pass outputs of the lowpass of one launch's nodes
     const size_t q = h.LQ;
     L.xh = n * c8;
-    L.t = q * n * c8;
+    L.t = t_elems_1d(h, n) * c8;
     L.u = q * n * c8;
     L.v = second ? q * (n >> h.res(1)) * c8 : 0;
-    L.w = 0;
+    L.w = q * (n >> h.res(h.J)) * c8;
   }
   if (p.padded) {
     L.pad_in = n * sizeof(float);
@@ -749,7 +766,7 @@ BwdLayout make_bwd_layout(const scat_plan &p, long batch) {
     // forward buffers as in make_layout; gradients: x spectrum, one octave's first-order
     // spectra, one (j1, j2) level's second-order spectra, output-grid spectra
     b.fwd.xh = n * c8;
-    b.fwd.t = l * n * c8;
+    b.fwd.t = t_elems_1d(h, n) * c8;
     b.fwd.u = l * n * c8;
     b.fwd.v = 0;
     b.tape = make_tape(p);
@@ -1144,14 +1161,22 @@ scat_status forward_1d(scat_plan *p, const float *in, float *out, long p0, long 
   const bool lp = tape == nullptr;  // form the lowpassed outputs
   const ChanMap none{1, 1, 0, 0};
 
+  // row-pass outputs of the lowpass (consumed by the column lowpass right after)
+  float2 *TL = reinterpret_cast<float2 *>(base + (lay.xh + lay.t + lay.u + lay.v) * pc);
+  const int m_out = N >> rJ;
+  // lowpass child of a signal at resolution r: phi at r, fold to rJ
+  auto low_child = [&](int r) {
+    return scat::Rows1dChild{tab + p->phi_off[r], TL, rJ - r, m_out};
+  };
+
   SCAT_TRY(scat::launch_col(0, x, pc, N1, N2, XH, N, nullptr, 0, nullptr, nullptr, none, K, tw,
                             tw_n, st));
   SCAT_TRY(scat::launch_row_fwd(XH, pc * N1, N2, tw, tw_n, st));
   // S0
   if (lp) {
-    SCAT_TRY(scat::launch_mulfold_invrow(XH, tab + p->phi_off[0], T, pc, 1, N1, N2, 0, rJ, N >> rJ,
+    SCAT_TRY(scat::launch_mulfold_invrow(XH, tab + p->phi_off[0], TL, pc, 1, N1, N2, 0, rJ, m_out,
                                          tw, tw_n, st));
-    SCAT_TRY(scat::launch_col(2, T, pc, N1, mc_out, nullptr, 0, nullptr, 0, nullptr, o,
+    SCAT_TRY(scat::launch_col(2, TL, pc, N1, mc_out, nullptr, 0, nullptr, 0, nullptr, o,
                               ChanMap{1, 1, 0, 0}, K, tw, tw_n, st));
   }
   int s2_base = 1 + J * Q;
@@ -1165,29 +1190,37 @@ scat_status forward_1d(scat_plan *p, const float *in, float *out, long p0, long 
     SCAT_TRY(scat::launch_col(1, T, pc * Q, N1, Mc1, U, M1, nullptr, 0, nullptr, nullptr, none, K,
                               tw, tw_n, st, false,
                               tape ? tape->base + tape->y1_off[j1] * pc : nullptr));
-    if (lp || kids) SCAT_TRY(scat::launch_row_fwd(U, pc * Q * N1, Mc1, tw, tw_n, st));
-    if (lp) {
-      SCAT_TRY(scat::launch_mulfold_invrow(U, tab + p->phi_off[r1], T, pc * Q, 1, N1, Mc1, 0,
-                                           rJ - r1, N >> rJ, tw, tw_n, st));
-      SCAT_TRY(scat::launch_col(2, T, pc * Q, N1, mc_out, nullptr, 0, nullptr, 0, nullptr, o,
-                                ChanMap{Q, Q, 0, 1 + j1 * Q}, K, tw, tw_n, st));
+    // one pass over the rows of U: the lowpass and the wavelets of every coarser octave
+    scat::Rows1dArgs ch;
+    ch.n = 0;
+    if (lp) ch.c[ch.n++] = low_child(r1);
+    float2 *tj[scat::kRows1dMaxChildren];
+    size_t t_used = 0;
+    for (int j2 = j1 + 1; kids && j2 < J; ++j2) {
+      const int r2 = h.res(j2);
+      tj[j2] = T + t_used * pc;
+      t_used += static_cast<size_t>(Q) * (N >> r2);
+      ch.c[ch.n++] = scat::Rows1dChild{tab + p->psi2_off[{r1, j2}], tj[j2], r2 - r1, N >> r2};
     }
+    SCAT_TRY(scat::launch_rows1d(U, pc * Q, N1, Mc1, ch, tw, tw_n, st));
+    if (lp)
+      SCAT_TRY(scat::launch_col(2, TL, pc * Q, N1, mc_out, nullptr, 0, nullptr, 0, nullptr, o,
+                                ChanMap{Q, Q, 0, 1 + j1 * Q}, K, tw, tw_n, st));
     if (!kids) continue;
     const int octs = J - 1 - j1;
     for (int j2 = j1 + 1; j2 < J; ++j2) {
       const int r2 = h.res(j2);
       const int Mc2 = N2 >> r2;
       const int M2 = N >> r2;
-      SCAT_TRY(scat::launch_mulfold_invrow(U, tab + p->psi2_off[{r1, j2}], T, pc * Q, 1, N1, Mc1, 0,
-                                           r2 - r1, M2, tw, tw_n, st));
-      SCAT_TRY(scat::launch_col(1, T, pc * Q, N1, Mc2, lp ? V : nullptr, M2, nullptr, 0, nullptr,
+      SCAT_TRY(scat::launch_col(1, tj[j2], pc * Q, N1, Mc2, lp ? V : nullptr, M2, nullptr, 0, nullptr,
                                 nullptr, none, K, tw, tw_n, st, false,
                                 tape ? tape->base + tape->y2_off.at({j1, j2}) * pc : nullptr));
       if (!lp) continue;
-      SCAT_TRY(scat::launch_row_fwd(V, pc * Q * N1, Mc2, tw, tw_n, st));
-      SCAT_TRY(scat::launch_mulfold_invrow(V, tab + p->phi_off[r2], T, pc * Q, 1, N1, Mc2, 0,
-                                           rJ - r2, N >> rJ, tw, tw_n, st));
-      SCAT_TRY(scat::launch_col(2, T, pc * Q, N1, mc_out, nullptr, 0, nullptr, 0, nullptr, o,
+      scat::Rows1dArgs lc;
+      lc.n = 1;
+      lc.c[0] = low_child(r2);
+      SCAT_TRY(scat::launch_rows1d(V, pc * Q, N1, Mc2, lc, tw, tw_n, st));
+      SCAT_TRY(scat::launch_col(2, TL, pc * Q, N1, mc_out, nullptr, 0, nullptr, 0, nullptr, o,
                                 ChanMap{Q, 1, octs, s2_base + (j2 - j1 - 1)}, K, tw, tw_n, st));
     }
     s2_base += Q * octs;

@@ -485,6 +485,186 @@ __global__ void k_col(const void *__restrict__ src_v, int Mr, int Mc, int TC,
 }
 
 // ------------------------------------------------------------------------------------
+// 1-D cascade, row half of everything that follows a modulus: forward row FFT of the
+// column spectra src [nodes][Sr][Sc] (never written back), then for every child c of the
+// list: product with the real table c.filt [Sr][Sc], sum over the 2^c.lg_fold blocks of the
+// row (second digit of the four-step order), inverse row FFT of Sc >> c.lg_fold points, the
+// four-step twiddle exp(+2 pi i k1 b / c.post_tw_m), store to c.dst [nodes][Sr][Sc >> lg_fold].
+// The children are the wavelets of all coarser octaves and / or the lowpass, so the signal
+// is read once for all of them.  RB rows per workgroup, all transforms through lds_fft.
+__global__ __launch_bounds__(256) void k_rows1d(const float2 *__restrict__ src, int Sr, int Sc,
+                                                int RB, Rows1dArgs a,
+                                                const float2 *__restrict__ tw, int tw_n) {
+  extern __shared__ float2 lds[];
+  float2 *spec = lds, *low = lds + RB * Sc;
+  // the Sc-point twiddle table in LDS: the transforms' strided reads of the global table
+  // (one cache line per twiddle) would otherwise sit on every butterfly's critical path
+  float2 *twl = low + RB * Sc;
+  for (int j = threadIdx.x; j < Sc; j += blockDim.x) twl[j] = tw[j * (tw_n / Sc)];
+  const int lgSc = ilog2(Sc);
+  const long row0 = static_cast<long>(blockIdx.x) * RB;
+  const float2 *sp = src + static_cast<size_t>(row0) * Sc;
+  for (int t = threadIdx.x; t < RB * Sc; t += blockDim.x) {
+    const int row = t >> lgSc, c = t & (Sc - 1);
+    spec[row * Sc + bitrev(c, lgSc)] = sp[t];
+  }
+  lds_fft<false, false>(spec, lgSc, RB, Sc, 1, twl, Sc);
+  const int k1_0 = static_cast<int>(row0 % Sr);  // RB divides Sr: the rows share one node
+  for (int ci = 0; ci < a.n; ++ci) {
+    const Rows1dChild &ch = a.c[ci];
+    const int lgm = lgSc - ch.lg_fold, m = 1 << lgm;
+    // products of the whole rows (every thread busy, filter reads contiguous), each block of
+    // m columns stored bit-reversed within itself; the blocks are then added pairwise, which
+    // leaves the folded row, bit-reversed, in the first m columns of its Sc-column slot
+    const float *fp = ch.filt + static_cast<size_t>(k1_0) * Sc;
+    for (int t = threadIdx.x; t < RB * Sc; t += blockDim.x) {
+      const int c = t & (Sc - 1);
+      const float2 v = spec[t];
+      const float f = fp[t];
+      low[(t - c) + (c & ~(m - 1)) + bitrev(c & (m - 1), lgm)] = make_float2(v.x * f, v.y * f);
+    }
+    for (int half = Sc >> 1; half >= m; half >>= 1) {
+      __syncthreads();
+      const int lgh = ilog2(half);
+      for (int t = threadIdx.x; t < RB * half; t += blockDim.x) {
+        const int row = t >> lgh, i = t & (half - 1);
+        float2 *q = low + row * Sc + i;
+        const float2 u = q[half];
+        q[0].x += u.x;
+        q[0].y += u.y;
+      }
+    }
+    lds_fft<true, false>(low, lgm, RB, Sc, 1, twl, Sc);
+    float2 *dp = ch.dst + static_cast<size_t>(row0) * m;
+    for (int t = threadIdx.x; t < RB * m; t += blockDim.x) {
+      const int row = t >> lgm, b = t & (m - 1);
+      float2 v = low[row * Sc + b];
+      if (ch.post_tw_m > 0) {
+        const int e = static_cast<int>((static_cast<long long>(k1_0 + row) * b) % ch.post_tw_m);
+        v = cmul(v, twiddle<true>(tw, tw_n, e, ch.post_tw_m));
+      }
+      dp[t] = v;
+    }
+    __syncthreads();  // `low` is reused by the next child
+  }
+}
+
+// ------------------------------------------------------------------------------------
+// k_rows1d with the transforms in registers, for rows of Sc = 16 T points (T lanes per row,
+// 256 / T rows per workgroup, wave-level synchronisation only).  The forward transform
+// leaves lane t with X[t + T i]; a child's fold by 2^d halves that register array
+// min(d, 4) times, the remaining halvings add lanes t and t ^ s; the folded row is parked
+// in the row's LDS slot in natural order, picked up by the m / 16 lanes that share its
+// inverse transform (one lane below 16 points), transformed and stored.
+template <int E2, int T2>
+__device__ __forceinline__ void rows1d_child_inv(float2 *slot, int t, int tw_step,
+                                                 const float2 *twl, float2 *dp, int k1,
+                                                 int post_tw_m, const float2 *__restrict__ tw,
+                                                 int tw_n, bool store) {
+  if (t >= T2) return;
+  float2 v[E2], wt[E2];
+#pragma unroll
+  for (int i = 0; i < E2; ++i) v[i] = slot[t + T2 * i];
+#pragma unroll
+  for (int k = 0; k < E2; ++k) wt[k] = twl[t * k * tw_step];
+  wave_sync();  // the slot becomes the exchange area
+  fft_core<E2, T2, true, true>(v, t, slot, T2 + 1, 1, wt);
+  if (!store) return;
+  const int step = post_tw_m > 0 ? tw_n / post_tw_m : 0;
+#pragma unroll
+  for (int i = 0; i < E2; ++i) {
+    const int b = t + T2 * i;
+    float2 o = v[i];
+    if (post_tw_m > 0) {
+      float2 w = tw[static_cast<int>((static_cast<long long>(k1) * b) & (post_tw_m - 1)) * step];
+      w.y = -w.y;
+      o = cmul(o, w);
+    }
+    dp[b] = o;
+  }
+}
+
+template <int T>
+__global__ __launch_bounds__(256) void k_rows1d_reg(const float2 *__restrict__ src, long rows,
+                                                    int Sr, Rows1dArgs a,
+                                                    const float2 *__restrict__ tw, int tw_n) {
+  constexpr int E = 16, Sc = E * T, RPB = 256 / T, XS = T == 1 ? E : E * (T + 1);
+  constexpr int lgSc = T == 1 ? 4 : T == 2 ? 5 : T == 4 ? 6 : T == 8 ? 7 : 8;
+  extern __shared__ float2 lds[];
+  float2 *twl = lds;
+  for (int j = threadIdx.x; j < Sc; j += blockDim.x) twl[j] = tw[j * (tw_n / Sc)];
+  __syncthreads();
+  const int rl = threadIdx.x / T, t = threadIdx.x % T;
+  const long row_raw = static_cast<long>(blockIdx.x) * RPB + rl;
+  const bool valid = row_raw < rows;
+  const long row = valid ? row_raw : rows - 1;  // idle groups redo the last row, unstored
+  const int k1 = static_cast<int>(row % Sr);
+  float2 *slot = lds + Sc + rl * XS;
+  float2 v[E];
+  {
+    const float2 *sp = src + static_cast<size_t>(row) * Sc + t;
+#pragma unroll
+    for (int i = 0; i < E; ++i) v[i] = sp[T * i];
+    float2 wt[E];
+#pragma unroll
+    for (int k = 0; k < E; ++k) wt[k] = twl[t * k];
+    fft_core<E, T, false, true>(v, t, slot, T + 1, 1, wt);
+  }
+  for (int ci = 0; ci < a.n; ++ci) {
+    const Rows1dChild &ch = a.c[ci];
+    const int lgm = lgSc - ch.lg_fold, m = 1 << lgm;
+    const float *fp = ch.filt + static_cast<size_t>(k1) * Sc + t;
+    float2 p[E];
+#pragma unroll
+    for (int i = 0; i < E; ++i) {
+      const float f = fp[T * i];
+      p[i] = make_float2(v[i].x * f, v[i].y * f);
+    }
+    int dd = ch.lg_fold;
+#pragma unroll
+    for (int h = E / 2; h >= 1; h >>= 1) {
+      if (dd > 0) {
+#pragma unroll
+        for (int i = 0; i < h; ++i) {
+          p[i].x += p[i + h].x;
+          p[i].y += p[i + h].y;
+        }
+        --dd;
+      }
+    }
+#pragma unroll
+    for (int s = T / 2; s >= 1; s >>= 1) {
+      if (dd > 0) {
+        p[0].x += __shfl_xor(p[0].x, s);
+        p[0].y += __shfl_xor(p[0].y, s);
+        --dd;
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < E; ++i)
+      if (t + T * i < m) slot[t + T * i] = p[i];
+    wave_sync();
+    float2 *dp = ch.dst + static_cast<size_t>(row) * m;
+    const int tws = Sc >> lgm;
+    switch (lgm) {
+      case 0:
+        if (t == 0 && valid) dp[0] = slot[0];
+        break;
+      case 1: rows1d_child_inv<2, 1>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, valid); break;
+      case 2: rows1d_child_inv<4, 1>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, valid); break;
+      case 3: rows1d_child_inv<8, 1>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, valid); break;
+      case 4: rows1d_child_inv<16, 1>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, valid); break;
+      case 5: if (T >= 2) rows1d_child_inv<16, (T >= 2 ? 2 : 1)>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, valid); break;
+      case 6: if (T >= 4) rows1d_child_inv<16, (T >= 4 ? 4 : 1)>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, valid); break;
+      case 7: if (T >= 8) rows1d_child_inv<16, (T >= 8 ? 8 : 1)>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, valid); break;
+      case 8: if (T >= 16) rows1d_child_inv<16, (T >= 16 ? 16 : 1)>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, valid); break;
+      default: break;
+    }
+    wave_sync();  // the slot is reused by the next child
+  }
+}
+
+// ------------------------------------------------------------------------------------
 // Forward row FFT in place: data [rows][Mc] complex, RB rows per workgroup.
 __global__ void k_row_fwd(float2 *__restrict__ data, int Mc, int RB,
                           const float2 *__restrict__ tw, int tw_n) {
@@ -1441,6 +1621,67 @@ hipError_t launch_row_fwd_reg_t(float2 *data, long rows, const float2 *tw, int t
 // ----------------------------------------------------------------------------- launchers
 
 void set_launch_observer(LaunchObserver *o) { g_observer = o; }
+
+template <int T>
+hipError_t launch_rows1d_reg_t(const float2 *src, long rows, int Sr, const Rows1dArgs &a, double bytes,
+                               double flops, const float2 *tw, int tw_n, hipStream_t st) {
+  constexpr int E = 16, Sc = E * T, RPB = 256 / T, XS = T == 1 ? E : E * (T + 1);
+  const long blocks = (rows + RPB - 1) / RPB;
+  if (blocks <= 0 || blocks > 0x7fffffffL) return hipErrorInvalidValue;
+  const size_t lds = (static_cast<size_t>(Sc) + static_cast<size_t>(RPB) * XS) * sizeof(float2);
+  const std::string name = "k_rows1d_reg<" + std::to_string(T) + ">";
+  Observe ob(name.c_str(), bytes, flops, st);
+  hipLaunchKernelGGL((k_rows1d_reg<T>), dim3(static_cast<unsigned>(blocks)), dim3(256), lds, st, src,
+                     rows, Sr, a, tw, tw_n);
+  return hipGetLastError();
+}
+
+hipError_t launch_rows1d(const float2 *src, long nodes, int Sr, int Sc, const Rows1dArgs &a,
+                         const float2 *tw, int tw_n, hipStream_t st) {
+  if (nodes <= 0 || a.n <= 0) return hipSuccess;
+  auto is_pow2 = [](int v) { return v > 0 && (v & (v - 1)) == 0; };
+  if (a.n > kRows1dMaxChildren || !is_pow2(Sr) || !is_pow2(Sc) || Sc < 2 || Sc > kTileElems ||
+      tw_n % Sc != 0)
+    return hipErrorInvalidValue;
+  int lgSc = 0;
+  while ((1 << lgSc) < Sc) ++lgSc;
+  double bytes = static_cast<double>(nodes) * Sr * Sc * 8, flops = fft_flops(Sc);
+  for (int i = 0; i < a.n; ++i) {
+    const Rows1dChild &c = a.c[i];
+    if (c.filt == nullptr || c.dst == nullptr || c.lg_fold < 0 || c.lg_fold > lgSc ||
+        (c.post_tw_m > 0 && (!is_pow2(c.post_tw_m) || tw_n % c.post_tw_m != 0)))
+      return hipErrorInvalidValue;
+    const double m = static_cast<double>(Sc >> c.lg_fold);
+    bytes += static_cast<double>(Sr) * Sc * 4 + static_cast<double>(nodes) * Sr * m * 8;
+    flops += 4.0 * Sc + fft_flops(m);
+  }
+  const double all_flops = static_cast<double>(nodes) * Sr * flops;
+  switch (Sc) {
+    case 16: return launch_rows1d_reg_t<1>(src, nodes * Sr, Sr, a, bytes, all_flops, tw, tw_n, st);
+    case 32: return launch_rows1d_reg_t<2>(src, nodes * Sr, Sr, a, bytes, all_flops, tw, tw_n, st);
+    case 64: return launch_rows1d_reg_t<4>(src, nodes * Sr, Sr, a, bytes, all_flops, tw, tw_n, st);
+    case 128: return launch_rows1d_reg_t<8>(src, nodes * Sr, Sr, a, bytes, all_flops, tw, tw_n, st);
+    case 256: return launch_rows1d_reg_t<16>(src, nodes * Sr, Sr, a, bytes, all_flops, tw, tw_n, st);
+    default: break;
+  }
+  // other row lengths: spectrum rows and one child's rows side by side in LDS
+  // (2 * RB * Sc elements), then the twiddle table
+  int RB = pow2_floor(kTileElems / 2 / Sc);
+  if (RB < 1) RB = 1;
+  if (RB > Sr) RB = Sr;
+  const long blocks = nodes * Sr / RB;
+  if (blocks <= 0 || blocks > 0x7fffffffL) return hipErrorInvalidValue;
+  const size_t lds = (2 * static_cast<size_t>(RB) + 1) * Sc * sizeof(float2);
+  if (lds > 65536) {
+    static unsigned long long lds_ok = 0;
+    hipError_t e = allow_large_lds(reinterpret_cast<const void *>(k_rows1d), lds_ok);
+    if (e != hipSuccess) return e;
+  }
+  Observe ob("k_rows1d", bytes, static_cast<double>(nodes) * Sr * flops, st);
+  hipLaunchKernelGGL(k_rows1d, dim3(static_cast<unsigned>(blocks)), dim3(kThreads), lds, st, src, Sr,
+                     Sc, RB, a, tw, tw_n);
+  return hipGetLastError();
+}
 
 hipError_t launch_mulfold_invrow(const float2 *src, const float *filt, float2 *dst, long S, int F,
                                  int Sr, int Sc, int fr, int fc, int post_tw_m, const float2 *tw,

@@ -57,6 +57,23 @@ hipError_t launch_col(int mode, const void *src, long nodes, int Mr, int Mc, flo
                       ChanMap cm, int K, const float2 *tw, int tw_n, hipStream_t st,
                       bool uc_half = false, float2 *y_out = nullptr);
 
+// 1-D cascade: forward row FFT of src [nodes][Sr][Sc] (column spectra, left untouched) and,
+// for each child, filter product + fold of the row by 2^lg_fold + inverse row FFT + four-step
+// twiddle, stored to the child's dst [nodes][Sr][Sc >> lg_fold] (see k_rows1d).
+constexpr int kRows1dMaxChildren = 24;
+struct Rows1dChild {
+  const float *filt;  // [Sr][Sc], carries the inverse-transform normalisation
+  float2 *dst;
+  int lg_fold;
+  int post_tw_m;  // 0 = no twiddle
+};
+struct Rows1dArgs {
+  int n;
+  Rows1dChild c[kRows1dMaxChildren];
+};
+hipError_t launch_rows1d(const float2 *src, long nodes, int Sr, int Sc, const Rows1dArgs &a,
+                         const float2 *tw, int tw_n, hipStream_t st);
+
 hipError_t launch_row_fwd(float2 *data, long rows, int Mc, const float2 *tw, int tw_n,
                           hipStream_t st);
 

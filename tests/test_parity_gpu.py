@@ -101,6 +101,8 @@ def test_config3_512x512_sample():
 
 @pytest.mark.parametrize("n,J,Q,max_order", [
     (64, 3, 2, 2), (256, 4, 1, 2), (1024, 5, 8, 2), (4096, 6, 8, 1), (8, 3, 1, 2), (2048, 2, 3, 2),
+    # rows of 4096 points (n2 = 2^J): the row kernel's largest LDS tile
+    (8192, 12, 1, 2), (1 << 18, 3, 2, 2),
 ])
 def test_1d_shapes(n, J, Q, max_order):
     rng = np.random.default_rng(n + J + Q)
