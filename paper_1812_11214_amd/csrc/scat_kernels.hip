@@ -556,11 +556,15 @@ __global__ __launch_bounds__(256) void k_rows1d(const float2 *__restrict__ src, 
 // min(d, 4) times, the remaining halvings add lanes t and t ^ s; the folded row is parked
 // in the row's LDS slot in natural order, picked up by the m / 16 lanes that share its
 // inverse transform (one lane below 16 points), transformed and stored.
-template <int E2, int T2>
+// Four-step twiddle of output b = t + T2 i of row k1: exp(+2 pi i k1 b / M), M = Sr m (so
+// k1 b < M).  With m = 16 T2 it factors into exp(2 pi i k1 t / M) (one table read per lane)
+// times exp(2 pi i k1 i / (16 Sr)), which depends on the row only: `rowtw`, read once per row.
+// (ROWTW = false: rows too short for that to pay; every twiddle is read from the table.)
+template <int E2, int T2, bool ROWTW>
 __device__ __forceinline__ void rows1d_child_inv(float2 *slot, int t, int tw_step,
                                                  const float2 *twl, float2 *dp, int k1,
                                                  int post_tw_m, const float2 *__restrict__ tw,
-                                                 int tw_n, bool store) {
+                                                 int tw_n, bool store, const float2 (&rowtw)[16]) {
   if (t >= T2) return;
   float2 v[E2], wt[E2];
 #pragma unroll
@@ -571,13 +575,23 @@ __device__ __forceinline__ void rows1d_child_inv(float2 *slot, int t, int tw_ste
   fft_core<E2, T2, true, true>(v, t, slot, T2 + 1, 1, wt);
   if (!store) return;
   const int step = post_tw_m > 0 ? tw_n / post_tw_m : 0;
+  float2 wl = make_float2(1.f, 0.f);
+  if (ROWTW && E2 == 16 && post_tw_m > 0) {
+    wl = tw[k1 * t * step];
+    wl.y = -wl.y;
+  }
 #pragma unroll
   for (int i = 0; i < E2; ++i) {
     const int b = t + T2 * i;
     float2 o = v[i];
     if (post_tw_m > 0) {
-      float2 w = tw[static_cast<int>((static_cast<long long>(k1) * b) & (post_tw_m - 1)) * step];
-      w.y = -w.y;
+      float2 w;
+      if (ROWTW && E2 == 16) {
+        w = cmul(wl, rowtw[i]);
+      } else {
+        w = tw[k1 * b * step];
+        w.y = -w.y;
+      }
       o = cmul(o, w);
     }
     dp[b] = o;
@@ -609,6 +623,17 @@ __global__ __launch_bounds__(256) void k_rows1d_reg(const float2 *__restrict__ s
 #pragma unroll
     for (int k = 0; k < E; ++k) wt[k] = twl[t * k];
     fft_core<E, T, false, true>(v, t, slot, T + 1, 1, wt);
+  }
+  // exp(+2 pi i k1 i / (16 Sr)): the row's share of every child's four-step twiddle
+  constexpr bool ROWTW = T >= 4;
+  float2 rowtw[16];
+  if (ROWTW) {
+    const int rstep = tw_n / (16 * Sr);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      rowtw[i] = rstep > 0 ? tw[k1 * i * rstep] : make_float2(1.f, 0.f);
+      rowtw[i].y = -rowtw[i].y;
+    }
   }
   for (int ci = 0; ci < a.n; ++ci) {
     const Rows1dChild &ch = a.c[ci];
@@ -650,14 +675,14 @@ __global__ __launch_bounds__(256) void k_rows1d_reg(const float2 *__restrict__ s
       case 0:
         if (t == 0 && valid) dp[0] = slot[0];
         break;
-      case 1: rows1d_child_inv<2, 1>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, valid); break;
-      case 2: rows1d_child_inv<4, 1>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, valid); break;
-      case 3: rows1d_child_inv<8, 1>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, valid); break;
-      case 4: rows1d_child_inv<16, 1>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, valid); break;
-      case 5: if (T >= 2) rows1d_child_inv<16, (T >= 2 ? 2 : 1)>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, valid); break;
-      case 6: if (T >= 4) rows1d_child_inv<16, (T >= 4 ? 4 : 1)>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, valid); break;
-      case 7: if (T >= 8) rows1d_child_inv<16, (T >= 8 ? 8 : 1)>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, valid); break;
-      case 8: if (T >= 16) rows1d_child_inv<16, (T >= 16 ? 16 : 1)>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, valid); break;
+      case 1: rows1d_child_inv<2, 1, ROWTW>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, valid, rowtw); break;
+      case 2: rows1d_child_inv<4, 1, ROWTW>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, valid, rowtw); break;
+      case 3: rows1d_child_inv<8, 1, ROWTW>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, valid, rowtw); break;
+      case 4: rows1d_child_inv<16, 1, ROWTW>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, valid, rowtw); break;
+      case 5: if (T >= 2) rows1d_child_inv<16, (T >= 2 ? 2 : 1), ROWTW>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, valid, rowtw); break;
+      case 6: if (T >= 4) rows1d_child_inv<16, (T >= 4 ? 4 : 1), ROWTW>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, valid, rowtw); break;
+      case 7: if (T >= 8) rows1d_child_inv<16, (T >= 8 ? 8 : 1), ROWTW>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, valid, rowtw); break;
+      case 8: if (T >= 16) rows1d_child_inv<16, (T >= 16 ? 16 : 1), ROWTW>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, valid, rowtw); break;
       default: break;
     }
     wave_sync();  // the slot is reused by the next child
@@ -1649,7 +1674,7 @@ hipError_t launch_rows1d(const float2 *src, long nodes, int Sr, int Sc, const Ro
   for (int i = 0; i < a.n; ++i) {
     const Rows1dChild &c = a.c[i];
     if (c.filt == nullptr || c.dst == nullptr || c.lg_fold < 0 || c.lg_fold > lgSc ||
-        (c.post_tw_m > 0 && (!is_pow2(c.post_tw_m) || tw_n % c.post_tw_m != 0)))
+        (c.post_tw_m > 0 && (c.post_tw_m != Sr * (Sc >> c.lg_fold) || tw_n % c.post_tw_m != 0)))
       return hipErrorInvalidValue;
     const double m = static_cast<double>(Sc >> c.lg_fold);
     bytes += static_cast<double>(Sr) * Sc * 4 + static_cast<double>(nodes) * Sr * m * 8;

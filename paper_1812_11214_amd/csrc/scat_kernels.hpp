@@ -65,7 +65,7 @@ struct Rows1dChild {
   const float *filt;  // [Sr][Sc], carries the inverse-transform normalisation
   float2 *dst;
   int lg_fold;
-  int post_tw_m;  // 0 = no twiddle
+  int post_tw_m;  // 0 = no twiddle, else Sr * (Sc >> lg_fold): the child's signal length
 };
 struct Rows1dArgs {
   int n;
