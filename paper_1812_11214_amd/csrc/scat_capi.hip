@@ -203,13 +203,13 @@ Layout make_layout(const scat_plan &p, long batch) {
     L.w = (w0 > w2 ? w0 : w2) * sizeof(float);
   } else {
     // t: see t_elems_1d; u: one octave's moduli (column spectra); v: one second-order
-    // level's; w: row-pass outputs of the lowpass of one launch's nodes
+    // level's; w: row-pass outputs of the lowpass for all K channels
     const size_t q = h.LQ;
     L.xh = n * c8;
     L.t = t_elems_1d(h, n) * c8;
     L.u = q * n * c8;
     L.v = second ? q * (n >> h.res(1)) * c8 : 0;
-    L.w = q * (n >> h.res(h.J)) * c8;
+    L.w = static_cast<size_t>(h.K) * (n >> h.res(h.J)) * c8;
   }
   if (p.padded) {
     L.pad_in = n * sizeof(float);
@@ -1161,12 +1161,15 @@ scat_status forward_1d(scat_plan *p, const float *in, float *out, long p0, long 
   const bool lp = tape == nullptr;  // form the lowpassed outputs
   const ChanMap none{1, 1, 0, 0};
 
-  // row-pass outputs of the lowpass (consumed by the column lowpass right after)
+  // row-pass outputs of the lowpass: channels 1 .. K-1 of every signal, channel-major, for
+  // one column pass at the end; then channel 0
   float2 *TL = reinterpret_cast<float2 *>(base + (lay.xh + lay.t + lay.u + lay.v) * pc);
   const int m_out = N >> rJ;
-  // lowpass child of a signal at resolution r: phi at r, fold to rJ
-  auto low_child = [&](int r) {
-    return scat::Rows1dChild{tab + p->phi_off[r], TL, rJ - r, m_out};
+  float2 *TL0 = TL + static_cast<size_t>(pc) * (K - 1) * m_out;
+  // lowpass child of nodes at resolution r whose output channels are cm: phi at r, fold to rJ
+  auto low_child = [&](int r, ChanMap cm) {
+    return scat::Rows1dChild{tab + p->phi_off[r], TL, rJ - r, m_out,
+                             ChanMap{cm.G, cm.inner, cm.outer_stride, cm.base - 1}, K - 1};
   };
 
   SCAT_TRY(scat::launch_col(0, x, pc, N1, N2, XH, N, nullptr, 0, nullptr, nullptr, none, K, tw,
@@ -1174,9 +1177,9 @@ scat_status forward_1d(scat_plan *p, const float *in, float *out, long p0, long 
   SCAT_TRY(scat::launch_row_fwd(XH, pc * N1, N2, tw, tw_n, st));
   // S0
   if (lp) {
-    SCAT_TRY(scat::launch_mulfold_invrow(XH, tab + p->phi_off[0], TL, pc, 1, N1, N2, 0, rJ, m_out,
+    SCAT_TRY(scat::launch_mulfold_invrow(XH, tab + p->phi_off[0], TL0, pc, 1, N1, N2, 0, rJ, m_out,
                                          tw, tw_n, st));
-    SCAT_TRY(scat::launch_col(2, TL, pc, N1, mc_out, nullptr, 0, nullptr, 0, nullptr, o,
+    SCAT_TRY(scat::launch_col(2, TL0, pc, N1, mc_out, nullptr, 0, nullptr, 0, nullptr, o,
                               ChanMap{1, 1, 0, 0}, K, tw, tw_n, st));
   }
   int s2_base = 1 + J * Q;
@@ -1193,19 +1196,17 @@ scat_status forward_1d(scat_plan *p, const float *in, float *out, long p0, long 
     // one pass over the rows of U: the lowpass and the wavelets of every coarser octave
     scat::Rows1dArgs ch;
     ch.n = 0;
-    if (lp) ch.c[ch.n++] = low_child(r1);
+    if (lp) ch.c[ch.n++] = low_child(r1, ChanMap{Q, Q, 0, 1 + j1 * Q});
     float2 *tj[scat::kRows1dMaxChildren];
     size_t t_used = 0;
     for (int j2 = j1 + 1; kids && j2 < J; ++j2) {
       const int r2 = h.res(j2);
       tj[j2] = T + t_used * pc;
       t_used += static_cast<size_t>(Q) * (N >> r2);
-      ch.c[ch.n++] = scat::Rows1dChild{tab + p->psi2_off[{r1, j2}], tj[j2], r2 - r1, N >> r2};
+      ch.c[ch.n++] = scat::Rows1dChild{tab + p->psi2_off[{r1, j2}], tj[j2], r2 - r1, N >> r2,
+                                       ChanMap{1, 1, 0, 0}, 0};
     }
     SCAT_TRY(scat::launch_rows1d(U, pc * Q, N1, Mc1, ch, tw, tw_n, st));
-    if (lp)
-      SCAT_TRY(scat::launch_col(2, TL, pc * Q, N1, mc_out, nullptr, 0, nullptr, 0, nullptr, o,
-                                ChanMap{Q, Q, 0, 1 + j1 * Q}, K, tw, tw_n, st));
     if (!kids) continue;
     const int octs = J - 1 - j1;
     for (int j2 = j1 + 1; j2 < J; ++j2) {
@@ -1218,13 +1219,15 @@ scat_status forward_1d(scat_plan *p, const float *in, float *out, long p0, long 
       if (!lp) continue;
       scat::Rows1dArgs lc;
       lc.n = 1;
-      lc.c[0] = low_child(r2);
+      lc.c[0] = low_child(r2, ChanMap{Q, 1, octs, s2_base + (j2 - j1 - 1)});
       SCAT_TRY(scat::launch_rows1d(V, pc * Q, N1, Mc2, lc, tw, tw_n, st));
-      SCAT_TRY(scat::launch_col(2, TL, pc * Q, N1, mc_out, nullptr, 0, nullptr, 0, nullptr, o,
-                                ChanMap{Q, 1, octs, s2_base + (j2 - j1 - 1)}, K, tw, tw_n, st));
     }
     s2_base += Q * octs;
   }
+  // column half of the lowpass for channels 1 .. K-1 of every signal at once
+  if (lp && K > 1)
+    SCAT_TRY(scat::launch_col(2, TL, pc * (K - 1), N1, mc_out, nullptr, 0, nullptr, 0, nullptr, o,
+                              ChanMap{K - 1, K - 1, 0, 1}, K, tw, tw_n, st));
   return SCAT_OK;
 }
 

@@ -535,7 +535,12 @@ __global__ __launch_bounds__(256) void k_rows1d(const float2 *__restrict__ src, 
       }
     }
     lds_fft<true, false>(low, lgm, RB, Sc, 1, twl, Sc);
-    float2 *dp = ch.dst + static_cast<size_t>(row0) * m;
+    long drow0 = row0;
+    if (ch.K > 0) {
+      const long node = row0 / Sr;
+      drow0 = ((node / ch.cm.G) * ch.K + chan_of(ch.cm, static_cast<int>(node % ch.cm.G))) * Sr + k1_0;
+    }
+    float2 *dp = ch.dst + static_cast<size_t>(drow0) * m;
     for (int t = threadIdx.x; t < RB * m; t += blockDim.x) {
       const int row = t >> lgm, b = t & (m - 1);
       float2 v = low[row * Sc + b];
@@ -558,13 +563,14 @@ __global__ __launch_bounds__(256) void k_rows1d(const float2 *__restrict__ src, 
 // inverse transform (one lane below 16 points), transformed and stored.
 // Four-step twiddle of output b = t + T2 i of row k1: exp(+2 pi i k1 b / M), M = Sr m (so
 // k1 b < M).  With m = 16 T2 it factors into exp(2 pi i k1 t / M) (one table read per lane)
-// times exp(2 pi i k1 i / (16 Sr)), which depends on the row only: `rowtw`, read once per row.
+// times exp(2 pi i k1 i / (16 Sr)), which depends on the row only: `rowtw`, read once per row
+// and kept behind the row's LDS slot.
 // (ROWTW = false: rows too short for that to pay; every twiddle is read from the table.)
 template <int E2, int T2, bool ROWTW>
 __device__ __forceinline__ void rows1d_child_inv(float2 *slot, int t, int tw_step,
                                                  const float2 *twl, float2 *dp, int k1,
                                                  int post_tw_m, const float2 *__restrict__ tw,
-                                                 int tw_n, bool store, const float2 (&rowtw)[16]) {
+                                                 int tw_n, bool store, const float2 *rowtw) {
   if (t >= T2) return;
   float2 v[E2], wt[E2];
 #pragma unroll
@@ -599,10 +605,12 @@ __device__ __forceinline__ void rows1d_child_inv(float2 *slot, int t, int tw_ste
 }
 
 template <int T>
-__global__ __launch_bounds__(256) void k_rows1d_reg(const float2 *__restrict__ src, long rows,
+__global__ __launch_bounds__(256, 4) void k_rows1d_reg(const float2 *__restrict__ src, long rows,
                                                     int Sr, Rows1dArgs a,
                                                     const float2 *__restrict__ tw, int tw_n) {
-  constexpr int E = 16, Sc = E * T, RPB = 256 / T, XS = T == 1 ? E : E * (T + 1);
+  constexpr bool ROWTW = T >= 4;
+  constexpr int E = 16, Sc = E * T, RPB = 256 / T;
+  constexpr int XS = (T == 1 ? E : E * (T + 1)) + (ROWTW ? 16 : 0);
   constexpr int lgSc = T == 1 ? 4 : T == 2 ? 5 : T == 4 ? 6 : T == 8 ? 7 : 8;
   extern __shared__ float2 lds[];
   float2 *twl = lds;
@@ -612,7 +620,8 @@ __global__ __launch_bounds__(256) void k_rows1d_reg(const float2 *__restrict__ s
   const long row_raw = static_cast<long>(blockIdx.x) * RPB + rl;
   const bool valid = row_raw < rows;
   const long row = valid ? row_raw : rows - 1;  // idle groups redo the last row, unstored
-  const int k1 = static_cast<int>(row % Sr);
+  const long node = row / Sr;
+  const int k1 = static_cast<int>(row - node * Sr);
   float2 *slot = lds + Sc + rl * XS;
   float2 v[E];
   {
@@ -625,14 +634,14 @@ __global__ __launch_bounds__(256) void k_rows1d_reg(const float2 *__restrict__ s
     fft_core<E, T, false, true>(v, t, slot, T + 1, 1, wt);
   }
   // exp(+2 pi i k1 i / (16 Sr)): the row's share of every child's four-step twiddle
-  constexpr bool ROWTW = T >= 4;
-  float2 rowtw[16];
+  float2 *rowtw = slot + XS - 16;
   if (ROWTW) {
+    // lane t fetches entries t, t + T, ... (T >= 4 lanes share the 16 entries)
     const int rstep = tw_n / (16 * Sr);
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      rowtw[i] = rstep > 0 ? tw[k1 * i * rstep] : make_float2(1.f, 0.f);
-      rowtw[i].y = -rowtw[i].y;
+    for (int i = t; i < 16; i += T) {
+      float2 w = rstep > 0 ? tw[k1 * i * rstep] : make_float2(1.f, 0.f);
+      w.y = -w.y;
+      rowtw[i] = w;
     }
   }
   for (int ci = 0; ci < a.n; ++ci) {
@@ -669,7 +678,10 @@ __global__ __launch_bounds__(256) void k_rows1d_reg(const float2 *__restrict__ s
     for (int i = 0; i < E; ++i)
       if (t + T * i < m) slot[t + T * i] = p[i];
     wave_sync();
-    float2 *dp = ch.dst + static_cast<size_t>(row) * m;
+    long drow = row;
+    if (ch.K > 0)
+      drow = ((node / ch.cm.G) * ch.K + chan_of(ch.cm, static_cast<int>(node % ch.cm.G))) * Sr + k1;
+    float2 *dp = ch.dst + static_cast<size_t>(drow) * m;
     const int tws = Sc >> lgm;
     switch (lgm) {
       case 0:
@@ -1650,7 +1662,8 @@ void set_launch_observer(LaunchObserver *o) { g_observer = o; }
 template <int T>
 hipError_t launch_rows1d_reg_t(const float2 *src, long rows, int Sr, const Rows1dArgs &a, double bytes,
                                double flops, const float2 *tw, int tw_n, hipStream_t st) {
-  constexpr int E = 16, Sc = E * T, RPB = 256 / T, XS = T == 1 ? E : E * (T + 1);
+  constexpr int E = 16, Sc = E * T, RPB = 256 / T;
+  constexpr int XS = (T == 1 ? E : E * (T + 1)) + (T >= 4 ? 16 : 0);  // as in the kernel
   const long blocks = (rows + RPB - 1) / RPB;
   if (blocks <= 0 || blocks > 0x7fffffffL) return hipErrorInvalidValue;
   const size_t lds = (static_cast<size_t>(Sc) + static_cast<size_t>(RPB) * XS) * sizeof(float2);
@@ -1674,7 +1687,8 @@ hipError_t launch_rows1d(const float2 *src, long nodes, int Sr, int Sc, const Ro
   for (int i = 0; i < a.n; ++i) {
     const Rows1dChild &c = a.c[i];
     if (c.filt == nullptr || c.dst == nullptr || c.lg_fold < 0 || c.lg_fold > lgSc ||
-        (c.post_tw_m > 0 && (c.post_tw_m != Sr * (Sc >> c.lg_fold) || tw_n % c.post_tw_m != 0)))
+        (c.post_tw_m > 0 && (c.post_tw_m != Sr * (Sc >> c.lg_fold) || tw_n % c.post_tw_m != 0)) ||
+        (c.K > 0 && (c.cm.G < 1 || c.cm.inner < 1 || nodes % c.cm.G != 0)))
       return hipErrorInvalidValue;
     const double m = static_cast<double>(Sc >> c.lg_fold);
     bytes += static_cast<double>(Sr) * Sc * 4 + static_cast<double>(nodes) * Sr * m * 8;

@@ -66,6 +66,10 @@ struct Rows1dChild {
   float2 *dst;
   int lg_fold;
   int post_tw_m;  // 0 = no twiddle, else Sr * (Sc >> lg_fold): the child's signal length
+  // K > 0: node p * cm.G + g is stored as signal number p * K + channel(cm, g) instead of at
+  // its own number (the lowpass children of a whole transform gathered channel-major)
+  ChanMap cm;
+  int K;
 };
 struct Rows1dArgs {
   int n;
