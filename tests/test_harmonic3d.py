@@ -171,7 +171,19 @@ def test_chunked_batches_match_unchunked():
 
 
 @pytest.mark.gpu
-def test_headline_volume_shape_sampled():
-    # the 64^3 case the benchmark's 3-D mode times, two volumes against the oracle
+def test_benchmark_workload_sampled():
+    """The 16 x 64^3 batch the benchmark's 3-D mode times, in one call; volumes 0, 7 and 15
+    against the oracle."""
     c = workloads.VOLUME_CONFIG
-    _check(workloads.volumes(c["shape"], 2), c["J"], c["LQ"])
+    x = workloads.volumes(c["shape"], c["batch"])
+    plan = scat.Scattering(c["shape"], c["J"], c["LQ"])
+    try:
+        got = gpu_forward(plan, x)
+        rows = plan.coeff_index()
+    finally:
+        plan.close()
+    pick = [0, 7, 15]
+    want = o3.harmonic_scattering3d(x[pick], c["J"], c["LQ"])
+    errs = per_order_errors(got[pick], want, order_of_channels(rows), x[pick])
+    print("3d workload", errs, flush=True)
+    assert max(errs.values()) <= TOL, errs
