@@ -32,10 +32,16 @@ def _grid(shape):
 
 
 def _shifts(shape, sigma):
-    """Grid shifts per side s such that the summed copies cover 10 standard deviations on
-    every axis, (s + 1/2) n >= 10 sigma (beyond that the Gaussian factor is below 2e-22 of
-    its peak, whatever the polynomial factor here)."""
-    return max(0, int(np.ceil(10.0 * sigma / min(shape) - 0.5)))
+    """Per axis, the number s of grid shifts on each side such that the summed copies cover 10
+    standard deviations, (s + 1/2) n >= 10 sigma (beyond that the Gaussian factor is below
+    2e-22 of its peak, whatever the polynomial factor here)."""
+    return tuple(max(0, int(np.ceil(10.0 * sigma / n - 0.5))) for n in shape)
+
+
+def _shift_ranges(shifts, shape):
+    if np.isscalar(shifts):
+        shifts = (int(shifts),) * len(shape)
+    return [range(-s, s + 1) for s in shifts]
 
 
 def solid_harmonic_wavelet(shape, j, l, m, shifts=None):
@@ -45,10 +51,10 @@ def solid_harmonic_wavelet(shape, j, l, m, shifts=None):
         shifts = _shifts(shape, float(2 ** j))
     base = _grid(shape).astype(np.float64)
     out = np.zeros(shape, dtype=np.complex128)
-    rng = range(-shifts, shifts + 1)
-    for s0 in rng:
-        for s1 in rng:
-            for s2 in rng:
+    r0, r1, r2 = _shift_ranges(shifts, shape)
+    for s0 in r0:
+        for s1 in r1:
+            for s2 in r2:
                 u = base + np.array([s0 * shape[0], s1 * shape[1], s2 * shape[2]],
                                     dtype=np.float64)[:, None, None, None]
                 v = u / float(2 ** j)
@@ -69,10 +75,10 @@ def gaussian_lowpass(shape, J, shifts=None):
         shifts = _shifts(shape, sigma)
     base = _grid(shape).astype(np.float64)
     out = np.zeros(shape)
-    rng = range(-shifts, shifts + 1)
-    for s0 in rng:
-        for s1 in rng:
-            for s2 in rng:
+    r0, r1, r2 = _shift_ranges(shifts, shape)
+    for s0 in r0:
+        for s1 in r1:
+            for s2 in r2:
                 u = base + np.array([s0 * shape[0], s1 * shape[1], s2 * shape[2]],
                                     dtype=np.float64)[:, None, None, None]
                 out += np.exp(-0.5 * (u ** 2).sum(axis=0) / sigma ** 2)
