@@ -89,6 +89,8 @@ __global__ __launch_bounds__(256) void k3_sample(const float2 *__restrict__ src,
 
 
 // ---- fused passes for volumes whose (axis 1, axis 2) slabs fit a workgroup's LDS --------
+// (slabs of up to 4096 points: 256 threads and 1 to 16 slabs per workgroup; 8192 and 16384
+// points: one slab per workgroup of 512 or 1024 threads and up to 152 KB of LDS)
 //
 // A 3-D transform is split into the two slab axes (one workgroup holds whole N1 x N2
 // slabs: rows through registers, a transposition through LDS, columns through registers)
@@ -115,31 +117,39 @@ __host__ __device__ constexpr int slab_row_stride(int N2) {
 template <int N1, int N2>
 struct Slab {
   static constexpr int T1 = N1 / 16, T2 = N2 / 16;
-  static constexpr int TS = N1 * N2 / 16;  // threads per slab, 16 points each
-  static constexpr int SPW = 256 / TS;     // slabs per workgroup
+  static constexpr int TS = N1 * N2 / 16;       // threads per slab, 16 points each
+  static constexpr int NT = TS < 256 ? 256 : TS;  // threads per workgroup
+  static constexpr int SPW = NT / TS;           // slabs per workgroup
   static constexpr int RS = slab_row_stride(N2);
   static constexpr size_t lds_bytes = static_cast<size_t>(SPW) * N1 * RS * sizeof(float2);
-  static_assert(N1 >= 16 && N2 >= 16 && TS <= 256 && TS >= 16, "slab shape");
+  static_assert(N1 >= 16 && N2 >= 16 && TS <= 1024 && TS >= 16 && lds_bytes <= 160 * 1024,
+                "slab shape");
 
   // v: this thread's 16 points of row r (columns t + T2 i) -> after the call its 16 points
-  // of column c (rows t1 + T1 i) of the slab transformed along both axes
+  // of column c (rows t1 + T1 i) of the slab transformed along both axes.  The twiddles are
+  // fetched right before each transform so that they are not live across the whole kernel.
   template <bool INV>
   static __device__ __forceinline__ void transform(float2 (&v)[16], float2 *area, int r, int t, int c,
-                                                   int t1, const float2 (&wr)[16],
-                                                   const float2 (&wc)[16]) {
-    fft_core<16, T2, INV, false>(v, t, area + r * RS, T2 + 1, 1, wr);
+                                                   int t1, const float2 *__restrict__ tw, int tw_n) {
+    {
+      float2 wr[16];
+      load_twiddles<16, T2>(wr, t, tw, tw_n);
+      fft_core<16, T2, INV, false>(v, t, area + r * RS, T2 + 1, 1, wr);
+    }
 #pragma unroll
     for (int i = 0; i < 16; ++i) area[r * RS + t + T2 * i] = v[i];
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < 16; ++i) v[i] = area[(t1 + T1 * i) * RS + c];
     __syncthreads();
+    float2 wc[16];
+    load_twiddles<16, T1>(wc, t1, tw, tw_n);
     fft_core<16, T1, INV, false>(v, t1, area + c, T1 * RS, RS, wc);
   }
 };
 
 template <int N1, int N2>
-__global__ __launch_bounds__(256) void k3_slab_mul_inv(const float2 *__restrict__ Fh,
+__global__ __launch_bounds__((Slab<N1, N2>::NT)) void k3_slab_mul_inv(const float2 *__restrict__ Fh,
                                                        const float2 *__restrict__ tab,
                                                        float2 *__restrict__ W, long slabs, int n0,
                                                        int M, size_t mstride,
@@ -156,18 +166,24 @@ __global__ __launch_bounds__(256) void k3_slab_mul_inv(const float2 *__restrict_
   const int k0 = static_cast<int>(sl % n0);
   const size_t base = static_cast<size_t>(sl) * N1 * N2;
   const float2 *src = Fh + base + r * N2 + t;
-  float2 f[16];
+  // the slab of F^ stays in registers across the filters, except in the 1024-thread
+  // variants (128 registers per thread), which read it again for every filter
+  constexpr bool KEEP = S::NT < 1024;
+  float2 f[KEEP ? 16 : 1];
+  if (KEEP) {
 #pragma unroll
-  for (int i = 0; i < 16; ++i) f[i] = src[S::T2 * i];
-  float2 wr[16], wc[16];
-  load_twiddles<16, S::T2>(wr, t, tw, tw_n);
-  load_twiddles<16, S::T1>(wc, t1, tw, tw_n);
+    for (int i = 0; i < 16; ++i) f[KEEP ? i : 0] = src[S::T2 * i];
+  }
   for (int m = 0; m < M; ++m) {
     const float2 *tb = tab + (static_cast<size_t>(m) * n0 + k0) * N1 * N2 + r * N2 + t;
     float2 v[16];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) v[i] = c_mul(f[i], tb[S::T2 * i]);
-    S::template transform<true>(v, area, r, t, c, t1, wr, wc);
+    for (int i = 0; i < 16; ++i) {
+      v[i] = c_mul(KEEP ? f[KEEP ? i : 0] : src[S::T2 * i], tb[S::T2 * i]);
+      // 1024-thread variants: two batches of loads, so that the operands in flight fit
+      if (!KEEP && i == 7) __builtin_amdgcn_sched_barrier(0);
+    }
+    S::template transform<true>(v, area, r, t, c, t1, tw, tw_n);
     if (live) {
       float2 *dst = W + static_cast<size_t>(m) * mstride + base + c;
 #pragma unroll
@@ -178,7 +194,7 @@ __global__ __launch_bounds__(256) void k3_slab_mul_inv(const float2 *__restrict_
 }
 
 template <int N1, int N2>
-__global__ __launch_bounds__(256) void k3_slab_fwd_low(const float2 *__restrict__ Tin,
+__global__ __launch_bounds__((Slab<N1, N2>::NT)) void k3_slab_fwd_low(const float2 *__restrict__ Tin,
                                                        float2 *__restrict__ Uout,
                                                        const float *__restrict__ phi,
                                                        float2 *__restrict__ P, long slabs, int n0,
@@ -200,10 +216,7 @@ __global__ __launch_bounds__(256) void k3_slab_fwd_low(const float2 *__restrict_
   float2 v[16];
 #pragma unroll
   for (int i = 0; i < 16; ++i) v[i] = src[S::T2 * i];
-  float2 wr[16], wc[16];
-  load_twiddles<16, S::T2>(wr, t, tw, tw_n);
-  load_twiddles<16, S::T1>(wc, t1, tw, tw_n);
-  S::template transform<false>(v, area, r, t, c, t1, wr, wc);
+  S::template transform<false>(v, area, r, t, c, t1, tw, tw_n);
   if (Uout != nullptr && live) {
     float2 *dst = Uout + base + c;
 #pragma unroll
@@ -321,7 +334,12 @@ hipError_t slab_mul_inv_t(const float2 *Fh, const float2 *tab, float2 *W, long v
   const double pts = static_cast<double>(slabs) * N1 * N2;
   LaunchScope obs(name.c_str(), pts * 8.0 * (1 + M) + 8.0 * M * n0 * N1 * N2,
                   pts * M * (5.0 * (ilog2h(N1) + ilog2h(N2)) + 6.0), st);
-  hipLaunchKernelGGL((k3_slab_mul_inv<N1, N2>), dim3(static_cast<unsigned>(blocks)), dim3(256),
+  if (S::lds_bytes > 65536) {
+    static unsigned long long lds_ok = 0;
+    hipError_t e = allow_large_lds(reinterpret_cast<const void *>(k3_slab_mul_inv<N1, N2>), lds_ok);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL((k3_slab_mul_inv<N1, N2>), dim3(static_cast<unsigned>(blocks)), dim3(S::NT),
                      S::lds_bytes, st, Fh, tab, W, slabs, n0, M,
                      static_cast<size_t>(slabs) * N1 * N2, tw, tw_n);
   return hipGetLastError();
@@ -342,7 +360,12 @@ hipError_t slab_fwd_low_t(const float2 *Tin, float2 *Uout, const float *phi, flo
   LaunchScope obs(name.c_str(),
                   pts * 8.0 * (Uout ? 2 : 1) + 4.0 * n0 * N1 * N2 + 8.0 * volumes * folded,
                   pts * (5.0 * (ilog2h(N1) + ilog2h(N2)) + 4.0), st);
-  hipLaunchKernelGGL((k3_slab_fwd_low<N1, N2>), dim3(static_cast<unsigned>(blocks)), dim3(256),
+  if (S::lds_bytes > 65536) {
+    static unsigned long long lds_ok = 0;
+    hipError_t e = allow_large_lds(reinterpret_cast<const void *>(k3_slab_fwd_low<N1, N2>), lds_ok);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL((k3_slab_fwd_low<N1, N2>), dim3(static_cast<unsigned>(blocks)), dim3(S::NT),
                      S::lds_bytes, st, Tin, Uout, phi, P, slabs, n0, J, folded * K, folded * chan,
                      tw, tw_n);
   return hipGetLastError();
@@ -371,8 +394,10 @@ hipError_t axis0_t(const float2 *W, const float *xreal, float2 *dst, long volume
 
 bool fused3_supported(int n0, int n1, int n2, int J) {
   auto p2 = [](int v) { return v > 0 && (v & (v - 1)) == 0; };
+  // slabs of up to 16384 points, except 256 x 64 whose padded rows exceed the LDS of a CU
   return p2(n0) && p2(n1) && p2(n2) && n0 >= 4 && n0 <= 256 && n1 >= 16 && n2 >= 16 &&
-         n1 * n2 <= 4096 && J >= 1 && J <= 4 && (n1 >> J) >= 1 && (n2 >> J) >= 1;
+         n1 * n2 <= 16384 && !(n1 == 256 && n2 == 64) && J >= 1 && J <= 4 && (n1 >> J) >= 1 &&
+         (n2 >> J) >= 1;
 }
 
 #define SCAT3_SLAB_DISPATCH(CALL)                  \
@@ -392,6 +417,12 @@ bool fused3_supported(int n0, int n1, int n2, int J) {
     case (128 << 12) | 16: CALL(128, 16);          \
     case (128 << 12) | 32: CALL(128, 32);          \
     case (256 << 12) | 16: CALL(256, 16);          \
+    case (32 << 12) | 256: CALL(32, 256);          \
+    case (64 << 12) | 128: CALL(64, 128);          \
+    case (128 << 12) | 64: CALL(128, 64);          \
+    case (256 << 12) | 32: CALL(256, 32);          \
+    case (64 << 12) | 256: CALL(64, 256);          \
+    case (128 << 12) | 128: CALL(128, 128);        \
     default: return hipErrorInvalidValue;          \
   }
 

@@ -98,6 +98,11 @@ def _check(x, J, L, max_order=2):
     ((4, 16, 16), 2, 1, 2), ((8, 64, 16), 3, 2, 2), ((16, 16, 256), 2, 1, 2),
     ((8, 256, 16), 1, 1, 2), ((32, 32, 128), 2, 1, 2), ((16, 128, 32), 4, 1, 2),
     ((16, 32, 16), 2, 8, 1), ((128, 16, 64), 2, 0, 2),
+    # slabs of 8192 and 16384 points (512 and 1024 threads per slab)
+    ((8, 64, 128), 2, 1, 2), ((4, 128, 64), 1, 2, 2), ((4, 32, 256), 2, 1, 2),
+    ((8, 256, 32), 3, 1, 2), ((4, 128, 128), 2, 1, 2), ((4, 64, 256), 1, 1, 2),
+    # 256 x 64 slabs take the general schedule
+    ((4, 256, 64), 2, 1, 2),
 ])
 def test_parity_density_volumes(shape, J, L, mo):
     _check(workloads.volumes(shape, 3), J, L, mo)
