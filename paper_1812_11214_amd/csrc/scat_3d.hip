@@ -148,7 +148,7 @@ struct Slab {
   }
 };
 
-template <int N1, int N2>
+template <int N1, int N2, bool SPLIT>
 __global__ __launch_bounds__((Slab<N1, N2>::NT)) void k3_slab_mul_inv(const float2 *__restrict__ Fh,
                                                        const float2 *__restrict__ tab,
                                                        float2 *__restrict__ W, long slabs, int n0,
@@ -166,21 +166,23 @@ __global__ __launch_bounds__((Slab<N1, N2>::NT)) void k3_slab_mul_inv(const floa
   const int k0 = static_cast<int>(sl % n0);
   const size_t base = static_cast<size_t>(sl) * N1 * N2;
   const float2 *src = Fh + base + r * N2 + t;
-  // the slab of F^ stays in registers across the filters, except in the 1024-thread
-  // variants (128 registers per thread), which read it again for every filter
-  constexpr bool KEEP = S::NT < 1024;
+  // the slab of F^ stays in registers across the filters; the 1024-thread variants (128
+  // registers per thread) instead take one filter per workgroup and read it again
+  constexpr bool KEEP = !SPLIT;
   float2 f[KEEP ? 16 : 1];
   if (KEEP) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) f[KEEP ? i : 0] = src[S::T2 * i];
   }
-  for (int m = 0; m < M; ++m) {
+  // SPLIT: one filter per workgroup (blockIdx.y), no loop state to carry
+  const int m_first = SPLIT ? static_cast<int>(blockIdx.y) : 0, m_last = SPLIT ? m_first + 1 : M;
+  for (int m = m_first; m < m_last; ++m) {
     const float2 *tb = tab + (static_cast<size_t>(m) * n0 + k0) * N1 * N2 + r * N2 + t;
     float2 v[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       v[i] = c_mul(KEEP ? f[KEEP ? i : 0] : src[S::T2 * i], tb[S::T2 * i]);
-      // 1024-thread variants: two batches of loads, so that the operands in flight fit
+      // two batches of loads, so that the operands in flight fit
       if (!KEEP && i == 7) __builtin_amdgcn_sched_barrier(0);
     }
     S::template transform<true>(v, area, r, t, c, t1, tw, tw_n);
@@ -189,7 +191,7 @@ __global__ __launch_bounds__((Slab<N1, N2>::NT)) void k3_slab_mul_inv(const floa
 #pragma unroll
       for (int i = 0; i < 16; ++i) dst[(t1 + S::T1 * i) * N2] = v[i];
     }
-    __syncthreads();  // the slab area is reused by the next filter
+    if (!SPLIT) __syncthreads();  // the slab area is reused by the next filter
   }
 }
 
@@ -334,12 +336,16 @@ hipError_t slab_mul_inv_t(const float2 *Fh, const float2 *tab, float2 *W, long v
   const double pts = static_cast<double>(slabs) * N1 * N2;
   LaunchScope obs(name.c_str(), pts * 8.0 * (1 + M) + 8.0 * M * n0 * N1 * N2,
                   pts * M * (5.0 * (ilog2h(N1) + ilog2h(N2)) + 6.0), st);
+  constexpr bool SPLIT = S::NT == 1024;  // (measured: slower for the smaller slabs)
+  if (SPLIT && M > 65535) return hipErrorInvalidValue;
   if (S::lds_bytes > 65536) {
     static unsigned long long lds_ok = 0;
-    hipError_t e = allow_large_lds(reinterpret_cast<const void *>(k3_slab_mul_inv<N1, N2>), lds_ok);
+    hipError_t e =
+        allow_large_lds(reinterpret_cast<const void *>(k3_slab_mul_inv<N1, N2, SPLIT>), lds_ok);
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL((k3_slab_mul_inv<N1, N2>), dim3(static_cast<unsigned>(blocks)), dim3(S::NT),
+  hipLaunchKernelGGL((k3_slab_mul_inv<N1, N2, SPLIT>),
+                     dim3(static_cast<unsigned>(blocks), SPLIT ? M : 1), dim3(S::NT),
                      S::lds_bytes, st, Fh, tab, W, slabs, n0, M,
                      static_cast<size_t>(slabs) * N1 * N2, tw, tw_n);
   return hipGetLastError();
