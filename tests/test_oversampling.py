@@ -75,6 +75,8 @@ def test_host_plan_output_shapes():
     ((256, 256), 3, 2, 1, 1, False), ((128, 64), 4, 3, 2, 2, False), ((512, 512), 2, 2, 1, 1, False),
     ((1024,), 5, 2, 2, 3, False), ((4096,), 6, 8, 1, 2, False), ((28, 28), 2, 4, 1, 3, True),
     ((16, 16), 2, 3, 7, 2, False),
+    # 1-D rows of 256 and 128 points with nothing / little folded in the row kernel
+    ((65536,), 4, 2, 4, 2, False), ((16384,), 5, 1, 3, 2, False),
 ])
 def test_oversampled_parity_gpu(shape, J, LQ, o, batch, padded):
     import torch
