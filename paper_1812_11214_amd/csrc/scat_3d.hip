@@ -102,8 +102,10 @@ __global__ __launch_bounds__(256) void k3_sample(const float2 *__restrict__ src,
 //                     transform carries two of them: |W_p|^2 = |F conv g_2p|^2 +
 //                     |F conv g_2p+1|^2, which is all the non-linearity needs
 //   k3_axis0_rho      inverse transform along axis 0 of every W_m, sum of squared moduli in
-//                     registers, square root, forward transform along axis 0
-//   k3_slab_fwd_low   forward transform over the slab axes (giving U^), product with the
+//                     registers, square root, forward transform along axis 0; the result T
+//                     is the axis-0 spectrum of a real signal: rows 0 .. n0/2 are stored
+//   k3_slab_fwd_low   forward transform over the slab axes of those rows (giving U^ for
+//                     k0 <= n0/2 and, by conjugate symmetry, for n0 - k0), product with the
 //                     lowpass and the sum over the aliases of the slab axes (periodic
 //                     subsampling by 2^J seen from the Fourier side)
 //   k3_fold0          the aliases of axis 0; the small inverse transforms then give S
@@ -195,6 +197,9 @@ __global__ __launch_bounds__((Slab<N1, N2>::NT)) void k3_slab_mul_inv(const floa
   }
 }
 
+// Tin holds slabs k0 = 0 .. n0/2 only (the axis-0 spectrum of a real signal); the slab
+// n0 - k0 of U^ and of the folded lowpass product is the conjugate of slab k0 with both
+// slab indices negated, and is written from the same registers.
 template <int N1, int N2>
 __global__ __launch_bounds__((Slab<N1, N2>::NT)) void k3_slab_fwd_low(const float2 *__restrict__ Tin,
                                                        float2 *__restrict__ Uout,
@@ -211,18 +216,25 @@ __global__ __launch_bounds__((Slab<N1, N2>::NT)) void k3_slab_fwd_low(const floa
   float2 *area = lds + s * N1 * S::RS;
   const int r = q / S::T2, t = q % S::T2;
   const int c = q % N2, t1 = q / N2;
-  const int k0 = static_cast<int>(sl % n0);
-  const long vol = sl / n0;
-  const size_t base = static_cast<size_t>(sl) * N1 * N2;
-  const float2 *src = Tin + base + r * N2 + t;
+  const int H = n0 / 2 + 1;
+  const int k0 = static_cast<int>(sl % H);
+  const long vol = sl / H;
+  const bool twin = k0 > 0 && k0 < n0 - k0;  // slab n0 - k0 is a different slab
+  const float2 *src = Tin + static_cast<size_t>(sl) * N1 * N2 + r * N2 + t;
   float2 v[16];
 #pragma unroll
   for (int i = 0; i < 16; ++i) v[i] = src[S::T2 * i];
   S::template transform<false>(v, area, r, t, c, t1, tw, tw_n);
   if (Uout != nullptr && live) {
-    float2 *dst = Uout + base + c;
+    float2 *dst = Uout + (static_cast<size_t>(vol) * n0 + k0) * N1 * N2 + c;
 #pragma unroll
     for (int i = 0; i < 16; ++i) dst[(t1 + S::T1 * i) * N2] = v[i];
+    if (twin) {
+      float2 *dm = Uout + (static_cast<size_t>(vol) * n0 + (n0 - k0)) * N1 * N2 + ((N2 - c) & (N2 - 1));
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+        dm[((N1 - (t1 + S::T1 * i)) & (N1 - 1)) * N2] = make_float2(v[i].x, -v[i].y);
+    }
   }
   // lowpass product, then the sum over the 4^J aliases of the slab axes
   const float *ph = phi + static_cast<size_t>(k0) * N1 * N2 + c;
@@ -235,8 +247,9 @@ __global__ __launch_bounds__((Slab<N1, N2>::NT)) void k3_slab_fwd_low(const floa
   __syncthreads();
   const int m1 = N1 >> J, m2 = N2 >> J, al = 1 << J;
   if (!live) return;
-  float2 *dst = P + static_cast<size_t>(vol) * p_vol_stride + chan_off +
-                static_cast<size_t>(k0) * m1 * m2;
+  float2 *pv = P + static_cast<size_t>(vol) * p_vol_stride + chan_off;
+  float2 *dst = pv + static_cast<size_t>(k0) * m1 * m2;
+  float2 *dm = pv + static_cast<size_t>(n0 - k0) * m1 * m2;
   for (int o = q; o < m1 * m2; o += S::TS) {
     const int a = o / m2, b = o - a * m2;
     float2 acc = make_float2(0.f, 0.f);
@@ -247,12 +260,15 @@ __global__ __launch_bounds__((Slab<N1, N2>::NT)) void k3_slab_fwd_low(const floa
         acc.y += e.y;
       }
     dst[o] = acc;
+    if (twin) dm[((m1 - a) & (m1 - 1)) * m2 + ((m2 - b) & (m2 - 1))] = make_float2(acc.x, -acc.y);
   }
 }
 
 // Axis 0 of [volumes][E*T][Mc]: a workgroup takes TC columns of one volume, thread (t, c)
 // holds rows t + T i.  xreal != nullptr: forward transform of the real input.  Else: inverse
 // transform of the M signals W_m, root of the sum of their squared moduli, forward transform.
+// The transformed signal is real, so only rows 0 .. N0/2 of its spectrum are stored:
+// dst [volumes][N0/2 + 1][Mc].
 template <int E, int T>
 __global__ __launch_bounds__(256) void k3_axis0_rho(const float2 *__restrict__ W,
                                                     const float *__restrict__ xreal,
@@ -290,9 +306,10 @@ __global__ __launch_bounds__(256) void k3_axis0_rho(const float2 *__restrict__ W
     for (int i = 0; i < E; ++i) v[i] = make_float2(__builtin_amdgcn_sqrtf(acc[i]), 0.f);
   }
   fft_core<E, T, false, false>(v, t, lds + c, KS, TC, wt);
-  float2 *o = dst + off;
+  float2 *o = dst + static_cast<size_t>(vol) * (N0 / 2 + 1) * Mc + static_cast<size_t>(t) * Mc + c0 + c;
 #pragma unroll
-  for (int i = 0; i < E; ++i) o[i * step] = v[i];
+  for (int i = 0; i < E; ++i)
+    if (t + T * i <= N0 / 2) o[i * step] = v[i];
 }
 
 // Q[g][a0][e] = sum_p P[g][a0 + m0 p][e]: g over volumes x channels, e over the m1*m2
@@ -356,15 +373,17 @@ hipError_t slab_fwd_low_t(const float2 *Tin, float2 *Uout, const float *phi, flo
                           long volumes, int n0, int J, int K, int chan, const float2 *tw, int tw_n,
                           hipStream_t st) {
   using S = Slab<N1, N2>;
-  const long slabs = volumes * n0;
+  const long slabs = volumes * (n0 / 2 + 1);
   const long blocks = (slabs + S::SPW - 1) / S::SPW;
   if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
   const size_t folded = static_cast<size_t>(n0) * (N1 >> J) * (N2 >> J);
   const std::string name =
       "k3_slab_fwd_low<" + std::to_string(N1) + ", " + std::to_string(N2) + ">";
   const double pts = static_cast<double>(slabs) * N1 * N2;
+  const double full = static_cast<double>(volumes) * n0 * N1 * N2;
   LaunchScope obs(name.c_str(),
-                  pts * 8.0 * (Uout ? 2 : 1) + 4.0 * n0 * N1 * N2 + 8.0 * volumes * folded,
+                  pts * 8.0 + (Uout ? full * 8.0 : 0.0) + 4.0 * (n0 / 2 + 1) * N1 * N2 +
+                      8.0 * volumes * folded,
                   pts * (5.0 * (ilog2h(N1) + ilog2h(N2)) + 4.0), st);
   if (S::lds_bytes > 65536) {
     static unsigned long long lds_ok = 0;
@@ -389,7 +408,7 @@ hipError_t axis0_t(const float2 *W, const float *xreal, float2 *dst, long volume
   const std::string name = "k3_axis0_rho<" + std::to_string(E) + ", " + std::to_string(T) + ">";
   const double pts = static_cast<double>(volumes) * E * T * Mc;
   const int passes = xreal ? 1 : M + 1;
-  LaunchScope obs(name.c_str(), pts * (xreal ? 12.0 : 8.0 * (M + 1)),
+  LaunchScope obs(name.c_str(), pts * (xreal ? 4.0 : 8.0 * M) + pts * 8.0 * (E * T / 2 + 1) / (E * T),
                   pts * (passes * 5.0 * ilog2h(E * T) + (xreal ? 0.0 : 4.0 * M)), st);
   hipLaunchKernelGGL((k3_axis0_rho<E, T>), dim3(static_cast<unsigned>(blocks)), dim3(T * TC), lds, st,
                      W, xreal, dst, Mc, TC, M, static_cast<size_t>(volumes) * E * T * Mc, tw, tw_n);
