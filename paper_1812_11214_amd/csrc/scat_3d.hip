@@ -348,8 +348,8 @@ hipError_t slab_mul_inv_t(const float2 *Fh, const float2 *tab, float2 *W, long v
   const long slabs = volumes * n0;
   const long blocks = (slabs + S::SPW - 1) / S::SPW;
   if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
-  const std::string name =
-      "k3_slab_mul_inv<" + std::to_string(N1) + ", " + std::to_string(N2) + ">";
+  const std::string name = "k3_slab_mul_inv<" + std::to_string(N1) + ", " + std::to_string(N2) +
+                           (S::NT == 1024 ? ", true>" : ", false>");
   const double pts = static_cast<double>(slabs) * N1 * N2;
   LaunchScope obs(name.c_str(), pts * 8.0 * (1 + M) + 8.0 * M * n0 * N1 * N2,
                   pts * M * (5.0 * (ilog2h(N1) + ilog2h(N2)) + 6.0), st);
