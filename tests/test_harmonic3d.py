@@ -103,6 +103,8 @@ def _check(x, J, L, max_order=2):
     ((8, 256, 32), 3, 1, 2), ((4, 128, 128), 2, 1, 2), ((4, 64, 256), 1, 1, 2),
     # 256 x 64 slabs take the general schedule
     ((4, 256, 64), 2, 1, 2),
+    # longest axis 0, deepest supported fold of the fused passes, largest degree
+    ((256, 16, 16), 1, 0, 1), ((16, 32, 32), 4, 1, 2), ((8, 16, 16), 1, 8, 2),
 ])
 def test_parity_density_volumes(shape, J, L, mo):
     _check(workloads.volumes(shape, 3), J, L, mo)
@@ -126,6 +128,20 @@ def test_parity_white_noise_and_batch_layout():
     errs = per_order_errors(got.reshape((6,) + got.shape[2:]), want.reshape((6,) + want.shape[2:]),
                             orders, x.reshape(6, 16, 16, 16))
     assert max(errs.values()) <= TOL, errs
+
+
+@pytest.mark.gpu
+def test_empty_batch_is_a_no_op():
+    import torch
+    for shape in ((8, 8, 8), (8, 16, 16)):
+        plan = scat.Scattering(shape, 1, 1)
+        try:
+            x = torch.empty((0,) + shape, dtype=torch.float32, device="cuda")
+            y = plan.forward(x)
+            torch.cuda.synchronize()
+            assert tuple(y.shape) == (0, plan.K) + plan.out_shape
+        finally:
+            plan.close()
 
 
 @pytest.mark.gpu
