@@ -359,7 +359,25 @@ __global__ __launch_bounds__(E == 32 ? 128 : 256) void k_mulfold_reg(
   fft_core<E, T, true, true>(v, t, lds + rl * (T == 1 ? E : E * (T + 1)), T + 1, 1, wt);
   if (!valid) return;
   float2 *dp = dst + ((static_cast<size_t>(s_idx) * F + f_idx) * Mr + qr) * M + t;
-  if (post_tw_m > 0) {
+  if (post_tw_m > 0 && E == 16 && T >= 4 && post_tw_m == Mr * M) {
+    // exp(+2 pi i qr b / (Mr M)), b = t + T i, factors into exp(2 pi i qr t / (Mr M)) (one
+    // table read per lane) and exp(2 pi i qr i / (16 Mr)): 16 values per row, fetched by the
+    // row's T lanes into its exchange slot instead of 16 scattered reads per lane
+    float2 *slot = lds + rl * (E * (T + 1));
+    const int bstep = tw_n / (16 * Mr);
+    for (int i = t; i < 16; i += T) slot[i] = tw[((qr * i) & (16 * Mr - 1)) * bstep];
+    wave_sync();
+    float2 wa = tw[((qr * t) & (post_tw_m - 1)) * (tw_n / post_tw_m)];
+    wa.y = -wa.y;
+    if (valid) {
+#pragma unroll
+      for (int i = 0; i < E; ++i) {
+        float2 wb = slot[i];
+        wb.y = -wb.y;
+        dp[T * i] = cmul(v[i], cmul(wa, wb));
+      }
+    }
+  } else if (post_tw_m > 0) {
     const int step = tw_n / post_tw_m;
 #pragma unroll
     for (int i = 0; i < E; ++i) {
@@ -810,6 +828,22 @@ __global__ __launch_bounds__(256) void k_col_fast(const void *__restrict__ src_v
 #pragma unroll
       for (int i = 0; i < E; ++i)
         if (t + T * i <= MR / 2) nt_store(up + i * step, v[i]);
+    } else if (post_tw_m > 0 && E == 16 && post_tw_m == MR * Mc) {
+      // four-step forward: times exp(-2 pi i k_r b / M), k_r = t + T i, b the column,
+      // M = MR Mc = 16 T Mc.  It factors into exp(-2 pi i t b / M) (one table read per
+      // thread) and exp(-2 pi i i b / (16 Mc)), which the workgroup's threads fetch once for
+      // its TC columns into LDS (16 TC entries) instead of 16 scattered reads per thread.
+      __syncthreads();
+      const int bmask = 16 * Mc - 1, bstep = tw_n / (16 * Mc);
+      for (int idx = threadIdx.x; idx < 16 * TC; idx += blockDim.x) {
+        const int i = idx / TC, cc = idx - i * TC;
+        lds[idx] = tw[((i * (c0 + cc)) & bmask) * bstep];
+      }
+      __syncthreads();
+      float2 *up = uc + plane + off0;
+      const float2 wa = tw[((t * (c0 + c)) & (post_tw_m - 1)) * (tw_n / post_tw_m)];
+#pragma unroll
+      for (int i = 0; i < E; ++i) up[i * step] = cmul(v[i], cmul(wa, lds[i * TC + c]));
     } else if (post_tw_m > 0) {
       // four-step forward: times exp(-2 pi i k_r c / post_tw_m), k_r = t + T i, c the column
       float2 *up = uc + plane + off0;
