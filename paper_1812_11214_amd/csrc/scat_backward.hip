@@ -286,7 +286,24 @@ __global__ __launch_bounds__(256) void k_cols_modback(float2 *__restrict__ data,
 #pragma unroll
   for (int i = 0; i < E; ++i) v[i] = p[i * step];
   float2 fs[E];  // four-step twiddles exp(-2 pi i k1 b / tw_m) of this thread's elements
-  if (tw_m > 0) {
+  if (tw_m > 0 && E == 16 && T > 1 && tw_m == M * Mc) {
+    // k1 = t + T i, b the column, tw_m = 16 T Mc: the twiddle is exp(-2 pi i t b / tw_m) (one
+    // table read per thread) times exp(-2 pi i i b / (16 Mc)), fetched once for the
+    // workgroup's TC columns into LDS (16 TC entries) instead of 16 scattered reads per thread
+    const int bmask = 16 * Mc - 1, bstep = tw_n / (16 * Mc);
+    for (int idx = threadIdx.x; idx < 16 * TC; idx += blockDim.x) {
+      const int i = idx / TC, cc = idx - i * TC;
+      lds[idx] = tw[((i * (c0 + cc)) & bmask) * bstep];
+    }
+    __syncthreads();
+    const float2 wa = tw[((t * (c0 + c)) & (tw_m - 1)) * (tw_n / tw_m)];
+#pragma unroll
+    for (int i = 0; i < E; ++i) {
+      fs[i] = c_mul(wa, lds[(i & 15) * TC + c]);
+      v[i] = c_mul(v[i], make_float2(fs[i].x, -fs[i].y));
+    }
+    __syncthreads();  // the table's place is the exchange area of the transforms below
+  } else if (tw_m > 0) {
     const int tstep = tw_n / tw_m;
 #pragma unroll
     for (int i = 0; i < E; ++i) {
