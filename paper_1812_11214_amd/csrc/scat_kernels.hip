@@ -622,14 +622,16 @@ __device__ __forceinline__ void rows1d_child_inv(float2 *slot, int t, int tw_ste
   }
 }
 
-template <int T>
+// (E = 16 points per lane; rows of 4 and 8 points: E = row length, T = 1.)
+template <int E, int T>
 __global__ __launch_bounds__(256, 4) void k_rows1d_reg(const float2 *__restrict__ src, long rows,
                                                     int Sr, Rows1dArgs a,
                                                     const float2 *__restrict__ tw, int tw_n) {
+  static_assert(E == 16 || T == 1, "short rows are held by one lane");
   constexpr bool ROWTW = T >= 4;
-  constexpr int E = 16, Sc = E * T, RPB = 256 / T;
+  constexpr int Sc = E * T, RPB = 256 / T;
   constexpr int XS = (T == 1 ? E : E * (T + 1)) + (ROWTW ? 16 : 0);
-  constexpr int lgSc = T == 1 ? 4 : T == 2 ? 5 : T == 4 ? 6 : T == 8 ? 7 : 8;
+  constexpr int lgSc = (E == 4 ? 2 : E == 8 ? 3 : 4) + (T == 1 ? 0 : T == 2 ? 1 : T == 4 ? 2 : T == 8 ? 3 : 4);
   extern __shared__ float2 lds[];
   float2 *twl = lds;
   for (int j = threadIdx.x; j < Sc; j += blockDim.x) twl[j] = tw[j * (tw_n / Sc)];
@@ -652,7 +654,7 @@ __global__ __launch_bounds__(256, 4) void k_rows1d_reg(const float2 *__restrict_
     fft_core<E, T, false, true>(v, t, slot, T + 1, 1, wt);
   }
   // exp(+2 pi i k1 i / (16 Sr)): the row's share of every child's four-step twiddle
-  float2 *rowtw = slot + XS - 16;
+  float2 *rowtw = ROWTW ? slot + XS - 16 : slot;
   if (ROWTW) {
     // lane t fetches entries t, t + T, ... (T >= 4 lanes share the 16 entries)
     const int rstep = tw_n / (16 * Sr);
@@ -707,8 +709,8 @@ __global__ __launch_bounds__(256, 4) void k_rows1d_reg(const float2 *__restrict_
         break;
       case 1: rows1d_child_inv<2, 1, ROWTW>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, valid, rowtw); break;
       case 2: rows1d_child_inv<4, 1, ROWTW>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, valid, rowtw); break;
-      case 3: rows1d_child_inv<8, 1, ROWTW>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, valid, rowtw); break;
-      case 4: rows1d_child_inv<16, 1, ROWTW>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, valid, rowtw); break;
+      case 3: if (E >= 8) rows1d_child_inv<(E >= 8 ? 8 : 4), 1, ROWTW>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, valid, rowtw); break;
+      case 4: if (E >= 16) rows1d_child_inv<(E >= 16 ? 16 : 4), 1, ROWTW>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, valid, rowtw); break;
       case 5: if (T >= 2) rows1d_child_inv<16, (T >= 2 ? 2 : 1), ROWTW>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, valid, rowtw); break;
       case 6: if (T >= 4) rows1d_child_inv<16, (T >= 4 ? 4 : 1), ROWTW>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, valid, rowtw); break;
       case 7: if (T >= 8) rows1d_child_inv<16, (T >= 8 ? 8 : 1), ROWTW>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, valid, rowtw); break;
@@ -1693,17 +1695,17 @@ hipError_t launch_row_fwd_reg_t(float2 *data, long rows, const float2 *tw, int t
 
 void set_launch_observer(LaunchObserver *o) { g_observer = o; }
 
-template <int T>
+template <int E, int T>
 hipError_t launch_rows1d_reg_t(const float2 *src, long rows, int Sr, const Rows1dArgs &a, double bytes,
                                double flops, const float2 *tw, int tw_n, hipStream_t st) {
-  constexpr int E = 16, Sc = E * T, RPB = 256 / T;
+  constexpr int Sc = E * T, RPB = 256 / T;
   constexpr int XS = (T == 1 ? E : E * (T + 1)) + (T >= 4 ? 16 : 0);  // as in the kernel
   const long blocks = (rows + RPB - 1) / RPB;
   if (blocks <= 0 || blocks > 0x7fffffffL) return hipErrorInvalidValue;
   const size_t lds = (static_cast<size_t>(Sc) + static_cast<size_t>(RPB) * XS) * sizeof(float2);
-  const std::string name = "k_rows1d_reg<" + std::to_string(T) + ">";
+  const std::string name = "k_rows1d_reg<" + std::to_string(E) + ", " + std::to_string(T) + ">";
   Observe ob(name.c_str(), bytes, flops, st);
-  hipLaunchKernelGGL((k_rows1d_reg<T>), dim3(static_cast<unsigned>(blocks)), dim3(256), lds, st, src,
+  hipLaunchKernelGGL((k_rows1d_reg<E, T>), dim3(static_cast<unsigned>(blocks)), dim3(256), lds, st, src,
                      rows, Sr, a, tw, tw_n);
   return hipGetLastError();
 }
@@ -1730,11 +1732,13 @@ hipError_t launch_rows1d(const float2 *src, long nodes, int Sr, int Sc, const Ro
   }
   const double all_flops = static_cast<double>(nodes) * Sr * flops;
   switch (Sc) {
-    case 16: return launch_rows1d_reg_t<1>(src, nodes * Sr, Sr, a, bytes, all_flops, tw, tw_n, st);
-    case 32: return launch_rows1d_reg_t<2>(src, nodes * Sr, Sr, a, bytes, all_flops, tw, tw_n, st);
-    case 64: return launch_rows1d_reg_t<4>(src, nodes * Sr, Sr, a, bytes, all_flops, tw, tw_n, st);
-    case 128: return launch_rows1d_reg_t<8>(src, nodes * Sr, Sr, a, bytes, all_flops, tw, tw_n, st);
-    case 256: return launch_rows1d_reg_t<16>(src, nodes * Sr, Sr, a, bytes, all_flops, tw, tw_n, st);
+    case 4: return launch_rows1d_reg_t<4, 1>(src, nodes * Sr, Sr, a, bytes, all_flops, tw, tw_n, st);
+    case 8: return launch_rows1d_reg_t<8, 1>(src, nodes * Sr, Sr, a, bytes, all_flops, tw, tw_n, st);
+    case 16: return launch_rows1d_reg_t<16, 1>(src, nodes * Sr, Sr, a, bytes, all_flops, tw, tw_n, st);
+    case 32: return launch_rows1d_reg_t<16, 2>(src, nodes * Sr, Sr, a, bytes, all_flops, tw, tw_n, st);
+    case 64: return launch_rows1d_reg_t<16, 4>(src, nodes * Sr, Sr, a, bytes, all_flops, tw, tw_n, st);
+    case 128: return launch_rows1d_reg_t<16, 8>(src, nodes * Sr, Sr, a, bytes, all_flops, tw, tw_n, st);
+    case 256: return launch_rows1d_reg_t<16, 16>(src, nodes * Sr, Sr, a, bytes, all_flops, tw, tw_n, st);
     default: break;
   }
   // other row lengths: spectrum rows and one child's rows side by side in LDS
@@ -1796,9 +1800,10 @@ hipError_t launch_col(int mode, const void *src, long nodes, int Mr, int Mc, flo
                       float2 *y_out) {
   if (y_out != nullptr && mode != 1) return hipErrorInvalidValue;
   if (uc_half && (mode == 2 || post_tw_m != 0 || Mr < 2)) return hipErrorInvalidValue;
-  // register-resident variant: modes 0/1, no four-step twiddle, column length 16*T with
-  // T | 16, at least 16 columns, lowpass length dividing the column length
-  if (mode != 2 && Mc >= 16 && tw_n % Mr == 0 && (post_tw_m == 0 || !uc_half) &&
+  // register-resident variant: modes 0/1, column length 16*T with T | 16, at least 16
+  // columns (4 without a lowpass tail), lowpass length dividing the column length
+  if (mode != 2 && (Mc >= 16 || (Mc >= 4 && w_out == nullptr)) && tw_n % Mr == 0 &&
+      (post_tw_m == 0 || !uc_half) &&
       (w_out == nullptr || (m_r >= 1 && m_r <= Mr))) {
     switch (Mr) {
       case 32: return launch_col_fast_t<32>(mode, src, nodes, Mc, uc, uc_half, post_tw_m, phi_rows, m_r, w_out, tw, tw_n, st, y_out);
