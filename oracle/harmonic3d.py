@@ -143,3 +143,58 @@ def harmonic_scattering3d(x, J, L, max_order=2, bank=None):
                 s2.append(lowpass(rho(U1h, psi_hat[j2][l])))
     out.extend(s2)
     return np.stack(out, axis=len(lead))
+
+
+def harmonic_scattering3d_backward(x, g, J, L, max_order=2, bank=None):
+    """Gradient of sum(g * harmonic_scattering3d(x)) with respect to x (the paper lists
+    differentiability as a feature, section 3, and prints no gradient): the adjoint chain of
+    the transform above.  x: (..., N0, N1, N2) real; g: the shape of the transform's output.
+
+    With F real, y_m = F conv psi_m and U = sqrt(sum_m |y_m|^2):
+        dU = sum_m Re(conj(y_m) dy_m) / U            (no gradient where U = 0)
+        g_F = Re sum_m corr(g_U y_m / U, psi_m)       (corr = adjoint of conv)
+    and for S = (F conv phi)[2^J n]: g_F = corr(upsample_zero(g_S), phi)."""
+    x = np.asarray(x, dtype=np.float64)
+    g = np.asarray(g, dtype=np.float64)
+    shape = x.shape[-3:]
+    if bank is None:
+        bank = bank_3d(shape, J, L)
+    psi_hat, phi_hat = bank['psi_hat'], bank['phi_hat']
+    ax = (-3, -2, -1)
+    s = 1 << J
+    lead = x.shape[:-3]
+    nl = len(lead)
+
+    def chan(c):
+        return g[(slice(None),) * nl + (c,)]
+
+    def lowpass_adj(gs):
+        up = np.zeros(lead + shape)
+        up[..., ::s, ::s, ::s] = gs
+        return np.fft.ifftn(np.fft.fftn(up, axes=ax) * np.conj(phi_hat), axes=ax).real
+
+    def filtered(Fh, wav_hat):
+        y = np.fft.ifftn(Fh[..., None, :, :, :] * wav_hat, axes=ax)
+        return y, np.sqrt((np.abs(y) ** 2).sum(axis=-4))
+
+    def rho_adj(gU, y, U, wav_hat):
+        safe = np.where(U > 0, U, 1.0)
+        h = np.where(U > 0, gU / safe, 0.0)[..., None, :, :, :] * y
+        return np.fft.ifftn((np.fft.fftn(h, axes=ax) * np.conj(wav_hat)).sum(axis=-4), axes=ax).real
+
+    X = np.fft.fftn(x, axes=ax)
+    gx = lowpass_adj(chan(0))
+    c1, c2 = 1, 1 + J * (L + 1)
+    for j1 in range(J):
+        for l in range(L + 1):
+            y1, U1 = filtered(X, psi_hat[j1][l])
+            gU1 = lowpass_adj(chan(c1))
+            c1 += 1
+            if max_order >= 2:
+                U1h = np.fft.fftn(U1, axes=ax)
+                for j2 in range(j1 + 1, J):
+                    y2, U2 = filtered(U1h, psi_hat[j2][l])
+                    gU1 = gU1 + rho_adj(lowpass_adj(chan(c2)), y2, U2, psi_hat[j2][l])
+                    c2 += 1
+            gx = gx + rho_adj(gU1, y1, U1, psi_hat[j1][l])
+    return gx
