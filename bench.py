@@ -35,7 +35,10 @@ def cpu_baseline(planes, dims, J, LQ, channels, budget_s=20.0, grad=None):
     if dims == 3:
         from oracle import harmonic3d
         bank = harmonic3d.bank_3d(planes.shape[-3:], J, LQ)
-        run = lambda x: harmonic3d.harmonic_scattering3d(x, J, LQ, bank=bank)
+        if grad is not None:
+            run = lambda x: harmonic3d.harmonic_scattering3d_backward(x, grad[:len(x)], J, LQ, bank=bank)
+        else:
+            run = lambda x: harmonic3d.harmonic_scattering3d(x, J, LQ, bank=bank)
     elif dims == 2 and grad is not None:
         n_r, n_c = planes.shape[-2:]
         bank = oracle.bank_2d(n_r, n_c, J, LQ)
@@ -95,9 +98,6 @@ def main():
 
     wl = args.workload
     cfg = workloads.config(wl)
-    if cfg["dims"] == 3 and args.backward:
-        print("bench.py: 3-D plans have no backward pass", file=sys.stderr)
-        sys.exit(2)
     P = workloads.num_planes(wl)
     C = cfg["channels"]
     x_host = workloads.planes(wl)

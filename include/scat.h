@@ -73,7 +73,8 @@ typedef enum {
  * standard deviation 2^J, both sampled at the integers and periodised; every convolution is
  * evaluated on the full grid and the lowpassed result read at the samples 2^J n.  Since rho
  * does not depend on the orthonormal basis of the degree-l harmonics, the tables hold the
- * real harmonics.  No padded plans, oversampling or scat_backward in 3-D (SCAT_ERR_ARG).
+ * real harmonics.  No padded plans or oversampling in 3-D (SCAT_ERR_ARG); scat_backward works
+ * on every 3-D plan.
  *
  * On success *out_plan is a new plan the caller must release with scat_plan_destroy.
  * On failure *out_plan is NULL and nothing is leaked.
@@ -165,7 +166,10 @@ scat_status scat_forward(scat_plan *plan, const float *in, float *out, long batc
  * complex signals before every modulus are kept in the plan's scratch buffer until the
  * call's work has run; the same one-call-in-flight rule as scat_forward applies, and the
  * two share the scratch buffer.  Enqueues on `stream`, does not synchronise.
- * Errors: SCAT_ERR_ARG for a padded 1-D plan, a 3-D plan or batch < 0.  SCAT_ERR_SHAPE, 2-D: unless every
+ * 3-D plans: rho = sqrt(sum_m |y_m|^2) passes g y_m / rho to y_m (nothing where rho = 0); the
+ * degree-0 signal y is real, so there the factor is sign(y), decided by rounding where |y| is
+ * below fp32 resolution.
+ * Errors: SCAT_ERR_ARG for a padded 1-D plan or batch < 0.  SCAT_ERR_SHAPE, 2-D: unless every
  * side and every side subsampled for the last octave lies in 4...512 and the output grid
  * has at most 1024 points; 1-D: unless the signal, seen as the n1 x n2 matrix of the
  * four-step transform (n2 = 2^max(ceil(log2(n)/2), J), n1 = n / n2), has n1 in 4...512 and

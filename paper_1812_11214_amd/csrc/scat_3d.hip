@@ -34,15 +34,62 @@ __global__ __launch_bounds__(256) void k3_real_to_complex(const float *__restric
     out[i] = make_float2(x[i], 0.f);
 }
 
-// dst[v][e] = src[v][e] * filt[e]: one real table applied to every volume of the batch
+// dst[v][e] (+)= src[v][e] * filt[e * fstride]: one real table applied to every volume of the
+// batch (fstride = 2 reads one member of a table pair stored as complex numbers)
 __global__ __launch_bounds__(256) void k3_mul_table(const float2 *__restrict__ src,
-                                                    const float *__restrict__ filt,
-                                                    float2 *__restrict__ dst, long total, long n) {
+                                                    const float *__restrict__ filt, int fstride,
+                                                    float2 *__restrict__ dst, long total, long n,
+                                                    int accumulate) {
   const long stride = static_cast<long>(gridDim.x) * blockDim.x;
   for (long i = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x; i < total; i += stride) {
-    const float f = filt[i % n];
+    const float f = filt[(i % n) * fstride];
     const float2 v = src[i];
-    dst[i] = make_float2(v.x * f, v.y * f);
+    float2 o = make_float2(v.x * f, v.y * f);
+    if (accumulate) {
+      const float2 d = dst[i];
+      o.x += d.x;
+      o.y += d.y;
+    }
+    dst[i] = o;
+  }
+}
+
+// Backward pass helpers.  up[v][a 2^J][b 2^J][c 2^J] = g[v][chan][a][b][c], zero elsewhere.
+__global__ __launch_bounds__(256) void k3_upsample(const float *__restrict__ g,
+                                                   float2 *__restrict__ up, long volumes, int K,
+                                                   int chan, int n0, int n1, int n2, int J) {
+  const long per = static_cast<long>(n0) * n1 * n2;
+  const long total = volumes * per;
+  const int mask = (1 << J) - 1;
+  const int m1 = n1 >> J, m2 = n2 >> J;
+  const long mper = static_cast<long>(n0 >> J) * m1 * m2;
+  const long stride = static_cast<long>(gridDim.x) * blockDim.x;
+  for (long i = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x; i < total; i += stride) {
+    const long v = i / per;
+    long e = i - v * per;
+    const int c = static_cast<int>(e % n2);
+    e /= n2;
+    const int b = static_cast<int>(e % n1);
+    const int a = static_cast<int>(e / n1);
+    float val = 0.f;
+    if (((a | b | c) & mask) == 0)
+      val = g[(static_cast<size_t>(v) * K + chan) * mper +
+              (static_cast<size_t>(a >> J) * m1 + (b >> J)) * m2 + (c >> J)];
+    up[i] = make_float2(val, 0.f);
+  }
+}
+
+// y[i] <- Re(gu[i]) * y[i] / sqrt(acc[i])  (0 where acc = sum_m |y_m|^2 vanishes): the
+// gradient of rho = sqrt(sum_m |y_m|^2) with respect to y_m, given the gradient of rho
+__global__ __launch_bounds__(256) void k3_rho_back(const float2 *__restrict__ gu,
+                                                   const float *__restrict__ acc,
+                                                   float2 *__restrict__ y, long total) {
+  const long stride = static_cast<long>(gridDim.x) * blockDim.x;
+  for (long i = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x; i < total; i += stride) {
+    const float a = acc[i];
+    const float s = a > 0.f ? gu[i].x / __builtin_amdgcn_sqrtf(a) : 0.f;
+    const float2 v = y[i];
+    y[i] = make_float2(v.x * s, v.y * s);
   }
 }
 
@@ -524,12 +571,31 @@ hipError_t launch3_real_to_complex(const float *x, float2 *out, long total, hipS
 }
 
 hipError_t launch3_mul_table(const float2 *src, const float *filt, float2 *dst, long volumes, long n,
-                             hipStream_t st) {
+                             hipStream_t st, int fstride, bool accumulate) {
   const long total = volumes * n;
   if (total <= 0) return hipSuccess;
-  LaunchScope obs("k3_mul_table", total * 16.0 + n * 4.0, total * 2.0, st);
-  hipLaunchKernelGGL(k3_mul_table, dim3(blocks_for(total)), dim3(256), 0, st, src, filt, dst, total,
-                     n);
+  if (fstride < 1) return hipErrorInvalidValue;
+  LaunchScope obs("k3_mul_table", total * (accumulate ? 24.0 : 16.0) + n * 4.0, total * 2.0, st);
+  hipLaunchKernelGGL(k3_mul_table, dim3(blocks_for(total)), dim3(256), 0, st, src, filt, fstride, dst,
+                     total, n, accumulate ? 1 : 0);
+  return hipGetLastError();
+}
+
+hipError_t launch3_upsample(const float *g, float2 *up, long volumes, int K, int chan, int n0, int n1,
+                            int n2, int J, hipStream_t st) {
+  const long total = volumes * n0 * n1 * n2;
+  if (total <= 0) return hipSuccess;
+  LaunchScope obs("k3_upsample", total * 8.0, 0.0, st);
+  hipLaunchKernelGGL(k3_upsample, dim3(blocks_for(total)), dim3(256), 0, st, g, up, volumes, K, chan,
+                     n0, n1, n2, J);
+  return hipGetLastError();
+}
+
+hipError_t launch3_rho_back(const float2 *gu, const float *acc, float2 *y, long total,
+                            hipStream_t st) {
+  if (total <= 0) return hipSuccess;
+  LaunchScope obs("k3_rho_back", total * 28.0, total * 4.0, st);
+  hipLaunchKernelGGL(k3_rho_back, dim3(blocks_for(total)), dim3(256), 0, st, gu, acc, y, total);
   return hipGetLastError();
 }
 

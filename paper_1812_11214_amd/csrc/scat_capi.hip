@@ -1139,6 +1139,112 @@ scat_status forward_3d(scat_plan *p, const float *in, float *out, long p0, long 
   return SCAT_OK;
 }
 
+// ---- backward pass of a 3-D plan (every shape: the full-grid schedule, transforms by the
+// plain passes).  With spectra A accumulated in the Fourier domain, S = sample(F conv phi)
+// gives A_F += phi^ FFT(upsample(g_S)); rho = sqrt(sum_m |y_m|^2), y_m = IFFT(F^ g_m) gives
+// A_F += sum_m g_m FFT(g_rho y_m / rho); g_F = Re IFFT(A_F).  The filtered signals y_m of the
+// node at hand (and of its child) are recomputed and kept while their gradients are formed.
+size_t bytes_per_volume_3d_bwd(const scat_plan &p) {
+  const size_t n = p.h3.points(), M = 2 * static_cast<size_t>(p.h3.L) + 1;
+  return n * sizeof(float2) * (5 + 2 * M) + n * sizeof(float) * 2;
+}
+
+scat_status backward_3d(scat_plan *p, const float *in, const float *gout, float *gin, long p0, long pc,
+                        hipStream_t st) {
+  const scat::HostPlan3D &h = p->h3;
+  const int n0 = h.shape[0], n1 = h.shape[1], n2 = h.shape[2];
+  const int J = h.J, L = h.L, K = h.K, M = 2 * L + 1;
+  const size_t n = h.points();
+  const long tot = pc * static_cast<long>(n);
+  const bool second = h.max_order == 2 && J >= 2;
+  float2 *XH = static_cast<float2 *>(p->d_scratch);
+  float2 *AX = XH + tot, *UH = AX + tot, *AU = UH + tot, *Wk = AU + tot;
+  float2 *W1 = Wk + tot, *W2 = W1 + static_cast<size_t>(M) * tot;
+  float *acc1 = reinterpret_cast<float *>(W2 + static_cast<size_t>(M) * tot), *acc2 = acc1 + tot;
+  const float *tab = p->d_tables;
+  const float2 *tw = p->d_tw;
+  const int tw_n = p->tw_n;
+  const float *x = in + static_cast<size_t>(p0) * n;
+  const size_t mout = static_cast<size_t>(n0 >> J) * (n1 >> J) * (n2 >> J);
+  const float *go = gout + static_cast<size_t>(p0) * K * mout;
+  float *gi = gin + static_cast<size_t>(p0) * n;
+  const float *phi = tab + p->phi3_off;
+  // table m of (j, l): fused plans keep them as interleaved pairs
+  auto table = [&](int j, int l, int m, int *stride) -> const float * {
+    const float *base = tab + p->psi3_off[static_cast<size_t>(j) * (L + 1) + l];
+    *stride = p->fused3 ? 2 : 1;
+    return p->fused3 ? base + static_cast<size_t>(m / 2) * 2 * n + (m & 1)
+                     : base + static_cast<size_t>(m) * n;
+  };
+  auto fft3 = [&](float2 *d, bool inv) {
+    return scat::launch3_fft(d, pc, n0, n1, n2, inv, tw, tw_n, st);
+  };
+  // dst (=|+=) phi^ FFT(upsample(g[chan]))
+  auto lowpass_adj = [&](int chan, float2 *dst, bool accumulate) -> hipError_t {
+    hipError_t e = scat::launch3_upsample(go, Wk, pc, K, chan, n0, n1, n2, J, st);
+    if (e != hipSuccess) return e;
+    e = fft3(Wk, false);
+    if (e != hipSuccess) return e;
+    return scat::launch3_mul_table(Wk, phi, dst, pc, static_cast<long>(n), st, 1, accumulate);
+  };
+  // W[m] = IFFT(Fh g_{j,l,m}), acc = sum_m |W[m]|^2
+  auto filtered = [&](const float2 *Fh, int j, int l, float2 *W, float *acc) -> hipError_t {
+    for (int m = 0; m < 2 * l + 1; ++m) {
+      int fs;
+      const float *t = table(j, l, m, &fs);
+      float2 *w = W + static_cast<size_t>(m) * tot;
+      hipError_t e = scat::launch3_mul_table(Fh, t, w, pc, static_cast<long>(n), st, fs, false);
+      if (e != hipSuccess) return e;
+      e = fft3(w, true);
+      if (e != hipSuccess) return e;
+      e = scat::launch3_accum_abs2(w, acc, tot, m == 0, st);
+      if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+  };
+  // A += sum_m g_m FFT(Re(gu) W[m] / sqrt(acc)); W is overwritten
+  auto rho_adj = [&](const float2 *gu, int j, int l, float2 *W, const float *acc,
+                     float2 *A) -> hipError_t {
+    for (int m = 0; m < 2 * l + 1; ++m) {
+      int fs;
+      const float *t = table(j, l, m, &fs);
+      float2 *w = W + static_cast<size_t>(m) * tot;
+      hipError_t e = scat::launch3_rho_back(gu, acc, w, tot, st);
+      if (e != hipSuccess) return e;
+      e = fft3(w, false);
+      if (e != hipSuccess) return e;
+      e = scat::launch3_mul_table(w, t, A, pc, static_cast<long>(n), st, fs, true);
+      if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+  };
+  SCAT_TRY(scat::launch3_real_to_complex(x, XH, tot, st));
+  SCAT_TRY(fft3(XH, false));
+  SCAT_TRY(lowpass_adj(0, AX, false));
+  int c1 = 1, c2 = 1 + J * (L + 1);
+  for (int j1 = 0; j1 < J; ++j1)
+    for (int l = 0; l <= L; ++l) {
+      SCAT_TRY(filtered(XH, j1, l, W1, acc1));
+      SCAT_TRY(lowpass_adj(c1++, AU, false));
+      if (second && j1 < J - 1) {
+        SCAT_TRY(scat::launch3_sqrt(acc1, UH, tot, st));
+        SCAT_TRY(fft3(UH, false));
+        for (int j2 = j1 + 1; j2 < J; ++j2) {
+          SCAT_TRY(filtered(UH, j2, l, W2, acc2));
+          // gradient of the child's modulus signal: Re IFFT(phi^ FFT(upsample(g)))
+          SCAT_TRY(lowpass_adj(c2++, Wk, false));
+          SCAT_TRY(fft3(Wk, true));
+          SCAT_TRY(rho_adj(Wk, j2, l, W2, acc2, AU));
+        }
+      }
+      SCAT_TRY(fft3(AU, true));
+      SCAT_TRY(rho_adj(AU, j1, l, W1, acc1, AX));
+    }
+  SCAT_TRY(fft3(AX, true));
+  SCAT_TRY(scat::launch3_real_part(AX, gi, tot, st));
+  return SCAT_OK;
+}
+
 // ---- 1-D schedule (four-step transforms: the signal is an n1 x n2 matrix)
 scat_status forward_1d(scat_plan *p, const float *in, float *out, long p0, long pc,
                        const Layout &lay, hipStream_t st, const Tape *tape) {
@@ -1346,7 +1452,37 @@ scat_status scat_backward(scat_plan *plan, const float *in, const float *grad_ou
   if (plan == nullptr) return SCAT_ERR_NULL;
   if (batch < 0) return SCAT_ERR_ARG;
   const scat::HostPlan &h = plan->host;
-  if (h.dims == 3) return SCAT_ERR_ARG;  // no backward pass for 3-D plans
+  if (h.dims == 3) {
+    if (batch == 0) return SCAT_OK;
+    if (in == nullptr || grad_out == nullptr || grad_in == nullptr) return SCAT_ERR_NULL;
+    if (!plan->has_device) return SCAT_ERR_DEVICE;
+    int dev3 = -1;
+    if (hipGetDevice(&dev3) != hipSuccess || dev3 != plan->device) return SCAT_ERR_DEVICE;
+    hipStream_t st3 = static_cast<hipStream_t>(stream);
+    const size_t per = bytes_per_volume_3d_bwd(*plan);
+    long chunk = static_cast<long>(scratch_budget() / per);
+    if (chunk < 1) chunk = 1;
+    if (chunk > batch) chunk = batch;
+    const size_t need3 = per * static_cast<size_t>(chunk);
+    if (need3 > plan->scratch_bytes) {
+      if (hipDeviceSynchronize() != hipSuccess) return SCAT_ERR_DEVICE;
+      if (plan->d_scratch) (void)hipFree(plan->d_scratch);
+      plan->d_scratch = nullptr;
+      plan->scratch_bytes = 0;
+      if (hipMalloc(&plan->d_scratch, need3) != hipSuccess) return SCAT_ERR_ALLOC;
+      plan->scratch_bytes = need3;
+    }
+    struct ObserverScope3 {
+      explicit ObserverScope3(scat::LaunchObserver *o) { scat::set_launch_observer(o); }
+      ~ObserverScope3() { scat::set_launch_observer(nullptr); }
+    } scope3(plan->timer.enabled ? &plan->timer : nullptr);
+    for (long p0 = 0; p0 < batch; p0 += chunk) {
+      const long pc = batch - p0 < chunk ? batch - p0 : chunk;
+      scat_status s3 = backward_3d(plan, in, grad_out, grad_in, p0, pc, st3);
+      if (s3 != SCAT_OK) return s3;
+    }
+    return SCAT_OK;
+  }
   if (h.dims == 1) {
     // signals are n1 x n2 matrices: n1-point column transforms, row transforms of n2 >> r
     if (plan->padded) return SCAT_ERR_ARG;
@@ -1415,9 +1551,13 @@ scat_status scat_backward(scat_plan *plan, const float *in, const float *grad_ou
 }
 
 size_t scat_plan_backward_workspace_bytes(const scat_plan *plan, long batch) {
-  if (plan == nullptr || batch <= 0 || (plan->host.dims == 1 && plan->padded) ||
-      plan->host.dims == 3)
-    return 0;
+  if (plan == nullptr || batch <= 0 || (plan->host.dims == 1 && plan->padded)) return 0;
+  if (plan->host.dims == 3) {
+    const size_t per = bytes_per_volume_3d_bwd(*plan);
+    long chunk = static_cast<long>(scratch_budget() / per);
+    if (chunk < 1) chunk = 1;
+    return per * static_cast<size_t>(chunk > batch ? batch : chunk);
+  }
   const BwdLayout bl = make_bwd_layout(*plan, batch);
   return bl.per_plane * static_cast<size_t>(bl.chunk);
 }

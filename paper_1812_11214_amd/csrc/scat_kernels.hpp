@@ -192,7 +192,12 @@ hipError_t launch3_fft(float2 *data, long volumes, int n0, int n1, int n2, bool 
 hipError_t launch3_real_to_complex(const float *x, float2 *out, long total, hipStream_t st);
 // dst[v][e] = src[v][e] * filt[e], e < n
 hipError_t launch3_mul_table(const float2 *src, const float *filt, float2 *dst, long volumes, long n,
-                             hipStream_t st);
+                             hipStream_t st, int fstride = 1, bool accumulate = false);
+// backward pass of the 3-D transform: zero-inserted output gradient, gradient through rho
+hipError_t launch3_upsample(const float *g, float2 *up, long volumes, int K, int chan, int n0, int n1,
+                            int n2, int J, hipStream_t st);
+hipError_t launch3_rho_back(const float2 *gu, const float *acc, float2 *y, long total,
+                            hipStream_t st);
 // acc[i] = |y[i]|^2 (first) or acc[i] + |y[i]|^2
 hipError_t launch3_accum_abs2(const float2 *y, float *acc, long total, bool first, hipStream_t st);
 // out[i] = (sqrt(acc[i]), 0)

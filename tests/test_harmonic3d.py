@@ -26,17 +26,18 @@ def test_bad_arguments(shape, J, L, mo, status):
     assert e.value.status == status
 
 
-def test_no_padding_oversampling_or_backward():
+def test_no_padding_or_oversampling():
     for kw in (dict(padded=True), dict(oversampling=1)):
         with pytest.raises(scat.ScatError) as e:
             scat.Scattering((8, 8, 8), 1, 1, host_only=True, **kw)
         assert e.value.status == 1
     p = scat.Scattering((8, 8, 8), 1, 1, host_only=True)
     try:
-        assert p.backward_workspace_bytes(4) == 0
-        with pytest.raises(scat.ScatError) as e:
-            scat.scat_backward(p._plan, 0, 0, 0, 0)
-        assert e.value.status == 1
+        assert p.backward_workspace_bytes(4) > p.workspace_bytes(4)
+        with pytest.raises(scat.ScatError) as e:        # host-only plan: no device
+            scat.scat_backward(p._plan, 8, 8, 8, 1)
+        assert e.value.status == 4
+        scat.scat_backward(p._plan, 0, 0, 0, 0)         # empty batch is a no-op
     finally:
         p.close()
 
@@ -208,3 +209,137 @@ def test_benchmark_workload_sampled():
     errs = per_order_errors(got[pick], want, order_of_channels(rows), x[pick])
     print("3d workload", errs, flush=True)
     assert max(errs.values()) <= TOL, errs
+
+
+# ---- backward pass ----------------------------------------------------------------------
+
+TOL_GRAD_MAX = 1e-4   # max |gpu - oracle| / max |oracle| per volume
+TOL_GRAD_L2 = 1e-5
+
+
+def _check_backward(x, J, L, max_order=2, seed=0):
+    import torch
+    shape = x.shape[-3:]
+    plan = scat.Scattering(shape, J, L, max_order)
+    try:
+        rng = np.random.default_rng(seed)
+        g = rng.standard_normal((x.shape[0], plan.K) + plan.out_shape).astype(np.float32)
+        gx = plan.backward(torch.from_numpy(x).cuda(), torch.from_numpy(g).cuda())
+        torch.cuda.synchronize()
+        got = gx.cpu().numpy().astype(np.float64)
+    finally:
+        plan.close()
+    want = o3.harmonic_scattering3d_backward(x, g, J, L, max_order)
+    P = x.shape[0]
+    d = (got - want).reshape(P, -1)
+    w = want.reshape(P, -1)
+    emax = (np.abs(d).max(axis=1) / np.abs(w).max(axis=1)).max()
+    el2 = (np.linalg.norm(d, axis=1) / np.linalg.norm(w, axis=1)).max()
+    print("3d backward", shape, J, L, max_order, "max-rel %.2e l2-rel %.2e" % (emax, el2), flush=True)
+    assert emax <= TOL_GRAD_MAX and el2 <= TOL_GRAD_L2, (emax, el2)
+    return got, want
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("shape,J,L,mo", [
+    ((8, 8, 8), 1, 1, 2), ((8, 8, 8), 2, 2, 2), ((16, 16, 16), 2, 2, 2), ((8, 16, 32), 1, 1, 2),
+    ((32, 32, 32), 2, 3, 2), ((16, 16, 16), 3, 1, 2), ((16, 32, 16), 2, 2, 1), ((4, 4, 4), 1, 0, 2),
+    ((16, 8, 64), 2, 4, 2), ((8, 64, 64), 2, 1, 2),
+])
+def test_backward_parity(shape, J, L, mo):
+    rng = np.random.default_rng(sum(shape) + 7 * J + L)
+    x = (workloads.volumes(shape, 2) + 0.2 * rng.standard_normal((2,) + shape)).astype(np.float32)
+    _check_backward(x, J, L, mo, seed=J + L)
+
+
+@pytest.mark.gpu
+def test_backward_zero_input_passes_only_the_order0_term():
+    import torch
+    shape, J, L = (8, 16, 16), 1, 2
+    x = np.zeros((2,) + shape, dtype=np.float32)
+    plan = scat.Scattering(shape, J, L)
+    try:
+        g = np.random.default_rng(3).standard_normal((2, plan.K) + plan.out_shape).astype(np.float32)
+        gx = plan.backward(torch.from_numpy(x).cuda(), torch.from_numpy(g).cuda())
+        g0 = g.copy()
+        g0[:, 1:] = 0
+        gx0 = plan.backward(torch.from_numpy(x).cuda(), torch.from_numpy(g0).cuda())
+        torch.cuda.synchronize()
+        a, b = gx.cpu().numpy(), gx0.cpu().numpy()
+    finally:
+        plan.close()
+    assert np.array_equal(a, b)
+    want = o3.harmonic_scattering3d_backward(x, g, J, L)
+    assert np.abs(a - want).max() <= 1e-5 * np.abs(want).max()
+
+
+def _smallest_l0_ratio(x, J, L, bank):
+    """min |y| / max |y| over the real-valued degree-0 filtered signals of one volume (first
+    and second order): where it is below fp32 resolution the sign of y, hence the gradient
+    of |y| at that point, is undecidable in fp32."""
+    X = np.fft.fftn(x)
+    worst = 1.0
+    for j1 in range(J):
+        y1 = np.fft.ifftn(X * bank['psi_hat'][j1][0][0])
+        a1 = np.abs(y1)
+        worst = min(worst, a1.min() / a1.max())
+        U1h = np.fft.fftn(a1)
+        for j2 in range(j1 + 1, J):
+            a2 = np.abs(np.fft.ifftn(U1h * bank['psi_hat'][j2][0][0]))
+            worst = min(worst, a2.min() / a2.max())
+    return worst
+
+
+@pytest.mark.gpu
+def test_backward_benchmark_workload_sampled():
+    """Backward pass of the 16 x 64^3 batch in one call; volumes 0, 7 and 15 against the oracle.
+
+    The degree-0 wavelet is real, so rho = |y| with y real: its gradient is sign(y) g, and
+    at a grid point where |y| is below fp32 resolution (about 1e-7 of its maximum; a 64^3
+    volume has such a point now and then) the sign is decided by rounding.  Both answers
+    are equally right there.  So: channels of degree >= 1 (and S0) are compared strictly on
+    every volume; the full gradient too, except that a volume whose degree-0 signals come
+    within 1e-6 of zero somewhere (relative to their maximum, per the oracle) may differ on
+    at most 0.1 % of its points (the wavelet's footprint around a flipped sign)."""
+    import torch
+    c = workloads.VOLUME_CONFIG
+    J, L = c["J"], c["LQ"]
+    # The densities alone vanish (to 1e-30) over most of the box; there rho ~ 0 and its
+    # gradient g y / rho is a direction that no fp32 computation can resolve (y is known to
+    # 1e-7 of its maximum).  A noise floor keeps the comparison well conditioned, as in the
+    # other backward cases.
+    noise = np.random.default_rng(99).standard_normal((c["batch"],) + tuple(c["shape"]))
+    x = (workloads.volumes(c["shape"], c["batch"]) + 0.2 * noise).astype(np.float32)
+    plan = scat.Scattering(c["shape"], J, L)
+    try:
+        rows = plan.coeff_index()
+        g = np.random.default_rng(181211214).standard_normal(
+            (c["batch"], plan.K) + plan.out_shape, dtype=np.float32)
+        keep = np.array([r[0] == 0 or r[2] >= 1 for r in rows])
+        g_hi = np.where(keep[None, :, None, None, None], g, 0).astype(np.float32)
+        xd = torch.from_numpy(x).cuda()
+        got = plan.backward(xd, torch.from_numpy(g).cuda()).cpu().numpy().astype(np.float64)
+        got_hi = plan.backward(xd, torch.from_numpy(g_hi).cuda()).cpu().numpy().astype(np.float64)
+    finally:
+        plan.close()
+    bank = o3.bank_3d(c["shape"], J, L)
+    strict = 0
+    for v in (0, 7, 15):
+        want_hi = o3.harmonic_scattering3d_backward(x[v:v + 1], g_hi[v:v + 1], J, L, bank=bank)[0]
+        e_hi = np.abs(got_hi[v] - want_hi).max() / np.abs(want_hi).max()
+        want = o3.harmonic_scattering3d_backward(x[v:v + 1], g[v:v + 1], J, L, bank=bank)[0]
+        emax = np.abs(got[v] - want).max() / np.abs(want).max()
+        el2 = np.linalg.norm(got[v] - want) / np.linalg.norm(want)
+        ratio = _smallest_l0_ratio(x[v].astype(np.float64), J, L, bank)
+        print("3d backward workload vol %d: degree>=1 max-rel %.2e; all max-rel %.2e l2-rel %.2e; "
+              "smallest |y0|/max %.1e" % (v, e_hi, emax, el2, ratio), flush=True)
+        assert e_hi <= TOL_GRAD_MAX, (v, e_hi)
+        if emax <= TOL_GRAD_MAX:
+            strict += 1
+            continue
+        # a rounding-decided sign: only allowed where the oracle shows an undecidable point,
+        # and then the damage must be local (the wavelet's footprint around that point)
+        bad = (np.abs(got[v] - want) > TOL_GRAD_MAX * np.abs(want).max()).mean()
+        assert ratio < 1e-6 and bad <= 1e-3 and el2 <= 1e-2, (v, emax, el2, ratio, bad)
+    print("3d backward workload: %d of 3 volumes within 1e-4 on all channels" % strict,
+          flush=True)
