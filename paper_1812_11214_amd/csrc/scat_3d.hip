@@ -54,6 +54,57 @@ __global__ __launch_bounds__(256) void k3_mul_table(const float2 *__restrict__ s
   }
 }
 
+// dst[v][k] (+)= phi[k] * Gs[v][chan][k mod m]: the spectrum of the zero-inserted output
+// gradient is the small spectrum Gs tiled over the grid (adjoint of lowpass + subsampling)
+__global__ __launch_bounds__(256) void k3_tile_phi(const float2 *__restrict__ Gs,
+                                                   const float *__restrict__ phi,
+                                                   float2 *__restrict__ dst, long volumes, int K,
+                                                   int chan, int n0, int n1, int n2, int J,
+                                                   int accumulate) {
+  const long per = static_cast<long>(n0) * n1 * n2;
+  const long total = volumes * per;
+  const int m0 = n0 >> J, m1 = n1 >> J, m2 = n2 >> J;
+  const long mper = static_cast<long>(m0) * m1 * m2;
+  const long stride = static_cast<long>(gridDim.x) * blockDim.x;
+  for (long i = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x; i < total; i += stride) {
+    const long v = i / per;
+    long e = i - v * per;
+    const int c = static_cast<int>(e % n2);
+    const long e1 = e / n2;
+    const int b = static_cast<int>(e1 % n1);
+    const int a = static_cast<int>(e1 / n1);
+    const float2 gs = Gs[(static_cast<size_t>(v) * K + chan) * mper +
+                         (static_cast<size_t>(a & (m0 - 1)) * m1 + (b & (m1 - 1))) * m2 + (c & (m2 - 1))];
+    const float f = phi[e];
+    float2 o = make_float2(gs.x * f, gs.y * f);
+    if (accumulate) {
+      const float2 d = dst[i];
+      o.x += d.x;
+      o.y += d.y;
+    }
+    dst[i] = o;
+  }
+}
+
+// dst[v][e] (+)= src[v][e] * c[e] (or conj(c[e])): a pair of real tables stored as one complex
+__global__ __launch_bounds__(256) void k3_mul_ctable(const float2 *__restrict__ src,
+                                                     const float2 *__restrict__ ctab,
+                                                     float2 *__restrict__ dst, long total, long n,
+                                                     int conj_table, int accumulate) {
+  const long stride = static_cast<long>(gridDim.x) * blockDim.x;
+  for (long i = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x; i < total; i += stride) {
+    float2 c = ctab[i % n];
+    if (conj_table) c.y = -c.y;
+    float2 o = c_mul(src[i], c);
+    if (accumulate) {
+      const float2 d = dst[i];
+      o.x += d.x;
+      o.y += d.y;
+    }
+    dst[i] = o;
+  }
+}
+
 // Backward pass helpers.  up[v][a 2^J][b 2^J][c 2^J] = g[v][chan][a][b][c], zero elsewhere.
 __global__ __launch_bounds__(256) void k3_upsample(const float *__restrict__ g,
                                                    float2 *__restrict__ up, long volumes, int K,
@@ -578,6 +629,27 @@ hipError_t launch3_mul_table(const float2 *src, const float *filt, float2 *dst, 
   LaunchScope obs("k3_mul_table", total * (accumulate ? 24.0 : 16.0) + n * 4.0, total * 2.0, st);
   hipLaunchKernelGGL(k3_mul_table, dim3(blocks_for(total)), dim3(256), 0, st, src, filt, fstride, dst,
                      total, n, accumulate ? 1 : 0);
+  return hipGetLastError();
+}
+
+hipError_t launch3_tile_phi(const float2 *Gs, const float *phi, float2 *dst, long volumes, int K,
+                            int chan, int n0, int n1, int n2, int J, bool accumulate, hipStream_t st) {
+  const long total = volumes * n0 * n1 * n2;
+  if (total <= 0) return hipSuccess;
+  LaunchScope obs("k3_tile_phi", total * (accumulate ? 16.0 : 8.0) + 4.0 * n0 * n1 * n2, total * 2.0,
+                  st);
+  hipLaunchKernelGGL(k3_tile_phi, dim3(blocks_for(total)), dim3(256), 0, st, Gs, phi, dst, volumes, K,
+                     chan, n0, n1, n2, J, accumulate ? 1 : 0);
+  return hipGetLastError();
+}
+
+hipError_t launch3_mul_ctable(const float2 *src, const float2 *ctab, float2 *dst, long volumes, long n,
+                              bool conj_table, bool accumulate, hipStream_t st) {
+  const long total = volumes * n;
+  if (total <= 0) return hipSuccess;
+  LaunchScope obs("k3_mul_ctable", total * (accumulate ? 24.0 : 16.0) + n * 8.0, total * 6.0, st);
+  hipLaunchKernelGGL(k3_mul_ctable, dim3(blocks_for(total)), dim3(256), 0, st, src, ctab, dst, total, n,
+                     conj_table ? 1 : 0, accumulate ? 1 : 0);
   return hipGetLastError();
 }
 

@@ -1146,7 +1146,10 @@ scat_status forward_3d(scat_plan *p, const float *in, float *out, long p0, long 
 // node at hand (and of its child) are recomputed and kept while their gradients are formed.
 size_t bytes_per_volume_3d_bwd(const scat_plan &p) {
   const size_t n = p.h3.points(), M = 2 * static_cast<size_t>(p.h3.L) + 1;
-  return n * sizeof(float2) * (5 + 2 * M) + n * sizeof(float) * 2;
+  // X^, A_X, U^, A_U, work; two sets of filtered signals; two sums of squares; the small
+  // spectra of the output gradient, all channels
+  return n * sizeof(float2) * (5 + 2 * M) + n * sizeof(float) * 2 +
+         static_cast<size_t>(p.h3.K) * (n >> (3 * p.h3.J)) * sizeof(float2);
 }
 
 scat_status backward_3d(scat_plan *p, const float *in, const float *gout, float *gin, long p0, long pc,
@@ -1161,6 +1164,7 @@ scat_status backward_3d(scat_plan *p, const float *in, const float *gout, float 
   float2 *AX = XH + tot, *UH = AX + tot, *AU = UH + tot, *Wk = AU + tot;
   float2 *W1 = Wk + tot, *W2 = W1 + static_cast<size_t>(M) * tot;
   float *acc1 = reinterpret_cast<float *>(W2 + static_cast<size_t>(M) * tot), *acc2 = acc1 + tot;
+  float2 *Gs = reinterpret_cast<float2 *>(acc2 + tot);
   const float *tab = p->d_tables;
   const float2 *tw = p->d_tw;
   const int tw_n = p->tw_n;
@@ -1179,21 +1183,31 @@ scat_status backward_3d(scat_plan *p, const float *in, const float *gout, float 
   auto fft3 = [&](float2 *d, bool inv) {
     return scat::launch3_fft(d, pc, n0, n1, n2, inv, tw, tw_n, st);
   };
-  // dst (=|+=) phi^ FFT(upsample(g[chan]))
+  // dst (=|+=) phi^ FFT(upsample(g[chan])): the spectrum of the zero-inserted gradient is
+  // the small spectrum of g tiled over the grid
   auto lowpass_adj = [&](int chan, float2 *dst, bool accumulate) -> hipError_t {
-    hipError_t e = scat::launch3_upsample(go, Wk, pc, K, chan, n0, n1, n2, J, st);
-    if (e != hipSuccess) return e;
-    e = fft3(Wk, false);
-    if (e != hipSuccess) return e;
-    return scat::launch3_mul_table(Wk, phi, dst, pc, static_cast<long>(n), st, 1, accumulate);
+    return scat::launch3_tile_phi(Gs, phi, dst, pc, K, chan, n0, n1, n2, J, accumulate, st);
   };
-  // W[m] = IFFT(Fh g_{j,l,m}), acc = sum_m |W[m]|^2
+  // member p of the pair tables of (j, l) (fused plans)
+  auto pair_table = [&](int j, int l, int pr) -> const float2 * {
+    return reinterpret_cast<const float2 *>(tab + p->psi3_off[static_cast<size_t>(j) * (L + 1) + l]) +
+           static_cast<size_t>(pr) * n;
+  };
+  // W[m] = IFFT(Fh g_{j,l,m}), acc = sum_m |W[m]|^2.  Fused plans: the tables come in pairs
+  // c = g_2p + i g_2p+1 and W[p] = IFFT(Fh c) carries both members (|W[p]|^2 is the sum of
+  // their squares, and the adjoint of the product is the product with conj(c)).
   auto filtered = [&](const float2 *Fh, int j, int l, float2 *W, float *acc) -> hipError_t {
-    for (int m = 0; m < 2 * l + 1; ++m) {
-      int fs;
-      const float *t = table(j, l, m, &fs);
+    const int cnt = p->fused3 ? l + 1 : 2 * l + 1;
+    for (int m = 0; m < cnt; ++m) {
       float2 *w = W + static_cast<size_t>(m) * tot;
-      hipError_t e = scat::launch3_mul_table(Fh, t, w, pc, static_cast<long>(n), st, fs, false);
+      hipError_t e;
+      if (p->fused3) {
+        e = scat::launch3_mul_ctable(Fh, pair_table(j, l, m), w, pc, static_cast<long>(n), false, false, st);
+      } else {
+        int fs;
+        const float *t = table(j, l, m, &fs);
+        e = scat::launch3_mul_table(Fh, t, w, pc, static_cast<long>(n), st, fs, false);
+      }
       if (e != hipSuccess) return e;
       e = fft3(w, true);
       if (e != hipSuccess) return e;
@@ -1205,19 +1219,27 @@ scat_status backward_3d(scat_plan *p, const float *in, const float *gout, float 
   // A += sum_m g_m FFT(Re(gu) W[m] / sqrt(acc)); W is overwritten
   auto rho_adj = [&](const float2 *gu, int j, int l, float2 *W, const float *acc,
                      float2 *A) -> hipError_t {
-    for (int m = 0; m < 2 * l + 1; ++m) {
-      int fs;
-      const float *t = table(j, l, m, &fs);
+    const int cnt = p->fused3 ? l + 1 : 2 * l + 1;
+    for (int m = 0; m < cnt; ++m) {
       float2 *w = W + static_cast<size_t>(m) * tot;
       hipError_t e = scat::launch3_rho_back(gu, acc, w, tot, st);
       if (e != hipSuccess) return e;
       e = fft3(w, false);
       if (e != hipSuccess) return e;
-      e = scat::launch3_mul_table(w, t, A, pc, static_cast<long>(n), st, fs, true);
+      if (p->fused3) {
+        e = scat::launch3_mul_ctable(w, pair_table(j, l, m), A, pc, static_cast<long>(n), true, true, st);
+      } else {
+        int fs;
+        const float *t = table(j, l, m, &fs);
+        e = scat::launch3_mul_table(w, t, A, pc, static_cast<long>(n), st, fs, true);
+      }
       if (e != hipSuccess) return e;
     }
     return hipSuccess;
   };
+  // small spectra of the output gradient, all channels of the chunk at once
+  SCAT_TRY(scat::launch3_real_to_complex(go, Gs, pc * K * static_cast<long>(mout), st));
+  SCAT_TRY(scat::launch3_fft(Gs, pc * K, n0 >> J, n1 >> J, n2 >> J, false, tw, tw_n, st));
   SCAT_TRY(scat::launch3_real_to_complex(x, XH, tot, st));
   SCAT_TRY(fft3(XH, false));
   SCAT_TRY(lowpass_adj(0, AX, false));

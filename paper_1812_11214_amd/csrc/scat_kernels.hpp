@@ -196,6 +196,10 @@ hipError_t launch3_mul_table(const float2 *src, const float *filt, float2 *dst, 
 // backward pass of the 3-D transform: zero-inserted output gradient, gradient through rho
 hipError_t launch3_upsample(const float *g, float2 *up, long volumes, int K, int chan, int n0, int n1,
                             int n2, int J, hipStream_t st);
+hipError_t launch3_tile_phi(const float2 *Gs, const float *phi, float2 *dst, long volumes, int K,
+                            int chan, int n0, int n1, int n2, int J, bool accumulate, hipStream_t st);
+hipError_t launch3_mul_ctable(const float2 *src, const float2 *ctab, float2 *dst, long volumes, long n,
+                              bool conj_table, bool accumulate, hipStream_t st);
 hipError_t launch3_rho_back(const float2 *gu, const float *acc, float2 *y, long total,
                             hipStream_t st);
 // acc[i] = |y[i]|^2 (first) or acc[i] + |y[i]|^2
