@@ -410,6 +410,107 @@ __global__ __launch_bounds__(256) void k3_axis0_rho(const float2 *__restrict__ W
     if (t + T * i <= N0 / 2) o[i * step] = v[i];
 }
 
+// Backward pass, axis 0 of the P signals W_p [volumes][E*T][Mc] (in place).
+// MODE 0: inverse transform of every W_p (the slab axes are already done), written back as
+//         the filtered signals y_p, and acc = sum_p |y_p|^2.
+// MODE 1: y_p <- Re(gu) y_p / sqrt(acc) (0 where acc = 0), then the forward transform.
+template <int E, int T, int MODE>
+__global__ __launch_bounds__(256) void k3_axis0_back(float2 *__restrict__ W, float *__restrict__ acc,
+                                                     const float2 *__restrict__ gu, int Mc, int TC,
+                                                     int P, size_t mstride,
+                                                     const float2 *__restrict__ tw, int tw_n) {
+  constexpr int N0 = E * T;
+  extern __shared__ float2 lds[];
+  const int KS = T * TC + (E == 32 ? 0 : 1);
+  const int c = threadIdx.x % TC, t = threadIdx.x / TC;
+  const int tiles = Mc / TC;
+  const long vol = blockIdx.x / tiles;
+  const int c0 = static_cast<int>(blockIdx.x % tiles) * TC;
+  const size_t off = static_cast<size_t>(vol) * N0 * Mc + static_cast<size_t>(t) * Mc + c0 + c;
+  const size_t step = static_cast<size_t>(T) * Mc;
+  float2 wt[E];
+  load_twiddles<E, T>(wt, t, tw, tw_n);
+  float a[E];
+#pragma unroll
+  for (int i = 0; i < E; ++i) {
+    if (MODE == 0) {
+      a[i] = 0.f;
+    } else {
+      const float s2 = acc[off + i * step];
+      a[i] = s2 > 0.f ? gu[off + i * step].x / __builtin_amdgcn_sqrtf(s2) : 0.f;
+    }
+  }
+  for (int p = 0; p < P; ++p) {
+    float2 *w = W + static_cast<size_t>(p) * mstride + off;
+    float2 v[E];
+#pragma unroll
+    for (int i = 0; i < E; ++i) v[i] = w[i * step];
+    if (MODE == 0) {
+      fft_core<E, T, true, false>(v, t, lds + c, KS, TC, wt);
+#pragma unroll
+      for (int i = 0; i < E; ++i) a[i] += v[i].x * v[i].x + v[i].y * v[i].y;
+    } else {
+#pragma unroll
+      for (int i = 0; i < E; ++i) v[i] = make_float2(v[i].x * a[i], v[i].y * a[i]);
+      fft_core<E, T, false, false>(v, t, lds + c, KS, TC, wt);
+    }
+#pragma unroll
+    for (int i = 0; i < E; ++i) w[i * step] = v[i];
+  }
+  if (MODE == 0) {
+#pragma unroll
+    for (int i = 0; i < E; ++i) acc[off + i * step] = a[i];
+  }
+}
+
+// Backward pass, slab axes: A[slab] += sum_p conj(c_p) * (forward slab transform of W_p), the
+// adjoint of k3_slab_mul_inv (c_p = the pair tables of the node); A's slab is read and
+// written once for all p.
+template <int N1, int N2>
+__global__ __launch_bounds__((Slab<N1, N2>::NT)) void k3_slab_fwd_mulacc(
+    const float2 *__restrict__ W, const float2 *__restrict__ tab, float2 *__restrict__ A, long slabs,
+    int n0, int P, size_t mstride, const float2 *__restrict__ tw, int tw_n) {
+  using S = Slab<N1, N2>;
+  extern __shared__ float2 lds[];
+  const int s = threadIdx.x / S::TS, q = threadIdx.x % S::TS;
+  const long slab = static_cast<long>(blockIdx.x) * S::SPW + s;
+  const bool live = slab < slabs;
+  const long sl = live ? slab : slabs - 1;
+  float2 *area = lds + s * N1 * S::RS;
+  const int r = q / S::T2, t = q % S::T2;
+  const int c = q % N2, t1 = q / N2;
+  const int k0 = static_cast<int>(sl % n0);
+  const size_t base = static_cast<size_t>(sl) * N1 * N2;
+  float2 sum[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) sum[i] = make_float2(0.f, 0.f);
+  for (int p = 0; p < P; ++p) {
+    const float2 *src = W + static_cast<size_t>(p) * mstride + base + r * N2 + t;
+    float2 v[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) v[i] = src[S::T2 * i];
+    S::template transform<false>(v, area, r, t, c, t1, tw, tw_n);
+    const float2 *tb = tab + (static_cast<size_t>(p) * n0 + k0) * N1 * N2 + c;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      float2 g = tb[(t1 + S::T1 * i) * N2];
+      g.y = -g.y;
+      const float2 o = c_mul(v[i], g);
+      sum[i].x += o.x;
+      sum[i].y += o.y;
+    }
+    __syncthreads();  // the slab area is reused by the next signal
+  }
+  if (!live) return;
+  float2 *dst = A + base + c;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    float2 *d = dst + (t1 + S::T1 * i) * N2;
+    const float2 old = *d;
+    *d = make_float2(old.x + sum[i].x, old.y + sum[i].y);
+  }
+}
+
 // Q[g][a0][e] = sum_p P[g][a0 + m0 p][e]: g over volumes x channels, e over the m1*m2
 // folded slab points
 __global__ __launch_bounds__(256) void k3_fold0(const float2 *__restrict__ P,
@@ -513,6 +614,54 @@ hipError_t axis0_t(const float2 *W, const float *xreal, float2 *dst, long volume
   return hipGetLastError();
 }
 
+template <int E, int T>
+hipError_t axis0_back_t(int mode, float2 *W, float *acc, const float2 *gu, long volumes, int Mc, int P,
+                        const float2 *tw, int tw_n, hipStream_t st) {
+  int TC = 256 / T;
+  if (TC > Mc) TC = Mc;
+  const long blocks = volumes * (Mc / TC);
+  if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
+  const size_t lds =
+      T == 1 ? 0 : static_cast<size_t>(E) * (T * TC + (E == 32 ? 0 : 1)) * sizeof(float2);
+  const std::string name = "k3_axis0_back<" + std::to_string(E) + ", " + std::to_string(T) + ", " +
+                           (mode ? "1>" : "0>");
+  const double pts = static_cast<double>(volumes) * E * T * Mc;
+  LaunchScope obs(name.c_str(), pts * (16.0 * P + (mode ? 12.0 : 4.0)),
+                  pts * P * (5.0 * ilog2h(E * T) + 4.0), st);
+  const size_t mstride = static_cast<size_t>(volumes) * E * T * Mc;
+  if (mode == 0)
+    hipLaunchKernelGGL((k3_axis0_back<E, T, 0>), dim3(static_cast<unsigned>(blocks)), dim3(T * TC), lds,
+                       st, W, acc, gu, Mc, TC, P, mstride, tw, tw_n);
+  else
+    hipLaunchKernelGGL((k3_axis0_back<E, T, 1>), dim3(static_cast<unsigned>(blocks)), dim3(T * TC), lds,
+                       st, W, acc, gu, Mc, TC, P, mstride, tw, tw_n);
+  return hipGetLastError();
+}
+
+template <int N1, int N2>
+hipError_t slab_fwd_mulacc_t(const float2 *W, const float2 *tab, float2 *A, long volumes, int n0, int P,
+                             const float2 *tw, int tw_n, hipStream_t st) {
+  using S = Slab<N1, N2>;
+  const long slabs = volumes * n0;
+  const long blocks = (slabs + S::SPW - 1) / S::SPW;
+  if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
+  const std::string name =
+      "k3_slab_fwd_mulacc<" + std::to_string(N1) + ", " + std::to_string(N2) + ">";
+  const double pts = static_cast<double>(slabs) * N1 * N2;
+  LaunchScope obs(name.c_str(), pts * 8.0 * (P + 2) + 8.0 * P * n0 * N1 * N2,
+                  pts * P * (5.0 * (ilog2h(N1) + ilog2h(N2)) + 8.0), st);
+  if (S::lds_bytes > 65536) {
+    static unsigned long long lds_ok = 0;
+    hipError_t e =
+        allow_large_lds(reinterpret_cast<const void *>(k3_slab_fwd_mulacc<N1, N2>), lds_ok);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL((k3_slab_fwd_mulacc<N1, N2>), dim3(static_cast<unsigned>(blocks)), dim3(S::NT),
+                     S::lds_bytes, st, W, tab, A, slabs, n0, P, static_cast<size_t>(slabs) * N1 * N2,
+                     tw, tw_n);
+  return hipGetLastError();
+}
+
 }  // namespace
 
 bool fused3_supported(int n0, int n1, int n2, int J) {
@@ -587,6 +736,36 @@ hipError_t launch3_axis0_rho(const float2 *W, const float *xreal, float2 *dst, l
     default: return hipErrorInvalidValue;
   }
 #undef SCAT3_B
+}
+
+hipError_t launch3_axis0_back(int mode, float2 *W, float *acc, const float2 *gu, long volumes, int n0,
+                              int Mc, int P, const float2 *tw, int tw_n, hipStream_t st) {
+  if (volumes <= 0 || P <= 0) return hipSuccess;
+  if (tw_n % n0 != 0 || Mc < 256 || (Mc & (Mc - 1)) != 0 || acc == nullptr ||
+      (mode != 0 && gu == nullptr))
+    return hipErrorInvalidValue;
+#define SCAT3_AB(E_, T_) return axis0_back_t<E_, T_>(mode, W, acc, gu, volumes, Mc, P, tw, tw_n, st)
+  switch (n0) {
+    case 4: SCAT3_AB(4, 1);
+    case 8: SCAT3_AB(8, 1);
+    case 16: SCAT3_AB(16, 1);
+    case 32: SCAT3_AB(16, 2);
+    case 64: SCAT3_AB(16, 4);
+    case 128: SCAT3_AB(16, 8);
+    case 256: SCAT3_AB(16, 16);
+    default: return hipErrorInvalidValue;
+  }
+#undef SCAT3_AB
+}
+
+hipError_t launch3_slab_fwd_mulacc(const float2 *W, const float2 *tab, float2 *A, long volumes, int n0,
+                                   int n1, int n2, int P, const float2 *tw, int tw_n,
+                                   hipStream_t st) {
+  if (volumes <= 0 || P <= 0) return hipSuccess;
+  if (tw_n % n1 != 0 || tw_n % n2 != 0) return hipErrorInvalidValue;
+#define SCAT3_D(A_, B_) return slab_fwd_mulacc_t<A_, B_>(W, tab, A, volumes, n0, P, tw, tw_n, st)
+  SCAT3_SLAB_DISPATCH(SCAT3_D)
+#undef SCAT3_D
 }
 
 hipError_t launch3_fold0(const float2 *P, float2 *Q, long groups, int n0, int m0, int slab,

@@ -1197,6 +1197,13 @@ scat_status backward_3d(scat_plan *p, const float *in, const float *gout, float 
   // c = g_2p + i g_2p+1 and W[p] = IFFT(Fh c) carries both members (|W[p]|^2 is the sum of
   // their squares, and the adjoint of the product is the product with conj(c)).
   auto filtered = [&](const float2 *Fh, int j, int l, float2 *W, float *acc) -> hipError_t {
+    if (p->fused3) {
+      // every pair of the node at once: product + inverse slab transform, then axis 0
+      hipError_t e = scat::launch3_slab_mul_inv(Fh, pair_table(j, l, 0), W, pc, n0, n1, n2, l + 1, tw,
+                                                tw_n, st);
+      if (e != hipSuccess) return e;
+      return scat::launch3_axis0_back(0, W, acc, nullptr, pc, n0, n1 * n2, l + 1, tw, tw_n, st);
+    }
     const int cnt = p->fused3 ? l + 1 : 2 * l + 1;
     for (int m = 0; m < cnt; ++m) {
       float2 *w = W + static_cast<size_t>(m) * tot;
@@ -1219,6 +1226,13 @@ scat_status backward_3d(scat_plan *p, const float *in, const float *gout, float 
   // A += sum_m g_m FFT(Re(gu) W[m] / sqrt(acc)); W is overwritten
   auto rho_adj = [&](const float2 *gu, int j, int l, float2 *W, const float *acc,
                      float2 *A) -> hipError_t {
+    if (p->fused3) {
+      hipError_t e = scat::launch3_axis0_back(1, W, const_cast<float *>(acc), gu, pc, n0, n1 * n2,
+                                              l + 1, tw, tw_n, st);
+      if (e != hipSuccess) return e;
+      return scat::launch3_slab_fwd_mulacc(W, pair_table(j, l, 0), A, pc, n0, n1, n2, l + 1, tw, tw_n,
+                                           st);
+    }
     const int cnt = p->fused3 ? l + 1 : 2 * l + 1;
     for (int m = 0; m < cnt; ++m) {
       float2 *w = W + static_cast<size_t>(m) * tot;

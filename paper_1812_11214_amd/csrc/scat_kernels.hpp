@@ -200,6 +200,13 @@ hipError_t launch3_tile_phi(const float2 *Gs, const float *phi, float2 *dst, lon
                             int chan, int n0, int n1, int n2, int J, bool accumulate, hipStream_t st);
 hipError_t launch3_mul_ctable(const float2 *src, const float2 *ctab, float2 *dst, long volumes, long n,
                               bool conj_table, bool accumulate, hipStream_t st);
+// fused backward passes (plans whose slabs fit a workgroup): axis 0 of the P pair signals in
+// place (mode 0: inverse transform + sum of squared moduli; mode 1: gradient through rho +
+// forward transform), and the adjoint of launch3_slab_mul_inv accumulated into A
+hipError_t launch3_axis0_back(int mode, float2 *W, float *acc, const float2 *gu, long volumes, int n0,
+                              int Mc, int P, const float2 *tw, int tw_n, hipStream_t st);
+hipError_t launch3_slab_fwd_mulacc(const float2 *W, const float2 *tab, float2 *A, long volumes, int n0,
+                                   int n1, int n2, int P, const float2 *tw, int tw_n, hipStream_t st);
 hipError_t launch3_rho_back(const float2 *gu, const float *acc, float2 *y, long total,
                             hipStream_t st);
 // acc[i] = |y[i]|^2 (first) or acc[i] + |y[i]|^2
