@@ -245,6 +245,8 @@ def _check_backward(x, J, L, max_order=2, seed=0):
     ((8, 8, 8), 1, 1, 2), ((8, 8, 8), 2, 2, 2), ((16, 16, 16), 2, 2, 2), ((8, 16, 32), 1, 1, 2),
     ((32, 32, 32), 2, 3, 2), ((16, 16, 16), 3, 1, 2), ((16, 32, 16), 2, 2, 1), ((4, 4, 4), 1, 0, 2),
     ((16, 8, 64), 2, 4, 2), ((8, 64, 64), 2, 1, 2),
+    # slabs of 8192 and 16384 points, and one that takes the general schedule
+    ((8, 64, 128), 2, 1, 2), ((4, 128, 128), 2, 2, 2), ((4, 256, 32), 1, 1, 2), ((4, 256, 64), 2, 1, 2),
 ])
 def test_backward_parity(shape, J, L, mo):
     rng = np.random.default_rng(sum(shape) + 7 * J + L)
