@@ -109,16 +109,17 @@ def coeff_index_3d(J, L, max_order=2):
     return rows
 
 
-def harmonic_scattering3d(x, J, L, max_order=2, bank=None):
+def harmonic_scattering3d(x, J, L, max_order=2, bank=None, oversampling=0):
     """x: (..., N0, N1, N2) real, sides multiples of 2^J.
-    Returns (..., K, N0 >> J, N1 >> J, N2 >> J)."""
+    Returns (..., K, N0 >> J, N1 >> J, N2 >> J).  oversampling = o: the outputs are read at
+    the samples 2^max(J-o, 0) n instead (nothing else is subsampled in this transform)."""
     x = np.asarray(x, dtype=np.float64)
     shape = x.shape[-3:]
     if bank is None:
         bank = bank_3d(shape, J, L)
     psi_hat, phi_hat = bank['psi_hat'], bank['phi_hat']
     ax = (-3, -2, -1)
-    s = 1 << J
+    s = 1 << max(J - oversampling, 0)
     lead = x.shape[:-3]
 
     def rho(Fh, wav_hat):
@@ -145,7 +146,23 @@ def harmonic_scattering3d(x, J, L, max_order=2, bank=None):
     return np.stack(out, axis=len(lead))
 
 
-def harmonic_scattering3d_backward(x, g, J, L, max_order=2, bank=None):
+def harmonic_scattering3d_padded(x, J, L, max_order=2, oversampling=0):
+    """Volumes of any size (the reading taken for signals that are not periodic powers of
+    two, as for the 2-D transform): symmetric extension to the periodic grid of
+    ``padded_size`` per axis, the periodic transform there, and the output samples that lie
+    inside the volume, ceil(N / 2^max(J-o,0)) per axis."""
+    from .scattering import pad_index, padded_size
+    x = np.asarray(x, dtype=np.float64)
+    n = x.shape[-3:]
+    P = [padded_size(k, J) for k in n]
+    xp = x[..., pad_index(n[0], P[0]), :, :][..., :, pad_index(n[1], P[1]), :][..., pad_index(n[2], P[2])]
+    y = harmonic_scattering3d(xp, J, L, max_order, oversampling=oversampling)
+    st = 1 << max(J - oversampling, 0)
+    o = [-(-k // st) for k in n]
+    return y[..., :o[0], :o[1], :o[2]]
+
+
+def harmonic_scattering3d_backward(x, g, J, L, max_order=2, bank=None, oversampling=0):
     """Gradient of sum(g * harmonic_scattering3d(x)) with respect to x (the paper lists
     differentiability as a feature, section 3, and prints no gradient): the adjoint chain of
     the transform above.  x: (..., N0, N1, N2) real; g: the shape of the transform's output.
@@ -161,7 +178,7 @@ def harmonic_scattering3d_backward(x, g, J, L, max_order=2, bank=None):
         bank = bank_3d(shape, J, L)
     psi_hat, phi_hat = bank['psi_hat'], bank['phi_hat']
     ax = (-3, -2, -1)
-    s = 1 << J
+    s = 1 << max(J - oversampling, 0)
     lead = x.shape[:-3]
     nl = len(lead)
 

@@ -145,3 +145,39 @@ def test_translation_by_the_sampling_step():
     a = h3.harmonic_scattering3d(x, J, L, bank=bank)
     b = h3.harmonic_scattering3d(np.roll(x, 2, axis=1), J, L, bank=bank)
     assert np.abs(b - np.roll(a, 1, axis=2)).max() <= 1e-12 * np.abs(a).max()
+
+
+def test_oversampled_output_contains_the_default_one():
+    """With oversampling o the outputs are read on a grid 2^o times finer; every 2^o-th
+    sample of it is the default output, and o >= J gives the lowpassed signals in full."""
+    rng = np.random.default_rng(8)
+    shape, J, L = (8, 16, 8), 2, 1
+    x = rng.standard_normal((2,) + shape)
+    bank = h3.bank_3d(shape, J, L)
+    base = h3.harmonic_scattering3d(x, J, L, bank=bank)
+    for o in (1, 2, 5):
+        y = h3.harmonic_scattering3d(x, J, L, bank=bank, oversampling=o)
+        st = 1 << min(o, J)
+        assert y.shape[-3:] == tuple(s >> (J - min(o, J)) for s in shape)
+        assert np.array_equal(y[..., ::st, ::st, ::st], base)
+
+
+def test_padded_volume_extension_sizes_and_constant():
+    from oracle.scattering import padded_size
+    rng = np.random.default_rng(9)
+    x = rng.standard_normal((1, 5, 7, 6))
+    J, L = 1, 1
+    y = h3.harmonic_scattering3d_padded(x, J, L)
+    assert y.shape == (1, 1 + J * (L + 1), 3, 4, 3)
+    # same as transforming numpy's symmetric pad rolled so that the volume starts at 0
+    P = [padded_size(k, J) for k in (5, 7, 6)]
+    xp = x
+    for axis, (k, Pk) in enumerate(zip((5, 7, 6), P)):
+        h = (Pk - k + 1) // 2
+        xp = np.roll(np.pad(xp, [(0, 0)] * (axis + 1) + [(Pk - k - h, h)] + [(0, 0)] * (2 - axis),
+                            mode='symmetric'), -(Pk - k - h), axis=axis + 1)
+    want = h3.harmonic_scattering3d(xp, J, L)[..., :3, :4, :3]
+    assert np.abs(y - want).max() <= 1e-13
+    # a constant volume stays constant under the symmetric extension: S0 equals it
+    c = h3.harmonic_scattering3d_padded(np.full((1, 5, 7, 6), 1.5), J, L)
+    assert np.abs(c[:, 0] - 1.5).max() <= 1e-12
