@@ -73,8 +73,10 @@ typedef enum {
  * standard deviation 2^J, both sampled at the integers and periodised; every convolution is
  * evaluated on the full grid and the lowpassed result read at the samples 2^J n.  Since rho
  * does not depend on the orthonormal basis of the degree-l harmonics, the tables hold the
- * real harmonics.  No padded plans or oversampling in 3-D (SCAT_ERR_ARG); scat_backward works
- * on every 3-D plan.
+ * real harmonics.  scat_plan_create_padded / SCAT_PLAN_PADDED: volumes of any size up to
+ * 256 - 2^J per side, extended symmetrically as described below (SCAT_ERR_SHAPE beyond).
+ * Oversampling o: only the output grid changes, the samples 2^max(J-o,0) n.  scat_backward
+ * works on every 3-D plan that is not padded.
  *
  * On success *out_plan is a new plan the caller must release with scat_plan_destroy.
  * On failure *out_plan is NULL and nothing is leaked.
@@ -169,7 +171,7 @@ scat_status scat_forward(scat_plan *plan, const float *in, float *out, long batc
  * 3-D plans: rho = sqrt(sum_m |y_m|^2) passes g y_m / rho to y_m (nothing where rho = 0); the
  * degree-0 signal y is real, so there the factor is sign(y), decided by rounding where |y| is
  * below fp32 resolution.
- * Errors: SCAT_ERR_ARG for a padded 1-D plan or batch < 0.  SCAT_ERR_SHAPE, 2-D: unless every
+ * Errors: SCAT_ERR_ARG for a padded 1-D or 3-D plan or batch < 0.  SCAT_ERR_SHAPE, 2-D: unless every
  * side and every side subsampled for the last octave lies in 4...512 and the output grid
  * has at most 1024 points; 1-D: unless the signal, seen as the n1 x n2 matrix of the
  * four-step transform (n2 = 2^max(ceil(log2(n)/2), J), n1 = n / n2), has n1 in 4...512 and

@@ -668,7 +668,7 @@ bool fused3_supported(int n0, int n1, int n2, int J) {
   auto p2 = [](int v) { return v > 0 && (v & (v - 1)) == 0; };
   // slabs of up to 16384 points, except 256 x 64 whose padded rows exceed the LDS of a CU
   return p2(n0) && p2(n1) && p2(n2) && n0 >= 4 && n0 <= 256 && n1 >= 16 && n2 >= 16 &&
-         n1 * n2 <= 16384 && !(n1 == 256 && n2 == 64) && J >= 1 && J <= 4 && (n1 >> J) >= 1 &&
+         n1 * n2 <= 16384 && !(n1 == 256 && n2 == 64) && J >= 0 && J <= 4 && (n1 >> J) >= 1 &&
          (n2 >> J) >= 1;
 }
 
@@ -711,7 +711,7 @@ hipError_t launch3_slab_fwd_low(const float2 *Tin, float2 *Uout, const float *ph
                                 long volumes, int n0, int n1, int n2, int J, int K, int chan,
                                 const float2 *tw, int tw_n, hipStream_t st) {
   if (volumes <= 0) return hipSuccess;
-  if (tw_n % n1 != 0 || tw_n % n2 != 0 || J < 1 || J > 4 || (n1 >> J) < 1 || (n2 >> J) < 1)
+  if (tw_n % n1 != 0 || tw_n % n2 != 0 || J < 0 || J > 4 || (n1 >> J) < 1 || (n2 >> J) < 1)
     return hipErrorInvalidValue;
 #define SCAT3_C(A_, B_) \
   return slab_fwd_low_t<A_, B_>(Tin, Uout, phi, P, volumes, n0, J, K, chan, tw, tw_n, st)

@@ -109,6 +109,8 @@ struct scat_plan {
   std::vector<size_t> psi3_off;  // per (j, l): its 2l+1 tables, contiguous
   size_t phi3_off = 0;
   bool fused3 = false;  // 3-D: slabs of the two fast axes fit a workgroup (fused passes)
+  int user_shape3[3] = {0, 0, 0};  // padded 3-D plans: the caller's volume and output sides
+  int user_out3[3] = {0, 0, 0};
   // signals of any size: the caller's shape, symmetrically extended to the plan's periodic
   // grid before the transform; the output is cropped to user_out
   bool padded = false;
@@ -162,6 +164,13 @@ Layout make_layout(const scat_plan &p, long batch) {
   const scat::HostPlan &h = p.host;
   if (h.dims == 3) {
     L.per_plane = bytes_per_volume_3d(p);
+    if (p.padded) {
+      // extended input and uncropped output behind the transform's buffers
+      L.pad_in = p.h3.points() * sizeof(float);
+      L.pad_out = static_cast<size_t>(h.K) * (p.h3.points() >> (3 * p.h3.out_shift())) * sizeof(float);
+      L.xh = L.per_plane;  // offset of those two per volume
+      L.per_plane += L.pad_in + L.pad_out;
+    }
     long c = static_cast<long>(scratch_budget() / L.per_plane);
     if (c < 1) c = 1;
     L.chunk = c > batch ? batch : c;
@@ -333,9 +342,21 @@ scat_status upload(scat_plan *p) {
 scat_status upload_3d(scat_plan *p);
 
 // 3-D solid harmonic plan: LQ is the largest degree L (degrees 0 .. L).
-scat_status create_3d(scat_plan **out_plan, const int *shape, int J, int L, int max_order,
+scat_status create_3d(scat_plan **out_plan, const int *user_shape, int J, int L, int max_order,
                       bool device, bool padded, int oversampling) {
-  if (padded || oversampling != 0) return SCAT_ERR_ARG;
+  int grid[3];
+  const int *shape = user_shape;
+  if (padded) {
+    // periodic grid: smallest power of two >= n + 2^J per axis
+    if (J < 1 || J > 8) return SCAT_ERR_ARG;
+    for (int d = 0; d < 3; ++d) {
+      if (user_shape[d] < 1 || user_shape[d] > 256) return SCAT_ERR_SHAPE;
+      int g = 1;
+      while (g < user_shape[d] + (1 << J)) g *= 2;
+      grid[d] = g;
+    }
+    shape = grid;
+  }
   int v = scat::validate_3d(shape, J, L, max_order);
   if (v != 0) return static_cast<scat_status>(v);
   scat_plan *p = new (std::nothrow) scat_plan;
@@ -346,12 +367,22 @@ scat_status create_3d(scat_plan **out_plan, const int *shape, int J, int L, int 
     delete p;
     return SCAT_ERR_ALLOC;
   }
+  p->h3.oversampling = oversampling;
   p->host.dims = 3;
   p->host.J = J;
   p->host.LQ = L;
   p->host.max_order = max_order;
   p->host.K = p->h3.K;
-  p->fused3 = scat::fused3_supported(shape[0], shape[1], shape[2], J);
+  p->host.oversampling = oversampling;
+  const int Jo = p->h3.out_shift();
+  p->fused3 = scat::fused3_supported(shape[0], shape[1], shape[2], Jo);
+  if (padded) {
+    p->padded = true;
+    for (int d = 0; d < 3; ++d) {
+      p->user_shape3[d] = user_shape[d];
+      p->user_out3[d] = (user_shape[d] + (1 << Jo) - 1) >> Jo;
+    }
+  }
   if (device) {
     scat_status s;
     try {
@@ -464,6 +495,42 @@ __global__ __launch_bounds__(256) void k_pad_symmetric(const float *__restrict__
     const int r = static_cast<int>(t % P_r);
     const long p = t / P_r;
     out[i] = in[(p * n_r + pad_source(r, n_r, P_r)) * n_c + pad_source(c, n_c, P_c)];
+  }
+}
+
+// 3-D versions of the symmetric extension and of the crop
+__global__ __launch_bounds__(256) void k_pad_symmetric3(const float *__restrict__ in,
+                                                        float *__restrict__ out, long volumes, int u0,
+                                                        int u1, int u2, int P0, int P1, int P2) {
+  const long per = static_cast<long>(P0) * P1 * P2;
+  const long total = volumes * per;
+  const long stride = static_cast<long>(gridDim.x) * blockDim.x;
+  for (long i = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x; i < total; i += stride) {
+    const long v = i / per;
+    long e = i - v * per;
+    const int c = static_cast<int>(e % P2);
+    e /= P2;
+    const int b = static_cast<int>(e % P1);
+    const int a = static_cast<int>(e / P1);
+    out[i] = in[((v * u0 + pad_source(a, u0, P0)) * u1 + pad_source(b, u1, P1)) * u2 +
+                pad_source(c, u2, P2)];
+  }
+}
+
+__global__ __launch_bounds__(256) void k_crop3(const float *__restrict__ in, float *__restrict__ out,
+                                               long maps, int m0, int m1, int m2, int o0, int o1,
+                                               int o2) {
+  const long per = static_cast<long>(o0) * o1 * o2;
+  const long total = maps * per;
+  const long stride = static_cast<long>(gridDim.x) * blockDim.x;
+  for (long i = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x; i < total; i += stride) {
+    const long g = i / per;
+    long e = i - g * per;
+    const int c = static_cast<int>(e % o2);
+    e /= o2;
+    const int b = static_cast<int>(e % o1);
+    const int a = static_cast<int>(e / o1);
+    out[i] = in[((g * m0 + a) * m1 + b) * m2 + c];
   }
 }
 
@@ -1025,8 +1092,9 @@ size_t bytes_per_volume_3d(const scat_plan &p) {
   const size_t n = h.points();
   if (!p.fused3)
     return n * sizeof(float2) * (p.host.max_order == 2 && p.host.J >= 2 ? 4 : 3) + n * sizeof(float);
-  const size_t folded12 = static_cast<size_t>(h.shape[0]) * (h.shape[1] >> h.J) * (h.shape[2] >> h.J);
-  return (n * (3 + h.L + 1) + static_cast<size_t>(h.K) * (folded12 + (n >> (3 * h.J)))) *
+  const int Jo = h.out_shift();
+  const size_t folded12 = static_cast<size_t>(h.shape[0]) * (h.shape[1] >> Jo) * (h.shape[2] >> Jo);
+  return (n * (3 + h.L + 1) + static_cast<size_t>(h.K) * (folded12 + (n >> (3 * Jo)))) *
          sizeof(float2);
 }
 
@@ -1035,10 +1103,11 @@ scat_status forward_3d_fused(scat_plan *p, const float *in, float *out, long p0,
   const scat::HostPlan3D &h = p->h3;
   const int n0 = h.shape[0], n1 = h.shape[1], n2 = h.shape[2];
   const int J = h.J, L = h.L, K = h.K;
+  const int Jo = h.out_shift();  // the outputs are read at the samples 2^Jo n
   const size_t n = h.points();
   const size_t tot = static_cast<size_t>(pc) * n;
   const bool second = h.max_order == 2 && J >= 2;
-  const int m0 = n0 >> J, m1 = n1 >> J, m2 = n2 >> J;
+  const int m0 = n0 >> Jo, m1 = n1 >> Jo, m2 = n2 >> Jo;
   float2 *XH = static_cast<float2 *>(p->d_scratch);
   float2 *UH = XH + tot;
   float2 *T = UH + tot;
@@ -1061,10 +1130,10 @@ scat_status forward_3d_fused(scat_plan *p, const float *in, float *out, long p0,
     if (e != hipSuccess) return e;
     e = scat::launch3_axis0_rho(W, nullptr, T, pc, n0, n1 * n2, l + 1, tw, tw_n, st);
     if (e != hipSuccess) return e;
-    return scat::launch3_slab_fwd_low(T, dst, phi, P, pc, n0, n1, n2, J, K, c, tw, tw_n, st);
+    return scat::launch3_slab_fwd_low(T, dst, phi, P, pc, n0, n1, n2, Jo, K, c, tw, tw_n, st);
   };
   SCAT_TRY(scat::launch3_axis0_rho(nullptr, x, T, pc, n0, n1 * n2, 0, tw, tw_n, st));
-  SCAT_TRY(scat::launch3_slab_fwd_low(T, XH, phi, P, pc, n0, n1, n2, J, K, 0, tw, tw_n, st));
+  SCAT_TRY(scat::launch3_slab_fwd_low(T, XH, phi, P, pc, n0, n1, n2, Jo, K, 0, tw, tw_n, st));
   int c1 = 1, c2 = 1 + J * (L + 1);
   for (int j1 = 0; j1 < J; ++j1)
     for (int l = 0; l <= L; ++l) {
@@ -1084,6 +1153,7 @@ scat_status forward_3d(scat_plan *p, const float *in, float *out, long p0, long 
   const scat::HostPlan3D &h = p->h3;
   const int n0 = h.shape[0], n1 = h.shape[1], n2 = h.shape[2];
   const int J = h.J, L = h.L, K = h.K;
+  const int Jo = h.out_shift();  // the outputs are read at the samples 2^Jo n
   const size_t n = h.points();
   const long tot = pc * static_cast<long>(n);
   const bool second = h.max_order == 2 && J >= 2;
@@ -1096,7 +1166,7 @@ scat_status forward_3d(scat_plan *p, const float *in, float *out, long p0, long 
   const float2 *tw = p->d_tw;
   const int tw_n = p->tw_n;
   const float *x = in + static_cast<size_t>(p0) * n;
-  const size_t mout = static_cast<size_t>(n0 >> J) * (n1 >> J) * (n2 >> J);
+  const size_t mout = static_cast<size_t>(n0 >> Jo) * (n1 >> Jo) * (n2 >> Jo);
   float *o = out + static_cast<size_t>(p0) * K * mout;
   // lowpass of the signal with spectrum Fh, read at the samples 2^J n, to channel c
   auto lowpass = [&](const float2 *Fh, int c) -> hipError_t {
@@ -1104,7 +1174,7 @@ scat_status forward_3d(scat_plan *p, const float *in, float *out, long p0, long 
     if (e != hipSuccess) return e;
     e = scat::launch3_fft(Wk, pc, n0, n1, n2, true, tw, tw_n, st);
     if (e != hipSuccess) return e;
-    return scat::launch3_sample(Wk, o, pc, K, c, n0, n1, n2, J, st);
+    return scat::launch3_sample(Wk, o, pc, K, c, n0, n1, n2, Jo, st);
   };
   // dst^ = FFT3( sqrt( sum_m |IFFT3(Fh psi_{j,l,m})|^2 ) )
   auto rho = [&](const float2 *Fh, int j, int l, float2 *dst) -> hipError_t {
@@ -1149,7 +1219,7 @@ size_t bytes_per_volume_3d_bwd(const scat_plan &p) {
   // X^, A_X, U^, A_U, work; two sets of filtered signals; two sums of squares; the small
   // spectra of the output gradient, all channels
   return n * sizeof(float2) * (5 + 2 * M) + n * sizeof(float) * 2 +
-         static_cast<size_t>(p.h3.K) * (n >> (3 * p.h3.J)) * sizeof(float2);
+         static_cast<size_t>(p.h3.K) * (n >> (3 * p.h3.out_shift())) * sizeof(float2);
 }
 
 scat_status backward_3d(scat_plan *p, const float *in, const float *gout, float *gin, long p0, long pc,
@@ -1157,6 +1227,7 @@ scat_status backward_3d(scat_plan *p, const float *in, const float *gout, float 
   const scat::HostPlan3D &h = p->h3;
   const int n0 = h.shape[0], n1 = h.shape[1], n2 = h.shape[2];
   const int J = h.J, L = h.L, K = h.K, M = 2 * L + 1;
+  const int Jo = h.out_shift();  // the outputs were read at the samples 2^Jo n
   const size_t n = h.points();
   const long tot = pc * static_cast<long>(n);
   const bool second = h.max_order == 2 && J >= 2;
@@ -1169,7 +1240,7 @@ scat_status backward_3d(scat_plan *p, const float *in, const float *gout, float 
   const float2 *tw = p->d_tw;
   const int tw_n = p->tw_n;
   const float *x = in + static_cast<size_t>(p0) * n;
-  const size_t mout = static_cast<size_t>(n0 >> J) * (n1 >> J) * (n2 >> J);
+  const size_t mout = static_cast<size_t>(n0 >> Jo) * (n1 >> Jo) * (n2 >> Jo);
   const float *go = gout + static_cast<size_t>(p0) * K * mout;
   float *gi = gin + static_cast<size_t>(p0) * n;
   const float *phi = tab + p->phi3_off;
@@ -1186,7 +1257,7 @@ scat_status backward_3d(scat_plan *p, const float *in, const float *gout, float 
   // dst (=|+=) phi^ FFT(upsample(g[chan])): the spectrum of the zero-inserted gradient is
   // the small spectrum of g tiled over the grid
   auto lowpass_adj = [&](int chan, float2 *dst, bool accumulate) -> hipError_t {
-    return scat::launch3_tile_phi(Gs, phi, dst, pc, K, chan, n0, n1, n2, J, accumulate, st);
+    return scat::launch3_tile_phi(Gs, phi, dst, pc, K, chan, n0, n1, n2, Jo, accumulate, st);
   };
   // member p of the pair tables of (j, l) (fused plans)
   auto pair_table = [&](int j, int l, int pr) -> const float2 * {
@@ -1253,7 +1324,7 @@ scat_status backward_3d(scat_plan *p, const float *in, const float *gout, float 
   };
   // small spectra of the output gradient, all channels of the chunk at once
   SCAT_TRY(scat::launch3_real_to_complex(go, Gs, pc * K * static_cast<long>(mout), st));
-  SCAT_TRY(scat::launch3_fft(Gs, pc * K, n0 >> J, n1 >> J, n2 >> J, false, tw, tw_n, st));
+  SCAT_TRY(scat::launch3_fft(Gs, pc * K, n0 >> Jo, n1 >> Jo, n2 >> Jo, false, tw, tw_n, st));
   SCAT_TRY(scat::launch3_real_to_complex(x, XH, tot, st));
   SCAT_TRY(fft3(XH, false));
   SCAT_TRY(lowpass_adj(0, AX, false));
@@ -1455,10 +1526,17 @@ scat_status scat_forward(scat_plan *plan, const float *in, float *out, long batc
                    (lay.xh + lay.t + lay.u + lay.v + lay.w) * static_cast<size_t>(lay.chunk);
       xp = reinterpret_cast<float *>(tail);
       op = reinterpret_cast<float *>(tail + lay.pad_in * static_cast<size_t>(lay.chunk));
-      const int ur = plan->user_shape[0], uc = plan->user_shape[1];
-      hipLaunchKernelGGL(k_pad_symmetric, dim3(stream_blocks(pc * h.shape[0] * h.shape[1])),
-                         dim3(256), 0, st, in + static_cast<size_t>(p0) * ur * uc, xp, pc, ur, uc,
-                         h.shape[0], h.shape[1]);
+      if (h.dims == 3) {
+        const int *u = plan->user_shape3, *g = plan->h3.shape;
+        hipLaunchKernelGGL(k_pad_symmetric3, dim3(stream_blocks(pc * static_cast<long>(plan->h3.points()))),
+                           dim3(256), 0, st, in + static_cast<size_t>(p0) * u[0] * u[1] * u[2], xp, pc,
+                           u[0], u[1], u[2], g[0], g[1], g[2]);
+      } else {
+        const int ur = plan->user_shape[0], uc = plan->user_shape[1];
+        hipLaunchKernelGGL(k_pad_symmetric, dim3(stream_blocks(pc * h.shape[0] * h.shape[1])),
+                           dim3(256), 0, st, in + static_cast<size_t>(p0) * ur * uc, xp, pc, ur, uc,
+                           h.shape[0], h.shape[1]);
+      }
       if (hipGetLastError() != hipSuccess) return SCAT_ERR_DEVICE;
       cin = xp;
       cout = op;
@@ -1471,7 +1549,15 @@ scat_status scat_forward(scat_plan *plan, const float *in, float *out, long batc
                     : plan->fused ? forward_2d_fused(plan, cin, cout, cp0, pc, lay, st)
                                   : forward_2d(plan, cin, cout, cp0, pc, lay, st);
     if (s != SCAT_OK) return s;
-    if (plan->padded) {
+    if (plan->padded && h.dims == 3) {
+      const int Jo = plan->h3.out_shift();
+      const int *g = plan->h3.shape, *o = plan->user_out3;
+      const long maps = pc * h.K;
+      hipLaunchKernelGGL(k_crop3, dim3(stream_blocks(maps * o[0] * o[1] * o[2])), dim3(256), 0, st, op,
+                         out + static_cast<size_t>(p0) * h.K * o[0] * o[1] * o[2], maps, g[0] >> Jo,
+                         g[1] >> Jo, g[2] >> Jo, o[0], o[1], o[2]);
+      if (hipGetLastError() != hipSuccess) return SCAT_ERR_DEVICE;
+    } else if (plan->padded) {
       const int m_r = h.dims == 2 ? h.shape[0] >> h.res(h.J) : 1, m_c = h.shape[1] >> h.res(h.J);
       const int o_r = plan->user_out[0], o_c = plan->user_out[1];
       hipLaunchKernelGGL(k_crop, dim3(stream_blocks(pc * h.K * o_r * o_c)), dim3(256), 0, st, op,
@@ -1489,6 +1575,7 @@ scat_status scat_backward(scat_plan *plan, const float *in, const float *grad_ou
   if (batch < 0) return SCAT_ERR_ARG;
   const scat::HostPlan &h = plan->host;
   if (h.dims == 3) {
+    if (plan->padded) return SCAT_ERR_ARG;
     if (batch == 0) return SCAT_OK;
     if (in == nullptr || grad_out == nullptr || grad_in == nullptr) return SCAT_ERR_NULL;
     if (!plan->has_device) return SCAT_ERR_DEVICE;
@@ -1587,7 +1674,7 @@ scat_status scat_backward(scat_plan *plan, const float *in, const float *grad_ou
 }
 
 size_t scat_plan_backward_workspace_bytes(const scat_plan *plan, long batch) {
-  if (plan == nullptr || batch <= 0 || (plan->host.dims == 1 && plan->padded)) return 0;
+  if (plan == nullptr || batch <= 0 || (plan->host.dims != 2 && plan->padded)) return 0;
   if (plan->host.dims == 3) {
     const size_t per = bytes_per_volume_3d_bwd(*plan);
     long chunk = static_cast<long>(scratch_budget() / per);
@@ -1619,7 +1706,8 @@ scat_status scat_plan_out_shape(const scat_plan *plan, int *shape_out) {
   if (plan == nullptr || shape_out == nullptr) return SCAT_ERR_NULL;
   const scat::HostPlan &h = plan->host;
   if (h.dims == 3) {
-    for (int d = 0; d < 3; ++d) shape_out[d] = plan->h3.shape[d] >> h.J;
+    for (int d = 0; d < 3; ++d)
+      shape_out[d] = plan->padded ? plan->user_out3[d] : plan->h3.shape[d] >> plan->h3.out_shift();
     return SCAT_OK;
   }
   if (plan->padded) {

@@ -21,6 +21,8 @@ struct HostPlan3D {
   int shape[3] = {1, 1, 1};
   int J = 0, L = 0, max_order = 0;
   int K = 0;
+  int oversampling = 0;  // the outputs are read at the samples 2^out_shift() n
+  int out_shift() const { return J > oversampling ? J - oversampling : 0; }
   std::vector<Coeff3D> index;
   // psi[(j * (L+1) + l)] = (2l+1) tables of shape[0]*shape[1]*shape[2] doubles, m-major
   std::vector<std::vector<double>> psi;

@@ -26,11 +26,25 @@ def test_bad_arguments(shape, J, L, mo, status):
     assert e.value.status == status
 
 
-def test_no_padding_or_oversampling():
-    for kw in (dict(padded=True), dict(oversampling=1)):
-        with pytest.raises(scat.ScatError) as e:
-            scat.Scattering((8, 8, 8), 1, 1, host_only=True, **kw)
+def test_padded_and_oversampled_plans_host_side():
+    p = scat.Scattering((5, 7, 6), 1, 1, host_only=True, padded=True)
+    try:
+        assert p.grid_shape == (8, 16, 8) and p.out_shape == (3, 4, 3)
+        assert p.backward_workspace_bytes(2) == 0
+        with pytest.raises(scat.ScatError) as e:        # no backward pass on padded 3-D plans
+            scat.scat_backward(p._plan, 8, 8, 8, 1)
         assert e.value.status == 1
+    finally:
+        p.close()
+    with pytest.raises(scat.ScatError) as e:            # grid would exceed 256 points per side
+        scat.Scattering((250, 8, 8), 3, 1, host_only=True, padded=True)
+    assert e.value.status == 2
+    for o, want in ((0, (2, 4, 2)), (1, (4, 8, 4)), (2, (8, 16, 8)), (9, (8, 16, 8))):
+        p = scat.Scattering((8, 16, 8), 2, 1, host_only=True, oversampling=o)
+        try:
+            assert p.out_shape == want
+        finally:
+            p.close()
     p = scat.Scattering((8, 8, 8), 1, 1, host_only=True)
     try:
         assert p.backward_workspace_bytes(4) > p.workspace_bytes(4)
@@ -345,3 +359,64 @@ def test_backward_benchmark_workload_sampled():
         assert ratio < 1e-6 and bad <= 1e-3 and el2 <= 1e-2, (v, emax, el2, ratio, bad)
     print("3d backward workload: %d of 3 volumes within 1e-4 on all channels" % strict,
           flush=True)
+
+
+# ---- oversampling and volumes of any size ------------------------------------------------
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("shape,J,L,o", [
+    ((16, 16, 16), 2, 2, 1), ((16, 16, 16), 2, 1, 2), ((8, 32, 16), 3, 1, 1), ((8, 8, 8), 2, 1, 1),
+    ((32, 32, 32), 2, 3, 5),
+])
+def test_oversampled_parity(shape, J, L, o):
+    x = workloads.volumes(shape, 2)
+    plan = scat.Scattering(shape, J, L, oversampling=o)
+    try:
+        got = gpu_forward(plan, x)
+        rows = plan.coeff_index()
+    finally:
+        plan.close()
+    want = o3.harmonic_scattering3d(x, J, L, oversampling=o)
+    errs = per_order_errors(got, want, order_of_channels(rows), x)
+    print("3d oversampled", shape, J, L, o, errs, flush=True)
+    assert max(errs.values()) <= TOL, errs
+
+
+@pytest.mark.gpu
+def test_oversampled_backward_parity():
+    import torch
+    shape, J, L, o = (16, 16, 16), 2, 2, 1
+    rng = np.random.default_rng(4)
+    x = (workloads.volumes(shape, 2) + 0.2 * rng.standard_normal((2,) + shape)).astype(np.float32)
+    plan = scat.Scattering(shape, J, L, oversampling=o)
+    try:
+        g = rng.standard_normal((2, plan.K) + plan.out_shape).astype(np.float32)
+        gx = plan.backward(torch.from_numpy(x).cuda(), torch.from_numpy(g).cuda())
+        torch.cuda.synchronize()
+        got = gx.cpu().numpy().astype(np.float64)
+    finally:
+        plan.close()
+    want = o3.harmonic_scattering3d_backward(x, g, J, L, oversampling=o)
+    emax = np.abs(got - want).max() / np.abs(want).max()
+    assert emax <= TOL_GRAD_MAX, emax
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("shape,J,L,o", [
+    ((5, 7, 6), 1, 1, 0), ((20, 24, 28), 2, 2, 0), ((30, 30, 30), 2, 1, 1), ((12, 50, 9), 3, 1, 0),
+    ((48, 40, 56), 2, 1, 0),
+])
+def test_padded_parity(shape, J, L, o):
+    rng = np.random.default_rng(sum(shape))
+    x = rng.standard_normal((2,) + shape).astype(np.float32)
+    plan = scat.Scattering(shape, J, L, padded=True, oversampling=o)
+    try:
+        got = gpu_forward(plan, x)
+        rows = plan.coeff_index()
+    finally:
+        plan.close()
+    want = o3.harmonic_scattering3d_padded(x, J, L, oversampling=o)
+    assert got.shape == want.shape
+    errs = per_order_errors(got, want, order_of_channels(rows), x)
+    print("3d padded", shape, J, L, o, errs, flush=True)
+    assert max(errs.values()) <= TOL, errs
