@@ -76,7 +76,7 @@ typedef enum {
  * real harmonics.  scat_plan_create_padded / SCAT_PLAN_PADDED: volumes of any size up to
  * 256 - 2^J per side, extended symmetrically as described below (SCAT_ERR_SHAPE beyond).
  * Oversampling o: only the output grid changes, the samples 2^max(J-o,0) n.  scat_backward
- * works on every 3-D plan that is not padded.
+ * works on every 3-D plan.
  *
  * On success *out_plan is a new plan the caller must release with scat_plan_destroy.
  * On failure *out_plan is NULL and nothing is leaked.
@@ -102,7 +102,7 @@ scat_status scat_plan_create_host(scat_plan **out_plan, int dims, const int *sha
  * transform runs on that grid, and the output keeps the samples 2^J k that lie inside the
  * signal: side ceil(n / 2^J).  scat_forward then takes inputs of `shape` and writes outputs
  * of scat_plan_out_shape; scat_plan_grid_shape tells the periodic grid; scat_plan_filter
- * refers to that grid.  scat_backward works on these plans too (2-D): it applies the
+ * refers to that grid.  scat_backward works on these plans too: it applies the
  * adjoints of the crop (zero extension) and of the symmetric extension (every sample
  * collects the gradients of its mirror images) around the periodic backward pass.
  * SCAT_ERR_SHAPE if the periodic grid exceeds what scat_plan_create accepts.
@@ -171,7 +171,7 @@ scat_status scat_forward(scat_plan *plan, const float *in, float *out, long batc
  * 3-D plans: rho = sqrt(sum_m |y_m|^2) passes g y_m / rho to y_m (nothing where rho = 0); the
  * degree-0 signal y is real, so there the factor is sign(y), decided by rounding where |y| is
  * below fp32 resolution.
- * Errors: SCAT_ERR_ARG for a padded 1-D or 3-D plan or batch < 0.  SCAT_ERR_SHAPE, 2-D: unless every
+ * Errors: SCAT_ERR_ARG for batch < 0.  SCAT_ERR_SHAPE, 2-D: unless every
  * side and every side subsampled for the last octave lies in 4...512 and the output grid
  * has at most 1024 points; 1-D: unless the signal, seen as the n1 x n2 matrix of the
  * four-step transform (n2 = 2^max(ceil(log2(n)/2), J), n1 = n / n2), has n1 in 4...512 and

@@ -7,7 +7,8 @@ product.
 """
 from .filters import bank_1d, bank_2d  # noqa: F401
 from .scattering import (coeff_index_1d, coeff_index_2d, pad_index, padded_size,  # noqa: F401
-                         scattering1d, scattering1d_backward, scattering1d_padded, scattering2d_padded,
+                         scattering1d, scattering1d_backward, scattering1d_padded,
+                         scattering1d_padded_backward, scattering2d_padded,
                          scattering2d_padded_backward,
                          scattering1d_plain, scattering2d, scattering2d_backward,
                          scattering2d_plain)

@@ -215,3 +215,28 @@ def harmonic_scattering3d_backward(x, g, J, L, max_order=2, bank=None, oversampl
                     c2 += 1
             gx = gx + rho_adj(gU1, y1, U1, psi_hat[j1][l])
     return gx
+
+
+def harmonic_scattering3d_padded_backward(x, g, J, L, max_order=2, oversampling=0):
+    """Gradient of sum(g * harmonic_scattering3d_padded(x)) with respect to x: zero-extend g
+    to the periodic grid's output (adjoint of the crop), run the periodic backward pass on
+    the extended volume, and add every extended sample's gradient to the voxel it mirrors
+    (adjoint of the symmetric extension)."""
+    from .scattering import pad_index, padded_size
+    x = np.asarray(x, dtype=np.float64)
+    g = np.asarray(g, dtype=np.float64)
+    n = x.shape[-3:]
+    P = [padded_size(k, J) for k in n]
+    idx = [pad_index(k, Pk) for k, Pk in zip(n, P)]
+    xp = x[..., idx[0], :, :][..., :, idx[1], :][..., idx[2]]
+    st = max(J - oversampling, 0)
+    gp = np.zeros(g.shape[:-3] + tuple(Pk >> st for Pk in P))
+    gp[..., :g.shape[-3], :g.shape[-2], :g.shape[-1]] = g
+    gxp = harmonic_scattering3d_backward(xp, gp, J, L, max_order, oversampling=oversampling)
+    a = np.zeros(x.shape[:-3] + (n[0], P[1], P[2]))
+    np.add.at(a, (Ellipsis, idx[0], slice(None), slice(None)), gxp)
+    b = np.zeros(x.shape[:-3] + (n[0], n[1], P[2]))
+    np.add.at(b, (Ellipsis, idx[1], slice(None)), a)
+    out = np.zeros(x.shape)
+    np.add.at(out, (Ellipsis, idx[2]), b)
+    return out

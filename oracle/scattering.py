@@ -274,6 +274,21 @@ def scattering1d_padded(x, J, Q, max_order=2):
     return S[..., :-(-n >> J)]
 
 
+def scattering1d_padded_backward(x, g, J, Q, max_order=2):
+    """1-D counterpart of ``scattering2d_padded_backward``."""
+    x = np.asarray(x, dtype=np.float64)
+    g = np.asarray(g, dtype=np.float64)
+    n = x.shape[-1]
+    P = padded_size(n, J)
+    idx = pad_index(n, P)
+    gp = np.zeros(g.shape[:-1] + (P >> J,))
+    gp[..., :g.shape[-1]] = g
+    gxp = scattering1d_backward(x[..., idx], gp, J, Q, max_order)
+    out = np.zeros(x.shape)
+    np.add.at(out, (Ellipsis, idx), gxp)
+    return out
+
+
 def scattering2d_plain(x, J, L, max_order=2, bank=None):
     """The three defining equations at full resolution, sampled at 2^J n."""
     x = np.asarray(x, dtype=np.float64)

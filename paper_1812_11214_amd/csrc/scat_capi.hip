@@ -596,6 +596,50 @@ __global__ __launch_bounds__(256) void k_unpad_symmetric(const float *__restrict
   }
 }
 
+// 3-D versions: adjoint of k_crop3 (zero extension) and of k_pad_symmetric3
+__global__ __launch_bounds__(256) void k_uncrop3(const float *__restrict__ in, float *__restrict__ out,
+                                                 long maps, int m0, int m1, int m2, int o0, int o1,
+                                                 int o2) {
+  const long per = static_cast<long>(m0) * m1 * m2;
+  const long total = maps * per;
+  const long stride = static_cast<long>(gridDim.x) * blockDim.x;
+  for (long i = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x; i < total; i += stride) {
+    const long g = i / per;
+    long e = i - g * per;
+    const int c = static_cast<int>(e % m2);
+    e /= m2;
+    const int b = static_cast<int>(e % m1);
+    const int a = static_cast<int>(e / m1);
+    out[i] = (a < o0 && b < o1 && c < o2) ? in[((g * o0 + a) * o1 + b) * o2 + c] : 0.f;
+  }
+}
+
+__global__ __launch_bounds__(256) void k_unpad_symmetric3(const float *__restrict__ gp,
+                                                          float *__restrict__ gx, long volumes, int u0,
+                                                          int u1, int u2, int P0, int P1, int P2) {
+  const long per = static_cast<long>(u0) * u1 * u2;
+  const long total = volumes * per;
+  const long stride = static_cast<long>(gridDim.x) * blockDim.x;
+  for (long i = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x; i < total; i += stride) {
+    const long v = i / per;
+    long e = i - v * per;
+    const int c = static_cast<int>(e % u2);
+    e /= u2;
+    const int b = static_cast<int>(e % u1);
+    const int a = static_cast<int>(e / u1);
+    const float *vol = gp + v * static_cast<long>(P0) * P1 * P2;
+    float acc = 0.f;
+    for_each_image(a, u0, P0, [&](int ia) {
+      for_each_image(b, u1, P1, [&](int ib) {
+        for_each_image(c, u2, P2, [&](int ic) {
+          acc += vol[(static_cast<size_t>(ia) * P1 + ib) * P2 + ic];
+        });
+      });
+    });
+    gx[i] = acc;
+  }
+}
+
 unsigned stream_blocks(long total) {
   long b = (total + 255) / 256;
   if (b > 65536 * 16) b = 65536 * 16;
@@ -841,7 +885,9 @@ BwdLayout make_bwd_layout(const scat_plan &p, long batch) {
     b.gu = l * n;
     b.ga = second ? l * (n >> h.res(1)) : 0;
     b.gh = l * (n >> h.res(h.J));
-    b.per_plane = b.fwd.xh + b.fwd.t + b.fwd.u + (b.tape.total + b.gx + b.gu + b.ga + b.gh) * c8;
+    if (p.padded) b.pad_floats = 2 * n + static_cast<size_t>(h.K) * (n >> h.res(h.J));
+    b.per_plane = b.fwd.xh + b.fwd.t + b.fwd.u + (b.tape.total + b.gx + b.gu + b.ga + b.gh) * c8 +
+                  b.pad_floats * sizeof(float);
   } else {
     const size_t t1 = l * n, t2 = second ? l * l * (n >> (2 * h.res(1))) : 0;
     if (p.fused) {
@@ -1575,14 +1621,17 @@ scat_status scat_backward(scat_plan *plan, const float *in, const float *grad_ou
   if (batch < 0) return SCAT_ERR_ARG;
   const scat::HostPlan &h = plan->host;
   if (h.dims == 3) {
-    if (plan->padded) return SCAT_ERR_ARG;
     if (batch == 0) return SCAT_OK;
     if (in == nullptr || grad_out == nullptr || grad_in == nullptr) return SCAT_ERR_NULL;
     if (!plan->has_device) return SCAT_ERR_DEVICE;
     int dev3 = -1;
     if (hipGetDevice(&dev3) != hipSuccess || dev3 != plan->device) return SCAT_ERR_DEVICE;
     hipStream_t st3 = static_cast<hipStream_t>(stream);
-    const size_t per = bytes_per_volume_3d_bwd(*plan);
+    // padded plans: extended input, its gradient and the zero-extended output gradient
+    // sit behind the periodic pass's buffers
+    const size_t n3 = plan->h3.points(), mout3 = n3 >> (3 * plan->h3.out_shift());
+    const size_t core = bytes_per_volume_3d_bwd(*plan);
+    const size_t per = core + (plan->padded ? (2 * n3 + h.K * mout3) * sizeof(float) : 0);
     long chunk = static_cast<long>(scratch_budget() / per);
     if (chunk < 1) chunk = 1;
     if (chunk > batch) chunk = batch;
@@ -1601,14 +1650,37 @@ scat_status scat_backward(scat_plan *plan, const float *in, const float *grad_ou
     } scope3(plan->timer.enabled ? &plan->timer : nullptr);
     for (long p0 = 0; p0 < batch; p0 += chunk) {
       const long pc = batch - p0 < chunk ? batch - p0 : chunk;
-      scat_status s3 = backward_3d(plan, in, grad_out, grad_in, p0, pc, st3);
+      if (!plan->padded) {
+        scat_status s3 = backward_3d(plan, in, grad_out, grad_in, p0, pc, st3);
+        if (s3 != SCAT_OK) return s3;
+        continue;
+      }
+      const int *u = plan->user_shape3, *g = plan->h3.shape, *o = plan->user_out3;
+      const int Jo = plan->h3.out_shift();
+      const size_t un = static_cast<size_t>(u[0]) * u[1] * u[2];
+      const size_t on = static_cast<size_t>(o[0]) * o[1] * o[2];
+      float *xp = reinterpret_cast<float *>(static_cast<char *>(plan->d_scratch) +
+                                            core * static_cast<size_t>(chunk));
+      float *gxp = xp + n3 * chunk;
+      float *gop = gxp + n3 * chunk;
+      hipLaunchKernelGGL(k_pad_symmetric3, dim3(stream_blocks(pc * static_cast<long>(n3))), dim3(256), 0,
+                         st3, in + static_cast<size_t>(p0) * un, xp, pc, u[0], u[1], u[2], g[0], g[1],
+                         g[2]);
+      hipLaunchKernelGGL(k_uncrop3, dim3(stream_blocks(pc * h.K * static_cast<long>(mout3))), dim3(256),
+                         0, st3, grad_out + static_cast<size_t>(p0) * h.K * on, gop, pc * h.K,
+                         g[0] >> Jo, g[1] >> Jo, g[2] >> Jo, o[0], o[1], o[2]);
+      if (hipGetLastError() != hipSuccess) return SCAT_ERR_DEVICE;
+      scat_status s3 = backward_3d(plan, xp, gop, gxp, 0, pc, st3);
       if (s3 != SCAT_OK) return s3;
+      hipLaunchKernelGGL(k_unpad_symmetric3, dim3(stream_blocks(pc * static_cast<long>(un))), dim3(256),
+                         0, st3, gxp, grad_in + static_cast<size_t>(p0) * un, pc, u[0], u[1], u[2], g[0],
+                         g[1], g[2]);
+      if (hipGetLastError() != hipSuccess) return SCAT_ERR_DEVICE;
     }
     return SCAT_OK;
   }
   if (h.dims == 1) {
     // signals are n1 x n2 matrices: n1-point column transforms, row transforms of n2 >> r
-    if (plan->padded) return SCAT_ERR_ARG;
     if (!scat::backward_side_supported(plan->n1) || plan->n2 > 512) return SCAT_ERR_SHAPE;
   } else {
     // every grid of the cascade must have sides the plain transforms handle, and the
@@ -1649,8 +1721,10 @@ scat_status scat_backward(scat_plan *plan, const float *in, const float *grad_ou
     }
     // padded plan: extend the input and (with zeros) the output gradient to the periodic
     // grid, run the periodic backward pass there, fold the extended gradient back
+    // (a 1-D signal is one row of n1 * n2 samples here, whatever its matrix form inside)
     const size_t n = static_cast<size_t>(plan->n1) * plan->n2;
-    const int m_r = plan->n1 >> h.res(h.J), m_c = plan->n2 >> h.res(h.J);
+    const int P_r = h.dims == 1 ? 1 : plan->n1, P_c = h.dims == 1 ? static_cast<int>(n) : plan->n2;
+    const int m_r = P_r >> (h.dims == 1 ? 0 : h.res(h.J)), m_c = P_c >> h.res(h.J);
     const int ur = plan->user_shape[0], uc = plan->user_shape[1];
     const int o_r = plan->user_out[0], o_c = plan->user_out[1];
     float *xp = reinterpret_cast<float *>(static_cast<char *>(plan->d_scratch) +
@@ -1659,24 +1733,27 @@ scat_status scat_backward(scat_plan *plan, const float *in, const float *grad_ou
     float *gxp = xp + n * bl.chunk;
     float *gop = gxp + n * bl.chunk;
     hipLaunchKernelGGL(k_pad_symmetric, dim3(stream_blocks(pc * static_cast<long>(n))), dim3(256), 0,
-                       st, in + static_cast<size_t>(p0) * ur * uc, xp, pc, ur, uc, plan->n1, plan->n2);
+                       st, in + static_cast<size_t>(p0) * ur * uc, xp, pc, ur, uc, P_r, P_c);
     hipLaunchKernelGGL(k_uncrop, dim3(stream_blocks(pc * h.K * m_r * m_c)), dim3(256), 0, st,
                        grad_out + static_cast<size_t>(p0) * h.K * o_r * o_c, gop, pc * h.K, m_r, m_c,
                        o_r, o_c);
     if (hipGetLastError() != hipSuccess) return SCAT_ERR_DEVICE;
-    scat_status s = backward_2d(plan, xp, gop, gxp, 0, pc, bl, st);
+    scat_status s = h.dims == 1 ? backward_1d(plan, xp, gop, gxp, 0, pc, bl, st)
+                                : backward_2d(plan, xp, gop, gxp, 0, pc, bl, st);
     if (s != SCAT_OK) return s;
     hipLaunchKernelGGL(k_unpad_symmetric, dim3(stream_blocks(pc * ur * uc)), dim3(256), 0, st, gxp,
-                       grad_in + static_cast<size_t>(p0) * ur * uc, pc, ur, uc, plan->n1, plan->n2);
+                       grad_in + static_cast<size_t>(p0) * ur * uc, pc, ur, uc, P_r, P_c);
     if (hipGetLastError() != hipSuccess) return SCAT_ERR_DEVICE;
   }
   return SCAT_OK;
 }
 
 size_t scat_plan_backward_workspace_bytes(const scat_plan *plan, long batch) {
-  if (plan == nullptr || batch <= 0 || (plan->host.dims != 2 && plan->padded)) return 0;
+  if (plan == nullptr || batch <= 0) return 0;
   if (plan->host.dims == 3) {
-    const size_t per = bytes_per_volume_3d_bwd(*plan);
+    const size_t n3 = plan->h3.points(), mout3 = n3 >> (3 * plan->h3.out_shift());
+    const size_t per = bytes_per_volume_3d_bwd(*plan) +
+                       (plan->padded ? (2 * n3 + plan->host.K * mout3) * sizeof(float) : 0);
     long chunk = static_cast<long>(scratch_budget() / per);
     if (chunk < 1) chunk = 1;
     return per * static_cast<size_t>(chunk > batch ? batch : chunk);

@@ -116,7 +116,7 @@ def test_filter_bank_1d_matches_oracle():
 
 
 def test_backward_argument_errors_need_no_gpu():
-    """scat_backward rejects padded 1-D plans, unsupported grids and bad arguments before
+    """scat_backward rejects unsupported grids and bad arguments before
     it touches the GPU (host-only plans are enough to see it)."""
     import paper_1812_11214_amd as scat
     from paper_1812_11214_amd import binding
@@ -128,8 +128,8 @@ def test_backward_argument_errors_need_no_gpu():
     try:
         assert L.scat_backward(one_d, None, None, None, 1, None) == 5      # supported: NULL args
         pad_1d = scat.scat_plan_create_padded_host((1000,), 4, 2)
-        assert L.scat_backward(pad_1d, None, None, None, 1, None) == 1     # SCAT_ERR_ARG
-        assert scat.scat_plan_backward_workspace_bytes(pad_1d, 4) == 0
+        assert L.scat_backward(pad_1d, None, None, None, 1, None) == 5     # supported: NULL args
+        assert scat.scat_plan_backward_workspace_bytes(pad_1d, 4) > 0
         scat.scat_plan_destroy(pad_1d)
         long_1d = scat.scat_plan_create_host((1 << 20,), 4, 2)             # 1024 x 1024 matrix
         assert L.scat_backward(long_1d, None, None, None, 1, None) == 2    # SCAT_ERR_SHAPE

@@ -122,6 +122,28 @@ def test_oracle_padded_backward_matches_finite_differences():
         assert abs(fd - np.sum(gx * d)) <= 1e-6 * max(abs(fd), 1e-3)
 
 
+def test_oracle_padded_backward_1d_and_3d_match_finite_differences():
+    from oracle import harmonic3d as o3
+    rng = np.random.default_rng(6)
+    x = rng.standard_normal((2, 50))
+    S = oracle.scattering1d_padded(x, 3, 2)
+    g = rng.standard_normal(S.shape)
+    gx = oracle.scattering1d_padded_backward(x, g, 3, 2)
+    d = rng.standard_normal(x.shape)
+    eps = 1e-6
+    f = lambda z: float(np.sum(g * oracle.scattering1d_padded(z, 3, 2)))
+    fd = (f(x + eps * d) - f(x - eps * d)) / (2 * eps)
+    assert abs(fd - np.sum(gx * d)) <= 1e-6 * max(abs(fd), 1e-3)
+    x = rng.standard_normal((1, 5, 7, 6)) + 0.3
+    S = o3.harmonic_scattering3d_padded(x, 1, 1)
+    g = rng.standard_normal(S.shape)
+    gx = o3.harmonic_scattering3d_padded_backward(x, g, 1, 1)
+    d = rng.standard_normal(x.shape)
+    f = lambda z: float(np.sum(g * o3.harmonic_scattering3d_padded(z, 1, 1)))
+    fd = (f(x + eps * d) - f(x - eps * d)) / (2 * eps)
+    assert abs(fd - np.sum(gx * d)) <= 1e-6 * max(abs(fd), 1e-3)
+
+
 def test_extension_adjoint_identity():
     """<pad(x), y> = <x, pad^T(y)> with pad^T as used by the oracle's backward pass."""
     rng = np.random.default_rng(2)
@@ -151,5 +173,47 @@ def test_padded_backward_parity_gpu(shape, J, L, batch):
         plan.close()
     want = oracle.scattering2d_padded_backward(x.astype(np.float64), g.astype(np.float64), J, L)
     for p in range(batch):
+        err = np.abs(got[p] - want[p]).max() / np.abs(want[p]).max()
+        assert err <= 1e-4, (p, err)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("n,J,Q,batch", [(1000, 4, 2, 3), (50, 3, 1, 2), (5000, 5, 4, 2)])
+def test_padded_backward_parity_gpu_1d(n, J, Q, batch):
+    import torch
+    rng = np.random.default_rng(n + J)
+    x = rng.standard_normal((batch, n)).astype(np.float32)
+    plan = scat.Scattering((n,), J, Q, padded=True)
+    try:
+        g = rng.standard_normal((batch, plan.K) + plan.out_shape).astype(np.float32)
+        gi = plan.backward(torch.from_numpy(x).cuda(), torch.from_numpy(g).cuda())
+        torch.cuda.synchronize()
+        got = gi.cpu().numpy().astype(np.float64)
+    finally:
+        plan.close()
+    want = oracle.scattering1d_padded_backward(x.astype(np.float64), g.astype(np.float64), J, Q)
+    for p in range(batch):
+        err = np.abs(got[p] - want[p]).max() / np.abs(want[p]).max()
+        assert err <= 1e-4, (p, err)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("shape,J,L,o", [((5, 7, 6), 1, 1, 0), ((20, 24, 28), 2, 2, 0),
+                                         ((12, 30, 9), 2, 1, 1)])
+def test_padded_backward_parity_gpu_3d(shape, J, L, o):
+    import torch
+    from oracle import harmonic3d as o3
+    rng = np.random.default_rng(sum(shape) + J)
+    x = rng.standard_normal((2,) + shape).astype(np.float32)
+    plan = scat.Scattering(shape, J, L, padded=True, oversampling=o)
+    try:
+        g = rng.standard_normal((2, plan.K) + plan.out_shape).astype(np.float32)
+        gi = plan.backward(torch.from_numpy(x).cuda(), torch.from_numpy(g).cuda())
+        torch.cuda.synchronize()
+        got = gi.cpu().numpy().astype(np.float64)
+    finally:
+        plan.close()
+    want = o3.harmonic_scattering3d_padded_backward(x, g, J, L, oversampling=o)
+    for p in range(2):
         err = np.abs(got[p] - want[p]).max() / np.abs(want[p]).max()
         assert err <= 1e-4, (p, err)
