@@ -105,31 +105,6 @@ __global__ __launch_bounds__(256) void k3_mul_ctable(const float2 *__restrict__ 
   }
 }
 
-// Backward pass helpers.  up[v][a 2^J][b 2^J][c 2^J] = g[v][chan][a][b][c], zero elsewhere.
-__global__ __launch_bounds__(256) void k3_upsample(const float *__restrict__ g,
-                                                   float2 *__restrict__ up, long volumes, int K,
-                                                   int chan, int n0, int n1, int n2, int J) {
-  const long per = static_cast<long>(n0) * n1 * n2;
-  const long total = volumes * per;
-  const int mask = (1 << J) - 1;
-  const int m1 = n1 >> J, m2 = n2 >> J;
-  const long mper = static_cast<long>(n0 >> J) * m1 * m2;
-  const long stride = static_cast<long>(gridDim.x) * blockDim.x;
-  for (long i = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x; i < total; i += stride) {
-    const long v = i / per;
-    long e = i - v * per;
-    const int c = static_cast<int>(e % n2);
-    e /= n2;
-    const int b = static_cast<int>(e % n1);
-    const int a = static_cast<int>(e / n1);
-    float val = 0.f;
-    if (((a | b | c) & mask) == 0)
-      val = g[(static_cast<size_t>(v) * K + chan) * mper +
-              (static_cast<size_t>(a >> J) * m1 + (b >> J)) * m2 + (c >> J)];
-    up[i] = make_float2(val, 0.f);
-  }
-}
-
 // y[i] <- Re(gu[i]) * y[i] / sqrt(acc[i])  (0 where acc = sum_m |y_m|^2 vanishes): the
 // gradient of rho = sqrt(sum_m |y_m|^2) with respect to y_m, given the gradient of rho
 __global__ __launch_bounds__(256) void k3_rho_back(const float2 *__restrict__ gu,
@@ -829,16 +804,6 @@ hipError_t launch3_mul_ctable(const float2 *src, const float2 *ctab, float2 *dst
   LaunchScope obs("k3_mul_ctable", total * (accumulate ? 24.0 : 16.0) + n * 8.0, total * 6.0, st);
   hipLaunchKernelGGL(k3_mul_ctable, dim3(blocks_for(total)), dim3(256), 0, st, src, ctab, dst, total, n,
                      conj_table ? 1 : 0, accumulate ? 1 : 0);
-  return hipGetLastError();
-}
-
-hipError_t launch3_upsample(const float *g, float2 *up, long volumes, int K, int chan, int n0, int n1,
-                            int n2, int J, hipStream_t st) {
-  const long total = volumes * n0 * n1 * n2;
-  if (total <= 0) return hipSuccess;
-  LaunchScope obs("k3_upsample", total * 8.0, 0.0, st);
-  hipLaunchKernelGGL(k3_upsample, dim3(blocks_for(total)), dim3(256), 0, st, g, up, volumes, K, chan,
-                     n0, n1, n2, J);
   return hipGetLastError();
 }
 

@@ -1490,6 +1490,26 @@ scat_status forward_1d(scat_plan *p, const float *in, float *out, long p0, long 
   return SCAT_OK;
 }
 
+// Makes the plan's scratch buffer at least `need` bytes (growing it synchronises the device).
+scat_status ensure_scratch(scat_plan *plan, size_t need) {
+  if (need <= plan->scratch_bytes) return SCAT_OK;
+  if (hipDeviceSynchronize() != hipSuccess) return SCAT_ERR_DEVICE;
+  if (plan->d_scratch) (void)hipFree(plan->d_scratch);
+  plan->d_scratch = nullptr;
+  plan->scratch_bytes = 0;
+  if (hipMalloc(&plan->d_scratch, need) != hipSuccess) return SCAT_ERR_ALLOC;
+  plan->scratch_bytes = need;
+  return SCAT_OK;
+}
+
+// Routes the launches of one call to the plan's timer while it records.
+struct ObserverScope {
+  explicit ObserverScope(scat_plan *plan) {
+    scat::set_launch_observer(plan->timer.enabled ? &plan->timer : nullptr);
+  }
+  ~ObserverScope() { scat::set_launch_observer(nullptr); }
+};
+
 }  // namespace
 
 extern "C" {
@@ -1547,18 +1567,11 @@ scat_status scat_forward(scat_plan *plan, const float *in, float *out, long batc
   hipStream_t st = static_cast<hipStream_t>(stream);
   const Layout lay = make_layout(*plan, batch);
   const size_t need = lay.per_plane * static_cast<size_t>(lay.chunk);
-  if (need > plan->scratch_bytes) {
-    if (hipDeviceSynchronize() != hipSuccess) return SCAT_ERR_DEVICE;
-    if (plan->d_scratch) (void)hipFree(plan->d_scratch);
-    plan->d_scratch = nullptr;
-    plan->scratch_bytes = 0;
-    if (hipMalloc(&plan->d_scratch, need) != hipSuccess) return SCAT_ERR_ALLOC;
-    plan->scratch_bytes = need;
+  {
+    const scat_status grown = ensure_scratch(plan, need);
+    if (grown != SCAT_OK) return grown;
   }
-  struct ObserverScope {
-    explicit ObserverScope(scat::LaunchObserver *o) { scat::set_launch_observer(o); }
-    ~ObserverScope() { scat::set_launch_observer(nullptr); }
-  } scope(plan->timer.enabled ? &plan->timer : nullptr);
+  ObserverScope observer_scope(plan);
   const scat::HostPlan &h = plan->host;
   for (long p0 = 0; p0 < batch; p0 += lay.chunk) {
     long pc = batch - p0 < lay.chunk ? batch - p0 : lay.chunk;
@@ -1636,18 +1649,11 @@ scat_status scat_backward(scat_plan *plan, const float *in, const float *grad_ou
     if (chunk < 1) chunk = 1;
     if (chunk > batch) chunk = batch;
     const size_t need3 = per * static_cast<size_t>(chunk);
-    if (need3 > plan->scratch_bytes) {
-      if (hipDeviceSynchronize() != hipSuccess) return SCAT_ERR_DEVICE;
-      if (plan->d_scratch) (void)hipFree(plan->d_scratch);
-      plan->d_scratch = nullptr;
-      plan->scratch_bytes = 0;
-      if (hipMalloc(&plan->d_scratch, need3) != hipSuccess) return SCAT_ERR_ALLOC;
-      plan->scratch_bytes = need3;
-    }
-    struct ObserverScope3 {
-      explicit ObserverScope3(scat::LaunchObserver *o) { scat::set_launch_observer(o); }
-      ~ObserverScope3() { scat::set_launch_observer(nullptr); }
-    } scope3(plan->timer.enabled ? &plan->timer : nullptr);
+    {
+    const scat_status grown = ensure_scratch(plan, need3);
+    if (grown != SCAT_OK) return grown;
+  }
+  ObserverScope observer_scope(plan);
     for (long p0 = 0; p0 < batch; p0 += chunk) {
       const long pc = batch - p0 < chunk ? batch - p0 : chunk;
       if (!plan->padded) {
@@ -1699,18 +1705,11 @@ scat_status scat_backward(scat_plan *plan, const float *in, const float *grad_ou
   hipStream_t st = static_cast<hipStream_t>(stream);
   BwdLayout bl = make_bwd_layout(*plan, batch);
   const size_t need = bl.per_plane * static_cast<size_t>(bl.chunk);
-  if (need > plan->scratch_bytes) {
-    if (hipDeviceSynchronize() != hipSuccess) return SCAT_ERR_DEVICE;
-    if (plan->d_scratch) (void)hipFree(plan->d_scratch);
-    plan->d_scratch = nullptr;
-    plan->scratch_bytes = 0;
-    if (hipMalloc(&plan->d_scratch, need) != hipSuccess) return SCAT_ERR_ALLOC;
-    plan->scratch_bytes = need;
+  {
+    const scat_status grown = ensure_scratch(plan, need);
+    if (grown != SCAT_OK) return grown;
   }
-  struct ObserverScope {
-    explicit ObserverScope(scat::LaunchObserver *o) { scat::set_launch_observer(o); }
-    ~ObserverScope() { scat::set_launch_observer(nullptr); }
-  } scope(plan->timer.enabled ? &plan->timer : nullptr);
+  ObserverScope observer_scope(plan);
   for (long p0 = 0; p0 < batch; p0 += bl.chunk) {
     long pc = batch - p0 < bl.chunk ? batch - p0 : bl.chunk;
     if (!plan->padded) {

@@ -193,9 +193,7 @@ hipError_t launch3_real_to_complex(const float *x, float2 *out, long total, hipS
 // dst[v][e] = src[v][e] * filt[e], e < n
 hipError_t launch3_mul_table(const float2 *src, const float *filt, float2 *dst, long volumes, long n,
                              hipStream_t st, int fstride = 1, bool accumulate = false);
-// backward pass of the 3-D transform: zero-inserted output gradient, gradient through rho
-hipError_t launch3_upsample(const float *g, float2 *up, long volumes, int K, int chan, int n0, int n1,
-                            int n2, int J, hipStream_t st);
+// backward pass of the 3-D transform: lowpass adjoint, pair-table products, gradient through rho
 hipError_t launch3_tile_phi(const float2 *Gs, const float *phi, float2 *dst, long volumes, int K,
                             int chan, int n0, int n1, int n2, int J, bool accumulate, hipStream_t st);
 hipError_t launch3_mul_ctable(const float2 *src, const float2 *ctab, float2 *dst, long volumes, long n,
