@@ -246,7 +246,9 @@ def scat_forward(plan, in_ptr, out_ptr, batch, stream_ptr=None):
 
 class Scattering:
     """Owner of one plan.  `forward` takes a contiguous float32 CUDA tensor whose trailing
-    dims equal `shape`; all leading dims are independent planes."""
+    dims equal `shape`; all leading dims are independent planes.  One or two sides: the Morlet
+    cascade (LQ = wavelets per octave Q / number of angles L); three sides: solid harmonic
+    scattering (LQ = the largest degree L)."""
 
     def __init__(self, shape, J, LQ, max_order=2, host_only=False, padded=False, oversampling=0):
         """padded=True: signals of any size, extended symmetrically to a periodic grid of
@@ -300,7 +302,7 @@ class Scattering:
         return out
 
     def backward(self, x, grad_out, grad_in=None):
-        """Gradient of sum(grad_out * forward(x)) with respect to x (2-D plans)."""
+        """Gradient of sum(grad_out * forward(x)) with respect to x."""
         import torch
         for t, nm in ((x, "x"), (grad_out, "grad_out")):
             if not (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()):
