@@ -445,7 +445,15 @@ scat_status create_common(scat_plan **out_plan, int dims, const int *user_shape,
     p->n2 = 1 << lg2;
     p->n1 = shape[0] >> lg2;
   }
+  // fused row pass: every launch of the schedule must be one the kernel takes -- the first
+  // order from the image itself and, per octave with children, from that octave's grid
   p->fused = dims == 2 && J <= 4 && scat::rows_fused_supported(p->n1, p->n2, p->host.res(J - 1));
+  if (p->fused && max_order == 2)
+    for (int j1 = 0; j1 + 1 < J; ++j1) {
+      const int r1 = p->host.res(j1);
+      if (!scat::rows_fused_supported(p->n1 >> r1, p->n2 >> r1, p->host.res(J - 1) - r1))
+        p->fused = false;
+    }
   p->tree = dims == 2 && oversampling == 0 && scat::tree_supported(p->n1, p->n2, J);
   if (padded) {
     p->padded = true;

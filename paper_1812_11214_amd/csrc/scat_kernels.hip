@@ -1928,6 +1928,10 @@ bool rows_fused_supported(int Sr, int Sc, int fmax) {
   if (fmax < 0 || fmax > 3) return false;
   if ((Sc >> fmax) < 16) return false;
   if ((Sr >> fmax) < 1) return false;
+  // a wave transforms 64 / (Sc / 16) rows at a time and owns whole groups of 2^fmax rows:
+  // the source needs a whole number of such row sets (thin images take the pass path)
+  const int rpw = 64 / (Sc / 16), g = 1 << fmax, rows_w = rpw > g ? rpw : g;
+  if (Sr < rows_w || Sr % rows_w != 0) return false;
   return true;
 }
 

@@ -57,6 +57,10 @@ def test_config1_blobs_prefix():
     ((32, 128), 3, 4, 2), ((128, 32), 2, 6, 2), ((16, 16), 4, 2, 2), ((4, 4), 2, 1, 2),
     ((128, 128), 4, 2, 2), ((32, 32), 2, 5, 2), ((32, 32), 2, 3, 1), ((32, 32), 2, 9, 2),
     ((32, 32), 2, 1, 2),
+    # thin images: fewer rows than one wave of the fused row pass transforms at a time
+    ((4, 128), 2, 5, 2), ((4, 64), 2, 3, 2), ((8, 64), 3, 2, 2), ((4, 32), 1, 2, 2),
+    # coarse octaves whose grids are too small for the fused row pass
+    ((32, 128), 4, 2, 2), ((64, 128), 4, 3, 2), ((16, 128), 3, 2, 2), ((16, 256), 4, 2, 2),
 ])
 def test_2d_shapes(shape, J, L, max_order):
     rng = np.random.default_rng(hash((shape, J, L)) % 2**32)
