@@ -53,7 +53,7 @@ typedef enum {
  * cascade uses, pre-scaled by the inverse-transform normalisation, stored as fp32) and
  * FFT twiddle tables, uploaded to the current HIP device.
  *
- *   dims       1 or 2
+ *   dims       1 or 2 (3: see below)
  *   shape      host array of `dims` ints; each a power of two and >= 2^J (2-D: rows, cols)
  *   J          number of octaves, >= 1; the output grid is shape >> J
  *   LQ         2-D: number of angles L >= 1;  1-D: first-order wavelets per octave Q >= 1
