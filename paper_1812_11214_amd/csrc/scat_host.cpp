@@ -51,7 +51,8 @@ void morlet_hat_2d(std::vector<double> &out, int n_r, int n_c, double sigma, dou
     }
   const double kappa = gab0 / env0;
   out.assign(static_cast<size_t>(n_r) * n_c, 0.0);
-  for (int kr = 0; kr < n_r; ++kr)
+  // rows are independent: spread over host threads (a 512 x 512 bank takes seconds on one)
+  parallel_for(n_r, [&](int kr) {
     for (int kc = 0; kc < n_c; ++kc) {
       double gab = 0.0, env = 0.0;
       for (int a = -A; a <= A; ++a) {
@@ -64,6 +65,7 @@ void morlet_hat_2d(std::vector<double> &out, int n_r, int n_c, double sigma, dou
       }
       out[static_cast<size_t>(kr) * n_c + kc] = gab - kappa * env;
     }
+  });
   out[0] = 0.0;  // exact zero mean (gab - kappa*env at the origin is 0 up to rounding)
 }
 

@@ -4,6 +4,8 @@
 #pragma once
 
 #include <cstddef>
+#include <atomic>
+#include <thread>
 #include <vector>
 
 namespace scat {
@@ -48,5 +50,31 @@ void build_host_plan(HostPlan &p, int dims, const int *shape, int J, int LQ, int
 
 // Number of second-order wavelets below first-order octave j1, i.e. octaves j1+1 .. J-1.
 inline int num_children_octaves(int J, int j1) { return J - 1 - j1; }
+
+// Runs body(i) for i in [0, count) on up to 16 host threads (the tables of large volumes
+// take seconds on one).
+template <class Fn>
+inline void parallel_for(int count, Fn body) {
+  unsigned hw = std::thread::hardware_concurrency();
+  int workers = static_cast<int>(hw == 0 ? 1 : hw > 16 ? 16 : hw);
+  if (workers > count) workers = count;
+  if (workers <= 1) {
+    for (int i = 0; i < count; ++i) body(i);
+    return;
+  }
+  std::atomic<int> next(0);
+  std::vector<std::thread> pool;
+  auto work = [&] {
+    for (int i = next.fetch_add(1); i < count; i = next.fetch_add(1)) body(i);
+  };
+  try {
+    for (int w = 1; w < workers; ++w) pool.emplace_back(work);
+  } catch (...) {
+    // could not start every thread: the ones that run, and this one, finish the job
+  }
+  work();
+  for (std::thread &t : pool) t.join();
+}
+
 
 }  // namespace scat

@@ -1,5 +1,7 @@
 #include "scat_host3d.hpp"
 
+#include "scat_host.hpp"
+
 #include <cmath>
 
 namespace scat {
@@ -91,47 +93,65 @@ void build_host_plan_3d(HostPlan3D &p, const int *shape, int J, int L, int max_o
   p.psi.assign(static_cast<size_t>(J) * (L + 1), std::vector<double>());
   for (int j = 0; j < J; ++j) {
     const double s = std::ldexp(1.0, j);
-    const int na = j == 0 ? 2 : 1;
+    const int na = j == 0 ? 2 : 1, A = 2 * na + 1;
+    // scaled alias frequencies of every index along each axis
+    std::vector<double> wa[3];
+    for (int d = 0; d < 3; ++d) {
+      wa[d].resize(static_cast<size_t>(shape[d]) * A);
+      for (int k = 0; k < shape[d]; ++k)
+        for (int a = -na; a <= na; ++a)
+          wa[d][static_cast<size_t>(k) * A + a + na] = s * (freq(k, shape[d]) + 2.0 * kPi * a);
+    }
     for (int l = 0; l <= L; ++l) {
       std::vector<double> &tab = p.psi[static_cast<size_t>(j) * (L + 1) + l];
       tab.assign(static_cast<size_t>(2 * l + 1) * n, 0.0);
-      double sh[2 * 8 + 1];
-      for (int k0 = 0; k0 < n0; ++k0)
+      // slices of axis 0 are independent: one thread each, a few at a time
+      auto slice = [&](int k0) {
+        double sh[2 * 8 + 1];
         for (int k1 = 0; k1 < n1; ++k1)
           for (int k2 = 0; k2 < n2; ++k2) {
             const size_t e = (static_cast<size_t>(k0) * n1 + k1) * n2 + k2;
-            for (int a0 = -na; a0 <= na; ++a0)
-              for (int a1 = -na; a1 <= na; ++a1)
-                for (int a2 = -na; a2 <= na; ++a2) {
-                  const double w0 = s * (freq(k0, n0) + 2.0 * kPi * a0);
-                  const double w1 = s * (freq(k1, n1) + 2.0 * kPi * a1);
-                  const double w2 = s * (freq(k2, n2) + 2.0 * kPi * a2);
+            for (int a0 = 0; a0 < A; ++a0) {
+              const double w0 = wa[0][static_cast<size_t>(k0) * A + a0];
+              if (w0 * w0 > 90.0) continue;
+              for (int a1 = 0; a1 < A; ++a1) {
+                const double w1 = wa[1][static_cast<size_t>(k1) * A + a1];
+                if (w0 * w0 + w1 * w1 > 90.0) continue;
+                for (int a2 = 0; a2 < A; ++a2) {
+                  const double w2 = wa[2][static_cast<size_t>(k2) * A + a2];
                   const double r2 = w0 * w0 + w1 * w1 + w2 * w2;
                   if (r2 > 90.0) continue;  // r^8 exp(-45) < 2e-12: below fp32 resolution
                   const double g = std::exp(-0.5 * r2);
                   solid_harmonics(l, w0, w1, w2, sh);
                   for (int m = 0; m < 2 * l + 1; ++m) tab[static_cast<size_t>(m) * n + e] += g * sh[m];
                 }
+              }
+            }
           }
+      };
+      parallel_for(n0, slice);
     }
   }
   // lowpass: Gaussian of std 2^J and unit mass sampled at the integers: its spectrum is
-  // the alias sum of exp(-(sigma |omega + 2 pi a|)^2 / 2)
+  // the alias sum of exp(-(sigma |omega + 2 pi a|)^2 / 2), a product of one sum per axis
   const double sig = std::ldexp(1.0, J);
+  std::vector<double> ph[3];
+  for (int d = 0; d < 3; ++d) {
+    ph[d].resize(shape[d]);
+    for (int k = 0; k < shape[d]; ++k) {
+      double acc = 0.0;
+      for (int a = -1; a <= 1; ++a) {
+        const double w = freq(k, shape[d]) + 2.0 * kPi * a;
+        acc += std::exp(-0.5 * sig * sig * w * w);
+      }
+      ph[d][k] = acc;
+    }
+  }
   p.phi.assign(n, 0.0);
   for (int k0 = 0; k0 < n0; ++k0)
     for (int k1 = 0; k1 < n1; ++k1)
-      for (int k2 = 0; k2 < n2; ++k2) {
-        double acc = 0.0;
-        for (int a0 = -1; a0 <= 1; ++a0)
-          for (int a1 = -1; a1 <= 1; ++a1)
-            for (int a2 = -1; a2 <= 1; ++a2) {
-              const double w0 = freq(k0, n0) + 2.0 * kPi * a0, w1 = freq(k1, n1) + 2.0 * kPi * a1,
-                           w2 = freq(k2, n2) + 2.0 * kPi * a2;
-              acc += std::exp(-0.5 * sig * sig * (w0 * w0 + w1 * w1 + w2 * w2));
-            }
-        p.phi[(static_cast<size_t>(k0) * n1 + k1) * n2 + k2] = acc;
-      }
+      for (int k2 = 0; k2 < n2; ++k2)
+        p.phi[(static_cast<size_t>(k0) * n1 + k1) * n2 + k2] = ph[0][k0] * ph[1][k1] * ph[2][k2];
 }
 
 }  // namespace scat
