@@ -197,4 +197,35 @@ __device__ __forceinline__ void fft_core(float2 (&v)[E], int t, float2 *xch, int
   group_sync<WAVE>();
 }
 
+// fft_core with the E twiddles of this thread read at their point of use from wl[k * ws]
+// (a table in LDS) instead of held in registers across the first stage: for kernels that
+// run several transforms and are short of registers.
+template <int E, int T, bool INV, bool WAVE = false>
+__device__ __forceinline__ void fft_core_tab(float2 (&v)[E], int t, float2 *xch, int sk, int st,
+                                             const float2 *wl, int ws) {
+  DftRegs<E, INV>::run(v);
+  if (T == 1) return;
+#pragma unroll
+  for (int k1 = 1; k1 < E; ++k1) {
+    float2 w = wl[k1 * ws];
+    if (INV) w.y = -w.y;
+    v[k1] = c_mul(v[k1], w);
+  }
+#pragma unroll
+  for (int k1 = 0; k1 < E; ++k1) xch[k1 * sk + t * st] = v[k1];
+  group_sync<WAVE>();
+  constexpr int U = E / T;
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    float2 a[T];
+    const int k1 = t + T * u;
+#pragma unroll
+    for (int j = 0; j < T; ++j) a[j] = xch[k1 * sk + j * st];
+    DftRegs<T, INV>::run(a);
+#pragma unroll
+    for (int k2 = 0; k2 < T; ++k2) v[u + U * k2] = a[k2];
+  }
+  group_sync<WAVE>();
+}
+
 }  // namespace scat

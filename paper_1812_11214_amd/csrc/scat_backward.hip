@@ -12,6 +12,7 @@
 #include <hip/hip_runtime.h>
 
 #include <string>
+#include <type_traits>
 
 #include "fft_regs.hpp"
 #include "scat_kernels.hpp"
@@ -267,7 +268,7 @@ __global__ __launch_bounds__(256) void k_fft_cols(float2 *__restrict__ data, int
 // exp(+2 pi i k1 b / tw_m) before the inverse column transform and by its conjugate after
 // the forward one (the twiddle step of the four-step transform; k1 = row, b = column).
 template <int E, int T>
-__global__ __launch_bounds__(256) void k_cols_modback(float2 *__restrict__ data,
+__global__ __launch_bounds__(256, (E <= 16 ? 4 : 1)) void k_cols_modback(float2 *__restrict__ data,
                                                       const float2 *__restrict__ y, int Mc, int TC,
                                                       int tw_m, const float2 *__restrict__ tw,
                                                       int tw_n) {
@@ -285,36 +286,56 @@ __global__ __launch_bounds__(256) void k_cols_modback(float2 *__restrict__ data,
   float2 v[E];
 #pragma unroll
   for (int i = 0; i < E; ++i) v[i] = p[i * step];
-  float2 fs[E];  // four-step twiddles exp(-2 pi i k1 b / tw_m) of this thread's elements
-  if (tw_m > 0 && E == 16 && T > 1 && tw_m == M * Mc) {
-    // k1 = t + T i, b the column, tw_m = 16 T Mc: the twiddle is exp(-2 pi i t b / tw_m) (one
-    // table read per thread) times exp(-2 pi i i b / (16 Mc)), fetched once for the
-    // workgroup's TC columns into LDS (16 TC entries) instead of 16 scattered reads per thread
+  // four-step twiddles exp(-2 pi i k1 b / tw_m) of this thread's elements.  FACT: k1 = t + T i,
+  // b the column, tw_m = 16 T Mc, so the twiddle is exp(-2 pi i t b / tw_m) (`wa`, one table
+  // read per thread) times exp(-2 pi i i b / (16 Mc)), fetched once for the workgroup's TC
+  // columns into LDS (`ftab`, 16 TC entries behind the exchange area) instead of 16 scattered
+  // reads per thread; they are rebuilt from there after the transforms rather than kept in
+  // registers across them.
+  const bool fact = tw_m > 0 && E == 16 && T > 1 && tw_m == M * Mc;
+  float2 *ftab = lds + E * KS;
+  float2 wa = make_float2(1.f, 0.f);
+  if (fact) {
     const int bmask = 16 * Mc - 1, bstep = tw_n / (16 * Mc);
     for (int idx = threadIdx.x; idx < 16 * TC; idx += blockDim.x) {
       const int i = idx / TC, cc = idx - i * TC;
-      lds[idx] = tw[((i * (c0 + cc)) & bmask) * bstep];
+      ftab[idx] = tw[((i * (c0 + cc)) & bmask) * bstep];
     }
     __syncthreads();
-    const float2 wa = tw[((t * (c0 + c)) & (tw_m - 1)) * (tw_n / tw_m)];
+    wa = tw[((t * (c0 + c)) & (tw_m - 1)) * (tw_n / tw_m)];
 #pragma unroll
     for (int i = 0; i < E; ++i) {
-      fs[i] = c_mul(wa, lds[(i & 15) * TC + c]);
-      v[i] = c_mul(v[i], make_float2(fs[i].x, -fs[i].y));
+      const float2 f = c_mul(wa, ftab[(i & 15) * TC + c]);
+      v[i] = c_mul(v[i], make_float2(f.x, -f.y));
     }
-    __syncthreads();  // the table's place is the exchange area of the transforms below
   } else if (tw_m > 0) {
     const int tstep = tw_n / tw_m;
 #pragma unroll
     for (int i = 0; i < E; ++i) {
       const int e = static_cast<int>((static_cast<long long>(t + T * i) * (c0 + c)) & (tw_m - 1));
-      fs[i] = tw[e * tstep];
-      v[i] = c_mul(v[i], make_float2(fs[i].x, -fs[i].y));
+      const float2 f = tw[e * tstep];
+      v[i] = c_mul(v[i], make_float2(f.x, -f.y));
     }
   }
-  float2 wt[E];
-  load_twiddles<E, T>(wt, t, tw, tw_n);
-  fft_core<E, T, true, false>(v, t, lds + c, KS, TC, wt);
+  // the transforms' own twiddles exp(-2 pi i t k / M), also through LDS (wtab[k T + t]);
+  // 512-point columns (E = 32) fill the LDS with their exchange area and keep them in registers
+  constexpr bool WTAB = E <= 16 && T > 1;
+  float2 *wtab = ftab + 16 * TC;
+  float2 wt[E];  // unused (and dropped by the compiler) with WTAB
+  if constexpr (WTAB) {
+    for (int idx = threadIdx.x; idx < M; idx += blockDim.x)
+      wtab[idx] = tw[(idx / T) * (idx % T) * (tw_n / M)];
+    __syncthreads();
+  } else {
+    load_twiddles<E, T>(wt, t, tw, tw_n);
+  }
+  auto transform = [&](auto inv) {
+    if constexpr (WTAB)
+      fft_core_tab<E, T, decltype(inv)::value, false>(v, t, lds + c, KS, TC, wtab + t, T);
+    else
+      fft_core<E, T, decltype(inv)::value, false>(v, t, lds + c, KS, TC, wt);
+  };
+  transform(std::true_type{});
 #pragma unroll
   for (int i = 0; i < E; ++i) {
     const float2 u = yp[i * step];
@@ -322,10 +343,17 @@ __global__ __launch_bounds__(256) void k_cols_modback(float2 *__restrict__ data,
     const float sgn = m2 > 0.f ? v[i].x / __builtin_amdgcn_sqrtf(m2) : 0.f;
     v[i] = make_float2(u.x * sgn, u.y * sgn);
   }
-  fft_core<E, T, false, false>(v, t, lds + c, KS, TC, wt);
-  if (tw_m > 0) {
+  transform(std::false_type{});
+  if (fact) {
 #pragma unroll
-    for (int i = 0; i < E; ++i) v[i] = c_mul(v[i], fs[i]);
+    for (int i = 0; i < E; ++i) v[i] = c_mul(v[i], c_mul(wa, ftab[(i & 15) * TC + c]));
+  } else if (tw_m > 0) {
+    const int tstep = tw_n / tw_m;
+#pragma unroll
+    for (int i = 0; i < E; ++i) {
+      const int e = static_cast<int>((static_cast<long long>(t + T * i) * (c0 + c)) & (tw_m - 1));
+      v[i] = c_mul(v[i], tw[e * tstep]);
+    }
   }
 #pragma unroll
   for (int i = 0; i < E; ++i) p[i * step] = v[i];
@@ -437,7 +465,10 @@ hipError_t cols_modback_t(float2 *data, const float2 *y, long nodes, int Mc, int
   if (TC > Mc) TC = Mc;
   const long blocks = nodes * (Mc / TC);
   if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
-  const size_t lds = T == 1 ? 0 : static_cast<size_t>(E) * (T * TC + (E == 32 ? 0 : 1)) * sizeof(float2);
+  // exchange area of the transforms, the table of row twiddles, the transforms' twiddles
+  const size_t lds = T == 1 ? 0
+                            : (static_cast<size_t>(E) * (T * TC + (E == 32 ? 0 : 1)) +
+                               (E <= 16 ? 16 * TC + E * T : 0)) * sizeof(float2);
   if (lds > 65536) return hipErrorInvalidValue;
   const std::string name = std::string("k_cols_modback<") + std::to_string(E) + ", " +
                            std::to_string(T) + ">";
@@ -466,6 +497,112 @@ hipError_t rows_lowpass_adj_t(const float2 *ghat, long nodes, int m_r, int m_c, 
   hipLaunchKernelGGL((k_rows_lowpass_adj<E, T>), dim3(static_cast<unsigned>(blocks)), dim3(NT), lds,
                      st, ghat, m_r, m_c, ilog2h(Mr), phi_rows, phi_cols, dst, rows, tw, tw_n);
   return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------
+// 1-D cascade, adjoint of the forward row kernel (k_rows1d_reg): the gradient of a parent's
+// column spectra, dst [nodes][Sr][Sc], from the gradients of its children.  Per row:
+//   dst = IFFT_Sc( sum_c  filt_c * tile_{Sc / m_c}( FFT_{m_c}(src_c row) ) )
+// where child c's row has m_c = Sc >> lg_fold points (tile = adjoint of the fold) and filt_c
+// is the real table [Sr][Sc] of the forward pass; both transforms unnormalised, no twiddles
+// (the four-step twiddles belong to the column kernels on either side).  Which node of src_c
+// belongs to a node of dst is the child's (cm, K) (see Rows1dAdjChild): the children may be
+// separate arrays, the nodes of one array (first order: the wavelets of one octave) or
+// channels of the channel-major array of output gradients.  The parent's
+// spectrum stays in registers over the whole child list (lane t holds k = t + T i), every
+// child is read once, and nothing but dst is written: the unfused form writes each child's
+// spectrum and re-reads and re-writes the parent once per child.
+// Same thread layout as the forward kernel: T lanes per row, 256 / T rows per workgroup,
+// wave-level synchronisation only; the child's transform runs on its m_c / 16 lanes.
+template <int E2, int T2>
+__device__ __forceinline__ void rows1d_child_fwd(float2 *slot, int t, int tw_step,
+                                                 const float2 *twl, const float2 *sp) {
+  if (t >= T2) return;
+  float2 v[E2], wt[E2];
+#pragma unroll
+  for (int i = 0; i < E2; ++i) v[i] = sp[t + T2 * i];
+#pragma unroll
+  for (int k = 0; k < E2; ++k) wt[k] = twl[t * k * tw_step];
+  fft_core<E2, T2, false, true>(v, t, slot, T2 + 1, 1, wt);
+  // the exchange area becomes the child's spectrum in natural order
+#pragma unroll
+  for (int i = 0; i < E2; ++i) slot[t + T2 * i] = v[i];
+}
+
+template <int E, int T>
+__global__ __launch_bounds__(256, 4) void k_rows1d_adj(float2 *__restrict__ dst, long rows, int Sr,
+                                                    Rows1dAdjArgs a,
+                                                    const float2 *__restrict__ tw, int tw_n) {
+  static_assert(E == 16 || T == 1, "short rows are held by one lane");
+  constexpr int Sc = E * T, RPB = 256 / T;
+  constexpr int XS = T == 1 ? E : E * (T + 1);
+  constexpr int lgSc = (E == 4 ? 2 : E == 8 ? 3 : 4) + (T == 1 ? 0 : T == 2 ? 1 : T == 4 ? 2 : T == 8 ? 3 : 4);
+  extern __shared__ float2 lds[];
+  float2 *twl = lds;
+  for (int j = threadIdx.x; j < Sc; j += blockDim.x) twl[j] = tw[j * (tw_n / Sc)];
+  __syncthreads();
+  const int rl = threadIdx.x / T, t = threadIdx.x % T;
+  const long row_raw = static_cast<long>(blockIdx.x) * RPB + rl;
+  const bool valid = row_raw < rows;
+  const long row = valid ? row_raw : rows - 1;  // idle groups redo the last row, unstored
+  const long node = row / Sr;
+  const int k1 = static_cast<int>(row - node * Sr);
+  float2 *slot = lds + Sc + rl * XS;
+  float2 acc[E];
+#pragma unroll
+  for (int i = 0; i < E; ++i) acc[i] = make_float2(0.f, 0.f);
+  for (int ci = 0; ci < a.n; ++ci) {
+    const Rows1dAdjChild &ch = a.c[ci];
+    const int lgm = lgSc - ch.lg_fold, m = 1 << lgm;
+    const long cnode = ch.K > 0 ? (node / ch.cm.G) * ch.K + chan(ch.cm, static_cast<int>(node % ch.cm.G))
+                                : node * ch.cm.G + ch.cm.base;
+    const float2 *sp = ch.src + (static_cast<size_t>(cnode) * Sr + k1) * m;
+    const int tws = Sc >> lgm;
+    switch (lgm) {
+      case 0:
+        if (t == 0) slot[0] = sp[0];
+        break;
+      case 1: rows1d_child_fwd<2, 1>(slot, t, tws, twl, sp); break;
+      case 2: rows1d_child_fwd<4, 1>(slot, t, tws, twl, sp); break;
+      case 3: if (E >= 8) rows1d_child_fwd<(E >= 8 ? 8 : 4), 1>(slot, t, tws, twl, sp); break;
+      case 4: if (E >= 16) rows1d_child_fwd<(E >= 16 ? 16 : 4), 1>(slot, t, tws, twl, sp); break;
+      case 5: if (T >= 2) rows1d_child_fwd<16, (T >= 2 ? 2 : 1)>(slot, t, tws, twl, sp); break;
+      case 6: if (T >= 4) rows1d_child_fwd<16, (T >= 4 ? 4 : 1)>(slot, t, tws, twl, sp); break;
+      case 7: if (T >= 8) rows1d_child_fwd<16, (T >= 8 ? 8 : 1)>(slot, t, tws, twl, sp); break;
+      case 8: if (T >= 16) rows1d_child_fwd<16, (T >= 16 ? 16 : 1)>(slot, t, tws, twl, sp); break;
+      default: break;
+    }
+    wave_sync();
+    // tile: lane t needs the spectrum at (t + T i) mod m.  For m >= T those are its first
+    // m / T registers' worth, repeated; below, the single entry t mod m.
+    float2 s[E];
+#pragma unroll
+    for (int i = 0; i < E; ++i) s[i] = slot[(t + T * i) & (m - 1)];
+    const float *fp = ch.filt + static_cast<size_t>(k1) * Sc + t;
+#pragma unroll
+    for (int i = 0; i < E; ++i) {
+      const float f = fp[T * i];
+      acc[i].x += s[i].x * f;
+      acc[i].y += s[i].y * f;
+    }
+    wave_sync();  // the slot is reused by the next child
+  }
+  float2 wt[E];
+#pragma unroll
+  for (int k = 0; k < E; ++k) wt[k] = twl[t * k];
+  fft_core<E, T, true, true>(acc, t, slot, T + 1, 1, wt);
+  if (!valid) return;
+  float2 *dp = dst + static_cast<size_t>(row) * Sc + t;
+  if (a.accumulate) {
+#pragma unroll
+    for (int i = 0; i < E; ++i) {
+      const float2 o = dp[T * i];
+      acc[i].x += o.x;
+      acc[i].y += o.y;
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < E; ++i) dp[T * i] = acc[i];
 }
 
 }  // namespace
@@ -683,6 +820,53 @@ hipError_t launch_tile_accum(float2 *dst, const float *filt, const float2 *G, lo
   hipLaunchKernelGGL((k_tile_accum<8, SB>), dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st,
                      dst, filt, G, count, S, F, ilog2h(Sr), ilog2h(Sc), ilog2h(Mr), ilog2h(Mc));
   return hipGetLastError();
+}
+
+template <int E, int T>
+hipError_t launch_rows1d_adj_t(float2 *dst, long rows, int Sr, const Rows1dAdjArgs &a, double bytes,
+                               double flops, const float2 *tw, int tw_n, hipStream_t st) {
+  constexpr int Sc = E * T, RPB = 256 / T;
+  constexpr int XS = T == 1 ? E : E * (T + 1);  // as in the kernel
+  const long blocks = (rows + RPB - 1) / RPB;
+  if (blocks <= 0 || blocks > 0x7fffffffL) return hipErrorInvalidValue;
+  const size_t lds = (static_cast<size_t>(Sc) + static_cast<size_t>(RPB) * XS) * sizeof(float2);
+  const std::string name = "k_rows1d_adj<" + std::to_string(E) + ", " + std::to_string(T) + ">";
+  LaunchScope obs(name.c_str(), bytes, flops, st);
+  hipLaunchKernelGGL((k_rows1d_adj<E, T>), dim3(static_cast<unsigned>(blocks)), dim3(256), lds, st, dst,
+                     rows, Sr, a, tw, tw_n);
+  return hipGetLastError();
+}
+
+bool rows1d_adj_supported(int Sc) { return Sc >= 4 && Sc <= 256 && pow2(Sc); }
+
+hipError_t launch_rows1d_adj(float2 *dst, long nodes, int Sr, int Sc, const Rows1dAdjArgs &a,
+                             const float2 *tw, int tw_n, hipStream_t st) {
+  if (nodes <= 0) return hipSuccess;
+  if (a.n < 0 || a.n > kRows1dMaxChildren || !pow2(Sr) || !rows1d_adj_supported(Sc) || tw_n % Sc != 0)
+    return hipErrorInvalidValue;
+  const int lgSc = ilog2h(Sc);
+  double bytes = static_cast<double>(nodes) * Sr * Sc * (a.accumulate ? 16 : 8), flops = 5.0 * Sc * lgSc;
+  for (int i = 0; i < a.n; ++i) {
+    const Rows1dAdjChild &c = a.c[i];
+    if (c.src == nullptr || c.filt == nullptr || c.lg_fold < 0 || c.lg_fold > lgSc ||
+        c.cm.G < 1 || (c.K == 0 && (c.cm.base < 0 || c.cm.base >= c.cm.G)) ||
+        (c.K > 0 && (c.cm.inner < 1 || nodes % c.cm.G != 0)))
+      return hipErrorInvalidValue;
+    const double m = static_cast<double>(Sc >> c.lg_fold);
+    bytes += static_cast<double>(Sr) * Sc * 4 + static_cast<double>(nodes) * Sr * m * 8;
+    flops += 4.0 * Sc + 5.0 * m * (lgSc - c.lg_fold);
+  }
+  const double all_flops = static_cast<double>(nodes) * Sr * flops;
+  const long rows = nodes * Sr;
+  switch (Sc) {
+    case 4: return launch_rows1d_adj_t<4, 1>(dst, rows, Sr, a, bytes, all_flops, tw, tw_n, st);
+    case 8: return launch_rows1d_adj_t<8, 1>(dst, rows, Sr, a, bytes, all_flops, tw, tw_n, st);
+    case 16: return launch_rows1d_adj_t<16, 1>(dst, rows, Sr, a, bytes, all_flops, tw, tw_n, st);
+    case 32: return launch_rows1d_adj_t<16, 2>(dst, rows, Sr, a, bytes, all_flops, tw, tw_n, st);
+    case 64: return launch_rows1d_adj_t<16, 4>(dst, rows, Sr, a, bytes, all_flops, tw, tw_n, st);
+    case 128: return launch_rows1d_adj_t<16, 8>(dst, rows, Sr, a, bytes, all_flops, tw, tw_n, st);
+    default: return launch_rows1d_adj_t<16, 16>(dst, rows, Sr, a, bytes, all_flops, tw, tw_n, st);
+  }
 }
 
 }  // namespace scat

@@ -876,6 +876,16 @@ struct BwdLayout {
   size_t pad_floats = 0;  // padded plans: extended input + extended gradients, floats per plane
 };
 
+// 1-D backward pass: the schedule built on the adjoint of the forward row kernel needs every
+// octave's row length (second digit of the four-step order) within that kernel's range.
+bool bwd1d_rows_adjoint(const scat_plan &p) {
+  const scat::HostPlan &h = p.host;
+  if (h.dims != 1) return false;
+  for (int j = 0; j < h.J; ++j)
+    if (!scat::rows1d_adj_supported(p.n2 >> h.res(j))) return false;
+  return true;
+}
+
 BwdLayout make_bwd_layout(const scat_plan &p, long batch) {
   BwdLayout b;
   const scat::HostPlan &h = p.host;
@@ -890,9 +900,18 @@ BwdLayout make_bwd_layout(const scat_plan &p, long batch) {
     b.fwd.v = 0;
     b.tape = make_tape(p);
     b.gx = n;
-    b.gu = l * n;
-    b.ga = second ? l * (n >> h.res(1)) : 0;
-    b.gh = l * (n >> h.res(h.J));
+    if (bwd1d_rows_adjoint(p)) {
+      // every octave's first-order gradients at once, the second-order gradients of one j1
+      // (all j2 > j1), and the column-transformed output gradients of all K channels
+      b.gu = b.ga = 0;
+      for (int j = 0; j < h.J; ++j) b.gu += l * (n >> h.res(j));
+      for (int j = 1; second && j < h.J; ++j) b.ga += l * (n >> h.res(j));
+      b.gh = static_cast<size_t>(h.K) * (n >> h.res(h.J));
+    } else {
+      b.gu = l * n;
+      b.ga = second ? l * (n >> h.res(1)) : 0;
+      b.gh = l * (n >> h.res(h.J));
+    }
     if (p.padded) b.pad_floats = 2 * n + static_cast<size_t>(h.K) * (n >> h.res(h.J));
     b.per_plane = b.fwd.xh + b.fwd.t + b.fwd.u + (b.tape.total + b.gx + b.gu + b.ga + b.gh) * c8 +
                   b.pad_floats * sizeof(float);
@@ -1061,6 +1080,72 @@ scat_status backward_1d(scat_plan *p, const float *in, const float *gout, float 
     if (e != hipSuccess) return e;
     return scat::launch_fft_rows_inplace(g, nodes * N1, Mc, false, tw, tw_n, st);
   };
+
+  if (bwd1d_rows_adjoint(*p)) {
+    // Adjoint row kernel: a node's gradient (column spectra, ready for the modulus backward)
+    // is one launch over the list of its children -- its own lowpass output and the
+    // second-order nodes below it -- and x's over the first-order nodes of all octaves.
+    auto lg = [](int v) {
+      int r = 0;
+      while ((1 << r) < v) ++r;
+      return r;
+    };
+    // column half of the forward four-step transform of all K output gradients at once
+    SCAT_TRY(scat::launch_gather_real(go, pc * K, ChanMap{K, K, 0, 0}, K, m, GH, st));
+    SCAT_TRY(scat::launch_fft_cols_inplace(GH, pc * K, N1, mc_out, false, tw, tw_n, st));
+    SCAT_TRY(scat::launch_twiddle(GH, pc * K, N1, mc_out, false, tw, tw_n, st));
+    auto low_child = [&](ChanMap cm, int res, int Mc) {
+      return scat::Rows1dAdjChild{GH, tab + p->phi_off[res], lg(Mc / mc_out), cm, K};
+    };
+    scat::Rows1dAdjArgs top{};
+    top.c[top.n++] = low_child(ChanMap{1, 1, 0, 0}, 0, N2);
+    auto flush_top = [&]() -> hipError_t {
+      hipError_t e = scat::launch_rows1d_adj(GX, pc, N1, N2, top, tw, tw_n, st);
+      top.n = 0;
+      top.accumulate = 1;
+      return e;
+    };
+    int s2 = 1 + J * Q;
+    float2 *GUj = GU;
+    for (int j1 = 0; j1 < J; ++j1) {
+      const int r1 = h.res(j1);
+      const int Mc1 = N2 >> r1;
+      const bool kids = h.max_order == 2 && j1 < J - 1;
+      const int octs = J - 1 - j1;
+      scat::Rows1dAdjArgs a{};
+      a.c[a.n++] = low_child(ChanMap{Q, Q, 0, 1 + j1 * Q}, r1, Mc1);
+      float2 *GAj = GA;
+      for (int j2 = j1 + 1; kids && j2 < J; ++j2) {
+        const int r2 = h.res(j2);
+        const int Mc2 = N2 >> r2;
+        scat::Rows1dAdjArgs a2{};
+        a2.c[a2.n++] = low_child(ChanMap{Q, 1, octs, s2 + (j2 - j1 - 1)}, r2, Mc2);
+        SCAT_TRY(scat::launch_rows1d_adj(GAj, pc * Q, N1, Mc2, a2, tw, tw_n, st));
+        SCAT_TRY(scat::launch_cols_modback(GAj, bl.tape.base + bl.tape.y2_off.at({j1, j2}) * pc,
+                                           pc * Q, N1, Mc2, tw, tw_n, st, Mc2 > 1 ? N1 * Mc2 : 0));
+        if (a.n == scat::kRows1dMaxChildren) return SCAT_ERR_ARG;  // J <= 12: at most 12 children
+        a.c[a.n++] = scat::Rows1dAdjChild{GAj, tab + p->psi2_off[{r1, j2}], r2 - r1,
+                                          ChanMap{1, 1, 0, 0}, 0};
+        GAj += static_cast<size_t>(pc) * Q * N1 * Mc2;
+      }
+      if (kids) s2 += Q * octs;
+      SCAT_TRY(scat::launch_rows1d_adj(GUj, pc * Q, N1, Mc1, a, tw, tw_n, st));
+      SCAT_TRY(scat::launch_cols_modback(GUj, bl.tape.base + bl.tape.y1_off[j1] * pc, pc * Q, N1, Mc1,
+                                         tw, tw_n, st, Mc1 > 1 ? N1 * Mc1 : 0));
+      for (int q = 0; q < Q; ++q) {
+        if (top.n == scat::kRows1dMaxChildren) SCAT_TRY(flush_top());
+        top.c[top.n++] = scat::Rows1dAdjChild{
+            GUj, tab + p->psi1_off[j1] + static_cast<size_t>(q) * N, r1, ChanMap{Q, 1, 0, q}, 0};
+      }
+      GUj += static_cast<size_t>(pc) * Q * N1 * Mc1;
+    }
+    SCAT_TRY(flush_top());
+    // g_x = Re(inverse four-step transform): the row half is done, twiddle and columns remain
+    SCAT_TRY(scat::launch_twiddle(GX, pc, N1, N2, true, tw, tw_n, st));
+    SCAT_TRY(scat::launch_fft_cols_inplace(GX, pc, N1, N2, true, tw, tw_n, st));
+    SCAT_TRY(scat::launch_take_real(GX, gi, pc * static_cast<long>(N), st));
+    return SCAT_OK;
+  }
 
   SCAT_TRY(lowpass_adj(pc, ChanMap{1, 1, 0, 0}, 0, N2, GX));
   int s2_base = 1 + J * Q;

@@ -78,6 +78,28 @@ struct Rows1dArgs {
 hipError_t launch_rows1d(const float2 *src, long nodes, int Sr, int Sc, const Rows1dArgs &a,
                          const float2 *tw, int tw_n, hipStream_t st);
 
+// Adjoint of launch_rows1d: dst [nodes][Sr][Sc] (= or +=) the inverse row FFT of
+// sum_c filt_c * tile(forward row FFT of child c), child rows of Sc >> lg_fold points (see
+// k_rows1d_adj).  Node g of dst reads node number
+//   K == 0:  g * cm.G + cm.base                       (one of the cm.G nodes under each parent)
+//   K  > 0:  (g / cm.G) * K + channel(cm, g % cm.G)   (channel-major arrays, as Rows1dChild)
+// of c.src.
+struct Rows1dAdjChild {
+  const float2 *src;
+  const float *filt;  // [Sr][Sc], the table of the forward pass
+  int lg_fold;
+  ChanMap cm;
+  int K;
+};
+struct Rows1dAdjArgs {
+  int n;
+  int accumulate;  // 0: dst is overwritten; 1: added to
+  Rows1dAdjChild c[kRows1dMaxChildren];
+};
+bool rows1d_adj_supported(int Sc);
+hipError_t launch_rows1d_adj(float2 *dst, long nodes, int Sr, int Sc, const Rows1dAdjArgs &a,
+                             const float2 *tw, int tw_n, hipStream_t st);
+
 hipError_t launch_row_fwd(float2 *data, long rows, int Mc, const float2 *tw, int tw_n,
                           hipStream_t st);
 
