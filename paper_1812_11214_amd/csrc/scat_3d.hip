@@ -9,6 +9,7 @@
 #include <string>
 
 #include "fft_regs.hpp"
+#include "slab_fft.hpp"
 #include "scat_kernels.hpp"
 
 namespace scat {
@@ -182,46 +183,6 @@ __global__ __launch_bounds__(256) void k3_sample(const float2 *__restrict__ src,
 //                     lowpass and the sum over the aliases of the slab axes (periodic
 //                     subsampling by 2^J seen from the Fourier side)
 //   k3_fold0          the aliases of axis 0; the small inverse transforms then give S
-
-// row stride of a slab in LDS: room for the row exchange of fft_core (16 (T2 + 1) elements)
-// plus a skew that spreads the rows of one wavefront over the banks
-__host__ __device__ constexpr int slab_row_stride(int N2) {
-  return N2 == 16 ? 17 : N2 == 256 ? N2 + 48 : N2 + 16 + N2 / 16;
-}
-
-template <int N1, int N2>
-struct Slab {
-  static constexpr int T1 = N1 / 16, T2 = N2 / 16;
-  static constexpr int TS = N1 * N2 / 16;       // threads per slab, 16 points each
-  static constexpr int NT = TS < 256 ? 256 : TS;  // threads per workgroup
-  static constexpr int SPW = NT / TS;           // slabs per workgroup
-  static constexpr int RS = slab_row_stride(N2);
-  static constexpr size_t lds_bytes = static_cast<size_t>(SPW) * N1 * RS * sizeof(float2);
-  static_assert(N1 >= 16 && N2 >= 16 && TS <= 1024 && TS >= 16 && lds_bytes <= 160 * 1024,
-                "slab shape");
-
-  // v: this thread's 16 points of row r (columns t + T2 i) -> after the call its 16 points
-  // of column c (rows t1 + T1 i) of the slab transformed along both axes.  The twiddles are
-  // fetched right before each transform so that they are not live across the whole kernel.
-  template <bool INV>
-  static __device__ __forceinline__ void transform(float2 (&v)[16], float2 *area, int r, int t, int c,
-                                                   int t1, const float2 *__restrict__ tw, int tw_n) {
-    {
-      float2 wr[16];
-      load_twiddles<16, T2>(wr, t, tw, tw_n);
-      fft_core<16, T2, INV, false>(v, t, area + r * RS, T2 + 1, 1, wr);
-    }
-#pragma unroll
-    for (int i = 0; i < 16; ++i) area[r * RS + t + T2 * i] = v[i];
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < 16; ++i) v[i] = area[(t1 + T1 * i) * RS + c];
-    __syncthreads();
-    float2 wc[16];
-    load_twiddles<16, T1>(wc, t1, tw, tw_n);
-    fft_core<16, T1, INV, false>(v, t1, area + c, T1 * RS, RS, wc);
-  }
-};
 
 template <int N1, int N2, bool SPLIT>
 __global__ __launch_bounds__((Slab<N1, N2>::NT)) void k3_slab_mul_inv(const float2 *__restrict__ Fh,

@@ -15,6 +15,7 @@
 #include <type_traits>
 
 #include "fft_regs.hpp"
+#include "slab_fft.hpp"
 #include "scat_kernels.hpp"
 
 namespace scat {
@@ -117,6 +118,38 @@ __global__ __launch_bounds__(256) void k_small_fft2(const float *__restrict__ go
     float2 acc = make_float2(0.f, 0.f);
     for (int r = 0; r < m_r; ++r) acc = c_add(acc, c_mul(s1[r * m_c + kc], twr[(r * kr) & (m_r - 1)]));
     op[i] = acc;
+  }
+}
+
+// k_small_fft2 for planes of 16 ... 128 points a side (square or 2 : 1) by the slab
+// transform: 16 points per thread, a 32 x 32 plane per wavefront.
+template <int N1, int N2>
+__global__ __launch_bounds__((Slab<N1, N2>::NT)) void k_slab_fft2_real(const float *__restrict__ gout,
+                                                                      ChanMap cm, int K,
+                                                                      float2 *__restrict__ ghat,
+                                                                      long nodes,
+                                                                      const float2 *__restrict__ tw,
+                                                                      int tw_n) {
+  using S = Slab<N1, N2>;
+  extern __shared__ float2 lds[];
+  const int s = threadIdx.x / S::TS, q = threadIdx.x % S::TS;
+  const long node_raw = static_cast<long>(blockIdx.x) * S::SPW + s;
+  const bool live = node_raw < nodes;
+  const long node = live ? node_raw : nodes - 1;  // idle threads shadow the last node, store nothing
+  float2 *area = lds + s * N1 * S::RS;
+  const int r = q / S::T2, t = q % S::T2;
+  const int c = q % N2, t1 = q / N2;
+  const long p = node / cm.G;
+  const int g = static_cast<int>(node - p * cm.G);
+  const float *gp = gout + (static_cast<size_t>(p) * K + chan(cm, g)) * (N1 * N2) + r * N2 + t;
+  float2 v[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) v[i] = make_float2(gp[S::T2 * i], 0.f);
+  S::template transform<false>(v, area, r, t, c, t1, tw, tw_n);
+  if (live) {
+    float2 *op = ghat + static_cast<size_t>(node) * (N1 * N2) + c;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) op[(t1 + S::T1 * i) * N2] = v[i];
   }
 }
 
@@ -605,6 +638,150 @@ __global__ __launch_bounds__(256, 4) void k_rows1d_adj(float2 *__restrict__ dst,
   for (int i = 0; i < E; ++i) dp[T * i] = acc[i];
 }
 
+// ------------------------------------------------------------------------------------
+// 2-D cascade: the gradient spectrum of a parent, dst [nodes][Sr][Sc], from the gradient
+// spectra of all its children in one pass,
+//   dst[kr][kc] (+)= sum_c filt_c[kr][kc] * src_c[kr mod (Sr >> fr_c)][kc mod (Sc >> fc_c)]
+// (the adjoint of filter product + fold, for every child at once), optionally followed by
+// the inverse row transform that the modulus backward step of the parent starts with.
+// filt_c is a table [Sr][Sc], or with filt_row != nullptr the separable filt_row[kr] filt[kc]
+// (lowpass; its src is the small transform of the parent's own output gradient).  Nodes of
+// the children as in Rows1dAdjChild.  T lanes per row hold the parent's row in registers
+// over the child list; dst is written once (the one-child-level-per-launch form re-reads
+// and re-writes it for every level, and once more for the row transform).
+template <int E, int T>
+__global__ __launch_bounds__(256, 4) void k_rows2d_adj(float2 *__restrict__ dst, long nodes, int Sr,
+                                                    Rows2dAdjArgs a,
+                                                    const float2 *__restrict__ tw, int tw_n) {
+  static_assert(E == 16 || T == 1, "short rows are held by one lane");
+  constexpr int Sc = E * T, RPB = 256 / T;
+  constexpr int XS = T == 1 ? E : E * (T + 1);
+  extern __shared__ float2 lds[];
+  // A workgroup takes 2^lgR rows kr0 + a (Sr >> lgR) of each of its nodes: the rows that
+  // read the same rows of the folded children (2^lgR = the largest fold of the list, at most
+  // 256 / T), so that those are fetched from memory once; its nodes share the filters' rows.
+  const int rl = threadIdx.x / T, t = threadIdx.x % T;
+  const int lgR = a.lg_rows, span = Sr >> lgR;
+  const int kr = static_cast<int>(blockIdx.x % span) + (rl & ((1 << lgR) - 1)) * span;
+  const long node_raw = static_cast<long>(blockIdx.x / span) * (RPB >> lgR) + (rl >> lgR);
+  const bool valid = node_raw < nodes;
+  const long node = valid ? node_raw : nodes - 1;  // idle groups redo the last node, unstored
+  const long row = node * Sr + kr;
+  float2 acc[E];
+#pragma unroll
+  for (int i = 0; i < E; ++i) acc[i] = make_float2(0.f, 0.f);
+  for (int ci = 0; ci < a.n; ++ci) {
+    const Rows2dAdjChild &ch = a.c[ci];
+    const int Mr = Sr >> ch.lg_fr, m = Sc >> ch.lg_fc;
+    const long cnode = ch.K > 0 ? (node / ch.cm.G) * ch.K + chan(ch.cm, static_cast<int>(node % ch.cm.G))
+                                : node * ch.cm.G + ch.cm.base;
+    const float2 *sp = ch.src + (static_cast<size_t>(cnode) * Mr + (kr & (Mr - 1))) * m;
+    // lane t needs the child's row at (t + T i) mod m: its first m / T values repeat
+    float2 sv[E];
+#pragma unroll
+    for (int i = 0; i < E; ++i)
+      if (i == 0 || t + T * i < m) sv[i] = sp[(t + T * i) & (m - 1)];
+#pragma unroll
+    for (int h = 1; h < E; h <<= 1)
+      if (T * h >= m) {
+#pragma unroll
+        for (int i = 0; i < h; ++i) sv[i + h] = sv[i];
+      }
+    if (ch.filt_row != nullptr) {
+      const float fr = ch.filt_row[kr];
+#pragma unroll
+      for (int i = 0; i < E; ++i) {
+        const float f = fr * ch.filt[t + T * i];
+        acc[i].x += sv[i].x * f;
+        acc[i].y += sv[i].y * f;
+      }
+    } else {
+      const float *fp = ch.filt + static_cast<size_t>(kr) * Sc + t;
+#pragma unroll
+      for (int i = 0; i < E; ++i) {
+        const float f = fp[T * i];
+        acc[i].x += sv[i].x * f;
+        acc[i].y += sv[i].y * f;
+      }
+    }
+  }
+  if (a.inverse) {
+    float2 wt[E];
+    load_twiddles<E, T>(wt, t, tw, tw_n);
+    fft_core<E, T, true, true>(acc, t, lds + rl * XS, T + 1, 1, wt);
+  }
+  if (!valid) return;
+  float2 *dp = dst + static_cast<size_t>(row) * Sc + t;
+  if (a.accumulate) {
+#pragma unroll
+    for (int i = 0; i < E; ++i) {
+      const float2 o = dp[T * i];
+      acc[i].x += o.x;
+      acc[i].y += o.y;
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < E; ++i) dp[T * i] = acc[i];
+}
+
+// ------------------------------------------------------------------------------------
+// Modulus backward step of whole nodes of N1 x N2 points (at most 16384) in one pass, the
+// node held by one workgroup (slab_fft.hpp): gradient spectrum -> inverse 2-D transform ->
+// a = Re(a) y / |y| against the taped y -> forward 2-D transform -> gradient spectrum of y.
+// LOW: the incoming spectrum is the node's adjoint lowpass, built on the fly from the small
+// transform ghat [node][m_r][m_c] of its output gradient: ghat tiled over the node times
+// phi_rows[k_r] phi_cols[k_c]; otherwise it is read from `data` (and replaced).
+// Per point: the tape read and the spectrum written (plus the spectrum read without LOW),
+// where the separate row and column passes read and write the node three times.
+template <int N1, int N2, bool LOW>
+__global__ __launch_bounds__((Slab<N1, N2>::NT)) void k_node_modback(
+    const float2 *__restrict__ ghat, int m_r, int m_c, const float *__restrict__ phi_rows,
+    const float *__restrict__ phi_cols, const float2 *__restrict__ y, float2 *__restrict__ data,
+    long nodes, const float2 *__restrict__ tw, int tw_n) {
+  using S = Slab<N1, N2>;
+  extern __shared__ float2 lds[];
+  const int s = threadIdx.x / S::TS, q = threadIdx.x % S::TS;
+  const long node_raw = static_cast<long>(blockIdx.x) * S::SPW + s;
+  const bool live = node_raw < nodes;
+  const long node = live ? node_raw : nodes - 1;  // idle threads shadow the last node, store nothing
+  float2 *area = lds + s * N1 * S::RS;
+  const int r = q / S::T2, t = q % S::T2;
+  const int c = q % N2, t1 = q / N2;
+  const size_t base = static_cast<size_t>(node) * N1 * N2;
+  float2 *row = data + base + r * N2 + t;
+  float2 v[16];
+  if (LOW) {
+    const float2 *gp = ghat + static_cast<size_t>(node) * m_r * m_c + (r & (m_r - 1)) * m_c;
+    const float fr = phi_rows[r];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int kc = t + S::T2 * i;
+      const float2 g = gp[kc & (m_c - 1)];
+      const float f = fr * phi_cols[kc];
+      v[i] = make_float2(g.x * f, g.y * f);
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) v[i] = row[S::T2 * i];
+  }
+  S::template transform<true>(v, area, r, t, c, t1, tw, tw_n);
+  {
+    const float2 *yp = y + base + c;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const float2 u = yp[(t1 + S::T1 * i) * N2];
+      const float m2 = u.x * u.x + u.y * u.y;
+      const float sgn = m2 > 0.f ? v[i].x / __builtin_amdgcn_sqrtf(m2) : 0.f;
+      v[i] = make_float2(u.x * sgn, u.y * sgn);
+    }
+  }
+  S::template transform_back<false>(v, area, r, t, c, t1, tw, tw_n);
+  if (live) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) row[S::T2 * i] = v[i];
+  }
+}
+
 }  // namespace
 
 bool backward_side_supported(int m) { return pow2(m) && m >= 4 && m <= 512; }
@@ -758,6 +935,67 @@ hipError_t launch_lowpass_adj(const float *gout, long nodes, ChanMap cm, int K, 
   return hipGetLastError();
 }
 
+// node shapes of k_node_modback: sides 16 ... 128, square or 2 : 1
+bool node_modback_supported(int Mr, int Mc) {
+  return pow2(Mr) && pow2(Mc) && Mr >= 16 && Mc >= 16 && Mr <= 128 && Mc <= 128 &&
+         (Mr == Mc || Mr == 2 * Mc || Mc == 2 * Mr);
+}
+
+#define SCAT_NODE_DISPATCH(CALL)            \
+  switch ((Mr << 12) | Mc) {                \
+    case (16 << 12) | 16: CALL(16, 16);     \
+    case (16 << 12) | 32: CALL(16, 32);     \
+    case (32 << 12) | 16: CALL(32, 16);     \
+    case (32 << 12) | 32: CALL(32, 32);     \
+    case (32 << 12) | 64: CALL(32, 64);     \
+    case (64 << 12) | 32: CALL(64, 32);     \
+    case (64 << 12) | 64: CALL(64, 64);     \
+    case (64 << 12) | 128: CALL(64, 128);   \
+    case (128 << 12) | 64: CALL(128, 64);   \
+    case (128 << 12) | 128: CALL(128, 128); \
+    default: return hipErrorInvalidValue;   \
+  }
+
+template <int N1, int N2>
+hipError_t slab_fft2_real_t(const float *gout, long nodes, ChanMap cm, int K, float2 *ghat,
+                            const float2 *tw, int tw_n, hipStream_t st) {
+  using S = Slab<N1, N2>;
+  const long blocks = (nodes + S::SPW - 1) / S::SPW;
+  if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
+  const std::string name = "k_slab_fft2_real<" + std::to_string(N1) + ", " + std::to_string(N2) + ">";
+  const double pts = static_cast<double>(nodes) * N1 * N2;
+  LaunchScope obs(name.c_str(), pts * 12.0, pts * 5.0 * (ilog2h(N1) + ilog2h(N2)), st);
+  if (S::lds_bytes > 65536) {
+    static unsigned long long lds_ok = 0;
+    hipError_t e = allow_large_lds(reinterpret_cast<const void *>(k_slab_fft2_real<N1, N2>), lds_ok);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL((k_slab_fft2_real<N1, N2>), dim3(static_cast<unsigned>(blocks)), dim3(S::NT),
+                     S::lds_bytes, st, gout, cm, K, ghat, nodes, tw, tw_n);
+  return hipGetLastError();
+}
+
+// ghat [node][m_r][m_c] = FFT2 of the nodes' output gradient planes
+hipError_t launch_small_fft2(const float *gout, long nodes, ChanMap cm, int K, int m_r, int m_c,
+                             float2 *ghat, const float2 *tw, int tw_n, hipStream_t st) {
+  if (nodes <= 0) return hipSuccess;
+  if (!pow2(m_r) || !pow2(m_c) || m_r * m_c > 1024 || tw_n % m_r != 0 || tw_n % m_c != 0 ||
+      nodes > 0x7fffffffL || cm.G < 1 || cm.inner < 1 || nodes % cm.G != 0)
+    return hipErrorInvalidValue;
+  if (node_modback_supported(m_r, m_c)) {
+    const int Mr = m_r, Mc = m_c;
+#define SCAT_SF(A_, B_) return slab_fft2_real_t<A_, B_>(gout, nodes, cm, K, ghat, tw, tw_n, st)
+    SCAT_NODE_DISPATCH(SCAT_SF)
+#undef SCAT_SF
+  }
+  const size_t lds = static_cast<size_t>(m_r) * m_c * (sizeof(float2) + sizeof(float)) +
+                     static_cast<size_t>(m_r + m_c) * sizeof(float2);
+  LaunchScope obs("k_small_fft2", nodes * 12.0 * m_r * m_c, nodes * 8.0 * m_r * m_c * (m_r + m_c), st);
+  hipLaunchKernelGGL(k_small_fft2, dim3(static_cast<unsigned>(nodes)), dim3(256), lds, st, gout, cm, K,
+                     m_r, m_c, ghat, tw, tw_n);
+  return hipGetLastError();
+}
+
 // Adjoint lowpass fused with the inverse row transform: dst [nodes][Mr][Mc] = inverse row
 // FFT of ( FFT2(g_out node)[k mod m] phi_rows[k_r] phi_cols[k_c] ); `ghat` is scratch for
 // the small transforms, nodes * m_r * m_c elements.
@@ -771,13 +1009,7 @@ hipError_t launch_lowpass_adj_rows(const float *gout, long nodes, ChanMap cm, in
       tw_n % m_c != 0 || nodes > 0x7fffffffL)
     return hipErrorInvalidValue;
   {
-    const size_t lds = static_cast<size_t>(m_r) * m_c * (sizeof(float2) + sizeof(float)) +
-                       static_cast<size_t>(m_r + m_c) * sizeof(float2);
-    LaunchScope obs("k_small_fft2", nodes * 12.0 * m_r * m_c, nodes * 8.0 * m_r * m_c * (m_r + m_c),
-                    st);
-    hipLaunchKernelGGL(k_small_fft2, dim3(static_cast<unsigned>(nodes)), dim3(256), lds, st, gout, cm,
-                       K, m_r, m_c, ghat, tw, tw_n);
-    hipError_t e = hipGetLastError();
+    hipError_t e = launch_small_fft2(gout, nodes, cm, K, m_r, m_c, ghat, tw, tw_n, st);
     if (e != hipSuccess) return e;
   }
 #define SCAT_RLA(E_, T_) \
@@ -866,6 +1098,110 @@ hipError_t launch_rows1d_adj(float2 *dst, long nodes, int Sr, int Sc, const Rows
     case 64: return launch_rows1d_adj_t<16, 4>(dst, rows, Sr, a, bytes, all_flops, tw, tw_n, st);
     case 128: return launch_rows1d_adj_t<16, 8>(dst, rows, Sr, a, bytes, all_flops, tw, tw_n, st);
     default: return launch_rows1d_adj_t<16, 16>(dst, rows, Sr, a, bytes, all_flops, tw, tw_n, st);
+  }
+}
+
+template <int N1, int N2, bool LOW>
+hipError_t node_modback_t(const float2 *ghat, int m_r, int m_c, const float *phi_rows,
+                          const float *phi_cols, const float2 *y, float2 *data, long nodes,
+                          const float2 *tw, int tw_n, hipStream_t st) {
+  using S = Slab<N1, N2>;
+  const long blocks = (nodes + S::SPW - 1) / S::SPW;
+  if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
+  const std::string name = "k_node_modback<" + std::to_string(N1) + ", " + std::to_string(N2) +
+                           (LOW ? ", true>" : ", false>");
+  const double pts = static_cast<double>(nodes) * N1 * N2;
+  LaunchScope obs(name.c_str(), pts * (LOW ? 16.0 : 24.0) + (LOW ? nodes * 8.0 * m_r * m_c : 0.0),
+                  pts * (10.0 * (ilog2h(N1) + ilog2h(N2)) + 8.0), st);
+  if (S::lds_bytes > 65536) {
+    static unsigned long long lds_ok = 0;
+    hipError_t e = allow_large_lds(reinterpret_cast<const void *>(k_node_modback<N1, N2, LOW>), lds_ok);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL((k_node_modback<N1, N2, LOW>), dim3(static_cast<unsigned>(blocks)), dim3(S::NT),
+                     S::lds_bytes, st, ghat, m_r, m_c, phi_rows, phi_cols, y, data, nodes, tw, tw_n);
+  return hipGetLastError();
+}
+
+hipError_t launch_node_modback(float2 *data, const float2 *y, long nodes, int Mr, int Mc,
+                               const float2 *tw, int tw_n, hipStream_t st) {
+  if (nodes <= 0) return hipSuccess;
+  if (!node_modback_supported(Mr, Mc) || tw_n % Mr != 0 || tw_n % Mc != 0 || data == nullptr ||
+      y == nullptr)
+    return hipErrorInvalidValue;
+#define SCAT_NM(A_, B_) \
+  return node_modback_t<A_, B_, false>(nullptr, 1, 1, nullptr, nullptr, y, data, nodes, tw, tw_n, st)
+  SCAT_NODE_DISPATCH(SCAT_NM)
+#undef SCAT_NM
+}
+
+hipError_t launch_node_modback_low(const float *gout, long nodes, ChanMap cm, int K, int m_r, int m_c,
+                                   int Mr, int Mc, const float *phi_rows, const float *phi_cols,
+                                   float2 *ghat, const float2 *y, float2 *dst, const float2 *tw,
+                                   int tw_n, hipStream_t st) {
+  if (nodes <= 0) return hipSuccess;
+  if (!node_modback_supported(Mr, Mc) || !pow2(m_r) || !pow2(m_c) || m_r > Mr || m_c > Mc ||
+      m_r * m_c > 1024 || tw_n % Mr != 0 || tw_n % Mc != 0 || tw_n % m_r != 0 || tw_n % m_c != 0 ||
+      nodes > 0x7fffffffL || cm.G < 1 || cm.inner < 1 || nodes % cm.G != 0)
+    return hipErrorInvalidValue;
+  {
+    hipError_t e = launch_small_fft2(gout, nodes, cm, K, m_r, m_c, ghat, tw, tw_n, st);
+    if (e != hipSuccess) return e;
+  }
+#define SCAT_NL(A_, B_) \
+  return node_modback_t<A_, B_, true>(ghat, m_r, m_c, phi_rows, phi_cols, y, dst, nodes, tw, tw_n, st)
+  SCAT_NODE_DISPATCH(SCAT_NL)
+#undef SCAT_NL
+}
+
+template <int E, int T>
+hipError_t launch_rows2d_adj_t(float2 *dst, long nodes, int Sr, Rows2dAdjArgs a, double bytes,
+                               double flops, const float2 *tw, int tw_n, hipStream_t st) {
+  constexpr int RPB = 256 / T;
+  constexpr int XS = T == 1 ? E : E * (T + 1);  // as in the kernel
+  // rows per node and workgroup: the largest row fold of the list (see the kernel)
+  a.lg_rows = 0;
+  for (int i = 0; i < a.n; ++i)
+    if (a.c[i].lg_fr > a.lg_rows) a.lg_rows = a.c[i].lg_fr;
+  while ((1 << a.lg_rows) > RPB || (1 << a.lg_rows) > Sr) --a.lg_rows;
+  const int npb = RPB >> a.lg_rows;
+  const long blocks = ((nodes + npb - 1) / npb) * (Sr >> a.lg_rows);
+  if (blocks <= 0 || blocks > 0x7fffffffL) return hipErrorInvalidValue;
+  const size_t lds = static_cast<size_t>(RPB) * XS * sizeof(float2);
+  const std::string name = "k_rows2d_adj<" + std::to_string(E) + ", " + std::to_string(T) + ">";
+  LaunchScope obs(name.c_str(), bytes, flops, st);
+  hipLaunchKernelGGL((k_rows2d_adj<E, T>), dim3(static_cast<unsigned>(blocks)), dim3(256), lds, st, dst,
+                     nodes, Sr, a, tw, tw_n);
+  return hipGetLastError();
+}
+
+hipError_t launch_rows2d_adj(float2 *dst, long nodes, int Sr, int Sc, const Rows2dAdjArgs &a,
+                             const float2 *tw, int tw_n, hipStream_t st) {
+  if (nodes <= 0) return hipSuccess;
+  if (a.n < 0 || a.n > kRows1dMaxChildren || !pow2(Sr) || !rows1d_adj_supported(Sc) || tw_n % Sc != 0)
+    return hipErrorInvalidValue;
+  const int lgSc = ilog2h(Sc), lgSr = ilog2h(Sr);
+  double bytes = static_cast<double>(nodes) * Sr * Sc * (a.accumulate ? 16 : 8);
+  double flops = a.inverse ? 5.0 * Sc * lgSc : 0.0;
+  for (int i = 0; i < a.n; ++i) {
+    const Rows2dAdjChild &c = a.c[i];
+    if (c.src == nullptr || c.filt == nullptr || c.lg_fr < 0 || c.lg_fr > lgSr || c.lg_fc < 0 ||
+        c.lg_fc > lgSc || c.cm.G < 1 || (c.K == 0 && (c.cm.base < 0 || c.cm.base >= c.cm.G)) ||
+        (c.K > 0 && (c.cm.inner < 1 || nodes % c.cm.G != 0)))
+      return hipErrorInvalidValue;
+    bytes += (c.filt_row != nullptr ? 0.0 : static_cast<double>(Sr) * Sc * 4) +
+             static_cast<double>(nodes) * (Sr >> c.lg_fr) * (Sc >> c.lg_fc) * 8;
+    flops += 4.0 * Sc;
+  }
+  const double all_flops = static_cast<double>(nodes) * Sr * flops;
+  switch (Sc) {
+    case 4: return launch_rows2d_adj_t<4, 1>(dst, nodes, Sr, a, bytes, all_flops, tw, tw_n, st);
+    case 8: return launch_rows2d_adj_t<8, 1>(dst, nodes, Sr, a, bytes, all_flops, tw, tw_n, st);
+    case 16: return launch_rows2d_adj_t<16, 1>(dst, nodes, Sr, a, bytes, all_flops, tw, tw_n, st);
+    case 32: return launch_rows2d_adj_t<16, 2>(dst, nodes, Sr, a, bytes, all_flops, tw, tw_n, st);
+    case 64: return launch_rows2d_adj_t<16, 4>(dst, nodes, Sr, a, bytes, all_flops, tw, tw_n, st);
+    case 128: return launch_rows2d_adj_t<16, 8>(dst, nodes, Sr, a, bytes, all_flops, tw, tw_n, st);
+    default: return launch_rows2d_adj_t<16, 16>(dst, nodes, Sr, a, bytes, all_flops, tw, tw_n, st);
   }
 }
 

@@ -876,11 +876,11 @@ struct BwdLayout {
   size_t pad_floats = 0;  // padded plans: extended input + extended gradients, floats per plane
 };
 
-// 1-D backward pass: the schedule built on the adjoint of the forward row kernel needs every
-// octave's row length (second digit of the four-step order) within that kernel's range.
-bool bwd1d_rows_adjoint(const scat_plan &p) {
+// Backward pass, 1-D and 2-D: the schedules built on the row-adjoint kernels (a node's
+// gradient from all its children in one launch) need every octave's row length (1-D: second
+// digit of the four-step order) within those kernels' range.
+bool bwd_rows_adjoint(const scat_plan &p) {
   const scat::HostPlan &h = p.host;
-  if (h.dims != 1) return false;
   for (int j = 0; j < h.J; ++j)
     if (!scat::rows1d_adj_supported(p.n2 >> h.res(j))) return false;
   return true;
@@ -900,7 +900,7 @@ BwdLayout make_bwd_layout(const scat_plan &p, long batch) {
     b.fwd.v = 0;
     b.tape = make_tape(p);
     b.gx = n;
-    if (bwd1d_rows_adjoint(p)) {
+    if (bwd_rows_adjoint(p)) {
       // every octave's first-order gradients at once, the second-order gradients of one j1
       // (all j2 > j1), and the column-transformed output gradients of all K channels
       b.gu = b.ga = 0;
@@ -936,7 +936,16 @@ BwdLayout make_bwd_layout(const scat_plan &p, long batch) {
     b.gu = l * n;
     b.ga = t2;
     // spectra of the output-grid gradient planes of one launch (at most L*L, or L, nodes)
-    b.gh = (second ? l * l : l) * static_cast<size_t>(p.n1 >> h.res(h.J)) * (p.n2 >> h.res(h.J));
+    const size_t mm = static_cast<size_t>(p.n1 >> h.res(h.J)) * (p.n2 >> h.res(h.J));
+    b.gh = (second ? l * l : l) * mm;
+    if (bwd_rows_adjoint(p)) {
+      // every octave's first-order gradients at once, the second-order gradients of one j1
+      // (all j2 > j1); output-grid spectra of x's and of one octave's own channels besides
+      b.gu = b.ga = 0;
+      for (int j = 0; j < h.J; ++j) b.gu += l * (n >> (2 * h.res(j)));
+      for (int j = 1; second && j < h.J; ++j) b.ga += l * l * (n >> (2 * h.res(j)));
+      b.gh += (l + 1) * mm;
+    }
     if (p.padded)
       b.pad_floats = 2 * n + static_cast<size_t>(h.K) * (p.n1 >> h.res(h.J)) * (p.n2 >> h.res(h.J));
     b.per_plane = b.fwd.xh + b.fwd.t + b.fwd.u + b.fwd.v +
@@ -949,6 +958,119 @@ BwdLayout make_bwd_layout(const scat_plan &p, long batch) {
   b.fwd.chunk = c;
   b.fwd.per_plane = b.per_plane;
   return b;
+}
+
+// ---- backward pass of the 2-D cascade for one chunk, schedule built on k_rows2d_adj: the
+// gradient spectrum of a first-order node is one launch over its own lowpass term and all
+// its second-order children, x's over its lowpass term and all first-order nodes; nodes
+// that fit one workgroup take the modulus backward step in a single kernel.
+scat_status backward_2d_rows_adjoint(scat_plan *p, const float *go, float *gi, long pc, BwdLayout &bl,
+                                     float2 *GX, float2 *GU, float2 *GA, float2 *GH, hipStream_t st) {
+  const scat::HostPlan &h = p->host;
+  const int J = h.J, L = h.LQ, K = h.K;
+  const int Nr = p->n1, Nc = p->n2;
+  const int rJ = h.res(J);
+  const int m_r = Nr >> rJ, m_c = Nc >> rJ;
+  const size_t n = static_cast<size_t>(Nr) * Nc, mm = static_cast<size_t>(m_r) * m_c;
+  const float *tab = p->d_tables;
+  const float2 *tw = p->d_tw;
+  const int tw_n = p->tw_n;
+  const bool second = h.max_order == 2 && J >= 2;
+  auto lg = [](int v) {
+    int r = 0;
+    while ((1 << r) < v) ++r;
+    return r;
+  };
+  // GH: scratch of the node kernels' launches, then the small transforms of x's and of the
+  // current octave's output gradients
+  float2 *GHX = GH + (second ? static_cast<size_t>(L) * L : static_cast<size_t>(L)) * mm * pc;
+  float2 *GHU = GHX + mm * pc;
+  auto low_child = [&](const float2 *ghat, int res, int Mr, int Mc) {
+    return scat::Rows2dAdjChild{ghat, tab + p->phi_cols_off[res], tab + p->phi_rows_off[res],
+                                lg(Mr / m_r), lg(Mc / m_c), ChanMap{1, 1, 0, 0}, 0};
+  };
+  SCAT_TRY(scat::launch_small_fft2(go, pc, ChanMap{1, 1, 0, 0}, K, m_r, m_c, GHX, tw, tw_n, st));
+  scat::Rows2dAdjArgs top{};
+  top.inverse = 1;
+  top.c[top.n++] = low_child(GHX, 0, Nr, Nc);
+  auto flush = [&](float2 *dst, long nodes, int Sr, int Sc, scat::Rows2dAdjArgs &a) -> hipError_t {
+    hipError_t e = scat::launch_rows2d_adj(dst, nodes, Sr, Sc, a, tw, tw_n, st);
+    a.n = 0;
+    a.accumulate = 1;
+    return e;
+  };
+  int s2_base = 1 + J * L;
+  float2 *GUj = GU;
+  for (int j1 = 0; j1 < J; ++j1) {
+    const int r1 = h.res(j1);
+    const int M1r = Nr >> r1, M1c = Nc >> r1;
+    const bool kids = second && j1 < J - 1;
+    const bool node1 = scat::node_modback_supported(M1r, M1c);
+    const float2 *y1 = bl.tape.base + bl.tape.y1_off[j1] * pc;
+    const ChanMap cm1{L, L, 0, 1 + j1 * L};
+    if (!kids && node1) {
+      SCAT_TRY(scat::launch_node_modback_low(go, pc * L, cm1, K, m_r, m_c, M1r, M1c,
+                                             tab + p->phi_rows_off[r1], tab + p->phi_cols_off[r1], GH,
+                                             y1, GUj, tw, tw_n, st));
+    } else if (!kids) {
+      SCAT_TRY(scat::launch_lowpass_adj_rows(go, pc * L, cm1, K, m_r, m_c, M1r, M1c,
+                                             tab + p->phi_rows_off[r1], tab + p->phi_cols_off[r1], GH,
+                                             GUj, tw, tw_n, st));
+      SCAT_TRY(scat::launch_cols_modback(GUj, y1, pc * L, M1r, M1c, tw, tw_n, st));
+      SCAT_TRY(scat::launch_fft_rows_inplace(GUj, pc * L * M1r, M1c, false, tw, tw_n, st));
+    } else {
+      const int octs = J - 1 - j1;
+      scat::Rows2dAdjArgs a{};
+      a.inverse = node1 ? 0 : 1;
+      SCAT_TRY(scat::launch_small_fft2(go, pc * L, cm1, K, m_r, m_c, GHU, tw, tw_n, st));
+      a.c[a.n++] = low_child(GHU, r1, M1r, M1c);
+      float2 *GAj = GA;
+      for (int j2 = j1 + 1; j2 < J; ++j2) {
+        const int r2 = h.res(j2);
+        const int M2r = Nr >> r2, M2c = Nc >> r2;
+        const long nodes = pc * L * L;
+        const ChanMap cm2{L * L, L, octs * L, s2_base + (j2 - j1 - 1) * L};
+        const float2 *y2 = bl.tape.base + bl.tape.y2_off.at({j1, j2}) * pc;
+        if (scat::node_modback_supported(M2r, M2c)) {
+          SCAT_TRY(scat::launch_node_modback_low(go, nodes, cm2, K, m_r, m_c, M2r, M2c,
+                                                 tab + p->phi_rows_off[r2], tab + p->phi_cols_off[r2],
+                                                 GH, y2, GAj, tw, tw_n, st));
+        } else {
+          SCAT_TRY(scat::launch_lowpass_adj_rows(go, nodes, cm2, K, m_r, m_c, M2r, M2c,
+                                                 tab + p->phi_rows_off[r2], tab + p->phi_cols_off[r2],
+                                                 GH, GAj, tw, tw_n, st));
+          SCAT_TRY(scat::launch_cols_modback(GAj, y2, nodes, M2r, M2c, tw, tw_n, st));
+          SCAT_TRY(scat::launch_fft_rows_inplace(GAj, nodes * M2r, M2c, false, tw, tw_n, st));
+        }
+        for (int l2 = 0; l2 < L; ++l2) {
+          if (a.n == scat::kRows1dMaxChildren) SCAT_TRY(flush(GUj, pc * L, M1r, M1c, a));
+          a.c[a.n++] = scat::Rows2dAdjChild{
+              GAj, tab + p->psi2_off[{r1, j2}] + static_cast<size_t>(l2) * M1r * M1c, nullptr,
+              r2 - r1, r2 - r1, ChanMap{L, 1, 0, l2}, 0};
+        }
+        GAj += static_cast<size_t>(nodes) * M2r * M2c;
+      }
+      s2_base += L * L * octs;
+      SCAT_TRY(flush(GUj, pc * L, M1r, M1c, a));
+      if (node1) {
+        SCAT_TRY(scat::launch_node_modback(GUj, y1, pc * L, M1r, M1c, tw, tw_n, st));
+      } else {
+        SCAT_TRY(scat::launch_cols_modback(GUj, y1, pc * L, M1r, M1c, tw, tw_n, st));
+        SCAT_TRY(scat::launch_fft_rows_inplace(GUj, pc * L * M1r, M1c, false, tw, tw_n, st));
+      }
+    }
+    for (int l = 0; l < L; ++l) {
+      if (top.n == scat::kRows1dMaxChildren) SCAT_TRY(flush(GX, pc, Nr, Nc, top));
+      top.c[top.n++] = scat::Rows2dAdjChild{GUj, tab + p->psi1_off[j1] + static_cast<size_t>(l) * n,
+                                            nullptr, r1, r1, ChanMap{L, 1, 0, l}, 0};
+    }
+    GUj += static_cast<size_t>(pc) * L * M1r * M1c;
+  }
+  SCAT_TRY(flush(GX, pc, Nr, Nc, top));
+  // g_x = Re(inverse transform): the rows are done
+  SCAT_TRY(scat::launch_fft_cols_inplace(GX, pc, Nr, Nc, true, tw, tw_n, st));
+  SCAT_TRY(scat::launch_take_real(GX, gi, pc * static_cast<long>(n), st));
+  return SCAT_OK;
 }
 
 scat_status backward_2d(scat_plan *p, const float *in, const float *gout, float *gin, long p0,
@@ -976,6 +1098,7 @@ scat_status backward_2d(scat_plan *p, const float *in, const float *gout, float 
   scat_status fs = p->fused ? forward_2d_fused(p, in, nullptr, p0, pc, bl.fwd, st, &bl.tape)
                             : forward_2d(p, in, nullptr, p0, pc, bl.fwd, st, &bl.tape);
   if (fs != SCAT_OK) return fs;
+  if (bwd_rows_adjoint(*p)) return backward_2d_rows_adjoint(p, go, gi, pc, bl, GX, GU, GA, GH, st);
 
   // order 0: g_X^ = adjoint lowpass of g_S0
   SCAT_TRY(scat::launch_lowpass_adj(go, pc, ChanMap{1, 1, 0, 0}, K, m_r, m_c, Nr, Nc,
@@ -988,10 +1111,18 @@ scat_status backward_2d(scat_plan *p, const float *in, const float *gout, float 
     const bool kids = h.max_order == 2 && j1 < J - 1;
     // g_U1^ starts as the adjoint lowpass of g_S1, then collects its children; without
     // children the inverse row transform can follow in the same pass
+    // nodes small enough for one workgroup take the whole modulus backward step (both
+    // inverse passes, the modulus, both forward passes) in a single kernel
+    const bool node1 = scat::node_modback_supported(M1r, M1c);
+    const float2 *y1 = bl.tape.base + bl.tape.y1_off[j1] * pc;
     if (kids) {
       SCAT_TRY(scat::launch_lowpass_adj(go, pc * L, ChanMap{L, L, 0, 1 + j1 * L}, K, m_r, m_c, M1r,
                                         M1c, tab + p->phi_rows_off[r1], tab + p->phi_cols_off[r1],
                                         GU, tw, tw_n, st));
+    } else if (node1) {
+      SCAT_TRY(scat::launch_node_modback_low(go, pc * L, ChanMap{L, L, 0, 1 + j1 * L}, K, m_r, m_c,
+                                             M1r, M1c, tab + p->phi_rows_off[r1],
+                                             tab + p->phi_cols_off[r1], GH, y1, GU, tw, tw_n, st));
     } else {
       SCAT_TRY(scat::launch_lowpass_adj_rows(go, pc * L, ChanMap{L, L, 0, 1 + j1 * L}, K, m_r, m_c,
                                              M1r, M1c, tab + p->phi_rows_off[r1],
@@ -1007,21 +1138,31 @@ scat_status backward_2d(scat_plan *p, const float *in, const float *gout, float 
         // modulus backward against the tape, forward); then forward rows and the
         // accumulation into the parent's gradient spectrum (fusing those two was measured
         // and is not faster: the accumulate is bound by its filter reads)
-        SCAT_TRY(scat::launch_lowpass_adj_rows(
-            go, nodes, ChanMap{L * L, L, octs * L, s2_base + (j2 - j1 - 1) * L}, K, m_r, m_c, M2r, M2c,
-            tab + p->phi_rows_off[r2], tab + p->phi_cols_off[r2], GH, GA, tw, tw_n, st));
-        SCAT_TRY(scat::launch_cols_modback(GA, bl.tape.base + bl.tape.y2_off.at({j1, j2}) * pc, nodes,
-                                           M2r, M2c, tw, tw_n, st));
-        SCAT_TRY(scat::launch_fft_rows_inplace(GA, nodes * M2r, M2c, false, tw, tw_n, st));
+        const ChanMap cm2{L * L, L, octs * L, s2_base + (j2 - j1 - 1) * L};
+        const float2 *y2 = bl.tape.base + bl.tape.y2_off.at({j1, j2}) * pc;
+        if (scat::node_modback_supported(M2r, M2c)) {
+          SCAT_TRY(scat::launch_node_modback_low(go, nodes, cm2, K, m_r, m_c, M2r, M2c,
+                                                 tab + p->phi_rows_off[r2], tab + p->phi_cols_off[r2],
+                                                 GH, y2, GA, tw, tw_n, st));
+        } else {
+          SCAT_TRY(scat::launch_lowpass_adj_rows(go, nodes, cm2, K, m_r, m_c, M2r, M2c,
+                                                 tab + p->phi_rows_off[r2], tab + p->phi_cols_off[r2],
+                                                 GH, GA, tw, tw_n, st));
+          SCAT_TRY(scat::launch_cols_modback(GA, y2, nodes, M2r, M2c, tw, tw_n, st));
+          SCAT_TRY(scat::launch_fft_rows_inplace(GA, nodes * M2r, M2c, false, tw, tw_n, st));
+        }
         SCAT_TRY(scat::launch_tile_accum(GU, tab + p->psi2_off[{r1, j2}], GA, pc * L, L, M1r, M1c,
                                          M2r, M2c, st));
       }
       s2_base += L * L * octs;
     }
-    if (kids) SCAT_TRY(scat::launch_fft_rows_inplace(GU, pc * L * M1r, M1c, true, tw, tw_n, st));
-    SCAT_TRY(scat::launch_cols_modback(GU, bl.tape.base + bl.tape.y1_off[j1] * pc, pc * L, M1r, M1c,
-                                       tw, tw_n, st));
-    SCAT_TRY(scat::launch_fft_rows_inplace(GU, pc * L * M1r, M1c, false, tw, tw_n, st));
+    if (kids && node1) {
+      SCAT_TRY(scat::launch_node_modback(GU, y1, pc * L, M1r, M1c, tw, tw_n, st));
+    } else if (kids || !node1) {
+      if (kids) SCAT_TRY(scat::launch_fft_rows_inplace(GU, pc * L * M1r, M1c, true, tw, tw_n, st));
+      SCAT_TRY(scat::launch_cols_modback(GU, y1, pc * L, M1r, M1c, tw, tw_n, st));
+      SCAT_TRY(scat::launch_fft_rows_inplace(GU, pc * L * M1r, M1c, false, tw, tw_n, st));
+    }
     SCAT_TRY(scat::launch_tile_accum(GX, tab + p->psi1_off[j1], GU, pc, L, Nr, Nc, M1r, M1c, st));
   }
   SCAT_TRY(scat::launch_fft2_inplace(GX, pc, Nr, Nc, true, tw, tw_n, st));
@@ -1081,7 +1222,7 @@ scat_status backward_1d(scat_plan *p, const float *in, const float *gout, float 
     return scat::launch_fft_rows_inplace(g, nodes * N1, Mc, false, tw, tw_n, st);
   };
 
-  if (bwd1d_rows_adjoint(*p)) {
+  if (bwd_rows_adjoint(*p)) {
     // Adjoint row kernel: a node's gradient (column spectra, ready for the modulus backward)
     // is one launch over the list of its children -- its own lowpass output and the
     // second-order nodes below it -- and x's over the first-order nodes of all octaves.

@@ -60,7 +60,7 @@ hipError_t launch_col(int mode, const void *src, long nodes, int Mr, int Mc, flo
 // 1-D cascade: forward row FFT of src [nodes][Sr][Sc] (column spectra, left untouched) and,
 // for each child, filter product + fold of the row by 2^lg_fold + inverse row FFT + four-step
 // twiddle, stored to the child's dst [nodes][Sr][Sc >> lg_fold] (see k_rows1d).
-constexpr int kRows1dMaxChildren = 24;
+constexpr int kRows1dMaxChildren = 32;
 struct Rows1dChild {
   const float *filt;  // [Sr][Sc], carries the inverse-transform normalisation
   float2 *dst;
@@ -98,6 +98,28 @@ struct Rows1dAdjArgs {
 };
 bool rows1d_adj_supported(int Sc);
 hipError_t launch_rows1d_adj(float2 *dst, long nodes, int Sr, int Sc, const Rows1dAdjArgs &a,
+                             const float2 *tw, int tw_n, hipStream_t st);
+
+// 2-D: dst [nodes][Sr][Sc] (= or +=) sum_c filt_c * tile(src_c), child planes of
+// (Sr >> lg_fr) x (Sc >> lg_fc) gradient spectra, then (inverse != 0) the inverse row
+// transform (see k_rows2d_adj).  filt_row != nullptr: the filter is filt_row[kr] * filt[kc].
+// Child nodes as in Rows1dAdjChild.  Row lengths as rows1d_adj_supported.
+struct Rows2dAdjChild {
+  const float2 *src;
+  const float *filt;
+  const float *filt_row;
+  int lg_fr, lg_fc;
+  ChanMap cm;
+  int K;
+};
+struct Rows2dAdjArgs {
+  int n;
+  int accumulate;
+  int inverse;
+  int lg_rows;  // set by the launcher
+  Rows2dAdjChild c[kRows1dMaxChildren];
+};
+hipError_t launch_rows2d_adj(float2 *dst, long nodes, int Sr, int Sc, const Rows2dAdjArgs &a,
                              const float2 *tw, int tw_n, hipStream_t st);
 
 hipError_t launch_row_fwd(float2 *data, long rows, int Mc, const float2 *tw, int tw_n,
@@ -152,6 +174,21 @@ hipError_t launch_tree32(const float2 *xh, long planes, int L, int max_order, co
                          const float *psi_j1, const float *phi_cols0, const float *phi_cols1,
                          const float *taps0, const float *taps1, float *out, int K,
                          hipStream_t st);
+
+// Modulus backward step of whole nodes in one pass (k_node_modback): data [nodes][Mr][Mc]
+// gradient spectra in, gradient spectra of the taped y [nodes][Mr][Mc] out, in place.  The
+// _low form starts from the node's adjoint lowpass instead (arguments as
+// launch_lowpass_adj_rows; ghat is scratch for nodes * m_r * m_c elements).
+bool node_modback_supported(int Mr, int Mc);
+// ghat [node][m_r][m_c] = 2-D transform of the nodes' output gradient planes (m_r * m_c <= 1024)
+hipError_t launch_small_fft2(const float *gout, long nodes, ChanMap cm, int K, int m_r, int m_c,
+                             float2 *ghat, const float2 *tw, int tw_n, hipStream_t st);
+hipError_t launch_node_modback(float2 *data, const float2 *y, long nodes, int Mr, int Mc,
+                               const float2 *tw, int tw_n, hipStream_t st);
+hipError_t launch_node_modback_low(const float *gout, long nodes, ChanMap cm, int K, int m_r, int m_c,
+                                   int Mr, int Mc, const float *phi_rows, const float *phi_cols,
+                                   float2 *ghat, const float2 *y, float2 *dst, const float2 *tw,
+                                   int tw_n, hipStream_t st);
 
 // ---- backward pass (scat_backward.hip): plain 2-D transforms in place and the adjoints of
 // the lowpass, the modulus and the filter-multiply-fold step.  Sides 4...512.
