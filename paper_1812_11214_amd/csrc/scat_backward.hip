@@ -745,6 +745,8 @@ __global__ __launch_bounds__((Slab<N1, N2>::NT)) void k_node_modback(
   const bool live = node_raw < nodes;
   const long node = live ? node_raw : nodes - 1;  // idle threads shadow the last node, store nothing
   float2 *area = lds + s * N1 * S::RS;
+  float2 *wtab = lds + S::SPW * N1 * S::RS;  // the transforms' twiddles, shared by the slabs
+  S::fill_twiddles(wtab, tw, tw_n);
   const int r = q / S::T2, t = q % S::T2;
   const int c = q % N2, t1 = q / N2;
   const size_t base = static_cast<size_t>(node) * N1 * N2;
@@ -764,7 +766,7 @@ __global__ __launch_bounds__((Slab<N1, N2>::NT)) void k_node_modback(
 #pragma unroll
     for (int i = 0; i < 16; ++i) v[i] = row[S::T2 * i];
   }
-  S::template transform<true>(v, area, r, t, c, t1, tw, tw_n);
+  S::template transform_tab<true>(v, area, r, t, c, t1, wtab);
   {
     const float2 *yp = y + base + c;
 #pragma unroll
@@ -775,7 +777,7 @@ __global__ __launch_bounds__((Slab<N1, N2>::NT)) void k_node_modback(
       v[i] = make_float2(u.x * sgn, u.y * sgn);
     }
   }
-  S::template transform_back<false>(v, area, r, t, c, t1, tw, tw_n);
+  S::template transform_back_tab<false>(v, area, r, t, c, t1, wtab);
   if (live) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) row[S::T2 * i] = v[i];
@@ -1113,13 +1115,14 @@ hipError_t node_modback_t(const float2 *ghat, int m_r, int m_c, const float *phi
   const double pts = static_cast<double>(nodes) * N1 * N2;
   LaunchScope obs(name.c_str(), pts * (LOW ? 16.0 : 24.0) + (LOW ? nodes * 8.0 * m_r * m_c : 0.0),
                   pts * (10.0 * (ilog2h(N1) + ilog2h(N2)) + 8.0), st);
-  if (S::lds_bytes > 65536) {
+  const size_t lds = S::lds_bytes + S::tab_elems * sizeof(float2);
+  if (lds > 65536) {
     static unsigned long long lds_ok = 0;
     hipError_t e = allow_large_lds(reinterpret_cast<const void *>(k_node_modback<N1, N2, LOW>), lds_ok);
     if (e != hipSuccess) return e;
   }
   hipLaunchKernelGGL((k_node_modback<N1, N2, LOW>), dim3(static_cast<unsigned>(blocks)), dim3(S::NT),
-                     S::lds_bytes, st, ghat, m_r, m_c, phi_rows, phi_cols, y, data, nodes, tw, tw_n);
+                     lds, st, ghat, m_r, m_c, phi_rows, phi_cols, y, data, nodes, tw, tw_n);
   return hipGetLastError();
 }
 

@@ -24,7 +24,8 @@ struct Slab {
   static constexpr int SPW = NT / TS;           // slabs per workgroup
   static constexpr int RS = slab_row_stride(N2);
   static constexpr size_t lds_bytes = static_cast<size_t>(SPW) * N1 * RS * sizeof(float2);
-  static_assert(N1 >= 16 && N2 >= 16 && TS <= 1024 && TS >= 16 && lds_bytes <= 160 * 1024,
+  static_assert(N1 >= 16 && N2 >= 16 && TS <= 1024 && TS >= 16 &&
+                    lds_bytes + (N1 + N2) * sizeof(float2) <= 160 * 1024,
                 "slab shape");
 
   // v: this thread's 16 points of row r (columns t + T2 i) -> after the call its 16 points
@@ -70,6 +71,44 @@ struct Slab {
     load_twiddles<16, T2>(wr, t, tw, tw_n);
     fft_core<16, T2, INV, false>(v, t, area + r * RS, T2 + 1, 1, wr);
   }
+  // The same two transforms with the threads' twiddles in LDS tables instead of registers
+  // (for kernels short of registers): wtr[k T2 + t] = exp(-2 pi i t k / N2), k < 16, t < T2,
+  // and wtc[k T1 + t1] likewise for N1; fill_twiddles writes both (tab_elems entries at
+  // `tab`, barrier included).
+  static constexpr int tab_elems = N1 + N2;
+  static __device__ __forceinline__ void fill_twiddles(float2 *tab, const float2 *__restrict__ tw,
+                                                       int tw_n) {
+    for (int idx = threadIdx.x; idx < N2; idx += blockDim.x)
+      tab[idx] = tw[(idx / T2) * (idx % T2) * (tw_n / N2)];
+    for (int idx = threadIdx.x; idx < N1; idx += blockDim.x)
+      tab[N2 + idx] = tw[(idx / T1) * (idx % T1) * (tw_n / N1)];
+    __syncthreads();
+  }
+  template <bool INV>
+  static __device__ __forceinline__ void transform_tab(float2 (&v)[16], float2 *area, int r, int t,
+                                                       int c, int t1, const float2 *tab) {
+    fft_core_tab<16, T2, INV, false>(v, t, area + r * RS, T2 + 1, 1, tab + t, T2);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) area[r * RS + t + T2 * i] = v[i];
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 16; ++i) v[i] = area[(t1 + T1 * i) * RS + c];
+    __syncthreads();
+    fft_core_tab<16, T1, INV, false>(v, t1, area + c, T1 * RS, RS, tab + N2 + t1, T1);
+  }
+  template <bool INV>
+  static __device__ __forceinline__ void transform_back_tab(float2 (&v)[16], float2 *area, int r,
+                                                            int t, int c, int t1, const float2 *tab) {
+    fft_core_tab<16, T1, INV, false>(v, t1, area + c, T1 * RS, RS, tab + N2 + t1, T1);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) area[(t1 + T1 * i) * RS + c] = v[i];
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 16; ++i) v[i] = area[r * RS + t + T2 * i];
+    __syncthreads();
+    fft_core_tab<16, T2, INV, false>(v, t, area + r * RS, T2 + 1, 1, tab + t, T2);
+  }
 };
+
 
 }  // namespace scat
