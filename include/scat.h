@@ -120,8 +120,8 @@ scat_status scat_plan_create_padded_host(scat_plan **out_plan, int dims, const i
  * output has sides shape >> max(J-o, 0).  With o >= J nothing is subsampled and the output,
  * read at the samples 2^J k, is the section-2 definition itself.  flags: bitwise OR of
  * SCAT_PLAN_PADDED (signals of any size, see scat_plan_create_padded) and
- * SCAT_PLAN_HOST_ONLY (no GPU, see scat_plan_create_host).  scat_backward needs an output
- * grid of at most 1024 points, which limits o there.
+ * SCAT_PLAN_HOST_ONLY (no GPU, see scat_plan_create_host).  scat_backward limits the size of
+ * the output grid in 2-D (see there), which limits o.
  */
 #define SCAT_PLAN_PADDED 1
 #define SCAT_PLAN_HOST_ONLY 2
@@ -173,7 +173,8 @@ scat_status scat_forward(scat_plan *plan, const float *in, float *out, long batc
  * below fp32 resolution.
  * Errors: SCAT_ERR_ARG for batch < 0.  SCAT_ERR_SHAPE, 2-D: unless every
  * side and every side subsampled for the last octave lies in 4...512 and the output grid
- * has at most 1024 points; 1-D: unless the signal, seen as the n1 x n2 matrix of the
+ * has at most 1024 points or, for images at most 256 wide, is one of 16 x 16 ... 128 x 128,
+ * square or 2 : 1; 1-D: unless the signal, seen as the n1 x n2 matrix of the
  * four-step transform (n2 = 2^max(ceil(log2(n)/2), J), n1 = n / n2), has n1 in 4...512 and
  * n2 <= 512 (so n <= 2^18 at most).
  */

@@ -943,6 +943,12 @@ bool node_modback_supported(int Mr, int Mc) {
          (Mr == Mc || Mr == 2 * Mc || Mc == 2 * Mr);
 }
 
+// output grids whose gradient planes launch_small_fft2 transforms: up to 1024 points by the
+// dense kernel, or a slab shape
+bool small_fft2_supported(int m_r, int m_c) {
+  return pow2(m_r) && pow2(m_c) && (m_r * m_c <= 1024 || node_modback_supported(m_r, m_c));
+}
+
 #define SCAT_NODE_DISPATCH(CALL)            \
   switch ((Mr << 12) | Mc) {                \
     case (16 << 12) | 16: CALL(16, 16);     \
@@ -981,7 +987,7 @@ hipError_t slab_fft2_real_t(const float *gout, long nodes, ChanMap cm, int K, fl
 hipError_t launch_small_fft2(const float *gout, long nodes, ChanMap cm, int K, int m_r, int m_c,
                              float2 *ghat, const float2 *tw, int tw_n, hipStream_t st) {
   if (nodes <= 0) return hipSuccess;
-  if (!pow2(m_r) || !pow2(m_c) || m_r * m_c > 1024 || tw_n % m_r != 0 || tw_n % m_c != 0 ||
+  if (!small_fft2_supported(m_r, m_c) || tw_n % m_r != 0 || tw_n % m_c != 0 ||
       nodes > 0x7fffffffL || cm.G < 1 || cm.inner < 1 || nodes % cm.G != 0)
     return hipErrorInvalidValue;
   if (node_modback_supported(m_r, m_c)) {
@@ -1007,7 +1013,7 @@ hipError_t launch_lowpass_adj_rows(const float *gout, long nodes, ChanMap cm, in
                                    const float2 *tw, int tw_n, hipStream_t st) {
   if (nodes <= 0) return hipSuccess;
   if (!pow2(m_r) || !pow2(m_c) || !backward_side_supported(Mr) || !backward_side_supported(Mc) ||
-      m_r > Mr || m_c > Mc || m_r * m_c > 1024 || tw_n % Mc != 0 || tw_n % m_r != 0 ||
+      m_r > Mr || m_c > Mc || !small_fft2_supported(m_r, m_c) || tw_n % Mc != 0 || tw_n % m_r != 0 ||
       tw_n % m_c != 0 || nodes > 0x7fffffffL)
     return hipErrorInvalidValue;
   {
@@ -1143,8 +1149,8 @@ hipError_t launch_node_modback_low(const float *gout, long nodes, ChanMap cm, in
                                    float2 *ghat, const float2 *y, float2 *dst, const float2 *tw,
                                    int tw_n, hipStream_t st) {
   if (nodes <= 0) return hipSuccess;
-  if (!node_modback_supported(Mr, Mc) || !pow2(m_r) || !pow2(m_c) || m_r > Mr || m_c > Mc ||
-      m_r * m_c > 1024 || tw_n % Mr != 0 || tw_n % Mc != 0 || tw_n % m_r != 0 || tw_n % m_c != 0 ||
+  if (!node_modback_supported(Mr, Mc) || !small_fft2_supported(m_r, m_c) || m_r > Mr || m_c > Mc ||
+      tw_n % Mr != 0 || tw_n % Mc != 0 || tw_n % m_r != 0 || tw_n % m_c != 0 ||
       nodes > 0x7fffffffL || cm.G < 1 || cm.inner < 1 || nodes % cm.G != 0)
     return hipErrorInvalidValue;
   {

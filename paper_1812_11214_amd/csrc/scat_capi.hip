@@ -1926,9 +1926,13 @@ scat_status scat_backward(scat_plan *plan, const float *in, const float *grad_ou
     // every grid of the cascade must have sides the plain transforms handle, and the
     // output grid must fit the adjoint lowpass kernel's LDS stage
     const int small_r = plan->n1 >> h.res(h.J - 1), small_c = plan->n2 >> h.res(h.J - 1);
+    const int m_r = plan->n1 >> h.res(h.J), m_c = plan->n2 >> h.res(h.J);
+    // (the per-level schedule's adjoint lowpass kernel transforms the gradient plane itself,
+    // in LDS: 1024 points at most)
+    const bool grid_ok = bwd_rows_adjoint(*plan) ? scat::small_fft2_supported(m_r, m_c)
+                                                 : static_cast<long>(m_r) * m_c <= 1024;
     if (!scat::backward_side_supported(plan->n1) || !scat::backward_side_supported(plan->n2) ||
-        !scat::backward_side_supported(small_r) || !scat::backward_side_supported(small_c) ||
-        static_cast<long>(plan->n1 >> h.res(h.J)) * (plan->n2 >> h.res(h.J)) > 1024)
+        !scat::backward_side_supported(small_r) || !scat::backward_side_supported(small_c) || !grid_ok)
       return SCAT_ERR_SHAPE;
   }
   if (batch == 0) return SCAT_OK;

@@ -180,7 +180,8 @@ hipError_t launch_tree32(const float2 *xh, long planes, int L, int max_order, co
 // _low form starts from the node's adjoint lowpass instead (arguments as
 // launch_lowpass_adj_rows; ghat is scratch for nodes * m_r * m_c elements).
 bool node_modback_supported(int Mr, int Mc);
-// ghat [node][m_r][m_c] = 2-D transform of the nodes' output gradient planes (m_r * m_c <= 1024)
+// ghat [node][m_r][m_c] = 2-D transform of the nodes' output gradient planes
+bool small_fft2_supported(int m_r, int m_c);
 hipError_t launch_small_fft2(const float *gout, long nodes, ChanMap cm, int K, int m_r, int m_c,
                              float2 *ghat, const float2 *tw, int tw_n, hipStream_t st);
 hipError_t launch_node_modback(float2 *data, const float2 *y, long nodes, int Mr, int Mc,

@@ -54,6 +54,12 @@ def _check(shape, J, L, max_order, x, g):
     ((8, 8), 1, 4, 2, 3), ((128, 128), 4, 3, 2, 1),
     # coarse octaves too small for the fused row pass of the recomputed forward cascade
     ((32, 128), 4, 2, 2, 2), ((64, 128), 4, 2, 2, 2), ((16, 128), 3, 2, 2, 2),
+    # 2 : 1 nodes held by one workgroup (both orientations), with and without children
+    ((64, 128), 2, 3, 2, 2), ((128, 64), 2, 2, 2, 2), ((128, 256), 3, 2, 2, 1),
+    # more children than one launch of the row-adjoint kernel takes (33 for x), nodes down to 8 x 8
+    ((64, 64), 4, 8, 2, 1),
+    # first order only at 256 x 256: leaves of 256 (column and row passes) and 128 (node kernel)
+    ((256, 256), 2, 2, 1, 1),
 ])
 def test_backward_shapes(shape, J, L, max_order, batch):
     rng = np.random.default_rng(hash((shape, J, L, max_order)) % 2**32)
@@ -131,6 +137,7 @@ def test_backward_zero_input_and_zero_gradient():
 @pytest.mark.parametrize("n,J,Q,max_order,o,batch", [
     (64, 3, 2, 2, 0, 3), (256, 4, 1, 2, 0, 2), (1024, 5, 8, 2, 0, 2), (4096, 6, 8, 1, 0, 2),
     (2048, 2, 3, 2, 0, 2), (1024, 5, 2, 2, 2, 3), (65536, 6, 8, 2, 0, 1),
+    (32768, 7, 4, 2, 0, 1), (8192, 4, 12, 2, 1, 2),
 ])
 def test_backward_1d(n, J, Q, max_order, o, batch):
     import torch

@@ -127,7 +127,10 @@ def test_oracle_backward_with_oversampling_matches_finite_differences():
 
 @pytest.mark.gpu
 @pytest.mark.parametrize("shape,J,L,o,batch", [((32, 32), 2, 3, 1, 3), ((64, 64), 3, 2, 1, 2),
-                                               ((32, 32), 3, 4, 3, 2)])
+                                               ((32, 32), 3, 4, 3, 2),
+                                               # output grids above 1024 points (slab transform
+                                               # of the gradient planes): 64 x 64 and 64 x 128
+                                               ((128, 128), 2, 2, 1, 2), ((64, 128), 3, 2, 3, 1)])
 def test_oversampled_backward_parity_gpu(shape, J, L, o, batch):
     import torch
     rng = np.random.default_rng(sum(shape) + J + o)
