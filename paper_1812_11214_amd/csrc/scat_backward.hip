@@ -766,12 +766,19 @@ __global__ __launch_bounds__((Slab<N1, N2>::NT)) void k_node_modback(
 #pragma unroll
     for (int i = 0; i < 16; ++i) v[i] = row[S::T2 * i];
   }
-  S::template transform_tab<true>(v, area, r, t, c, t1, wtab);
+  // the tape values are requested before the inverse transform and used after it (loads do
+  // not move across its barriers by themselves)
+  float2 yv[16];
   {
     const float2 *yp = y + base + c;
 #pragma unroll
+    for (int i = 0; i < 16; ++i) yv[i] = yp[(t1 + S::T1 * i) * N2];
+  }
+  S::template transform_tab<true>(v, area, r, t, c, t1, wtab);
+  {
+#pragma unroll
     for (int i = 0; i < 16; ++i) {
-      const float2 u = yp[(t1 + S::T1 * i) * N2];
+      const float2 u = yv[i];
       const float m2 = u.x * u.x + u.y * u.y;
       const float sgn = m2 > 0.f ? v[i].x / __builtin_amdgcn_sqrtf(m2) : 0.f;
       v[i] = make_float2(u.x * sgn, u.y * sgn);
