@@ -301,7 +301,7 @@ __global__ __launch_bounds__(256) void k_fft_cols(float2 *__restrict__ data, int
 // exp(+2 pi i k1 b / tw_m) before the inverse column transform and by its conjugate after
 // the forward one (the twiddle step of the four-step transform; k1 = row, b = column).
 template <int E, int T>
-__global__ __launch_bounds__(256, (E <= 16 ? 4 : 1)) void k_cols_modback(float2 *__restrict__ data,
+__global__ __launch_bounds__(256, (E <= 16 ? 3 : 1)) void k_cols_modback(float2 *__restrict__ data,
                                                       const float2 *__restrict__ y, int Mc, int TC,
                                                       int tw_m, const float2 *__restrict__ tw,
                                                       int tw_n) {
@@ -368,10 +368,15 @@ __global__ __launch_bounds__(256, (E <= 16 ? 4 : 1)) void k_cols_modback(float2 
     else
       fft_core<E, T, decltype(inv)::value, false>(v, t, lds + c, KS, TC, wt);
   };
+  // the tape values are requested before the inverse transform and used after it (3 waves
+  // per SIMD with them in flight beat 4 without)
+  float2 yv[E];
+#pragma unroll
+  for (int i = 0; i < E; ++i) yv[i] = yp[i * step];
   transform(std::true_type{});
 #pragma unroll
   for (int i = 0; i < E; ++i) {
-    const float2 u = yp[i * step];
+    const float2 u = yv[i];
     const float m2 = u.x * u.x + u.y * u.y;
     const float sgn = m2 > 0.f ? v[i].x / __builtin_amdgcn_sqrtf(m2) : 0.f;
     v[i] = make_float2(u.x * sgn, u.y * sgn);
