@@ -16,6 +16,7 @@
 
 #include <cmath>
 #include <string>
+#include <type_traits>
 
 #include "fft_regs.hpp"
 #include "scat_kernels.hpp"
@@ -1009,8 +1010,25 @@ __global__ __launch_bounds__(256) void k_col_node(const void *__restrict__ src_v
   const int node = blockIdx.x;
   const size_t plane = static_cast<size_t>(node) * MR * Mc;
   const int step = T * Mc;
+  // 128-row nodes (three workgroups per CU, bound by registers): the transforms' twiddles in
+  // an LDS table behind W instead of 32 registers, which pays for requesting the next tile
+  // before the current one is transformed
+  constexpr bool EARLY = MR == 128;
+  float2 *wtab = reinterpret_cast<float2 *>(Wl + LM * WS);  // wtab[k T + t], EARLY only
   float2 wt[E];
-  load_twiddles<E, T>(wt, t, tw, tw_n);
+  if constexpr (EARLY) {
+    for (int idx = threadIdx.x; idx < MR; idx += blockDim.x)
+      wtab[idx] = tw[(idx / T) * (idx % T) * (tw_n / MR)];
+    __syncthreads();
+  } else {
+    load_twiddles<E, T>(wt, t, tw, tw_n);
+  }
+  auto column_fft = [&](float2 (&v)[E], auto inv) {
+    if constexpr (EARLY)
+      fft_core_tab<E, T, decltype(inv)::value>(v, t, lds + c, KS, TC, wtab + t, T);
+    else
+      fft_core<E, T, decltype(inv)::value>(v, t, lds + c, KS, TC, wt);
+  };
   float phr[E];
 #pragma unroll
   for (int i = 0; i < E; ++i) phr[i] = phi_rows[t + T * i];
@@ -1030,22 +1048,23 @@ __global__ __launch_bounds__(256) void k_col_node(const void *__restrict__ src_v
       for (int i = 0; i < E; ++i) vn[i] = nt_load(sp + i * step);
     }
   };
-  if (PF) fetch(0);
+  if (PF || EARLY) fetch(0);
 #pragma unroll 1
   for (int c0 = 0; c0 < Mc; c0 += TC) {
     const int off0 = t * Mc + c0 + c;
-    if (!PF) fetch(c0);
+    if (!PF && !EARLY) fetch(c0);
     float2 v[E];
 #pragma unroll
     for (int i = 0; i < E; ++i) v[i] = vn[i];
+    if (EARLY && c0 + TC < Mc) fetch(c0 + TC);
     if (MODE != 0) {
-      fft_core<E, T, true>(v, t, lds + c, KS, TC, wt);
+      column_fft(v, std::true_type{});
 #pragma unroll
       for (int i = 0; i < E; ++i)
         v[i] = make_float2(__builtin_amdgcn_sqrtf(v[i].x * v[i].x + v[i].y * v[i].y), 0.f);
     }
-    fft_core<E, T, false>(v, t, lds + c, KS, TC, wt);
-    if (PF && c0 + TC < Mc) fetch(c0 + TC);
+    column_fft(v, std::false_type{});
+    if (PF && !EARLY && c0 + TC < Mc) fetch(c0 + TC);
     if (uc != nullptr) {
       if (uc_half) {
         float2 *up = uc + static_cast<size_t>(node) * (MR / 2 + 1) * Mc + off0;
@@ -1171,7 +1190,8 @@ hipError_t launch_col_node_t(int mode, const void *src, long nodes, float2 *uc, 
   constexpr int XW = (16 * KS > 80 * TC) ? 16 * KS : 80 * TC;
   constexpr int WS = MR + 4;
   if (nodes <= 0 || nodes > 0x7fffffffL) return hipErrorInvalidValue;
-  size_t lds = static_cast<size_t>(XW) * sizeof(float2) + static_cast<size_t>(LM) * WS * sizeof(float);
+  size_t lds = static_cast<size_t>(XW) * sizeof(float2) + static_cast<size_t>(LM) * WS * sizeof(float) +
+               (MR == 128 ? MR * sizeof(float2) : 0);  // + the twiddle table of the 128-row variant
   const std::string name = "k_col_node<" + std::to_string(MR) + ", " + (mode ? "1" : "0") + ", " +
                            std::to_string(LM) + ((uc != nullptr && MR >= 256) ? ", true>" : ", false>");
   const double pts = static_cast<double>(nodes) * MR * MR;
