@@ -60,6 +60,8 @@ def _check(shape, J, L, max_order, x, g):
     ((64, 64), 4, 8, 2, 1),
     # first order only at 256 x 256: leaves of 256 (column and row passes) and 128 (node kernel)
     ((256, 256), 2, 2, 1, 1),
+    # 512-wide rows: the per-level schedule, with the node kernel where nodes fit
+    ((64, 512), 3, 2, 2, 1),
 ])
 def test_backward_shapes(shape, J, L, max_order, batch):
     rng = np.random.default_rng(hash((shape, J, L, max_order)) % 2**32)
@@ -138,6 +140,8 @@ def test_backward_zero_input_and_zero_gradient():
     (64, 3, 2, 2, 0, 3), (256, 4, 1, 2, 0, 2), (1024, 5, 8, 2, 0, 2), (4096, 6, 8, 1, 0, 2),
     (2048, 2, 3, 2, 0, 2), (1024, 5, 2, 2, 2, 3), (65536, 6, 8, 2, 0, 1),
     (32768, 7, 4, 2, 0, 1), (8192, 4, 12, 2, 1, 2),
+    # 512-point rows of the four-step matrix: the per-level schedule
+    (262144, 3, 1, 2, 0, 1),
 ])
 def test_backward_1d(n, J, Q, max_order, o, batch):
     import torch
