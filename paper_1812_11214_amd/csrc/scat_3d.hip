@@ -364,8 +364,16 @@ __global__ __launch_bounds__(256) void k3_axis0_back(float2 *__restrict__ W, flo
   const int c0 = static_cast<int>(blockIdx.x % tiles) * TC;
   const size_t off = static_cast<size_t>(vol) * N0 * Mc + static_cast<size_t>(t) * Mc + c0 + c;
   const size_t step = static_cast<size_t>(T) * Mc;
-  float2 wt[E];
-  load_twiddles<E, T>(wt, t, tw, tw_n);
+  // The transforms' twiddles in an LDS table behind the exchange area (wtab[k T + t]); the
+  // registers they would take hold the next signal's values, requested before the current
+  // signal is transformed (otherwise they would queue behind its stores).
+  constexpr bool TAB = T > 1;
+  float2 *wtab = lds + E * KS;
+  if (TAB) {
+    for (int idx = threadIdx.x; idx < N0; idx += blockDim.x)
+      wtab[idx] = tw[(idx / T) * (idx % T) * (tw_n / N0)];
+    __syncthreads();
+  }
   float a[E];
 #pragma unroll
   for (int i = 0; i < E; ++i) {
@@ -376,19 +384,27 @@ __global__ __launch_bounds__(256) void k3_axis0_back(float2 *__restrict__ W, flo
       a[i] = s2 > 0.f ? gu[off + i * step].x / __builtin_amdgcn_sqrtf(s2) : 0.f;
     }
   }
+  float2 vn[E];
+  auto fetch = [&](int p) {
+    const float2 *w = W + static_cast<size_t>(p) * mstride + off;
+#pragma unroll
+    for (int i = 0; i < E; ++i) vn[i] = w[i * step];
+  };
+  fetch(0);
   for (int p = 0; p < P; ++p) {
     float2 *w = W + static_cast<size_t>(p) * mstride + off;
     float2 v[E];
 #pragma unroll
-    for (int i = 0; i < E; ++i) v[i] = w[i * step];
+    for (int i = 0; i < E; ++i) v[i] = vn[i];
+    if (p + 1 < P) fetch(p + 1);
     if (MODE == 0) {
-      fft_core<E, T, true, false>(v, t, lds + c, KS, TC, wt);
+      fft_core_tab<E, T, true, false>(v, t, lds + c, KS, TC, wtab + t, T);
 #pragma unroll
       for (int i = 0; i < E; ++i) a[i] += v[i].x * v[i].x + v[i].y * v[i].y;
     } else {
 #pragma unroll
       for (int i = 0; i < E; ++i) v[i] = make_float2(v[i].x * a[i], v[i].y * a[i]);
-      fft_core<E, T, false, false>(v, t, lds + c, KS, TC, wt);
+      fft_core_tab<E, T, false, false>(v, t, lds + c, KS, TC, wtab + t, T);
     }
 #pragma unroll
     for (int i = 0; i < E; ++i) w[i * step] = v[i];
@@ -417,6 +433,10 @@ __global__ __launch_bounds__((Slab<N1, N2>::NT)) void k3_slab_fwd_mulacc(
   const int c = q % N2, t1 = q / N2;
   const int k0 = static_cast<int>(sl % n0);
   const size_t base = static_cast<size_t>(sl) * N1 * N2;
+  // the transforms' twiddles in LDS tables: their registers go to the table values, which
+  // are requested before the transform they are used after
+  float2 *wtab = lds + S::SPW * N1 * S::RS;
+  S::fill_twiddles(wtab, tw, tw_n);
   float2 sum[16];
 #pragma unroll
   for (int i = 0; i < 16; ++i) sum[i] = make_float2(0.f, 0.f);
@@ -425,11 +445,14 @@ __global__ __launch_bounds__((Slab<N1, N2>::NT)) void k3_slab_fwd_mulacc(
     float2 v[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) v[i] = src[S::T2 * i];
-    S::template transform<false>(v, area, r, t, c, t1, tw, tw_n);
     const float2 *tb = tab + (static_cast<size_t>(p) * n0 + k0) * N1 * N2 + c;
+    float2 gt[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) gt[i] = tb[(t1 + S::T1 * i) * N2];
+    S::template transform_tab<false>(v, area, r, t, c, t1, wtab);
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      float2 g = tb[(t1 + S::T1 * i) * N2];
+      float2 g = gt[i];
       g.y = -g.y;
       const float2 o = c_mul(v[i], g);
       sum[i].x += o.x;
@@ -557,8 +580,9 @@ hipError_t axis0_back_t(int mode, float2 *W, float *acc, const float2 *gu, long 
   if (TC > Mc) TC = Mc;
   const long blocks = volumes * (Mc / TC);
   if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
+  // exchange area of the transforms, then their twiddle table
   const size_t lds =
-      T == 1 ? 0 : static_cast<size_t>(E) * (T * TC + (E == 32 ? 0 : 1)) * sizeof(float2);
+      T == 1 ? 0 : (static_cast<size_t>(E) * (T * TC + (E == 32 ? 0 : 1)) + E * T) * sizeof(float2);
   const std::string name = "k3_axis0_back<" + std::to_string(E) + ", " + std::to_string(T) + ", " +
                            (mode ? "1>" : "0>");
   const double pts = static_cast<double>(volumes) * E * T * Mc;
@@ -586,14 +610,15 @@ hipError_t slab_fwd_mulacc_t(const float2 *W, const float2 *tab, float2 *A, long
   const double pts = static_cast<double>(slabs) * N1 * N2;
   LaunchScope obs(name.c_str(), pts * 8.0 * (P + 2) + 8.0 * P * n0 * N1 * N2,
                   pts * P * (5.0 * (ilog2h(N1) + ilog2h(N2)) + 8.0), st);
-  if (S::lds_bytes > 65536) {
+  const size_t lds = S::lds_bytes + S::tab_elems * sizeof(float2);
+  if (lds > 65536) {
     static unsigned long long lds_ok = 0;
     hipError_t e =
         allow_large_lds(reinterpret_cast<const void *>(k3_slab_fwd_mulacc<N1, N2>), lds_ok);
     if (e != hipSuccess) return e;
   }
   hipLaunchKernelGGL((k3_slab_fwd_mulacc<N1, N2>), dim3(static_cast<unsigned>(blocks)), dim3(S::NT),
-                     S::lds_bytes, st, W, tab, A, slabs, n0, P, static_cast<size_t>(slabs) * N1 * N2,
+                     lds, st, W, tab, A, slabs, n0, P, static_cast<size_t>(slabs) * N1 * N2,
                      tw, tw_n);
   return hipGetLastError();
 }
