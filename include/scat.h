@@ -173,8 +173,8 @@ scat_status scat_forward(scat_plan *plan, const float *in, float *out, long batc
  * below fp32 resolution.
  * Errors: SCAT_ERR_ARG for batch < 0.  SCAT_ERR_SHAPE, 2-D: unless every
  * side and every side subsampled for the last octave lies in 4...512 and the output grid
- * has at most 1024 points or, for images at most 256 wide, is one of 16 x 16 ... 128 x 128,
- * square or 2 : 1; 1-D: unless the signal, seen as the n1 x n2 matrix of the
+ * has at most 1024 points or is one of 16 x 16 ... 128 x 128, square or 2 : 1 (the latter
+ * only if the rows keep at least 4 points at every octave); 1-D: unless the signal, seen as the n1 x n2 matrix of the
  * four-step transform (n2 = 2^max(ceil(log2(n)/2), J), n1 = n / n2), has n1 in 4...512 and
  * n2 <= 512 (so n <= 2^18 at most).
  */

@@ -710,10 +710,12 @@ __global__ __launch_bounds__(256, 4) void k_rows2d_adj(float2 *__restrict__ dst,
       }
     }
   }
-  if (a.inverse) {
-    float2 wt[E];
-    load_twiddles<E, T>(wt, t, tw, tw_n);
-    fft_core<E, T, true, true>(acc, t, lds + rl * XS, T + 1, 1, wt);
+  if constexpr (T <= E) {  // (512-point rows, T = 32: no transform here, see the launcher)
+    if (a.inverse) {
+      float2 wt[E];
+      load_twiddles<E, T>(wt, t, tw, tw_n);
+      fft_core<E, T, true, true>(acc, t, lds + rl * XS, T + 1, 1, wt);
+    }
   }
   if (!valid) return;
   float2 *dp = dst + static_cast<size_t>(row) * Sc + t;
@@ -1188,7 +1190,7 @@ hipError_t launch_rows2d_adj_t(float2 *dst, long nodes, int Sr, Rows2dAdjArgs a,
   const int npb = RPB >> a.lg_rows;
   const long blocks = ((nodes + npb - 1) / npb) * (Sr >> a.lg_rows);
   if (blocks <= 0 || blocks > 0x7fffffffL) return hipErrorInvalidValue;
-  const size_t lds = static_cast<size_t>(RPB) * XS * sizeof(float2);
+  const size_t lds = T > E ? 0 : static_cast<size_t>(RPB) * XS * sizeof(float2);
   const std::string name = "k_rows2d_adj<" + std::to_string(E) + ", " + std::to_string(T) + ">";
   LaunchScope obs(name.c_str(), bytes, flops, st);
   hipLaunchKernelGGL((k_rows2d_adj<E, T>), dim3(static_cast<unsigned>(blocks)), dim3(256), lds, st, dst,
@@ -1196,10 +1198,16 @@ hipError_t launch_rows2d_adj_t(float2 *dst, long nodes, int Sr, Rows2dAdjArgs a,
   return hipGetLastError();
 }
 
+// row lengths of k_rows2d_adj: 4 ... 512, the inverse row transform up to 256
+bool rows2d_adj_supported(int Sc, bool inverse) {
+  return pow2(Sc) && Sc >= 4 && Sc <= (inverse ? 256 : 512);
+}
+
 hipError_t launch_rows2d_adj(float2 *dst, long nodes, int Sr, int Sc, const Rows2dAdjArgs &a,
                              const float2 *tw, int tw_n, hipStream_t st) {
   if (nodes <= 0) return hipSuccess;
-  if (a.n < 0 || a.n > kRows1dMaxChildren || !pow2(Sr) || !rows1d_adj_supported(Sc) || tw_n % Sc != 0)
+  if (a.n < 0 || a.n > kRows1dMaxChildren || !pow2(Sr) || !rows2d_adj_supported(Sc, a.inverse != 0) ||
+      tw_n % Sc != 0)
     return hipErrorInvalidValue;
   const int lgSc = ilog2h(Sc), lgSr = ilog2h(Sr);
   double bytes = static_cast<double>(nodes) * Sr * Sc * (a.accumulate ? 16 : 8);
@@ -1222,7 +1230,8 @@ hipError_t launch_rows2d_adj(float2 *dst, long nodes, int Sr, int Sc, const Rows
     case 32: return launch_rows2d_adj_t<16, 2>(dst, nodes, Sr, a, bytes, all_flops, tw, tw_n, st);
     case 64: return launch_rows2d_adj_t<16, 4>(dst, nodes, Sr, a, bytes, all_flops, tw, tw_n, st);
     case 128: return launch_rows2d_adj_t<16, 8>(dst, nodes, Sr, a, bytes, all_flops, tw, tw_n, st);
-    default: return launch_rows2d_adj_t<16, 16>(dst, nodes, Sr, a, bytes, all_flops, tw, tw_n, st);
+    case 256: return launch_rows2d_adj_t<16, 16>(dst, nodes, Sr, a, bytes, all_flops, tw, tw_n, st);
+    default: return launch_rows2d_adj_t<16, 32>(dst, nodes, Sr, a, bytes, all_flops, tw, tw_n, st);
   }
 }
 

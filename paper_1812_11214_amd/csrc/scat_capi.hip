@@ -881,8 +881,11 @@ struct BwdLayout {
 // digit of the four-step order) within those kernels' range.
 bool bwd_rows_adjoint(const scat_plan &p) {
   const scat::HostPlan &h = p.host;
-  for (int j = 0; j < h.J; ++j)
-    if (!scat::rows1d_adj_supported(p.n2 >> h.res(j))) return false;
+  for (int j = 0; j < h.J; ++j) {
+    const int len = p.n2 >> h.res(j);
+    if (h.dims == 1 ? !scat::rows1d_adj_supported(len) : !scat::rows2d_adj_supported(len, false))
+      return false;
+  }
   return true;
 }
 
@@ -990,8 +993,11 @@ scat_status backward_2d_rows_adjoint(scat_plan *p, const float *go, float *gi, l
                                 lg(Mr / m_r), lg(Mc / m_c), ChanMap{1, 1, 0, 0}, 0};
   };
   SCAT_TRY(scat::launch_small_fft2(go, pc, ChanMap{1, 1, 0, 0}, K, m_r, m_c, GHX, tw, tw_n, st));
+  // (rows of 512 points: the row-adjoint kernel leaves the inverse row transform to a pass of
+  // its own)
+  const bool top_inv = scat::rows2d_adj_supported(Nc, true);
   scat::Rows2dAdjArgs top{};
-  top.inverse = 1;
+  top.inverse = top_inv ? 1 : 0;
   top.c[top.n++] = low_child(GHX, 0, Nr, Nc);
   auto flush = [&](float2 *dst, long nodes, int Sr, int Sc, scat::Rows2dAdjArgs &a) -> hipError_t {
     hipError_t e = scat::launch_rows2d_adj(dst, nodes, Sr, Sc, a, tw, tw_n, st);
@@ -1020,8 +1026,9 @@ scat_status backward_2d_rows_adjoint(scat_plan *p, const float *go, float *gi, l
       SCAT_TRY(scat::launch_fft_rows_inplace(GUj, pc * L * M1r, M1c, false, tw, tw_n, st));
     } else {
       const int octs = J - 1 - j1;
+      const bool fused_inv = !node1 && scat::rows2d_adj_supported(M1c, true);
       scat::Rows2dAdjArgs a{};
-      a.inverse = node1 ? 0 : 1;
+      a.inverse = fused_inv ? 1 : 0;
       SCAT_TRY(scat::launch_small_fft2(go, pc * L, cm1, K, m_r, m_c, GHU, tw, tw_n, st));
       a.c[a.n++] = low_child(GHU, r1, M1r, M1c);
       float2 *GAj = GA;
@@ -1055,6 +1062,8 @@ scat_status backward_2d_rows_adjoint(scat_plan *p, const float *go, float *gi, l
       if (node1) {
         SCAT_TRY(scat::launch_node_modback(GUj, y1, pc * L, M1r, M1c, tw, tw_n, st));
       } else {
+        if (!fused_inv)
+          SCAT_TRY(scat::launch_fft_rows_inplace(GUj, pc * L * M1r, M1c, true, tw, tw_n, st));
         SCAT_TRY(scat::launch_cols_modback(GUj, y1, pc * L, M1r, M1c, tw, tw_n, st));
         SCAT_TRY(scat::launch_fft_rows_inplace(GUj, pc * L * M1r, M1c, false, tw, tw_n, st));
       }
@@ -1067,7 +1076,8 @@ scat_status backward_2d_rows_adjoint(scat_plan *p, const float *go, float *gi, l
     GUj += static_cast<size_t>(pc) * L * M1r * M1c;
   }
   SCAT_TRY(flush(GX, pc, Nr, Nc, top));
-  // g_x = Re(inverse transform): the rows are done
+  // g_x = Re(inverse transform): the rows are done (or follow here), then the columns
+  if (!top_inv) SCAT_TRY(scat::launch_fft_rows_inplace(GX, pc * Nr, Nc, true, tw, tw_n, st));
   SCAT_TRY(scat::launch_fft_cols_inplace(GX, pc, Nr, Nc, true, tw, tw_n, st));
   SCAT_TRY(scat::launch_take_real(GX, gi, pc * static_cast<long>(n), st));
   return SCAT_OK;

@@ -103,7 +103,7 @@ hipError_t launch_rows1d_adj(float2 *dst, long nodes, int Sr, int Sc, const Rows
 // 2-D: dst [nodes][Sr][Sc] (= or +=) sum_c filt_c * tile(src_c), child planes of
 // (Sr >> lg_fr) x (Sc >> lg_fc) gradient spectra, then (inverse != 0) the inverse row
 // transform (see k_rows2d_adj).  filt_row != nullptr: the filter is filt_row[kr] * filt[kc].
-// Child nodes as in Rows1dAdjChild.  Row lengths as rows1d_adj_supported.
+// Child nodes as in Rows1dAdjChild.  Row lengths 4 ... 512, with the inverse transform up to 256.
 struct Rows2dAdjChild {
   const float2 *src;
   const float *filt;
@@ -119,6 +119,7 @@ struct Rows2dAdjArgs {
   int lg_rows;  // set by the launcher
   Rows2dAdjChild c[kRows1dMaxChildren];
 };
+bool rows2d_adj_supported(int Sc, bool inverse);
 hipError_t launch_rows2d_adj(float2 *dst, long nodes, int Sr, int Sc, const Rows2dAdjArgs &a,
                              const float2 *tw, int tw_n, hipStream_t st);
 
