@@ -3,7 +3,8 @@
 // "Relation to previous software") and gives no formulas; the forward cascade is a chain of
 // real-linear maps and complex moduli, so its transpose is the chain of adjoints in
 // reverse order:
-//   S = Re IFFT_m(fold(Z^ phi))   ->  g_Z^ = tile(FFT_m(g_S)) phi        (k_lowpass_adj)
+//   S = Re IFFT_m(fold(Z^ phi))   ->  g_Z^ = tile(FFT_m(g_S)) phi        (k_small_fft2 / k_slab_fft2_real, then
+//                                                                        the consumer tiles and multiplies)
 //   Z^ = FFT(Z), Z real           ->  g_Z  = Re IFFT(g_Z^)               (k_fft_rows, k_cols_modback)
 //   Z = |y|                       ->  g_y  = g_Z y / |y|  (0 at y = 0)   (k_cols_modback)
 //   y = IFFT(fold(A^ psi))        ->  g_A^ += tile(FFT(g_y)) psi         (k_fft_* + k_tile_accum)
@@ -24,60 +25,6 @@ namespace {
 
 __device__ __forceinline__ int chan(const ChanMap &cm, int g) {
   return cm.base + (g / cm.inner) * cm.outer_stride + (g % cm.inner);
-}
-
-// Adjoint of the lowpass + subsampling: g_out [planes][K][m_r][m_c] real (node g of plane p
-// at channel chan(cm, g)) -> dst [node][Mr][Mc] = FFT2_m(g)[k_r mod m_r][k_c mod m_c] *
-// phi_rows[k_r] * phi_cols[k_c].  One workgroup per node; the m_r x m_c transform is two
-// dense stages in LDS (it is tiny next to the Mr x Mc plane written afterwards).
-__global__ __launch_bounds__(256) void k_lowpass_adj(const float *__restrict__ gout, ChanMap cm,
-                                                     int K, int m_r, int m_c, int lgMr, int lgMc,
-                                                     const float *__restrict__ phi_rows,
-                                                     const float *__restrict__ phi_cols,
-                                                     float2 *__restrict__ dst,
-                                                     const float2 *__restrict__ tw, int tw_n) {
-  extern __shared__ float2 lds[];
-  const int mm = m_r * m_c;
-  float2 *s1 = lds, *s2 = lds + mm;
-  float2 *twc = lds + 2 * mm, *twr = twc + m_c;  // exp(-2 pi i j / m_c), exp(-2 pi i j / m_r)
-  float *a = reinterpret_cast<float *>(twr + m_r);
-  const long node = blockIdx.x;
-  const long p = node / cm.G;
-  const int g = static_cast<int>(node - p * cm.G);
-  const float *gp = gout + (static_cast<size_t>(p) * K + chan(cm, g)) * mm;
-  for (int i = threadIdx.x; i < mm; i += blockDim.x) a[i] = gp[i];
-  const int sc = tw_n / m_c, sr = tw_n / m_r;
-  for (int i = threadIdx.x; i < m_c; i += blockDim.x) twc[i] = tw[i * sc];
-  for (int i = threadIdx.x; i < m_r; i += blockDim.x) twr[i] = tw[i * sr];
-  __syncthreads();
-  for (int i = threadIdx.x; i < mm; i += blockDim.x) {
-    const int r = i / m_c, kc = i - r * m_c;
-    float2 acc = make_float2(0.f, 0.f);
-    for (int b = 0; b < m_c; ++b) {
-      const float2 w = twc[(b * kc) & (m_c - 1)];
-      const float x = a[r * m_c + b];
-      acc.x += x * w.x;
-      acc.y += x * w.y;
-    }
-    s1[i] = acc;
-  }
-  __syncthreads();
-  for (int i = threadIdx.x; i < mm; i += blockDim.x) {
-    const int kr = i / m_c, kc = i - kr * m_c;
-    float2 acc = make_float2(0.f, 0.f);
-    for (int r = 0; r < m_r; ++r) acc = c_add(acc, c_mul(s1[r * m_c + kc], twr[(r * kr) & (m_r - 1)]));
-    s2[i] = acc;
-  }
-  __syncthreads();
-  const int Mc = 1 << lgMc;
-  const int total = 1 << (lgMr + lgMc);
-  float2 *dp = dst + (static_cast<size_t>(node) << (lgMr + lgMc));
-  for (int i = threadIdx.x; i < total; i += blockDim.x) {
-    const int kr = i >> lgMc, kc = i & (Mc - 1);
-    const float f = phi_rows[kr] * phi_cols[kc];
-    const float2 v = s2[(kr & (m_r - 1)) * m_c + (kc & (m_c - 1))];
-    dp[i] = make_float2(v.x * f, v.y * f);
-  }
 }
 
 // First half of the adjoint lowpass: Ghat [node][m_r][m_c] = FFT2 of the node's gradient
@@ -897,57 +844,6 @@ hipError_t launch_tile_filter(const float2 *ghat, const float *filt, float2 *dst
                   st);
   hipLaunchKernelGGL(k_tile_filter, dim3(grid_for(count)), dim3(256), 0, st, ghat, filt, dst, count,
                      ilog2h(n1), ilog2h(Mc), ilog2h(mc));
-  return hipGetLastError();
-}
-
-hipError_t launch_fft2_inplace(float2 *data, long nodes, int Mr, int Mc, bool inverse,
-                               const float2 *tw, int tw_n, hipStream_t st) {
-  if (nodes <= 0) return hipSuccess;
-  if (!backward_side_supported(Mr) || !backward_side_supported(Mc) || tw_n % Mr != 0 ||
-      tw_n % Mc != 0)
-    return hipErrorInvalidValue;
-  const long rows = nodes * Mr;
-  hipError_t e;
-#define SCAT_ROWS(E_, T_) e = rows_t<E_, T_>(data, rows, inverse, tw, tw_n, st)
-  switch (Mc) {
-    case 4: SCAT_ROWS(4, 1); break;
-    case 8: SCAT_ROWS(8, 1); break;
-    case 16: SCAT_ROWS(16, 1); break;
-    case 32: SCAT_ROWS(16, 2); break;
-    case 64: SCAT_ROWS(16, 4); break;
-    case 128: SCAT_ROWS(16, 8); break;
-    case 256: SCAT_ROWS(16, 16); break;
-    default: SCAT_ROWS(32, 16); break;
-  }
-#undef SCAT_ROWS
-  if (e != hipSuccess) return e;
-#define SCAT_COLS(E_, T_) return cols_t<E_, T_>(data, nodes, Mc, inverse, tw, tw_n, st)
-  switch (Mr) {
-    case 4: SCAT_COLS(4, 1);
-    case 8: SCAT_COLS(8, 1);
-    case 16: SCAT_COLS(16, 1);
-    case 32: SCAT_COLS(16, 2);
-    case 64: SCAT_COLS(16, 4);
-    case 128: SCAT_COLS(16, 8);
-    case 256: SCAT_COLS(16, 16);
-    default: SCAT_COLS(32, 16);
-  }
-#undef SCAT_COLS
-}
-
-hipError_t launch_lowpass_adj(const float *gout, long nodes, ChanMap cm, int K, int m_r, int m_c,
-                              int Mr, int Mc, const float *phi_rows, const float *phi_cols,
-                              float2 *dst, const float2 *tw, int tw_n, hipStream_t st) {
-  if (nodes <= 0) return hipSuccess;
-  if (!pow2(m_r) || !pow2(m_c) || !pow2(Mr) || !pow2(Mc) || m_r > Mr || m_c > Mc ||
-      m_r * m_c > 1024 || tw_n % m_r != 0 || tw_n % m_c != 0 || nodes > 0x7fffffffL)
-    return hipErrorInvalidValue;
-  const size_t lds = static_cast<size_t>(m_r) * m_c * (2 * sizeof(float2) + sizeof(float)) +
-                     static_cast<size_t>(m_r + m_c) * sizeof(float2);
-  LaunchScope obs("k_lowpass_adj", nodes * (m_r * m_c * 4.0 + Mr * 8.0 * Mc),
-                  nodes * (8.0 * m_r * m_c * (m_r + m_c) + 3.0 * Mr * Mc), st);
-  hipLaunchKernelGGL(k_lowpass_adj, dim3(static_cast<unsigned>(nodes)), dim3(256), lds, st, gout, cm,
-                     K, m_r, m_c, ilog2h(Mr), ilog2h(Mc), phi_rows, phi_cols, dst, tw, tw_n);
   return hipGetLastError();
 }
 

@@ -876,16 +876,12 @@ struct BwdLayout {
   size_t pad_floats = 0;  // padded plans: extended input + extended gradients, floats per plane
 };
 
-// Backward pass, 1-D and 2-D: the schedules built on the row-adjoint kernels (a node's
-// gradient from all its children in one launch) need every octave's row length (1-D: second
-// digit of the four-step order) within those kernels' range.
+// 1-D backward pass: the schedule built on the adjoint of the forward row kernel needs every
+// octave's row length (second digit of the four-step order) within that kernel's range.
 bool bwd_rows_adjoint(const scat_plan &p) {
   const scat::HostPlan &h = p.host;
-  for (int j = 0; j < h.J; ++j) {
-    const int len = p.n2 >> h.res(j);
-    if (h.dims == 1 ? !scat::rows1d_adj_supported(len) : !scat::rows2d_adj_supported(len, false))
-      return false;
-  }
+  for (int j = 0; j < h.J; ++j)
+    if (!scat::rows1d_adj_supported(p.n2 >> h.res(j))) return false;
   return true;
 }
 
@@ -936,19 +932,15 @@ BwdLayout make_bwd_layout(const scat_plan &p, long batch) {
     }
     b.tape = make_tape(p);
     b.gx = n;
-    b.gu = l * n;
-    b.ga = t2;
     // spectra of the output-grid gradient planes of one launch (at most L*L, or L, nodes)
     const size_t mm = static_cast<size_t>(p.n1 >> h.res(h.J)) * (p.n2 >> h.res(h.J));
     b.gh = (second ? l * l : l) * mm;
-    if (bwd_rows_adjoint(p)) {
-      // every octave's first-order gradients at once, the second-order gradients of one j1
-      // (all j2 > j1); output-grid spectra of x's and of one octave's own channels besides
-      b.gu = b.ga = 0;
-      for (int j = 0; j < h.J; ++j) b.gu += l * (n >> (2 * h.res(j)));
-      for (int j = 1; second && j < h.J; ++j) b.ga += l * l * (n >> (2 * h.res(j)));
-      b.gh += (l + 1) * mm;
-    }
+    // every octave's first-order gradients at once, the second-order gradients of one j1
+    // (all j2 > j1); output-grid spectra of x's and of one octave's own channels besides
+    b.gu = b.ga = 0;
+    for (int j = 0; j < h.J; ++j) b.gu += l * (n >> (2 * h.res(j)));
+    for (int j = 1; second && j < h.J; ++j) b.ga += l * l * (n >> (2 * h.res(j)));
+    b.gh += (l + 1) * mm;
     if (p.padded)
       b.pad_floats = 2 * n + static_cast<size_t>(h.K) * (p.n1 >> h.res(h.J)) * (p.n2 >> h.res(h.J));
     b.per_plane = b.fwd.xh + b.fwd.t + b.fwd.u + b.fwd.v +
@@ -1099,85 +1091,15 @@ scat_status backward_2d(scat_plan *p, const float *in, const float *gout, float 
   float2 *GU = GX + bl.gx * pc;
   float2 *GA = GU + bl.gu * pc;
   float2 *GH = GA + bl.ga * pc;
-  const float *tab = p->d_tables;
-  const float2 *tw = p->d_tw;
-  const int tw_n = p->tw_n;
   const float *go = gout + static_cast<size_t>(p0) * K * m_r * m_c;
   float *gi = gin + static_cast<size_t>(p0) * n;
 
   scat_status fs = p->fused ? forward_2d_fused(p, in, nullptr, p0, pc, bl.fwd, st, &bl.tape)
                             : forward_2d(p, in, nullptr, p0, pc, bl.fwd, st, &bl.tape);
   if (fs != SCAT_OK) return fs;
-  if (bwd_rows_adjoint(*p)) return backward_2d_rows_adjoint(p, go, gi, pc, bl, GX, GU, GA, GH, st);
-
-  // order 0: g_X^ = adjoint lowpass of g_S0
-  SCAT_TRY(scat::launch_lowpass_adj(go, pc, ChanMap{1, 1, 0, 0}, K, m_r, m_c, Nr, Nc,
-                                    tab + p->phi_rows_off[0], tab + p->phi_cols_off[0], GX, tw, tw_n,
-                                    st));
-  int s2_base = 1 + J * L;
-  for (int j1 = 0; j1 < J; ++j1) {
-    const int r1 = h.res(j1);
-    const int M1r = Nr >> r1, M1c = Nc >> r1;
-    const bool kids = h.max_order == 2 && j1 < J - 1;
-    // g_U1^ starts as the adjoint lowpass of g_S1, then collects its children; without
-    // children the inverse row transform can follow in the same pass
-    // nodes small enough for one workgroup take the whole modulus backward step (both
-    // inverse passes, the modulus, both forward passes) in a single kernel
-    const bool node1 = scat::node_modback_supported(M1r, M1c);
-    const float2 *y1 = bl.tape.base + bl.tape.y1_off[j1] * pc;
-    if (kids) {
-      SCAT_TRY(scat::launch_lowpass_adj(go, pc * L, ChanMap{L, L, 0, 1 + j1 * L}, K, m_r, m_c, M1r,
-                                        M1c, tab + p->phi_rows_off[r1], tab + p->phi_cols_off[r1],
-                                        GU, tw, tw_n, st));
-    } else if (node1) {
-      SCAT_TRY(scat::launch_node_modback_low(go, pc * L, ChanMap{L, L, 0, 1 + j1 * L}, K, m_r, m_c,
-                                             M1r, M1c, tab + p->phi_rows_off[r1],
-                                             tab + p->phi_cols_off[r1], GH, y1, GU, tw, tw_n, st));
-    } else {
-      SCAT_TRY(scat::launch_lowpass_adj_rows(go, pc * L, ChanMap{L, L, 0, 1 + j1 * L}, K, m_r, m_c,
-                                             M1r, M1c, tab + p->phi_rows_off[r1],
-                                             tab + p->phi_cols_off[r1], GH, GU, tw, tw_n, st));
-    }
-    if (kids) {
-      const int octs = J - 1 - j1;
-      for (int j2 = j1 + 1; j2 < J; ++j2) {
-        const int r2 = h.res(j2);
-        const int M2r = Nr >> r2, M2c = Nc >> r2;
-        const long nodes = pc * L * L;
-        // adjoint lowpass and inverse rows in one pass; then one column pass (inverse,
-        // modulus backward against the tape, forward); then forward rows and the
-        // accumulation into the parent's gradient spectrum (fusing those two was measured
-        // and is not faster: the accumulate is bound by its filter reads)
-        const ChanMap cm2{L * L, L, octs * L, s2_base + (j2 - j1 - 1) * L};
-        const float2 *y2 = bl.tape.base + bl.tape.y2_off.at({j1, j2}) * pc;
-        if (scat::node_modback_supported(M2r, M2c)) {
-          SCAT_TRY(scat::launch_node_modback_low(go, nodes, cm2, K, m_r, m_c, M2r, M2c,
-                                                 tab + p->phi_rows_off[r2], tab + p->phi_cols_off[r2],
-                                                 GH, y2, GA, tw, tw_n, st));
-        } else {
-          SCAT_TRY(scat::launch_lowpass_adj_rows(go, nodes, cm2, K, m_r, m_c, M2r, M2c,
-                                                 tab + p->phi_rows_off[r2], tab + p->phi_cols_off[r2],
-                                                 GH, GA, tw, tw_n, st));
-          SCAT_TRY(scat::launch_cols_modback(GA, y2, nodes, M2r, M2c, tw, tw_n, st));
-          SCAT_TRY(scat::launch_fft_rows_inplace(GA, nodes * M2r, M2c, false, tw, tw_n, st));
-        }
-        SCAT_TRY(scat::launch_tile_accum(GU, tab + p->psi2_off[{r1, j2}], GA, pc * L, L, M1r, M1c,
-                                         M2r, M2c, st));
-      }
-      s2_base += L * L * octs;
-    }
-    if (kids && node1) {
-      SCAT_TRY(scat::launch_node_modback(GU, y1, pc * L, M1r, M1c, tw, tw_n, st));
-    } else if (kids || !node1) {
-      if (kids) SCAT_TRY(scat::launch_fft_rows_inplace(GU, pc * L * M1r, M1c, true, tw, tw_n, st));
-      SCAT_TRY(scat::launch_cols_modback(GU, y1, pc * L, M1r, M1c, tw, tw_n, st));
-      SCAT_TRY(scat::launch_fft_rows_inplace(GU, pc * L * M1r, M1c, false, tw, tw_n, st));
-    }
-    SCAT_TRY(scat::launch_tile_accum(GX, tab + p->psi1_off[j1], GU, pc, L, Nr, Nc, M1r, M1c, st));
-  }
-  SCAT_TRY(scat::launch_fft2_inplace(GX, pc, Nr, Nc, true, tw, tw_n, st));
-  SCAT_TRY(scat::launch_take_real(GX, gi, pc * static_cast<long>(n), st));
-  return SCAT_OK;
+  // (every plan scat_backward accepts keeps at least 4 points per row at every octave, which
+  // is all the row-adjoint schedule asks for)
+  return backward_2d_rows_adjoint(p, go, gi, pc, bl, GX, GU, GA, GH, st);
 }
 
 scat_status forward_1d(scat_plan *p, const float *in, float *out, long p0, long pc,
@@ -1937,10 +1859,7 @@ scat_status scat_backward(scat_plan *plan, const float *in, const float *grad_ou
     // output grid must fit the adjoint lowpass kernel's LDS stage
     const int small_r = plan->n1 >> h.res(h.J - 1), small_c = plan->n2 >> h.res(h.J - 1);
     const int m_r = plan->n1 >> h.res(h.J), m_c = plan->n2 >> h.res(h.J);
-    // (the per-level schedule's adjoint lowpass kernel transforms the gradient plane itself,
-    // in LDS: 1024 points at most)
-    const bool grid_ok = bwd_rows_adjoint(*plan) ? scat::small_fft2_supported(m_r, m_c)
-                                                 : static_cast<long>(m_r) * m_c <= 1024;
+    const bool grid_ok = scat::small_fft2_supported(m_r, m_c);
     if (!scat::backward_side_supported(plan->n1) || !scat::backward_side_supported(plan->n2) ||
         !scat::backward_side_supported(small_r) || !scat::backward_side_supported(small_c) || !grid_ok)
       return SCAT_ERR_SHAPE;

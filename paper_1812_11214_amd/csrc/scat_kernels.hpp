@@ -195,9 +195,6 @@ hipError_t launch_node_modback_low(const float *gout, long nodes, ChanMap cm, in
 // ---- backward pass (scat_backward.hip): plain 2-D transforms in place and the adjoints of
 // the lowpass, the modulus and the filter-multiply-fold step.  Sides 4...512.
 bool backward_side_supported(int m);
-// data [nodes][Mr][Mc] complex, unnormalised forward or inverse 2-D transform in place
-hipError_t launch_fft2_inplace(float2 *data, long nodes, int Mr, int Mc, bool inverse,
-                               const float2 *tw, int tw_n, hipStream_t st);
 // rows only: data [rows][Mc]
 hipError_t launch_fft_rows_inplace(float2 *data, long rows, int Mc, bool inverse, const float2 *tw,
                                    int tw_n, hipStream_t st);
@@ -218,11 +215,6 @@ hipError_t launch_gather_real(const float *gout, long nodes, ChanMap cm, int K, 
 // dst[node][k1][k2] = ghat[node][k1][k2 mod mc] * filt[k1][k2]
 hipError_t launch_tile_filter(const float2 *ghat, const float *filt, float2 *dst, long nodes, int n1,
                               int Mc, int mc, hipStream_t st);
-// dst [nodes][Mr][Mc] = FFT2(g_out node)[k mod m] * phi_rows[k_r] * phi_cols[k_c]; node g of
-// plane p is channel chan(cm, g) of g_out [planes][K][m_r][m_c]; m_r * m_c <= 1024
-hipError_t launch_lowpass_adj(const float *gout, long nodes, ChanMap cm, int K, int m_r, int m_c,
-                              int Mr, int Mc, const float *phi_rows, const float *phi_cols,
-                              float2 *dst, const float2 *tw, int tw_n, hipStream_t st);
 // the same followed by the inverse row transform, in one pass over dst; `ghat` is scratch
 // of nodes * m_r * m_c elements
 hipError_t launch_lowpass_adj_rows(const float *gout, long nodes, ChanMap cm, int K, int m_r,
