@@ -165,3 +165,38 @@ def test_backward_1d(n, J, Q, max_order, o, batch):
     print("backward 1d", n, J, Q, max_order, o, "max-rel %.2e l2-rel %.2e" % (worst_max, worst_l2),
           flush=True)
     assert worst_max <= TOL_MAX and worst_l2 <= TOL_L2, (worst_max, worst_l2)
+
+
+@pytest.mark.parametrize("shape,J,LQ,batch", [((64, 64), 3, 4, 7), ((4096,), 5, 4, 5)])
+def test_backward_in_chunks_matches_one_pass(shape, J, LQ, batch):
+    """A scratch budget that forces one plane per chunk (read once per process, hence the child
+    process) gives bit for bit the gradient of the single-chunk pass."""
+    import torch
+    import subprocess, sys, os, tempfile
+    rng = np.random.default_rng(5 + len(shape))
+    x = rng.standard_normal((batch,) + shape).astype(np.float32)
+    plan = scat.Scattering(shape, J, LQ)
+    try:
+        g = rng.standard_normal((batch, plan.K) + plan.out_shape).astype(np.float32)
+        a = plan.backward(torch.from_numpy(x).cuda(), torch.from_numpy(g).cuda())
+        torch.cuda.synchronize()
+        a = a.cpu().numpy()
+    finally:
+        plan.close()
+    code = (
+        "import sys, numpy as np, torch\n"
+        "sys.path.insert(0, %r)\n"
+        "import paper_1812_11214_amd as scat\n"
+        "d = np.load(sys.argv[1])\n"
+        "p = scat.Scattering(%r, %d, %d)\n"
+        "y = p.backward(torch.from_numpy(d['x']).cuda(), torch.from_numpy(d['g']).cuda())\n"
+        "torch.cuda.synchronize()\n"
+        "np.save(sys.argv[2], y.cpu().numpy()); p.close()\n"
+    ) % (os.path.dirname(os.path.dirname(os.path.abspath(__file__))), shape, J, LQ)
+    with tempfile.TemporaryDirectory() as d:
+        inp, out = os.path.join(d, "in.npz"), os.path.join(d, "y.npy")
+        np.savez(inp, x=x, g=g)
+        env = dict(os.environ, SCAT_SCRATCH_MB="1")
+        subprocess.run([sys.executable, "-c", code, inp, out], check=True, env=env, timeout=240)
+        b = np.load(out)
+    assert np.array_equal(a, b)
