@@ -687,7 +687,7 @@ __global__ __launch_bounds__(256, 4) void k_rows2d_adj(float2 *__restrict__ dst,
 // phi_rows[k_r] phi_cols[k_c]; otherwise it is read from `data` (and replaced).
 // Per point: the tape read and the spectrum written (plus the spectrum read without LOW),
 // where the separate row and column passes read and write the node three times.
-template <int N1, int N2, bool LOW>
+template <int N1, int N2, bool LOW, bool YROWS>
 __global__ __launch_bounds__((Slab<N1, N2>::NT)) void k_node_modback(
     const float2 *__restrict__ ghat, int m_r, int m_c, const float *__restrict__ phi_rows,
     const float *__restrict__ phi_cols, const float2 *__restrict__ y, float2 *__restrict__ data,
@@ -729,6 +729,10 @@ __global__ __launch_bounds__((Slab<N1, N2>::NT)) void k_node_modback(
     for (int i = 0; i < 16; ++i) yv[i] = yp[(t1 + S::T1 * i) * N2];
   }
   S::template transform_tab<true>(v, area, r, t, c, t1, wtab);
+  // YROWS: `y` holds the forward row pass's output (the node before its inverse column
+  // transform); the columns are transformed here, which spares the forward pass that kernel
+  // and the tape one write and one read of the node
+  if (YROWS) fft_core_tab<16, S::T1, true, false>(yv, t1, area + c, S::T1 * S::RS, S::RS, wtab + N2 + t1, S::T1);
   {
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
@@ -1019,7 +1023,7 @@ hipError_t launch_rows1d_adj(float2 *dst, long nodes, int Sr, int Sc, const Rows
   }
 }
 
-template <int N1, int N2, bool LOW>
+template <int N1, int N2, bool LOW, bool YROWS>
 hipError_t node_modback_t(const float2 *ghat, int m_r, int m_c, const float *phi_rows,
                           const float *phi_cols, const float2 *y, float2 *data, long nodes,
                           const float2 *tw, int tw_n, hipStream_t st) {
@@ -1027,17 +1031,17 @@ hipError_t node_modback_t(const float2 *ghat, int m_r, int m_c, const float *phi
   const long blocks = (nodes + S::SPW - 1) / S::SPW;
   if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
   const std::string name = "k_node_modback<" + std::to_string(N1) + ", " + std::to_string(N2) +
-                           (LOW ? ", true>" : ", false>");
+                           (LOW ? ", true" : ", false") + (YROWS ? ", true>" : ", false>");
   const double pts = static_cast<double>(nodes) * N1 * N2;
   LaunchScope obs(name.c_str(), pts * (LOW ? 16.0 : 24.0) + (LOW ? nodes * 8.0 * m_r * m_c : 0.0),
-                  pts * (10.0 * (ilog2h(N1) + ilog2h(N2)) + 8.0), st);
+                  pts * (10.0 * (ilog2h(N1) + ilog2h(N2)) + 8.0 + (YROWS ? 5.0 * ilog2h(N1) : 0.0)), st);
   const size_t lds = S::lds_bytes + S::tab_elems * sizeof(float2);
   if (lds > 65536) {
     static unsigned long long lds_ok = 0;
-    hipError_t e = allow_large_lds(reinterpret_cast<const void *>(k_node_modback<N1, N2, LOW>), lds_ok);
+    hipError_t e = allow_large_lds(reinterpret_cast<const void *>(k_node_modback<N1, N2, LOW, YROWS>), lds_ok);
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL((k_node_modback<N1, N2, LOW>), dim3(static_cast<unsigned>(blocks)), dim3(S::NT),
+  hipLaunchKernelGGL((k_node_modback<N1, N2, LOW, YROWS>), dim3(static_cast<unsigned>(blocks)), dim3(S::NT),
                      lds, st, ghat, m_r, m_c, phi_rows, phi_cols, y, data, nodes, tw, tw_n);
   return hipGetLastError();
 }
@@ -1049,7 +1053,7 @@ hipError_t launch_node_modback(float2 *data, const float2 *y, long nodes, int Mr
       y == nullptr)
     return hipErrorInvalidValue;
 #define SCAT_NM(A_, B_) \
-  return node_modback_t<A_, B_, false>(nullptr, 1, 1, nullptr, nullptr, y, data, nodes, tw, tw_n, st)
+  return node_modback_t<A_, B_, false, false>(nullptr, 1, 1, nullptr, nullptr, y, data, nodes, tw, tw_n, st)
   SCAT_NODE_DISPATCH(SCAT_NM)
 #undef SCAT_NM
 }
@@ -1057,7 +1061,7 @@ hipError_t launch_node_modback(float2 *data, const float2 *y, long nodes, int Mr
 hipError_t launch_node_modback_low(const float *gout, long nodes, ChanMap cm, int K, int m_r, int m_c,
                                    int Mr, int Mc, const float *phi_rows, const float *phi_cols,
                                    float2 *ghat, const float2 *y, float2 *dst, const float2 *tw,
-                                   int tw_n, hipStream_t st) {
+                                   int tw_n, hipStream_t st, bool y_rows) {
   if (nodes <= 0) return hipSuccess;
   if (!node_modback_supported(Mr, Mc) || !small_fft2_supported(m_r, m_c) || m_r > Mr || m_c > Mc ||
       tw_n % Mr != 0 || tw_n % Mc != 0 || tw_n % m_r != 0 || tw_n % m_c != 0 ||
@@ -1067,8 +1071,11 @@ hipError_t launch_node_modback_low(const float *gout, long nodes, ChanMap cm, in
     hipError_t e = launch_small_fft2(gout, nodes, cm, K, m_r, m_c, ghat, tw, tw_n, st);
     if (e != hipSuccess) return e;
   }
-#define SCAT_NL(A_, B_) \
-  return node_modback_t<A_, B_, true>(ghat, m_r, m_c, phi_rows, phi_cols, y, dst, nodes, tw, tw_n, st)
+#define SCAT_NL(A_, B_)                                                                           \
+  return y_rows ? node_modback_t<A_, B_, true, true>(ghat, m_r, m_c, phi_rows, phi_cols, y, dst, \
+                                                     nodes, tw, tw_n, st)                        \
+                : node_modback_t<A_, B_, true, false>(ghat, m_r, m_c, phi_rows, phi_cols, y, dst, \
+                                                      nodes, tw, tw_n, st)
   SCAT_NODE_DISPATCH(SCAT_NL)
 #undef SCAT_NL
 }

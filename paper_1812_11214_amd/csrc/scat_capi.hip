@@ -758,6 +758,14 @@ scat_status forward_2d(scat_plan *p, const float *in, float *out, long p0, long 
 
 // ---- 2-D schedule with the fused row pass (no full 2-D spectrum is ever stored).  With a
 // tape the signals before each modulus are kept and the outputs S are not formed.
+// Taped forward pass of a fused 2-D plan: a leaf node (no children below it) small enough for
+// the whole-node backward kernel is taped as the row pass leaves it, before its inverse
+// column transform -- that kernel transforms the columns itself, and the forward pass skips
+// the leaf's column kernel.
+bool tape_holds_rows(const scat_plan &p, int Mr, int Mc) {
+  return p.fused && scat::node_modback_supported(Mr, Mc);
+}
+
 scat_status forward_2d_fused(scat_plan *p, const float *in, float *out, long p0, long pc,
                              const Layout &lay, hipStream_t st, const Tape *tape = nullptr) {
   const scat::HostPlan &h = p->host;
@@ -804,7 +812,10 @@ scat_status forward_2d_fused(scat_plan *p, const float *in, float *out, long p0,
     scat::FusedLevel lv[4];
     size_t off = 0;
     for (int j1 = 0; j1 < J; ++j1) {
+      const bool kids = h.max_order == 2 && j1 < J - 1;
       t1[j1] = T + off;
+      if (tape != nullptr && !kids && tape_holds_rows(*p, Nr >> h.res(j1), Nc >> h.res(j1)))
+        t1[j1] = tape->base + tape->y1_off[j1] * pc;  // straight to the tape, no column pass
       lv[j1] = scat::FusedLevel{h.res(j1), L, tab + p->psi1_off[j1], t1[j1]};
       off += static_cast<size_t>(pc) * L * (n >> (2 * h.res(j1)));
     }
@@ -815,6 +826,7 @@ scat_status forward_2d_fused(scat_plan *p, const float *in, float *out, long p0,
     const int r1 = h.res(j1);
     const int M1r = Nr >> r1, M1c = Nc >> r1;
     const bool kids = h.max_order == 2 && j1 < J - 1;
+    if (tape != nullptr && !kids && tape_holds_rows(*p, M1r, M1c)) continue;
     SCAT_TRY(col_and_lowpass(1, t1[j1], pc * L, M1r, M1c, r1, kids ? U : nullptr,
                              ChanMap{L, L, 0, 1 + j1 * L},
                              tape ? tape->base + tape->y1_off[j1] * pc : nullptr));
@@ -826,6 +838,8 @@ scat_status forward_2d_fused(scat_plan *p, const float *in, float *out, long p0,
       size_t off = 0;
       for (int j2 = j1 + 1; j2 < J; ++j2) {
         t2[j2] = V + off;
+        if (tape != nullptr && tape_holds_rows(*p, Nr >> h.res(j2), Nc >> h.res(j2)))
+          t2[j2] = tape->base + tape->y2_off.at({j1, j2}) * pc;
         lv[j2 - j1 - 1] = scat::FusedLevel{h.res(j2) - r1, L, tab + p->psi2_off[{r1, j2}], t2[j2]};
         off += static_cast<size_t>(pc) * L * L * (n >> (2 * h.res(j2)));
       }
@@ -834,6 +848,7 @@ scat_status forward_2d_fused(scat_plan *p, const float *in, float *out, long p0,
     for (int j2 = j1 + 1; j2 < J; ++j2) {
       const int r2 = h.res(j2);
       const int M2r = Nr >> r2, M2c = Nc >> r2;
+      if (tape != nullptr && tape_holds_rows(*p, M2r, M2c)) continue;
       SCAT_TRY(col_and_lowpass(1, t2[j2], pc * L * L, M2r, M2c, r2, nullptr,
                                ChanMap{L * L, L, octs * L, s2_base + (j2 - j1 - 1) * L},
                                tape ? tape->base + tape->y2_off.at({j1, j2}) * pc : nullptr));
@@ -1009,7 +1024,7 @@ scat_status backward_2d_rows_adjoint(scat_plan *p, const float *go, float *gi, l
     if (!kids && node1) {
       SCAT_TRY(scat::launch_node_modback_low(go, pc * L, cm1, K, m_r, m_c, M1r, M1c,
                                              tab + p->phi_rows_off[r1], tab + p->phi_cols_off[r1], GH,
-                                             y1, GUj, tw, tw_n, st));
+                                             y1, GUj, tw, tw_n, st, tape_holds_rows(*p, M1r, M1c)));
     } else if (!kids) {
       SCAT_TRY(scat::launch_lowpass_adj_rows(go, pc * L, cm1, K, m_r, m_c, M1r, M1c,
                                              tab + p->phi_rows_off[r1], tab + p->phi_cols_off[r1], GH,
@@ -1033,7 +1048,8 @@ scat_status backward_2d_rows_adjoint(scat_plan *p, const float *go, float *gi, l
         if (scat::node_modback_supported(M2r, M2c)) {
           SCAT_TRY(scat::launch_node_modback_low(go, nodes, cm2, K, m_r, m_c, M2r, M2c,
                                                  tab + p->phi_rows_off[r2], tab + p->phi_cols_off[r2],
-                                                 GH, y2, GAj, tw, tw_n, st));
+                                                 GH, y2, GAj, tw, tw_n, st,
+                                                 tape_holds_rows(*p, M2r, M2c)));
         } else {
           SCAT_TRY(scat::launch_lowpass_adj_rows(go, nodes, cm2, K, m_r, m_c, M2r, M2c,
                                                  tab + p->phi_rows_off[r2], tab + p->phi_cols_off[r2],

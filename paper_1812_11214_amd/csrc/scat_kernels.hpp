@@ -179,7 +179,9 @@ hipError_t launch_tree32(const float2 *xh, long planes, int L, int max_order, co
 // Modulus backward step of whole nodes in one pass (k_node_modback): data [nodes][Mr][Mc]
 // gradient spectra in, gradient spectra of the taped y [nodes][Mr][Mc] out, in place.  The
 // _low form starts from the node's adjoint lowpass instead (arguments as
-// launch_lowpass_adj_rows; ghat is scratch for nodes * m_r * m_c elements).
+// launch_lowpass_adj_rows; ghat is scratch for nodes * m_r * m_c elements); with y_rows, y is
+// the node before its inverse column transform (the forward row pass's output) and the
+// kernel transforms the columns itself.
 bool node_modback_supported(int Mr, int Mc);
 // ghat [node][m_r][m_c] = 2-D transform of the nodes' output gradient planes
 bool small_fft2_supported(int m_r, int m_c);
@@ -190,7 +192,7 @@ hipError_t launch_node_modback(float2 *data, const float2 *y, long nodes, int Mr
 hipError_t launch_node_modback_low(const float *gout, long nodes, ChanMap cm, int K, int m_r, int m_c,
                                    int Mr, int Mc, const float *phi_rows, const float *phi_cols,
                                    float2 *ghat, const float2 *y, float2 *dst, const float2 *tw,
-                                   int tw_n, hipStream_t st);
+                                   int tw_n, hipStream_t st, bool y_rows = false);
 
 // ---- backward pass (scat_backward.hip): plain 2-D transforms in place and the adjoints of
 // the lowpass, the modulus and the filter-multiply-fold step.  Sides 4...512.
