@@ -250,8 +250,8 @@ __global__ __launch_bounds__(256) void k_fft_cols(float2 *__restrict__ data, int
 template <int E, int T>
 __global__ __launch_bounds__(256, (E <= 16 ? 3 : 1)) void k_cols_modback(float2 *__restrict__ data,
                                                       const float2 *__restrict__ y, int Mc, int TC,
-                                                      int tw_m, const float2 *__restrict__ tw,
-                                                      int tw_n) {
+                                                      int tw_m, int y_rows,
+                                                      const float2 *__restrict__ tw, int tw_n) {
   constexpr int M = E * T;
   extern __shared__ float2 lds[];
   const int KS = T * TC + (E == 32 ? 0 : 1);
@@ -309,17 +309,21 @@ __global__ __launch_bounds__(256, (E <= 16 ? 3 : 1)) void k_cols_modback(float2 
   } else {
     load_twiddles<E, T>(wt, t, tw, tw_n);
   }
-  auto transform = [&](auto inv) {
+  auto transform_of = [&](float2 (&a)[E], auto inv) {
     if constexpr (WTAB)
-      fft_core_tab<E, T, decltype(inv)::value, false>(v, t, lds + c, KS, TC, wtab + t, T);
+      fft_core_tab<E, T, decltype(inv)::value, false>(a, t, lds + c, KS, TC, wtab + t, T);
     else
-      fft_core<E, T, decltype(inv)::value, false>(v, t, lds + c, KS, TC, wt);
+      fft_core<E, T, decltype(inv)::value, false>(a, t, lds + c, KS, TC, wt);
   };
+  auto transform = [&](auto inv) { transform_of(v, inv); };
   // the tape values are requested before the inverse transform and used after it (3 waves
   // per SIMD with them in flight beat 4 without)
   float2 yv[E];
 #pragma unroll
   for (int i = 0; i < E; ++i) yv[i] = yp[i * step];
+  // y_rows: `y` holds the node before its inverse column transform (the forward row pass's
+  // output, which spares the forward pass its column kernel): transformed here
+  if (y_rows) transform_of(yv, std::true_type{});
   transform(std::true_type{});
 #pragma unroll
   for (int i = 0; i < E; ++i) {
@@ -444,7 +448,7 @@ hipError_t cols_t(float2 *data, long nodes, int Mc, bool inverse, const float2 *
 }
 
 template <int E, int T>
-hipError_t cols_modback_t(float2 *data, const float2 *y, long nodes, int Mc, int tw_m,
+hipError_t cols_modback_t(float2 *data, const float2 *y, long nodes, int Mc, int tw_m, bool y_rows,
                           const float2 *tw, int tw_n, hipStream_t st) {
   int TC = 256 / T;
   if (TC > Mc) TC = Mc;
@@ -459,9 +463,9 @@ hipError_t cols_modback_t(float2 *data, const float2 *y, long nodes, int Mc, int
                            std::to_string(T) + ">";
   const double n = static_cast<double>(E) * T;
   LaunchScope obs(name.c_str(), nodes * n * Mc * 24,
-                  nodes * Mc * (10.0 * n * ilog2h(E * T) + 8.0 * n), st);
+                  nodes * Mc * ((y_rows ? 15.0 : 10.0) * n * ilog2h(E * T) + 8.0 * n), st);
   hipLaunchKernelGGL((k_cols_modback<E, T>), dim3(static_cast<unsigned>(blocks)), dim3(T * TC), lds,
-                     st, data, y, Mc, TC, tw_m, tw, tw_n);
+                     st, data, y, Mc, TC, tw_m, static_cast<int>(y_rows), tw, tw_n);
   return hipGetLastError();
 }
 
@@ -773,12 +777,12 @@ hipError_t launch_fft_rows_inplace(float2 *data, long rows, int Mc, bool inverse
 }
 
 hipError_t launch_cols_modback(float2 *data, const float2 *y, long nodes, int Mr, int Mc,
-                               const float2 *tw, int tw_n, hipStream_t st, int tw_m) {
+                               const float2 *tw, int tw_n, hipStream_t st, int tw_m, bool y_rows) {
   if (nodes <= 0) return hipSuccess;
   if (!backward_side_supported(Mr) || !pow2(Mc) || Mc > 512 || tw_n % Mr != 0 ||
       (tw_m > 0 && (!pow2(tw_m) || tw_n % tw_m != 0)))
     return hipErrorInvalidValue;
-#define SCAT_CM(E_, T_) return cols_modback_t<E_, T_>(data, y, nodes, Mc, tw_m, tw, tw_n, st)
+#define SCAT_CM(E_, T_) return cols_modback_t<E_, T_>(data, y, nodes, Mc, tw_m, y_rows, tw, tw_n, st)
   switch (Mr) {
     case 4: SCAT_CM(4, 1);
     case 8: SCAT_CM(8, 1);

@@ -204,7 +204,8 @@ hipError_t launch_fft_rows_inplace(float2 *data, long rows, int Mc, bool inverse
 // against y of the same layout, forward transform
 // tw_m > 0: with the four-step twiddles exp(+-2 pi i k1 b / tw_m) around the column passes
 hipError_t launch_cols_modback(float2 *data, const float2 *y, long nodes, int Mr, int Mc,
-                               const float2 *tw, int tw_n, hipStream_t st, int tw_m = 0);
+                               const float2 *tw, int tw_n, hipStream_t st, int tw_m = 0,
+                               bool y_rows = false);
 // columns only (any power-of-two number of columns up to 512)
 hipError_t launch_fft_cols_inplace(float2 *data, long nodes, int Mr, int Mc, bool inverse,
                                    const float2 *tw, int tw_n, hipStream_t st);
