@@ -758,13 +758,11 @@ scat_status forward_2d(scat_plan *p, const float *in, float *out, long p0, long 
 
 // ---- 2-D schedule with the fused row pass (no full 2-D spectrum is ever stored).  With a
 // tape the signals before each modulus are kept and the outputs S are not formed.
-// Taped forward pass of a fused 2-D plan: a leaf node (no children below it) small enough for
-// the whole-node backward kernel is taped as the row pass leaves it, before its inverse
-// column transform -- that kernel transforms the columns itself, and the forward pass skips
-// the leaf's column kernel.
-bool tape_holds_rows(const scat_plan &p, int Mr, int Mc) {
-  return p.fused && scat::node_modback_supported(Mr, Mc);
-}
+// Taped forward pass of a fused 2-D plan: a leaf node (no children below it) is taped as the
+// row pass leaves it, before its inverse column transform -- the backward kernels (whole-node
+// or column) transform the columns themselves, and the forward pass skips the leaf's column
+// kernel.
+bool tape_holds_rows(const scat_plan &p) { return p.fused; }
 
 scat_status forward_2d_fused(scat_plan *p, const float *in, float *out, long p0, long pc,
                              const Layout &lay, hipStream_t st, const Tape *tape = nullptr) {
@@ -814,7 +812,7 @@ scat_status forward_2d_fused(scat_plan *p, const float *in, float *out, long p0,
     for (int j1 = 0; j1 < J; ++j1) {
       const bool kids = h.max_order == 2 && j1 < J - 1;
       t1[j1] = T + off;
-      if (tape != nullptr && !kids && tape_holds_rows(*p, Nr >> h.res(j1), Nc >> h.res(j1)))
+      if (tape != nullptr && !kids && tape_holds_rows(*p))
         t1[j1] = tape->base + tape->y1_off[j1] * pc;  // straight to the tape, no column pass
       lv[j1] = scat::FusedLevel{h.res(j1), L, tab + p->psi1_off[j1], t1[j1]};
       off += static_cast<size_t>(pc) * L * (n >> (2 * h.res(j1)));
@@ -826,7 +824,7 @@ scat_status forward_2d_fused(scat_plan *p, const float *in, float *out, long p0,
     const int r1 = h.res(j1);
     const int M1r = Nr >> r1, M1c = Nc >> r1;
     const bool kids = h.max_order == 2 && j1 < J - 1;
-    if (tape != nullptr && !kids && tape_holds_rows(*p, M1r, M1c)) continue;
+    if (tape != nullptr && !kids && tape_holds_rows(*p)) continue;
     SCAT_TRY(col_and_lowpass(1, t1[j1], pc * L, M1r, M1c, r1, kids ? U : nullptr,
                              ChanMap{L, L, 0, 1 + j1 * L},
                              tape ? tape->base + tape->y1_off[j1] * pc : nullptr));
@@ -838,7 +836,7 @@ scat_status forward_2d_fused(scat_plan *p, const float *in, float *out, long p0,
       size_t off = 0;
       for (int j2 = j1 + 1; j2 < J; ++j2) {
         t2[j2] = V + off;
-        if (tape != nullptr && tape_holds_rows(*p, Nr >> h.res(j2), Nc >> h.res(j2)))
+        if (tape != nullptr && tape_holds_rows(*p))
           t2[j2] = tape->base + tape->y2_off.at({j1, j2}) * pc;
         lv[j2 - j1 - 1] = scat::FusedLevel{h.res(j2) - r1, L, tab + p->psi2_off[{r1, j2}], t2[j2]};
         off += static_cast<size_t>(pc) * L * L * (n >> (2 * h.res(j2)));
@@ -848,7 +846,7 @@ scat_status forward_2d_fused(scat_plan *p, const float *in, float *out, long p0,
     for (int j2 = j1 + 1; j2 < J; ++j2) {
       const int r2 = h.res(j2);
       const int M2r = Nr >> r2, M2c = Nc >> r2;
-      if (tape != nullptr && tape_holds_rows(*p, M2r, M2c)) continue;
+      if (tape != nullptr && tape_holds_rows(*p)) continue;
       SCAT_TRY(col_and_lowpass(1, t2[j2], pc * L * L, M2r, M2c, r2, nullptr,
                                ChanMap{L * L, L, octs * L, s2_base + (j2 - j1 - 1) * L},
                                tape ? tape->base + tape->y2_off.at({j1, j2}) * pc : nullptr));
@@ -1024,12 +1022,13 @@ scat_status backward_2d_rows_adjoint(scat_plan *p, const float *go, float *gi, l
     if (!kids && node1) {
       SCAT_TRY(scat::launch_node_modback_low(go, pc * L, cm1, K, m_r, m_c, M1r, M1c,
                                              tab + p->phi_rows_off[r1], tab + p->phi_cols_off[r1], GH,
-                                             y1, GUj, tw, tw_n, st, tape_holds_rows(*p, M1r, M1c)));
+                                             y1, GUj, tw, tw_n, st, tape_holds_rows(*p)));
     } else if (!kids) {
       SCAT_TRY(scat::launch_lowpass_adj_rows(go, pc * L, cm1, K, m_r, m_c, M1r, M1c,
                                              tab + p->phi_rows_off[r1], tab + p->phi_cols_off[r1], GH,
                                              GUj, tw, tw_n, st));
-      SCAT_TRY(scat::launch_cols_modback(GUj, y1, pc * L, M1r, M1c, tw, tw_n, st));
+      SCAT_TRY(scat::launch_cols_modback(GUj, y1, pc * L, M1r, M1c, tw, tw_n, st, 0,
+                                         tape_holds_rows(*p)));
       SCAT_TRY(scat::launch_fft_rows_inplace(GUj, pc * L * M1r, M1c, false, tw, tw_n, st));
     } else {
       const int octs = J - 1 - j1;
@@ -1049,12 +1048,13 @@ scat_status backward_2d_rows_adjoint(scat_plan *p, const float *go, float *gi, l
           SCAT_TRY(scat::launch_node_modback_low(go, nodes, cm2, K, m_r, m_c, M2r, M2c,
                                                  tab + p->phi_rows_off[r2], tab + p->phi_cols_off[r2],
                                                  GH, y2, GAj, tw, tw_n, st,
-                                                 tape_holds_rows(*p, M2r, M2c)));
+                                                 tape_holds_rows(*p)));
         } else {
           SCAT_TRY(scat::launch_lowpass_adj_rows(go, nodes, cm2, K, m_r, m_c, M2r, M2c,
                                                  tab + p->phi_rows_off[r2], tab + p->phi_cols_off[r2],
                                                  GH, GAj, tw, tw_n, st));
-          SCAT_TRY(scat::launch_cols_modback(GAj, y2, nodes, M2r, M2c, tw, tw_n, st));
+          SCAT_TRY(scat::launch_cols_modback(GAj, y2, nodes, M2r, M2c, tw, tw_n, st, 0,
+                                             tape_holds_rows(*p)));
           SCAT_TRY(scat::launch_fft_rows_inplace(GAj, nodes * M2r, M2c, false, tw, tw_n, st));
         }
         for (int l2 = 0; l2 < L; ++l2) {
