@@ -594,6 +594,23 @@ __global__ __launch_bounds__(256, 4) void k_rows1d_adj(float2 *__restrict__ dst,
   for (int i = 0; i < E; ++i) dp[T * i] = acc[i];
 }
 
+// acc[i] += f[i] * s[i mod EP]: the child's EP distinct values of this lane (sp[T j], j < EP)
+// against the filter values fp[T i] (times fr)
+template <int E, int T, int EP>
+__device__ __forceinline__ void rows2d_accumulate(float2 (&acc)[E], const float2 *__restrict__ sp,
+                                                  const float *__restrict__ fp, float fr) {
+  constexpr int NP = EP < E ? EP : E;
+  float2 sv[NP];
+#pragma unroll
+  for (int j = 0; j < NP; ++j) sv[j] = sp[T * j];
+#pragma unroll
+  for (int i = 0; i < E; ++i) {
+    const float f = fr * fp[T * i];
+    acc[i].x += sv[i % NP].x * f;
+    acc[i].y += sv[i % NP].y * f;
+  }
+}
+
 // ------------------------------------------------------------------------------------
 // 2-D cascade: the gradient spectrum of a parent, dst [nodes][Sr][Sc], from the gradient
 // spectra of all its children in one pass,
@@ -612,6 +629,8 @@ __global__ __launch_bounds__(256, 4) void k_rows2d_adj(float2 *__restrict__ dst,
   static_assert(E == 16 || T == 1, "short rows are held by one lane");
   constexpr int Sc = E * T, RPB = 256 / T;
   constexpr int XS = T == 1 ? E : E * (T + 1);
+  constexpr int lgT = T == 1 ? 0 : T == 2 ? 1 : T == 4 ? 2 : T == 8 ? 3 : T == 16 ? 4 : 5;
+  constexpr int lgSc = (E == 4 ? 2 : E == 8 ? 3 : 4) + lgT;
   extern __shared__ float2 lds[];
   // A workgroup takes 2^lgR rows kr0 + a (Sr >> lgR) of each of its nodes: the rows that
   // read the same rows of the folded children (2^lgR = the largest fold of the list, at most
@@ -632,33 +651,19 @@ __global__ __launch_bounds__(256, 4) void k_rows2d_adj(float2 *__restrict__ dst,
     const long cnode = ch.K > 0 ? (node / ch.cm.G) * ch.K + chan(ch.cm, static_cast<int>(node % ch.cm.G))
                                 : node * ch.cm.G + ch.cm.base;
     const float2 *sp = ch.src + (static_cast<size_t>(cnode) * Mr + (kr & (Mr - 1))) * m;
-    // lane t needs the child's row at (t + T i) mod m: its first m / T values repeat
-    float2 sv[E];
-#pragma unroll
-    for (int i = 0; i < E; ++i)
-      if (i == 0 || t + T * i < m) sv[i] = sp[(t + T * i) & (m - 1)];
-#pragma unroll
-    for (int h = 1; h < E; h <<= 1)
-      if (T * h >= m) {
-#pragma unroll
-        for (int i = 0; i < h; ++i) sv[i + h] = sv[i];
-      }
-    if (ch.filt_row != nullptr) {
-      const float fr = ch.filt_row[kr];
-#pragma unroll
-      for (int i = 0; i < E; ++i) {
-        const float f = fr * ch.filt[t + T * i];
-        acc[i].x += sv[i].x * f;
-        acc[i].y += sv[i].y * f;
-      }
-    } else {
-      const float *fp = ch.filt + static_cast<size_t>(kr) * Sc + t;
-#pragma unroll
-      for (int i = 0; i < E; ++i) {
-        const float f = fp[T * i];
-        acc[i].x += sv[i].x * f;
-        acc[i].y += sv[i].y * f;
-      }
+    // lane t needs the child's row at (t + T i) mod m: its first EP = m / T values, repeated
+    // (below T points: the single value at t mod m).  EP is the same for the whole launch's
+    // lanes, so the accumulate is specialised on it: EP loads at fixed offsets, no masks.
+    const float fr = ch.filt_row != nullptr ? ch.filt_row[kr] : 1.f;
+    const float *fp = ch.filt_row != nullptr ? ch.filt + t : ch.filt + static_cast<size_t>(kr) * Sc + t;
+    const int lgEP = (lgSc - ch.lg_fc) - lgT;
+    switch (lgEP) {
+      case 0: rows2d_accumulate<E, T, 1>(acc, sp + t, fp, fr); break;
+      case 1: rows2d_accumulate<E, T, 2>(acc, sp + t, fp, fr); break;
+      case 2: rows2d_accumulate<E, T, 4>(acc, sp + t, fp, fr); break;
+      case 3: rows2d_accumulate<E, T, 8>(acc, sp + t, fp, fr); break;
+      case 4: rows2d_accumulate<E, T, 16>(acc, sp + t, fp, fr); break;
+      default: rows2d_accumulate<E, T, 1>(acc, sp + (t & (m - 1)), fp, fr); break;  // m < T
     }
   }
   if constexpr (T <= E) {  // (512-point rows, T = 32: no transform here, see the launcher)
