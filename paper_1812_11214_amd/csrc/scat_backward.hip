@@ -1056,13 +1056,16 @@ hipError_t node_modback_t(const float2 *ghat, int m_r, int m_c, const float *phi
 }
 
 hipError_t launch_node_modback(float2 *data, const float2 *y, long nodes, int Mr, int Mc,
-                               const float2 *tw, int tw_n, hipStream_t st) {
+                               const float2 *tw, int tw_n, hipStream_t st, bool y_rows) {
   if (nodes <= 0) return hipSuccess;
   if (!node_modback_supported(Mr, Mc) || tw_n % Mr != 0 || tw_n % Mc != 0 || data == nullptr ||
       y == nullptr)
     return hipErrorInvalidValue;
-#define SCAT_NM(A_, B_) \
-  return node_modback_t<A_, B_, false, false>(nullptr, 1, 1, nullptr, nullptr, y, data, nodes, tw, tw_n, st)
+#define SCAT_NM(A_, B_)                                                                          \
+  return y_rows ? node_modback_t<A_, B_, false, true>(nullptr, 1, 1, nullptr, nullptr, y, data,  \
+                                                      nodes, tw, tw_n, st)                       \
+                : node_modback_t<A_, B_, false, false>(nullptr, 1, 1, nullptr, nullptr, y, data, \
+                                                       nodes, tw, tw_n, st)
   SCAT_NODE_DISPATCH(SCAT_NM)
 #undef SCAT_NM
 }

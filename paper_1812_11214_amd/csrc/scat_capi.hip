@@ -677,7 +677,10 @@ Tape make_tape(const scat_plan &p) {
   size_t off = 0;
   for (int j1 = 0; j1 < h.J; ++j1) {
     t.y1_off.push_back(off);
-    off += l * (n >> (d * h.res(j1)));
+    // (fused 2-D plans read the first-order signals of nodes with children from the forward
+    // pass's own buffer: no tape slot)
+    const bool kids = h.max_order == 2 && j1 < h.J - 1;
+    if (!(d == 2 && p.fused && kids)) off += l * (n >> (d * h.res(j1)));
   }
   if (h.max_order == 2)
     for (int j1 = 0; j1 < h.J; ++j1)
@@ -761,7 +764,8 @@ scat_status forward_2d(scat_plan *p, const float *in, float *out, long p0, long 
 // Taped forward pass of a fused 2-D plan: a leaf node (no children below it) is taped as the
 // row pass leaves it, before its inverse column transform -- the backward kernels (whole-node
 // or column) transform the columns themselves, and the forward pass skips the leaf's column
-// kernel.
+// kernel.  First-order nodes with children are not taped at all: their row-pass output stays
+// in the forward pass's buffer T, and the backward pass reads it there the same way.
 bool tape_holds_rows(const scat_plan &p) { return p.fused; }
 
 scat_status forward_2d_fused(scat_plan *p, const float *in, float *out, long p0, long pc,
@@ -827,7 +831,8 @@ scat_status forward_2d_fused(scat_plan *p, const float *in, float *out, long p0,
     if (tape != nullptr && !kids && tape_holds_rows(*p)) continue;
     SCAT_TRY(col_and_lowpass(1, t1[j1], pc * L, M1r, M1c, r1, kids ? U : nullptr,
                              ChanMap{L, L, 0, 1 + j1 * L},
-                             tape ? tape->base + tape->y1_off[j1] * pc : nullptr));
+                             tape && !tape_holds_rows(*p) ? tape->base + tape->y1_off[j1] * pc
+                                                          : nullptr));
     if (!kids) continue;
     const int octs = J - 1 - j1;
     std::vector<float2 *> t2(J);
@@ -1012,12 +1017,19 @@ scat_status backward_2d_rows_adjoint(scat_plan *p, const float *go, float *gi, l
   };
   int s2_base = 1 + J * L;
   float2 *GUj = GU;
+  const float2 *Tfwd = reinterpret_cast<const float2 *>(static_cast<const char *>(p->d_scratch) +
+                                                        bl.fwd.xh * pc);
+  size_t t_off = 0;  // as forward_2d_fused lays out T: all octaves, one after the other
   for (int j1 = 0; j1 < J; ++j1) {
     const int r1 = h.res(j1);
     const int M1r = Nr >> r1, M1c = Nc >> r1;
     const bool kids = second && j1 < J - 1;
     const bool node1 = scat::node_modback_supported(M1r, M1c);
+    // the signal before the modulus: taped (leaves of fused plans: as row-pass output), or
+    // for nodes with children of fused plans the row-pass output still in the forward buffer
     const float2 *y1 = bl.tape.base + bl.tape.y1_off[j1] * pc;
+    if (kids && tape_holds_rows(*p)) y1 = Tfwd + t_off;
+    t_off += static_cast<size_t>(pc) * L * M1r * M1c;
     const ChanMap cm1{L, L, 0, 1 + j1 * L};
     if (!kids && node1) {
       SCAT_TRY(scat::launch_node_modback_low(go, pc * L, cm1, K, m_r, m_c, M1r, M1c,
@@ -1068,11 +1080,13 @@ scat_status backward_2d_rows_adjoint(scat_plan *p, const float *go, float *gi, l
       s2_base += L * L * octs;
       SCAT_TRY(flush(GUj, pc * L, M1r, M1c, a));
       if (node1) {
-        SCAT_TRY(scat::launch_node_modback(GUj, y1, pc * L, M1r, M1c, tw, tw_n, st));
+        SCAT_TRY(scat::launch_node_modback(GUj, y1, pc * L, M1r, M1c, tw, tw_n, st,
+                                           tape_holds_rows(*p)));
       } else {
         if (!fused_inv)
           SCAT_TRY(scat::launch_fft_rows_inplace(GUj, pc * L * M1r, M1c, true, tw, tw_n, st));
-        SCAT_TRY(scat::launch_cols_modback(GUj, y1, pc * L, M1r, M1c, tw, tw_n, st));
+        SCAT_TRY(scat::launch_cols_modback(GUj, y1, pc * L, M1r, M1c, tw, tw_n, st, 0,
+                                           tape_holds_rows(*p)));
         SCAT_TRY(scat::launch_fft_rows_inplace(GUj, pc * L * M1r, M1c, false, tw, tw_n, st));
       }
     }

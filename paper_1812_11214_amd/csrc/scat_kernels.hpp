@@ -188,7 +188,7 @@ bool small_fft2_supported(int m_r, int m_c);
 hipError_t launch_small_fft2(const float *gout, long nodes, ChanMap cm, int K, int m_r, int m_c,
                              float2 *ghat, const float2 *tw, int tw_n, hipStream_t st);
 hipError_t launch_node_modback(float2 *data, const float2 *y, long nodes, int Mr, int Mc,
-                               const float2 *tw, int tw_n, hipStream_t st);
+                               const float2 *tw, int tw_n, hipStream_t st, bool y_rows = false);
 hipError_t launch_node_modback_low(const float *gout, long nodes, ChanMap cm, int K, int m_r, int m_c,
                                    int Mr, int Mc, const float *phi_rows, const float *phi_cols,
                                    float2 *ghat, const float2 *y, float2 *dst, const float2 *tw,
