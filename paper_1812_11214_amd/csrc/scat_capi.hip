@@ -1176,11 +1176,11 @@ scat_status backward_1d(scat_plan *p, const float *in, const float *gout, float 
     return scat::launch_tile_filter(GH, tab + p->phi_off[res], dst, nodes, N1, Mc, mc_out, st);
   };
   // spectrum -> signal, modulus backward against the taped y, signal -> spectrum
-  // (leaf: y is the taped row-pass output of a node without children, see forward_1d)
-  auto through_modulus = [&](float2 *g, const float2 *y, long nodes, int Mc, bool leaf) -> hipError_t {
+  // (y is the taped row-pass output of the node, see forward_1d)
+  auto through_modulus = [&](float2 *g, const float2 *y, long nodes, int Mc) -> hipError_t {
     hipError_t e = scat::launch_fft_rows_inplace(g, nodes * N1, Mc, true, tw, tw_n, st);
     if (e != hipSuccess) return e;
-    e = scat::launch_cols_modback(g, y, nodes, N1, Mc, tw, tw_n, st, Mc > 1 ? N1 * Mc : 0, leaf);
+    e = scat::launch_cols_modback(g, y, nodes, N1, Mc, tw, tw_n, st, Mc > 1 ? N1 * Mc : 0, true);
     if (e != hipSuccess) return e;
     return scat::launch_fft_rows_inplace(g, nodes * N1, Mc, false, tw, tw_n, st);
   };
@@ -1235,7 +1235,7 @@ scat_status backward_1d(scat_plan *p, const float *in, const float *gout, float 
       if (kids) s2 += Q * octs;
       SCAT_TRY(scat::launch_rows1d_adj(GUj, pc * Q, N1, Mc1, a, tw, tw_n, st));
       SCAT_TRY(scat::launch_cols_modback(GUj, bl.tape.base + bl.tape.y1_off[j1] * pc, pc * Q, N1, Mc1,
-                                         tw, tw_n, st, Mc1 > 1 ? N1 * Mc1 : 0, !kids));
+                                         tw, tw_n, st, Mc1 > 1 ? N1 * Mc1 : 0, true));
       for (int q = 0; q < Q; ++q) {
         if (top.n == scat::kRows1dMaxChildren) SCAT_TRY(flush_top());
         top.c[top.n++] = scat::Rows1dAdjChild{
@@ -1263,12 +1263,12 @@ scat_status backward_1d(scat_plan *p, const float *in, const float *gout, float 
       const int r2 = h.res(j2);
       const int Mc2 = N2 >> r2;
       SCAT_TRY(lowpass_adj(pc * Q, ChanMap{Q, 1, octs, s2_base + (j2 - j1 - 1)}, r2, Mc2, GA));
-      SCAT_TRY(through_modulus(GA, bl.tape.base + bl.tape.y2_off.at({j1, j2}) * pc, pc * Q, Mc2, true));
+      SCAT_TRY(through_modulus(GA, bl.tape.base + bl.tape.y2_off.at({j1, j2}) * pc, pc * Q, Mc2));
       SCAT_TRY(scat::launch_tile_accum(GU, tab + p->psi2_off[{r1, j2}], GA, pc * Q, 1, N1, Mc1, N1,
                                        Mc2, st));
     }
     if (kids) s2_base += Q * octs;
-    SCAT_TRY(through_modulus(GU, bl.tape.base + bl.tape.y1_off[j1] * pc, pc * Q, Mc1, !kids));
+    SCAT_TRY(through_modulus(GU, bl.tape.base + bl.tape.y1_off[j1] * pc, pc * Q, Mc1));
     SCAT_TRY(scat::launch_tile_accum(GX, tab + p->psi1_off[j1], GU, pc, Q, N1, N2, N1, Mc1, st));
   }
   // g_x = Re(inverse four-step transform of g_X^)
@@ -1644,19 +1644,16 @@ scat_status forward_1d(scat_plan *p, const float *in, float *out, long p0, long 
     const int Mc1 = N2 >> r1;
     const int M1 = N >> r1;
     const bool kids = h.max_order == 2 && j1 < J - 1;
-    // Taped pass: a leaf node (no children below it) is taped as its row pass leaves it,
-    // before the inverse column transform, which the backward pass's column kernel does
-    // itself; the leaf's column kernel is skipped here.
-    if (tape != nullptr && !kids) {
-      SCAT_TRY(scat::launch_mulfold_invrow(XH, tab + p->psi1_off[j1], tape->base + tape->y1_off[j1] * pc,
-                                           pc, Q, N1, N2, 0, r1, M1, tw, tw_n, st));
-      continue;
-    }
-    SCAT_TRY(scat::launch_mulfold_invrow(XH, tab + p->psi1_off[j1], T, pc, Q, N1, N2, 0, r1, M1,
+    // Taped pass: every node is taped as its row pass leaves it, before the inverse column
+    // transform, which the backward pass's column kernel does itself: the row pass writes
+    // straight into the tape, a leaf (no children below it) needs no column kernel here, and
+    // the column kernel of a node with children writes their spectra only.
+    float2 *t1 = tape ? tape->base + tape->y1_off[j1] * pc : T;
+    SCAT_TRY(scat::launch_mulfold_invrow(XH, tab + p->psi1_off[j1], t1, pc, Q, N1, N2, 0, r1, M1,
                                          tw, tw_n, st));
-    SCAT_TRY(scat::launch_col(1, T, pc * Q, N1, Mc1, U, M1, nullptr, 0, nullptr, nullptr, none, K,
-                              tw, tw_n, st, false,
-                              tape ? tape->base + tape->y1_off[j1] * pc : nullptr));
+    if (tape != nullptr && !kids) continue;
+    SCAT_TRY(scat::launch_col(1, t1, pc * Q, N1, Mc1, U, M1, nullptr, 0, nullptr, nullptr, none, K,
+                              tw, tw_n, st));
     // one pass over the rows of U: the lowpass and the wavelets of every coarser octave
     scat::Rows1dArgs ch;
     ch.n = 0;
