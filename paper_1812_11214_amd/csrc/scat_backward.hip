@@ -611,6 +611,25 @@ __device__ __forceinline__ void rows2d_accumulate(float2 (&acc)[E], const float2
   }
 }
 
+// The same for a child of full row length given BEFORE its forward row transform (pre_rows):
+// the lane's 16 values are transformed in registers first, which spares the child a row pass
+// of its own.
+template <int E, int T>
+__device__ __forceinline__ void rows2d_accumulate_fft(float2 (&acc)[E], const float2 *__restrict__ sp,
+                                                      const float *__restrict__ fp, float fr, int t,
+                                                      float2 *xch, const float2 *wtab) {
+  float2 sv[E];
+#pragma unroll
+  for (int j = 0; j < E; ++j) sv[j] = sp[T * j];
+  fft_core_tab<E, T, false, true>(sv, t, xch, T + 1, 1, wtab + t, T);
+#pragma unroll
+  for (int i = 0; i < E; ++i) {
+    const float f = fr * fp[T * i];
+    acc[i].x += sv[i].x * f;
+    acc[i].y += sv[i].y * f;
+  }
+}
+
 // ------------------------------------------------------------------------------------
 // 2-D cascade: the gradient spectrum of a parent, dst [nodes][Sr][Sc], from the gradient
 // spectra of all its children in one pass,
@@ -632,6 +651,14 @@ __global__ __launch_bounds__(256, 4) void k_rows2d_adj(float2 *__restrict__ dst,
   constexpr int lgT = T == 1 ? 0 : T == 2 ? 1 : T == 4 ? 2 : T == 8 ? 3 : T == 16 ? 4 : 5;
   constexpr int lgSc = (E == 4 ? 2 : E == 8 ? 3 : 4) + lgT;
   extern __shared__ float2 lds[];
+  // twiddles of the children's forward row transforms (pre_rows), wtab[k T + t], behind the
+  // rows' exchange areas
+  float2 *wtab = lds + RPB * XS;
+  if (T > 1 && T <= E && a.any_pre_rows) {
+    for (int idx = threadIdx.x; idx < Sc; idx += blockDim.x)
+      wtab[idx] = tw[(idx / T) * (idx % T) * (tw_n / Sc)];
+    __syncthreads();
+  }
   // A workgroup takes 2^lgR rows kr0 + a (Sr >> lgR) of each of its nodes: the rows that
   // read the same rows of the folded children (2^lgR = the largest fold of the list, at most
   // 256 / T), so that those are fetched from memory once; its nodes share the filters' rows.
@@ -657,6 +684,12 @@ __global__ __launch_bounds__(256, 4) void k_rows2d_adj(float2 *__restrict__ dst,
     const float fr = ch.filt_row != nullptr ? ch.filt_row[kr] : 1.f;
     const float *fp = ch.filt_row != nullptr ? ch.filt + t : ch.filt + static_cast<size_t>(kr) * Sc + t;
     const int lgEP = (lgSc - ch.lg_fc) - lgT;
+    if constexpr (T <= E) {
+      if (ch.pre_rows) {  // (full-length rows only, checked by the launcher)
+        rows2d_accumulate_fft<E, T>(acc, sp + t, fp, fr, t, lds + rl * XS, wtab);
+        continue;
+      }
+    }
     switch (lgEP) {
       case 0: rows2d_accumulate<E, T, 1>(acc, sp + t, fp, fr); break;
       case 1: rows2d_accumulate<E, T, 2>(acc, sp + t, fp, fr); break;
@@ -1105,7 +1138,10 @@ hipError_t launch_rows2d_adj_t(float2 *dst, long nodes, int Sr, Rows2dAdjArgs a,
   const int npb = RPB >> a.lg_rows;
   const long blocks = ((nodes + npb - 1) / npb) * (Sr >> a.lg_rows);
   if (blocks <= 0 || blocks > 0x7fffffffL) return hipErrorInvalidValue;
-  const size_t lds = T > E ? 0 : static_cast<size_t>(RPB) * XS * sizeof(float2);
+  a.any_pre_rows = 0;
+  for (int i = 0; i < a.n; ++i)
+    if (a.c[i].pre_rows) a.any_pre_rows = 1;
+  const size_t lds = T > E ? 0 : (static_cast<size_t>(RPB) * XS + E * T) * sizeof(float2);
   const std::string name = "k_rows2d_adj<" + std::to_string(E) + ", " + std::to_string(T) + ">";
   LaunchScope obs(name.c_str(), bytes, flops, st);
   hipLaunchKernelGGL((k_rows2d_adj<E, T>), dim3(static_cast<unsigned>(blocks)), dim3(256), lds, st, dst,
@@ -1131,8 +1167,10 @@ hipError_t launch_rows2d_adj(float2 *dst, long nodes, int Sr, int Sc, const Rows
     const Rows2dAdjChild &c = a.c[i];
     if (c.src == nullptr || c.filt == nullptr || c.lg_fr < 0 || c.lg_fr > lgSr || c.lg_fc < 0 ||
         c.lg_fc > lgSc || c.cm.G < 1 || (c.K == 0 && (c.cm.base < 0 || c.cm.base >= c.cm.G)) ||
-        (c.K > 0 && (c.cm.inner < 1 || nodes % c.cm.G != 0)))
+        (c.K > 0 && (c.cm.inner < 1 || nodes % c.cm.G != 0)) ||
+        (c.pre_rows != 0 && (c.lg_fc != 0 || Sc > 256)))
       return hipErrorInvalidValue;
+    if (c.pre_rows) flops += 5.0 * Sc * lgSc;
     bytes += (c.filt_row != nullptr ? 0.0 : static_cast<double>(Sr) * Sc * 4) +
              static_cast<double>(nodes) * (Sr >> c.lg_fr) * (Sc >> c.lg_fc) * 8;
     flops += 4.0 * Sc;

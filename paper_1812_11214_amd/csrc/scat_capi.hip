@@ -1025,6 +1025,9 @@ scat_status backward_2d_rows_adjoint(scat_plan *p, const float *go, float *gi, l
     const int M1r = Nr >> r1, M1c = Nc >> r1;
     const bool kids = second && j1 < J - 1;
     const bool node1 = scat::node_modback_supported(M1r, M1c);
+    // a full-resolution level that goes through the column kernel leaves its forward row
+    // transform to x's row-adjoint launch, which does it in registers on the way in
+    const bool pre_rows = !node1 && r1 == 0 && top_inv;
     // the signal before the modulus: taped (leaves of fused plans: as row-pass output), or
     // for nodes with children of fused plans the row-pass output still in the forward buffer
     const float2 *y1 = bl.tape.base + bl.tape.y1_off[j1] * pc;
@@ -1041,7 +1044,8 @@ scat_status backward_2d_rows_adjoint(scat_plan *p, const float *go, float *gi, l
                                              GUj, tw, tw_n, st));
       SCAT_TRY(scat::launch_cols_modback(GUj, y1, pc * L, M1r, M1c, tw, tw_n, st, 0,
                                          tape_holds_rows(*p)));
-      SCAT_TRY(scat::launch_fft_rows_inplace(GUj, pc * L * M1r, M1c, false, tw, tw_n, st));
+      if (!pre_rows)
+        SCAT_TRY(scat::launch_fft_rows_inplace(GUj, pc * L * M1r, M1c, false, tw, tw_n, st));
     } else {
       const int octs = J - 1 - j1;
       const bool fused_inv = !node1 && scat::rows2d_adj_supported(M1c, true);
@@ -1087,13 +1091,14 @@ scat_status backward_2d_rows_adjoint(scat_plan *p, const float *go, float *gi, l
           SCAT_TRY(scat::launch_fft_rows_inplace(GUj, pc * L * M1r, M1c, true, tw, tw_n, st));
         SCAT_TRY(scat::launch_cols_modback(GUj, y1, pc * L, M1r, M1c, tw, tw_n, st, 0,
                                            tape_holds_rows(*p)));
-        SCAT_TRY(scat::launch_fft_rows_inplace(GUj, pc * L * M1r, M1c, false, tw, tw_n, st));
+        if (!pre_rows)
+          SCAT_TRY(scat::launch_fft_rows_inplace(GUj, pc * L * M1r, M1c, false, tw, tw_n, st));
       }
     }
     for (int l = 0; l < L; ++l) {
       if (top.n == scat::kRows1dMaxChildren) SCAT_TRY(flush(GX, pc, Nr, Nc, top));
       top.c[top.n++] = scat::Rows2dAdjChild{GUj, tab + p->psi1_off[j1] + static_cast<size_t>(l) * n,
-                                            nullptr, r1, r1, ChanMap{L, 1, 0, l}, 0};
+                                            nullptr, r1, r1, ChanMap{L, 1, 0, l}, 0, pre_rows ? 1 : 0};
     }
     GUj += static_cast<size_t>(pc) * L * M1r * M1c;
   }

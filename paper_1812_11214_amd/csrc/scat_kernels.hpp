@@ -111,12 +111,13 @@ struct Rows2dAdjChild {
   int lg_fr, lg_fc;
   ChanMap cm;
   int K;
+  int pre_rows;  // 1: src is given before its forward row transform (lg_fc == 0, rows <= 256)
 };
 struct Rows2dAdjArgs {
   int n;
   int accumulate;
   int inverse;
-  int lg_rows;  // set by the launcher
+  int lg_rows, any_pre_rows;  // set by the launcher
   Rows2dAdjChild c[kRows1dMaxChildren];
 };
 bool rows2d_adj_supported(int Sc, bool inverse);
