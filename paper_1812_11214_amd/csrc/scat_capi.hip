@@ -942,7 +942,8 @@ BwdLayout make_bwd_layout(const scat_plan &p, long batch) {
       b.fwd.xh = n * c8;
       b.fwd.t = ft1 * c8;
       b.fwd.u = second ? l * n * c8 : 0;
-      b.fwd.v = second ? ft2 * c8 : 0;
+      b.fwd.v = 0;  // the taped pass writes the second-order row-pass outputs into the tape
+      (void)ft2;
     } else {
       b.fwd.xh = n * c8;
       b.fwd.t = (t1 > t2 ? t1 : t2) * c8;
