@@ -728,12 +728,16 @@ scat_status forward_2d(scat_plan *p, const float *in, float *out, long p0, long 
     const int r1 = h.res(j1);
     const int M1r = Nr >> r1, M1c = Nc >> r1;
     const bool kids = h.max_order == 2 && j1 < J - 1;
-    SCAT_TRY(scat::launch_mulfold_invrow(XH, tab + p->psi1_off[j1], T, pc, L, Nr, Nc, r1, r1, 0,
+    // Taped pass: every node is taped as its row pass leaves it, before the inverse column
+    // transform (the backward kernels transform the columns themselves): the row pass writes
+    // into the tape, a leaf needs no column kernel, a node with children only its spectra.
+    float2 *t1 = tape ? tape->base + tape->y1_off[j1] * pc : T;
+    SCAT_TRY(scat::launch_mulfold_invrow(XH, tab + p->psi1_off[j1], t1, pc, L, Nr, Nc, r1, r1, 0,
                                          tw, tw_n, st));
-    SCAT_TRY(scat::launch_col(1, T, pc * L, M1r, M1c, kids ? U : nullptr, 0,
+    if (tape != nullptr && !kids) continue;
+    SCAT_TRY(scat::launch_col(1, t1, pc * L, M1r, M1c, kids ? U : nullptr, 0,
                               tab + p->phi_rows_off[r1], m_r, lp ? W : nullptr, nullptr, none, K,
-                              tw, tw_n, st, false,
-                              tape ? tape->base + tape->y1_off[j1] * pc : nullptr));
+                              tw, tw_n, st));
     if (lp)
       SCAT_TRY(scat::launch_row_lowpass(W, pc * L, m_r, M1c, m_c, tab + p->phi_cols_off[r1], o,
                                         ChanMap{L, L, 0, 1 + j1 * L}, K, tw, tw_n, st));
@@ -743,11 +747,12 @@ scat_status forward_2d(scat_plan *p, const float *in, float *out, long p0, long 
     for (int j2 = j1 + 1; j2 < J; ++j2) {
       const int r2 = h.res(j2);
       const int M2r = Nr >> r2, M2c = Nc >> r2;
-      SCAT_TRY(scat::launch_mulfold_invrow(U, tab + p->psi2_off[{r1, j2}], T, pc * L, L, M1r, M1c,
+      float2 *t2 = tape ? tape->base + tape->y2_off.at({j1, j2}) * pc : T;
+      SCAT_TRY(scat::launch_mulfold_invrow(U, tab + p->psi2_off[{r1, j2}], t2, pc * L, L, M1r, M1c,
                                            r2 - r1, r2 - r1, 0, tw, tw_n, st));
-      SCAT_TRY(scat::launch_col(1, T, pc * L * L, M2r, M2c, nullptr, 0, tab + p->phi_rows_off[r2],
-                                m_r, lp ? W : nullptr, nullptr, none, K, tw, tw_n, st, false,
-                                tape ? tape->base + tape->y2_off.at({j1, j2}) * pc : nullptr));
+      if (tape != nullptr) continue;
+      SCAT_TRY(scat::launch_col(1, t2, pc * L * L, M2r, M2c, nullptr, 0, tab + p->phi_rows_off[r2],
+                                m_r, W, nullptr, none, K, tw, tw_n, st));
       if (lp)
         SCAT_TRY(scat::launch_row_lowpass(W, pc * L * L, m_r, M2c, m_c, tab + p->phi_cols_off[r2],
                                           o, ChanMap{L * L, L, octs * L, s2_base + (j2 - j1 - 1) * L},
@@ -761,12 +766,12 @@ scat_status forward_2d(scat_plan *p, const float *in, float *out, long p0, long 
 
 // ---- 2-D schedule with the fused row pass (no full 2-D spectrum is ever stored).  With a
 // tape the signals before each modulus are kept and the outputs S are not formed.
-// Taped forward pass of a fused 2-D plan: a leaf node (no children below it) is taped as the
-// row pass leaves it, before its inverse column transform -- the backward kernels (whole-node
-// or column) transform the columns themselves, and the forward pass skips the leaf's column
-// kernel.  First-order nodes with children are not taped at all: their row-pass output stays
-// in the forward pass's buffer T, and the backward pass reads it there the same way.
-bool tape_holds_rows(const scat_plan &p) { return p.fused; }
+// Taped forward pass, 2-D: a node is taped as the row pass leaves it, before its inverse
+// column transform -- the backward kernels (whole-node or column) transform the columns
+// themselves, and the forward pass runs no column kernel for leaves (nodes without children).
+// Fused plans do not tape first-order nodes with children at all: their row-pass output
+// stays in the forward pass's buffer T, and the backward pass reads it there the same way.
+bool first_order_in_forward_buffer(const scat_plan &p) { return p.fused; }
 
 scat_status forward_2d_fused(scat_plan *p, const float *in, float *out, long p0, long pc,
                              const Layout &lay, hipStream_t st, const Tape *tape = nullptr) {
@@ -816,7 +821,7 @@ scat_status forward_2d_fused(scat_plan *p, const float *in, float *out, long p0,
     for (int j1 = 0; j1 < J; ++j1) {
       const bool kids = h.max_order == 2 && j1 < J - 1;
       t1[j1] = T + off;
-      if (tape != nullptr && !kids && tape_holds_rows(*p))
+      if (tape != nullptr && !kids)
         t1[j1] = tape->base + tape->y1_off[j1] * pc;  // straight to the tape, no column pass
       lv[j1] = scat::FusedLevel{h.res(j1), L, tab + p->psi1_off[j1], t1[j1]};
       off += static_cast<size_t>(pc) * L * (n >> (2 * h.res(j1)));
@@ -828,11 +833,10 @@ scat_status forward_2d_fused(scat_plan *p, const float *in, float *out, long p0,
     const int r1 = h.res(j1);
     const int M1r = Nr >> r1, M1c = Nc >> r1;
     const bool kids = h.max_order == 2 && j1 < J - 1;
-    if (tape != nullptr && !kids && tape_holds_rows(*p)) continue;
+    if (tape != nullptr && !kids) continue;
     SCAT_TRY(col_and_lowpass(1, t1[j1], pc * L, M1r, M1c, r1, kids ? U : nullptr,
                              ChanMap{L, L, 0, 1 + j1 * L},
-                             tape && !tape_holds_rows(*p) ? tape->base + tape->y1_off[j1] * pc
-                                                          : nullptr));
+                             nullptr));
     if (!kids) continue;
     const int octs = J - 1 - j1;
     std::vector<float2 *> t2(J);
@@ -841,7 +845,7 @@ scat_status forward_2d_fused(scat_plan *p, const float *in, float *out, long p0,
       size_t off = 0;
       for (int j2 = j1 + 1; j2 < J; ++j2) {
         t2[j2] = V + off;
-        if (tape != nullptr && tape_holds_rows(*p))
+        if (tape != nullptr)
           t2[j2] = tape->base + tape->y2_off.at({j1, j2}) * pc;
         lv[j2 - j1 - 1] = scat::FusedLevel{h.res(j2) - r1, L, tab + p->psi2_off[{r1, j2}], t2[j2]};
         off += static_cast<size_t>(pc) * L * L * (n >> (2 * h.res(j2)));
@@ -851,7 +855,7 @@ scat_status forward_2d_fused(scat_plan *p, const float *in, float *out, long p0,
     for (int j2 = j1 + 1; j2 < J; ++j2) {
       const int r2 = h.res(j2);
       const int M2r = Nr >> r2, M2c = Nc >> r2;
-      if (tape != nullptr && tape_holds_rows(*p)) continue;
+      if (tape != nullptr) continue;
       SCAT_TRY(col_and_lowpass(1, t2[j2], pc * L * L, M2r, M2c, r2, nullptr,
                                ChanMap{L * L, L, octs * L, s2_base + (j2 - j1 - 1) * L},
                                tape ? tape->base + tape->y2_off.at({j1, j2}) * pc : nullptr));
@@ -1032,19 +1036,19 @@ scat_status backward_2d_rows_adjoint(scat_plan *p, const float *go, float *gi, l
     // the signal before the modulus: taped (leaves of fused plans: as row-pass output), or
     // for nodes with children of fused plans the row-pass output still in the forward buffer
     const float2 *y1 = bl.tape.base + bl.tape.y1_off[j1] * pc;
-    if (kids && tape_holds_rows(*p)) y1 = Tfwd + t_off;
+    if (kids && first_order_in_forward_buffer(*p)) y1 = Tfwd + t_off;
     t_off += static_cast<size_t>(pc) * L * M1r * M1c;
     const ChanMap cm1{L, L, 0, 1 + j1 * L};
     if (!kids && node1) {
       SCAT_TRY(scat::launch_node_modback_low(go, pc * L, cm1, K, m_r, m_c, M1r, M1c,
                                              tab + p->phi_rows_off[r1], tab + p->phi_cols_off[r1], GH,
-                                             y1, GUj, tw, tw_n, st, tape_holds_rows(*p)));
+                                             y1, GUj, tw, tw_n, st, true));
     } else if (!kids) {
       SCAT_TRY(scat::launch_lowpass_adj_rows(go, pc * L, cm1, K, m_r, m_c, M1r, M1c,
                                              tab + p->phi_rows_off[r1], tab + p->phi_cols_off[r1], GH,
                                              GUj, tw, tw_n, st));
       SCAT_TRY(scat::launch_cols_modback(GUj, y1, pc * L, M1r, M1c, tw, tw_n, st, 0,
-                                         tape_holds_rows(*p)));
+                                         true));
       if (!pre_rows)
         SCAT_TRY(scat::launch_fft_rows_inplace(GUj, pc * L * M1r, M1c, false, tw, tw_n, st));
     } else {
@@ -1065,13 +1069,13 @@ scat_status backward_2d_rows_adjoint(scat_plan *p, const float *go, float *gi, l
           SCAT_TRY(scat::launch_node_modback_low(go, nodes, cm2, K, m_r, m_c, M2r, M2c,
                                                  tab + p->phi_rows_off[r2], tab + p->phi_cols_off[r2],
                                                  GH, y2, GAj, tw, tw_n, st,
-                                                 tape_holds_rows(*p)));
+                                                 true));
         } else {
           SCAT_TRY(scat::launch_lowpass_adj_rows(go, nodes, cm2, K, m_r, m_c, M2r, M2c,
                                                  tab + p->phi_rows_off[r2], tab + p->phi_cols_off[r2],
                                                  GH, GAj, tw, tw_n, st));
           SCAT_TRY(scat::launch_cols_modback(GAj, y2, nodes, M2r, M2c, tw, tw_n, st, 0,
-                                             tape_holds_rows(*p)));
+                                             true));
           SCAT_TRY(scat::launch_fft_rows_inplace(GAj, nodes * M2r, M2c, false, tw, tw_n, st));
         }
         for (int l2 = 0; l2 < L; ++l2) {
@@ -1086,12 +1090,12 @@ scat_status backward_2d_rows_adjoint(scat_plan *p, const float *go, float *gi, l
       SCAT_TRY(flush(GUj, pc * L, M1r, M1c, a));
       if (node1) {
         SCAT_TRY(scat::launch_node_modback(GUj, y1, pc * L, M1r, M1c, tw, tw_n, st,
-                                           tape_holds_rows(*p)));
+                                           true));
       } else {
         if (!fused_inv)
           SCAT_TRY(scat::launch_fft_rows_inplace(GUj, pc * L * M1r, M1c, true, tw, tw_n, st));
         SCAT_TRY(scat::launch_cols_modback(GUj, y1, pc * L, M1r, M1c, tw, tw_n, st, 0,
-                                           tape_holds_rows(*p)));
+                                           true));
         if (!pre_rows)
           SCAT_TRY(scat::launch_fft_rows_inplace(GUj, pc * L * M1r, M1c, false, tw, tw_n, st));
       }
