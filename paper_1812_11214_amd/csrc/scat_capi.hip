@@ -661,7 +661,8 @@ unsigned stream_blocks(long total) {
 
 // Where the backward pass keeps the complex signals before every modulus: per-plane element
 // offsets into one array (chunk-major like all scratch: array of octave j1 starts at
-// y1_off[j1] * planes_in_chunk).
+// y1_off[j1] * planes_in_chunk).  Each signal is kept as the row pass leaves it, i.e. BEFORE
+// its inverse column transform, which the backward kernels do themselves.
 struct Tape {
   float2 *base = nullptr;
   std::vector<size_t> y1_off;                     // per j1: [planes*L][M1r][M1c]
@@ -694,7 +695,8 @@ Tape make_tape(const scat_plan &p) {
 }
 
 // ---- 2-D schedule for one chunk of `pc` planes starting at plane p0.  With a tape the
-// signals before each modulus are kept and the outputs S are not formed (`out` unused).
+// signals before each modulus are kept (see Tape) and the outputs S are not formed (`out`
+// unused).
 scat_status forward_2d(scat_plan *p, const float *in, float *out, long p0, long pc,
                        const Layout &lay, hipStream_t st, const Tape *tape = nullptr) {
   const scat::HostPlan &h = p->host;
@@ -798,11 +800,11 @@ scat_status forward_2d_fused(scat_plan *p, const float *in, float *out, long p0,
   // else the column pass followed by the row half of the lowpass.  Column spectra of the
   // real signals go to `uc` (may be null) as their non-redundant half (rows 0..Mr/2).
   auto col_and_lowpass = [&](int mode, const void *src, long nodes, int Mr, int Mc, int res,
-                             float2 *uc, ChanMap cm, float2 *y_out = nullptr) -> hipError_t {
+                             float2 *uc, ChanMap cm) -> hipError_t {
     const float *pr = tab + p->phi_rows_off[res], *pcs = tab + p->phi_cols_off[res];
-    if (tape != nullptr)  // column pass only, keeping the signal before the modulus
+    if (tape != nullptr)  // taped pass: the column pass only, for the children's spectra
       return scat::launch_col(mode, src, nodes, Mr, Mc, uc, 0, pr, m_r, nullptr, nullptr, none, K,
-                              tw, tw_n, st, true, y_out);
+                              tw, tw_n, st, true);
     if (scat::col_node_supported(Mr, Mc, m_r, m_c, tw_n))
       return scat::launch_col_node(mode, src, nodes, Mr, m_r, uc, true, pr, pcs, o, cm, K, tw, tw_n,
                                    st);
@@ -835,8 +837,7 @@ scat_status forward_2d_fused(scat_plan *p, const float *in, float *out, long p0,
     const bool kids = h.max_order == 2 && j1 < J - 1;
     if (tape != nullptr && !kids) continue;
     SCAT_TRY(col_and_lowpass(1, t1[j1], pc * L, M1r, M1c, r1, kids ? U : nullptr,
-                             ChanMap{L, L, 0, 1 + j1 * L},
-                             nullptr));
+                             ChanMap{L, L, 0, 1 + j1 * L}));
     if (!kids) continue;
     const int octs = J - 1 - j1;
     std::vector<float2 *> t2(J);
@@ -857,8 +858,7 @@ scat_status forward_2d_fused(scat_plan *p, const float *in, float *out, long p0,
       const int M2r = Nr >> r2, M2c = Nc >> r2;
       if (tape != nullptr) continue;
       SCAT_TRY(col_and_lowpass(1, t2[j2], pc * L * L, M2r, M2c, r2, nullptr,
-                               ChanMap{L * L, L, octs * L, s2_base + (j2 - j1 - 1) * L},
-                               tape ? tape->base + tape->y2_off.at({j1, j2}) * pc : nullptr));
+                               ChanMap{L * L, L, octs * L, s2_base + (j2 - j1 - 1) * L}));
     }
     s2_base += L * L * octs;
   }
@@ -1033,8 +1033,8 @@ scat_status backward_2d_rows_adjoint(scat_plan *p, const float *go, float *gi, l
     // a full-resolution level that goes through the column kernel leaves its forward row
     // transform to x's row-adjoint launch, which does it in registers on the way in
     const bool pre_rows = !node1 && r1 == 0 && top_inv;
-    // the signal before the modulus: taped (leaves of fused plans: as row-pass output), or
-    // for nodes with children of fused plans the row-pass output still in the forward buffer
+    // the signal before the modulus as its row pass left it: in the tape, or for nodes with
+    // children of fused plans still in the forward pass's buffer
     const float2 *y1 = bl.tape.base + bl.tape.y1_off[j1] * pc;
     if (kids && first_order_in_forward_buffer(*p)) y1 = Tfwd + t_off;
     t_off += static_cast<size_t>(pc) * L * M1r * M1c;

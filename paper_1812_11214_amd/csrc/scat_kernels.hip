@@ -407,8 +407,7 @@ __global__ void k_col(const void *__restrict__ src_v, int Mr, int Mc, int TC,
                       float2 *__restrict__ uc, int uc_half, int post_tw_m,
                       const float *__restrict__ phi_rows,
                       int m_r, float *__restrict__ w_out, float *__restrict__ out, ChanMap cm,
-                      int K, const float2 *__restrict__ tw, int tw_n,
-                      float2 *__restrict__ y_out) {
+                      int K, const float2 *__restrict__ tw, int tw_n) {
   extern __shared__ float2 lds[];
   const int log2mr = ilog2(Mr);
   const int tiles = Mc / TC;
@@ -438,14 +437,6 @@ __global__ void k_col(const void *__restrict__ src_v, int Mr, int Mc, int TC,
       op[static_cast<size_t>(i) * Mc + c0 + c] = lds[t].x;
     }
     return;
-  }
-  if (MODE == 1 && y_out != nullptr) {
-    // the complex signal before the modulus (needed by the backward pass)
-    for (int t = threadIdx.x; t < total; t += blockDim.x) {
-      int i = t / TC, c = t % TC;
-      y_out[plane + static_cast<size_t>(i) * Mc + c0 + c] = lds[t];
-    }
-    __syncthreads();
   }
   if (MODE == 1) {
     // modulus, and put the result in bit-reversed order for the forward transform:
@@ -789,8 +780,7 @@ __global__ __launch_bounds__(256) void k_col_fast(const void *__restrict__ src_v
                                                   int post_tw_m,
                                                   const float *__restrict__ phi_rows, int m_r,
                                                   float *__restrict__ w_out,
-                                                  const float2 *__restrict__ tw, int tw_n,
-                                                  float2 *__restrict__ y_out) {
+                                                  const float2 *__restrict__ tw, int tw_n) {
   constexpr int E = MR > 256 ? 32 : 16, T = MR / E;
   extern __shared__ float2 lds[];
   const int KS = T * TC + 16;
@@ -813,12 +803,6 @@ __global__ __launch_bounds__(256) void k_col_fast(const void *__restrict__ src_v
 #pragma unroll
     for (int i = 0; i < E; ++i) v[i] = nt_load(sp + i * step);
     fft_core<E, T, true>(v, t, lds + c, KS, TC, wt);
-    if (y_out != nullptr) {
-      // the complex signal before the modulus (needed by the backward pass)
-      float2 *yp = y_out + plane + off0;
-#pragma unroll
-      for (int i = 0; i < E; ++i) yp[i * step] = v[i];
-    }
 #pragma unroll
     for (int i = 0; i < E; ++i)
       v[i] = make_float2(__builtin_amdgcn_sqrtf(v[i].x * v[i].x + v[i].y * v[i].y), 0.f);
@@ -931,7 +915,7 @@ __global__ __launch_bounds__(256) void k_col_fast(const void *__restrict__ src_v
 template <int MR>
 hipError_t launch_col_fast_t(int mode, const void *src, long nodes, int Mc, float2 *uc, bool uc_half,
                              int post_tw_m, const float *phi_rows, int m_r, float *w_out,
-                             const float2 *tw, int tw_n, hipStream_t st, float2 *y_out) {
+                             const float2 *tw, int tw_n, hipStream_t st) {
   constexpr int E = MR > 256 ? 32 : 16, T = MR / E;
   if (post_tw_m > 0 && (uc_half || tw_n % post_tw_m != 0 || (post_tw_m & (post_tw_m - 1)) != 0))
     return hipErrorInvalidValue;
@@ -967,8 +951,7 @@ hipError_t launch_col_fast_t(int mode, const void *src, long nodes, int Mc, floa
       if (e != hipSuccess) return e;                                        \
     }                                                                      \
     hipLaunchKernelGGL((k_col_fast<MR, MODE_, LM_>), g, b, lds, st, src, Mc, TC, uc,              \
-                       static_cast<int>(uc_half), post_tw_m, phi_rows, m_r, w_out, tw, tw_n,      \
-                       y_out);                                                                    \
+                       static_cast<int>(uc_half), post_tw_m, phi_rows, m_r, w_out, tw, tw_n);     \
   }
   if (mode == 0) {
     if (lm == 32) SCAT_COL_LAUNCH(0, 32)
@@ -1816,9 +1799,7 @@ hipError_t launch_mulfold_invrow(const float2 *src, const float *filt, float2 *d
 
 hipError_t launch_col(int mode, const void *src, long nodes, int Mr, int Mc, float2 *uc,
                       int post_tw_m, const float *phi_rows, int m_r, float *w_out, float *out,
-                      ChanMap cm, int K, const float2 *tw, int tw_n, hipStream_t st, bool uc_half,
-                      float2 *y_out) {
-  if (y_out != nullptr && mode != 1) return hipErrorInvalidValue;
+                      ChanMap cm, int K, const float2 *tw, int tw_n, hipStream_t st, bool uc_half) {
   if (uc_half && (mode == 2 || post_tw_m != 0 || Mr < 2)) return hipErrorInvalidValue;
   // register-resident variant: modes 0/1, column length 16*T with T | 16, at least 16
   // columns (4 without a lowpass tail), lowpass length dividing the column length
@@ -1826,11 +1807,11 @@ hipError_t launch_col(int mode, const void *src, long nodes, int Mr, int Mc, flo
       (post_tw_m == 0 || !uc_half) &&
       (w_out == nullptr || (m_r >= 1 && m_r <= Mr))) {
     switch (Mr) {
-      case 32: return launch_col_fast_t<32>(mode, src, nodes, Mc, uc, uc_half, post_tw_m, phi_rows, m_r, w_out, tw, tw_n, st, y_out);
-      case 64: return launch_col_fast_t<64>(mode, src, nodes, Mc, uc, uc_half, post_tw_m, phi_rows, m_r, w_out, tw, tw_n, st, y_out);
-      case 128: return launch_col_fast_t<128>(mode, src, nodes, Mc, uc, uc_half, post_tw_m, phi_rows, m_r, w_out, tw, tw_n, st, y_out);
-      case 256: return launch_col_fast_t<256>(mode, src, nodes, Mc, uc, uc_half, post_tw_m, phi_rows, m_r, w_out, tw, tw_n, st, y_out);
-      case 512: return launch_col_fast_t<512>(mode, src, nodes, Mc, uc, uc_half, post_tw_m, phi_rows, m_r, w_out, tw, tw_n, st, y_out);
+      case 32: return launch_col_fast_t<32>(mode, src, nodes, Mc, uc, uc_half, post_tw_m, phi_rows, m_r, w_out, tw, tw_n, st);
+      case 64: return launch_col_fast_t<64>(mode, src, nodes, Mc, uc, uc_half, post_tw_m, phi_rows, m_r, w_out, tw, tw_n, st);
+      case 128: return launch_col_fast_t<128>(mode, src, nodes, Mc, uc, uc_half, post_tw_m, phi_rows, m_r, w_out, tw, tw_n, st);
+      case 256: return launch_col_fast_t<256>(mode, src, nodes, Mc, uc, uc_half, post_tw_m, phi_rows, m_r, w_out, tw, tw_n, st);
+      case 512: return launch_col_fast_t<512>(mode, src, nodes, Mc, uc, uc_half, post_tw_m, phi_rows, m_r, w_out, tw, tw_n, st);
       default: break;
     }
   }
@@ -1855,15 +1836,15 @@ hipError_t launch_col(int mode, const void *src, long nodes, int Mr, int Mc, flo
   switch (mode) {
     case 0:
       hipLaunchKernelGGL(k_col<0>, g, b, lds, st, src, Mr, Mc, TC, uc, static_cast<int>(uc_half), post_tw_m, phi_rows, m_r,
-                         w_out, out, cm, K, tw, tw_n, y_out);
+                         w_out, out, cm, K, tw, tw_n);
       break;
     case 1:
       hipLaunchKernelGGL(k_col<1>, g, b, lds, st, src, Mr, Mc, TC, uc, static_cast<int>(uc_half), post_tw_m, phi_rows, m_r,
-                         w_out, out, cm, K, tw, tw_n, y_out);
+                         w_out, out, cm, K, tw, tw_n);
       break;
     case 2:
       hipLaunchKernelGGL(k_col<2>, g, b, lds, st, src, Mr, Mc, TC, uc, static_cast<int>(uc_half), post_tw_m, phi_rows, m_r,
-                         w_out, out, cm, K, tw, tw_n, y_out);
+                         w_out, out, cm, K, tw, tw_n);
       break;
     default:
       return hipErrorInvalidValue;

@@ -55,7 +55,7 @@ hipError_t launch_mulfold_invrow(const float2 *src, const float *filt, float2 *d
 hipError_t launch_col(int mode, const void *src, long nodes, int Mr, int Mc, float2 *uc,
                       int post_tw_m, const float *phi_rows, int m_r, float *w_out, float *out,
                       ChanMap cm, int K, const float2 *tw, int tw_n, hipStream_t st,
-                      bool uc_half = false, float2 *y_out = nullptr);
+                      bool uc_half = false);
 
 // 1-D cascade: forward row FFT of src [nodes][Sr][Sc] (column spectra, left untouched) and,
 // for each child, filter product + fold of the row by 2^lg_fold + inverse row FFT + four-step
