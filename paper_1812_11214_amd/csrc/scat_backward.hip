@@ -28,42 +28,54 @@ __device__ __forceinline__ int chan(const ChanMap &cm, int g) {
 }
 
 // First half of the adjoint lowpass: Ghat [node][m_r][m_c] = FFT2 of the node's gradient
-// plane (two dense stages in LDS; the planes are tiny).
+// plane (two dense stages in LDS; the planes are tiny).  A workgroup takes NPW = 256 / (m_r m_c)
+// nodes when a plane has fewer than 256 points, one thread per point (else one node, several
+// points per thread).
 __global__ __launch_bounds__(256) void k_small_fft2(const float *__restrict__ gout, ChanMap cm,
-                                                    int K, int m_r, int m_c,
+                                                    int K, int m_r, int m_c, int NPW, long nodes,
                                                     float2 *__restrict__ ghat,
                                                     const float2 *__restrict__ tw, int tw_n) {
   extern __shared__ float2 lds[];
   const int mm = m_r * m_c;
-  float2 *s1 = lds;
-  float2 *twc = lds + mm, *twr = twc + m_c;
-  float *a = reinterpret_cast<float *>(twr + m_r);
-  const long node = blockIdx.x;
+  float2 *s1 = lds;                      // NPW planes
+  float2 *twc = lds + NPW * mm, *twr = twc + m_c;
+  float *a = reinterpret_cast<float *>(twr + m_r);  // NPW planes
+  const int per = NPW > 1 ? mm : static_cast<int>(blockDim.x);  // threads of one node
+  const int nl = threadIdx.x / per, t0 = threadIdx.x - nl * per;
+  const long node_raw = static_cast<long>(blockIdx.x) * NPW + nl;
+  const bool live = nl < NPW && node_raw < nodes;
+  const long node = live ? node_raw : nodes - 1;  // idle threads shadow the last node, store nothing
   const long p = node / cm.G;
   const int g = static_cast<int>(node - p * cm.G);
   const float *gp = gout + (static_cast<size_t>(p) * K + chan(cm, g)) * mm;
-  for (int i = threadIdx.x; i < mm; i += blockDim.x) a[i] = gp[i];
+  const int slot = nl < NPW ? nl : 0;
+  float *an = a + slot * mm;
+  float2 *sn = s1 + slot * mm;
+  if (nl < NPW)
+    for (int i = t0; i < mm; i += per) an[i] = gp[i];
   const int sc = tw_n / m_c, sr = tw_n / m_r;
   for (int i = threadIdx.x; i < m_c; i += blockDim.x) twc[i] = tw[i * sc];
   for (int i = threadIdx.x; i < m_r; i += blockDim.x) twr[i] = tw[i * sr];
   __syncthreads();
-  for (int i = threadIdx.x; i < mm; i += blockDim.x) {
-    const int r = i / m_c, kc = i - r * m_c;
-    float2 acc = make_float2(0.f, 0.f);
-    for (int b = 0; b < m_c; ++b) {
-      const float2 w = twc[(b * kc) & (m_c - 1)];
-      const float x = a[r * m_c + b];
-      acc.x += x * w.x;
-      acc.y += x * w.y;
+  if (nl < NPW)
+    for (int i = t0; i < mm; i += per) {
+      const int r = i / m_c, kc = i - r * m_c;
+      float2 acc = make_float2(0.f, 0.f);
+      for (int b = 0; b < m_c; ++b) {
+        const float2 w = twc[(b * kc) & (m_c - 1)];
+        const float x = an[r * m_c + b];
+        acc.x += x * w.x;
+        acc.y += x * w.y;
+      }
+      sn[i] = acc;
     }
-    s1[i] = acc;
-  }
   __syncthreads();
+  if (!live) return;
   float2 *op = ghat + static_cast<size_t>(node) * mm;
-  for (int i = threadIdx.x; i < mm; i += blockDim.x) {
+  for (int i = t0; i < mm; i += per) {
     const int kr = i / m_c, kc = i - kr * m_c;
     float2 acc = make_float2(0.f, 0.f);
-    for (int r = 0; r < m_r; ++r) acc = c_add(acc, c_mul(s1[r * m_c + kc], twr[(r * kr) & (m_r - 1)]));
+    for (int r = 0; r < m_r; ++r) acc = c_add(acc, c_mul(sn[r * m_c + kc], twr[(r * kr) & (m_r - 1)]));
     op[i] = acc;
   }
 }
@@ -952,11 +964,14 @@ hipError_t launch_small_fft2(const float *gout, long nodes, ChanMap cm, int K, i
     SCAT_NODE_DISPATCH(SCAT_SF)
 #undef SCAT_SF
   }
-  const size_t lds = static_cast<size_t>(m_r) * m_c * (sizeof(float2) + sizeof(float)) +
+  const int mm = m_r * m_c;
+  const int npw = mm < 256 ? 256 / mm : 1;  // nodes per workgroup
+  const long blocks = (nodes + npw - 1) / npw;
+  const size_t lds = static_cast<size_t>(npw) * mm * (sizeof(float2) + sizeof(float)) +
                      static_cast<size_t>(m_r + m_c) * sizeof(float2);
   LaunchScope obs("k_small_fft2", nodes * 12.0 * m_r * m_c, nodes * 8.0 * m_r * m_c * (m_r + m_c), st);
-  hipLaunchKernelGGL(k_small_fft2, dim3(static_cast<unsigned>(nodes)), dim3(256), lds, st, gout, cm, K,
-                     m_r, m_c, ghat, tw, tw_n);
+  hipLaunchKernelGGL(k_small_fft2, dim3(static_cast<unsigned>(blocks)), dim3(256), lds, st, gout, cm, K,
+                     m_r, m_c, npw, nodes, ghat, tw, tw_n);
   return hipGetLastError();
 }
 
