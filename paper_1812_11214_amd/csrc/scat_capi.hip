@@ -808,6 +808,9 @@ scat_status forward_2d_fused(scat_plan *p, const float *in, float *out, long p0,
     if (scat::col_node_supported(Mr, Mc, m_r, m_c, tw_n))
       return scat::launch_col_node(mode, src, nodes, Mr, m_r, uc, true, pr, pcs, o, cm, K, tw, tw_n,
                                    st);
+    if (mode == 1 && uc == nullptr && scat::leaf_node_supported(Mr, Mc, m_r, m_c, tw_n))
+      return scat::launch_leaf_node(static_cast<const float2 *>(src), nodes, Mr, m_r, pr, pcs, o, cm, K,
+                                    tw, tw_n, st);
     hipError_t e = scat::launch_col(mode, src, nodes, Mr, Mc, uc, 0, pr, m_r, W, nullptr, none, K,
                                     tw, tw_n, st, true);
     if (e != hipSuccess) return e;

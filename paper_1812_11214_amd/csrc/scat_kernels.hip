@@ -19,6 +19,7 @@
 #include <type_traits>
 
 #include "fft_regs.hpp"
+#include "slab_fft.hpp"
 #include "scat_kernels.hpp"
 
 namespace scat {
@@ -1153,6 +1154,92 @@ __global__ __launch_bounds__(256) void k_col_node(const void *__restrict__ src_v
   }
 }
 
+// ------------------------------------------------------------------------------------
+// Leaf nodes of N x N points (no children below them) in one pass, the node held by one
+// workgroup in LDS (slab_fft.hpp): row-pass output src [node][N][N] -> inverse column
+// transform -> modulus -> forward 2-D transform -> product with the separable lowpass ->
+// sum over the (N / M)^2 aliases -> inverse M x M transform (by the first wavefront) ->
+// out[plane][channel][M][M].  Replaces the column kernel, its W rows in memory and the
+// row-lowpass kernel for nodes below the whole-node column kernel's range.
+template <int N, int M>
+__global__ __launch_bounds__(256) void k_leaf_node(const float2 *__restrict__ src,
+                                                   const float *__restrict__ phi_rows,
+                                                   const float *__restrict__ phi_cols,
+                                                   float *__restrict__ out, ChanMap cm, int K,
+                                                   const float2 *__restrict__ tw, int tw_n) {
+  using S = Slab<N, N>;
+  using Q = Slab<M, M>;
+  static_assert(S::TS == 256 && Q::TS == 64, "one node per workgroup, the small plane per wavefront");
+  extern __shared__ float2 lds[];
+  float2 *area = lds;
+  float2 *wtab = lds + N * S::RS;
+  S::fill_twiddles(wtab, tw, tw_n);
+  const int q = threadIdx.x;
+  const int r = q / S::T2, t = q % S::T2;
+  const int c = q % N, t1 = q / N;
+  const long node = blockIdx.x;
+  const float2 *sp = src + static_cast<size_t>(node) * N * N + c;
+  float2 v[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) v[i] = nt_load(sp + (t1 + S::T1 * i) * N);
+  fft_core_tab<16, S::T1, true, false>(v, t1, area + c, S::T1 * S::RS, S::RS, wtab + N + t1, S::T1);
+#pragma unroll
+  for (int i = 0; i < 16; ++i)
+    v[i] = make_float2(__builtin_amdgcn_sqrtf(v[i].x * v[i].x + v[i].y * v[i].y), 0.f);
+  S::template transform_back_tab<false>(v, area, r, t, c, t1, wtab);
+  {
+    const float fr = phi_rows[r];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const float f = fr * phi_cols[t + S::T2 * i];
+      area[r * S::RS + t + S::T2 * i] = make_float2(v[i].x * f, v[i].y * f);
+    }
+  }
+  __syncthreads();
+  // the alias sums by all threads (M M / 256 folded points each), parked in the area with
+  // the small plane's strides
+  constexpr int PER = M * M / 256;
+  float2 fo[PER];
+#pragma unroll
+  for (int k = 0; k < PER; ++k) {
+    const int o = q + 256 * k, orow = o / M, ocol = o % M;
+    float2 acc = make_float2(0.f, 0.f);
+#pragma unroll
+    for (int a = 0; a < N / M; ++a)
+#pragma unroll
+      for (int b = 0; b < N / M; ++b) {
+        const float2 e = area[(orow + M * a) * S::RS + ocol + M * b];
+        acc.x += e.x;
+        acc.y += e.y;
+      }
+    fo[k] = acc;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < PER; ++k) {
+    const int o = q + 256 * k;
+    area[(o / M) * Q::RS + o % M] = fo[k];
+  }
+  __syncthreads();
+  if (q >= Q::TS) return;  // the rest is one wavefront's work
+  const int rq = q / Q::T2, tq = q % Q::T2;
+  const int cq = q % M, t1q = q / M;
+  float2 w[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) w[i] = area[rq * Q::RS + tq + Q::T2 * i];
+  wave_sync();  // the area becomes the small transform's exchange and transpose space
+  Q::template transform<true, true>(w, area, rq, tq, cq, t1q, tw, tw_n);
+  const long pl = node / cm.G;
+  const int g = static_cast<int>(node - pl * cm.G);
+  float *op = out + (static_cast<size_t>(pl) * K + chan_of(cm, g)) * M * M + cq;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) op[(t1q + Q::T1 * i) * M] = w[i].x;
+}
+
+bool leaf_node_supported_impl(int Mr, int Mc, int m_r, int m_c, int tw_n) {
+  return Mr == 64 && Mc == 64 && m_r == 32 && m_c == 32 && tw_n % 64 == 0;
+}
+
 // True if launch_col_node handles nodes of MR x MR with lowpass length lm on both axes.
 bool col_node_supported_impl(int Mr, int Mc, int m_r, int m_c, int tw_n) {
   if (Mr != Mc || m_r != m_c) return false;
@@ -1903,6 +1990,28 @@ hipError_t launch_row_lowpass(const float *w, long nodes, int m_r, int Mc, int m
 
 bool col_node_supported(int Mr, int Mc, int m_r, int m_c, int tw_n) {
   return col_node_supported_impl(Mr, Mc, m_r, m_c, tw_n);
+}
+
+bool leaf_node_supported(int Mr, int Mc, int m_r, int m_c, int tw_n) {
+  return leaf_node_supported_impl(Mr, Mc, m_r, m_c, tw_n);
+}
+
+hipError_t launch_leaf_node(const float2 *src, long nodes, int Mr, int m, const float *phi_rows,
+                            const float *phi_cols, float *out, ChanMap cm, int K, const float2 *tw,
+                            int tw_n, hipStream_t st) {
+  if (nodes <= 0) return hipSuccess;
+  if (!leaf_node_supported_impl(Mr, Mr, m, m, tw_n) || nodes > 0x7fffffffL || cm.G < 1 ||
+      cm.inner < 1 || nodes % cm.G != 0)
+    return hipErrorInvalidValue;
+  using S = Slab<64, 64>;
+  const size_t lds = S::lds_bytes + S::tab_elems * sizeof(float2);
+  const double pts = static_cast<double>(nodes) * 64 * 64;
+  Observe ob("k_leaf_node<64, 32>", pts * 8 + static_cast<double>(nodes) * 32 * 32 * 4,
+             static_cast<double>(nodes) * (3.0 * 64 * fft_flops(64) + 2.0 * 32 * fft_flops(32)) + 10.0 * pts,
+             st);
+  hipLaunchKernelGGL((k_leaf_node<64, 32>), dim3(static_cast<unsigned>(nodes)), dim3(256), lds, st, src,
+                     phi_rows, phi_cols, out, cm, K, tw, tw_n);
+  return hipGetLastError();
 }
 
 hipError_t launch_col_node(int mode, const void *src, long nodes, int Mr, int m, float2 *uc,

@@ -139,6 +139,13 @@ hipError_t launch_col_node(int mode, const void *src, long nodes, int Mr, int m,
                            bool uc_half, const float *phi_rows, const float *phi_cols, float *out,
                            ChanMap cm, int K, const float2 *tw, int tw_n, hipStream_t st);
 
+// Leaf nodes (no children; 64 x 64 with a 32 x 32 output) from the row pass's output to the
+// output coefficients in one kernel (see k_leaf_node).
+bool leaf_node_supported(int Mr, int Mc, int m_r, int m_c, int tw_n);
+hipError_t launch_leaf_node(const float2 *src, long nodes, int Mr, int m, const float *phi_rows,
+                            const float *phi_cols, float *out, ChanMap cm, int K, const float2 *tw,
+                            int tw_n, hipStream_t st);
+
 // One level of the fused row pass: wavelets `filt` ([F][Sr][Sc] real, pre-scaled) applied
 // with fold 2^f on both axes, outputs to dst [NS*F][Sr>>f][Sc>>f].
 struct FusedLevel {

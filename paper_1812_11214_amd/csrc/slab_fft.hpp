@@ -31,23 +31,25 @@ struct Slab {
   // v: this thread's 16 points of row r (columns t + T2 i) -> after the call its 16 points
   // of column c (rows t1 + T1 i) of the slab transformed along both axes.  The twiddles are
   // fetched right before each transform so that they are not live across the whole kernel.
-  template <bool INV>
+  // (WAVE: the slab's threads are the lanes of one wavefront, TS <= 64, and synchronise among
+  // themselves only)
+  template <bool INV, bool WAVE = false>
   static __device__ __forceinline__ void transform(float2 (&v)[16], float2 *area, int r, int t, int c,
                                                    int t1, const float2 *__restrict__ tw, int tw_n) {
     {
       float2 wr[16];
       load_twiddles<16, T2>(wr, t, tw, tw_n);
-      fft_core<16, T2, INV, false>(v, t, area + r * RS, T2 + 1, 1, wr);
+      fft_core<16, T2, INV, WAVE>(v, t, area + r * RS, T2 + 1, 1, wr);
     }
 #pragma unroll
     for (int i = 0; i < 16; ++i) area[r * RS + t + T2 * i] = v[i];
-    __syncthreads();
+    group_sync<WAVE>();
 #pragma unroll
     for (int i = 0; i < 16; ++i) v[i] = area[(t1 + T1 * i) * RS + c];
-    __syncthreads();
+    group_sync<WAVE>();
     float2 wc[16];
     load_twiddles<16, T1>(wc, t1, tw, tw_n);
-    fft_core<16, T1, INV, false>(v, t1, area + c, T1 * RS, RS, wc);
+    fft_core<16, T1, INV, WAVE>(v, t1, area + c, T1 * RS, RS, wc);
   }
 
   // The way back: v holds 16 points of column c (rows t1 + T1 i); after the call the thread's
