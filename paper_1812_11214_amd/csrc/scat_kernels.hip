@@ -1156,84 +1156,97 @@ __global__ __launch_bounds__(256) void k_col_node(const void *__restrict__ src_v
 
 // ------------------------------------------------------------------------------------
 // Leaf nodes of N x N points (no children below them) in one pass, the node held by one
-// workgroup in LDS (slab_fft.hpp): row-pass output src [node][N][N] -> inverse column
-// transform -> modulus -> forward 2-D transform -> product with the separable lowpass ->
-// sum over the (N / M)^2 aliases -> inverse M x M transform (by the first wavefront) ->
-// out[plane][channel][M][M].  Replaces the column kernel, its W rows in memory and the
-// row-lowpass kernel for nodes below the whole-node column kernel's range.
+// workgroup in LDS: row-pass output src [node][N][N] -> out[plane][channel][M][M], in place
+// of the column kernel, its W rows in memory and the row-lowpass kernel, for nodes below the
+// whole-node column kernel's range.  The two halves of the separable lowpass are taken one
+// after the other, each right after the transform it follows, so that the row stage works
+// on the M lowpassed rows only:
+//   stage A (all 256 threads, thread = column c, rows t1 + 4 i): inverse column transform,
+//     modulus, forward column transform, phi_rows and the alias sum over rows in registers,
+//     inverse M-point column transform -> W [M][N] real, in LDS;
+//   stage B (the first two wavefronts, 8 lanes per pair of rows of W, the pair travelling as
+//     real and imaginary part of one complex row): forward row transform, phi_cols and the
+//     alias sum over columns, regrouped through LDS, inverse M-point row transform -> S.
 template <int N, int M>
 __global__ __launch_bounds__(256) void k_leaf_node(const float2 *__restrict__ src,
-                                                   const float *__restrict__ phi_rows,
-                                                   const float *__restrict__ phi_cols,
-                                                   float *__restrict__ out, ChanMap cm, int K,
-                                                   const float2 *__restrict__ tw, int tw_n) {
-  using S = Slab<N, N>;
-  using Q = Slab<M, M>;
-  static_assert(S::TS == 256 && Q::TS == 64, "one node per workgroup, the small plane per wavefront");
+                                                    const float *__restrict__ phi_rows,
+                                                    const float *__restrict__ phi_cols,
+                                                    float *__restrict__ out, ChanMap cm, int K,
+                                                    const float2 *__restrict__ tw, int tw_n) {
+  static_assert(N == 64 && M == 32, "thread layout below");
+  constexpr int T1 = N / 16;             // 4 threads per column
+  constexpr int RS = slab_row_stride(N);  // 84
+  constexpr int WS = N + 1;               // floats per row of W
   extern __shared__ float2 lds[];
-  float2 *area = lds;
-  float2 *wtab = lds + N * S::RS;
-  S::fill_twiddles(wtab, tw, tw_n);
+  float2 *area = lds;                                   // N * RS: exchange areas
+  float2 *wtab = lds + N * RS;                          // N: twiddles of the N-point columns
+  float *wl = reinterpret_cast<float *>(wtab + N);      // M * WS: W
   const int q = threadIdx.x;
-  const int r = q / S::T2, t = q % S::T2;
-  const int c = q % N, t1 = q / N;
+  for (int idx = q; idx < N; idx += 256) wtab[idx] = tw[(idx / T1) * (idx % T1) * (tw_n / N)];
+  __syncthreads();
   const long node = blockIdx.x;
-  const float2 *sp = src + static_cast<size_t>(node) * N * N + c;
-  float2 v[16];
-#pragma unroll
-  for (int i = 0; i < 16; ++i) v[i] = nt_load(sp + (t1 + S::T1 * i) * N);
-  fft_core_tab<16, S::T1, true, false>(v, t1, area + c, S::T1 * S::RS, S::RS, wtab + N + t1, S::T1);
-#pragma unroll
-  for (int i = 0; i < 16; ++i)
-    v[i] = make_float2(__builtin_amdgcn_sqrtf(v[i].x * v[i].x + v[i].y * v[i].y), 0.f);
-  S::template transform_back_tab<false>(v, area, r, t, c, t1, wtab);
   {
-    const float fr = phi_rows[r];
+    const int c = q % N, t1 = q / N;
+    const float2 *sp = src + static_cast<size_t>(node) * N * N + c;
+    float2 v[16];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const float f = fr * phi_cols[t + S::T2 * i];
-      area[r * S::RS + t + S::T2 * i] = make_float2(v[i].x * f, v[i].y * f);
+    for (int i = 0; i < 16; ++i) v[i] = nt_load(sp + (t1 + T1 * i) * N);
+    fft_core_tab<16, T1, true, false>(v, t1, area + c, T1 * RS, RS, wtab + t1, T1);
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+      v[i] = make_float2(__builtin_amdgcn_sqrtf(v[i].x * v[i].x + v[i].y * v[i].y), 0.f);
+    fft_core_tab<16, T1, false, false>(v, t1, area + c, T1 * RS, RS, wtab + t1, T1);
+    // rows k and k + M fold onto row k: registers i and i + 8
+    float2 f[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float p0 = phi_rows[t1 + T1 * i], p1 = phi_rows[t1 + T1 * (i + 8)];
+      f[i] = make_float2(v[i].x * p0 + v[i + 8].x * p1, v[i].y * p0 + v[i + 8].y * p1);
     }
+    float2 w8[8];
+    load_twiddles<8, T1>(w8, t1, tw, tw_n);
+    fft_core<8, T1, true, false>(f, t1, area + c, T1 * RS, RS, w8);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) wl[(t1 + T1 * i) * WS + c] = f[i].x;
   }
   __syncthreads();
-  // the alias sums by all threads (M M / 256 folded points each), parked in the area with
-  // the small plane's strides
-  constexpr int PER = M * M / 256;
-  float2 fo[PER];
+  if (q >= 128) return;  // stage B: M / 2 row pairs, 8 lanes each, wave-level synchronisation only
+  const int p = q / 8, t = q % 8;
+  float2 z[8];
 #pragma unroll
-  for (int k = 0; k < PER; ++k) {
-    const int o = q + 256 * k, orow = o / M, ocol = o % M;
-    float2 acc = make_float2(0.f, 0.f);
-#pragma unroll
-    for (int a = 0; a < N / M; ++a)
-#pragma unroll
-      for (int b = 0; b < N / M; ++b) {
-        const float2 e = area[(orow + M * a) * S::RS + ocol + M * b];
-        acc.x += e.x;
-        acc.y += e.y;
-      }
-    fo[k] = acc;
+  for (int i = 0; i < 8; ++i)
+    z[i] = make_float2(wl[(2 * p) * WS + t + 8 * i], wl[(2 * p + 1) * WS + t + 8 * i]);
+  float2 *xb = area + p * 80;  // 8 * (8 + 1) exchange elements, then the regrouping space
+  {
+    float2 w8[8];
+    load_twiddles<8, 8>(w8, t, tw, tw_n);
+    fft_core<8, 8, false, true>(z, t, xb, 9, 1, w8);
   }
-  __syncthreads();
+  // columns k and k + M fold onto column k: registers i and i + 4
 #pragma unroll
-  for (int k = 0; k < PER; ++k) {
-    const int o = q + 256 * k;
-    area[(o / M) * Q::RS + o % M] = fo[k];
+  for (int i = 0; i < 4; ++i) {
+    const float p0 = phi_cols[t + 8 * i], p1 = phi_cols[t + 8 * (i + 4)];
+    xb[t + 8 * i] = make_float2(z[i].x * p0 + z[i + 4].x * p1, z[i].y * p0 + z[i + 4].y * p1);
   }
-  __syncthreads();
-  if (q >= Q::TS) return;  // the rest is one wavefront's work
-  const int rq = q / Q::T2, tq = q % Q::T2;
-  const int cq = q % M, t1q = q / M;
-  float2 w[16];
+  wave_sync();
+  if (t >= 4) return;  // 4 lanes per pair share the M-point inverse transform
+  float2 g[8];
 #pragma unroll
-  for (int i = 0; i < 16; ++i) w[i] = area[rq * Q::RS + tq + Q::T2 * i];
-  wave_sync();  // the area becomes the small transform's exchange and transpose space
-  Q::template transform<true, true>(w, area, rq, tq, cq, t1q, tw, tw_n);
+  for (int i = 0; i < 8; ++i) g[i] = xb[t + 4 * i];
+  wave_sync();
+  {
+    float2 w8[8];
+    load_twiddles<8, 4>(w8, t, tw, tw_n);
+    fft_core<8, 4, true, true>(g, t, xb + 32, 5, 1, w8);
+  }
   const long pl = node / cm.G;
-  const int g = static_cast<int>(node - pl * cm.G);
-  float *op = out + (static_cast<size_t>(pl) * K + chan_of(cm, g)) * M * M + cq;
+  const int gch = static_cast<int>(node - pl * cm.G);
+  float *op = out + (static_cast<size_t>(pl) * K + chan_of(cm, gch)) * M * M + (2 * p) * M;
 #pragma unroll
-  for (int i = 0; i < 16; ++i) op[(t1q + Q::T1 * i) * M] = w[i].x;
+  for (int i = 0; i < 8; ++i) {
+    op[t + 4 * i] = g[i].x;
+    op[M + t + 4 * i] = g[i].y;
+  }
 }
 
 bool leaf_node_supported_impl(int Mr, int Mc, int m_r, int m_c, int tw_n) {
@@ -2003,11 +2016,12 @@ hipError_t launch_leaf_node(const float2 *src, long nodes, int Mr, int m, const 
   if (!leaf_node_supported_impl(Mr, Mr, m, m, tw_n) || nodes > 0x7fffffffL || cm.G < 1 ||
       cm.inner < 1 || nodes % cm.G != 0)
     return hipErrorInvalidValue;
-  using S = Slab<64, 64>;
-  const size_t lds = S::lds_bytes + S::tab_elems * sizeof(float2);
+  const size_t lds = (static_cast<size_t>(64) * slab_row_stride(64) + 64) * sizeof(float2) +
+                     static_cast<size_t>(32) * 65 * sizeof(float);
   const double pts = static_cast<double>(nodes) * 64 * 64;
   Observe ob("k_leaf_node<64, 32>", pts * 8 + static_cast<double>(nodes) * 32 * 32 * 4,
-             static_cast<double>(nodes) * (3.0 * 64 * fft_flops(64) + 2.0 * 32 * fft_flops(32)) + 10.0 * pts,
+             static_cast<double>(nodes) * (2.0 * 64 * fft_flops(64) + 64 * fft_flops(32) +
+                                           16 * (fft_flops(64) + fft_flops(32))) + 8.0 * pts,
              st);
   hipLaunchKernelGGL((k_leaf_node<64, 32>), dim3(static_cast<unsigned>(nodes)), dim3(256), lds, st, src,
                      phi_rows, phi_cols, out, cm, K, tw, tw_n);
