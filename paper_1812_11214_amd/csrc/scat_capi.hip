@@ -737,6 +737,12 @@ scat_status forward_2d(scat_plan *p, const float *in, float *out, long p0, long 
     SCAT_TRY(scat::launch_mulfold_invrow(XH, tab + p->psi1_off[j1], t1, pc, L, Nr, Nc, r1, r1, 0,
                                          tw, tw_n, st));
     if (tape != nullptr && !kids) continue;
+    if (lp && !kids && scat::leaf_node_supported(M1r, M1c, m_r, m_c, tw_n)) {
+      SCAT_TRY(scat::launch_leaf_node(t1, pc * L, M1r, m_r, tab + p->phi_rows_off[r1],
+                                      tab + p->phi_cols_off[r1], o, ChanMap{L, L, 0, 1 + j1 * L}, K, tw,
+                                      tw_n, st));
+      continue;
+    }
     SCAT_TRY(scat::launch_col(1, t1, pc * L, M1r, M1c, kids ? U : nullptr, 0,
                               tab + p->phi_rows_off[r1], m_r, lp ? W : nullptr, nullptr, none, K,
                               tw, tw_n, st));
@@ -753,12 +759,16 @@ scat_status forward_2d(scat_plan *p, const float *in, float *out, long p0, long 
       SCAT_TRY(scat::launch_mulfold_invrow(U, tab + p->psi2_off[{r1, j2}], t2, pc * L, L, M1r, M1c,
                                            r2 - r1, r2 - r1, 0, tw, tw_n, st));
       if (tape != nullptr) continue;
+      const ChanMap cm2{L * L, L, octs * L, s2_base + (j2 - j1 - 1) * L};
+      if (scat::leaf_node_supported(M2r, M2c, m_r, m_c, tw_n)) {  // the whole leaf in one kernel
+        SCAT_TRY(scat::launch_leaf_node(t2, pc * L * L, M2r, m_r, tab + p->phi_rows_off[r2],
+                                        tab + p->phi_cols_off[r2], o, cm2, K, tw, tw_n, st));
+        continue;
+      }
       SCAT_TRY(scat::launch_col(1, t2, pc * L * L, M2r, M2c, nullptr, 0, tab + p->phi_rows_off[r2],
                                 m_r, W, nullptr, none, K, tw, tw_n, st));
-      if (lp)
-        SCAT_TRY(scat::launch_row_lowpass(W, pc * L * L, m_r, M2c, m_c, tab + p->phi_cols_off[r2],
-                                          o, ChanMap{L * L, L, octs * L, s2_base + (j2 - j1 - 1) * L},
-                                          K, tw, tw_n, st));
+      SCAT_TRY(scat::launch_row_lowpass(W, pc * L * L, m_r, M2c, m_c, tab + p->phi_cols_off[r2], o, cm2,
+                                        K, tw, tw_n, st));
     }
     s2_base += L * L * octs;
   }
