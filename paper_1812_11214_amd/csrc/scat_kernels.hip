@@ -1074,15 +1074,16 @@ __global__ __launch_bounds__(256) void k_col_node(const void *__restrict__ src_v
     for (int j = 0; j < JT; ++j) lds[(t + T * j) * TC + c] = fm[j];
     __syncthreads();
     if (LM == 32) {
-      if (static_cast<int>(threadIdx.x) < 2 * TC) {
-        const int tp = threadIdx.x & 1, cc = threadIdx.x >> 1;
-        float2 y[16], w2[16];
+      // 4 lanes per column, 8 points each (half the threads of a 32-column tile)
+      if (static_cast<int>(threadIdx.x) < 4 * TC) {
+        const int tp = threadIdx.x & 3, cc = threadIdx.x >> 2;
+        float2 y[8], w2[8];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) y[i] = lds[(tp + 2 * i) * TC + cc];
-        load_twiddles<16, 2>(w2, tp, tw, tw_n);
-        fft_core<16, 2, true, true>(y, tp, lds + LM * TC + cc * 48, 3, 1, w2);
+        for (int i = 0; i < 8; ++i) y[i] = lds[(tp + 4 * i) * TC + cc];
+        load_twiddles<8, 4>(w2, tp, tw, tw_n);
+        fft_core<8, 4, true, true>(y, tp, lds + LM * TC + cc * 48, 5, 1, w2);
 #pragma unroll
-        for (int i = 0; i < 16; ++i) Wl[(tp + 2 * i) * WS + c0 + cc] = y[i].x;
+        for (int i = 0; i < 8; ++i) Wl[(tp + 4 * i) * WS + c0 + cc] = y[i].x;
       }
     } else {
       if (static_cast<int>(threadIdx.x) < TC) {
@@ -1126,16 +1127,16 @@ __global__ __launch_bounds__(256) void k_col_node(const void *__restrict__ src_v
     const int pl = node / cm.G, g = node % cm.G;
     float *op = out + ((static_cast<size_t>(pl) * K + chan_of(cm, g)) * LM + 2 * pr) * LM;
     if (LM == 32) {
-      if (tr < 2) {
-        float2 y[16], w2[16];
+      if (tr < 4) {  // 4 lanes per row pair, 8 points each
+        float2 y[8], w2[8];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) y[i] = xr[tr + 2 * i];
-        load_twiddles<16, 2>(w2, tr, tw, tw_n);
-        fft_core<16, 2, true, true>(y, tr, xr + 32, 3, 1, w2);
+        for (int i = 0; i < 8; ++i) y[i] = xr[tr + 4 * i];
+        load_twiddles<8, 4>(w2, tr, tw, tw_n);
+        fft_core<8, 4, true, true>(y, tr, xr + 32, 5, 1, w2);
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          op[tr + 2 * i] = y[i].x;
-          op[LM + tr + 2 * i] = y[i].y;
+        for (int i = 0; i < 8; ++i) {
+          op[tr + 4 * i] = y[i].x;
+          op[LM + tr + 4 * i] = y[i].y;
         }
       }
     } else {
