@@ -865,7 +865,19 @@ __global__ __launch_bounds__(256) void k_col_fast(const void *__restrict__ src_v
 #pragma unroll
     for (int j = 0; j < JT; ++j) lds[(t + T * j) * TC + c] = fm[j];
     __syncthreads();
-    if (LM_R == 32) {
+    if (LM_R == 32 && T >= 4) {
+      // 4 lanes per column, 8 points each
+      if (static_cast<int>(threadIdx.x) < 4 * TC) {
+        const int tp = threadIdx.x & 3, cc = threadIdx.x >> 2;
+        float2 y[8], w2[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) y[i] = lds[(tp + 4 * i) * TC + cc];
+        load_twiddles<8, 4>(w2, tp, tw, tw_n);
+        fft_core<8, 4, true, true>(y, tp, lds + LM_R * TC + cc * 48, 5, 1, w2);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) wp[(tp + 4 * i) * Mc + cc] = y[i].x;
+      }
+    } else if (LM_R == 32) {
       if (static_cast<int>(threadIdx.x) < 2 * TC) {
         const int tp = threadIdx.x & 1, cc = threadIdx.x >> 1;
         float2 y[16], w2[16];
@@ -1641,7 +1653,20 @@ __global__ __launch_bounds__(256) void k_row_lowpass_fast(const float *__restric
     const long pl = node / cm.G;
     const int g = static_cast<int>(node % cm.G);
     float *op = out + ((static_cast<size_t>(pl) * K + chan_of(cm, g)) * m_r + r) * LM_C;
-    if (LM_C == 32) {
+    if (LM_C == 32 && T >= 4) {
+      if (t < 4) {  // 4 lanes per row pair, 8 points each
+        float2 y[8], w2[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) y[i] = xch[t + 4 * i];
+        load_twiddles<8, 4>(w2, t, tw, tw_n);
+        fft_core<8, 4, true, true>(y, t, xch + 16 * (T + 1), 5, 1, w2);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          op[t + 4 * i] = y[i].x;
+          op[LM_C + t + 4 * i] = y[i].y;
+        }
+      }
+    } else if (LM_C == 32) {
       if (t < 2) {
         float2 y[16], w2[16];
 #pragma unroll
