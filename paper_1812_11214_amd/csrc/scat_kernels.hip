@@ -1187,13 +1187,16 @@ __global__ __launch_bounds__(256) void k_leaf_node(const float2 *__restrict__ sr
                                                     float *__restrict__ out, ChanMap cm, int K,
                                                     const float2 *__restrict__ tw, int tw_n) {
   static_assert(N == 64 && M == 32, "thread layout below");
-  constexpr int T1 = N / 16;             // 4 threads per column
-  constexpr int RS = slab_row_stride(N);  // 84
-  constexpr int WS = N + 1;               // floats per row of W
+  constexpr int T1 = N / 16;  // 4 threads per column
+  constexpr int RS = N;       // the exchange areas are accessed along c: no padding needed
+  constexpr int WS = N + 1;   // floats per row of W
   extern __shared__ float2 lds[];
-  float2 *area = lds;                                   // N * RS: exchange areas
-  float2 *wtab = lds + N * RS;                          // N: twiddles of the N-point columns
-  float *wl = reinterpret_cast<float *>(wtab + N);      // M * WS: W
+  float2 *area = lds;                           // N * RS: exchange areas of stage A
+  float2 *wtab = lds + N * RS;                  // N: twiddles of the N-point columns
+  // W takes the head of the area once stage A's transforms are done, stage B's exchange
+  // areas follow it
+  float *wl = reinterpret_cast<float *>(area);  // M * WS floats
+  constexpr int WL2 = (M * WS + 1) / 2;         // the same in float2 elements
   const int q = threadIdx.x;
   for (int idx = q; idx < N; idx += 256) wtab[idx] = tw[(idx / T1) * (idx % T1) * (tw_n / N)];
   __syncthreads();
@@ -1229,7 +1232,7 @@ __global__ __launch_bounds__(256) void k_leaf_node(const float2 *__restrict__ sr
 #pragma unroll
   for (int i = 0; i < 8; ++i)
     z[i] = make_float2(wl[(2 * p) * WS + t + 8 * i], wl[(2 * p + 1) * WS + t + 8 * i]);
-  float2 *xb = area + p * 80;  // 8 * (8 + 1) exchange elements, then the regrouping space
+  float2 *xb = area + WL2 + p * 80;  // 8 * (8 + 1) exchange elements, then the regrouping space
   {
     float2 w8[8];
     load_twiddles<8, 8>(w8, t, tw, tw_n);
@@ -2042,8 +2045,7 @@ hipError_t launch_leaf_node(const float2 *src, long nodes, int Mr, int m, const 
   if (!leaf_node_supported_impl(Mr, Mr, m, m, tw_n) || nodes > 0x7fffffffL || cm.G < 1 ||
       cm.inner < 1 || nodes % cm.G != 0)
     return hipErrorInvalidValue;
-  const size_t lds = (static_cast<size_t>(64) * slab_row_stride(64) + 64) * sizeof(float2) +
-                     static_cast<size_t>(32) * 65 * sizeof(float);
+  const size_t lds = (static_cast<size_t>(64) * 64 + 64) * sizeof(float2);
   const double pts = static_cast<double>(nodes) * 64 * 64;
   Observe ob("k_leaf_node<64, 32>", pts * 8 + static_cast<double>(nodes) * 32 * 32 * 4,
              static_cast<double>(nodes) * (2.0 * 64 * fft_flops(64) + 64 * fft_flops(32) +
