@@ -61,6 +61,8 @@ def test_config1_blobs_prefix():
     ((4, 128), 2, 5, 2), ((4, 64), 2, 3, 2), ((8, 64), 3, 2, 2), ((4, 32), 1, 2, 2),
     # coarse octaves whose grids are too small for the fused row pass
     ((32, 128), 4, 2, 2), ((64, 128), 4, 3, 2), ((16, 128), 3, 2, 2), ((16, 256), 4, 2, 2),
+    # 64 x 64 leaves with a 32 x 32 output (whole-leaf kernel): first and second order
+    ((128, 128), 2, 3, 2), ((64, 64), 1, 4, 2), ((128, 128), 2, 2, 1),
 ])
 def test_2d_shapes(shape, J, L, max_order):
     rng = np.random.default_rng(hash((shape, J, L)) % 2**32)
@@ -71,6 +73,7 @@ def test_2d_shapes(shape, J, L, max_order):
 @pytest.mark.parametrize("shape,J,L,max_order,batch", [
     ((512, 64), 3, 3, 2, 2), ((64, 512), 2, 5, 2, 2), ((256, 256), 5, 2, 2, 1),
     ((1024, 32), 2, 5, 2, 1), ((512, 512), 2, 6, 1, 1), ((128, 128), 6, 3, 2, 2),
+    ((512, 512), 4, 2, 2, 1),  # 64 x 64 leaves of the stored-spectrum schedule
 ])
 def test_2d_stored_spectrum_path(shape, J, L, max_order, batch):
     """Shapes the fused row pass does not take (a side of 512 or more, or more than four
