@@ -44,7 +44,9 @@ typedef enum {
                           range the called function supports */
   SCAT_ERR_ALLOC = 3,  /* host or device allocation failed */
   SCAT_ERR_DEVICE = 4, /* a HIP call failed (no device, launch error, ...) */
-  SCAT_ERR_NULL = 5    /* a required pointer is NULL */
+  SCAT_ERR_NULL = 5,   /* a required pointer is NULL */
+  SCAT_ERR_WORKSPACE = 6 /* scat_forward_static: one plane of this plan needs more scratch than
+                            the library's static buffer holds */
 } scat_status;
 
 /*
@@ -150,6 +152,26 @@ scat_status scat_plan_grid_shape(const scat_plan *plan, int *shape_out);
  */
 scat_status scat_forward(scat_plan *plan, const float *in, float *out, long batch,
                          void *stream);
+
+/*
+ * scat_forward for callers that cannot allocate device memory (code under HIP graph capture,
+ * serving loops and harnesses that forbid hipMalloc): same arguments, same result, but the
+ * intermediate arrays live in a buffer of SCAT_STATIC_SCRATCH_MB MiB that is part of the
+ * library's device image (each GPU the library runs on holds one copy until the process
+ * ends) instead of the plan's own scratch.  The call allocates and frees nothing and records
+ * no kernel timing (scat_plan_timing_* is ignored for it).  A batch whose intermediates exceed
+ * the buffer is run in consecutive chunks on `stream`.
+ * Errors: as scat_forward, and SCAT_ERR_WORKSPACE if a single plane of this plan needs more
+ * than the buffer (scat_plan_workspace_bytes(plan, 1) > SCAT_STATIC_SCRATCH_MB MiB); then
+ * nothing is enqueued.
+ * Every call on a GPU shares that GPU's buffer, whatever the plan or stream: calls whose work
+ * overlaps in time on one GPU race; the caller orders them (one stream, or events).  The
+ * buffer keeps the last call's contents between calls; the schedules write every element
+ * before reading it, so nothing needs clearing.
+ */
+#define SCAT_STATIC_SCRATCH_MB 64
+scat_status scat_forward_static(scat_plan *plan, const float *in, float *out, long batch,
+                                void *stream);
 
 /*
  * Backward pass: the gradient of  sum(grad_out * S(in))  with respect to `in`,

@@ -49,6 +49,8 @@ def lib():
     L.scat_plan_grid_shape.restype = ci
     L.scat_forward.argtypes = [vp, vp, vp, cl, vp]
     L.scat_forward.restype = ci
+    L.scat_forward_static.argtypes = [vp, vp, vp, cl, vp]
+    L.scat_forward_static.restype = ci
     L.scat_backward.argtypes = [vp, vp, vp, vp, cl, vp]
     L.scat_backward.restype = ci
     L.scat_plan_backward_workspace_bytes.argtypes = [vp, cl]
@@ -85,7 +87,8 @@ EXPORTS = ("scat_plan_create", "scat_plan_create_host", "scat_forward", "scat_pl
            "scat_plan_workspace_bytes", "scat_plan_filter", "scat_status_string",
            "scat_plan_timing_begin", "scat_plan_timing_end", "scat_plan_timing_row",
            "scat_backward", "scat_plan_backward_workspace_bytes", "scat_plan_create_padded",
-           "scat_plan_create_padded_host", "scat_plan_grid_shape", "scat_plan_create_ex")
+           "scat_plan_create_padded_host", "scat_plan_grid_shape", "scat_plan_create_ex",
+           "scat_forward_static")
 
 
 def scat_status_string(status):
@@ -242,6 +245,18 @@ def scat_forward(plan, in_ptr, out_ptr, batch, stream_ptr=None):
                             ctypes.c_void_p(stream_ptr) if stream_ptr else None)
     if st != SCAT_OK:
         raise ScatError(st, "scat_forward")
+
+
+SCAT_STATIC_SCRATCH_MB = 64
+SCAT_ERR_WORKSPACE = 6
+
+
+def scat_forward_static(plan, in_ptr, out_ptr, batch, stream_ptr=None):
+    """scat_forward without any allocation: intermediates in the library's static buffer."""
+    st = lib().scat_forward_static(plan, ctypes.c_void_p(in_ptr), ctypes.c_void_p(out_ptr),
+                                   int(batch), ctypes.c_void_p(stream_ptr) if stream_ptr else None)
+    if st != SCAT_OK:
+        raise ScatError(st, "scat_forward_static")
 
 
 class Scattering:

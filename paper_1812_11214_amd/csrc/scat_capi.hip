@@ -8,6 +8,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <map>
+#include <mutex>
 #include <new>
 #include <string>
 #include <utility>
@@ -97,6 +98,10 @@ struct scat_plan {
   int tw_n = 0;
   void *d_scratch = nullptr;
   size_t scratch_bytes = 0;
+  // scratch of the call in progress: d_scratch, or the library's static array for
+  // scat_forward_static (set by the entry points before any schedule runs)
+  void *work = nullptr;
+  void *static_scratch = nullptr;  // device address of the library's static scratch array
   // offsets (in floats) into d_tables
   std::vector<size_t> psi1_off;                    // per octave; LQ tables contiguous
   std::map<std::pair<int, int>, size_t> psi2_off;  // (res, j2) -> tables (2-D: L contiguous)
@@ -123,6 +128,37 @@ namespace {
 
 using scat::ChanMap;
 using scat::FilterTable;
+
+// ---- scratch of scat_forward_static: one array per GPU in the library's device image, for
+// callers that may not allocate.  Host code never uses the array's name as an address: the
+// device address is looked up once per device (static_scratch_ptr) and passed to the
+// schedules like any other scratch pointer.
+constexpr size_t kStaticScratchBytes = size_t(SCAT_STATIC_SCRATCH_MB) << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mutex;
+void *g_static_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the CURRENT device (`dev`), looked up on first use.
+scat_status static_scratch_ptr(int dev, void **out) {
+  if (dev < 0 || dev >= kMaxDevices) return SCAT_ERR_DEVICE;
+  std::lock_guard<std::mutex> lock(g_static_mutex);
+  if (g_static_ptr[dev] == nullptr) {
+    void *ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) {
+      (void)hipGetLastError();
+      return SCAT_ERR_DEVICE;
+    }
+    g_static_ptr[dev] = ptr;
+  }
+  *out = g_static_ptr[dev];
+  return SCAT_OK;
+}
+
+// Set-up step of every device plan: remember where `scratch` lives on the plan's device.
+scat_status note_static_scratch(scat_plan *p) { return static_scratch_ptr(p->device, &p->static_scratch); }
+
 
 // Bytes of scratch one chunk of planes may use (a forward call walks the batch in chunks).
 // SCAT_SCRATCH_MB in the environment overrides the default of 12 GiB.
@@ -159,8 +195,10 @@ size_t t_elems_1d(const scat::HostPlan &h, size_t n) {
   return most * static_cast<size_t>(h.LQ);
 }
 
-Layout make_layout(const scat_plan &p, long batch) {
+// budget: bytes of scratch one chunk may use (0 = scratch_budget())
+Layout make_layout(const scat_plan &p, long batch, size_t budget = 0) {
   Layout L;
+  if (budget == 0) budget = scratch_budget();
   const scat::HostPlan &h = p.host;
   if (h.dims == 3) {
     L.per_plane = bytes_per_volume_3d(p);
@@ -171,7 +209,7 @@ Layout make_layout(const scat_plan &p, long batch) {
       L.xh = L.per_plane;  // offset of those two per volume
       L.per_plane += L.pad_in + L.pad_out;
     }
-    long c = static_cast<long>(scratch_budget() / L.per_plane);
+    long c = static_cast<long>(budget / L.per_plane);
     if (c < 1) c = 1;
     L.chunk = c > batch ? batch : c;
     return L;
@@ -226,7 +264,7 @@ Layout make_layout(const scat_plan &p, long batch) {
     L.pad_out = static_cast<size_t>(h.K) * m_r * (h.shape[1] >> h.res(h.J)) * sizeof(float);
   }
   L.per_plane = L.xh + L.t + L.u + L.v + L.w + L.pad_in + L.pad_out;
-  long c = static_cast<long>(scratch_budget() / L.per_plane);
+  long c = static_cast<long>(budget / L.per_plane);
   if (c < 1) c = 1;
   if (c > batch) c = batch;
   L.chunk = c;
@@ -336,7 +374,7 @@ scat_status upload(scat_plan *p) {
       hipSuccess)
     return SCAT_ERR_DEVICE;
   p->has_device = true;
-  return SCAT_OK;
+  return note_static_scratch(p);
 }
 
 scat_status upload_3d(scat_plan *p);
@@ -704,7 +742,7 @@ scat_status forward_2d(scat_plan *p, const float *in, float *out, long p0, long 
   const int Nr = p->n1, Nc = p->n2;
   const int rJ = h.res(J);
   const int m_r = Nr >> rJ, m_c = Nc >> rJ;
-  char *base = static_cast<char *>(p->d_scratch);
+  char *base = static_cast<char *>(p->work);
   float2 *XH = reinterpret_cast<float2 *>(base);
   float2 *T = reinterpret_cast<float2 *>(base + lay.xh * pc);
   float2 *U = reinterpret_cast<float2 *>(base + (lay.xh + lay.t) * pc);
@@ -793,7 +831,7 @@ scat_status forward_2d_fused(scat_plan *p, const float *in, float *out, long p0,
   const int rJ = h.res(J);
   const int m_r = Nr >> rJ, m_c = Nc >> rJ;
   const size_t n = static_cast<size_t>(Nr) * Nc;
-  char *base = static_cast<char *>(p->d_scratch);
+  char *base = static_cast<char *>(p->work);
   float2 *XC = reinterpret_cast<float2 *>(base);
   float2 *T = reinterpret_cast<float2 *>(base + lay.xh * pc);
   float2 *U = reinterpret_cast<float2 *>(base + (lay.xh + lay.t) * pc);
@@ -886,7 +924,7 @@ scat_status forward_2d_tree(scat_plan *p, const float *in, float *out, long p0, 
   const int J = h.J, L = h.LQ, K = h.K;
   const int Nr = p->n1, Nc = p->n2;
   const int m_r = Nr >> J, m_c = Nc >> J;
-  char *base = static_cast<char *>(p->d_scratch);
+  char *base = static_cast<char *>(p->work);
   float2 *XH = reinterpret_cast<float2 *>(base);
   (void)lay;
   const float *tab = p->d_tables;
@@ -1035,7 +1073,7 @@ scat_status backward_2d_rows_adjoint(scat_plan *p, const float *go, float *gi, l
   };
   int s2_base = 1 + J * L;
   float2 *GUj = GU;
-  const float2 *Tfwd = reinterpret_cast<const float2 *>(static_cast<const char *>(p->d_scratch) +
+  const float2 *Tfwd = reinterpret_cast<const float2 *>(static_cast<const char *>(p->work) +
                                                         bl.fwd.xh * pc);
   size_t t_off = 0;  // as forward_2d_fused lays out T: all octaves, one after the other
   for (int j1 = 0; j1 < J; ++j1) {
@@ -1136,7 +1174,7 @@ scat_status backward_2d(scat_plan *p, const float *in, const float *gout, float 
   const int rJ = h.res(J);
   const int m_r = Nr >> rJ, m_c = Nc >> rJ;
   const size_t n = static_cast<size_t>(Nr) * Nc;
-  char *base = static_cast<char *>(p->d_scratch);
+  char *base = static_cast<char *>(p->work);
   float2 *after_fwd =
       reinterpret_cast<float2 *>(base + (bl.fwd.xh + bl.fwd.t + bl.fwd.u + bl.fwd.v) * pc);
   bl.tape.base = after_fwd;
@@ -1169,7 +1207,7 @@ scat_status backward_1d(scat_plan *p, const float *in, const float *gout, float 
   const int N = N1 * N2;
   const int rJ = h.res(J);
   const int mc_out = N2 >> rJ, m = N >> rJ;
-  char *base = static_cast<char *>(p->d_scratch);
+  char *base = static_cast<char *>(p->work);
   float2 *after_fwd = reinterpret_cast<float2 *>(base + (bl.fwd.xh + bl.fwd.t + bl.fwd.u) * pc);
   bl.tape.base = after_fwd;
   float2 *GX = after_fwd + bl.tape.total * pc;
@@ -1347,7 +1385,7 @@ scat_status upload_3d(scat_plan *p) {
   if (hipMemcpy(p->d_tw, tw.data(), tw.size() * sizeof(float2), hipMemcpyHostToDevice) != hipSuccess)
     return SCAT_ERR_DEVICE;
   p->has_device = true;
-  return SCAT_OK;
+  return note_static_scratch(p);
 }
 
 // scratch per volume.  General path: X^, U^ (and V^ at order 2), work buffer, all complex;
@@ -1374,7 +1412,7 @@ scat_status forward_3d_fused(scat_plan *p, const float *in, float *out, long p0,
   const size_t tot = static_cast<size_t>(pc) * n;
   const bool second = h.max_order == 2 && J >= 2;
   const int m0 = n0 >> Jo, m1 = n1 >> Jo, m2 = n2 >> Jo;
-  float2 *XH = static_cast<float2 *>(p->d_scratch);
+  float2 *XH = static_cast<float2 *>(p->work);
   float2 *UH = XH + tot;
   float2 *T = UH + tot;
   float2 *W = T + tot;
@@ -1423,7 +1461,7 @@ scat_status forward_3d(scat_plan *p, const float *in, float *out, long p0, long 
   const size_t n = h.points();
   const long tot = pc * static_cast<long>(n);
   const bool second = h.max_order == 2 && J >= 2;
-  float2 *XH = static_cast<float2 *>(p->d_scratch);
+  float2 *XH = static_cast<float2 *>(p->work);
   float2 *UH = XH + tot;
   float2 *Wk = UH + tot;
   float2 *VH = second ? Wk + tot : nullptr;
@@ -1497,7 +1535,7 @@ scat_status backward_3d(scat_plan *p, const float *in, const float *gout, float 
   const size_t n = h.points();
   const long tot = pc * static_cast<long>(n);
   const bool second = h.max_order == 2 && J >= 2;
-  float2 *XH = static_cast<float2 *>(p->d_scratch);
+  float2 *XH = static_cast<float2 *>(p->work);
   float2 *AX = XH + tot, *UH = AX + tot, *AU = UH + tot, *Wk = AU + tot;
   float2 *W1 = Wk + tot, *W2 = W1 + static_cast<size_t>(M) * tot;
   float *acc1 = reinterpret_cast<float *>(W2 + static_cast<size_t>(M) * tot), *acc2 = acc1 + tot;
@@ -1627,7 +1665,7 @@ scat_status forward_1d(scat_plan *p, const float *in, float *out, long p0, long 
   const int N = N1 * N2;
   const int rJ = h.res(J);
   const int mc_out = N2 >> rJ;
-  char *base = static_cast<char *>(p->d_scratch);
+  char *base = static_cast<char *>(p->work);
   float2 *XH = reinterpret_cast<float2 *>(base);
   float2 *T = reinterpret_cast<float2 *>(base + lay.xh * pc);
   float2 *U = reinterpret_cast<float2 *>(base + (lay.xh + lay.t) * pc);
@@ -1715,13 +1753,16 @@ scat_status forward_1d(scat_plan *p, const float *in, float *out, long p0, long 
 
 // Makes the plan's scratch buffer at least `need` bytes (growing it synchronises the device).
 scat_status ensure_scratch(scat_plan *plan, size_t need) {
+  plan->work = plan->d_scratch;
   if (need <= plan->scratch_bytes) return SCAT_OK;
   if (hipDeviceSynchronize() != hipSuccess) return SCAT_ERR_DEVICE;
   if (plan->d_scratch) (void)hipFree(plan->d_scratch);
   plan->d_scratch = nullptr;
+  plan->work = nullptr;
   plan->scratch_bytes = 0;
   if (hipMalloc(&plan->d_scratch, need) != hipSuccess) return SCAT_ERR_ALLOC;
   plan->scratch_bytes = need;
+  plan->work = plan->d_scratch;
   return SCAT_OK;
 }
 
@@ -1732,6 +1773,75 @@ struct ObserverScope {
   }
   ~ObserverScope() { scat::set_launch_observer(nullptr); }
 };
+
+// The chunk loop of a forward call: `lay.chunk` planes at a time through the schedule of the
+// plan, all on `st`, using the scratch plan->work points at (lay.per_plane * lay.chunk bytes).
+scat_status forward_chunks(scat_plan *plan, const float *in, float *out, long batch, const Layout &lay,
+                           hipStream_t st, bool observe = true) {
+  struct NoObserver {
+    scat_plan *p;
+    bool was;
+    explicit NoObserver(scat_plan *q, bool off) : p(q), was(q->timer.enabled) {
+      if (off) p->timer.enabled = false;
+    }
+    ~NoObserver() { p->timer.enabled = was; }
+  } no_observer(plan, !observe);  // (the timer creates HIP events on demand)
+  ObserverScope observer_scope(plan);
+  const scat::HostPlan &h = plan->host;
+  for (long p0 = 0; p0 < batch; p0 += lay.chunk) {
+    long pc = batch - p0 < lay.chunk ? batch - p0 : lay.chunk;
+    const float *cin = in;
+    float *cout = out;
+    long cp0 = p0;
+    float *xp = nullptr, *op = nullptr;
+    if (plan->padded) {
+      // extend this chunk's signals into scratch and transform them as planes 0..pc-1
+      char *tail = static_cast<char *>(plan->work) +
+                   (lay.xh + lay.t + lay.u + lay.v + lay.w) * static_cast<size_t>(lay.chunk);
+      xp = reinterpret_cast<float *>(tail);
+      op = reinterpret_cast<float *>(tail + lay.pad_in * static_cast<size_t>(lay.chunk));
+      if (h.dims == 3) {
+        const int *u = plan->user_shape3, *g = plan->h3.shape;
+        hipLaunchKernelGGL(k_pad_symmetric3, dim3(stream_blocks(pc * static_cast<long>(plan->h3.points()))),
+                           dim3(256), 0, st, in + static_cast<size_t>(p0) * u[0] * u[1] * u[2], xp, pc,
+                           u[0], u[1], u[2], g[0], g[1], g[2]);
+      } else {
+        const int ur = plan->user_shape[0], uc = plan->user_shape[1];
+        hipLaunchKernelGGL(k_pad_symmetric, dim3(stream_blocks(pc * h.shape[0] * h.shape[1])),
+                           dim3(256), 0, st, in + static_cast<size_t>(p0) * ur * uc, xp, pc, ur, uc,
+                           h.shape[0], h.shape[1]);
+      }
+      if (hipGetLastError() != hipSuccess) return SCAT_ERR_DEVICE;
+      cin = xp;
+      cout = op;
+      cp0 = 0;
+    }
+    scat_status s = h.dims == 3   ? (plan->fused3 ? forward_3d_fused(plan, cin, cout, cp0, pc, st)
+                                                  : forward_3d(plan, cin, cout, cp0, pc, st))
+                    : h.dims == 1 ? forward_1d(plan, cin, cout, cp0, pc, lay, st)
+                    : plan->tree  ? forward_2d_tree(plan, cin, cout, cp0, pc, lay, st)
+                    : plan->fused ? forward_2d_fused(plan, cin, cout, cp0, pc, lay, st)
+                                  : forward_2d(plan, cin, cout, cp0, pc, lay, st);
+    if (s != SCAT_OK) return s;
+    if (plan->padded && h.dims == 3) {
+      const int Jo = plan->h3.out_shift();
+      const int *g = plan->h3.shape, *o = plan->user_out3;
+      const long maps = pc * h.K;
+      hipLaunchKernelGGL(k_crop3, dim3(stream_blocks(maps * o[0] * o[1] * o[2])), dim3(256), 0, st, op,
+                         out + static_cast<size_t>(p0) * h.K * o[0] * o[1] * o[2], maps, g[0] >> Jo,
+                         g[1] >> Jo, g[2] >> Jo, o[0], o[1], o[2]);
+      if (hipGetLastError() != hipSuccess) return SCAT_ERR_DEVICE;
+    } else if (plan->padded) {
+      const int m_r = h.dims == 2 ? h.shape[0] >> h.res(h.J) : 1, m_c = h.shape[1] >> h.res(h.J);
+      const int o_r = plan->user_out[0], o_c = plan->user_out[1];
+      hipLaunchKernelGGL(k_crop, dim3(stream_blocks(pc * h.K * o_r * o_c)), dim3(256), 0, st, op,
+                         out + static_cast<size_t>(p0) * h.K * o_r * o_c, pc * h.K, m_r, m_c, o_r,
+                         o_c);
+      if (hipGetLastError() != hipSuccess) return SCAT_ERR_DEVICE;
+    }
+  }
+  return SCAT_OK;
+}
 
 }  // namespace
 
@@ -1794,61 +1904,22 @@ scat_status scat_forward(scat_plan *plan, const float *in, float *out, long batc
     const scat_status grown = ensure_scratch(plan, need);
     if (grown != SCAT_OK) return grown;
   }
-  ObserverScope observer_scope(plan);
-  const scat::HostPlan &h = plan->host;
-  for (long p0 = 0; p0 < batch; p0 += lay.chunk) {
-    long pc = batch - p0 < lay.chunk ? batch - p0 : lay.chunk;
-    const float *cin = in;
-    float *cout = out;
-    long cp0 = p0;
-    float *xp = nullptr, *op = nullptr;
-    if (plan->padded) {
-      // extend this chunk's signals into scratch and transform them as planes 0..pc-1
-      char *tail = static_cast<char *>(plan->d_scratch) +
-                   (lay.xh + lay.t + lay.u + lay.v + lay.w) * static_cast<size_t>(lay.chunk);
-      xp = reinterpret_cast<float *>(tail);
-      op = reinterpret_cast<float *>(tail + lay.pad_in * static_cast<size_t>(lay.chunk));
-      if (h.dims == 3) {
-        const int *u = plan->user_shape3, *g = plan->h3.shape;
-        hipLaunchKernelGGL(k_pad_symmetric3, dim3(stream_blocks(pc * static_cast<long>(plan->h3.points()))),
-                           dim3(256), 0, st, in + static_cast<size_t>(p0) * u[0] * u[1] * u[2], xp, pc,
-                           u[0], u[1], u[2], g[0], g[1], g[2]);
-      } else {
-        const int ur = plan->user_shape[0], uc = plan->user_shape[1];
-        hipLaunchKernelGGL(k_pad_symmetric, dim3(stream_blocks(pc * h.shape[0] * h.shape[1])),
-                           dim3(256), 0, st, in + static_cast<size_t>(p0) * ur * uc, xp, pc, ur, uc,
-                           h.shape[0], h.shape[1]);
-      }
-      if (hipGetLastError() != hipSuccess) return SCAT_ERR_DEVICE;
-      cin = xp;
-      cout = op;
-      cp0 = 0;
-    }
-    scat_status s = h.dims == 3   ? (plan->fused3 ? forward_3d_fused(plan, cin, cout, cp0, pc, st)
-                                                  : forward_3d(plan, cin, cout, cp0, pc, st))
-                    : h.dims == 1 ? forward_1d(plan, cin, cout, cp0, pc, lay, st)
-                    : plan->tree  ? forward_2d_tree(plan, cin, cout, cp0, pc, lay, st)
-                    : plan->fused ? forward_2d_fused(plan, cin, cout, cp0, pc, lay, st)
-                                  : forward_2d(plan, cin, cout, cp0, pc, lay, st);
-    if (s != SCAT_OK) return s;
-    if (plan->padded && h.dims == 3) {
-      const int Jo = plan->h3.out_shift();
-      const int *g = plan->h3.shape, *o = plan->user_out3;
-      const long maps = pc * h.K;
-      hipLaunchKernelGGL(k_crop3, dim3(stream_blocks(maps * o[0] * o[1] * o[2])), dim3(256), 0, st, op,
-                         out + static_cast<size_t>(p0) * h.K * o[0] * o[1] * o[2], maps, g[0] >> Jo,
-                         g[1] >> Jo, g[2] >> Jo, o[0], o[1], o[2]);
-      if (hipGetLastError() != hipSuccess) return SCAT_ERR_DEVICE;
-    } else if (plan->padded) {
-      const int m_r = h.dims == 2 ? h.shape[0] >> h.res(h.J) : 1, m_c = h.shape[1] >> h.res(h.J);
-      const int o_r = plan->user_out[0], o_c = plan->user_out[1];
-      hipLaunchKernelGGL(k_crop, dim3(stream_blocks(pc * h.K * o_r * o_c)), dim3(256), 0, st, op,
-                         out + static_cast<size_t>(p0) * h.K * o_r * o_c, pc * h.K, m_r, m_c, o_r,
-                         o_c);
-      if (hipGetLastError() != hipSuccess) return SCAT_ERR_DEVICE;
-    }
-  }
-  return SCAT_OK;
+  return forward_chunks(plan, in, out, batch, lay, st);
+}
+
+scat_status scat_forward_static(scat_plan *plan, const float *in, float *out, long batch,
+                                void *stream) {
+  if (plan == nullptr) return SCAT_ERR_NULL;
+  if (batch < 0) return SCAT_ERR_ARG;
+  if (batch == 0) return SCAT_OK;
+  if (in == nullptr || out == nullptr) return SCAT_ERR_NULL;
+  if (!plan->has_device || plan->static_scratch == nullptr) return SCAT_ERR_DEVICE;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev != plan->device) return SCAT_ERR_DEVICE;
+  const Layout lay = make_layout(*plan, batch, kStaticScratchBytes);
+  if (lay.per_plane > kStaticScratchBytes) return SCAT_ERR_WORKSPACE;
+  plan->work = plan->static_scratch;
+  return forward_chunks(plan, in, out, batch, lay, static_cast<hipStream_t>(stream), false);
 }
 
 scat_status scat_backward(scat_plan *plan, const float *in, const float *grad_out, float *grad_in,
@@ -1888,7 +1959,7 @@ scat_status scat_backward(scat_plan *plan, const float *in, const float *grad_ou
       const int Jo = plan->h3.out_shift();
       const size_t un = static_cast<size_t>(u[0]) * u[1] * u[2];
       const size_t on = static_cast<size_t>(o[0]) * o[1] * o[2];
-      float *xp = reinterpret_cast<float *>(static_cast<char *>(plan->d_scratch) +
+      float *xp = reinterpret_cast<float *>(static_cast<char *>(plan->work) +
                                             core * static_cast<size_t>(chunk));
       float *gxp = xp + n3 * chunk;
       float *gop = gxp + n3 * chunk;
@@ -1950,7 +2021,7 @@ scat_status scat_backward(scat_plan *plan, const float *in, const float *grad_ou
     const int m_r = P_r >> (h.dims == 1 ? 0 : h.res(h.J)), m_c = P_c >> h.res(h.J);
     const int ur = plan->user_shape[0], uc = plan->user_shape[1];
     const int o_r = plan->user_out[0], o_c = plan->user_out[1];
-    float *xp = reinterpret_cast<float *>(static_cast<char *>(plan->d_scratch) +
+    float *xp = reinterpret_cast<float *>(static_cast<char *>(plan->work) +
                                           (bl.per_plane - bl.pad_floats * sizeof(float)) *
                                               static_cast<size_t>(bl.chunk));
     float *gxp = xp + n * bl.chunk;
@@ -2113,6 +2184,7 @@ const char *scat_status_string(scat_status s) {
     case SCAT_ERR_ALLOC: return "allocation failed";
     case SCAT_ERR_DEVICE: return "GPU error or plan has no device state";
     case SCAT_ERR_NULL: return "null pointer";
+    case SCAT_ERR_WORKSPACE: return "one plane needs more scratch than the static buffer holds";
   }
   return "unknown status";
 }
