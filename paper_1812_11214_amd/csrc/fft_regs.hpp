@@ -29,6 +29,16 @@ __device__ __forceinline__ float2 c_mulc(float2 a, float wr, float wi) {
   return make_float2(a.x * wr - a.y * s, a.x * s + a.y * wr);
 }
 
+// g / sqrt(m2), the factor of the modulus adjoint; 0 where m2 = 0.  The hardware root does not
+// take denormal inputs (it would return 0 and the quotient would be infinite), so a tiny m2 is
+// first scaled into the normal range by an exact power of two.
+__device__ __forceinline__ float over_sqrt(float g, float m2) {
+  if (!(m2 > 0.f)) return 0.f;
+  const bool tiny = m2 < 1.0e-30f;
+  const float r = g / __builtin_amdgcn_sqrtf(tiny ? m2 * 0x1p+64f : m2);
+  return tiny ? r * 0x1p+32f : r;
+}
+
 template <bool INV>
 __device__ __forceinline__ void dft4(float2 &x0, float2 &x1, float2 &x2, float2 &x3) {
   float2 t0 = c_add(x0, x2), t1 = c_sub(x0, x2), t2 = c_add(x1, x3), t3 = c_rot<INV>(c_sub(x1, x3));

@@ -114,7 +114,7 @@ __global__ __launch_bounds__(256) void k3_rho_back(const float2 *__restrict__ gu
   const long stride = static_cast<long>(gridDim.x) * blockDim.x;
   for (long i = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x; i < total; i += stride) {
     const float a = acc[i];
-    const float s = a > 0.f ? gu[i].x / __builtin_amdgcn_sqrtf(a) : 0.f;
+    const float s = over_sqrt(gu[i].x, a);
     const float2 v = y[i];
     y[i] = make_float2(v.x * s, v.y * s);
   }
@@ -381,7 +381,7 @@ __global__ __launch_bounds__(256) void k3_axis0_back(float2 *__restrict__ W, flo
       a[i] = 0.f;
     } else {
       const float s2 = acc[off + i * step];
-      a[i] = s2 > 0.f ? gu[off + i * step].x / __builtin_amdgcn_sqrtf(s2) : 0.f;
+      a[i] = over_sqrt(gu[off + i * step].x, s2);
     }
   }
   float2 vn[E];

@@ -341,7 +341,7 @@ __global__ __launch_bounds__(256, (E <= 16 ? 3 : 1)) void k_cols_modback(float2 
   for (int i = 0; i < E; ++i) {
     const float2 u = yv[i];
     const float m2 = u.x * u.x + u.y * u.y;
-    const float sgn = m2 > 0.f ? v[i].x / __builtin_amdgcn_sqrtf(m2) : 0.f;
+    const float sgn = over_sqrt(v[i].x, m2);
     v[i] = make_float2(u.x * sgn, u.y * sgn);
   }
   transform(std::false_type{});
@@ -792,7 +792,7 @@ __global__ __launch_bounds__((Slab<N1, N2>::NT)) void k_node_modback(
     for (int i = 0; i < 16; ++i) {
       const float2 u = yv[i];
       const float m2 = u.x * u.x + u.y * u.y;
-      const float sgn = m2 > 0.f ? v[i].x / __builtin_amdgcn_sqrtf(m2) : 0.f;
+      const float sgn = over_sqrt(v[i].x, m2);
       v[i] = make_float2(u.x * sgn, u.y * sgn);
     }
   }

@@ -136,6 +136,21 @@ def test_backward_zero_input_and_zero_gradient():
     assert np.all(_backward(shape, J, L, 2, x, np.zeros_like(g)) == 0)
 
 
+def test_backward_tiny_input_gives_finite_gradient():
+    """Inputs so small that |y|^2 is a denormal (or underflows) before the modulus: the
+    gradient must stay finite and bounded by what the unit factors y/|y| allow."""
+    shape, J, L = (32, 32), 2, 8
+    K = 1 + J * L + L * L
+    rng = np.random.default_rng(4)
+    g = rng.standard_normal((3, K, 8, 8)).astype(np.float32)
+    x = rng.standard_normal((3,) + shape).astype(np.float32)
+    ref = _backward(shape, J, L, 2, x, g)
+    for scale in (1e-18, 1e-20, 1e-23):
+        got = _backward(shape, J, L, 2, (x * np.float32(scale)).astype(np.float32), g)
+        assert np.isfinite(got).all(), scale
+        assert np.abs(got).max() <= 10 * np.abs(ref).max(), scale
+
+
 @pytest.mark.parametrize("n,J,Q,max_order,o,batch", [
     (64, 3, 2, 2, 0, 3), (256, 4, 1, 2, 0, 2), (1024, 5, 8, 2, 0, 2), (4096, 6, 8, 1, 0, 2),
     (2048, 2, 3, 2, 0, 2), (1024, 5, 2, 2, 2, 3), (65536, 6, 8, 2, 0, 1),

@@ -149,6 +149,44 @@ def test_config2_full_batch_sampled():
     assert got[:, order > 0].min() > -1e-4
 
 
+def _full_batch_sampled(wl, sample, dims):
+    """Workload `wl` at its full batch in one call (the launch shapes the benchmark times);
+    the sampled planes are compared with the oracle one by one, every plane is checked for
+    finite values and non-negative S1, S2."""
+    c = workloads.config(wl)
+    P = workloads.num_planes(wl)
+    x = workloads.planes(wl)
+    plan = scat.Scattering(c["shape"], c["J"], c["LQ"])
+    try:
+        got = gpu_forward(plan, x)
+        rows = plan.coeff_index()
+    finally:
+        plan.close()
+    assert got.shape[0] == P and np.isfinite(got).all()
+    order = order_of_channels(rows)
+    assert got[:, order > 0].min() > -1e-4 * np.abs(got).max()
+    if dims == 2:
+        bank = oracle.bank_2d(c["shape"][0], c["shape"][1], c["J"], c["LQ"])
+        want = oracle.scattering2d(x[sample], c["J"], c["LQ"], bank=bank)
+    else:
+        want = oracle.scattering1d(x[sample], c["J"], c["LQ"])
+    errs = per_order_errors(got[sample], want, order, x[sample])
+    print("workload", wl, "full batch of", P, "planes sampled", sample, errs, flush=True)
+    assert max(errs.values()) <= TOL, errs
+
+
+def test_config1_full_batch_sampled():
+    _full_batch_sampled(1, [0, 1, 2, 1535, 1536, 3070, 3071], 2)
+
+
+def test_config3_full_batch_sampled():
+    _full_batch_sampled(3, [0, 15, 31], 2)
+
+
+def test_config4_full_batch_sampled():
+    _full_batch_sampled(4, [0, 31, 63], 1)
+
+
 @pytest.mark.parametrize("shape,J,L,batch", [((64, 64), 2, 3, 7), ((64, 128), 3, 5, 3),
                                              ((256, 64), 3, 1, 2), ((32, 32), 1, 8, 5),
                                              ((256, 256), 4, 2, 1), ((128, 64), 4, 3, 2)])
