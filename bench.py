@@ -6,9 +6,12 @@
 A step is one forward transform (S0, S1, S2) of the whole batch of the headline
 workload: Scattering2D, J=3, L=8, 128 RGB images of 256x256 (384 planes), synthetic
 1/f^2 Gaussian fields, inputs and outputs resident in HBM.  Prints ONE JSON line:
-throughput in images/s, the roofline of the kernel that takes the most time (timed live
-with HIP events inside the library on the stream it launches on), and the fp64 CPU
-oracle timed on this machine's host cores on a bounded sample of the same workload.
+throughput in images/s; `roofline`, the fraction of the binding roofline (fp32 vector ALUs:
+the path's algorithmic bytes need far less time at the HBM peak than its model flops at the
+ALU peak) reached by the kernel that takes the most time, timed live with HIP events inside
+the library on the stream it launches on; `step`, the same for the whole step together with
+the algorithmic and the measured HBM traffic and their ratio; and the fp64 CPU oracle timed
+on this machine's host cores on a bounded sample of the same workload.
 """
 import argparse
 import json
@@ -23,15 +26,81 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 ALU_PEAK_TFLOPS = 157.3        # MI355X fp32 vector peak (256 CUs x 4 SIMD x 16 lanes x 2 x 2.4 GHz)
 WORKLOAD = 2                   # index into workloads.CONFIGS: 2-D J=3 L=8 256x256, 128x3 planes
 # committed rocprofv3 counter summaries, profiles/hbm_traffic_<tag>.txt, per workload index
-TRAFFIC_TAGS = {0: "2d_J2_L8_32x32_b4", 1: "2d_J2_L8_32x32_b3072", 2: "2d_J3_L8_256x256_b384",
+TRAFFIC_TAGS = {1: "2d_J2_L8_32x32_b3072", 2: "2d_J3_L8_256x256_b384",
                 3: "2d_J4_L8_512x512_b32", 4: "1d_J6_Q8_65536_b64", 5: "3d_J2_L3_64x64x64_b16"}
+# Algorithmic work per plane of the forward transform, per workload index: model flops
+# (5 n log2 n for every transform of the cascade taken as a full complex one, plus the
+# pointwise products, folds and moduli) and bytes (input + output + filter tables / planes).
+MODEL_MFLOP_PER_PLANE = {0: 2.50 + 0.52, 1: 2.50 + 0.52, 2: 332.2 + 60.0, 3: 1587.7 + 342.0,
+                         4: 296.0 + 43.5}
+ALG_BYTES_PER_PLANE = {0: 4096 + 20736 + 17664, 1: 4096 + 20736 + 23, 2: 262144 + 888832 + 18645,
+                       3: 1048576 + 1708032 + 1239552, 4: 262144 + 692224 + 237000}
 
 
-def cpu_baseline(planes, dims, J, LQ, channels, budget_s=20.0, grad=None):
-    """Time the oracle (single process, numpy FFTs are single threaded) on as many planes
-    of the workload as fit in about budget_s seconds.  With `grad` (dL/dS for every plane)
-    the oracle's backward pass is timed instead of its forward pass."""
+def oracle_worker(wl, start, count, t_start):
+    """One process of the all-cores leg (`bench.py --oracle-worker wl start count t_start`):
+    builds the filter bank and its planes untimed, waits for the common start time, runs the
+    forward oracle and prints when it started and finished (time.time())."""
     import oracle
+    from paper_1812_11214_amd import workloads
+    cfg = workloads.config(wl)
+    x = workloads.planes(wl, count, start)
+    if cfg["dims"] == 2:
+        bank = oracle.bank_2d(cfg["shape"][0], cfg["shape"][1], cfg["J"], cfg["LQ"])
+        run = lambda v: oracle.scattering2d(v, cfg["J"], cfg["LQ"], bank=bank)
+    else:
+        bank = oracle.bank_1d(cfg["shape"][0], cfg["J"], cfg["LQ"])
+        run = lambda v: oracle.scattering1d(v, cfg["J"], cfg["LQ"], bank=bank)
+    run(x[:1])
+    ready = time.time()
+    while time.time() < t_start:
+        time.sleep(0.001)
+    t0 = time.time()
+    run(x)
+    print("%.6f %.6f %.6f" % (ready, t0, time.time()), flush=True)
+
+
+def cpu_all_cores(wl, total_planes, channels, per_plane_s, budget_s):
+    """The forward oracle on one worker process per host core this process may run on (at most
+    16), each with its own planes of the workload (planes are independent; numpy's FFT is
+    single threaded).  The workers start together; throughput = planes / (last end - start)."""
+    import subprocess
+    cores = min(len(os.sched_getaffinity(0)), 16)
+    per = int(max(1, min(total_planes // cores, budget_s / max(per_plane_s, 1e-6))))
+    setup_s = 20.0 + 3.0 * per_plane_s           # imports, bank, planes, one warm-up plane
+    t_start = time.time() + setup_s
+    env = dict(os.environ, OMP_NUM_THREADS="1", OPENBLAS_NUM_THREADS="1", MKL_NUM_THREADS="1")
+    procs = [subprocess.Popen([sys.executable, os.path.abspath(__file__), "--oracle-worker",
+                               str(wl), str(i * per), str(per), repr(t_start)],
+                              stdout=subprocess.PIPE, stderr=subprocess.DEVNULL, text=True, env=env)
+             for i in range(cores)]
+    ends, late = [], 0
+    try:
+        for pr in procs:
+            outp, _ = pr.communicate(timeout=setup_s + 6.0 * per * per_plane_s + 60.0)
+            ready, t0, t1 = (float(v) for v in outp.split())
+            late += ready > t_start
+            ends.append(t1)
+    except Exception:
+        for pr in procs:
+            if pr.poll() is None:
+                pr.kill()
+        return None
+    dt = max(ends) - t_start
+    return {"value": cores * per / dt / channels, "unit": "images/s", "cores": cores,
+            "sample": "%d planes on each of %d worker processes, started together, %.1f s%s"
+                      % (per, cores, dt, " (%d workers were late)" % late if late else "")}
+
+
+def cpu_baseline(planes, dims, J, LQ, channels, budget_s=20.0, grad=None, wl=None):
+    """Time the oracle on as many planes of the workload as fit in about budget_s seconds:
+    one process on one core (numpy's FFT is single threaded) and, for the forward pass of the
+    1-D and 2-D cascades, a pool of processes on all host cores.  With `grad` (dL/dS for every
+    plane) the oracle's backward pass is timed instead of its forward pass."""
+    import oracle
+    pool_leg = grad is None and dims in (1, 2) and wl is not None
+    if pool_leg:
+        budget_s *= 0.4               # the rest goes to the all-cores leg
     if dims == 3:
         from oracle import harmonic3d
         bank = harmonic3d.bank_3d(planes.shape[-3:], J, LQ)
@@ -60,14 +129,26 @@ def cpu_baseline(planes, dims, J, LQ, channels, budget_s=20.0, grad=None):
     t0 = time.perf_counter()
     run(planes[:n])
     dt = time.perf_counter() - t0
-    return {"value": n / dt / channels, "unit": "images/s", "cores": 1, "kind": "oracle",
-            "sample": "%d of %d planes (%d-channel images), fp64 numpy %s, filter bank "
-                      "prebuilt, %.1f s" % (n, len(planes), channels,
-                                            "backward pass (forward recomputed inside)"
-                                            if grad is not None else "cascade", dt)}
+    single = {"value": n / dt / channels, "unit": "images/s", "cores": 1, "kind": "oracle",
+              "sample": "%d of %d planes (%d-channel images), fp64 numpy %s, filter bank "
+                        "prebuilt, %.1f s" % (n, len(planes), channels,
+                                              "backward pass (forward recomputed inside)"
+                                              if grad is not None else "cascade", dt)}
+    if not pool_leg:
+        return single
+    allc = cpu_all_cores(wl, len(planes), channels, dt / n, budget_s * 1.5)
+    if allc is None:
+        return single
+    return {"value": allc["value"], "unit": "images/s", "cores": allc["cores"], "kind": "oracle",
+            "sample": "fp64 numpy cascade, filter bank prebuilt, %d-channel images: %s"
+                      % (channels, allc["sample"]),
+            "single_core": single}
 
 
 def main():
+    if len(sys.argv) == 6 and sys.argv[1] == "--oracle-worker":
+        oracle_worker(int(sys.argv[2]), int(sys.argv[3]), int(sys.argv[4]), float(sys.argv[5]))
+        return
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
@@ -82,6 +163,9 @@ def main():
                     help="time the backward pass (gradient with respect to the input of a "
                          "seeded random dL/dS; recomputes the forward cascade inside) instead "
                          "of the forward transform")
+    ap.add_argument("--node-kernels", action="store_true",
+                    help="2-D 256x256 / 128x128 plans: walk the tree with one workgroup per node "
+                         "(SCAT_PLAN_NODE_KERNELS) instead of the default schedule")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (a kernel of known "
                          "traffic, to calibrate profiler byte counters)")
@@ -107,7 +191,7 @@ def main():
         sys.exit(1)
     torch.cuda.set_device(0)
     x = torch.from_numpy(x_host).cuda()
-    plan = scat.Scattering(cfg["shape"], cfg["J"], cfg["LQ"])
+    plan = scat.Scattering(cfg["shape"], cfg["J"], cfg["LQ"], node_kernels=args.node_kernels)
     out = torch.empty((P, plan.K) + plan.out_shape, dtype=torch.float32, device="cuda")
     g_host = None
     if args.backward:
@@ -139,17 +223,18 @@ def main():
 
     # timed region: K steps, the dominant kernel's launches bracketed by HIP events
     plan.timing_begin(dominant)
-    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    start.record()
-    for _ in range(args.steps):
+    marks[0].record()
+    for i in range(args.steps):
         step()
-    stop.record()
+        marks[i + 1].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     dom = plan.timing_end()[dominant]
-    ms_per_step = start.elapsed_time(stop) / args.steps
+    ms_per_step = marks[0].elapsed_time(marks[-1]) / args.steps
+    each = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
 
     # sanity: the output is finite and S0 of a zero-mean unit-variance field is small
     chk = (gin if args.backward else out)[:2].float().cpu().numpy()
@@ -158,7 +243,6 @@ def main():
     avg_ms = dom["ms"] / dom["launches"]
     bytes_per_launch = dom["alg_bytes"] / dom["launches"]
     flops_per_launch = dom["model_flops"] / dom["launches"]
-    achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9
     # HBM bytes per launch of every kernel from the committed rocprofv3 counter summary
     # (FETCH_SIZE and WRITE_SIZE runs of this same command, scaled by a plain copy)
     per_kernel = {}
@@ -171,36 +255,52 @@ def main():
                 if not line.startswith("#") and len(cols) == 5:
                     per_kernel[cols[0]] = float(cols[4])
     traffic = per_kernel.get(dominant)
-    # whole step: measured HBM bytes of all its launches over the measured step time
-    pipeline = None
+    measured_step_bytes = None
     if per_kernel and all(k in per_kernel for k in table):
-        step_bytes = sum(per_kernel[k] * table[k]["launches"] for k in table)
-        rate = step_bytes / (ms_per_step * 1e-3) / 1e9
-        pipeline = {"hbm_bytes_per_step": step_bytes, "achieved": rate, "unit": "GB/s",
-                    "frac": rate / HBM_PEAK_GBS,
-                    "alg_bytes_per_step": sum(v["alg_bytes"] for v in table.values())}
+        measured_step_bytes = sum(per_kernel[k] * table[k]["launches"] for k in table)
+
+    # ---- the dominant kernel against the roofline that binds it.  Its work: the model flops
+    # of the transforms and pointwise steps it performs (5 n log2 n per transform; the
+    # library's per-launch figure) and, as HBM bytes, what of the path's inputs, outputs and
+    # tables it touches; everything else it moves is intermediate traffic, not work.
     model_tflops = flops_per_launch / (avg_ms * 1e-3) / 1e12
-    # the roofline that bounds this kernel: the larger of the time its least traffic needs
-    # at the HBM peak and the time its model flops need at the fp32 vector peak
-    hbm_bound = bytes_per_launch / (HBM_PEAK_GBS * 1e9) >= flops_per_launch / (ALU_PEAK_TFLOPS * 1e12)
-    if hbm_bound:
-        roofline = {"bound": "hbm", "kernel": dominant, "achieved": achieved,
-                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS}
-    else:
-        roofline = {"bound": "alu", "kernel": dominant, "achieved": model_tflops,
-                    "peak": ALU_PEAK_TFLOPS, "unit": "TFLOP/s",
-                    "frac": model_tflops / ALU_PEAK_TFLOPS}
-    roofline.update({"traffic": traffic, "avg_launch_ms": avg_ms,
-                     "launches_timed": dom["launches"],
-                     "alg_bytes_per_launch": bytes_per_launch, "alg_gbs": achieved,
-                     "model_tflops": model_tflops,
-                     "share_of_step": dom["ms"] / args.steps / ms_per_step})
-    # whole step against the fp32 vector peak with the 5 n log2 n flop model
-    step_flops = sum(v["model_flops"] for v in table.values())
-    step_tflops = step_flops / (ms_per_step * 1e-3) / 1e12
-    pipeline_alu = {"model_flops_per_step": step_flops, "achieved": step_tflops,
-                    "unit": "TFLOP/s", "peak": ALU_PEAK_TFLOPS,
-                    "frac": step_tflops / ALU_PEAK_TFLOPS}
+    t_alu = flops_per_launch / (ALU_PEAK_TFLOPS * 1e12)
+    roofline = {"bound": "alu", "kernel": dominant, "achieved": model_tflops,
+                "peak": ALU_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": model_tflops / ALU_PEAK_TFLOPS,
+                "traffic": traffic, "avg_launch_ms": avg_ms, "launches_timed": dom["launches"],
+                "model_flops_per_launch": flops_per_launch,
+                "share_of_step": dom["ms"] / args.steps / ms_per_step,
+                # the kernel's own least I/O (intermediates included) over its time: how fast
+                # the pass moves data, NOT a fraction of any roofline of the path
+                "pass_io_bytes_per_launch": bytes_per_launch,
+                "pass_io_gbs": bytes_per_launch / (avg_ms * 1e-3) / 1e9}
+
+    # ---- the whole step: model flops and algorithmic bytes (input + output + tables) of the
+    # workload against the two peaks; the binding roofline is the one that needs more time
+    t_step = ms_per_step * 1e-3
+    if not args.backward and wl in MODEL_MFLOP_PER_PLANE:
+        step_flops = MODEL_MFLOP_PER_PLANE[wl] * 1e6 * P
+        alg_bytes = float(ALG_BYTES_PER_PLANE[wl]) * P
+    else:  # no tabulated figure: the library's own sums (flops) and plain input + output
+        step_flops = sum(v["model_flops"] for v in table.values())
+        alg_bytes = float(x.numel() * 4 + out.numel() * 4) * (2 if args.backward else 1)
+    t_alu_step = step_flops / (ALU_PEAK_TFLOPS * 1e12)
+    t_hbm_step = alg_bytes / (HBM_PEAK_GBS * 1e9)
+    step_info = {
+        "model_flops": step_flops, "model_tflops": step_flops / t_step / 1e12,
+        "frac_alu": t_alu_step / t_step,
+        "alg_bytes": alg_bytes, "alg_gbs": alg_bytes / t_step / 1e9,
+        "hbm_alg_frac": t_hbm_step / t_step,
+        "binding": "alu" if t_alu_step >= t_hbm_step else "hbm",
+        "frac_binding": max(t_alu_step, t_hbm_step) / t_step,
+        "measured_hbm_bytes": measured_step_bytes,
+        "measured_hbm_gbs": measured_step_bytes / t_step / 1e9 if measured_step_bytes else None,
+        "measured_hbm_frac": (measured_step_bytes / t_step / 1e9 / HBM_PEAK_GBS
+                              if measured_step_bytes else None),
+        "traffic_amplification": measured_step_bytes / alg_bytes if measured_step_bytes else None,
+        "library_model_flops": sum(v["model_flops"] for v in table.values()),
+        "ms_median": each[len(each) // 2], "ms_min": each[0], "ms_max": each[-1],
+    }
 
     images_per_s = (P / C) / (ms_per_step * 1e-3)
     result = {
@@ -213,18 +313,18 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": cfg["name"], "planes_per_step": P, "channels": C,
                    "J": cfg["J"], "LQ": cfg["LQ"], "shape": list(cfg["shape"]), "max_order": 2,
-                   "coefficients": plan.K},
+                   "coefficients": plan.K,
+                   "schedule": "node_kernels" if args.node_kernels else "default"},
         "planes_per_s": P / (ms_per_step * 1e-3),
         "wall_ms_per_step": wall / args.steps * 1e3,
         "roofline": roofline,
-        "pipeline_hbm": pipeline,
-        "pipeline_alu": pipeline_alu,
+        "step": step_info,
         "kernel_table_ms": {k: round(v["ms"], 4) for k, v in table.items()},
     }
     plan.close()
     if args.cpu_seconds > 0:
         result["cpu_baseline"] = cpu_baseline(x_host, cfg["dims"], cfg["J"], cfg["LQ"], C,
-                                              args.cpu_seconds, grad=g_host)
+                                              args.cpu_seconds, grad=g_host, wl=wl)
     print(json.dumps(result))
 
 
