@@ -121,12 +121,19 @@ scat_status scat_plan_create_padded_host(scat_plan **out_plan, int dims, const i
  * octave j the grid is subsampled by 2^max(j-o, 0) and the output by 2^max(J-o, 0), so the
  * output has sides shape >> max(J-o, 0).  With o >= J nothing is subsampled and the output,
  * read at the samples 2^J k, is the section-2 definition itself.  flags: bitwise OR of
- * SCAT_PLAN_PADDED (signals of any size, see scat_plan_create_padded) and
- * SCAT_PLAN_HOST_ONLY (no GPU, see scat_plan_create_host).  scat_backward limits the size of
+ * SCAT_PLAN_PADDED (signals of any size, see scat_plan_create_padded),
+ * SCAT_PLAN_HOST_ONLY (no GPU, see scat_plan_create_host) and SCAT_PLAN_NODE_KERNELS (below).  scat_backward limits the size of
  * the output grid in 2-D (see there), which limits o.
  */
 #define SCAT_PLAN_PADDED 1
 #define SCAT_PLAN_HOST_ONLY 2
+/* 2-D plans of 256 x 256 at J = 3 or 128 x 128 at J = 2: scat_forward walks the tree with
+ * one workgroup per node (the "Implementation" paragraph's depth-first walk: a node's inverse
+ * transform, modulus, lowpass and, for parents, spectrum never leave the compute unit; only
+ * the spectra of the input and of first-order moduli with children are kept in scratch)
+ * instead of the row and column passes over the whole batch.  Same results to rounding.
+ * Ignored by other shapes and by scat_backward. */
+#define SCAT_PLAN_NODE_KERNELS 4
 scat_status scat_plan_create_ex(scat_plan **out_plan, int dims, const int *shape, int J, int LQ,
                                 int max_order, int oversampling, int flags);
 

@@ -109,6 +109,12 @@ struct scat_plan {
   std::vector<size_t> phi_off;                     // 1-D, per res
   bool fused = false;  // 2-D: the fused row pass can serve every level of this plan
   bool tree = false;   // 2-D: planes small enough for the whole-tree-in-LDS kernel
+  // 2-D: every node of the tree is computed by one workgroup (scat_node.hip): forward calls
+  // keep only the spectra of x and of the first-order moduli with children in scratch
+  bool node = false;
+  std::map<int, size_t> poly_psi_off;          // j2 -> [L][4][N/2][N/2] sign-folded wavelets
+  std::vector<size_t> taps_r_off, taps_c_off;  // per res: spatial lowpass taps [2R+1]
+  size_t ptaps_r_off = 0, ptaps_c_off = 0;     // polyphase taps of resolution 0: [2][2R+1]
   // 3-D solid harmonic plans (host.dims == 3; host carries J, LQ = L, max_order, K only)
   scat::HostPlan3D h3;
   std::vector<size_t> psi3_off;  // per (j, l): its 2l+1 tables, contiguous
@@ -220,6 +226,20 @@ Layout make_layout(const scat_plan &p, long batch, size_t budget = 0) {
   if (h.dims == 2 && p.tree) {
     // xh: spectra of x; everything else stays in LDS
     L.xh = n * c8;
+  } else if (h.dims == 2 && p.node) {
+    // xh: spectrum of x; u: half spectra of one octave's first-order moduli (the first
+    // octave of a 256 x 256 image as four polyphase components each); w: that octave's four
+    // partial lowpass outputs per node
+    const size_t l = h.LQ;
+    L.xh = n * c8;
+    size_t most = 0;
+    for (int j = 0; second && j + 1 < h.J; ++j) {
+      const size_t M1 = static_cast<size_t>(p.n1) >> j;
+      const size_t per = M1 > 128 ? 4 * (M1 / 4 + 1) * (M1 / 2) : (M1 / 2 + 1) * M1;
+      most = std::max(most, l * per);
+    }
+    L.u = most * c8;
+    L.w = p.n1 > 128 ? l * 4 * 32 * 32 * sizeof(float) : 0;
   } else if (h.dims == 2 && p.fused) {
     // xh: column spectra of x; t: first-order row-pass outputs of all octaves at once
     // (sum over j of L*n/4^j); u: column spectra of one octave's moduli; v: second-order
@@ -356,6 +376,74 @@ scat_status upload(scat_plan *p) {
       }
     }
   }
+  if (p->node) {
+    const int N = p->n1;
+    const double two_pi_ = 6.283185307179586476925286766559;
+    // spatial taps of a lowpass factor: g[d] = (1/len) sum_k phi[k] cos(2 pi k d / len)
+    auto spatial = [&](const std::vector<double> &ph) {
+      const size_t len = ph.size();
+      std::vector<double> g(len);
+      for (size_t d = 0; d < len; ++d) {
+        double acc = 0.0;
+        for (size_t k = 0; k < len; ++k) acc += ph[k] * std::cos(two_pi_ * static_cast<double>((k * d) % len) / len);
+        g[d] = acc / static_cast<double>(len);
+      }
+      return g;
+    };
+    auto push_taps = [&](const std::vector<double> &g, int R, int stride, int shift) {
+      // taps[d + R] = g[(stride d - shift) mod len], |d| <= R
+      const long len = static_cast<long>(g.size());
+      const size_t off = pool.size();
+      for (int d = -R; d <= R; ++d) {
+        long i = (static_cast<long>(stride) * d - shift) % len;
+        if (i < 0) i += len;
+        pool.push_back(static_cast<float>(g[i]));
+      }
+      return off;
+    };
+    p->taps_r_off.assign(h.J, 0);
+    p->taps_c_off.assign(h.J, 0);
+    for (int r = 0; r < h.J; ++r) {
+      const int len = N >> r;
+      const std::vector<double> gr = spatial(h.phi_rows[r]), gc = spatial(h.phi_cols[r]);
+      if (len > 128) {
+        // components of len/2 points: taps phi[2 d - p], p = 0, 1
+        const int R = 4 * (len / 2 / 32);
+        p->ptaps_r_off = push_taps(gr, R, 2, 0);
+        push_taps(gr, R, 2, 1);
+        p->ptaps_c_off = push_taps(gc, R, 2, 0);
+        push_taps(gc, R, 2, 1);
+      } else {
+        const int R = 4 * (len / 32);
+        p->taps_r_off[r] = push_taps(gr, R, 1, 0);
+        p->taps_c_off[r] = push_taps(gc, R, 1, 0);
+      }
+    }
+    if (N > 128 && h.max_order == 2) {
+      // children of the polyphase octave: R_q[k] = sum_a (-1)^(a.q) psi[k + M a], M = N/2
+      const int M = N / 2;
+      const double scale = 1.0 / (static_cast<double>(N) * N);
+      for (int j2 = 1; j2 < h.J; ++j2) {
+        p->poly_psi_off[j2] = pool.size();
+        for (int l = 0; l < h.LQ; ++l) {
+          const FilterTable &t = *h.find(1, j2 * h.LQ + l, 0);
+          for (int q = 0; q < 4; ++q) {
+            const int qr = q >> 1, qc = q & 1;
+            for (int kr = 0; kr < M; ++kr)
+              for (int kc = 0; kc < M; ++kc) {
+                double acc = 0.0;
+                for (int ar = 0; ar < 2; ++ar)
+                  for (int ac = 0; ac < 2; ++ac) {
+                    const double v = t.v[static_cast<size_t>(kr + M * ar) * N + kc + M * ac];
+                    acc += ((ar * qr + ac * qc) & 1) ? -v : v;
+                  }
+                pool.push_back(static_cast<float>(acc * scale));
+              }
+          }
+        }
+      }
+    }
+  }
   // twiddles exp(-2 pi i j / tw_n), evaluated in double
   p->tw_n = h.dims == 2 ? (p->n1 > p->n2 ? p->n1 : p->n2) : p->n1 * p->n2;
   std::vector<float2> tw(p->tw_n);
@@ -439,7 +527,8 @@ scat_status create_3d(scat_plan **out_plan, const int *user_shape, int J, int L,
 }
 
 scat_status create_common(scat_plan **out_plan, int dims, const int *user_shape, int J, int LQ,
-                          int max_order, bool device, bool padded = false, int oversampling = 0) {
+                          int max_order, bool device, bool padded = false, int oversampling = 0,
+                          bool node_kernels = false) {
   if (out_plan == nullptr) return SCAT_ERR_NULL;
   *out_plan = nullptr;
   if (user_shape == nullptr) return SCAT_ERR_NULL;
@@ -493,6 +582,10 @@ scat_status create_common(scat_plan **out_plan, int dims, const int *user_shape,
         p->fused = false;
     }
   p->tree = dims == 2 && oversampling == 0 && scat::tree_supported(p->n1, p->n2, J);
+  // whole-node kernels: square grids whose octaves are 128 or 64 points a side, or 256 as four
+  // polyphase components, with the 32 x 32 output grid their lowpass stage is laid out for
+  p->node = node_kernels && dims == 2 && oversampling == 0 && p->n1 == p->n2 &&
+            ((p->n1 == 256 && J == 3) || (p->n1 == 128 && J == 2));
   if (padded) {
     p->padded = true;
     for (int d = 0; d < dims; ++d) {
@@ -910,6 +1003,87 @@ scat_status forward_2d_fused(scat_plan *p, const float *in, float *out, long p0,
       if (tape != nullptr) continue;
       SCAT_TRY(col_and_lowpass(1, t2[j2], pc * L * L, M2r, M2c, r2, nullptr,
                                ChanMap{L * L, L, octs * L, s2_base + (j2 - j1 - 1) * L}));
+    }
+    s2_base += L * L * octs;
+  }
+  return SCAT_OK;
+}
+
+// ---- 2-D schedule with one workgroup per node (scat_node.hip): the spectrum of x, then per
+// first-order octave one launch for its L nodes (four polyphase components each when the
+// octave has 256 points a side) and one launch per child octave; a node's inverse transform,
+// modulus, lowpass and (for parents) forward transform all stay in the LDS of one workgroup.
+scat_status forward_2d_node(scat_plan *p, const float *in, float *out, long p0, long pc,
+                            const Layout &lay, hipStream_t st) {
+  const scat::HostPlan &h = p->host;
+  const int J = h.J, L = h.LQ, K = h.K;
+  const int N = p->n1;
+  const int m = N >> J;
+  const size_t n = static_cast<size_t>(N) * N;
+  char *base = static_cast<char *>(p->work);
+  float2 *XH = reinterpret_cast<float2 *>(base);
+  float2 *U = reinterpret_cast<float2 *>(base + lay.xh * pc);
+  float *PART = reinterpret_cast<float *>(base + (lay.xh + lay.u) * pc);
+  const float *tab = p->d_tables;
+  const float2 *tw = p->d_tw;
+  const int tw_n = p->tw_n;
+  const float *x = in + static_cast<size_t>(p0) * n;
+  float *o = out + static_cast<size_t>(p0) * K * m * m;
+  // x -> column spectra (rows 0 .. N/2) and S0, then the row transform: the spectrum of x
+  SCAT_TRY(scat::launch_col_node(0, x, pc, N, m, XH, true, tab + p->phi_rows_off[0],
+                                 tab + p->phi_cols_off[0], o, ChanMap{1, 1, 0, 0}, K, tw, tw_n, st));
+  SCAT_TRY(scat::launch_row_fwd(XH, pc * (N / 2 + 1), N, tw, tw_n, st));
+  int s2_base = 1 + J * L;
+  for (int j1 = 0; j1 < J; ++j1) {
+    const int M1 = N >> j1;
+    const bool kids = h.max_order == 2 && j1 < J - 1;
+    const bool poly = M1 > 128;
+    scat::NodeLaunch a{};
+    a.M = poly ? M1 / 2 : M1;
+    a.A = N / a.M;
+    a.P = 1;
+    a.poly = poly;
+    a.src = XH;
+    a.filt = tab + p->psi1_off[j1];
+    a.taps_r = tab + (poly ? p->ptaps_r_off : p->taps_r_off[j1]);
+    a.taps_c = tab + (poly ? p->ptaps_c_off : p->taps_c_off[j1]);
+    a.uout = kids ? U : nullptr;
+    a.out = poly ? PART : o;
+    a.NS = pc;
+    a.F = L;
+    a.G = 1;
+    a.chan_base = 1 + j1 * L;
+    a.chan_src = 0;
+    a.chan_f = 1;
+    a.K = K;
+    a.tw = tw;
+    a.tw_n = tw_n;
+    SCAT_TRY(scat::launch_node(a, st));
+    if (poly) SCAT_TRY(scat::launch_sum4(PART, o, pc * L, L, K, 1 + j1 * L, st));
+    if (!kids) continue;
+    const int octs = J - 1 - j1;
+    for (int j2 = j1 + 1; j2 < J; ++j2) {
+      scat::NodeLaunch c{};
+      c.M = N >> j2;
+      c.P = poly ? 4 : 1;
+      c.A = (poly ? M1 / 2 : M1) / c.M;
+      c.poly = false;
+      c.src = U;
+      c.filt = tab + (poly ? p->poly_psi_off.at(j2) : p->psi2_off.at({j1, j2}));
+      c.taps_r = tab + p->taps_r_off[j2];
+      c.taps_c = tab + p->taps_c_off[j2];
+      c.uout = nullptr;
+      c.out = o;
+      c.NS = pc * L;
+      c.F = L;
+      c.G = L;
+      c.chan_base = s2_base + (j2 - j1 - 1) * L;
+      c.chan_src = octs * L;
+      c.chan_f = 1;
+      c.K = K;
+      c.tw = tw;
+      c.tw_n = tw_n;
+      SCAT_TRY(scat::launch_node(c, st));
     }
     s2_base += L * L * octs;
   }
@@ -1820,6 +1994,7 @@ scat_status forward_chunks(scat_plan *plan, const float *in, float *out, long ba
                                                   : forward_3d(plan, cin, cout, cp0, pc, st))
                     : h.dims == 1 ? forward_1d(plan, cin, cout, cp0, pc, lay, st)
                     : plan->tree  ? forward_2d_tree(plan, cin, cout, cp0, pc, lay, st)
+                    : plan->node  ? forward_2d_node(plan, cin, cout, cp0, pc, lay, st)
                     : plan->fused ? forward_2d_fused(plan, cin, cout, cp0, pc, lay, st)
                                   : forward_2d(plan, cin, cout, cp0, pc, lay, st);
     if (s != SCAT_OK) return s;
@@ -1864,12 +2039,13 @@ scat_status scat_plan_create_padded_host(scat_plan **out_plan, int dims, const i
 
 scat_status scat_plan_create_ex(scat_plan **out_plan, int dims, const int *shape, int J, int LQ,
                                 int max_order, int oversampling, int flags) {
-  if (flags & ~3) {
+  if (flags & ~7) {
     if (out_plan != nullptr) *out_plan = nullptr;
     return SCAT_ERR_ARG;
   }
   return create_common(out_plan, dims, shape, J, LQ, max_order, (flags & SCAT_PLAN_HOST_ONLY) == 0,
-                       (flags & SCAT_PLAN_PADDED) != 0, oversampling);
+                       (flags & SCAT_PLAN_PADDED) != 0, oversampling,
+                       (flags & SCAT_PLAN_NODE_KERNELS) != 0);
 }
 
 scat_status scat_plan_grid_shape(const scat_plan *plan, int *shape_out) {

@@ -184,6 +184,36 @@ hipError_t launch_tree32(const float2 *xh, long planes, int L, int max_order, co
                          const float *taps0, const float *taps1, float *out, int K,
                          hipStream_t st);
 
+// Whole nodes of the 2-D tree in one kernel each (scat_node.hip): spectrum of the node from
+// its parent's stored half spectra (P sources of S x S, S = M * A, with A x A aliases folded),
+// inverse transform, modulus, lowpass to the 32 x 32 output grid by a separable FIR filter
+// (taps: 2 R + 1 values, R = 4 M / 32; polyphase nodes: two sets, for p = 0 and p = 1), and
+// optionally the half spectrum of the modulus for the node's children.
+//   src    [NS][P][S/2+1][S]; filt [F][P][S][S]; items per source: F (poly: 4 F, the four
+//          polyphase components of each filter's node, component index 2 p_r + p_c fastest)
+//   uout   null or [NS * items][M/2+1][M] (poly: times w^(p.k), w = exp(-2 pi i / 2M))
+//   out    [planes][K][32][32] with channel = chan_base + (source % G) * chan_src +
+//          filter * chan_f and plane = source / G; poly: parts [NS * items][32][32]
+struct NodeLaunch {
+  int M, A, P;
+  bool poly;
+  const float2 *src;
+  const float *filt;
+  const float *taps_r, *taps_c;
+  float2 *uout;
+  float *out;
+  long NS;
+  int F, G;
+  int chan_base, chan_src, chan_f, K;
+  const float2 *tw;
+  int tw_n;
+};
+bool node_supported(int M, int A, int P, bool poly);
+hipError_t launch_node(const NodeLaunch &n, hipStream_t st);
+// out[plane][chan_base + g][32][32] = sum of the four parts of node plane * G + g
+hipError_t launch_sum4(const float *part, float *out, long nodes, int G, int K, int chan_base,
+                       hipStream_t st);
+
 // Modulus backward step of whole nodes in one pass (k_node_modback): data [nodes][Mr][Mc]
 // gradient spectra in, gradient spectra of the taped y [nodes][Mr][Mc] out, in place.  The
 // _low form starts from the node's adjoint lowpass instead (arguments as

@@ -1,0 +1,315 @@
+// Depth-first 2-D cascade: one workgroup computes one whole node of the scattering tree in LDS.
+//
+// A node is |x (*) psi| (or ||x (*) psi_1| (*) psi_2|) on its own subsampled grid of M x M
+// points, M = 64 or 128 (paper, section 2 "Implementation": convolutions as Fourier products,
+// every filtered signal downsampled, the tree walked branch by branch so that intermediates
+// are dropped as soon as the children are done).  The workgroup
+//   1. forms the node's spectrum  Z[k] = sum over sources q and aliases a of
+//      src_q[k + M a] * filt_q[k + M a]   (filter product + periodisation = subsampling),
+//      reading its parent's spectrum through the caches,
+//   2. inverse 2-D transform in registers + LDS, 3. modulus,
+//   4. lowpass phi_J and subsampling to the 32 x 32 output grid as a separable FIR filter with
+//      the spatial taps of phi (5 sigma each side), straight to the output coefficients,
+//   5. (nodes with children only) forward 2-D transform of the modulus, stored as the
+//      non-redundant half spectrum for the children.
+// Only the input's spectrum, the spectra of first-order moduli that have children, and the
+// output coefficients ever go to memory.
+//
+// Nodes of 2M x 2M points (the first octave of a 256 x 256 image) do not fit the LDS of a
+// compute unit; they are split into their four polyphase components u_p[m] = u[2m + p],
+// p in {0,1}^2, each an M x M node of its own (POLY):
+//   y_p = IFFT_M( conj(w^(p.k)) sum_a (-1)^(a.p) Y[k + M a] ),  w = exp(-2 pi i / 2M),
+// and since U[k + M a] = sum_p (-1)^(a.p) w^(p.k) U_p[k], the children read the four stored
+// spectra w^(p.k) U_p[k] as four sources with the sign-folded filter tables
+// R_p[k] = sum_a (-1)^(a.p) psi[k + M a]  (P = 4).  Each component adds its part of the
+// lowpassed output (taps phi[2d - p]); k_sum4 adds the four parts.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <string>
+
+#include "fft_regs.hpp"
+#include "slab_fft.hpp"
+#include "scat_kernels.hpp"
+
+namespace scat {
+
+namespace {
+
+constexpr int kOut = 32;  // side of the output grid the FIR stage is laid out for
+
+double fft2_flops(double n) { return n > 1 ? 10.0 * n * n * std::log2(n) : 0.0; }
+
+struct NodeArgs {
+  const float2 *src;    // [NS][P][S/2+1][S] half spectra, S = M * A
+  const float *filt;    // [F][P][S][S] real tables (carry the 1/N^2 of the inverse transforms)
+  const float *taps_r;  // lowpass taps along a column (row index varies): [2R+1], POLY: [2][2R+1]
+  const float *taps_c;  // along a row
+  float2 *uout;         // null, or [(NS*I)][M/2+1][M]: half spectrum of every node's modulus
+  float *out;           // [planes][K][32][32], POLY: the parts [(NS*I)][32][32]
+  long NS;              // sources
+  int F;                // filters per source; items per source I = F (POLY: 4 F, component fastest)
+  int G;                // sources per plane
+  int chan_base, chan_src, chan_f;  // channel = base + (source % G) * chan_src + filter * chan_f
+  int K;
+  const float2 *tw;     // exp(-2 pi i j / tw_n)
+  int tw_n;
+};
+
+// Workgroup b serves source 8 (b / 8 / I) + b % 8 and item (b / 8) % I: workgroups are dealt
+// to the eight XCDs in turn, so all items of one source run on one XCD, one after the other,
+// and its L2 holds the source's spectrum for them.
+template <int M, int A, int P, bool POLY>
+__global__ __launch_bounds__(M * M / 16) void k_node(NodeArgs a) {
+  using SL = Slab<M, M>;
+  constexpr int NT = M * M / 16, T = M / 16, S = M * A, RS = SL::RS;
+  constexpr int DEC = M / kOut, R = 4 * DEC, NTAP = 2 * R + 1;
+  static_assert(P == 1 || P == 4, "sources");
+  static_assert(!POLY || P == 1, "a polyphase node reads a plain spectrum");
+  extern __shared__ float2 lds[];
+  float2 *area = lds;
+  float2 *wtab = lds + M * RS;
+  const int tid = threadIdx.x;
+  const int I = a.F * (POLY ? 4 : 1);
+  const long bq = blockIdx.x >> 3;
+  const long s = (blockIdx.x & 7) + 8 * (bq / I);
+  const int item = static_cast<int>(bq % I);
+  if (s >= a.NS) return;
+  const int f = POLY ? item >> 2 : item;
+  const int pr = POLY ? (item >> 1) & 1 : 0, pc = POLY ? item & 1 : 0;
+  SL::fill_twiddles(wtab, a.tw, a.tw_n);
+  const int tw_step = a.tw_n / (2 * M);  // POLY only: table step of w = exp(-2 pi i / 2M)
+
+  // ---- 1. spectrum of the node: thread = one column, rows rg + T i (coalesced reads)
+  {
+    const float2 *src = a.src + static_cast<size_t>(s) * P * (S / 2 + 1) * S;
+    const float *filt = a.filt + static_cast<size_t>(f) * P * S * S;
+    const int col = tid % M, rg = tid / M;
+#pragma unroll 2
+    for (int i = 0; i < 16; ++i) {
+      const int kr0 = rg + T * i;
+      float2 acc = make_float2(0.f, 0.f);
+#pragma unroll
+      for (int q = 0; q < P; ++q) {
+        const float2 *sq = src + static_cast<size_t>(q) * (S / 2 + 1) * S;
+        const float *fq = filt + static_cast<size_t>(q) * S * S;
+#pragma unroll
+        for (int ar = 0; ar < A; ++ar) {
+          const int kr = kr0 + M * ar;
+          // rows above S/2 are not stored: U[kr][kc] = conj(U[S - kr][-kc]); the stored
+          // spectra of polyphase components carry w^(p.k), which adds the sign
+          // (-1)^(q_r) (-1)^(q_c [kc != 0]) to the mirrored value
+          const bool mir = kr > S / 2;  // the same for every lane of a wave
+          const int krs = mir ? S - kr : kr;
+#pragma unroll
+          for (int ac = 0; ac < A; ++ac) {
+            const int kc = col + M * ac;
+            const int kcs = mir ? (S - kc) & (S - 1) : kc;
+            const float2 v = sq[krs * S + kcs];
+            float fv = fq[kr * S + kc];
+            if (POLY && ((ar * pr + ac * pc) & 1)) fv = -fv;
+            float fx = fv, fy = fv;
+            if (mir) {
+              if (P == 4 && (((q >> 1) & 1) ^ ((q & 1) & (kc != 0 ? 1 : 0)))) fx = -fx;
+              fy = -fx;
+            }
+            acc.x = fmaf(v.x, fx, acc.x);
+            acc.y = fmaf(v.y, fy, acc.y);
+          }
+        }
+      }
+      if (POLY) {
+        const float2 w = a.tw[((pr * kr0 + pc * col) * tw_step) & (a.tw_n - 1)];
+        acc = make_float2(acc.x * w.x + acc.y * w.y, acc.y * w.x - acc.x * w.y);  // * conj(w)
+      }
+      area[kr0 * RS + col] = acc;
+    }
+  }
+  __syncthreads();
+
+  // ---- 2. inverse transform: row layout in, column layout (rows t1 + T i of column c) out
+  const int r = tid / T, t = tid % T;
+  const int c = tid % M, t1 = tid / M;
+  float2 v[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) v[i] = area[r * RS + t + T * i];
+  __syncthreads();
+  SL::template transform_tab<true>(v, area, r, t, c, t1, wtab);
+
+  // ---- 3. modulus
+  float u[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) u[i] = __builtin_amdgcn_sqrtf(v[i].x * v[i].x + v[i].y * v[i].y);
+
+  // ---- 4. lowpass + subsampling by DEC: rows first (H: along a row), then columns (V)
+  constexpr int US = M + 1, HS = kOut + 1;
+  float *ub = reinterpret_cast<float *>(area);  // [M][US]
+  float *hb = ub + M * US;                      // [M][HS]
+#pragma unroll
+  for (int i = 0; i < 16; ++i) ub[(t1 + T * i) * US + c] = u[i];
+  __syncthreads();
+  {
+    constexpr int OPT = kOut * M / NT;  // outputs per thread, adjacent columns
+    constexpr int NIN = DEC * (OPT - 1) + NTAP;
+    const int rr = tid % M, mg = tid / M;
+    const float *tc = a.taps_c + (POLY ? pc * NTAP : 0);
+    float acc[OPT];
+#pragma unroll
+    for (int j = 0; j < OPT; ++j) acc[j] = 0.f;
+    const int e0 = DEC * OPT * mg - R;
+#pragma unroll
+    for (int e = 0; e < NIN; ++e) {
+      const float val = ub[rr * US + ((e0 + e) & (M - 1))];
+#pragma unroll
+      for (int j = 0; j < OPT; ++j) {
+        const int ti = DEC * j + 2 * R - e;  // tap index d + R of input column DEC m - d
+        if (ti >= 0 && ti <= 2 * R) acc[j] = fmaf(tc[ti], val, acc[j]);
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < OPT; ++j) hb[rr * HS + OPT * mg + j] = acc[j];
+  }
+  __syncthreads();
+  {
+    constexpr int OPV = kOut * kOut / NT;  // outputs per thread, adjacent rows
+    constexpr int NIN = DEC * (OPV - 1) + NTAP;
+    const int mc = tid % kOut, ng = tid / kOut;
+    const float *tr = a.taps_r + (POLY ? pr * NTAP : 0);
+    float acc[OPV];
+#pragma unroll
+    for (int j = 0; j < OPV; ++j) acc[j] = 0.f;
+    const int e0 = DEC * OPV * ng - R;
+#pragma unroll
+    for (int e = 0; e < NIN; ++e) {
+      const float val = hb[((e0 + e) & (M - 1)) * HS + mc];
+#pragma unroll
+      for (int j = 0; j < OPV; ++j) {
+        const int ti = DEC * j + 2 * R - e;
+        if (ti >= 0 && ti <= 2 * R) acc[j] = fmaf(tr[ti], val, acc[j]);
+      }
+    }
+    float *op;
+    if (POLY) {
+      op = a.out + (static_cast<size_t>(s) * I + item) * kOut * kOut;
+    } else {
+      const long plane = s / a.G;
+      const int g = static_cast<int>(s - plane * a.G);
+      op = a.out + (static_cast<size_t>(plane) * a.K + a.chan_base + g * a.chan_src + f * a.chan_f) *
+                       kOut * kOut;
+    }
+#pragma unroll
+    for (int j = 0; j < OPV; ++j) op[(OPV * ng + j) * kOut + mc] = acc[j];
+  }
+  if (a.uout == nullptr) return;
+
+  // ---- 5. spectrum of the modulus for the children (rows 0 .. M/2)
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 16; ++i) v[i] = make_float2(u[i], 0.f);
+  SL::template transform_back_tab<false>(v, area, r, t, c, t1, wtab);
+  if (r > M / 2) return;
+  float2 *up = a.uout + ((static_cast<size_t>(s) * I + item) * (M / 2 + 1) + r) * M + t;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    float2 val = v[i];
+    if (POLY) val = c_mul(val, a.tw[((pr * r + pc * (t + T * i)) * tw_step) & (a.tw_n - 1)]);
+    up[T * i] = val;
+  }
+}
+
+// out[plane][chan_base + g][.] = sum of the four parts of node (plane, g)
+__global__ __launch_bounds__(256) void k_sum4(const float *__restrict__ part, float *__restrict__ out,
+                                               long nodes, int G, int K, int chan_base) {
+  const long idx = static_cast<long>(blockIdx.x) * 256 + threadIdx.x;
+  constexpr int PL = kOut * kOut;
+  if (idx >= nodes * PL) return;
+  const long node = idx / PL;
+  const int e = static_cast<int>(idx - node * PL);
+  const float *p = part + node * 4 * PL + e;
+  const long plane = node / G;
+  const int g = static_cast<int>(node - plane * G);
+  out[(plane * K + chan_base + g) * PL + e] = (p[0] + p[PL]) + (p[2 * PL] + p[3 * PL]);
+}
+
+template <int M, int A, int P, bool POLY>
+hipError_t launch_node_t(const NodeArgs &a, hipStream_t st) {
+  using SL = Slab<M, M>;
+  constexpr int S = M * A;
+  const int I = a.F * (POLY ? 4 : 1);
+  const long blocks = 8 * ((a.NS + 7) / 8) * I;
+  if (a.NS <= 0 || blocks > 0x7fffffffL || a.tw_n % (POLY ? 2 * M : M) != 0) return hipErrorInvalidValue;
+  const size_t lds = SL::lds_bytes + SL::tab_elems * sizeof(float2);
+  const std::string name = "k_node<" + std::to_string(M) + ", " + std::to_string(A) + ", " +
+                           std::to_string(P) + (POLY ? ", true>" : ", false>");
+  const double items = static_cast<double>(a.NS) * I;
+  const double pts = static_cast<double>(M) * M;
+  LaunchScope obs(name.c_str(),
+                  static_cast<double>(a.NS) * P * (S / 2 + 1) * S * 8 +
+                      static_cast<double>(a.F) * P * S * S * 4 + items * kOut * kOut * 4 +
+                      (a.uout ? items * (M / 2 + 1) * M * 8 : 0),
+                  items * ((a.uout ? 2 : 1) * fft2_flops(M) + fft2_flops(kOut) +
+                           pts * (4.0 * P * A * A + 4.0 + 2.0) + fft2_flops(M) * (a.uout ? 0 : 1)),
+                  st);
+  if (lds > 65536) {
+    static unsigned long long lds_ok = 0;
+    hipError_t e = allow_large_lds(reinterpret_cast<const void *>(k_node<M, A, P, POLY>), lds_ok);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL((k_node<M, A, P, POLY>), dim3(static_cast<unsigned>(blocks)), dim3(M * M / 16), lds,
+                     st, a);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool node_supported(int M, int A, int P, bool poly) {
+  if (poly) return M == 128 && A == 2 && P == 1;
+  if (M == 128) return (A == 1 && (P == 1 || P == 4)) || (A == 2 && P == 1);
+  if (M == 64) return (A == 2 && (P == 1 || P == 4)) || (A == 4 && P == 1);
+  return false;
+}
+
+hipError_t launch_node(const NodeLaunch &n, hipStream_t st) {
+  if (!node_supported(n.M, n.A, n.P, n.poly) || n.G < 1 || n.F < 1) return hipErrorInvalidValue;
+  NodeArgs a;
+  a.src = n.src;
+  a.filt = n.filt;
+  a.taps_r = n.taps_r;
+  a.taps_c = n.taps_c;
+  a.uout = n.uout;
+  a.out = n.out;
+  a.NS = n.NS;
+  a.F = n.F;
+  a.G = n.G;
+  a.chan_base = n.chan_base;
+  a.chan_src = n.chan_src;
+  a.chan_f = n.chan_f;
+  a.K = n.K;
+  a.tw = n.tw;
+  a.tw_n = n.tw_n;
+#define SCAT_NODE(M_, A_, P_, POLY_) \
+  if (n.M == M_ && n.A == A_ && n.P == P_ && n.poly == POLY_) return launch_node_t<M_, A_, P_, POLY_>(a, st)
+  SCAT_NODE(128, 2, 1, true);
+  SCAT_NODE(128, 2, 1, false);
+  SCAT_NODE(128, 1, 1, false);
+  SCAT_NODE(128, 1, 4, false);
+  SCAT_NODE(64, 2, 4, false);
+  SCAT_NODE(64, 2, 1, false);
+  SCAT_NODE(64, 4, 1, false);
+#undef SCAT_NODE
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_sum4(const float *part, float *out, long nodes, int G, int K, int chan_base,
+                       hipStream_t st) {
+  if (nodes <= 0) return hipSuccess;
+  const long total = nodes * kOut * kOut;
+  const long blocks = (total + 255) / 256;
+  if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
+  LaunchScope obs("k_sum4", static_cast<double>(total) * 20.0, static_cast<double>(total) * 3.0, st);
+  hipLaunchKernelGGL(k_sum4, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st, part, out, nodes, G, K,
+                     chan_base);
+  return hipGetLastError();
+}
+
+}  // namespace scat
