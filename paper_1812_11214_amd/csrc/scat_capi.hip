@@ -115,6 +115,10 @@ struct scat_plan {
   std::map<int, size_t> poly_psi_off;          // j2 -> [L][4][N/2][N/2] sign-folded wavelets
   std::vector<size_t> taps_r_off, taps_c_off;  // per res: spatial lowpass taps [2R+1]
   size_t ptaps_r_off = 0, ptaps_c_off = 0;     // polyphase taps of resolution 0: [2][2R+1]
+  // per wavelet table: which (N >> j2) x (N >> j2) blocks of it are not negligible (bit
+  // a_r * A + a_c); mask_off[{res, j2}] -> L words in d_masks
+  unsigned *d_masks = nullptr;
+  std::map<std::pair<int, int>, size_t> mask_off;
   // 3-D solid harmonic plans (host.dims == 3; host carries J, LQ = L, max_order, K only)
   scat::HostPlan3D h3;
   std::vector<size_t> psi3_off;  // per (j, l): its 2l+1 tables, contiguous
@@ -295,6 +299,8 @@ void free_device(scat_plan *p) {
   if (p->d_tables) (void)hipFree(p->d_tables);
   if (p->d_tw) (void)hipFree(p->d_tw);
   if (p->d_scratch) (void)hipFree(p->d_scratch);
+  if (p->d_masks) (void)hipFree(p->d_masks);
+  p->d_masks = nullptr;
   p->d_tables = nullptr;
   p->d_tw = nullptr;
   p->d_scratch = nullptr;
@@ -418,6 +424,36 @@ scat_status upload(scat_plan *p) {
         p->taps_r_off[r] = push_taps(gr, R, 1, 0);
         p->taps_c_off[r] = push_taps(gc, R, 1, 0);
       }
+    }
+    // blocks of (N >> j2) points a side on which a wavelet stays below 1e-7 of its peak are
+    // skipped by the node kernels (their sum is far below fp32 rounding of the rest)
+    std::vector<unsigned> masks;
+    for (int j2 = 1; j2 < h.J; ++j2)
+      for (int r = 0; r < j2; ++r) {
+        if (r > 0 && h.max_order < 2) continue;
+        p->mask_off[{r, j2}] = masks.size();
+        const int side = N >> r, blk = N >> j2, A = side / blk;
+        for (int l = 0; l < h.LQ; ++l) {
+          const FilterTable &t = *h.find(r == 0 ? 1 : 2, j2 * h.LQ + l, r);
+          double peak = 0.0;
+          for (double v : t.v) peak = std::max(peak, std::fabs(v));
+          unsigned m = 0;
+          for (int ar = 0; ar < A; ++ar)
+            for (int ac = 0; ac < A; ++ac) {
+              double big = 0.0;
+              for (int i = 0; i < blk; ++i)
+                for (int k = 0; k < blk; ++k)
+                  big = std::max(big, std::fabs(t.v[static_cast<size_t>(ar * blk + i) * side + ac * blk + k]));
+              if (big > 1e-7 * peak) m |= 1u << (ar * A + ac);
+            }
+          masks.push_back(m);
+        }
+      }
+    if (!masks.empty()) {
+      if (hipMalloc(&p->d_masks, masks.size() * sizeof(unsigned)) != hipSuccess) return SCAT_ERR_ALLOC;
+      if (hipMemcpy(p->d_masks, masks.data(), masks.size() * sizeof(unsigned), hipMemcpyHostToDevice) !=
+          hipSuccess)
+        return SCAT_ERR_DEVICE;
     }
     if (N > 128 && h.max_order == 2) {
       // children of the polyphase octave: R_q[k] = sum_a (-1)^(a.q) psi[k + M a], M = N/2
@@ -1045,6 +1081,7 @@ scat_status forward_2d_node(scat_plan *p, const float *in, float *out, long p0, 
     a.poly = poly;
     a.src = XH;
     a.filt = tab + p->psi1_off[j1];
+    a.mask = (!poly && j1 > 0) ? p->d_masks + p->mask_off.at({0, j1}) : nullptr;
     a.taps_r = tab + (poly ? p->ptaps_r_off : p->taps_r_off[j1]);
     a.taps_c = tab + (poly ? p->ptaps_c_off : p->taps_c_off[j1]);
     a.uout = kids ? U : nullptr;
@@ -1070,6 +1107,7 @@ scat_status forward_2d_node(scat_plan *p, const float *in, float *out, long p0, 
       c.poly = false;
       c.src = U;
       c.filt = tab + (poly ? p->poly_psi_off.at(j2) : p->psi2_off.at({j1, j2}));
+      c.mask = poly ? nullptr : p->d_masks + p->mask_off.at({j1, j2});
       c.taps_r = tab + p->taps_r_off[j2];
       c.taps_c = tab + p->taps_c_off[j2];
       c.uout = nullptr;

@@ -191,6 +191,7 @@ hipError_t launch_tree32(const float2 *xh, long planes, int L, int max_order, co
 // optionally the half spectrum of the modulus for the node's children.
 //   src    [NS][P][S/2+1][S]; filt [F][P][S][S]; items per source: F (poly: 4 F, the four
 //          polyphase components of each filter's node, component index 2 p_r + p_c fastest)
+//   mask   filters that vanish on whole M x M alias blocks of their table: the blocks to skip
 //   uout   null or [NS * items][M/2+1][M] (poly: times w^(p.k), w = exp(-2 pi i / 2M))
 //   out    [planes][K][32][32] with channel = chan_base + (source % G) * chan_src +
 //          filter * chan_f and plane = source / G; poly: parts [NS * items][32][32]
@@ -199,6 +200,7 @@ struct NodeLaunch {
   bool poly;
   const float2 *src;
   const float *filt;
+  const unsigned *mask;  // null, or [F] device words: bit (q A + a_r) A + a_c set = block in use
   const float *taps_r, *taps_c;
   float2 *uout;
   float *out;

@@ -1,7 +1,8 @@
 // Depth-first 2-D cascade: one workgroup computes one whole node of the scattering tree in LDS.
 //
 // A node is |x (*) psi| (or ||x (*) psi_1| (*) psi_2|) on its own subsampled grid of M x M
-// points, M = 64 or 128 (paper, section 2 "Implementation": convolutions as Fourier products,
+// points, M = 64 (k_node, 256 threads, three workgroups per compute unit) or 128 (k_node_half,
+// 512 threads, two per compute unit) (paper, section 2 "Implementation": convolutions as Fourier products,
 // every filtered signal downsampled, the tree walked branch by branch so that intermediates
 // are dropped as soon as the children are done).  The workgroup
 //   1. forms the node's spectrum  Z[k] = sum over sources q and aliases a of
@@ -26,7 +27,9 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <cstdlib>
 #include <string>
+#include <type_traits>
 
 #include "fft_regs.hpp"
 #include "slab_fft.hpp"
@@ -43,6 +46,8 @@ double fft2_flops(double n) { return n > 1 ? 10.0 * n * n * std::log2(n) : 0.0; 
 struct NodeArgs {
   const float2 *src;    // [NS][P][S/2+1][S] half spectra, S = M * A
   const float *filt;    // [F][P][S][S] real tables (carry the 1/N^2 of the inverse transforms)
+  const unsigned *mask; // null, or per filter: bit (q A + ar) A + ac clear = that M x M block of
+                        // table q is negligible everywhere and is skipped
   const float *taps_r;  // lowpass taps along a column (row index varies): [2R+1], POLY: [2][2R+1]
   const float *taps_c;  // along a row
   float2 *uout;         // null, or [(NS*I)][M/2+1][M]: half spectrum of every node's modulus
@@ -60,7 +65,8 @@ struct NodeArgs {
 // to the eight XCDs in turn, so all items of one source run on one XCD, one after the other,
 // and its L2 holds the source's spectrum for them.
 template <int M, int A, int P, bool POLY>
-__global__ __launch_bounds__(M * M / 16) void k_node(NodeArgs a) {
+__global__ __launch_bounds__(M * M / 16, 3) void k_node(NodeArgs a) {
+  static_assert(M == 64, "128 x 128 nodes take k_node_half");
   using SL = Slab<M, M>;
   constexpr int NT = M * M / 16, T = M / 16, S = M * A, RS = SL::RS;
   constexpr int DEC = M / kOut, R = 4 * DEC, NTAP = 2 * R + 1;
@@ -80,49 +86,65 @@ __global__ __launch_bounds__(M * M / 16) void k_node(NodeArgs a) {
   SL::fill_twiddles(wtab, a.tw, a.tw_n);
   const int tw_step = a.tw_n / (2 * M);  // POLY only: table step of w = exp(-2 pi i / 2M)
 
-  // ---- 1. spectrum of the node: thread = one column, rows rg + T i (coalesced reads)
+  // ---- 1. spectrum of the node: thread = one column, rows rg + T i (coalesced reads).
+  // Measured: the waves of a workgroup reading neighbouring rows at the same time is what the
+  // memory system likes (a wave on 16 consecutive rows of its own is 2-3 times slower), and a
+  // branch per term instead of per block serialises the loads (also 2-3 times slower).  One
+  // pass of the loop takes one alias block of one source (all 16 rows of the thread: 32 loads
+  // in flight); blocks on which the filter is negligible are left out.
   {
     const float2 *src = a.src + static_cast<size_t>(s) * P * (S / 2 + 1) * S;
     const float *filt = a.filt + static_cast<size_t>(f) * P * S * S;
-    const int col = tid % M, rg = tid / M;
-#pragma unroll 2
-    for (int i = 0; i < 16; ++i) {
-      const int kr0 = rg + T * i;
-      float2 acc = make_float2(0.f, 0.f);
+    // (the row group is the same for all lanes of a wave: kept scalar, so that row addresses are
+    // scalar bases with one lane offset)
+    const int col = tid % M, rg = __builtin_amdgcn_readfirstlane(tid / M);
+    {
+      float2 acc[16];
+      constexpr unsigned kAll = P * A * A >= 32 ? 0xffffffffu : (1u << (P * A * A)) - 1u;
+      unsigned rem = (a.mask != nullptr ? a.mask[f] : 0xffffffffu) & kAll;  // workgroup-uniform
 #pragma unroll
-      for (int q = 0; q < P; ++q) {
+      for (int i = 0; i < 16; ++i) acc[i] = make_float2(0.f, 0.f);
+      while (rem != 0u) {
+        const int bit = __builtin_amdgcn_readfirstlane(__ffs(rem) - 1);
+        rem &= rem - 1u;
+        const int ac = bit % A, ar = (bit / A) % A, q = bit / (A * A);
         const float2 *sq = src + static_cast<size_t>(q) * (S / 2 + 1) * S;
-        const float *fq = filt + static_cast<size_t>(q) * S * S;
+        const float *fq = filt + static_cast<size_t>(q) * S * S + (M * ar) * S;
+        const unsigned kc = static_cast<unsigned>(col + M * ac) & (S - 1);
+        const unsigned kcm = (S - kc) & (S - 1);
+        // sign of the whole block: polyphase alias sign (-1)^(a.p)
+        const float sblk = (POLY && ((ar * pr + ac * pc) & 1)) ? -1.f : 1.f;
+        // rows above S/2 are not stored: U[kr][kc] = conj(U[S - kr][-kc]); the stored spectra of
+        // polyphase components carry w^(p.k), which gives the mirrored value the extra sign
+        // (-1)^(q_r) (-1)^(q_c [kc != 0])
+        const float smir = (P == 4 && (((q >> 1) & 1) ^ ((q & 1) & (kc != 0 ? 1 : 0)))) ? -sblk : sblk;
+        float2 v[16];
+        float fv[16];
 #pragma unroll
-        for (int ar = 0; ar < A; ++ar) {
-          const int kr = kr0 + M * ar;
-          // rows above S/2 are not stored: U[kr][kc] = conj(U[S - kr][-kc]); the stored
-          // spectra of polyphase components carry w^(p.k), which adds the sign
-          // (-1)^(q_r) (-1)^(q_c [kc != 0]) to the mirrored value
+        for (int i = 0; i < 16; ++i) {
+          const int kr = rg + T * i + M * ar;
           const bool mir = kr > S / 2;  // the same for every lane of a wave
-          const int krs = mir ? S - kr : kr;
+          v[i] = (sq + (mir ? S - kr : kr) * S)[mir ? kcm : kc];
+          fv[i] = (fq + (rg + T * i) * S)[kc];
+        }
 #pragma unroll
-          for (int ac = 0; ac < A; ++ac) {
-            const int kc = col + M * ac;
-            const int kcs = mir ? (S - kc) & (S - 1) : kc;
-            const float2 v = sq[krs * S + kcs];
-            float fv = fq[kr * S + kc];
-            if (POLY && ((ar * pr + ac * pc) & 1)) fv = -fv;
-            float fx = fv, fy = fv;
-            if (mir) {
-              if (P == 4 && (((q >> 1) & 1) ^ ((q & 1) & (kc != 0 ? 1 : 0)))) fx = -fx;
-              fy = -fx;
-            }
-            acc.x = fmaf(v.x, fx, acc.x);
-            acc.y = fmaf(v.y, fy, acc.y);
-          }
+        for (int i = 0; i < 16; ++i) {
+          const bool mir = rg + T * i + M * ar > S / 2;
+          const float fx = fv[i] * (mir ? smir : sblk);
+          acc[i].x = fmaf(v[i].x, fx, acc[i].x);
+          acc[i].y = fmaf(v[i].y, mir ? -fx : fx, acc[i].y);
         }
       }
-      if (POLY) {
-        const float2 w = a.tw[((pr * kr0 + pc * col) * tw_step) & (a.tw_n - 1)];
-        acc = make_float2(acc.x * w.x + acc.y * w.y, acc.y * w.x - acc.x * w.y);  // * conj(w)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int kr0 = rg + T * i;
+        float2 z = acc[i];
+        if (POLY) {
+          const float2 w = a.tw[((pr * kr0 + pc * col) * tw_step) & (a.tw_n - 1)];
+          z = make_float2(z.x * w.x + z.y * w.y, z.y * w.x - z.x * w.y);  // * conj(w)
+        }
+        area[kr0 * RS + col] = z;
       }
-      area[kr0 * RS + col] = acc;
     }
   }
   __syncthreads();
@@ -217,6 +239,215 @@ __global__ __launch_bounds__(M * M / 16) void k_node(NodeArgs a) {
   }
 }
 
+// ------------------------------------------------------------------------------------
+// k_node for 128 x 128 nodes with HALF the workgroup: 512 threads hold the node in registers
+// (32 points each) and use LDS only to exchange one half of it at a time, 78 KB instead of
+// 156 KB, so that TWO workgroups share a compute unit and one's memory and LDS phases run
+// under the other's arithmetic (a single resident workgroup adds its phases up: measured).
+//   spectrum + row transforms: rows 0..63, then rows 64..127 (thread = row r or r + 64,
+//     columns t + 8 i), through the same 64 row slots of 152 elements;
+//   transposition: columns 0..63, then 64..127, through 128 rows of 76 elements;
+//   column transforms: column c, then c + 64 (thread = rows t1 + 8 i), exchange in place;
+//   lowpass as in k_node, with the row-filtered values parked in registers while the
+//   unfiltered plane is still being read, then written over it.
+template <int A, int P, bool POLY>
+__global__ __launch_bounds__(512, 2) void k_node_half(NodeArgs a) {
+  constexpr int M = 128, T = 8, NT = 512, S = M * A;
+  constexpr int RSR = 152, RSC = 76;
+  constexpr int DEC = M / kOut, R = 4 * DEC, NTAP = 2 * R + 1;
+  extern __shared__ float2 lds[];
+  float2 *area = lds;             // 64 * RSR = 128 * RSC elements
+  float2 *wtab = lds + 64 * RSR;  // twiddles: [k * T + t] for rows, the same again for columns
+  const int tid = threadIdx.x;
+  const int I = a.F * (POLY ? 4 : 1);
+  const long bq = blockIdx.x >> 3;
+  const long s = (blockIdx.x & 7) + 8 * (bq / I);
+  const int item = static_cast<int>(bq % I);
+  if (s >= a.NS) return;
+  const int f = POLY ? item >> 2 : item;
+  const int pr = POLY ? (item >> 1) & 1 : 0, pc = POLY ? item & 1 : 0;
+  for (int idx = tid; idx < M; idx += NT) wtab[idx] = a.tw[(idx / T) * (idx % T) * (a.tw_n / M)];
+  const int tw_step = a.tw_n / (2 * M);
+  const int r = tid / T, t = tid % T;    // row roles: rows r and r + 64, columns t + 8 i
+  const int c = tid % 64, t1 = tid / 64; // column roles: columns c and c + 64, rows t1 + 8 i
+  const float2 *wl = wtab + t, *wlc = wtab + t1;
+  __syncthreads();
+
+  // ---- 1 + 2a. spectrum of the node (half of its rows at a time) and inverse row transforms
+  float2 vh[2][16];
+  {
+    const float2 *src = a.src + static_cast<size_t>(s) * P * (S / 2 + 1) * S;
+    const float *filt = a.filt + static_cast<size_t>(f) * P * S * S;
+    const int col = tid % M;
+    const int rg = __builtin_amdgcn_readfirstlane(tid / M);  // 0..3, the same for a wave
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+#pragma unroll 2
+      for (int i = 0; i < 16; ++i) {
+        const int lr = rg + 4 * i;  // row within the half
+        const int kr0 = 64 * h + lr;
+        float2 z = make_float2(0.f, 0.f);
+#pragma unroll
+        for (int q = 0; q < P; ++q) {
+          const float2 *sq = src + static_cast<size_t>(q) * (S / 2 + 1) * S;
+          const float *fq = filt + static_cast<size_t>(q) * S * S;
+#pragma unroll
+          for (int ar = 0; ar < A; ++ar) {
+            const int kr = kr0 + M * ar;
+            const bool mir = kr > S / 2;  // the same for every lane of a wave
+            const int krs = mir ? S - kr : kr;
+#pragma unroll
+            for (int ac = 0; ac < A; ++ac) {
+              const unsigned kc = static_cast<unsigned>(col + M * ac) & (S - 1);
+              const unsigned kcs = mir ? (S - kc) & (S - 1) : kc;
+              const float2 v = (sq + krs * S)[kcs];
+              float fv = (fq + kr * S)[kc];
+              if (POLY && ((ar * pr + ac * pc) & 1)) fv = -fv;
+              float fx = fv, fy = fv;
+              if (mir) {
+                if (P == 4 && (((q >> 1) & 1) ^ ((q & 1) & (kc != 0 ? 1 : 0)))) fx = -fx;
+                fy = -fx;
+              }
+              z.x = fmaf(v.x, fx, z.x);
+              z.y = fmaf(v.y, fy, z.y);
+            }
+          }
+        }
+        if (POLY) {
+          const float2 w = a.tw[((pr * kr0 + pc * col) * tw_step) & (a.tw_n - 1)];
+          z = make_float2(z.x * w.x + z.y * w.y, z.y * w.x - z.x * w.y);  // * conj(w)
+        }
+        area[lr * RSR + col] = z;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < 16; ++i) vh[h][i] = area[r * RSR + t + T * i];
+      __syncthreads();
+      fft_core_tab<16, T, true, false>(vh[h], t, area + r * RSR, T + 1, 1, wl, T);
+    }
+  }
+  // ---- 2b. transposition, half of the columns at a time, and inverse column transforms
+  float2 w[2][16];
+#pragma unroll
+  for (int hc = 0; hc < 2; ++hc) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      area[r * RSC + t + T * i] = vh[0][8 * hc + i];
+      area[(r + 64) * RSC + t + T * i] = vh[1][8 * hc + i];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 16; ++i) w[hc][i] = area[(t1 + T * i) * RSC + c];
+    __syncthreads();
+  }
+#pragma unroll
+  for (int hc = 0; hc < 2; ++hc)
+    fft_core_tab<16, T, true, false>(w[hc], t1, area + c, T * RSC, RSC, wlc, T);
+
+  // ---- 3. modulus; 4. lowpass + subsampling (rows first, then columns)
+  constexpr int US = M + 1, HS = kOut + 1;
+  float *ub = reinterpret_cast<float *>(area);  // [M][US], later [M][HS] over it
+  float u[2][16];
+#pragma unroll
+  for (int hc = 0; hc < 2; ++hc)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      u[hc][i] = __builtin_amdgcn_sqrtf(w[hc][i].x * w[hc][i].x + w[hc][i].y * w[hc][i].y);
+      ub[(t1 + T * i) * US + c + 64 * hc] = u[hc][i];
+    }
+  __syncthreads();
+  {
+    constexpr int OPT = kOut * M / NT;  // 8 outputs per thread, adjacent columns
+    constexpr int NIN = DEC * (OPT - 1) + NTAP;
+    const int rr = tid % M, mg = tid / M;
+    const float *tc = a.taps_c + (POLY ? pc * NTAP : 0);
+    float acc[OPT];
+#pragma unroll
+    for (int j = 0; j < OPT; ++j) acc[j] = 0.f;
+    const int e0 = DEC * OPT * mg - R;
+#pragma unroll
+    for (int e = 0; e < NIN; ++e) {
+      const float val = ub[rr * US + ((e0 + e) & (M - 1))];
+#pragma unroll
+      for (int j = 0; j < OPT; ++j) {
+        const int ti = DEC * j + 2 * R - e;
+        if (ti >= 0 && ti <= 2 * R) acc[j] = fmaf(tc[ti], val, acc[j]);
+      }
+    }
+    __syncthreads();  // the plane has been read by everybody: the filtered rows go over it
+#pragma unroll
+    for (int j = 0; j < OPT; ++j) ub[rr * HS + OPT * mg + j] = acc[j];
+  }
+  __syncthreads();
+  {
+    constexpr int OPV = kOut * kOut / NT;  // 2 outputs per thread, adjacent rows
+    constexpr int NIN = DEC * (OPV - 1) + NTAP;
+    const int mc = tid % kOut, ng = tid / kOut;
+    const float *tr = a.taps_r + (POLY ? pr * NTAP : 0);
+    float acc[OPV];
+#pragma unroll
+    for (int j = 0; j < OPV; ++j) acc[j] = 0.f;
+    const int e0 = DEC * OPV * ng - R;
+#pragma unroll
+    for (int e = 0; e < NIN; ++e) {
+      const float val = ub[((e0 + e) & (M - 1)) * HS + mc];
+#pragma unroll
+      for (int j = 0; j < OPV; ++j) {
+        const int ti = DEC * j + 2 * R - e;
+        if (ti >= 0 && ti <= 2 * R) acc[j] = fmaf(tr[ti], val, acc[j]);
+      }
+    }
+    float *op;
+    if (POLY) {
+      op = a.out + (static_cast<size_t>(s) * I + item) * kOut * kOut;
+    } else {
+      const long plane = s / a.G;
+      const int g = static_cast<int>(s - plane * a.G);
+      op = a.out + (static_cast<size_t>(plane) * a.K + a.chan_base + g * a.chan_src + f * a.chan_f) *
+                       kOut * kOut;
+    }
+#pragma unroll
+    for (int j = 0; j < OPV; ++j) op[(OPV * ng + j) * kOut + mc] = acc[j];
+  }
+  if (a.uout == nullptr) return;
+
+  // ---- 5. spectrum of the modulus for the children: forward columns, transposition back,
+  // forward rows; rows 0 .. 64 are stored
+  __syncthreads();
+#pragma unroll
+  for (int hc = 0; hc < 2; ++hc) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) w[hc][i] = make_float2(u[hc][i], 0.f);
+    fft_core_tab<16, T, false, false>(w[hc], t1, area + c, T * RSC, RSC, wlc, T);
+  }
+#pragma unroll
+  for (int hc = 0; hc < 2; ++hc) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) area[(t1 + T * i) * RSC + c] = w[hc][i];
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      vh[0][8 * hc + i] = area[r * RSC + t + T * i];
+      vh[1][8 * hc + i] = area[(r + 64) * RSC + t + T * i];
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    fft_core_tab<16, T, false, false>(vh[h], t, area + r * RSR, T + 1, 1, wl, T);
+    const int row = r + 64 * h;
+    if (row <= M / 2) {
+      float2 *up = a.uout + ((static_cast<size_t>(s) * I + item) * (M / 2 + 1) + row) * M + t;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        float2 val = vh[h][i];
+        if (POLY) val = c_mul(val, a.tw[((pr * row + pc * (t + T * i)) * tw_step) & (a.tw_n - 1)]);
+        up[T * i] = val;
+      }
+    }
+  }
+}
+
 // out[plane][chan_base + g][.] = sum of the four parts of node (plane, g)
 __global__ __launch_bounds__(256) void k_sum4(const float *__restrict__ part, float *__restrict__ out,
                                                long nodes, int G, int K, int chan_base) {
@@ -239,8 +470,8 @@ hipError_t launch_node_t(const NodeArgs &a, hipStream_t st) {
   const long blocks = 8 * ((a.NS + 7) / 8) * I;
   if (a.NS <= 0 || blocks > 0x7fffffffL || a.tw_n % (POLY ? 2 * M : M) != 0) return hipErrorInvalidValue;
   const size_t lds = SL::lds_bytes + SL::tab_elems * sizeof(float2);
-  const std::string name = "k_node<" + std::to_string(M) + ", " + std::to_string(A) + ", " +
-                           std::to_string(P) + (POLY ? ", true>" : ", false>");
+  const std::string name = (M == 128 ? "k_node_half<" : "k_node<64, ") + std::to_string(A) + ", " +
+                            std::to_string(P) + (POLY ? ", true>" : ", false>");
   const double items = static_cast<double>(a.NS) * I;
   const double pts = static_cast<double>(M) * M;
   LaunchScope obs(name.c_str(),
@@ -250,13 +481,17 @@ hipError_t launch_node_t(const NodeArgs &a, hipStream_t st) {
                   items * ((a.uout ? 2 : 1) * fft2_flops(M) + fft2_flops(kOut) +
                            pts * (4.0 * P * A * A + 4.0 + 2.0) + fft2_flops(M) * (a.uout ? 0 : 1)),
                   st);
-  if (lds > 65536) {
+  if constexpr (M == 128) {
+    const size_t lds_h = (64 * 152 + 128) * sizeof(float2);
     static unsigned long long lds_ok = 0;
-    hipError_t e = allow_large_lds(reinterpret_cast<const void *>(k_node<M, A, P, POLY>), lds_ok);
+    hipError_t e = allow_large_lds(reinterpret_cast<const void *>(k_node_half<A, P, POLY>), lds_ok);
     if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((k_node_half<A, P, POLY>), dim3(static_cast<unsigned>(blocks)), dim3(512), lds_h, st,
+                       a);
+  } else {
+    hipLaunchKernelGGL((k_node<M, A, P, POLY>), dim3(static_cast<unsigned>(blocks)), dim3(M * M / 16), lds,
+                       st, a);
   }
-  hipLaunchKernelGGL((k_node<M, A, P, POLY>), dim3(static_cast<unsigned>(blocks)), dim3(M * M / 16), lds,
-                     st, a);
   return hipGetLastError();
 }
 
@@ -274,6 +509,7 @@ hipError_t launch_node(const NodeLaunch &n, hipStream_t st) {
   NodeArgs a;
   a.src = n.src;
   a.filt = n.filt;
+  a.mask = n.mask;
   a.taps_r = n.taps_r;
   a.taps_c = n.taps_c;
   a.uout = n.uout;
