@@ -246,8 +246,9 @@ def main():
     # HBM bytes per launch of every kernel from the committed rocprofv3 counter summary
     # (FETCH_SIZE and WRITE_SIZE runs of this same command, scaled by a plain copy)
     per_kernel = {}
-    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_%s%s.txt"
-                         % (TRAFFIC_TAGS.get(wl, "none"), "_backward" if args.backward else ""))
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_%s%s%s.txt"
+                         % (TRAFFIC_TAGS.get(wl, "none"), "_backward" if args.backward else "",
+                            "_node_kernels" if args.node_kernels else ""))
     if os.path.exists(tpath):
         with open(tpath) as f:
             for line in f:
