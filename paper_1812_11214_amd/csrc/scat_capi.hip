@@ -112,6 +112,7 @@ struct scat_plan {
   // 2-D: every node of the tree is computed by one workgroup (scat_node.hip): forward calls
   // keep only the spectra of x and of the first-order moduli with children in scratch
   bool node = false;
+  bool node_tables = false;  // shapes the whole-node kernels serve: their taps and masks are uploaded
   std::map<int, size_t> poly_psi_off;          // j2 -> [L][4][N/2][N/2] sign-folded wavelets
   std::vector<size_t> taps_r_off, taps_c_off;  // per res: spatial lowpass taps [2R+1]
   size_t ptaps_r_off = 0, ptaps_c_off = 0;     // polyphase taps of resolution 0: [2][2R+1]
@@ -382,7 +383,7 @@ scat_status upload(scat_plan *p) {
       }
     }
   }
-  if (p->node) {
+  if (p->node_tables) {
     const int N = p->n1;
     const double two_pi_ = 6.283185307179586476925286766559;
     // spatial taps of a lowpass factor: g[d] = (1/len) sum_k phi[k] cos(2 pi k d / len)
@@ -455,7 +456,7 @@ scat_status upload(scat_plan *p) {
           hipSuccess)
         return SCAT_ERR_DEVICE;
     }
-    if (N > 128 && h.max_order == 2) {
+    if (p->node && N > 128 && h.max_order == 2) {
       // children of the polyphase octave: R_q[k] = sum_a (-1)^(a.q) psi[k + M a], M = N/2
       const int M = N / 2;
       const double scale = 1.0 / (static_cast<double>(N) * N);
@@ -620,8 +621,9 @@ scat_status create_common(scat_plan **out_plan, int dims, const int *user_shape,
   p->tree = dims == 2 && oversampling == 0 && scat::tree_supported(p->n1, p->n2, J);
   // whole-node kernels: square grids whose octaves are 128 or 64 points a side, or 256 as four
   // polyphase components, with the 32 x 32 output grid their lowpass stage is laid out for
-  p->node = node_kernels && dims == 2 && oversampling == 0 && p->n1 == p->n2 &&
-            ((p->n1 == 256 && J == 3) || (p->n1 == 128 && J == 2));
+  p->node_tables = dims == 2 && oversampling == 0 && p->n1 == p->n2 &&
+                   ((p->n1 == 256 && J == 3) || (p->n1 == 128 && J == 2));
+  p->node = node_kernels && p->node_tables;
   if (padded) {
     p->padded = true;
     for (int d = 0; d < dims; ++d) {
@@ -1020,6 +1022,37 @@ scat_status forward_2d_fused(scat_plan *p, const float *in, float *out, long p0,
                              ChanMap{L, L, 0, 1 + j1 * L}));
     if (!kids) continue;
     const int octs = J - 1 - j1;
+    // 64 x 64 children of 128 x 128 nodes (one child octave): one workgroup per child, fed by
+    // the nodes' full row-and-column spectra (measured faster than the row pass + leaf kernel
+    // pair, and no row-pass output goes to memory)
+    if (tape == nullptr && p->node_tables && M1r == 128 && M1c == 128 && octs == 1 && m_r == 32) {
+      const int j2 = j1 + 1;
+      SCAT_TRY(scat::launch_row_fwd(U, pc * L * (M1r / 2 + 1), M1c, tw, tw_n, st));
+      scat::NodeLaunch c{};
+      c.M = 64;
+      c.A = 2;
+      c.P = 1;
+      c.poly = false;
+      c.src = U;
+      c.filt = tab + p->psi2_off.at({r1, j2});
+      c.mask = p->d_masks + p->mask_off.at({r1, j2});
+      c.taps_r = tab + p->taps_r_off[j2];
+      c.taps_c = tab + p->taps_c_off[j2];
+      c.uout = nullptr;
+      c.out = o;
+      c.NS = pc * L;
+      c.F = L;
+      c.G = L;
+      c.chan_base = s2_base;
+      c.chan_src = L;
+      c.chan_f = 1;
+      c.K = K;
+      c.tw = tw;
+      c.tw_n = tw_n;
+      SCAT_TRY(scat::launch_node(c, st));
+      s2_base += L * L * octs;
+      continue;
+    }
     std::vector<float2 *> t2(J);
     {
       scat::FusedLevel lv[4];

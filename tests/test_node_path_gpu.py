@@ -83,6 +83,9 @@ def test_node_schedule_is_the_one_that_runs():
                 assert plan.workspace_bytes(1) < 4 << 20   # spectra of x and of one octave only
         finally:
             plan.close()
-    assert any(k.startswith("k_node<") for k in names[True]), names[True]
+    assert any(k.startswith("k_node_half<") for k in names[True]), names[True]
     assert not any(k.startswith("k_rows_fused") for k in names[True]), names[True]
-    assert not any(k.startswith("k_node<") for k in names[False]), names[False]
+    # the default schedule: row and column passes (and the whole-node kernel only for the
+    # 64 x 64 children of the 128 x 128 nodes)
+    assert any(k.startswith("k_rows_fused") for k in names[False]), names[False]
+    assert not any(k.startswith("k_node_half<") for k in names[False]), names[False]
