@@ -461,21 +461,38 @@ scat_status upload(scat_plan *p) {
       const int M = N / 2;
       const double scale = 1.0 / (static_cast<double>(N) * N);
       for (int j2 = 1; j2 < h.J; ++j2) {
+        while (pool.size() % 4 != 0) pool.push_back(0.f);  // 16-byte loads of the table
         p->poly_psi_off[j2] = pool.size();
         for (int l = 0; l < h.LQ; ++l) {
           const FilterTable &t = *h.find(1, j2 * h.LQ + l, 0);
-          for (int q = 0; q < 4; ++q) {
+          auto folded = [&](int q, int kr, int kc) {
             const int qr = q >> 1, qc = q & 1;
-            for (int kr = 0; kr < M; ++kr)
-              for (int kc = 0; kc < M; ++kc) {
-                double acc = 0.0;
-                for (int ar = 0; ar < 2; ++ar)
-                  for (int ac = 0; ac < 2; ++ac) {
-                    const double v = t.v[static_cast<size_t>(kr + M * ar) * N + kc + M * ac];
-                    acc += ((ar * qr + ac * qc) & 1) ? -v : v;
-                  }
-                pool.push_back(static_cast<float>(acc * scale));
+            double acc = 0.0;
+            for (int ar = 0; ar < 2; ++ar)
+              for (int ac = 0; ac < 2; ++ac) {
+                const double v = t.v[static_cast<size_t>(kr + M * ar) * N + kc + M * ac];
+                acc += ((ar * qr + ac * qc) & 1) ? -v : v;
               }
+            return static_cast<float>(acc * scale);
+          };
+          if ((N >> j2) == M) {
+            // children as large as a component: [row][column parity][column pair][component],
+            // the four component values of a point side by side (one 16-byte load)
+            for (int kr = 0; kr < M; ++kr)
+              for (int e = 0; e < 2; ++e)
+                for (int cp = 0; cp < M / 2; ++cp)
+                  for (int q = 0; q < 4; ++q) pool.push_back(folded(q, kr, 2 * cp + e));
+          } else if ((N >> j2) == M / 2) {
+            // children half as large: [row][column block][column parity][column pair][component]
+            for (int kr = 0; kr < M; ++kr)
+              for (int ac = 0; ac < 2; ++ac)
+                for (int e = 0; e < 2; ++e)
+                  for (int cp = 0; cp < M / 4; ++cp)
+                    for (int q = 0; q < 4; ++q) pool.push_back(folded(q, kr, (M / 2) * ac + 2 * cp + e));
+          } else {
+            for (int q = 0; q < 4; ++q)
+              for (int kr = 0; kr < M; ++kr)
+                for (int kc = 0; kc < M; ++kc) pool.push_back(folded(q, kr, kc));
           }
         }
       }

@@ -72,7 +72,7 @@ __global__ __launch_bounds__(M * M / 16, 3) void k_node(NodeArgs a) {
   constexpr int DEC = M / kOut, R = 4 * DEC, NTAP = 2 * R + 1;
   static_assert(P == 1 || P == 4, "sources");
   static_assert(!POLY || P == 1, "a polyphase node reads a plain spectrum");
-  extern __shared__ float2 lds[];
+  extern __shared__ __attribute__((aligned(16))) float2 lds[];
   float2 *area = lds;
   float2 *wtab = lds + M * RS;
   const int tid = threadIdx.x;
@@ -86,6 +86,89 @@ __global__ __launch_bounds__(M * M / 16, 3) void k_node(NodeArgs a) {
   SL::fill_twiddles(wtab, a.tw, a.tw_n);
   const int tw_step = a.tw_n / (2 * M);  // POLY only: table step of w = exp(-2 pi i / 2M)
 
+  if constexpr (A == 2 && P == 4 && !POLY) {
+    // ---- 1 (children of a polyphase parent). Every stored source row (0 .. 64, 128 columns) is
+    // read once, by half a wavefront: a lane takes two adjacent columns of both column blocks
+    // and of all four components (16-byte loads).  Row rho contributes to row rho of the node
+    // directly and, through the conjugate symmetry of the stored spectra
+    // W_q[128 - rho][-c] = s_q(c) conj(W_q[rho][c]), to row 64 - rho (the alias row 128 - rho);
+    // rows 0 and 64, which mirror onto themselves, both fold onto row 0.  The direct parts are
+    // written to LDS first, the second parts are added after a barrier.  Filter table:
+    // [row][column block][column parity][column pair][component].
+    const float4 *src4 = reinterpret_cast<const float4 *>(a.src + static_cast<size_t>(s) * 4 * 65 * S);
+    const float4 *f4 = reinterpret_cast<const float4 *>(a.filt + static_cast<size_t>(f) * 4 * S * S);
+    const int cq = tid & 31, st = tid >> 5;
+    float2 z2[8][2];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int row = st + 8 * i;
+      const bool first = row == 0;
+      const int row2 = first ? 64 : S - row;
+      float4 w[2][4], d[2][2], m[2][2];
+#pragma unroll
+      for (int ac = 0; ac < 2; ++ac) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) w[ac][q] = src4[(q * 65 + row) * (S / 2) + 32 * ac + cq];
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          d[ac][e] = f4[((row * 2 + ac) * 2 + e) * 32 + cq];
+          const int idx = first ? 32 * ac + cq : (64 - 32 * ac - cq - e) & 63;
+          m[ac][e] = f4[((row2 * 2 + (idx >> 5)) * 2 + e) * 32 + (idx & 31)];
+        }
+      }
+      float4 zd = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+      for (int ac = 0; ac < 2; ++ac) {
+        const float dq0[4] = {d[ac][0].x, d[ac][0].y, d[ac][0].z, d[ac][0].w};
+        const float dq1[4] = {d[ac][1].x, d[ac][1].y, d[ac][1].z, d[ac][1].w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          zd.x = fmaf(w[ac][q].x, dq0[q], zd.x);
+          zd.y = fmaf(w[ac][q].y, dq0[q], zd.y);
+          zd.z = fmaf(w[ac][q].z, dq1[q], zd.z);
+          zd.w = fmaf(w[ac][q].w, dq1[q], zd.w);
+        }
+      }
+      *reinterpret_cast<float4 *>(area + row * RS + 2 * cq) = zd;
+      if (first) {
+#pragma unroll
+        for (int ac = 0; ac < 2; ++ac)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) w[ac][q] = src4[(q * 65 + 64) * (S / 2) + 32 * ac + cq];
+      }
+      float4 zs = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+      for (int ac = 0; ac < 2; ++ac) {
+        // s = (1, sc, -1, -sc), sc = -1 except for column 0
+        const float sc0 = first ? 1.f : (ac == 0 && cq == 0) ? 1.f : -1.f;
+        const float sc1 = first ? 1.f : -1.f;
+        const float sn = first ? 1.f : -1.f;
+        const float g0[4] = {m[ac][0].x, sc0 * m[ac][0].y, sn * m[ac][0].z, sn * sc0 * m[ac][0].w};
+        const float g1[4] = {m[ac][1].x, sc1 * m[ac][1].y, sn * m[ac][1].z, sn * sc1 * m[ac][1].w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          zs.x = fmaf(w[ac][q].x, g0[q], zs.x);
+          zs.y = fmaf(w[ac][q].y, g0[q], zs.y);
+          zs.z = fmaf(w[ac][q].z, g1[q], zs.z);
+          zs.w = fmaf(w[ac][q].w, g1[q], zs.w);
+        }
+      }
+      const float cj = first ? 1.f : -1.f;
+      z2[i][0] = make_float2(zs.x, cj * zs.y);
+      z2[i][1] = make_float2(zs.z, cj * zs.w);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int row = st + 8 * i;
+      const bool first = row == 0;
+      float2 *tr = area + (first ? 0 : M - row) * RS;
+      const int c0 = first ? 2 * cq : (M - 2 * cq) & (M - 1), c1 = first ? 2 * cq + 1 : M - 1 - 2 * cq;
+      float2 o0 = tr[c0], o1 = tr[c1];
+      tr[c0] = make_float2(o0.x + z2[i][0].x, o0.y + z2[i][0].y);
+      tr[c1] = make_float2(o1.x + z2[i][1].x, o1.y + z2[i][1].y);
+    }
+  } else
   // ---- 1. spectrum of the node: thread = one column, rows rg + T i (coalesced reads).
   // Measured: the waves of a workgroup reading neighbouring rows at the same time is what the
   // memory system likes (a wave on 16 consecutive rows of its own is 2-3 times slower), and a
@@ -255,7 +338,7 @@ __global__ __launch_bounds__(512, 2) void k_node_half(NodeArgs a) {
   constexpr int M = 128, T = 8, NT = 512, S = M * A;
   constexpr int RSR = 152, RSC = 76;
   constexpr int DEC = M / kOut, R = 4 * DEC, NTAP = 2 * R + 1;
-  extern __shared__ float2 lds[];
+  extern __shared__ __attribute__((aligned(16))) float2 lds[];
   float2 *area = lds;             // 64 * RSR = 128 * RSC elements
   float2 *wtab = lds + 64 * RSR;  // twiddles: [k * T + t] for rows, the same again for columns
   const int tid = threadIdx.x;
@@ -275,7 +358,78 @@ __global__ __launch_bounds__(512, 2) void k_node_half(NodeArgs a) {
 
   // ---- 1 + 2a. spectrum of the node (half of its rows at a time) and inverse row transforms
   float2 vh[2][16];
-  {
+  if constexpr (A == 1 && P == 4 && !POLY) {
+    // Children of a polyphase parent.  Every stored source row r (1 .. 63) is read once and
+    // serves two rows of the node: row r directly and row M - r through the conjugate symmetry
+    // W_q[M - r][-c] = s_q(c) conj(W_q[r][c]) of the stored spectra (s_q: the sign the phase
+    // factor of component q leaves, see the top of this file); rows 0 and 64 mirror onto
+    // themselves and are read whole.  A lane takes two adjacent columns of all four
+    // components (16-byte loads); the filter table is laid out [row][column parity][column
+    // pair][component], so that the four component values of a point are one 16-byte load,
+    // contiguous across the wave for the direct and for the mirrored columns alike.
+    const float4 *src4 = reinterpret_cast<const float4 *>(a.src + static_cast<size_t>(s) * 4 * 65 * M);
+    const float4 *f4 = reinterpret_cast<const float4 *>(a.filt + static_cast<size_t>(f) * 4 * M * M);
+    const int cp = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int cm0 = (64 - cp) & 63, cm1 = 63 - cp;        // column pairs of the mirrored columns
+    const int col_m0 = (M - 2 * cp) & (M - 1), col_m1 = M - 1 - 2 * cp;
+    const float sc0 = cp == 0 ? 1.f : -1.f;                // s_1(c) = -s_3(c) for c = 2 cp; -1 for 2 cp + 1
+    float2 zm[8][2];  // second rows (64 .. 127), kept until the first half has been transformed
+#pragma unroll 2
+    for (int i = 0; i < 8; ++i) {
+      const int row = wv + 8 * i;
+      const bool first = i == 0 && wv == 0;  // row 0: its partner is row 64, read directly
+      float4 w[4], w2[4], d[2], m[2];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) w[q] = src4[(q * 65 + row) * (M / 2) + cp];
+      d[0] = f4[(row * 2 + 0) * 64 + cp];
+      d[1] = f4[(row * 2 + 1) * 64 + cp];
+      const int row2 = first ? 64 : M - row;
+      m[0] = f4[(row2 * 2 + 0) * 64 + (first ? cp : cm0)];
+      m[1] = f4[(row2 * 2 + 1) * 64 + (first ? cp : cm1)];
+      if (first) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) w2[q] = src4[(q * 65 + 64) * (M / 2) + cp];
+      } else {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) w2[q] = w[q];
+      }
+      float4 zd;  // direct: columns 2 cp (x, y) and 2 cp + 1 (z, w)
+      zd.x = w[0].x * d[0].x + w[1].x * d[0].y + w[2].x * d[0].z + w[3].x * d[0].w;
+      zd.y = w[0].y * d[0].x + w[1].y * d[0].y + w[2].y * d[0].z + w[3].y * d[0].w;
+      zd.z = w[0].z * d[1].x + w[1].z * d[1].y + w[2].z * d[1].z + w[3].z * d[1].w;
+      zd.w = w[0].w * d[1].x + w[1].w * d[1].y + w[2].w * d[1].z + w[3].w * d[1].w;
+      *reinterpret_cast<float4 *>(area + row * RSR + 2 * cp) = zd;
+      // partner row: sum_q s_q conj(w_q) m_q with s = (1, sc, -1, -sc), or the plain product for row 64
+      const float g00 = m[0].x, g01 = first ? m[0].y : sc0 * m[0].y, g02 = first ? m[0].z : -m[0].z,
+                  g03 = first ? m[0].w : -sc0 * m[0].w;
+      const float g10 = m[1].x, g11 = first ? m[1].y : -m[1].y, g12 = first ? m[1].z : -m[1].z,
+                  g13 = first ? m[1].w : m[1].w;
+      const float cj = first ? 1.f : -1.f;
+      zm[i][0].x = w2[0].x * g00 + w2[1].x * g01 + w2[2].x * g02 + w2[3].x * g03;
+      zm[i][0].y = cj * (w2[0].y * g00 + w2[1].y * g01 + w2[2].y * g02 + w2[3].y * g03);
+      zm[i][1].x = w2[0].z * g10 + w2[1].z * g11 + w2[2].z * g12 + w2[3].z * g13;
+      zm[i][1].y = cj * (w2[0].w * g10 + w2[1].w * g11 + w2[2].w * g12 + w2[3].w * g13);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 16; ++i) vh[0][i] = area[r * RSR + t + T * i];
+    __syncthreads();
+    fft_core_tab<16, T, true, false>(vh[0], t, area + r * RSR, T + 1, 1, wl, T);  // ends with a barrier
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int row = wv + 8 * i;
+      const bool first = i == 0 && wv == 0;
+      const int slot = first ? 0 : 64 - row;  // rows 64 .. 127 go through slots 0 .. 63
+      area[slot * RSR + (first ? 2 * cp : col_m0)] = zm[i][0];
+      area[slot * RSR + (first ? 2 * cp + 1 : col_m1)] = zm[i][1];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 16; ++i) vh[1][i] = area[r * RSR + t + T * i];
+    __syncthreads();
+    fft_core_tab<16, T, true, false>(vh[1], t, area + r * RSR, T + 1, 1, wl, T);
+  } else {
     const float2 *src = a.src + static_cast<size_t>(s) * P * (S / 2 + 1) * S;
     const float *filt = a.filt + static_cast<size_t>(f) * P * S * S;
     const int col = tid % M;
