@@ -114,6 +114,10 @@ struct scat_plan {
   bool node = false;
   bool node_tables = false;  // shapes the whole-node kernels serve: their taps and masks are uploaded
   std::map<int, size_t> poly_psi_off;          // j2 -> [L][4][N/2][N/2] sign-folded wavelets
+  // (res, j) -> the L wavelets of octave j on the grid of resolution res in the layout of the
+  // whole-node kernels whose source is twice as large as the node (M = side / 2):
+  // [row][column block][column parity][column pair] = psi[row][M block + 2 pair + parity]
+  std::map<std::pair<int, int>, size_t> node2_off;
   std::vector<size_t> taps_r_off, taps_c_off;  // per res: spatial lowpass taps [2R+1]
   size_t ptaps_r_off = 0, ptaps_c_off = 0;     // polyphase taps of resolution 0: [2][2R+1]
   // per wavelet table: which (N >> j2) x (N >> j2) blocks of it are not negligible (bit
@@ -455,6 +459,29 @@ scat_status upload(scat_plan *p) {
       if (hipMemcpy(p->d_masks, masks.data(), masks.size() * sizeof(unsigned), hipMemcpyHostToDevice) !=
           hipSuccess)
         return SCAT_ERR_DEVICE;
+    }
+    {
+      std::vector<std::pair<int, int>> want;
+      if (N > 128) want.push_back({0, 0});
+      for (int r = 0; r + 1 < h.J; ++r)
+        if (r == 0 || h.max_order == 2) want.push_back({r, r + 1});
+      for (const auto &rj : want) {
+        const int r = rj.first, j = rj.second;
+        const int side = N >> r, M = side / 2;
+        if (M != 64 && M != 128) continue;
+        const double scale = 1.0 / (static_cast<double>(side) * side);
+        while (pool.size() % 4 != 0) pool.push_back(0.f);
+        p->node2_off[rj] = pool.size();
+        for (int l = 0; l < h.LQ; ++l) {
+          const FilterTable &t = *h.find(r == 0 ? 1 : 2, j * h.LQ + l, r);
+          for (int kr = 0; kr < side; ++kr)
+            for (int ac = 0; ac < 2; ++ac)
+              for (int e = 0; e < 2; ++e)
+                for (int cp = 0; cp < M / 2; ++cp)
+                  pool.push_back(static_cast<float>(
+                      t.v[static_cast<size_t>(kr) * side + M * ac + 2 * cp + e] * scale));
+        }
+      }
     }
     if (p->node && N > 128 && h.max_order == 2) {
       // children of the polyphase octave: R_q[k] = sum_a (-1)^(a.q) psi[k + M a], M = N/2
@@ -1051,8 +1078,8 @@ scat_status forward_2d_fused(scat_plan *p, const float *in, float *out, long p0,
       c.P = 1;
       c.poly = false;
       c.src = U;
-      c.filt = tab + p->psi2_off.at({r1, j2});
-      c.mask = p->d_masks + p->mask_off.at({r1, j2});
+      c.filt = tab + p->node2_off.at({r1, j2});
+      c.mask = nullptr;
       c.taps_r = tab + p->taps_r_off[j2];
       c.taps_c = tab + p->taps_c_off[j2];
       c.uout = nullptr;
@@ -1130,8 +1157,9 @@ scat_status forward_2d_node(scat_plan *p, const float *in, float *out, long p0, 
     a.P = 1;
     a.poly = poly;
     a.src = XH;
-    a.filt = tab + p->psi1_off[j1];
-    a.mask = (!poly && j1 > 0) ? p->d_masks + p->mask_off.at({0, j1}) : nullptr;
+    const bool a2 = a.A == 2;  // kernels that read the paired-column table
+    a.filt = tab + (a2 ? p->node2_off.at({0, j1}) : p->psi1_off[j1]);
+    a.mask = (!poly && j1 > 0 && !a2) ? p->d_masks + p->mask_off.at({0, j1}) : nullptr;
     a.taps_r = tab + (poly ? p->ptaps_r_off : p->taps_r_off[j1]);
     a.taps_c = tab + (poly ? p->ptaps_c_off : p->taps_c_off[j1]);
     a.uout = kids ? U : nullptr;
@@ -1156,8 +1184,9 @@ scat_status forward_2d_node(scat_plan *p, const float *in, float *out, long p0, 
       c.A = (poly ? M1 / 2 : M1) / c.M;
       c.poly = false;
       c.src = U;
-      c.filt = tab + (poly ? p->poly_psi_off.at(j2) : p->psi2_off.at({j1, j2}));
-      c.mask = poly ? nullptr : p->d_masks + p->mask_off.at({j1, j2});
+      const bool c2 = !poly && c.A == 2;
+      c.filt = tab + (poly ? p->poly_psi_off.at(j2) : c2 ? p->node2_off.at({j1, j2}) : p->psi2_off.at({j1, j2}));
+      c.mask = (poly || c2) ? nullptr : p->d_masks + p->mask_off.at({j1, j2});
       c.taps_r = tab + p->taps_r_off[j2];
       c.taps_c = tab + p->taps_c_off[j2];
       c.uout = nullptr;

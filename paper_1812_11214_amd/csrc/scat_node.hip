@@ -64,6 +64,21 @@ struct NodeArgs {
 // Workgroup b serves source 8 (b / 8 / I) + b % 8 and item (b / 8) % I: workgroups are dealt
 // to the eight XCDs in turn, so all items of one source run on one XCD, one after the other,
 // and its L2 holds the source's spectrum for them.
+// The P component values of table entry idx (entries of P floats, side by side)
+template <int P>
+__device__ __forceinline__ void load_comps(float (&d)[P], const float *tab, int idx) {
+  if constexpr (P == 4) {
+    const float4 v = reinterpret_cast<const float4 *>(tab)[idx];
+    d[0] = v.x;
+    d[1] = v.y;
+    d[2] = v.z;
+    d[3] = v.w;
+  } else {
+    static_assert(P == 1, "components");
+    d[0] = tab[idx];
+  }
+}
+
 template <int M, int A, int P, bool POLY>
 __global__ __launch_bounds__(M * M / 16, 3) void k_node(NodeArgs a) {
   static_assert(M == 64, "128 x 128 nodes take k_node_half");
@@ -86,17 +101,18 @@ __global__ __launch_bounds__(M * M / 16, 3) void k_node(NodeArgs a) {
   SL::fill_twiddles(wtab, a.tw, a.tw_n);
   const int tw_step = a.tw_n / (2 * M);  // POLY only: table step of w = exp(-2 pi i / 2M)
 
-  if constexpr (A == 2 && P == 4 && !POLY) {
-    // ---- 1 (children of a polyphase parent). Every stored source row (0 .. 64, 128 columns) is
-    // read once, by half a wavefront: a lane takes two adjacent columns of both column blocks
-    // and of all four components (16-byte loads).  Row rho contributes to row rho of the node
-    // directly and, through the conjugate symmetry of the stored spectra
-    // W_q[128 - rho][-c] = s_q(c) conj(W_q[rho][c]), to row 64 - rho (the alias row 128 - rho);
-    // rows 0 and 64, which mirror onto themselves, both fold onto row 0.  The direct parts are
-    // written to LDS first, the second parts are added after a barrier.  Filter table:
-    // [row][column block][column parity][column pair][component].
-    const float4 *src4 = reinterpret_cast<const float4 *>(a.src + static_cast<size_t>(s) * 4 * 65 * S);
-    const float4 *f4 = reinterpret_cast<const float4 *>(a.filt + static_cast<size_t>(f) * 4 * S * S);
+  if constexpr (A == 2) {
+    // ---- 1 (source twice as large as the node). Every stored source row (0 .. 64, 128 columns)
+    // is read once, by half a wavefront: a lane takes two adjacent columns of both column
+    // blocks and of all P components (16-byte loads).  Row rho contributes to row rho of the
+    // node directly and, through the conjugate symmetry of the stored spectra
+    // W_q[128 - rho][-c] = s_q(c) conj(W_q[rho][c]) (s_q = 1 for a plain spectrum), to row
+    // 64 - rho (the alias row 128 - rho); rows 0 and 64, which mirror onto themselves, both
+    // fold onto row 0.  The direct parts are written to LDS first, the second parts are added
+    // after a barrier.  Filter table: [row][column block][column parity][column pair][component].
+    static_assert(!POLY, "polyphase nodes are 128 x 128");
+    const float4 *src4 = reinterpret_cast<const float4 *>(a.src + static_cast<size_t>(s) * P * 65 * S);
+    const float *ft = a.filt + static_cast<size_t>(f) * P * S * S;
     const int cq = tid & 31, st = tid >> 5;
     float2 z2[8][2];
 #pragma unroll
@@ -104,53 +120,57 @@ __global__ __launch_bounds__(M * M / 16, 3) void k_node(NodeArgs a) {
       const int row = st + 8 * i;
       const bool first = row == 0;
       const int row2 = first ? 64 : S - row;
-      float4 w[2][4], d[2][2], m[2][2];
+      float4 w[2][P];
+      float d[2][2][P], m[2][2][P];
 #pragma unroll
       for (int ac = 0; ac < 2; ++ac) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) w[ac][q] = src4[(q * 65 + row) * (S / 2) + 32 * ac + cq];
+        for (int q = 0; q < P; ++q) w[ac][q] = src4[(q * 65 + row) * (S / 2) + 32 * ac + cq];
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
-          d[ac][e] = f4[((row * 2 + ac) * 2 + e) * 32 + cq];
           const int idx = first ? 32 * ac + cq : (64 - 32 * ac - cq - e) & 63;
-          m[ac][e] = f4[((row2 * 2 + (idx >> 5)) * 2 + e) * 32 + (idx & 31)];
+          load_comps<P>(d[ac][e], ft, ((row * 2 + ac) * 2 + e) * 32 + cq);
+          load_comps<P>(m[ac][e], ft, ((row2 * 2 + (idx >> 5)) * 2 + e) * 32 + (idx & 31));
         }
       }
       float4 zd = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-      for (int ac = 0; ac < 2; ++ac) {
-        const float dq0[4] = {d[ac][0].x, d[ac][0].y, d[ac][0].z, d[ac][0].w};
-        const float dq1[4] = {d[ac][1].x, d[ac][1].y, d[ac][1].z, d[ac][1].w};
+      for (int ac = 0; ac < 2; ++ac)
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          zd.x = fmaf(w[ac][q].x, dq0[q], zd.x);
-          zd.y = fmaf(w[ac][q].y, dq0[q], zd.y);
-          zd.z = fmaf(w[ac][q].z, dq1[q], zd.z);
-          zd.w = fmaf(w[ac][q].w, dq1[q], zd.w);
+        for (int q = 0; q < P; ++q) {
+          zd.x = fmaf(w[ac][q].x, d[ac][0][q], zd.x);
+          zd.y = fmaf(w[ac][q].y, d[ac][0][q], zd.y);
+          zd.z = fmaf(w[ac][q].z, d[ac][1][q], zd.z);
+          zd.w = fmaf(w[ac][q].w, d[ac][1][q], zd.w);
         }
-      }
       *reinterpret_cast<float4 *>(area + row * RS + 2 * cq) = zd;
       if (first) {
 #pragma unroll
         for (int ac = 0; ac < 2; ++ac)
 #pragma unroll
-          for (int q = 0; q < 4; ++q) w[ac][q] = src4[(q * 65 + 64) * (S / 2) + 32 * ac + cq];
+          for (int q = 0; q < P; ++q) w[ac][q] = src4[(q * 65 + 64) * (S / 2) + 32 * ac + cq];
       }
       float4 zs = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
       for (int ac = 0; ac < 2; ++ac) {
-        // s = (1, sc, -1, -sc), sc = -1 except for column 0
-        const float sc0 = first ? 1.f : (ac == 0 && cq == 0) ? 1.f : -1.f;
-        const float sc1 = first ? 1.f : -1.f;
-        const float sn = first ? 1.f : -1.f;
-        const float g0[4] = {m[ac][0].x, sc0 * m[ac][0].y, sn * m[ac][0].z, sn * sc0 * m[ac][0].w};
-        const float g1[4] = {m[ac][1].x, sc1 * m[ac][1].y, sn * m[ac][1].z, sn * sc1 * m[ac][1].w};
+        if constexpr (P == 4) {
+          // s = (1, sc, -1, -sc), sc = -1 except for column 0
+          const float sc0 = first ? 1.f : (ac == 0 && cq == 0) ? 1.f : -1.f;
+          const float sc1 = first ? 1.f : -1.f;
+          const float sn = first ? 1.f : -1.f;
+          m[ac][0][1] *= sc0;
+          m[ac][0][2] *= sn;
+          m[ac][0][3] *= sn * sc0;
+          m[ac][1][1] *= sc1;
+          m[ac][1][2] *= sn;
+          m[ac][1][3] *= sn * sc1;
+        }
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          zs.x = fmaf(w[ac][q].x, g0[q], zs.x);
-          zs.y = fmaf(w[ac][q].y, g0[q], zs.y);
-          zs.z = fmaf(w[ac][q].z, g1[q], zs.z);
-          zs.w = fmaf(w[ac][q].w, g1[q], zs.w);
+        for (int q = 0; q < P; ++q) {
+          zs.x = fmaf(w[ac][q].x, m[ac][0][q], zs.x);
+          zs.y = fmaf(w[ac][q].y, m[ac][0][q], zs.y);
+          zs.z = fmaf(w[ac][q].z, m[ac][1][q], zs.z);
+          zs.w = fmaf(w[ac][q].w, m[ac][1][q], zs.w);
         }
       }
       const float cj = first ? 1.f : -1.f;
@@ -334,7 +354,7 @@ __global__ __launch_bounds__(M * M / 16, 3) void k_node(NodeArgs a) {
 //   lowpass as in k_node, with the row-filtered values parked in registers while the
 //   unfiltered plane is still being read, then written over it.
 template <int A, int P, bool POLY>
-__global__ __launch_bounds__(512, 2) void k_node_half(NodeArgs a) {
+__global__ __launch_bounds__(512, 4) void k_node_half(NodeArgs a) {
   constexpr int M = 128, T = 8, NT = 512, S = M * A;
   constexpr int RSR = 152, RSC = 76;
   constexpr int DEC = M / kOut, R = 4 * DEC, NTAP = 2 * R + 1;
@@ -351,6 +371,10 @@ __global__ __launch_bounds__(512, 2) void k_node_half(NodeArgs a) {
   const int pr = POLY ? (item >> 1) & 1 : 0, pc = POLY ? item & 1 : 0;
   for (int idx = tid; idx < M; idx += NT) wtab[idx] = a.tw[(idx / T) * (idx % T) * (a.tw_n / M)];
   const int tw_step = a.tw_n / (2 * M);
+  // polyphase nodes: w^k = exp(-2 pi i k / 2M), k < 2M, behind the transforms' twiddles
+  float2 *w2m = wtab + M;
+  if (POLY)
+    for (int idx = tid; idx < 2 * M; idx += NT) w2m[idx] = a.tw[idx * tw_step];
   const int r = tid / T, t = tid % T;    // row roles: rows r and r + 64, columns t + 8 i
   const int c = tid % 64, t1 = tid / 64; // column roles: columns c and c + 64, rows t1 + 8 i
   const float2 *wl = wtab + t, *wlc = wtab + t1;
@@ -427,6 +451,103 @@ __global__ __launch_bounds__(512, 2) void k_node_half(NodeArgs a) {
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < 16; ++i) vh[1][i] = area[r * RSR + t + T * i];
+    __syncthreads();
+    fft_core_tab<16, T, true, false>(vh[1], t, area + r * RSR, T + 1, 1, wl, T);
+  } else if constexpr (A == 2 && P == 1) {
+    // Source twice as large as the node (the spectrum of x, or of a 256 x 256 parent).  A wave
+    // takes one stored source row (0 .. 128; 256 columns) at a time, a lane two adjacent columns
+    // of both column blocks (16-byte loads).  Row rho contributes to row rho of the node
+    // directly and, as conj(W[rho][c]) = W[256 - rho][-c], to row 128 - rho (the alias row
+    // 256 - rho); rows 0 and 128 both fold onto row 0.  The node's rows go through LDS in two
+    // halves: first the direct parts are written, then, after a barrier, the mirrored parts
+    // are added (every element by exactly one lane).  So every row of the source is read
+    // twice (a row's direct part belongs to one half of the node, its mirrored part to the other).
+    // Filter table: [row][column block][column parity][column pair].
+    const float4 *src4 = reinterpret_cast<const float4 *>(a.src + static_cast<size_t>(s) * (S / 2 + 1) * S);
+    const float *ft = a.filt + static_cast<size_t>(f) * S * S;
+    const int cp = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int c0 = (M - 2 * cp) & (M - 1), c1 = M - 1 - 2 * cp;  // columns of the mirrored parts
+    // polyphase alias signs (-1)^(a.p): of the direct parts (row block 0), and of the mirrored
+    // parts (row block 1, column block of the mirrored column)
+    const float sg1 = (POLY && pc) ? -1.f : 1.f;
+    float sm[2][2];
+    int mi[2][2];  // table index of the mirrored column, without the row
+#pragma unroll
+    for (int ac = 0; ac < 2; ++ac)
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        const int idx = (128 - 64 * ac - cp - e) & 127;
+        mi[ac][e] = ((idx >> 6) * 2 + e) * 64 + (idx & 63);
+        sm[ac][e] = (POLY && ((pr + (idx >> 6) * pc) & 1)) ? -1.f : 1.f;
+      }
+    auto direct = [&](int row, float sr) {  // row of the source and of the table; sr: sign of its row block
+      const float4 w0 = src4[row * (S / 2) + cp], w1 = src4[row * (S / 2) + 64 + cp];
+      const float d00 = ft[((row * 2 + 0) * 2 + 0) * 64 + cp] * sr, d01 = ft[((row * 2 + 0) * 2 + 1) * 64 + cp] * sr;
+      const float d10 = ft[((row * 2 + 1) * 2 + 0) * 64 + cp] * (sr * sg1),
+                  d11 = ft[((row * 2 + 1) * 2 + 1) * 64 + cp] * (sr * sg1);
+      return make_float4(w0.x * d00 + w1.x * d10, w0.y * d00 + w1.y * d10, w0.z * d01 + w1.z * d11,
+                         w0.w * d01 + w1.w * d11);
+    };
+    auto mirrored = [&](int row) {  // conj of the products with table row 256 - row, mirrored columns
+      const float4 w0 = src4[row * (S / 2) + cp], w1 = src4[row * (S / 2) + 64 + cp];
+      const float *fr = ft + (S - row) * 2 * 2 * 64;
+      const float m00 = fr[mi[0][0]] * sm[0][0], m01 = fr[mi[0][1]] * sm[0][1];
+      const float m10 = fr[mi[1][0]] * sm[1][0], m11 = fr[mi[1][1]] * sm[1][1];
+      return make_float4(w0.x * m00 + w1.x * m10, -(w0.y * m00 + w1.y * m10), w0.z * m01 + w1.z * m11,
+                         -(w0.w * m01 + w1.w * m11));
+    };
+    auto add_at = [&](int slot, int ca, int cb, float4 z) {
+      float2 *tr = area + slot * RSR;
+      const float2 oa = tr[ca], ob = tr[cb];
+      tr[ca] = make_float2(oa.x + z.x, oa.y + z.y);
+      tr[cb] = make_float2(ob.x + z.z, ob.y + z.w);
+    };
+    auto take_rows = [&](float2 (&v)[16], int h) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        float2 z = area[r * RSR + t + T * i];
+        if (POLY) {
+          const float2 w = w2m[(pr * (r + 64 * h) + pc * (t + T * i)) & (2 * M - 1)];
+          z = make_float2(z.x * w.x + z.y * w.y, z.y * w.x - z.x * w.y);  // * conj(w)
+        }
+        v[i] = z;
+      }
+    };
+    const float sr1 = (POLY && pr) ? -1.f : 1.f;
+    // first half: direct parts of rows 0 .. 63
+#pragma unroll 4
+    for (int i = 0; i < 8; ++i) {
+      const int row = wv + 8 * i;
+      *reinterpret_cast<float4 *>(area + row * RSR + 2 * cp) = direct(row, 1.f);
+    }
+    __syncthreads();
+    // mirrored parts of source rows 65 .. 127 (rows 63 .. 1 of the node); row 128 is the alias of row 0
+#pragma unroll 4
+    for (int i = 0; i < 8; ++i) {
+      const int row = 64 + wv + 8 * i;
+      if (row != 64) add_at(M - row, c0, c1, mirrored(row));
+    }
+    if (wv == 0) add_at(0, 2 * cp, 2 * cp + 1, direct(M, sr1));
+    __syncthreads();
+    take_rows(vh[0], 0);
+    __syncthreads();
+    fft_core_tab<16, T, true, false>(vh[0], t, area + r * RSR, T + 1, 1, wl, T);  // ends with a barrier
+    // second half: rows 64 .. 127 through slots 0 .. 63; direct parts, then the mirrored parts of
+    // source rows 1 .. 64
+#pragma unroll 4
+    for (int i = 0; i < 8; ++i) {
+      const int row = 64 + wv + 8 * i;
+      *reinterpret_cast<float4 *>(area + (row - 64) * RSR + 2 * cp) = direct(row, 1.f);
+    }
+    __syncthreads();
+#pragma unroll 4
+    for (int i = 0; i < 8; ++i) {
+      const int row = i == 0 && wv == 0 ? 64 : wv + 8 * i;  // row 0 has no mirrored part: wave 0 takes row 64
+      add_at(64 - row, c0, c1, mirrored(row));
+    }
+    __syncthreads();
+    take_rows(vh[1], 1);
     __syncthreads();
     fft_core_tab<16, T, true, false>(vh[1], t, area + r * RSR, T + 1, 1, wl, T);
   } else {
@@ -595,7 +716,7 @@ __global__ __launch_bounds__(512, 2) void k_node_half(NodeArgs a) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         float2 val = vh[h][i];
-        if (POLY) val = c_mul(val, a.tw[((pr * row + pc * (t + T * i)) * tw_step) & (a.tw_n - 1)]);
+        if (POLY) val = c_mul(val, w2m[(pr * row + pc * (t + T * i)) & (2 * M - 1)]);
         up[T * i] = val;
       }
     }
@@ -636,7 +757,7 @@ hipError_t launch_node_t(const NodeArgs &a, hipStream_t st) {
                            pts * (4.0 * P * A * A + 4.0 + 2.0) + fft2_flops(M) * (a.uout ? 0 : 1)),
                   st);
   if constexpr (M == 128) {
-    const size_t lds_h = (64 * 152 + 128) * sizeof(float2);
+    const size_t lds_h = (64 * 152 + 128 + (POLY ? 256 : 0)) * sizeof(float2);
     static unsigned long long lds_ok = 0;
     hipError_t e = allow_large_lds(reinterpret_cast<const void *>(k_node_half<A, P, POLY>), lds_ok);
     if (e != hipSuccess) return e;
