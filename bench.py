@@ -163,9 +163,10 @@ def main():
                     help="time the backward pass (gradient with respect to the input of a "
                          "seeded random dL/dS; recomputes the forward cascade inside) instead "
                          "of the forward transform")
-    ap.add_argument("--node-kernels", action="store_true",
-                    help="2-D 256x256 / 128x128 plans: walk the tree with one workgroup per node "
-                         "(SCAT_PLAN_NODE_KERNELS) instead of the default schedule")
+    ap.add_argument("--pass-kernels", action="store_true",
+                    help="2-D 256x256 / 128x128 plans: row and column passes over the whole batch "
+                         "(SCAT_PLAN_PASS_KERNELS) instead of the default walk of the tree with "
+                         "one workgroup per node")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (a kernel of known "
                          "traffic, to calibrate profiler byte counters)")
@@ -191,7 +192,7 @@ def main():
         sys.exit(1)
     torch.cuda.set_device(0)
     x = torch.from_numpy(x_host).cuda()
-    plan = scat.Scattering(cfg["shape"], cfg["J"], cfg["LQ"], node_kernels=args.node_kernels)
+    plan = scat.Scattering(cfg["shape"], cfg["J"], cfg["LQ"], node_kernels=not args.pass_kernels)
     out = torch.empty((P, plan.K) + plan.out_shape, dtype=torch.float32, device="cuda")
     g_host = None
     if args.backward:
@@ -248,7 +249,7 @@ def main():
     per_kernel = {}
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic_%s%s%s.txt"
                          % (TRAFFIC_TAGS.get(wl, "none"), "_backward" if args.backward else "",
-                            "_node_kernels" if args.node_kernels else ""))
+                            "_pass_kernels" if args.pass_kernels else ""))
     if os.path.exists(tpath):
         with open(tpath) as f:
             for line in f:
@@ -315,7 +316,7 @@ def main():
         "config": {"workload": cfg["name"], "planes_per_step": P, "channels": C,
                    "J": cfg["J"], "LQ": cfg["LQ"], "shape": list(cfg["shape"]), "max_order": 2,
                    "coefficients": plan.K,
-                   "schedule": "node_kernels" if args.node_kernels else "default"},
+                   "schedule": "pass_kernels" if args.pass_kernels else "default"},
         "planes_per_s": P / (ms_per_step * 1e-3),
         "wall_ms_per_step": wall / args.steps * 1e3,
         "roofline": roofline,

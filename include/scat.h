@@ -122,18 +122,23 @@ scat_status scat_plan_create_padded_host(scat_plan **out_plan, int dims, const i
  * output has sides shape >> max(J-o, 0).  With o >= J nothing is subsampled and the output,
  * read at the samples 2^J k, is the section-2 definition itself.  flags: bitwise OR of
  * SCAT_PLAN_PADDED (signals of any size, see scat_plan_create_padded),
- * SCAT_PLAN_HOST_ONLY (no GPU, see scat_plan_create_host) and SCAT_PLAN_NODE_KERNELS (below).  scat_backward limits the size of
+ * SCAT_PLAN_HOST_ONLY (no GPU, see scat_plan_create_host), SCAT_PLAN_NODE_KERNELS and
+ * SCAT_PLAN_PASS_KERNELS (below).  scat_backward limits the size of
  * the output grid in 2-D (see there), which limits o.
  */
 #define SCAT_PLAN_PADDED 1
 #define SCAT_PLAN_HOST_ONLY 2
-/* 2-D plans of 256 x 256 at J = 3 or 128 x 128 at J = 2: scat_forward walks the tree with
- * one workgroup per node (the "Implementation" paragraph's depth-first walk: a node's inverse
- * transform, modulus, lowpass and, for parents, spectrum never leave the compute unit; only
- * the spectra of the input and of first-order moduli with children are kept in scratch)
- * instead of the row and column passes over the whole batch.  Same results to rounding.
- * Ignored by other shapes and by scat_backward. */
+/* 2-D plans of 256 x 256 at J = 3 or 128 x 128 at J = 2 (without oversampling): scat_forward
+ * walks the tree with one workgroup per node (the "Implementation" paragraph's depth-first
+ * walk: a node's inverse transform, modulus, lowpass and, for parents, spectrum never leave
+ * the compute unit; only the spectra of the input and of first-order moduli with children are
+ * kept in scratch).  This is what these plans do by default; SCAT_PLAN_NODE_KERNELS is kept
+ * for callers that ask for it by name and changes nothing.  SCAT_PLAN_PASS_KERNELS selects
+ * the row and column passes over the whole batch instead (the schedule of every other 2-D
+ * shape), for comparison: same results to rounding.  Both are ignored by other shapes and by
+ * scat_backward. */
 #define SCAT_PLAN_NODE_KERNELS 4
+#define SCAT_PLAN_PASS_KERNELS 8
 scat_status scat_plan_create_ex(scat_plan **out_plan, int dims, const int *shape, int J, int LQ,
                                 int max_order, int oversampling, int flags);
 

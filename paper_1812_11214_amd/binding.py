@@ -114,10 +114,12 @@ def scat_plan_create(shape, J, LQ, max_order=2):
 SCAT_PLAN_PADDED = 1
 SCAT_PLAN_HOST_ONLY = 2
 SCAT_PLAN_NODE_KERNELS = 4
+SCAT_PLAN_PASS_KERNELS = 8
 
 
 def scat_plan_create_ex(shape, J, LQ, max_order=2, oversampling=0, flags=0):
-    """General plan creation: oversampling >= 0, flags = SCAT_PLAN_PADDED | SCAT_PLAN_HOST_ONLY."""
+    """General plan creation: oversampling >= 0, flags = SCAT_PLAN_PADDED | SCAT_PLAN_HOST_ONLY |
+    SCAT_PLAN_NODE_KERNELS | SCAT_PLAN_PASS_KERNELS."""
     shape = tuple(int(s) for s in shape)
     arr = (ctypes.c_int * len(shape))(*shape)
     handle = ctypes.c_void_p()
@@ -267,12 +269,12 @@ class Scattering:
     scattering (LQ = the largest degree L)."""
 
     def __init__(self, shape, J, LQ, max_order=2, host_only=False, padded=False, oversampling=0,
-                 node_kernels=False):
+                 node_kernels=True):
         """padded=True: signals of any size, extended symmetrically to a periodic grid of
         power-of-two sides (scat_plan_create_padded); else `shape` is that periodic grid.
         oversampling=o: every signal 2^o times finer than the default schedule.
-        node_kernels=True: 256x256/J=3 and 128x128/J=2 plans walk the tree one workgroup per
-        node (SCAT_PLAN_NODE_KERNELS)."""
+        node_kernels=False: 256x256/J=3 and 128x128/J=2 plans, which by default walk the tree one
+        workgroup per node, use the row and column passes instead (SCAT_PLAN_PASS_KERNELS)."""
         self.shape = tuple(int(s) for s in shape)
         self.dims = len(self.shape)
         self.J, self.LQ, self.max_order = int(J), int(LQ), int(max_order)
@@ -280,7 +282,7 @@ class Scattering:
         self._plan = None
         self.oversampling = int(oversampling)
         flags = ((SCAT_PLAN_PADDED if padded else 0) | (SCAT_PLAN_HOST_ONLY if host_only else 0)
-                 | (SCAT_PLAN_NODE_KERNELS if node_kernels else 0))
+                 | (0 if node_kernels else SCAT_PLAN_PASS_KERNELS))
         self._plan = scat_plan_create_ex(self.shape, J, LQ, max_order, oversampling, flags)
         self.K = scat_plan_num_coeffs(self._plan)
         self.out_shape = scat_plan_out_shape(self._plan, self.dims)

@@ -609,7 +609,7 @@ scat_status create_3d(scat_plan **out_plan, const int *user_shape, int J, int L,
 
 scat_status create_common(scat_plan **out_plan, int dims, const int *user_shape, int J, int LQ,
                           int max_order, bool device, bool padded = false, int oversampling = 0,
-                          bool node_kernels = false) {
+                          bool node_kernels = true) {
   if (out_plan == nullptr) return SCAT_ERR_NULL;
   *out_plan = nullptr;
   if (user_shape == nullptr) return SCAT_ERR_NULL;
@@ -2156,13 +2156,13 @@ scat_status scat_plan_create_padded_host(scat_plan **out_plan, int dims, const i
 
 scat_status scat_plan_create_ex(scat_plan **out_plan, int dims, const int *shape, int J, int LQ,
                                 int max_order, int oversampling, int flags) {
-  if (flags & ~7) {
+  if (flags & ~15) {
     if (out_plan != nullptr) *out_plan = nullptr;
     return SCAT_ERR_ARG;
   }
   return create_common(out_plan, dims, shape, J, LQ, max_order, (flags & SCAT_PLAN_HOST_ONLY) == 0,
                        (flags & SCAT_PLAN_PADDED) != 0, oversampling,
-                       (flags & SCAT_PLAN_NODE_KERNELS) != 0);
+                       (flags & SCAT_PLAN_PASS_KERNELS) == 0);
 }
 
 scat_status scat_plan_grid_shape(const scat_plan *plan, int *shape_out) {

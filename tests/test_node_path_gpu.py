@@ -69,12 +69,14 @@ def test_node_schedule_padded_200x200():
 
 
 def test_node_schedule_is_the_one_that_runs():
-    """With the flag the launches are the whole-node kernels; without it the pass kernels."""
+    """By default the launches are the whole-node kernels; with SCAT_PLAN_PASS_KERNELS the pass
+    kernels."""
     import torch
     x = torch.from_numpy(workloads.planes(2, 2)).cuda()
     names = {}
     for flag in (True, False):
-        plan = scat.Scattering((256, 256), 3, 8, node_kernels=flag)
+        plan = (scat.Scattering((256, 256), 3, 8) if flag
+                else scat.Scattering((256, 256), 3, 8, node_kernels=False))
         try:
             plan.timing_begin(None)
             plan.forward(x)
@@ -85,7 +87,24 @@ def test_node_schedule_is_the_one_that_runs():
             plan.close()
     assert any(k.startswith("k_node_half<") for k in names[True]), names[True]
     assert not any(k.startswith("k_rows_fused") for k in names[True]), names[True]
-    # the default schedule: row and column passes (and the whole-node kernel only for the
+    # the pass schedule: row and column passes (and the whole-node kernel only for the
     # 64 x 64 children of the 128 x 128 nodes)
     assert any(k.startswith("k_rows_fused") for k in names[False]), names[False]
     assert not any(k.startswith("k_node_half<") for k in names[False]), names[False]
+
+
+@pytest.mark.parametrize("n,J,L,batch", [(256, 3, 8, 3), (128, 2, 6, 9)])
+def test_pass_schedule_still_matches(n, J, L, batch):
+    """The row-and-column-pass schedule of the shapes whose default is the whole-node one."""
+    rng = np.random.default_rng(77 * n + L)
+    x = rng.standard_normal((batch, n, n)).astype(np.float32)
+    plan = scat.Scattering((n, n), J, L, node_kernels=False)
+    try:
+        got = gpu_forward(plan, x)
+        rows = plan.coeff_index()
+    finally:
+        plan.close()
+    want = oracle.scattering2d(x, J, L)
+    errs = per_order_errors(got, want, order_of_channels(rows), x)
+    print("passes", n, J, L, batch, errs, flush=True)
+    assert max(errs.values()) <= TOL, errs
