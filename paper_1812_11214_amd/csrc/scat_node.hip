@@ -373,6 +373,7 @@ __global__ __launch_bounds__(512, 4) void k_node_half(NodeArgs a) {
   const int tw_step = a.tw_n / (2 * M);
   // polyphase nodes: w^k = exp(-2 pi i k / 2M), k < 2M, behind the transforms' twiddles
   float2 *w2m = wtab + M;
+  float2 *row64 = w2m + 2 * M;  // 64 elements: row 64 of the packed column spectra (parents only)
   if (POLY)
     for (int idx = tid; idx < 2 * M; idx += NT) w2m[idx] = a.tw[idx * tw_step];
   const int r = tid / T, t = tid % T;    // row roles: rows r and r + 64, columns t + 8 i
@@ -686,39 +687,56 @@ __global__ __launch_bounds__(512, 4) void k_node_half(NodeArgs a) {
   }
   if (a.uout == nullptr) return;
 
-  // ---- 5. spectrum of the modulus for the children: forward columns, transposition back,
-  // forward rows; rows 0 .. 64 are stored
+  // ---- 5. spectrum of the modulus for the children; rows 0 .. 64 are stored.  The modulus is
+  // real: a thread's two columns c and c + 64 travel through ONE column transform as
+  // z = (u_c + i u_(c+64)) / 2, and the row threads take them apart again on the way in,
+  // U_c[k] = Z[k] + conj(Z[-k]), U_(c+64)[k] = -i (Z[k] - conj(Z[-k])); only rows 0 .. 64 are
+  // transformed along the rows (row 64 by eight lanes of the first wavefront on their own).
   __syncthreads();
+  {
+    float2 z[16];
 #pragma unroll
-  for (int hc = 0; hc < 2; ++hc) {
+    for (int i = 0; i < 16; ++i) z[i] = make_float2(0.5f * u[0][i], 0.5f * u[1][i]);
+    fft_core_tab<16, T, false, false>(z, t1, area + c, T * RSC, RSC, wlc, T);
 #pragma unroll
-    for (int i = 0; i < 16; ++i) w[hc][i] = make_float2(u[hc][i], 0.f);
-    fft_core_tab<16, T, false, false>(w[hc], t1, area + c, T * RSC, RSC, wlc, T);
+    for (int i = 0; i < 16; ++i) area[(t1 + T * i) * RSC + c] = z[i];
   }
-#pragma unroll
-  for (int hc = 0; hc < 2; ++hc) {
-#pragma unroll
-    for (int i = 0; i < 16; ++i) area[(t1 + T * i) * RSC + c] = w[hc][i];
-    __syncthreads();
+  __syncthreads();
+  {
+    const int rm = (M - r) & (M - 1);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      vh[0][8 * hc + i] = area[r * RSC + t + T * i];
-      vh[1][8 * hc + i] = area[(r + 64) * RSC + t + T * i];
+      const float2 za = area[r * RSC + t + T * i], zb = area[rm * RSC + t + T * i];
+      vh[0][i] = make_float2(za.x + zb.x, za.y - zb.y);
+      vh[0][8 + i] = make_float2(za.y + zb.y, zb.x - za.x);
     }
-    __syncthreads();
+    if (tid < 64) row64[tid] = area[64 * RSC + tid];  // kept aside: the row transforms reuse the area
   }
+  __syncthreads();
+  fft_core_tab<16, T, false, false>(vh[0], t, area + r * RSR, T + 1, 1, wl, T);  // ends with a barrier
+  {
+    float2 *up = a.uout + ((static_cast<size_t>(s) * I + item) * (M / 2 + 1) + r) * M + t;
 #pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    fft_core_tab<16, T, false, false>(vh[h], t, area + r * RSR, T + 1, 1, wl, T);
-    const int row = r + 64 * h;
-    if (row <= M / 2) {
-      float2 *up = a.uout + ((static_cast<size_t>(s) * I + item) * (M / 2 + 1) + row) * M + t;
+    for (int i = 0; i < 16; ++i) {
+      float2 val = vh[0][i];
+      if (POLY) val = c_mul(val, w2m[(pr * r + pc * (t + T * i)) & (2 * M - 1)]);
+      up[T * i] = val;
+    }
+  }
+  if (tid < T) {
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        float2 val = vh[h][i];
-        if (POLY) val = c_mul(val, w2m[(pr * row + pc * (t + T * i)) & (2 * M - 1)]);
-        up[T * i] = val;
-      }
+    for (int i = 0; i < 8; ++i) {
+      const float2 za = row64[t + T * i];
+      vh[0][i] = make_float2(2.f * za.x, 0.f);
+      vh[0][8 + i] = make_float2(2.f * za.y, 0.f);
+    }
+    fft_core_tab<16, T, false, true>(vh[0], t, area, T + 1, 1, wl, T);
+    float2 *up = a.uout + ((static_cast<size_t>(s) * I + item) * (M / 2 + 1) + 64) * M + t;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      float2 val = vh[0][i];
+      if (POLY) val = c_mul(val, w2m[(pr * 64 + pc * (t + T * i)) & (2 * M - 1)]);
+      up[T * i] = val;
     }
   }
 }
@@ -757,7 +775,7 @@ hipError_t launch_node_t(const NodeArgs &a, hipStream_t st) {
                            pts * (4.0 * P * A * A + 4.0 + 2.0) + fft2_flops(M) * (a.uout ? 0 : 1)),
                   st);
   if constexpr (M == 128) {
-    const size_t lds_h = (64 * 152 + 128 + (POLY ? 256 : 0)) * sizeof(float2);
+    const size_t lds_h = (64 * 152 + 128 + 256 + 64) * sizeof(float2);
     static unsigned long long lds_ok = 0;
     hipError_t e = allow_large_lds(reinterpret_cast<const void *>(k_node_half<A, P, POLY>), lds_ok);
     if (e != hipSuccess) return e;
