@@ -400,7 +400,7 @@ __global__ __launch_bounds__(512, 4) void k_node_half(NodeArgs a) {
     const int col_m0 = (M - 2 * cp) & (M - 1), col_m1 = M - 1 - 2 * cp;
     const float sc0 = cp == 0 ? 1.f : -1.f;                // s_1(c) = -s_3(c) for c = 2 cp; -1 for 2 cp + 1
     float2 zm[8][2];  // second rows (64 .. 127), kept until the first half has been transformed
-#pragma unroll 2
+#pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int row = wv + 8 * i;
       const bool first = i == 0 && wv == 0;  // row 0: its partner is row 64, read directly
