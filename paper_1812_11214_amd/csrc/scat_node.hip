@@ -115,67 +115,143 @@ __global__ __launch_bounds__(M * M / 16, 3) void k_node(NodeArgs a) {
     const float *ft = a.filt + static_cast<size_t>(f) * P * S * S;
     const int cq = tid & 31, st = tid >> 5;
     float2 z2[8][2];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int row = st + 8 * i;
-      const bool first = row == 0;
-      const int row2 = first ? 64 : S - row;
-      float4 w[2][P];
-      float d[2][2][P], m[2][2][P];
-#pragma unroll
-      for (int ac = 0; ac < 2; ++ac) {
-#pragma unroll
-        for (int q = 0; q < P; ++q) w[ac][q] = src4[(q * 65 + row) * (S / 2) + 32 * ac + cq];
-#pragma unroll
+    if constexpr (P == 4) {
+      // (four components: a row's sixteen 16-byte loads at once; measured faster than the
+      // pipelined form below, which is the faster one for a single component)
+  #pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int row = st + 8 * i;
+        const bool first = row == 0;
+        const int row2 = first ? 64 : S - row;
+        float4 w[2][P];
+        float d[2][2][P], m[2][2][P];
+  #pragma unroll
+        for (int ac = 0; ac < 2; ++ac) {
+  #pragma unroll
+          for (int q = 0; q < P; ++q) w[ac][q] = src4[(q * 65 + row) * (S / 2) + 32 * ac + cq];
+  #pragma unroll
+          for (int e = 0; e < 2; ++e) {
+            const int idx = first ? 32 * ac + cq : (64 - 32 * ac - cq - e) & 63;
+            load_comps<P>(d[ac][e], ft, ((row * 2 + ac) * 2 + e) * 32 + cq);
+            load_comps<P>(m[ac][e], ft, ((row2 * 2 + (idx >> 5)) * 2 + e) * 32 + (idx & 31));
+          }
+        }
+        float4 zd = make_float4(0.f, 0.f, 0.f, 0.f);
+  #pragma unroll
+        for (int ac = 0; ac < 2; ++ac)
+  #pragma unroll
+          for (int q = 0; q < P; ++q) {
+            zd.x = fmaf(w[ac][q].x, d[ac][0][q], zd.x);
+            zd.y = fmaf(w[ac][q].y, d[ac][0][q], zd.y);
+            zd.z = fmaf(w[ac][q].z, d[ac][1][q], zd.z);
+            zd.w = fmaf(w[ac][q].w, d[ac][1][q], zd.w);
+          }
+        *reinterpret_cast<float4 *>(area + row * RS + 2 * cq) = zd;
+        if (first) {
+  #pragma unroll
+          for (int ac = 0; ac < 2; ++ac)
+  #pragma unroll
+            for (int q = 0; q < P; ++q) w[ac][q] = src4[(q * 65 + 64) * (S / 2) + 32 * ac + cq];
+        }
+        float4 zs = make_float4(0.f, 0.f, 0.f, 0.f);
+  #pragma unroll
+        for (int ac = 0; ac < 2; ++ac) {
+          if constexpr (P == 4) {
+            // s = (1, sc, -1, -sc), sc = -1 except for column 0
+            const float sc0 = first ? 1.f : (ac == 0 && cq == 0) ? 1.f : -1.f;
+            const float sc1 = first ? 1.f : -1.f;
+            const float sn = first ? 1.f : -1.f;
+            m[ac][0][1] *= sc0;
+            m[ac][0][2] *= sn;
+            m[ac][0][3] *= sn * sc0;
+            m[ac][1][1] *= sc1;
+            m[ac][1][2] *= sn;
+            m[ac][1][3] *= sn * sc1;
+          }
+  #pragma unroll
+          for (int q = 0; q < P; ++q) {
+            zs.x = fmaf(w[ac][q].x, m[ac][0][q], zs.x);
+            zs.y = fmaf(w[ac][q].y, m[ac][0][q], zs.y);
+            zs.z = fmaf(w[ac][q].z, m[ac][1][q], zs.z);
+            zs.w = fmaf(w[ac][q].w, m[ac][1][q], zs.w);
+          }
+        }
+        const float cj = first ? 1.f : -1.f;
+        z2[i][0] = make_float2(zs.x, cj * zs.y);
+        z2[i][1] = make_float2(zs.z, cj * zs.w);
+      }
+    } else {
+      // One unit of work = one column block (ac) of one source row; the loads of the next units
+      // are issued before the arithmetic of the current one (left to itself the compiler waits
+      // for each row's loads before it issues the next row's).
+      struct Unit {
+        float4 w[P];
+        float d[2][P], m[2][P];
+      };
+      constexpr int DEPTH = P == 4 ? 2 : 4;  // units in flight
+      auto load_unit = [&](Unit &un, int u) {
+        const int i = u >> 1, ac = u & 1;
+        const int row = st + 8 * i;
+        const bool first = row == 0;
+        const int row2 = first ? 64 : S - row;
+  #pragma unroll
+        for (int q = 0; q < P; ++q) un.w[q] = src4[(q * 65 + row) * (S / 2) + 32 * ac + cq];
+  #pragma unroll
         for (int e = 0; e < 2; ++e) {
           const int idx = first ? 32 * ac + cq : (64 - 32 * ac - cq - e) & 63;
-          load_comps<P>(d[ac][e], ft, ((row * 2 + ac) * 2 + e) * 32 + cq);
-          load_comps<P>(m[ac][e], ft, ((row2 * 2 + (idx >> 5)) * 2 + e) * 32 + (idx & 31));
+          load_comps<P>(un.d[e], ft, ((row * 2 + ac) * 2 + e) * 32 + cq);
+          load_comps<P>(un.m[e], ft, ((row2 * 2 + (idx >> 5)) * 2 + e) * 32 + (idx & 31));
         }
-      }
-      float4 zd = make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll
-      for (int ac = 0; ac < 2; ++ac)
-#pragma unroll
+      };
+      Unit buf[DEPTH];
+  #pragma unroll
+      for (int u = 0; u < DEPTH - 1; ++u) load_unit(buf[u], u);
+      float4 zd, zs;
+  #pragma unroll
+      for (int u = 0; u < 16; ++u) {
+        const int i = u >> 1, ac = u & 1;
+        const int row = st + 8 * i;
+        const bool first = row == 0;
+        if (u + DEPTH - 1 < 16) load_unit(buf[(u + DEPTH - 1) % DEPTH], u + DEPTH - 1);
+        Unit &un = buf[u % DEPTH];
+        if (ac == 0) zd = zs = make_float4(0.f, 0.f, 0.f, 0.f);
+  #pragma unroll
         for (int q = 0; q < P; ++q) {
-          zd.x = fmaf(w[ac][q].x, d[ac][0][q], zd.x);
-          zd.y = fmaf(w[ac][q].y, d[ac][0][q], zd.y);
-          zd.z = fmaf(w[ac][q].z, d[ac][1][q], zd.z);
-          zd.w = fmaf(w[ac][q].w, d[ac][1][q], zd.w);
+          zd.x = fmaf(un.w[q].x, un.d[0][q], zd.x);
+          zd.y = fmaf(un.w[q].y, un.d[0][q], zd.y);
+          zd.z = fmaf(un.w[q].z, un.d[1][q], zd.z);
+          zd.w = fmaf(un.w[q].w, un.d[1][q], zd.w);
         }
-      *reinterpret_cast<float4 *>(area + row * RS + 2 * cq) = zd;
-      if (first) {
-#pragma unroll
-        for (int ac = 0; ac < 2; ++ac)
-#pragma unroll
-          for (int q = 0; q < P; ++q) w[ac][q] = src4[(q * 65 + 64) * (S / 2) + 32 * ac + cq];
-      }
-      float4 zs = make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll
-      for (int ac = 0; ac < 2; ++ac) {
+        if (first) {  // row 0: its second part is row 64 itself, not a mirrored row
+  #pragma unroll
+          for (int q = 0; q < P; ++q) un.w[q] = src4[(q * 65 + 64) * (S / 2) + 32 * ac + cq];
+        }
         if constexpr (P == 4) {
           // s = (1, sc, -1, -sc), sc = -1 except for column 0
           const float sc0 = first ? 1.f : (ac == 0 && cq == 0) ? 1.f : -1.f;
           const float sc1 = first ? 1.f : -1.f;
           const float sn = first ? 1.f : -1.f;
-          m[ac][0][1] *= sc0;
-          m[ac][0][2] *= sn;
-          m[ac][0][3] *= sn * sc0;
-          m[ac][1][1] *= sc1;
-          m[ac][1][2] *= sn;
-          m[ac][1][3] *= sn * sc1;
+          un.m[0][1] *= sc0;
+          un.m[0][2] *= sn;
+          un.m[0][3] *= sn * sc0;
+          un.m[1][1] *= sc1;
+          un.m[1][2] *= sn;
+          un.m[1][3] *= sn * sc1;
         }
-#pragma unroll
+  #pragma unroll
         for (int q = 0; q < P; ++q) {
-          zs.x = fmaf(w[ac][q].x, m[ac][0][q], zs.x);
-          zs.y = fmaf(w[ac][q].y, m[ac][0][q], zs.y);
-          zs.z = fmaf(w[ac][q].z, m[ac][1][q], zs.z);
-          zs.w = fmaf(w[ac][q].w, m[ac][1][q], zs.w);
+          zs.x = fmaf(un.w[q].x, un.m[0][q], zs.x);
+          zs.y = fmaf(un.w[q].y, un.m[0][q], zs.y);
+          zs.z = fmaf(un.w[q].z, un.m[1][q], zs.z);
+          zs.w = fmaf(un.w[q].w, un.m[1][q], zs.w);
+        }
+        if (ac == 1) {
+          *reinterpret_cast<float4 *>(area + row * RS + 2 * cq) = zd;
+          const float cj = first ? 1.f : -1.f;
+          z2[i][0] = make_float2(zs.x, cj * zs.y);
+          z2[i][1] = make_float2(zs.z, cj * zs.w);
         }
       }
-      const float cj = first ? 1.f : -1.f;
-      z2[i][0] = make_float2(zs.x, cj * zs.y);
-      z2[i][1] = make_float2(zs.z, cj * zs.w);
     }
     __syncthreads();
 #pragma unroll
@@ -400,25 +476,36 @@ __global__ __launch_bounds__(512, 4) void k_node_half(NodeArgs a) {
     const int col_m0 = (M - 2 * cp) & (M - 1), col_m1 = M - 1 - 2 * cp;
     const float sc0 = cp == 0 ? 1.f : -1.f;                // s_1(c) = -s_3(c) for c = 2 cp; -1 for 2 cp + 1
     float2 zm[8][2];  // second rows (64 .. 127), kept until the first half has been transformed
+    // The loads of row i + 1 are issued before the arithmetic of row i (two rows in flight: left
+    // to itself the compiler waits for each row's loads before it issues the next row's).
+    struct Item {
+      float4 w[4], d[2], m[2];
+    };
+    auto load_item = [&](Item &it, int i) {
+      const int row = wv + 8 * i;
+      const bool first = i == 0 && wv == 0;  // row 0: its partner is row 64, read directly
+      const int row2 = first ? 64 : M - row;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) it.w[q] = src4[(q * 65 + row) * (M / 2) + cp];
+      it.d[0] = f4[(row * 2 + 0) * 64 + cp];
+      it.d[1] = f4[(row * 2 + 1) * 64 + cp];
+      it.m[0] = f4[(row2 * 2 + 0) * 64 + (first ? cp : cm0)];
+      it.m[1] = f4[(row2 * 2 + 1) * 64 + (first ? cp : cm1)];
+    };
+    Item buf[2];
+    float4 w64[4];  // row 64 of the four components (first wave only)
+    load_item(buf[0], 0);
+    if (wv == 0) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) w64[q] = src4[(q * 65 + 64) * (M / 2) + cp];
+    }
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int row = wv + 8 * i;
-      const bool first = i == 0 && wv == 0;  // row 0: its partner is row 64, read directly
-      float4 w[4], w2[4], d[2], m[2];
-#pragma unroll
-      for (int q = 0; q < 4; ++q) w[q] = src4[(q * 65 + row) * (M / 2) + cp];
-      d[0] = f4[(row * 2 + 0) * 64 + cp];
-      d[1] = f4[(row * 2 + 1) * 64 + cp];
-      const int row2 = first ? 64 : M - row;
-      m[0] = f4[(row2 * 2 + 0) * 64 + (first ? cp : cm0)];
-      m[1] = f4[(row2 * 2 + 1) * 64 + (first ? cp : cm1)];
-      if (first) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) w2[q] = src4[(q * 65 + 64) * (M / 2) + cp];
-      } else {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) w2[q] = w[q];
-      }
+      const bool first = i == 0 && wv == 0;
+      if (i + 1 < 8) load_item(buf[(i + 1) & 1], i + 1);
+      const Item &it = buf[i & 1];
+      const float4 *w = it.w, *d = it.d, *m = it.m;
       float4 zd;  // direct: columns 2 cp (x, y) and 2 cp + 1 (z, w)
       zd.x = w[0].x * d[0].x + w[1].x * d[0].y + w[2].x * d[0].z + w[3].x * d[0].w;
       zd.y = w[0].y * d[0].x + w[1].y * d[0].y + w[2].y * d[0].z + w[3].y * d[0].w;
@@ -426,6 +513,9 @@ __global__ __launch_bounds__(512, 4) void k_node_half(NodeArgs a) {
       zd.w = w[0].w * d[1].x + w[1].w * d[1].y + w[2].w * d[1].z + w[3].w * d[1].w;
       *reinterpret_cast<float4 *>(area + row * RSR + 2 * cp) = zd;
       // partner row: sum_q s_q conj(w_q) m_q with s = (1, sc, -1, -sc), or the plain product for row 64
+      float4 w2[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) w2[q] = (i == 0 && first) ? w64[q] : w[q];
       const float g00 = m[0].x, g01 = first ? m[0].y : sc0 * m[0].y, g02 = first ? m[0].z : -m[0].z,
                   g03 = first ? m[0].w : -sc0 * m[0].w;
       const float g10 = m[1].x, g11 = first ? m[1].y : -m[1].y, g12 = first ? m[1].z : -m[1].z,
@@ -716,10 +806,14 @@ __global__ __launch_bounds__(512, 4) void k_node_half(NodeArgs a) {
   fft_core_tab<16, T, false, false>(vh[0], t, area + r * RSR, T + 1, 1, wl, T);  // ends with a barrier
   {
     float2 *up = a.uout + ((static_cast<size_t>(s) * I + item) * (M / 2 + 1) + r) * M + t;
+    // (the same table entries were read for the node's own rows at the start; hidden from the
+    // compiler, which would otherwise keep all sixteen alive, and spill them, to save these reads)
+    int wbase = pr * r + pc * t;
+    asm volatile("" : "+v"(wbase));
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       float2 val = vh[0][i];
-      if (POLY) val = c_mul(val, w2m[(pr * r + pc * (t + T * i)) & (2 * M - 1)]);
+      if (POLY) val = c_mul(val, w2m[(wbase + pc * T * i) & (2 * M - 1)]);
       up[T * i] = val;
     }
   }
