@@ -98,7 +98,9 @@ __global__ __launch_bounds__(M * M / 16, 3) void k_node(NodeArgs a) {
   if (s >= a.NS) return;
   const int f = POLY ? item >> 2 : item;
   const int pr = POLY ? (item >> 1) & 1 : 0, pc = POLY ? item & 1 : 0;
-  SL::fill_twiddles(wtab, a.tw, a.tw_n);
+  // (no barrier here: the table is first read after the barrier that ends the spectrum phase,
+  // and the workgroup's loads start without waiting for the twiddle fetch)
+  SL::fill_twiddles(wtab, a.tw, a.tw_n, false);
   const int tw_step = a.tw_n / (2 * M);  // POLY only: table step of w = exp(-2 pi i / 2M)
 
   if constexpr (A == 2) {
@@ -455,7 +457,7 @@ __global__ __launch_bounds__(512, 4) void k_node_half(NodeArgs a) {
   const int r = tid / T, t = tid % T;    // row roles: rows r and r + 64, columns t + 8 i
   const int c = tid % 64, t1 = tid / 64; // column roles: columns c and c + 64, rows t1 + 8 i
   const float2 *wl = wtab + t, *wlc = wtab + t1;
-  __syncthreads();
+  // (no barrier here: the tables are first read after the barriers of the spectrum phase)
 
   // ---- 1 + 2a. spectrum of the node (half of its rows at a time) and inverse row transforms
   float2 vh[2][16];

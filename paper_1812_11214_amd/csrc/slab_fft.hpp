@@ -76,15 +76,15 @@ struct Slab {
   // The same two transforms with the threads' twiddles in LDS tables instead of registers
   // (for kernels short of registers): wtr[k T2 + t] = exp(-2 pi i t k / N2), k < 16, t < T2,
   // and wtc[k T1 + t1] likewise for N1; fill_twiddles writes both (tab_elems entries at
-  // `tab`, barrier included).
+  // `tab`, barrier included unless the caller declines it).
   static constexpr int tab_elems = N1 + N2;
   static __device__ __forceinline__ void fill_twiddles(float2 *tab, const float2 *__restrict__ tw,
-                                                       int tw_n) {
+                                                       int tw_n, bool sync = true) {
     for (int idx = threadIdx.x; idx < N2; idx += blockDim.x)
       tab[idx] = tw[(idx / T2) * (idx % T2) * (tw_n / N2)];
     for (int idx = threadIdx.x; idx < N1; idx += blockDim.x)
       tab[N2 + idx] = tw[(idx / T1) * (idx % T1) * (tw_n / N1)];
-    __syncthreads();
+    if (sync) __syncthreads();  // (else: the caller has a barrier of its own before the first use)
   }
   template <bool INV>
   static __device__ __forceinline__ void transform_tab(float2 (&v)[16], float2 *area, int r, int t,
