@@ -427,14 +427,14 @@ __global__ __launch_bounds__(M * M / 16, 3) void k_node(NodeArgs a) {
 // under the other's arithmetic (a single resident workgroup adds its phases up: measured).
 //   spectrum + row transforms: rows 0..63, then rows 64..127 (thread = row r or r + 64,
 //     columns t + 8 i), through the same 64 row slots of 152 elements;
-//   transposition: columns 0..63, then 64..127, through 128 rows of 76 elements;
+//   transposition: columns 0..63, then 64..127, through 128 rows of 72 elements (rows 16 banks apart: no conflicts);
 //   column transforms: column c, then c + 64 (thread = rows t1 + 8 i), exchange in place;
 //   lowpass as in k_node, with the row-filtered values parked in registers while the
 //   unfiltered plane is still being read, then written over it.
 template <int A, int P, bool POLY>
 __global__ __launch_bounds__(512, 4) void k_node_half(NodeArgs a) {
   constexpr int M = 128, T = 8, NT = 512, S = M * A;
-  constexpr int RSR = 152, RSC = 76;
+  constexpr int RSR = 152, RSC = 72;
   constexpr int DEC = M / kOut, R = 4 * DEC, NTAP = 2 * R + 1;
   extern __shared__ __attribute__((aligned(16))) float2 lds[];
   float2 *area = lds;             // 64 * RSR = 128 * RSC elements
