@@ -120,18 +120,18 @@ __global__ __launch_bounds__(M * M / 16, 3) void k_node(NodeArgs a) {
     if constexpr (P == 4) {
       // (four components: a row's sixteen 16-byte loads at once; measured faster than the
       // pipelined form below, which is the faster one for a single component)
-  #pragma unroll
+#pragma unroll
       for (int i = 0; i < 8; ++i) {
         const int row = st + 8 * i;
         const bool first = row == 0;
         const int row2 = first ? 64 : S - row;
         float4 w[2][P];
         float d[2][2][P], m[2][2][P];
-  #pragma unroll
+#pragma unroll
         for (int ac = 0; ac < 2; ++ac) {
-  #pragma unroll
+#pragma unroll
           for (int q = 0; q < P; ++q) w[ac][q] = src4[(q * 65 + row) * (S / 2) + 32 * ac + cq];
-  #pragma unroll
+#pragma unroll
           for (int e = 0; e < 2; ++e) {
             const int idx = first ? 32 * ac + cq : (64 - 32 * ac - cq - e) & 63;
             load_comps<P>(d[ac][e], ft, ((row * 2 + ac) * 2 + e) * 32 + cq);
@@ -139,9 +139,9 @@ __global__ __launch_bounds__(M * M / 16, 3) void k_node(NodeArgs a) {
           }
         }
         float4 zd = make_float4(0.f, 0.f, 0.f, 0.f);
-  #pragma unroll
+#pragma unroll
         for (int ac = 0; ac < 2; ++ac)
-  #pragma unroll
+#pragma unroll
           for (int q = 0; q < P; ++q) {
             zd.x = fmaf(w[ac][q].x, d[ac][0][q], zd.x);
             zd.y = fmaf(w[ac][q].y, d[ac][0][q], zd.y);
@@ -150,13 +150,13 @@ __global__ __launch_bounds__(M * M / 16, 3) void k_node(NodeArgs a) {
           }
         *reinterpret_cast<float4 *>(area + row * RS + 2 * cq) = zd;
         if (first) {
-  #pragma unroll
+#pragma unroll
           for (int ac = 0; ac < 2; ++ac)
-  #pragma unroll
+#pragma unroll
             for (int q = 0; q < P; ++q) w[ac][q] = src4[(q * 65 + 64) * (S / 2) + 32 * ac + cq];
         }
         float4 zs = make_float4(0.f, 0.f, 0.f, 0.f);
-  #pragma unroll
+#pragma unroll
         for (int ac = 0; ac < 2; ++ac) {
           if constexpr (P == 4) {
             // s = (1, sc, -1, -sc), sc = -1 except for column 0
@@ -170,7 +170,7 @@ __global__ __launch_bounds__(M * M / 16, 3) void k_node(NodeArgs a) {
             m[ac][1][2] *= sn;
             m[ac][1][3] *= sn * sc1;
           }
-  #pragma unroll
+#pragma unroll
           for (int q = 0; q < P; ++q) {
             zs.x = fmaf(w[ac][q].x, m[ac][0][q], zs.x);
             zs.y = fmaf(w[ac][q].y, m[ac][0][q], zs.y);
@@ -183,76 +183,46 @@ __global__ __launch_bounds__(M * M / 16, 3) void k_node(NodeArgs a) {
         z2[i][1] = make_float2(zs.z, cj * zs.w);
       }
     } else {
-      // One unit of work = one column block (ac) of one source row; the loads of the next units
-      // are issued before the arithmetic of the current one (left to itself the compiler waits
-      // for each row's loads before it issues the next row's).
-      struct Unit {
-        float4 w[P];
-        float d[2][P], m[2][P];
+      // One component: the filter values of a lane's four points of a row (two columns in each
+      // column block) are ONE 16-byte load -- from table row rho for the direct part, from table
+      // row S - rho for the mirrored part (rows above S / 2 are stored in the order the lanes
+      // need them mirrored).  The loads of the next rows are issued before the arithmetic of
+      // the current one (left to itself the compiler waits for each row's loads first).
+      const float4 *ft4 = reinterpret_cast<const float4 *>(ft);
+      struct Item {
+        float4 w0, w1, d, m;
       };
-      constexpr int DEPTH = P == 4 ? 2 : 4;  // units in flight
-      auto load_unit = [&](Unit &un, int u) {
-        const int i = u >> 1, ac = u & 1;
+      constexpr int DEPTH = 3;  // rows in flight
+      auto load_item = [&](Item &it, int i) {
+        const int row = st + 8 * i;
+        it.w0 = src4[row * (S / 2) + cq];
+        it.w1 = src4[row * (S / 2) + 32 + cq];
+        it.d = ft4[row * 32 + cq];
+        it.m = ft4[(row == 0 ? 64 : S - row) * 32 + cq];
+      };
+      // (x, y): column 2 cq, (z, w): column 2 cq + 1; f = values for (block 0, block 1) x parity
+      auto products = [](const float4 &w0, const float4 &w1, const float4 &f) {
+        return make_float4(w0.x * f.x + w1.x * f.z, w0.y * f.x + w1.y * f.z, w0.z * f.y + w1.z * f.w,
+                           w0.w * f.y + w1.w * f.w);
+      };
+      Item buf[DEPTH];
+#pragma unroll
+      for (int i = 0; i < DEPTH - 1; ++i) load_item(buf[i], i);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
         const int row = st + 8 * i;
         const bool first = row == 0;
-        const int row2 = first ? 64 : S - row;
-  #pragma unroll
-        for (int q = 0; q < P; ++q) un.w[q] = src4[(q * 65 + row) * (S / 2) + 32 * ac + cq];
-  #pragma unroll
-        for (int e = 0; e < 2; ++e) {
-          const int idx = first ? 32 * ac + cq : (64 - 32 * ac - cq - e) & 63;
-          load_comps<P>(un.d[e], ft, ((row * 2 + ac) * 2 + e) * 32 + cq);
-          load_comps<P>(un.m[e], ft, ((row2 * 2 + (idx >> 5)) * 2 + e) * 32 + (idx & 31));
-        }
-      };
-      Unit buf[DEPTH];
-  #pragma unroll
-      for (int u = 0; u < DEPTH - 1; ++u) load_unit(buf[u], u);
-      float4 zd, zs;
-  #pragma unroll
-      for (int u = 0; u < 16; ++u) {
-        const int i = u >> 1, ac = u & 1;
-        const int row = st + 8 * i;
-        const bool first = row == 0;
-        if (u + DEPTH - 1 < 16) load_unit(buf[(u + DEPTH - 1) % DEPTH], u + DEPTH - 1);
-        Unit &un = buf[u % DEPTH];
-        if (ac == 0) zd = zs = make_float4(0.f, 0.f, 0.f, 0.f);
-  #pragma unroll
-        for (int q = 0; q < P; ++q) {
-          zd.x = fmaf(un.w[q].x, un.d[0][q], zd.x);
-          zd.y = fmaf(un.w[q].y, un.d[0][q], zd.y);
-          zd.z = fmaf(un.w[q].z, un.d[1][q], zd.z);
-          zd.w = fmaf(un.w[q].w, un.d[1][q], zd.w);
-        }
+        if (i + DEPTH - 1 < 8) load_item(buf[(i + DEPTH - 1) % DEPTH], i + DEPTH - 1);
+        Item &it = buf[i % DEPTH];
+        *reinterpret_cast<float4 *>(area + row * RS + 2 * cq) = products(it.w0, it.w1, it.d);
         if (first) {  // row 0: its second part is row 64 itself, not a mirrored row
-  #pragma unroll
-          for (int q = 0; q < P; ++q) un.w[q] = src4[(q * 65 + 64) * (S / 2) + 32 * ac + cq];
+          it.w0 = src4[64 * (S / 2) + cq];
+          it.w1 = src4[64 * (S / 2) + 32 + cq];
         }
-        if constexpr (P == 4) {
-          // s = (1, sc, -1, -sc), sc = -1 except for column 0
-          const float sc0 = first ? 1.f : (ac == 0 && cq == 0) ? 1.f : -1.f;
-          const float sc1 = first ? 1.f : -1.f;
-          const float sn = first ? 1.f : -1.f;
-          un.m[0][1] *= sc0;
-          un.m[0][2] *= sn;
-          un.m[0][3] *= sn * sc0;
-          un.m[1][1] *= sc1;
-          un.m[1][2] *= sn;
-          un.m[1][3] *= sn * sc1;
-        }
-  #pragma unroll
-        for (int q = 0; q < P; ++q) {
-          zs.x = fmaf(un.w[q].x, un.m[0][q], zs.x);
-          zs.y = fmaf(un.w[q].y, un.m[0][q], zs.y);
-          zs.z = fmaf(un.w[q].z, un.m[1][q], zs.z);
-          zs.w = fmaf(un.w[q].w, un.m[1][q], zs.w);
-        }
-        if (ac == 1) {
-          *reinterpret_cast<float4 *>(area + row * RS + 2 * cq) = zd;
-          const float cj = first ? 1.f : -1.f;
-          z2[i][0] = make_float2(zs.x, cj * zs.y);
-          z2[i][1] = make_float2(zs.z, cj * zs.w);
-        }
+        const float4 zs = products(it.w0, it.w1, it.m);
+        const float cj = first ? 1.f : -1.f;
+        z2[i][0] = make_float2(zs.x, cj * zs.y);
+        z2[i][1] = make_float2(zs.z, cj * zs.w);
       }
     }
     __syncthreads();
@@ -555,7 +525,6 @@ __global__ __launch_bounds__(512, 4) void k_node_half(NodeArgs a) {
     // halves: first the direct parts are written, then, after a barrier, the mirrored parts
     // are added (every element by exactly one lane).  So every row of the source is read
     // twice (a row's direct part belongs to one half of the node, its mirrored part to the other).
-    // Filter table: [row][column block][column parity][column pair].
     const float4 *src4 = reinterpret_cast<const float4 *>(a.src + static_cast<size_t>(s) * (S / 2 + 1) * S);
     const float *ft = a.filt + static_cast<size_t>(f) * S * S;
     const int cp = tid & 63;
@@ -563,30 +532,30 @@ __global__ __launch_bounds__(512, 4) void k_node_half(NodeArgs a) {
     const int c0 = (M - 2 * cp) & (M - 1), c1 = M - 1 - 2 * cp;  // columns of the mirrored parts
     // polyphase alias signs (-1)^(a.p): of the direct parts (row block 0), and of the mirrored
     // parts (row block 1, column block of the mirrored column)
+    const float4 *ft4 = reinterpret_cast<const float4 *>(ft);
     const float sg1 = (POLY && pc) ? -1.f : 1.f;
     float sm[2][2];
-    int mi[2][2];  // table index of the mirrored column, without the row
 #pragma unroll
     for (int ac = 0; ac < 2; ++ac)
 #pragma unroll
       for (int e = 0; e < 2; ++e) {
-        const int idx = (128 - 64 * ac - cp - e) & 127;
-        mi[ac][e] = ((idx >> 6) * 2 + e) * 64 + (idx & 63);
+        const int idx = (128 - 64 * ac - cp - e) & 127;  // column pair of the mirrored column
         sm[ac][e] = (POLY && ((pr + (idx >> 6) * pc) & 1)) ? -1.f : 1.f;
       }
+    // The filter values of a lane's four points of a row (two columns in each column block) are
+    // ONE 16-byte load: (block 0, block 1) x column parity, from table row rho for the direct
+    // part and from table row 256 - rho, stored in mirrored order, for the mirrored part.
     auto direct = [&](int row, float sr) {  // row of the source and of the table; sr: sign of its row block
       const float4 w0 = src4[row * (S / 2) + cp], w1 = src4[row * (S / 2) + 64 + cp];
-      const float d00 = ft[((row * 2 + 0) * 2 + 0) * 64 + cp] * sr, d01 = ft[((row * 2 + 0) * 2 + 1) * 64 + cp] * sr;
-      const float d10 = ft[((row * 2 + 1) * 2 + 0) * 64 + cp] * (sr * sg1),
-                  d11 = ft[((row * 2 + 1) * 2 + 1) * 64 + cp] * (sr * sg1);
+      const float4 f = ft4[row * 64 + cp];
+      const float d00 = f.x * sr, d01 = f.y * sr, d10 = f.z * (sr * sg1), d11 = f.w * (sr * sg1);
       return make_float4(w0.x * d00 + w1.x * d10, w0.y * d00 + w1.y * d10, w0.z * d01 + w1.z * d11,
                          w0.w * d01 + w1.w * d11);
     };
     auto mirrored = [&](int row) {  // conj of the products with table row 256 - row, mirrored columns
       const float4 w0 = src4[row * (S / 2) + cp], w1 = src4[row * (S / 2) + 64 + cp];
-      const float *fr = ft + (S - row) * 2 * 2 * 64;
-      const float m00 = fr[mi[0][0]] * sm[0][0], m01 = fr[mi[0][1]] * sm[0][1];
-      const float m10 = fr[mi[1][0]] * sm[1][0], m11 = fr[mi[1][1]] * sm[1][1];
+      const float4 f = ft4[(S - row) * 64 + cp];
+      const float m00 = f.x * sm[0][0], m01 = f.y * sm[0][1], m10 = f.z * sm[1][0], m11 = f.w * sm[1][1];
       return make_float4(w0.x * m00 + w1.x * m10, -(w0.y * m00 + w1.y * m10), w0.z * m01 + w1.z * m11,
                          -(w0.w * m01 + w1.w * m11));
     };
