@@ -115,9 +115,11 @@ struct scat_plan {
   bool node_tables = false;  // shapes the whole-node kernels serve: their taps and masks are uploaded
   std::map<int, size_t> poly_psi_off;          // j2 -> [L][4][N/2][N/2] sign-folded wavelets
   // (res, j) -> the L wavelets of octave j on the grid of resolution res in the layout of the
-  // whole-node kernels whose source is twice as large as the node (M = side / 2):
+  // whole-node kernels whose source is twice as large as the node (M = side / 2).  M = 128:
   // [row][column pair][column block][column parity] = psi[row][c], c = M block + 2 pair + parity,
-  // for rows 0 .. side / 2 and psi[row][-c] for the rows above (read for the mirrored parts)
+  // for rows 0 .. side / 2 and psi[row][-c] for the rows above (read for the mirrored parts);
+  // M = 64: [row][column block][column parity][column pair] = psi[row][c] (the layouts each
+  // kernel measured faster with)
   std::map<std::pair<int, int>, size_t> node2_off;
   std::vector<size_t> taps_r_off, taps_c_off;  // per res: spatial lowpass taps [2R+1]
   size_t ptaps_r_off = 0, ptaps_c_off = 0;     // polyphase taps of resolution 0: [2][2R+1]
@@ -475,14 +477,23 @@ scat_status upload(scat_plan *p) {
         p->node2_off[rj] = pool.size();
         for (int l = 0; l < h.LQ; ++l) {
           const FilterTable &t = *h.find(r == 0 ? 1 : 2, j * h.LQ + l, r);
-          for (int kr = 0; kr < side; ++kr)
-            for (int cp = 0; cp < M / 2; ++cp)
+          if (M == 128) {
+            for (int kr = 0; kr < side; ++kr)
+              for (int cp = 0; cp < M / 2; ++cp)
+                for (int ac = 0; ac < 2; ++ac)
+                  for (int e = 0; e < 2; ++e) {
+                    const int c = M * ac + 2 * cp + e;
+                    const int col = kr <= side / 2 ? c : (side - c) & (side - 1);
+                    pool.push_back(static_cast<float>(t.v[static_cast<size_t>(kr) * side + col] * scale));
+                  }
+          } else {
+            for (int kr = 0; kr < side; ++kr)
               for (int ac = 0; ac < 2; ++ac)
-                for (int e = 0; e < 2; ++e) {
-                  const int c = M * ac + 2 * cp + e;
-                  const int col = kr <= side / 2 ? c : (side - c) & (side - 1);
-                  pool.push_back(static_cast<float>(t.v[static_cast<size_t>(kr) * side + col] * scale));
-                }
+                for (int e = 0; e < 2; ++e)
+                  for (int cp = 0; cp < M / 2; ++cp)
+                    pool.push_back(static_cast<float>(
+                        t.v[static_cast<size_t>(kr) * side + M * ac + 2 * cp + e] * scale));
+          }
         }
       }
     }

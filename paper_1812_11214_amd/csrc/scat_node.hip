@@ -183,46 +183,76 @@ __global__ __launch_bounds__(M * M / 16, 3) void k_node(NodeArgs a) {
         z2[i][1] = make_float2(zs.z, cj * zs.w);
       }
     } else {
-      // One component: the filter values of a lane's four points of a row (two columns in each
-      // column block) are ONE 16-byte load -- from table row rho for the direct part, from table
-      // row S - rho for the mirrored part (rows above S / 2 are stored in the order the lanes
-      // need them mirrored).  The loads of the next rows are issued before the arithmetic of
-      // the current one (left to itself the compiler waits for each row's loads first).
-      const float4 *ft4 = reinterpret_cast<const float4 *>(ft);
-      struct Item {
-        float4 w0, w1, d, m;
+      // One unit of work = one column block (ac) of one source row; the loads of the next units
+      // are issued before the arithmetic of the current one (left to itself the compiler waits
+      // for each row's loads before it issues the next row's).
+      struct Unit {
+        float4 w[P];
+        float d[2][P], m[2][P];
       };
-      constexpr int DEPTH = 3;  // rows in flight
-      auto load_item = [&](Item &it, int i) {
-        const int row = st + 8 * i;
-        it.w0 = src4[row * (S / 2) + cq];
-        it.w1 = src4[row * (S / 2) + 32 + cq];
-        it.d = ft4[row * 32 + cq];
-        it.m = ft4[(row == 0 ? 64 : S - row) * 32 + cq];
-      };
-      // (x, y): column 2 cq, (z, w): column 2 cq + 1; f = values for (block 0, block 1) x parity
-      auto products = [](const float4 &w0, const float4 &w1, const float4 &f) {
-        return make_float4(w0.x * f.x + w1.x * f.z, w0.y * f.x + w1.y * f.z, w0.z * f.y + w1.z * f.w,
-                           w0.w * f.y + w1.w * f.w);
-      };
-      Item buf[DEPTH];
-#pragma unroll
-      for (int i = 0; i < DEPTH - 1; ++i) load_item(buf[i], i);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
+      constexpr int DEPTH = P == 4 ? 2 : 4;  // units in flight
+      auto load_unit = [&](Unit &un, int u) {
+        const int i = u >> 1, ac = u & 1;
         const int row = st + 8 * i;
         const bool first = row == 0;
-        if (i + DEPTH - 1 < 8) load_item(buf[(i + DEPTH - 1) % DEPTH], i + DEPTH - 1);
-        Item &it = buf[i % DEPTH];
-        *reinterpret_cast<float4 *>(area + row * RS + 2 * cq) = products(it.w0, it.w1, it.d);
-        if (first) {  // row 0: its second part is row 64 itself, not a mirrored row
-          it.w0 = src4[64 * (S / 2) + cq];
-          it.w1 = src4[64 * (S / 2) + 32 + cq];
+        const int row2 = first ? 64 : S - row;
+#pragma unroll
+        for (int q = 0; q < P; ++q) un.w[q] = src4[(q * 65 + row) * (S / 2) + 32 * ac + cq];
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          const int idx = first ? 32 * ac + cq : (64 - 32 * ac - cq - e) & 63;
+          load_comps<P>(un.d[e], ft, ((row * 2 + ac) * 2 + e) * 32 + cq);
+          load_comps<P>(un.m[e], ft, ((row2 * 2 + (idx >> 5)) * 2 + e) * 32 + (idx & 31));
         }
-        const float4 zs = products(it.w0, it.w1, it.m);
-        const float cj = first ? 1.f : -1.f;
-        z2[i][0] = make_float2(zs.x, cj * zs.y);
-        z2[i][1] = make_float2(zs.z, cj * zs.w);
+      };
+      Unit buf[DEPTH];
+#pragma unroll
+      for (int u = 0; u < DEPTH - 1; ++u) load_unit(buf[u], u);
+      float4 zd, zs;
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+        const int i = u >> 1, ac = u & 1;
+        const int row = st + 8 * i;
+        const bool first = row == 0;
+        if (u + DEPTH - 1 < 16) load_unit(buf[(u + DEPTH - 1) % DEPTH], u + DEPTH - 1);
+        Unit &un = buf[u % DEPTH];
+        if (ac == 0) zd = zs = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int q = 0; q < P; ++q) {
+          zd.x = fmaf(un.w[q].x, un.d[0][q], zd.x);
+          zd.y = fmaf(un.w[q].y, un.d[0][q], zd.y);
+          zd.z = fmaf(un.w[q].z, un.d[1][q], zd.z);
+          zd.w = fmaf(un.w[q].w, un.d[1][q], zd.w);
+        }
+        if (first) {  // row 0: its second part is row 64 itself, not a mirrored row
+#pragma unroll
+          for (int q = 0; q < P; ++q) un.w[q] = src4[(q * 65 + 64) * (S / 2) + 32 * ac + cq];
+        }
+        if constexpr (P == 4) {
+          // s = (1, sc, -1, -sc), sc = -1 except for column 0
+          const float sc0 = first ? 1.f : (ac == 0 && cq == 0) ? 1.f : -1.f;
+          const float sc1 = first ? 1.f : -1.f;
+          const float sn = first ? 1.f : -1.f;
+          un.m[0][1] *= sc0;
+          un.m[0][2] *= sn;
+          un.m[0][3] *= sn * sc0;
+          un.m[1][1] *= sc1;
+          un.m[1][2] *= sn;
+          un.m[1][3] *= sn * sc1;
+        }
+#pragma unroll
+        for (int q = 0; q < P; ++q) {
+          zs.x = fmaf(un.w[q].x, un.m[0][q], zs.x);
+          zs.y = fmaf(un.w[q].y, un.m[0][q], zs.y);
+          zs.z = fmaf(un.w[q].z, un.m[1][q], zs.z);
+          zs.w = fmaf(un.w[q].w, un.m[1][q], zs.w);
+        }
+        if (ac == 1) {
+          *reinterpret_cast<float4 *>(area + row * RS + 2 * cq) = zd;
+          const float cj = first ? 1.f : -1.f;
+          z2[i][0] = make_float2(zs.x, cj * zs.y);
+          z2[i][1] = make_float2(zs.z, cj * zs.w);
+        }
       }
     }
     __syncthreads();
