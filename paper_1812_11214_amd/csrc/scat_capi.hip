@@ -519,10 +519,21 @@ scat_status upload(scat_plan *p) {
           if ((N >> j2) == M) {
             // children as large as a component: [row][column parity][column pair][component],
             // the four component values of a point side by side (one 16-byte load)
+            // rows above M / 2 are only read for mirrored parts (the stored half spectra have
+            // W_q[M - r][-c] = s_q(c) conj(W_q[r][c])): they hold s_q(c) R_q[row][-c] at c's place
             for (int kr = 0; kr < M; ++kr)
               for (int e = 0; e < 2; ++e)
                 for (int cp = 0; cp < M / 2; ++cp)
-                  for (int q = 0; q < 4; ++q) pool.push_back(folded(q, kr, 2 * cp + e));
+                  for (int q = 0; q < 4; ++q) {
+                    const int c = 2 * cp + e;
+                    if (kr <= M / 2) {
+                      pool.push_back(folded(q, kr, c));
+                    } else {
+                      const bool neg = ((q >> 1) & 1) ^ ((q & 1) & (c != 0 ? 1 : 0));
+                      const float v = folded(q, kr, (M - c) & (M - 1));
+                      pool.push_back(neg ? -v : v);
+                    }
+                  }
           } else if ((N >> j2) == M / 2) {
             // children half as large: [row][column block][column parity][column pair][component]
             for (int kr = 0; kr < M; ++kr)

@@ -474,9 +474,7 @@ __global__ __launch_bounds__(512, 4) void k_node_half(NodeArgs a) {
     const float4 *f4 = reinterpret_cast<const float4 *>(a.filt + static_cast<size_t>(f) * 4 * M * M);
     const int cp = tid & 63;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int cm0 = (64 - cp) & 63, cm1 = 63 - cp;        // column pairs of the mirrored columns
     const int col_m0 = (M - 2 * cp) & (M - 1), col_m1 = M - 1 - 2 * cp;
-    const float sc0 = cp == 0 ? 1.f : -1.f;                // s_1(c) = -s_3(c) for c = 2 cp; -1 for 2 cp + 1
     float2 zm[8][2];  // second rows (64 .. 127), kept until the first half has been transformed
     // The loads of row i + 1 are issued before the arithmetic of row i (two rows in flight: left
     // to itself the compiler waits for each row's loads before it issues the next row's).
@@ -491,8 +489,8 @@ __global__ __launch_bounds__(512, 4) void k_node_half(NodeArgs a) {
       for (int q = 0; q < 4; ++q) it.w[q] = src4[(q * 65 + row) * (M / 2) + cp];
       it.d[0] = f4[(row * 2 + 0) * 64 + cp];
       it.d[1] = f4[(row * 2 + 1) * 64 + cp];
-      it.m[0] = f4[(row2 * 2 + 0) * 64 + (first ? cp : cm0)];
-      it.m[1] = f4[(row2 * 2 + 1) * 64 + (first ? cp : cm1)];
+      it.m[0] = f4[(row2 * 2 + 0) * 64 + cp];
+      it.m[1] = f4[(row2 * 2 + 1) * 64 + cp];
     };
     Item buf[2];
     float4 w64[4];  // row 64 of the four components (first wave only)
@@ -514,19 +512,16 @@ __global__ __launch_bounds__(512, 4) void k_node_half(NodeArgs a) {
       zd.z = w[0].z * d[1].x + w[1].z * d[1].y + w[2].z * d[1].z + w[3].z * d[1].w;
       zd.w = w[0].w * d[1].x + w[1].w * d[1].y + w[2].w * d[1].z + w[3].w * d[1].w;
       *reinterpret_cast<float4 *>(area + row * RSR + 2 * cp) = zd;
-      // partner row: sum_q s_q conj(w_q) m_q with s = (1, sc, -1, -sc), or the plain product for row 64
+      // partner row: sum_q conj(w_q) m_q (table rows above 64 are stored for that: at the lane's
+      // own place and with the sign s_q), or the plain product for row 64
       float4 w2[4];
 #pragma unroll
       for (int q = 0; q < 4; ++q) w2[q] = (i == 0 && first) ? w64[q] : w[q];
-      const float g00 = m[0].x, g01 = first ? m[0].y : sc0 * m[0].y, g02 = first ? m[0].z : -m[0].z,
-                  g03 = first ? m[0].w : -sc0 * m[0].w;
-      const float g10 = m[1].x, g11 = first ? m[1].y : -m[1].y, g12 = first ? m[1].z : -m[1].z,
-                  g13 = first ? m[1].w : m[1].w;
-      const float cj = first ? 1.f : -1.f;
-      zm[i][0].x = w2[0].x * g00 + w2[1].x * g01 + w2[2].x * g02 + w2[3].x * g03;
-      zm[i][0].y = cj * (w2[0].y * g00 + w2[1].y * g01 + w2[2].y * g02 + w2[3].y * g03);
-      zm[i][1].x = w2[0].z * g10 + w2[1].z * g11 + w2[2].z * g12 + w2[3].z * g13;
-      zm[i][1].y = cj * (w2[0].w * g10 + w2[1].w * g11 + w2[2].w * g12 + w2[3].w * g13);
+      const float cj = first ? 1.f : -1.f;  // mirrored parts are conjugated
+      zm[i][0].x = w2[0].x * m[0].x + w2[1].x * m[0].y + w2[2].x * m[0].z + w2[3].x * m[0].w;
+      zm[i][0].y = cj * (w2[0].y * m[0].x + w2[1].y * m[0].y + w2[2].y * m[0].z + w2[3].y * m[0].w);
+      zm[i][1].x = w2[0].z * m[1].x + w2[1].z * m[1].y + w2[2].z * m[1].z + w2[3].z * m[1].w;
+      zm[i][1].y = cj * (w2[0].w * m[1].x + w2[1].w * m[1].y + w2[2].w * m[1].z + w2[3].w * m[1].w);
     }
     __syncthreads();
 #pragma unroll
