@@ -360,9 +360,16 @@ __global__ __launch_bounds__(M * M / 16, 3) void k_node(NodeArgs a) {
 #pragma unroll
     for (int j = 0; j < OPT; ++j) acc[j] = 0.f;
     const int e0 = DEC * OPT * mg - R;
+    // e0 is a multiple of 8: within a run of 8 inputs the column index does not wrap, so one
+    // address per run and constant offsets inside it (no index arithmetic per read)
+    constexpr int SEG = 8, NSEG = (NIN + SEG - 1) / SEG;
+    static_assert((DEC * OPT) % SEG == 0 && R % SEG == 0, "runs of inputs that do not wrap");
+    const float *seg[NSEG];
+#pragma unroll
+    for (int k = 0; k < NSEG; ++k) seg[k] = ub + rr * US + ((e0 + SEG * k) & (M - 1));
 #pragma unroll
     for (int e = 0; e < NIN; ++e) {
-      const float val = ub[rr * US + ((e0 + e) & (M - 1))];
+      const float val = seg[e / SEG][e % SEG];
 #pragma unroll
       for (int j = 0; j < OPT; ++j) {
         const int ti = DEC * j + 2 * R - e;  // tap index d + R of input column DEC m - d
@@ -382,9 +389,14 @@ __global__ __launch_bounds__(M * M / 16, 3) void k_node(NodeArgs a) {
 #pragma unroll
     for (int j = 0; j < OPV; ++j) acc[j] = 0.f;
     const int e0 = DEC * OPV * ng - R;
+    constexpr int SEG = 8, NSEG = (NIN + SEG - 1) / SEG;  // e0 is a multiple of 8: see above
+    static_assert((DEC * OPV) % SEG == 0 && R % SEG == 0, "runs of inputs that do not wrap");
+    const float *seg[NSEG];
+#pragma unroll
+    for (int k = 0; k < NSEG; ++k) seg[k] = hb + ((e0 + SEG * k) & (M - 1)) * HS + mc;
 #pragma unroll
     for (int e = 0; e < NIN; ++e) {
-      const float val = hb[((e0 + e) & (M - 1)) * HS + mc];
+      const float val = seg[e / SEG][(e % SEG) * HS];
 #pragma unroll
       for (int j = 0; j < OPV; ++j) {
         const int ti = DEC * j + 2 * R - e;
