@@ -2,9 +2,9 @@
 //
 // A node is |x (*) psi| (or ||x (*) psi_1| (*) psi_2|) on its own subsampled grid of M x M
 // points, M = 64 (k_node, 256 threads, three workgroups per compute unit) or 128 (k_node_half,
-// 512 threads, two per compute unit) (paper, section 2 "Implementation": convolutions as Fourier products,
-// every filtered signal downsampled, the tree walked branch by branch so that intermediates
-// are dropped as soon as the children are done).  The workgroup
+// 512 threads, two per compute unit) (paper, section 2 "Implementation": convolutions as
+// Fourier products, every filtered signal downsampled, the tree walked branch by branch so
+// that intermediates are dropped as soon as the children are done).  The workgroup
 //   1. forms the node's spectrum  Z[k] = sum over sources q and aliases a of
 //      src_q[k + M a] * filt_q[k + M a]   (filter product + periodisation = subsampling),
 //      reading its parent's spectrum through the caches,
@@ -434,15 +434,21 @@ __global__ __launch_bounds__(M * M / 16, 3) void k_node(NodeArgs a) {
 
 // ------------------------------------------------------------------------------------
 // k_node for 128 x 128 nodes with HALF the workgroup: 512 threads hold the node in registers
-// (32 points each) and use LDS only to exchange one half of it at a time, 78 KB instead of
+// (32 points each) and use LDS only to exchange one half of it at a time, 81 KB instead of
 // 156 KB, so that TWO workgroups share a compute unit and one's memory and LDS phases run
 // under the other's arithmetic (a single resident workgroup adds its phases up: measured).
 //   spectrum + row transforms: rows 0..63, then rows 64..127 (thread = row r or r + 64,
-//     columns t + 8 i), through the same 64 row slots of 152 elements;
-//   transposition: columns 0..63, then 64..127, through 128 rows of 72 elements (rows 16 banks apart: no conflicts);
+//     columns t + 8 i), through the same 64 row slots of 152 elements; the spectrum phase
+//     reads every stored source row once for the two node rows it serves (the stored half
+//     spectra are conjugate-symmetric), a lane taking two adjacent columns per 16-byte load;
+//   transposition: columns 0..63, then 64..127, through 128 rows of 72 elements (rows 16
+//     banks apart: no conflicts);
 //   column transforms: column c, then c + 64 (thread = rows t1 + 8 i), exchange in place;
 //   lowpass as in k_node, with the row-filtered values parked in registers while the
-//   unfiltered plane is still being read, then written over it.
+//   unfiltered plane is still being read, then written over it;
+//   parents: forward transform of the (real) modulus with the thread's two columns as one
+//     complex pair, rows 0..64 only.
+// Four waves per SIMD: 128 vector registers (launch bounds).
 template <int A, int P, bool POLY>
 __global__ __launch_bounds__(512, 4) void k_node_half(NodeArgs a) {
   constexpr int M = 128, T = 8, NT = 512, S = M * A;
