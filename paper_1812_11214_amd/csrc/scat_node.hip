@@ -455,7 +455,7 @@ __global__ __launch_bounds__(512, 4) void k_node_half(NodeArgs a) {
   constexpr int RSR = 152, RSC = 72;
   constexpr int DEC = M / kOut, R = 4 * DEC, NTAP = 2 * R + 1;
   extern __shared__ __attribute__((aligned(16))) float2 lds[];
-  float2 *area = lds;             // 64 * RSR = 128 * RSC elements
+  float2 *area = lds;             // 64 * RSR elements (128 * RSC fit in them)
   float2 *wtab = lds + 64 * RSR;  // twiddles: [k * T + t] for rows, the same again for columns
   const int tid = threadIdx.x;
   const int I = a.F * (POLY ? 4 : 1);

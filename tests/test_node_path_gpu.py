@@ -16,7 +16,8 @@ pytestmark = pytest.mark.gpu
 
 @pytest.mark.parametrize("n,J,L,max_order,batch", [
     (256, 3, 8, 2, 2), (256, 3, 3, 2, 3), (256, 3, 5, 1, 1), (256, 3, 1, 2, 5),
-    (128, 2, 8, 2, 3), (128, 2, 5, 2, 7), (128, 2, 4, 1, 2),
+    (256, 3, 2, 2, 9), (256, 3, 6, 2, 1), (256, 3, 7, 2, 2),
+    (128, 2, 8, 2, 3), (128, 2, 5, 2, 7), (128, 2, 4, 1, 2), (128, 2, 7, 2, 11),
 ])
 def test_node_schedule_white_noise(n, J, L, max_order, batch):
     rng = np.random.default_rng(1000 * n + 10 * L + batch)
