@@ -126,6 +126,10 @@ struct scat_plan {
   // per wavelet table: which (N >> j2) x (N >> j2) blocks of it are not negligible (bit
   // a_r * A + a_c); mask_off[{res, j2}] -> L words in d_masks
   unsigned *d_masks = nullptr;
+  // the same for the row pass of the general 2-D schedule (any grid; 64-bit words, bit
+  // a_r * A_c + a_c): mask64_off[{res, j}] -> L words in d_masks64 (absent when A_r * A_c > 64)
+  unsigned long long *d_masks64 = nullptr;
+  std::map<std::pair<int, int>, size_t> mask64_off;
   std::map<std::pair<int, int>, size_t> mask_off;
   // 3-D solid harmonic plans (host.dims == 3; host carries J, LQ = L, max_order, K only)
   scat::HostPlan3D h3;
@@ -309,6 +313,8 @@ void free_device(scat_plan *p) {
   if (p->d_scratch) (void)hipFree(p->d_scratch);
   if (p->d_masks) (void)hipFree(p->d_masks);
   p->d_masks = nullptr;
+  if (p->d_masks64) (void)hipFree(p->d_masks64);
+  p->d_masks64 = nullptr;
   p->d_tables = nullptr;
   p->d_tw = nullptr;
   p->d_scratch = nullptr;
@@ -388,6 +394,42 @@ scat_status upload(scat_plan *p) {
         for (size_t k = 0; k < len; ++k) acc += ph[k] * std::cos(two_pi_ * static_cast<double>((k * m) % len) / len);
         pool.push_back(static_cast<float>(acc / static_cast<double>(len)));
       }
+    }
+  }
+  if (h.dims == 2 && !p->tree && h.oversampling == 0) {
+    // alias blocks of (n1 >> j) x (n2 >> j) points on which a wavelet of octave j stays below
+    // 1e-7 of its peak: skipped by the row pass of the general schedule
+    std::vector<unsigned long long> m64;
+    for (int j = 1; j < h.J; ++j)
+      for (int r = 0; r < j; ++r) {
+        if (r > 0 && h.max_order < 2) continue;
+        const int sr = p->n1 >> r, sc = p->n2 >> r;
+        const int br = p->n1 >> j, bc = p->n2 >> j;
+        if (br < 1 || bc < 1) continue;
+        const int Ar = sr / br, Ac = sc / bc;
+        if (Ar * Ac > 64 || Ar * Ac < 2) continue;
+        p->mask64_off[{r, j}] = m64.size();
+        for (int l = 0; l < h.LQ; ++l) {
+          const FilterTable &t = *h.find(r == 0 ? 1 : 2, j * h.LQ + l, r);
+          double peak = 0.0;
+          for (double v : t.v) peak = std::max(peak, std::fabs(v));
+          unsigned long long m = 0;
+          for (int ar = 0; ar < Ar; ++ar)
+            for (int ac = 0; ac < Ac; ++ac) {
+              double big = 0.0;
+              for (int i = 0; i < br; ++i)
+                for (int k = 0; k < bc; ++k)
+                  big = std::max(big, std::fabs(t.v[static_cast<size_t>(ar * br + i) * sc + ac * bc + k]));
+              if (big > 1e-7 * peak) m |= 1ull << (ar * Ac + ac);
+            }
+          m64.push_back(m);
+        }
+      }
+    if (!m64.empty()) {
+      if (hipMalloc(&p->d_masks64, m64.size() * sizeof(unsigned long long)) != hipSuccess) return SCAT_ERR_ALLOC;
+      if (hipMemcpy(p->d_masks64, m64.data(), m64.size() * sizeof(unsigned long long),
+                    hipMemcpyHostToDevice) != hipSuccess)
+        return SCAT_ERR_DEVICE;
     }
   }
   if (p->node_tables) {
@@ -972,8 +1014,14 @@ scat_status forward_2d(scat_plan *p, const float *in, float *out, long p0, long 
     // transform (the backward kernels transform the columns themselves): the row pass writes
     // into the tape, a leaf needs no column kernel, a node with children only its spectra.
     float2 *t1 = tape ? tape->base + tape->y1_off[j1] * pc : T;
+    auto mask_of = [&](int r, int j) -> const unsigned long long * {
+      auto it = p->mask64_off.find({r, j});
+      return (p->d_masks64 != nullptr && it != p->mask64_off.end() && h.res(j) == j && h.res(r) == r)
+                 ? p->d_masks64 + it->second
+                 : nullptr;
+    };
     SCAT_TRY(scat::launch_mulfold_invrow(XH, tab + p->psi1_off[j1], t1, pc, L, Nr, Nc, r1, r1, 0,
-                                         tw, tw_n, st));
+                                         tw, tw_n, st, mask_of(0, j1)));
     if (tape != nullptr && !kids) continue;
     if (lp && !kids && scat::leaf_node_supported(M1r, M1c, m_r, m_c, tw_n)) {
       SCAT_TRY(scat::launch_leaf_node(t1, pc * L, M1r, m_r, tab + p->phi_rows_off[r1],
@@ -995,7 +1043,7 @@ scat_status forward_2d(scat_plan *p, const float *in, float *out, long p0, long 
       const int M2r = Nr >> r2, M2c = Nc >> r2;
       float2 *t2 = tape ? tape->base + tape->y2_off.at({j1, j2}) * pc : T;
       SCAT_TRY(scat::launch_mulfold_invrow(U, tab + p->psi2_off[{r1, j2}], t2, pc * L, L, M1r, M1c,
-                                           r2 - r1, r2 - r1, 0, tw, tw_n, st));
+                                           r2 - r1, r2 - r1, 0, tw, tw_n, st, mask_of(j1, j2)));
       if (tape != nullptr) continue;
       const ChanMap cm2{L * L, L, octs * L, s2_base + (j2 - j1 - 1) * L};
       if (scat::leaf_node_supported(M2r, M2c, m_r, m_c, tw_n)) {  // the whole leaf in one kernel

@@ -229,7 +229,7 @@ template <int E, int T, bool MULTI>
 __global__ __launch_bounds__(E == 32 ? 128 : 256) void k_mulfold_reg(
     const float2 *__restrict__ src, const float *__restrict__ filt, float2 *__restrict__ dst,
     long rows, int F, int Sr, int Sc, int fr, int fc, int lgMr, int post_tw_m,
-    const float2 *__restrict__ tw, int tw_n) {
+    const float2 *__restrict__ tw, int tw_n, const unsigned long long *__restrict__ mask) {
   constexpr int NT = E == 32 ? 128 : 256;
   constexpr int RPB = NT / T, M = E * T;
   extern __shared__ float2 lds[];
@@ -291,10 +291,20 @@ __global__ __launch_bounds__(E == 32 ? 128 : 256) void k_mulfold_reg(
       for (int j = 0; j < FB; ++j)
 #pragma unroll
         for (int e = 0; e < CPL; ++e) acc[j][e] = make_float2(0.f, 0.f);
+      // alias blocks (a, b) on which every filter of the run is negligible are left out (mask:
+      // per filter, bit a * nsteps + b set = block in use; M >= 64 only, so that a column step
+      // is one alias block).  A test per filter inside the block measured slower: its branches
+      // serialise the loads.
+      unsigned long long used = ~0ull;
+      if (mask != nullptr) {
+        used = 0ull;
+        for (int j = 0; j < n; ++j) used |= mask[f_r + j];
+      }
       for (int a = 0; a < nfr; ++a) {
         const size_t ro = static_cast<size_t>(q_r + a * Mr) * Sc;
 #pragma unroll 2
         for (int b = 0; b < nsteps; ++b) {
+          if (!((used >> (a * nsteps + b)) & 1ull)) continue;
           const size_t o = ro + static_cast<size_t>(b) * W;
           float2 x[CPL];
 #pragma unroll
@@ -1778,7 +1788,7 @@ int pow2_floor(int v) {
 template <int E, int T>
 hipError_t launch_mulfold_reg_t(const float2 *src, const float *filt, float2 *dst, long S, int F,
                                 int Sr, int Sc, int fr, int fc, int post_tw_m, const float2 *tw,
-                                int tw_n, hipStream_t st) {
+                                int tw_n, hipStream_t st, const unsigned long long *mask) {
   constexpr int NT = E == 32 ? 128 : 256, RPB = NT / T;
   const int Mr = Sr >> fr, Mc = Sc >> fc;
   int lgMr = 0;
@@ -1792,6 +1802,9 @@ hipError_t launch_mulfold_reg_t(const float2 *src, const float *filt, float2 *ds
   const size_t lds = static_cast<size_t>(RPB) * (T == 1 ? E : E * (T + 1)) * sizeof(float2);
   const double spts = static_cast<double>(S) * Sr * Sc, opts = static_cast<double>(S) * F * Mr * Mc;
   const bool multi = F >= 2 && (E * T >= 64 || (E * T >= 32 && Sc >= 64));
+  // block masks: rows of at least 64 points (a column step of the kernel is one alias block)
+  // and at most 64 blocks
+  const unsigned long long *mk = (E * T >= 64 && fr + fc <= 6) ? mask : nullptr;
   const std::string name = "k_mulfold_reg<" + std::to_string(E) + ", " + std::to_string(T) +
                            (multi ? ", true>" : ", false>");
   Observe ob(name.c_str(), spts * 8 + static_cast<double>(F) * Sr * Sc * 4 + opts * 8,
@@ -1799,10 +1812,10 @@ hipError_t launch_mulfold_reg_t(const float2 *src, const float *filt, float2 *ds
   if (multi)
     hipLaunchKernelGGL((k_mulfold_reg<E, T, true>), dim3(static_cast<unsigned>(blocks)),
                        dim3(NT), lds, st, src, filt, dst, rows, F, Sr, Sc, fr, fc, lgMr, post_tw_m,
-                       tw, tw_n);
+                       tw, tw_n, mk);
   else
     hipLaunchKernelGGL((k_mulfold_reg<E, T, false>), dim3(static_cast<unsigned>(blocks)), dim3(NT),
-                       lds, st, src, filt, dst, rows, F, Sr, Sc, fr, fc, lgMr, post_tw_m, tw, tw_n);
+                       lds, st, src, filt, dst, rows, F, Sr, Sc, fr, fc, lgMr, post_tw_m, tw, tw_n, mk);
   return hipGetLastError();
 }
 
@@ -1894,10 +1907,10 @@ hipError_t launch_rows1d(const float2 *src, long nodes, int Sr, int Sc, const Ro
 
 hipError_t launch_mulfold_invrow(const float2 *src, const float *filt, float2 *dst, long S, int F,
                                  int Sr, int Sc, int fr, int fc, int post_tw_m, const float2 *tw,
-                                 int tw_n, hipStream_t st) {
+                                 int tw_n, hipStream_t st, const unsigned long long *mask) {
   const int Mr = Sr >> fr, Mc = Sc >> fc;
 #define SCAT_MF(E_, T_) \
-  return launch_mulfold_reg_t<E_, T_>(src, filt, dst, S, F, Sr, Sc, fr, fc, post_tw_m, tw, tw_n, st)
+  return launch_mulfold_reg_t<E_, T_>(src, filt, dst, S, F, Sr, Sc, fr, fc, post_tw_m, tw, tw_n, st, mask)
   if (S > 0 && F > 0 && Mr >= 1) {
     switch (Mc) {
       case 4: SCAT_MF(4, 1);

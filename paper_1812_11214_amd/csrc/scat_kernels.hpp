@@ -48,9 +48,12 @@ struct ChanMap {
   int G, inner, outer_stride, base;
 };
 
+// mask (optional, device): per filter a 64-bit word, bit a_r * 2^fc + a_c set = the alias block
+// (a_r, a_c) of (Sr >> fr) x (Sc >> fc) points holds values that matter; blocks whose bit is
+// clear for every filter processed together are skipped (needs 2^(fr + fc) <= 64).
 hipError_t launch_mulfold_invrow(const float2 *src, const float *filt, float2 *dst, long S, int F,
                                  int Sr, int Sc, int fr, int fc, int post_tw_m, const float2 *tw,
-                                 int tw_n, hipStream_t st);
+                                 int tw_n, hipStream_t st, const unsigned long long *mask = nullptr);
 
 hipError_t launch_col(int mode, const void *src, long nodes, int Mr, int Mc, float2 *uc,
                       int post_tw_m, const float *phi_rows, int m_r, float *w_out, float *out,
