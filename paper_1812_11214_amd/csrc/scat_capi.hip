@@ -112,7 +112,9 @@ struct scat_plan {
   // 2-D: every node of the tree is computed by one workgroup (scat_node.hip): forward calls
   // keep only the spectra of x and of the first-order moduli with children in scratch
   bool node = false;
-  bool node_tables = false;  // shapes the whole-node kernels serve: their taps and masks are uploaded
+  bool node_tables = false;  // shapes the whole-node schedule serves: its filter tables are uploaded
+  bool node_taps = false;    // square grids with a 32 x 32 output grid: the spatial lowpass taps of the
+                             // whole-node kernels are uploaded (children of 64 or 128 points a side)
   std::map<int, size_t> poly_psi_off;          // j2 -> [L][4][N/2][N/2] sign-folded wavelets
   // (res, j) -> the L wavelets of octave j on the grid of resolution res in the layout of the
   // whole-node kernels whose source is twice as large as the node (M = side / 2).  M = 128:
@@ -123,14 +125,11 @@ struct scat_plan {
   std::map<std::pair<int, int>, size_t> node2_off;
   std::vector<size_t> taps_r_off, taps_c_off;  // per res: spatial lowpass taps [2R+1]
   size_t ptaps_r_off = 0, ptaps_c_off = 0;     // polyphase taps of resolution 0: [2][2R+1]
-  // per wavelet table: which (N >> j2) x (N >> j2) blocks of it are not negligible (bit
-  // a_r * A + a_c); mask_off[{res, j2}] -> L words in d_masks
-  unsigned *d_masks = nullptr;
-  // the same for the row pass of the general 2-D schedule (any grid; 64-bit words, bit
-  // a_r * A_c + a_c): mask64_off[{res, j}] -> L words in d_masks64 (absent when A_r * A_c > 64)
+  // per wavelet table: which (n1 >> j) x (n2 >> j) alias blocks of it are not negligible (bit
+  // a_r * A_c + a_c); mask64_off[{res, j}] -> L words in d_masks64 (absent when A_r * A_c > 64).
+  // Read by the whole-node kernels and by the row pass of the general 2-D schedule.
   unsigned long long *d_masks64 = nullptr;
   std::map<std::pair<int, int>, size_t> mask64_off;
-  std::map<std::pair<int, int>, size_t> mask_off;
   // 3-D solid harmonic plans (host.dims == 3; host carries J, LQ = L, max_order, K only)
   scat::HostPlan3D h3;
   std::vector<size_t> psi3_off;  // per (j, l): its 2l+1 tables, contiguous
@@ -311,8 +310,6 @@ void free_device(scat_plan *p) {
   if (p->d_tables) (void)hipFree(p->d_tables);
   if (p->d_tw) (void)hipFree(p->d_tw);
   if (p->d_scratch) (void)hipFree(p->d_scratch);
-  if (p->d_masks) (void)hipFree(p->d_masks);
-  p->d_masks = nullptr;
   if (p->d_masks64) (void)hipFree(p->d_masks64);
   p->d_masks64 = nullptr;
   p->d_tables = nullptr;
@@ -432,7 +429,7 @@ scat_status upload(scat_plan *p) {
         return SCAT_ERR_DEVICE;
     }
   }
-  if (p->node_tables) {
+  if (p->node_taps) {
     const int N = p->n1;
     const double two_pi_ = 6.283185307179586476925286766559;
     // spatial taps of a lowpass factor: g[d] = (1/len) sum_k phi[k] cos(2 pi k d / len)
@@ -461,6 +458,7 @@ scat_status upload(scat_plan *p) {
     p->taps_c_off.assign(h.J, 0);
     for (int r = 0; r < h.J; ++r) {
       const int len = N >> r;
+      if (len > 256) continue;  // no whole-node kernel for such nodes
       const std::vector<double> gr = spatial(h.phi_rows[r]), gc = spatial(h.phi_cols[r]);
       if (len > 128) {
         // components of len/2 points: taps phi[2 d - p], p = 0, 1
@@ -475,37 +473,7 @@ scat_status upload(scat_plan *p) {
         p->taps_c_off[r] = push_taps(gc, R, 1, 0);
       }
     }
-    // blocks of (N >> j2) points a side on which a wavelet stays below 1e-7 of its peak are
-    // skipped by the node kernels (their sum is far below fp32 rounding of the rest)
-    std::vector<unsigned> masks;
-    for (int j2 = 1; j2 < h.J; ++j2)
-      for (int r = 0; r < j2; ++r) {
-        if (r > 0 && h.max_order < 2) continue;
-        p->mask_off[{r, j2}] = masks.size();
-        const int side = N >> r, blk = N >> j2, A = side / blk;
-        for (int l = 0; l < h.LQ; ++l) {
-          const FilterTable &t = *h.find(r == 0 ? 1 : 2, j2 * h.LQ + l, r);
-          double peak = 0.0;
-          for (double v : t.v) peak = std::max(peak, std::fabs(v));
-          unsigned m = 0;
-          for (int ar = 0; ar < A; ++ar)
-            for (int ac = 0; ac < A; ++ac) {
-              double big = 0.0;
-              for (int i = 0; i < blk; ++i)
-                for (int k = 0; k < blk; ++k)
-                  big = std::max(big, std::fabs(t.v[static_cast<size_t>(ar * blk + i) * side + ac * blk + k]));
-              if (big > 1e-7 * peak) m |= 1u << (ar * A + ac);
-            }
-          masks.push_back(m);
-        }
-      }
-    if (!masks.empty()) {
-      if (hipMalloc(&p->d_masks, masks.size() * sizeof(unsigned)) != hipSuccess) return SCAT_ERR_ALLOC;
-      if (hipMemcpy(p->d_masks, masks.data(), masks.size() * sizeof(unsigned), hipMemcpyHostToDevice) !=
-          hipSuccess)
-        return SCAT_ERR_DEVICE;
-    }
-    {
+    if (p->node_tables) {
       std::vector<std::pair<int, int>> want;
       if (N > 128) want.push_back({0, 0});
       for (int r = 0; r + 1 < h.J; ++r)
@@ -735,6 +703,7 @@ scat_status create_common(scat_plan **out_plan, int dims, const int *user_shape,
   p->node_tables = dims == 2 && oversampling == 0 && p->n1 == p->n2 &&
                    ((p->n1 == 256 && J == 3) || (p->n1 == 128 && J == 2));
   p->node = node_kernels && p->node_tables;
+  p->node_taps = dims == 2 && oversampling == 0 && p->n1 == p->n2 && J < 31 && (p->n1 >> J) == 32;
   if (padded) {
     p->padded = true;
     for (int d = 0; d < dims; ++d) {
@@ -1041,6 +1010,35 @@ scat_status forward_2d(scat_plan *p, const float *in, float *out, long p0, long 
     for (int j2 = j1 + 1; j2 < J; ++j2) {
       const int r2 = h.res(j2);
       const int M2r = Nr >> r2, M2c = Nc >> r2;
+      if (lp && p->node_taps && M2r == M2c && (M2r == 64 || M2r == 128) && m_r == 32 &&
+          mask_of(j1, j2) != nullptr && scat::node_supported(M2r, M1r / M2r, 1, false, true)) {
+        // children of 64 or 128 points a side: one workgroup per child, fed by its parent's
+        // whole spectrum (no row-pass output, column pass or lowpass pass through memory)
+        scat::NodeLaunch c{};
+        c.M = M2r;
+        c.A = M1r / M2r;
+        c.P = 1;
+        c.poly = false;
+        c.full = true;
+        c.src = U;
+        c.filt = tab + p->psi2_off[{r1, j2}];
+        c.mask = mask_of(j1, j2);
+        c.taps_r = tab + p->taps_r_off[r2];
+        c.taps_c = tab + p->taps_c_off[r2];
+        c.uout = nullptr;
+        c.out = o;
+        c.NS = pc * L;
+        c.F = L;
+        c.G = L;
+        c.chan_base = s2_base + (j2 - j1 - 1) * L;
+        c.chan_src = octs * L;
+        c.chan_f = 1;
+        c.K = K;
+        c.tw = tw;
+        c.tw_n = tw_n;
+        SCAT_TRY(scat::launch_node(c, st));
+        continue;
+      }
       float2 *t2 = tape ? tape->base + tape->y2_off.at({j1, j2}) * pc : T;
       SCAT_TRY(scat::launch_mulfold_invrow(U, tab + p->psi2_off[{r1, j2}], t2, pc * L, L, M1r, M1c,
                                            r2 - r1, r2 - r1, 0, tw, tw_n, st, mask_of(j1, j2)));
@@ -1232,7 +1230,7 @@ scat_status forward_2d_node(scat_plan *p, const float *in, float *out, long p0, 
     a.src = XH;
     const bool a2 = a.A == 2;  // kernels that read the paired-column table
     a.filt = tab + (a2 ? p->node2_off.at({0, j1}) : p->psi1_off[j1]);
-    a.mask = (!poly && j1 > 0 && !a2) ? p->d_masks + p->mask_off.at({0, j1}) : nullptr;
+    a.mask = (!poly && j1 > 0 && !a2) ? p->d_masks64 + p->mask64_off.at({0, j1}) : nullptr;
     a.taps_r = tab + (poly ? p->ptaps_r_off : p->taps_r_off[j1]);
     a.taps_c = tab + (poly ? p->ptaps_c_off : p->taps_c_off[j1]);
     a.uout = kids ? U : nullptr;
@@ -1259,7 +1257,7 @@ scat_status forward_2d_node(scat_plan *p, const float *in, float *out, long p0, 
       c.src = U;
       const bool c2 = !poly && c.A == 2;
       c.filt = tab + (poly ? p->poly_psi_off.at(j2) : c2 ? p->node2_off.at({j1, j2}) : p->psi2_off.at({j1, j2}));
-      c.mask = (poly || c2) ? nullptr : p->d_masks + p->mask_off.at({j1, j2});
+      c.mask = (poly || c2) ? nullptr : p->d_masks64 + p->mask64_off.at({j1, j2});
       c.taps_r = tab + p->taps_r_off[j2];
       c.taps_c = tab + p->taps_c_off[j2];
       c.uout = nullptr;

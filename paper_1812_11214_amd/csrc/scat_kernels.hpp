@@ -201,9 +201,10 @@ hipError_t launch_tree32(const float2 *xh, long planes, int L, int max_order, co
 struct NodeLaunch {
   int M, A, P;
   bool poly;
+  bool full;  // src holds all S rows of one spectrum per node ([NS][S][S]) instead of rows 0 .. S/2
   const float2 *src;
   const float *filt;
-  const unsigned *mask;  // null, or [F] device words: bit (q A + a_r) A + a_c set = block in use
+  const unsigned long long *mask;  // null, or [F] device words: bit (q A + a_r) A + a_c set = block in use
   const float *taps_r, *taps_c;
   float2 *uout;
   float *out;
@@ -213,7 +214,7 @@ struct NodeLaunch {
   const float2 *tw;
   int tw_n;
 };
-bool node_supported(int M, int A, int P, bool poly);
+bool node_supported(int M, int A, int P, bool poly, bool full = false);
 hipError_t launch_node(const NodeLaunch &n, hipStream_t st);
 // out[plane][chan_base + g][32][32] = sum of the four parts of node plane * G + g
 hipError_t launch_sum4(const float *part, float *out, long nodes, int G, int K, int chan_base,

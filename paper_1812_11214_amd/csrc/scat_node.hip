@@ -44,10 +44,10 @@ constexpr int kOut = 32;  // side of the output grid the FIR stage is laid out f
 double fft2_flops(double n) { return n > 1 ? 10.0 * n * n * std::log2(n) : 0.0; }
 
 struct NodeArgs {
-  const float2 *src;    // [NS][P][S/2+1][S] half spectra, S = M * A
+  const float2 *src;    // [NS][P][S/2+1][S] half spectra, S = M * A (FULL: [NS][S][S], all rows)
   const float *filt;    // [F][P][S][S] real tables (carry the 1/N^2 of the inverse transforms)
-  const unsigned *mask; // null, or per filter: bit (q A + ar) A + ac clear = that M x M block of
-                        // table q is negligible everywhere and is skipped
+  const unsigned long long *mask;  // null, or per filter: bit (q A + ar) A + ac clear = that M x M
+                                   // block of table q is negligible everywhere and is skipped
   const float *taps_r;  // lowpass taps along a column (row index varies): [2R+1], POLY: [2][2R+1]
   const float *taps_c;  // along a row
   float2 *uout;         // null, or [(NS*I)][M/2+1][M]: half spectrum of every node's modulus
@@ -79,8 +79,9 @@ __device__ __forceinline__ void load_comps(float (&d)[P], const float *tab, int 
   }
 }
 
-template <int M, int A, int P, bool POLY>
+template <int M, int A, int P, bool POLY, bool FULL>
 __global__ __launch_bounds__(M * M / 16, 3) void k_node(NodeArgs a) {
+  static_assert(!FULL || P == 1, "a full spectrum is one source");
   static_assert(M == 64, "128 x 128 nodes take k_node_half");
   using SL = Slab<M, M>;
   constexpr int NT = M * M / 16, T = M / 16, S = M * A, RS = SL::RS;
@@ -103,7 +104,7 @@ __global__ __launch_bounds__(M * M / 16, 3) void k_node(NodeArgs a) {
   SL::fill_twiddles(wtab, a.tw, a.tw_n, false);
   const int tw_step = a.tw_n / (2 * M);  // POLY only: table step of w = exp(-2 pi i / 2M)
 
-  if constexpr (A == 2) {
+  if constexpr (A == 2 && !FULL) {
     // ---- 1 (source twice as large as the node). Every stored source row (0 .. 64, 128 columns)
     // is read once, by half a wavefront: a lane takes two adjacent columns of both column
     // blocks and of all P components (16-byte loads).  Row rho contributes to row rho of the
@@ -274,22 +275,24 @@ __global__ __launch_bounds__(M * M / 16, 3) void k_node(NodeArgs a) {
   // pass of the loop takes one alias block of one source (all 16 rows of the thread: 32 loads
   // in flight); blocks on which the filter is negligible are left out.
   {
-    const float2 *src = a.src + static_cast<size_t>(s) * P * (S / 2 + 1) * S;
+    constexpr int SROWS = FULL ? S : S / 2 + 1;  // stored rows of a source
+    const float2 *src = a.src + static_cast<size_t>(s) * P * SROWS * S;
     const float *filt = a.filt + static_cast<size_t>(f) * P * S * S;
     // (the row group is the same for all lanes of a wave: kept scalar, so that row addresses are
     // scalar bases with one lane offset)
     const int col = tid % M, rg = __builtin_amdgcn_readfirstlane(tid / M);
     {
       float2 acc[16];
-      constexpr unsigned kAll = P * A * A >= 32 ? 0xffffffffu : (1u << (P * A * A)) - 1u;
-      unsigned rem = (a.mask != nullptr ? a.mask[f] : 0xffffffffu) & kAll;  // workgroup-uniform
+      static_assert(P * A * A <= 64, "one mask word per filter");
+      constexpr unsigned long long kAll = P * A * A >= 64 ? ~0ull : (1ull << (P * A * A)) - 1ull;
+      unsigned long long rem = (a.mask != nullptr ? a.mask[f] : ~0ull) & kAll;  // workgroup-uniform
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[i] = make_float2(0.f, 0.f);
-      while (rem != 0u) {
-        const int bit = __builtin_amdgcn_readfirstlane(__ffs(rem) - 1);
-        rem &= rem - 1u;
+      while (rem != 0ull) {
+        const int bit = __builtin_amdgcn_readfirstlane(__ffsll(static_cast<long long>(rem)) - 1);
+        rem &= rem - 1ull;
         const int ac = bit % A, ar = (bit / A) % A, q = bit / (A * A);
-        const float2 *sq = src + static_cast<size_t>(q) * (S / 2 + 1) * S;
+        const float2 *sq = src + static_cast<size_t>(q) * SROWS * S;
         const float *fq = filt + static_cast<size_t>(q) * S * S + (M * ar) * S;
         const unsigned kc = static_cast<unsigned>(col + M * ac) & (S - 1);
         const unsigned kcm = (S - kc) & (S - 1);
@@ -304,13 +307,13 @@ __global__ __launch_bounds__(M * M / 16, 3) void k_node(NodeArgs a) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           const int kr = rg + T * i + M * ar;
-          const bool mir = kr > S / 2;  // the same for every lane of a wave
+          const bool mir = !FULL && kr > S / 2;  // the same for every lane of a wave
           v[i] = (sq + (mir ? S - kr : kr) * S)[mir ? kcm : kc];
           fv[i] = (fq + (rg + T * i) * S)[kc];
         }
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          const bool mir = rg + T * i + M * ar > S / 2;
+          const bool mir = !FULL && rg + T * i + M * ar > S / 2;
           const float fx = fv[i] * (mir ? smir : sblk);
           acc[i].x = fmaf(v[i].x, fx, acc[i].x);
           acc[i].y = fmaf(v[i].y, mir ? -fx : fx, acc[i].y);
@@ -449,8 +452,9 @@ __global__ __launch_bounds__(M * M / 16, 3) void k_node(NodeArgs a) {
 //   parents: forward transform of the (real) modulus with the thread's two columns as one
 //     complex pair, rows 0..64 only.
 // Four waves per SIMD: 128 vector registers (launch bounds).
-template <int A, int P, bool POLY>
+template <int A, int P, bool POLY, bool FULL>
 __global__ __launch_bounds__(512, 4) void k_node_half(NodeArgs a) {
+  static_assert(!FULL || P == 1, "a full spectrum is one source");
   constexpr int M = 128, T = 8, NT = 512, S = M * A;
   constexpr int RSR = 152, RSC = 72;
   constexpr int DEC = M / kOut, R = 4 * DEC, NTAP = 2 * R + 1;
@@ -479,7 +483,7 @@ __global__ __launch_bounds__(512, 4) void k_node_half(NodeArgs a) {
 
   // ---- 1 + 2a. spectrum of the node (half of its rows at a time) and inverse row transforms
   float2 vh[2][16];
-  if constexpr (A == 1 && P == 4 && !POLY) {
+  if constexpr (A == 1 && P == 4 && !POLY && !FULL) {
     // Children of a polyphase parent.  Every stored source row r (1 .. 63) is read once and
     // serves two rows of the node: row r directly and row M - r through the conjugate symmetry
     // W_q[M - r][-c] = s_q(c) conj(W_q[r][c]) of the stored spectra (s_q: the sign the phase
@@ -559,7 +563,7 @@ __global__ __launch_bounds__(512, 4) void k_node_half(NodeArgs a) {
     for (int i = 0; i < 16; ++i) vh[1][i] = area[r * RSR + t + T * i];
     __syncthreads();
     fft_core_tab<16, T, true, false>(vh[1], t, area + r * RSR, T + 1, 1, wl, T);
-  } else if constexpr (A == 2 && P == 1) {
+  } else if constexpr (A == 2 && P == 1 && !FULL) {
     // Source twice as large as the node (the spectrum of x, or of a 256 x 256 parent).  A wave
     // takes one stored source row (0 .. 128; 256 columns) at a time, a lane two adjacent columns
     // of both column blocks (16-byte loads).  Row rho contributes to row rho of the node
@@ -656,45 +660,60 @@ __global__ __launch_bounds__(512, 4) void k_node_half(NodeArgs a) {
     __syncthreads();
     fft_core_tab<16, T, true, false>(vh[1], t, area + r * RSR, T + 1, 1, wl, T);
   } else {
-    const float2 *src = a.src + static_cast<size_t>(s) * P * (S / 2 + 1) * S;
+    // Any source: thread = one column, rows rg + 4 i of a half of the node.  One pass of the
+    // inner loop takes one alias block of one source (all 16 rows of the thread: 32 loads in
+    // flight); alias blocks on which the filter is negligible are left out.
+    constexpr int SROWS = FULL ? S : S / 2 + 1;  // stored rows of a source
+    const float2 *src = a.src + static_cast<size_t>(s) * P * SROWS * S;
     const float *filt = a.filt + static_cast<size_t>(f) * P * S * S;
     const int col = tid % M;
     const int rg = __builtin_amdgcn_readfirstlane(tid / M);  // 0..3, the same for a wave
+    static_assert(P * A * A <= 64, "one mask word per filter");
+    constexpr unsigned long long kAll = P * A * A >= 64 ? ~0ull : (1ull << (P * A * A)) - 1ull;
+    const unsigned long long used = ((P == 1 && a.mask != nullptr) ? a.mask[f] : ~0ull) & kAll;  // uniform
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-#pragma unroll 2
+      float2 acc[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[i] = make_float2(0.f, 0.f);
+      unsigned long long rem = used;
+      while (rem != 0ull) {
+        const int bit = __builtin_amdgcn_readfirstlane(__ffsll(static_cast<long long>(rem)) - 1);
+        rem &= rem - 1ull;
+        const int ac = bit % A, ar = (bit / A) % A, q = bit / (A * A);
+        const float2 *sq = src + static_cast<size_t>(q) * SROWS * S;
+        const float *fq = filt + static_cast<size_t>(q) * S * S + (M * ar + 64 * h) * S;
+        const unsigned kc = static_cast<unsigned>(col + M * ac) & (S - 1);
+        const unsigned kcm = (S - kc) & (S - 1);
+        // sign of the whole block: polyphase alias sign (-1)^(a.p)
+        const float sblk = (POLY && ((ar * pr + ac * pc) & 1)) ? -1.f : 1.f;
+        // rows above S/2 are not stored: U[kr][kc] = conj(U[S - kr][-kc]); the stored spectra of
+        // polyphase components carry w^(p.k), which gives the mirrored value the extra sign
+        // (-1)^(q_r) (-1)^(q_c [kc != 0])
+        const float smir = (P == 4 && (((q >> 1) & 1) ^ ((q & 1) & (kc != 0 ? 1 : 0)))) ? -sblk : sblk;
+        float2 v[16];
+        float fv[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int kr = 64 * h + rg + 4 * i + M * ar;
+          const bool mir = !FULL && kr > S / 2;  // the same for every lane of a wave
+          v[i] = (sq + (mir ? S - kr : kr) * S)[mir ? kcm : kc];
+          fv[i] = (fq + (rg + 4 * i) * S)[kc];
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const bool mir = !FULL && 64 * h + rg + 4 * i + M * ar > S / 2;
+          const float fx = fv[i] * (mir ? smir : sblk);
+          acc[i].x = fmaf(v[i].x, fx, acc[i].x);
+          acc[i].y = fmaf(v[i].y, mir ? -fx : fx, acc[i].y);
+        }
+      }
+#pragma unroll
       for (int i = 0; i < 16; ++i) {
         const int lr = rg + 4 * i;  // row within the half
-        const int kr0 = 64 * h + lr;
-        float2 z = make_float2(0.f, 0.f);
-#pragma unroll
-        for (int q = 0; q < P; ++q) {
-          const float2 *sq = src + static_cast<size_t>(q) * (S / 2 + 1) * S;
-          const float *fq = filt + static_cast<size_t>(q) * S * S;
-#pragma unroll
-          for (int ar = 0; ar < A; ++ar) {
-            const int kr = kr0 + M * ar;
-            const bool mir = kr > S / 2;  // the same for every lane of a wave
-            const int krs = mir ? S - kr : kr;
-#pragma unroll
-            for (int ac = 0; ac < A; ++ac) {
-              const unsigned kc = static_cast<unsigned>(col + M * ac) & (S - 1);
-              const unsigned kcs = mir ? (S - kc) & (S - 1) : kc;
-              const float2 v = (sq + krs * S)[kcs];
-              float fv = (fq + kr * S)[kc];
-              if (POLY && ((ar * pr + ac * pc) & 1)) fv = -fv;
-              float fx = fv, fy = fv;
-              if (mir) {
-                if (P == 4 && (((q >> 1) & 1) ^ ((q & 1) & (kc != 0 ? 1 : 0)))) fx = -fx;
-                fy = -fx;
-              }
-              z.x = fmaf(v.x, fx, z.x);
-              z.y = fmaf(v.y, fy, z.y);
-            }
-          }
-        }
+        float2 z = acc[i];
         if (POLY) {
-          const float2 w = a.tw[((pr * kr0 + pc * col) * tw_step) & (a.tw_n - 1)];
+          const float2 w = a.tw[((pr * (64 * h + lr) + pc * col) * tw_step) & (a.tw_n - 1)];
           z = make_float2(z.x * w.x + z.y * w.y, z.y * w.x - z.x * w.y);  // * conj(w)
         }
         area[lr * RSR + col] = z;
@@ -875,7 +894,7 @@ __global__ __launch_bounds__(256) void k_sum4(const float *__restrict__ part, fl
   out[(plane * K + chan_base + g) * PL + e] = (p[0] + p[PL]) + (p[2 * PL] + p[3 * PL]);
 }
 
-template <int M, int A, int P, bool POLY>
+template <int M, int A, int P, bool POLY, bool FULL = false>
 hipError_t launch_node_t(const NodeArgs &a, hipStream_t st) {
   using SL = Slab<M, M>;
   constexpr int S = M * A;
@@ -884,11 +903,11 @@ hipError_t launch_node_t(const NodeArgs &a, hipStream_t st) {
   if (a.NS <= 0 || blocks > 0x7fffffffL || a.tw_n % (POLY ? 2 * M : M) != 0) return hipErrorInvalidValue;
   const size_t lds = SL::lds_bytes + SL::tab_elems * sizeof(float2);
   const std::string name = (M == 128 ? "k_node_half<" : "k_node<64, ") + std::to_string(A) + ", " +
-                            std::to_string(P) + (POLY ? ", true>" : ", false>");
+                            std::to_string(P) + (POLY ? ", true" : ", false") + (FULL ? ", full>" : ">");
   const double items = static_cast<double>(a.NS) * I;
   const double pts = static_cast<double>(M) * M;
   LaunchScope obs(name.c_str(),
-                  static_cast<double>(a.NS) * P * (S / 2 + 1) * S * 8 +
+                  static_cast<double>(a.NS) * P * (FULL ? S : S / 2 + 1) * S * 8 +
                       static_cast<double>(a.F) * P * S * S * 4 + items * kOut * kOut * 4 +
                       (a.uout ? items * (M / 2 + 1) * M * 8 : 0),
                   items * ((a.uout ? 2 : 1) * fft2_flops(M) + fft2_flops(kOut) +
@@ -897,12 +916,12 @@ hipError_t launch_node_t(const NodeArgs &a, hipStream_t st) {
   if constexpr (M == 128) {
     const size_t lds_h = (64 * 152 + 128 + 256 + 64) * sizeof(float2);
     static unsigned long long lds_ok = 0;
-    hipError_t e = allow_large_lds(reinterpret_cast<const void *>(k_node_half<A, P, POLY>), lds_ok);
+    hipError_t e = allow_large_lds(reinterpret_cast<const void *>(k_node_half<A, P, POLY, FULL>), lds_ok);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((k_node_half<A, P, POLY>), dim3(static_cast<unsigned>(blocks)), dim3(512), lds_h, st,
+    hipLaunchKernelGGL((k_node_half<A, P, POLY, FULL>), dim3(static_cast<unsigned>(blocks)), dim3(512), lds_h, st,
                        a);
   } else {
-    hipLaunchKernelGGL((k_node<M, A, P, POLY>), dim3(static_cast<unsigned>(blocks)), dim3(M * M / 16), lds,
+    hipLaunchKernelGGL((k_node<M, A, P, POLY, FULL>), dim3(static_cast<unsigned>(blocks)), dim3(M * M / 16), lds,
                        st, a);
   }
   return hipGetLastError();
@@ -910,7 +929,9 @@ hipError_t launch_node_t(const NodeArgs &a, hipStream_t st) {
 
 }  // namespace
 
-bool node_supported(int M, int A, int P, bool poly) {
+bool node_supported(int M, int A, int P, bool poly, bool full) {
+  if (full)  // children (no spectrum of their own) of parents whose whole spectrum is stored
+    return !poly && P == 1 && ((M == 128 && (A == 2 || A == 4)) || (M == 64 && (A == 2 || A == 4 || A == 8)));
   if (poly) return M == 128 && A == 2 && P == 1;
   if (M == 128) return (A == 1 && (P == 1 || P == 4)) || (A == 2 && P == 1);
   if (M == 64) return (A == 2 && (P == 1 || P == 4)) || (A == 4 && P == 1);
@@ -918,7 +939,8 @@ bool node_supported(int M, int A, int P, bool poly) {
 }
 
 hipError_t launch_node(const NodeLaunch &n, hipStream_t st) {
-  if (!node_supported(n.M, n.A, n.P, n.poly) || n.G < 1 || n.F < 1) return hipErrorInvalidValue;
+  if (!node_supported(n.M, n.A, n.P, n.poly, n.full) || n.G < 1 || n.F < 1) return hipErrorInvalidValue;
+  if (n.full && n.uout != nullptr) return hipErrorInvalidValue;
   NodeArgs a;
   a.src = n.src;
   a.filt = n.filt;
@@ -936,6 +958,14 @@ hipError_t launch_node(const NodeLaunch &n, hipStream_t st) {
   a.K = n.K;
   a.tw = n.tw;
   a.tw_n = n.tw_n;
+#define SCAT_NODE_FULL(M_, A_) \
+  if (n.full && n.M == M_ && n.A == A_) return launch_node_t<M_, A_, 1, false, true>(a, st)
+  SCAT_NODE_FULL(128, 2);
+  SCAT_NODE_FULL(128, 4);
+  SCAT_NODE_FULL(64, 2);
+  SCAT_NODE_FULL(64, 4);
+  SCAT_NODE_FULL(64, 8);
+#undef SCAT_NODE_FULL
 #define SCAT_NODE(M_, A_, P_, POLY_) \
   if (n.M == M_ && n.A == A_ && n.P == P_ && n.poly == POLY_) return launch_node_t<M_, A_, P_, POLY_>(a, st)
   SCAT_NODE(128, 2, 1, true);
