@@ -429,6 +429,50 @@ scat_status upload(scat_plan *p) {
         return SCAT_ERR_DEVICE;
     }
   }
+  if (h.dims == 1 && h.oversampling == 0) {
+    // 1-D, first order: the row pass folds the second digit of the four-step frequency index
+    // only, so alias block b of octave j is the band [b, b + 1) N / 2^j of frequencies
+    std::vector<unsigned long long> m64;
+    const size_t N = static_cast<size_t>(p->n1) * p->n2;
+    for (int j = 1; j < h.J && j <= 6; ++j) {
+      const size_t band = N >> j;
+      if (band < 1 || (static_cast<size_t>(p->n2) >> j) < 1) continue;
+      p->mask64_off[{0, j}] = m64.size();
+      for (int q = 0; q < h.LQ; ++q) {
+        const FilterTable &t = *h.find(1, j * h.LQ + q, 0);
+        double peak = 0.0;
+        for (double v : t.v) peak = std::max(peak, std::fabs(v));
+        unsigned long long m = 0;
+        for (int b = 0; b < (1 << j); ++b) {
+          double big = 0.0;
+          for (size_t k = b * band; k < (b + 1) * band; ++k) big = std::max(big, std::fabs(t.v[k]));
+          if (big > 1e-7 * peak) m |= 1ull << b;
+        }
+        m64.push_back(m);
+      }
+    }
+    // the lowpass at full resolution, folded by 2^J (key {-1, J})
+    if (h.J >= 1 && h.J <= 6 && (static_cast<size_t>(p->n2) >> h.J) >= 1) {
+      const size_t band = N >> h.J;
+      const FilterTable &t = *h.find(0, 0, 0);
+      double peak = 0.0;
+      for (double v : t.v) peak = std::max(peak, std::fabs(v));
+      unsigned long long m = 0;
+      for (int b = 0; b < (1 << h.J); ++b) {
+        double big = 0.0;
+        for (size_t k = b * band; k < (b + 1) * band; ++k) big = std::max(big, std::fabs(t.v[k]));
+        if (big > 1e-7 * peak) m |= 1ull << b;
+      }
+      p->mask64_off[{-1, h.J}] = m64.size();
+      m64.push_back(m);
+    }
+    if (!m64.empty()) {
+      if (hipMalloc(&p->d_masks64, m64.size() * sizeof(unsigned long long)) != hipSuccess) return SCAT_ERR_ALLOC;
+      if (hipMemcpy(p->d_masks64, m64.data(), m64.size() * sizeof(unsigned long long),
+                    hipMemcpyHostToDevice) != hipSuccess)
+        return SCAT_ERR_DEVICE;
+    }
+  }
   if (p->node_taps) {
     const int N = p->n1;
     const double two_pi_ = 6.283185307179586476925286766559;
@@ -2056,8 +2100,13 @@ scat_status forward_1d(scat_plan *p, const float *in, float *out, long p0, long 
   SCAT_TRY(scat::launch_row_fwd(XH, pc * N1, N2, tw, tw_n, st));
   // S0
   if (lp) {
+    const unsigned long long *m0 = nullptr;
+    {
+      auto it = p->mask64_off.find({-1, J});
+      if (p->d_masks64 != nullptr && it != p->mask64_off.end() && rJ == J) m0 = p->d_masks64 + it->second;
+    }
     SCAT_TRY(scat::launch_mulfold_invrow(XH, tab + p->phi_off[0], TL0, pc, 1, N1, N2, 0, rJ, m_out,
-                                         tw, tw_n, st));
+                                         tw, tw_n, st, m0));
     SCAT_TRY(scat::launch_col(2, TL0, pc, N1, mc_out, nullptr, 0, nullptr, 0, nullptr, o,
                               ChanMap{1, 1, 0, 0}, K, tw, tw_n, st));
   }
@@ -2072,8 +2121,13 @@ scat_status forward_1d(scat_plan *p, const float *in, float *out, long p0, long 
     // straight into the tape, a leaf (no children below it) needs no column kernel here, and
     // the column kernel of a node with children writes their spectra only.
     float2 *t1 = tape ? tape->base + tape->y1_off[j1] * pc : T;
+    const unsigned long long *m1 = nullptr;
+    {
+      auto it = p->mask64_off.find({0, j1});
+      if (p->d_masks64 != nullptr && it != p->mask64_off.end() && r1 == j1) m1 = p->d_masks64 + it->second;
+    }
     SCAT_TRY(scat::launch_mulfold_invrow(XH, tab + p->psi1_off[j1], t1, pc, Q, N1, N2, 0, r1, M1,
-                                         tw, tw_n, st));
+                                         tw, tw_n, st, m1));
     if (tape != nullptr && !kids) continue;
     SCAT_TRY(scat::launch_col(1, t1, pc * Q, N1, Mc1, U, M1, nullptr, 0, nullptr, nullptr, none, K,
                               tw, tw_n, st));

@@ -292,8 +292,7 @@ __global__ __launch_bounds__(E == 32 ? 128 : 256) void k_mulfold_reg(
 #pragma unroll
         for (int e = 0; e < CPL; ++e) acc[j][e] = make_float2(0.f, 0.f);
       // alias blocks (a, b) on which every filter of the run is negligible are left out (mask:
-      // per filter, bit a * nsteps + b set = block in use; M >= 64 only, so that a column step
-      // is one alias block).  A test per filter inside the block measured slower: its branches
+      // per filter, bit a * 2^fc + b set = block in use).  A test per filter inside the block measured slower: its branches
       // serialise the loads.
       unsigned long long used = ~0ull;
       if (mask != nullptr) {
@@ -304,7 +303,8 @@ __global__ __launch_bounds__(E == 32 ? 128 : 256) void k_mulfold_reg(
         const size_t ro = static_cast<size_t>(q_r + a * Mr) * Sc;
 #pragma unroll 2
         for (int b = 0; b < nsteps; ++b) {
-          if (!((used >> (a * nsteps + b)) & 1ull)) continue;
+          // (a step covers W / M alias blocks: one for rows of 64 points and more)
+          if (!((used >> ((a * nsteps + b) * (W / M))) & ((1ull << (W / M)) - 1ull))) continue;
           const size_t o = ro + static_cast<size_t>(b) * W;
           float2 x[CPL];
 #pragma unroll
@@ -350,11 +350,13 @@ __global__ __launch_bounds__(E == 32 ? 128 : 256) void k_mulfold_reg(
     // measured) or sources narrower than a wave: the T lanes of a row gather directly
     const float2 *sp = src + static_cast<size_t>(s_idx) * Sr * Sc + t;
     const float *fp = filt + static_cast<size_t>(f_idx) * Sr * Sc + t;
+    const unsigned long long used = mask != nullptr ? mask[f_idx] : ~0ull;  // per row (its filter)
 #pragma unroll
     for (int i = 0; i < E; ++i) v[i] = make_float2(0.f, 0.f);
     for (int a = 0; a < nfr; ++a) {
       const size_t ro = static_cast<size_t>(qr + a * Mr) * Sc;
       for (int b = 0; b < nfc; ++b) {
+        if (!((used >> (a * nfc + b)) & 1ull)) continue;
         const size_t o = ro + static_cast<size_t>(b) * M;
 #pragma unroll
         for (int i = 0; i < E; ++i) {
@@ -1802,9 +1804,8 @@ hipError_t launch_mulfold_reg_t(const float2 *src, const float *filt, float2 *ds
   const size_t lds = static_cast<size_t>(RPB) * (T == 1 ? E : E * (T + 1)) * sizeof(float2);
   const double spts = static_cast<double>(S) * Sr * Sc, opts = static_cast<double>(S) * F * Mr * Mc;
   const bool multi = F >= 2 && (E * T >= 64 || (E * T >= 32 && Sc >= 64));
-  // block masks: rows of at least 64 points (a column step of the kernel is one alias block)
-  // and at most 64 blocks
-  const unsigned long long *mk = (E * T >= 64 && fr + fc <= 6) ? mask : nullptr;
+  // block masks: at most 64 alias blocks
+  const unsigned long long *mk = fr + fc <= 6 ? mask : nullptr;
   const std::string name = "k_mulfold_reg<" + std::to_string(E) + ", " + std::to_string(T) +
                            (multi ? ", true>" : ", false>");
   Observe ob(name.c_str(), spts * 8 + static_cast<double>(F) * Sr * Sc * 4 + opts * 8,
