@@ -109,3 +109,29 @@ def test_pass_schedule_still_matches(n, J, L, batch):
     errs = per_order_errors(got, want, order_of_channels(rows), x)
     print("passes", n, J, L, batch, errs, flush=True)
     assert max(errs.values()) <= TOL, errs
+
+
+def test_general_schedule_hands_small_children_to_node_kernels():
+    """512 x 512 at J = 4 (row and column passes with stored spectra): the second-order nodes
+    of 64 and 128 points a side are computed by whole-node kernels that read the parent's whole
+    spectrum; parity of the whole transform, and the launches are the ones expected."""
+    import torch
+    rng = np.random.default_rng(512)
+    x = rng.standard_normal((2, 512, 512)).astype(np.float32)
+    plan = scat.Scattering((512, 512), 4, 2)
+    try:
+        xd = torch.from_numpy(x).cuda()
+        plan.timing_begin(None)
+        got = plan.forward(xd)
+        torch.cuda.synchronize()
+        names = set(plan.timing_end())
+        got = got.cpu().numpy().astype(np.float64)
+        rows = plan.coeff_index()
+    finally:
+        plan.close()
+    assert any(k.startswith("k_node_half<4, 1, false, full") for k in names), names
+    assert any(k.startswith("k_node<64, 8, 1, false, full") for k in names), names
+    want = oracle.scattering2d(x, 4, 2)
+    errs = per_order_errors(got, want, order_of_channels(rows), x)
+    print("512 general + node children", errs, flush=True)
+    assert max(errs.values()) <= TOL, errs
