@@ -1,7 +1,7 @@
 // Depth-first 2-D cascade: one workgroup computes one whole node of the scattering tree in LDS.
 //
 // A node is |x (*) psi| (or ||x (*) psi_1| (*) psi_2|) on its own subsampled grid of M x M
-// points, M = 64 (k_node, 256 threads, three workgroups per compute unit) or 128 (k_node_half,
+// points, M = 64 (k_node, 256 threads, four workgroups per compute unit) or 128 (k_node_half,
 // 512 threads, two per compute unit) (paper, section 2 "Implementation": convolutions as
 // Fourier products, every filtered signal downsampled, the tree walked branch by branch so
 // that intermediates are dropped as soon as the children are done).  The workgroup
@@ -80,11 +80,15 @@ __device__ __forceinline__ void load_comps(float (&d)[P], const float *tab, int 
 }
 
 template <int M, int A, int P, bool POLY, bool FULL>
-__global__ __launch_bounds__(M * M / 16, 3) void k_node(NodeArgs a) {
+__global__ __launch_bounds__(M * M / 16, 4) void k_node(NodeArgs a) {
   static_assert(!FULL || P == 1, "a full spectrum is one source");
   static_assert(M == 64, "128 x 128 nodes take k_node_half");
   using SL = Slab<M, M>;
-  constexpr int NT = M * M / 16, T = M / 16, S = M * A, RS = SL::RS;
+  // Row slots of 76 elements (rows 24 banks apart: conflict-free for the lanes of eight rows)
+  // with an unpadded row exchange (16 x T elements): 39 KB per workgroup, FOUR workgroups per
+  // compute unit.
+  constexpr int NT = M * M / 16, T = M / 16, S = M * A, RS = 76, SK = T;
+  static_assert(RS >= M && RS >= 16 * SK, "row slot holds a row and its exchange");
   constexpr int DEC = M / kOut, R = 4 * DEC, NTAP = 2 * R + 1;
   static_assert(P == 1 || P == 4, "sources");
   static_assert(!POLY || P == 1, "a polyphase node reads a plain spectrum");
@@ -340,7 +344,14 @@ __global__ __launch_bounds__(M * M / 16, 3) void k_node(NodeArgs a) {
 #pragma unroll
   for (int i = 0; i < 16; ++i) v[i] = area[r * RS + t + T * i];
   __syncthreads();
-  SL::template transform_tab<true>(v, area, r, t, c, t1, wtab);
+  fft_core_tab<16, T, true, false>(v, t, area + r * RS, SK, 1, wtab + t, T);
+#pragma unroll
+  for (int i = 0; i < 16; ++i) area[r * RS + t + T * i] = v[i];
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 16; ++i) v[i] = area[(t1 + T * i) * RS + c];
+  __syncthreads();
+  fft_core_tab<16, T, true, false>(v, t1, area + c, T * RS, RS, wtab + M + t1, T);
 
   // ---- 3. modulus
   float u[16];
@@ -424,7 +435,14 @@ __global__ __launch_bounds__(M * M / 16, 3) void k_node(NodeArgs a) {
   __syncthreads();
 #pragma unroll
   for (int i = 0; i < 16; ++i) v[i] = make_float2(u[i], 0.f);
-  SL::template transform_back_tab<false>(v, area, r, t, c, t1, wtab);
+  fft_core_tab<16, T, false, false>(v, t1, area + c, T * RS, RS, wtab + M + t1, T);
+#pragma unroll
+  for (int i = 0; i < 16; ++i) area[(t1 + T * i) * RS + c] = v[i];
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 16; ++i) v[i] = area[r * RS + t + T * i];
+  __syncthreads();
+  fft_core_tab<16, T, false, false>(v, t, area + r * RS, SK, 1, wtab + t, T);
   if (r > M / 2) return;
   float2 *up = a.uout + ((static_cast<size_t>(s) * I + item) * (M / 2 + 1) + r) * M + t;
 #pragma unroll
@@ -901,7 +919,10 @@ hipError_t launch_node_t(const NodeArgs &a, hipStream_t st) {
   const int I = a.F * (POLY ? 4 : 1);
   const long blocks = 8 * ((a.NS + 7) / 8) * I;
   if (a.NS <= 0 || blocks > 0x7fffffffL || a.tw_n % (POLY ? 2 * M : M) != 0) return hipErrorInvalidValue;
-  const size_t lds = SL::lds_bytes + SL::tab_elems * sizeof(float2);
+  // k_node: rows + twiddles (39 KB: four workgroups per compute unit).  The four-component
+  // variant is bound by its loads and measured faster with THREE workgroups per compute unit
+  // (fewer loads in flight): it asks for 44 KB.
+  const size_t lds = P == 4 ? static_cast<size_t>(44) << 10 : (static_cast<size_t>(M) * 76 + 2 * M) * sizeof(float2);
   const std::string name = (M == 128 ? "k_node_half<" : "k_node<64, ") + std::to_string(A) + ", " +
                             std::to_string(P) + (POLY ? ", true" : ", false") + (FULL ? ", full>" : ">");
   const double items = static_cast<double>(a.NS) * I;
