@@ -914,7 +914,6 @@ __global__ __launch_bounds__(256) void k_sum4(const float *__restrict__ part, fl
 
 template <int M, int A, int P, bool POLY, bool FULL = false>
 hipError_t launch_node_t(const NodeArgs &a, hipStream_t st) {
-  using SL = Slab<M, M>;
   constexpr int S = M * A;
   const int I = a.F * (POLY ? 4 : 1);
   const long blocks = 8 * ((a.NS + 7) / 8) * I;
