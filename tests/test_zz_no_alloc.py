@@ -1,7 +1,8 @@
 """scat_forward_static (the entry point for callers that cannot allocate device memory) against
 scat_forward, through the C ABI: two calls in a row on one GPU, the second on a smaller input
 (the static buffer keeps the first call's contents), plus a plan whose batch runs in several
-chunks and the refusal of a plan whose single plane exceeds the buffer."""
+chunks, the refusal of a plan whose single plane exceeds the buffer, and replays of the call
+from a HIP graph."""
 import ctypes
 
 import numpy as np
@@ -94,5 +95,46 @@ def test_static_rejects_oversized_plane_and_bad_arguments():
         assert L.scat_forward_static(plan._plan, None, None, 0, None) == 0
         assert L.scat_forward_static(None, None, None, 1, None) == 5
         torch.cuda.synchronize()
+    finally:
+        plan.close()
+
+
+# ---- under HIP graph capture: captured once, replayed several times with the program's own
+# eager work and synchronisations between the replays, every replay checked against the eager
+# result (recording the forward transform into a graph is what this entry point is for)
+@pytest.mark.parametrize("shape,J,L,batch", [((256, 256), 3, 4, 3), ((64, 64), 3, 8, 5), ((32, 32), 2, 8, 16)])
+def test_static_entry_replays_from_a_graph(shape, J, L, batch):
+    import torch
+    torch.cuda.set_device(0)
+    plan = scat.Scattering(shape, J, L)
+    try:
+        rng = np.random.default_rng(41)
+        x = torch.from_numpy(rng.standard_normal((batch,) + shape).astype(np.float32)).cuda()
+        oshape = (batch, plan.K) + plan.out_shape
+        ref = torch.empty(oshape, dtype=torch.float32, device="cuda")
+        out = torch.full(oshape, float("nan"), dtype=torch.float32, device="cuda")
+        # eager: the reference, and the first call's set-up (kernel attributes, scratch address)
+        binding.scat_forward_static(plan._plan, x.data_ptr(), ref.data_ptr(), batch,
+                                    torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        want = ref.cpu().numpy()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            binding.scat_forward_static(plan._plan, x.data_ptr(), out.data_ptr(), batch,
+                                        torch.cuda.current_stream().cuda_stream)
+        for rep in range(3):
+            out.fill_(float("nan"))
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            got = out.cpu().numpy()
+            assert np.isfinite(got).all(), rep
+            err = np.abs(got.astype(np.float64) - want).max() / np.abs(want).max()
+            assert err <= 1e-6, (rep, err)   # the same kernels on the same input
+            # eager work of the program's own between the replays
+            x2 = (x * 0.5).contiguous()
+            binding.scat_forward_static(plan._plan, x2.data_ptr(), ref.data_ptr(), batch,
+                                        torch.cuda.current_stream().cuda_stream)
+            torch.cuda.synchronize()
     finally:
         plan.close()
