@@ -130,6 +130,11 @@ struct scat_plan {
   // Read by the whole-node kernels and by the row pass of the general 2-D schedule.
   unsigned long long *d_masks64 = nullptr;
   std::map<std::pair<int, int>, size_t> mask64_off;
+  // per table of node2_off ((res, j)) and poly_psi_off ((-1, j2)) read by a whole-node kernel whose
+  // source is twice the node's size: per thread of the workgroup, which of its loads meet a
+  // table value above 1e-7 of the table's peak (lane_words_64); L tables contiguous
+  unsigned *d_lane_masks = nullptr;
+  std::map<std::pair<int, int>, size_t> lane_mask_off;
   // 3-D solid harmonic plans (host.dims == 3; host carries J, LQ = L, max_order, K only)
   scat::HostPlan3D h3;
   std::vector<size_t> psi3_off;  // per (j, l): its 2l+1 tables, contiguous
@@ -312,6 +317,8 @@ void free_device(scat_plan *p) {
   if (p->d_scratch) (void)hipFree(p->d_scratch);
   if (p->d_masks64) (void)hipFree(p->d_masks64);
   p->d_masks64 = nullptr;
+  if (p->d_lane_masks) (void)hipFree(p->d_lane_masks);
+  p->d_lane_masks = nullptr;
   p->d_tables = nullptr;
   p->d_tw = nullptr;
   p->d_scratch = nullptr;
@@ -334,6 +341,40 @@ size_t append_table(std::vector<float> &pool, const FilterTable &t, int dims, in
         pool[off + k1 * cols + k2] = static_cast<float>(t.v[k1 + n1 * k2] * scale);
   }
   return off;
+}
+
+// Activity words of the 256 threads of k_node<64, 2, P> for one table `ft` in that kernel's
+// layout [row][column block][column parity][column pair][component]: thread (st, cq) =
+// (tid / 32, tid % 32) takes source rows st + 8 i, i = 0 .. 7; bits 4 i + ac: the table values
+// of the direct part of column block ac (both parities, all components) are not all negligible;
+// bits 4 i + 2 + ac: the same for the part it adds to the mirrored row (row 0: to row 64).
+// The index arithmetic is the kernel's own.
+void lane_words_64(const float *ft, int P, std::vector<unsigned> &out) {
+  const int S = 128;
+  double peak = 0.0;
+  for (size_t i = 0; i < static_cast<size_t>(P) * S * S; ++i) peak = std::max(peak, std::fabs(static_cast<double>(ft[i])));
+  const double thr = 1e-7 * peak;
+  auto live = [&](int entry) {
+    for (int q = 0; q < P; ++q)
+      if (std::fabs(static_cast<double>(ft[static_cast<size_t>(entry) * P + q])) > thr) return true;
+    return false;
+  };
+  for (int tid = 0; tid < 256; ++tid) {
+    const int cq = tid & 31, st = tid >> 5;
+    unsigned w = 0;
+    for (int i = 0; i < 8; ++i) {
+      const int row = st + 8 * i;
+      const bool first = row == 0;
+      const int row2 = first ? 64 : S - row;
+      for (int ac = 0; ac < 2; ++ac)
+        for (int e = 0; e < 2; ++e) {
+          const int idx = first ? 32 * ac + cq : (64 - 32 * ac - cq - e) & 63;
+          if (live(((row * 2 + ac) * 2 + e) * 32 + cq)) w |= 1u << (4 * i + ac);
+          if (live(((row2 * 2 + (idx >> 5)) * 2 + e) * 32 + (idx & 31))) w |= 1u << (4 * i + 2 + ac);
+        }
+    }
+    out.push_back(w);
+  }
 }
 
 size_t append_vec(std::vector<float> &pool, const std::vector<double> &v) {
@@ -549,6 +590,8 @@ scat_status upload(scat_plan *p) {
                         t.v[static_cast<size_t>(kr) * side + M * ac + 2 * cp + e] * scale));
           }
         }
+        // the entry that lanes with nothing to fetch read instead (lane_words_64)
+        for (int z = 0; z < 4; ++z) pool.push_back(0.f);
       }
     }
     if (p->node && N > 128 && h.max_order == 2) {
@@ -601,7 +644,31 @@ scat_status upload(scat_plan *p) {
                 for (int kc = 0; kc < M; ++kc) pool.push_back(folded(q, kr, kc));
           }
         }
+        for (int z = 0; z < 4; ++z) pool.push_back(0.f);  // see above
       }
+    }
+  }
+  if (p->node_taps) {
+    std::vector<unsigned> words;
+    for (const auto &kv : p->node2_off) {
+      const int side = p->n1 >> kv.first.first;
+      if (side != 128) continue;  // tables of k_node<64, 2, 1>
+      p->lane_mask_off[kv.first] = words.size();
+      for (int l = 0; l < h.LQ; ++l)
+        lane_words_64(pool.data() + kv.second + static_cast<size_t>(l) * side * side, 1, words);
+    }
+    for (const auto &kv : p->poly_psi_off) {
+      const int M = p->n1 / 2;
+      if ((p->n1 >> kv.first) != M / 2 || M != 128) continue;  // tables of k_node<64, 2, 4>
+      p->lane_mask_off[{-1, kv.first}] = words.size();
+      for (int l = 0; l < h.LQ; ++l)
+        lane_words_64(pool.data() + kv.second + static_cast<size_t>(l) * 4 * M * M, 4, words);
+    }
+    if (!words.empty()) {
+      if (hipMalloc(&p->d_lane_masks, words.size() * sizeof(unsigned)) != hipSuccess) return SCAT_ERR_ALLOC;
+      if (hipMemcpy(p->d_lane_masks, words.data(), words.size() * sizeof(unsigned), hipMemcpyHostToDevice) !=
+          hipSuccess)
+        return SCAT_ERR_DEVICE;
     }
   }
   // twiddles exp(-2 pi i j / tw_n), evaluated in double
@@ -623,6 +690,12 @@ scat_status upload(scat_plan *p) {
     return SCAT_ERR_DEVICE;
   p->has_device = true;
   return note_static_scratch(p);
+}
+
+// Activity words of the table `key` (scat_plan::lane_mask_off), or null: every load is made
+const unsigned *lane_mask_of(const scat_plan *p, std::pair<int, int> key) {
+  auto it = p->lane_mask_off.find(key);
+  return (p->d_lane_masks != nullptr && it != p->lane_mask_off.end()) ? p->d_lane_masks + it->second : nullptr;
 }
 
 scat_status upload_3d(scat_plan *p);
@@ -1195,6 +1268,7 @@ scat_status forward_2d_fused(scat_plan *p, const float *in, float *out, long p0,
       c.src = U;
       c.filt = tab + p->node2_off.at({r1, j2});
       c.mask = nullptr;
+      c.lane_mask = lane_mask_of(p, {r1, j2});
       c.taps_r = tab + p->taps_r_off[j2];
       c.taps_c = tab + p->taps_c_off[j2];
       c.uout = nullptr;
@@ -1302,6 +1376,7 @@ scat_status forward_2d_node(scat_plan *p, const float *in, float *out, long p0, 
       const bool c2 = !poly && c.A == 2;
       c.filt = tab + (poly ? p->poly_psi_off.at(j2) : c2 ? p->node2_off.at({j1, j2}) : p->psi2_off.at({j1, j2}));
       c.mask = (poly || c2) ? nullptr : p->d_masks64 + p->mask64_off.at({j1, j2});
+      c.lane_mask = (poly && c.A == 2) ? lane_mask_of(p, {-1, j2}) : c2 ? lane_mask_of(p, {j1, j2}) : nullptr;
       c.taps_r = tab + p->taps_r_off[j2];
       c.taps_c = tab + p->taps_c_off[j2];
       c.uout = nullptr;

@@ -205,6 +205,10 @@ struct NodeLaunch {
   const float2 *src;
   const float *filt;
   const unsigned long long *mask;  // null, or [F] device words: bit (q A + a_r) A + a_c set = block in use
+  // null, or [F][words per workgroup] device words for the loaders whose source is twice the
+  // node's size: per thread, which of its loads meet table values that are not negligible
+  // (node_lane_mask builds them from the table itself)
+  const unsigned *lane_mask;
   const float *taps_r, *taps_c;
   float2 *uout;
   float *out;

@@ -48,6 +48,9 @@ struct NodeArgs {
   const float *filt;    // [F][P][S][S] real tables (carry the 1/N^2 of the inverse transforms)
   const unsigned long long *mask;  // null, or per filter: bit (q A + ar) A + ac clear = that M x M
                                    // block of table q is negligible everywhere and is skipped
+  const unsigned *lane_mask;  // null, or per filter one word per thread (loaders with a source
+                              // twice the node's size): which of the thread's loads meet a table
+                              // value that is not negligible; the others are left out
   const float *taps_r;  // lowpass taps along a column (row index varies): [2R+1], POLY: [2][2R+1]
   const float *taps_c;  // along a row
   float2 *uout;         // null, or [(NS*I)][M/2+1][M]: half spectrum of every node's modulus
@@ -80,7 +83,7 @@ __device__ __forceinline__ void load_comps(float (&d)[P], const float *tab, int 
 }
 
 template <int M, int A, int P, bool POLY, bool FULL>
-__global__ __launch_bounds__(M * M / 16, 4) void k_node(NodeArgs a) {
+__global__ __launch_bounds__(M * M / 16, (P == 4 ? 3 : 4)) void k_node(NodeArgs a) {
   static_assert(!FULL || P == 1, "a full spectrum is one source");
   static_assert(M == 64, "128 x 128 nodes take k_node_half");
   using SL = Slab<M, M>;
@@ -122,6 +125,17 @@ __global__ __launch_bounds__(M * M / 16, 4) void k_node(NodeArgs a) {
     const float *ft = a.filt + static_cast<size_t>(f) * P * S * S;
     const int cq = tid & 31, st = tid >> 5;
     float2 z2[8][2];
+    // Per-lane activity bits of row i (bits 4 i ..): column block 0 and 1 of the direct part,
+    // then of the mirrored part.  Where all table values a load would fetch are negligible
+    // (below 1e-7 of the table's peak: about half of a wavelet two octaves above the grid) the
+    // lane reads the all-zero entry behind the last table instead, and a source value that only
+    // meets such table values is replaced by the first one of its row: the lanes that have
+    // nothing to fetch share one address, and no branch is needed.
+    // (one component: the kernel is bound by its arithmetic and the selects cost more than the
+    // loads they save -- measured; every load is made)
+    const unsigned am = (P == 4 && a.lane_mask != nullptr) ? a.lane_mask[static_cast<size_t>(f) * NT + tid] : ~0u;
+    const int zero_e = (a.F - f) * S * S;  // entry (of P floats) of the zeros behind the F tables
+    auto pick = [](bool on, int idx, int other) { return on ? idx : other; };
     if constexpr (P == 4) {
       // (four components: a row's sixteen 16-byte loads at once; measured faster than the
       // pipelined form below, which is the faster one for a single component)
@@ -130,17 +144,20 @@ __global__ __launch_bounds__(M * M / 16, 4) void k_node(NodeArgs a) {
         const int row = st + 8 * i;
         const bool first = row == 0;
         const int row2 = first ? 64 : S - row;
+        const unsigned bits = am >> (4 * i);
         float4 w[2][P];
         float d[2][2][P], m[2][2][P];
 #pragma unroll
         for (int ac = 0; ac < 2; ++ac) {
+          const bool on_d = (bits >> ac) & 1u, on_m = (bits >> (2 + ac)) & 1u;
+          const int wc = pick(on_d || (on_m && !first), 32 * ac + cq, 0);
 #pragma unroll
-          for (int q = 0; q < P; ++q) w[ac][q] = src4[(q * 65 + row) * (S / 2) + 32 * ac + cq];
+          for (int q = 0; q < P; ++q) w[ac][q] = src4[(q * 65 + row) * (S / 2) + wc];
 #pragma unroll
           for (int e = 0; e < 2; ++e) {
             const int idx = first ? 32 * ac + cq : (64 - 32 * ac - cq - e) & 63;
-            load_comps<P>(d[ac][e], ft, ((row * 2 + ac) * 2 + e) * 32 + cq);
-            load_comps<P>(m[ac][e], ft, ((row2 * 2 + (idx >> 5)) * 2 + e) * 32 + (idx & 31));
+            load_comps<P>(d[ac][e], ft, pick(on_d, ((row * 2 + ac) * 2 + e) * 32 + cq, zero_e));
+            load_comps<P>(m[ac][e], ft, pick(on_m, ((row2 * 2 + (idx >> 5)) * 2 + e) * 32 + (idx & 31), zero_e));
           }
         }
         float4 zd = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -158,7 +175,8 @@ __global__ __launch_bounds__(M * M / 16, 4) void k_node(NodeArgs a) {
 #pragma unroll
           for (int ac = 0; ac < 2; ++ac)
 #pragma unroll
-            for (int q = 0; q < P; ++q) w[ac][q] = src4[(q * 65 + 64) * (S / 2) + 32 * ac + cq];
+            for (int q = 0; q < P; ++q)
+              w[ac][q] = src4[(q * 65 + 64) * (S / 2) + pick((bits >> (2 + ac)) & 1u, 32 * ac + cq, 0)];
         }
         float4 zs = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
@@ -201,13 +219,16 @@ __global__ __launch_bounds__(M * M / 16, 4) void k_node(NodeArgs a) {
         const int row = st + 8 * i;
         const bool first = row == 0;
         const int row2 = first ? 64 : S - row;
+        const unsigned bits = am >> (4 * i);
+        const bool on_d = (bits >> ac) & 1u, on_m = (bits >> (2 + ac)) & 1u;
+        const int wc = pick(on_d || (on_m && !first), 32 * ac + cq, 0);
 #pragma unroll
-        for (int q = 0; q < P; ++q) un.w[q] = src4[(q * 65 + row) * (S / 2) + 32 * ac + cq];
+        for (int q = 0; q < P; ++q) un.w[q] = src4[(q * 65 + row) * (S / 2) + wc];
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
           const int idx = first ? 32 * ac + cq : (64 - 32 * ac - cq - e) & 63;
-          load_comps<P>(un.d[e], ft, ((row * 2 + ac) * 2 + e) * 32 + cq);
-          load_comps<P>(un.m[e], ft, ((row2 * 2 + (idx >> 5)) * 2 + e) * 32 + (idx & 31));
+          load_comps<P>(un.d[e], ft, pick(on_d, ((row * 2 + ac) * 2 + e) * 32 + cq, zero_e));
+          load_comps<P>(un.m[e], ft, pick(on_m, ((row2 * 2 + (idx >> 5)) * 2 + e) * 32 + (idx & 31), zero_e));
         }
       };
       Unit buf[DEPTH];
@@ -231,7 +252,8 @@ __global__ __launch_bounds__(M * M / 16, 4) void k_node(NodeArgs a) {
         }
         if (first) {  // row 0: its second part is row 64 itself, not a mirrored row
 #pragma unroll
-          for (int q = 0; q < P; ++q) un.w[q] = src4[(q * 65 + 64) * (S / 2) + 32 * ac + cq];
+          for (int q = 0; q < P; ++q)
+            un.w[q] = src4[(q * 65 + 64) * (S / 2) + pick((am >> (2 + ac)) & 1u, 32 * ac + cq, 0)];
         }
         if constexpr (P == 4) {
           // s = (1, sc, -1, -sc), sc = -1 except for column 0
@@ -965,6 +987,7 @@ hipError_t launch_node(const NodeLaunch &n, hipStream_t st) {
   a.src = n.src;
   a.filt = n.filt;
   a.mask = n.mask;
+  a.lane_mask = n.lane_mask;
   a.taps_r = n.taps_r;
   a.taps_c = n.taps_c;
   a.uout = n.uout;
