@@ -148,6 +148,11 @@ struct scat_plan {
   int user_shape[2] = {1, 1};  // 2-D (rows, cols); 1-D (1, n)
   int user_out[2] = {1, 1};
   std::vector<size_t> taps_off;  // tree: spatial taps of the lowpass along a column, per res
+  // 1-D, second order: the nodes of child octave j2 under ALL parent octaves j1 < j2 go through
+  // one column launch and one lowpass launch, numbered (signal, j1, k); chan1d_off[j2] -> the
+  // j2 * Q output channels (minus one: channel 0 is kept apart) of that numbering in d_chan1d
+  int *d_chan1d = nullptr;
+  std::vector<size_t> chan1d_off;
 };
 
 namespace {
@@ -219,6 +224,20 @@ size_t t_elems_1d(const scat::HostPlan &h, size_t n) {
     most = std::max(most, std::max(first, kids));
   }
   return most * static_cast<size_t>(h.LQ);
+}
+
+// 1-D forward pass (no tape): elements per signal of the second-order row-pass outputs, kept
+// for ALL parent octaves and grouped by child octave j2 (j2 * Q signals of n >> res(j2)
+// elements each), and of the largest such group (the column pass's output buffer V).
+size_t kids_elems_1d(const scat::HostPlan &h, size_t n, size_t *largest) {
+  size_t all = 0, most = 0;
+  for (int j2 = 1; h.max_order == 2 && j2 < h.J; ++j2) {
+    const size_t g = static_cast<size_t>(j2) * h.LQ * (n >> h.res(j2));
+    all += g;
+    most = std::max(most, g);
+  }
+  if (largest) *largest = most;
+  return all;
 }
 
 // budget: bytes of scratch one chunk may use (0 = scratch_budget())
@@ -293,9 +312,12 @@ Layout make_layout(const scat_plan &p, long batch, size_t budget = 0) {
     // level's; w: row-pass outputs of the lowpass for all K channels
     const size_t q = h.LQ;
     L.xh = n * c8;
-    L.t = t_elems_1d(h, n) * c8;
+    // t: one octave's first-order row-pass outputs, then the grouped second-order ones
+    size_t vmost = 0;
+    const size_t kids = kids_elems_1d(h, n, &vmost);
+    L.t = std::max(t_elems_1d(h, n), q * n + kids) * c8;
     L.u = q * n * c8;
-    L.v = second ? q * (n >> h.res(1)) * c8 : 0;
+    L.v = second ? std::max(vmost, q * (n >> h.res(1))) * c8 : 0;
     L.w = static_cast<size_t>(h.K) * (n >> h.res(h.J)) * c8;
   }
   if (p.padded) {
@@ -319,6 +341,8 @@ void free_device(scat_plan *p) {
   p->d_masks64 = nullptr;
   if (p->d_lane_masks) (void)hipFree(p->d_lane_masks);
   p->d_lane_masks = nullptr;
+  if (p->d_chan1d) (void)hipFree(p->d_chan1d);
+  p->d_chan1d = nullptr;
   p->d_tables = nullptr;
   p->d_tw = nullptr;
   p->d_scratch = nullptr;
@@ -647,6 +671,22 @@ scat_status upload(scat_plan *p) {
         for (int z = 0; z < 4; ++z) pool.push_back(0.f);  // see above
       }
     }
+  }
+  if (h.dims == 1 && h.max_order == 2 && h.J >= 2) {
+    std::vector<int> chans;
+    p->chan1d_off.assign(h.J, 0);
+    for (int j2 = 1; j2 < h.J; ++j2) {
+      p->chan1d_off[j2] = chans.size();
+      int s2_base = 1 + h.J * h.LQ;
+      for (int j1 = 0; j1 < j2; ++j1) {
+        const int octs = h.J - 1 - j1;
+        for (int k = 0; k < h.LQ; ++k) chans.push_back(s2_base + k * octs + (j2 - j1 - 1) - 1);
+        s2_base += h.LQ * octs;
+      }
+    }
+    if (hipMalloc(&p->d_chan1d, chans.size() * sizeof(int)) != hipSuccess) return SCAT_ERR_ALLOC;
+    if (hipMemcpy(p->d_chan1d, chans.data(), chans.size() * sizeof(int), hipMemcpyHostToDevice) != hipSuccess)
+      return SCAT_ERR_DEVICE;
   }
   if (p->node_taps) {
     std::vector<unsigned> words;
@@ -2185,7 +2225,16 @@ scat_status forward_1d(scat_plan *p, const float *in, float *out, long p0, long 
     SCAT_TRY(scat::launch_col(2, TL0, pc, N1, mc_out, nullptr, 0, nullptr, 0, nullptr, o,
                               ChanMap{1, 1, 0, 0}, K, tw, tw_n, st));
   }
-  int s2_base = 1 + J * Q;
+  // second-order row-pass outputs, grouped by child octave (behind one octave's first-order ones)
+  float2 *T2 = T + static_cast<size_t>(Q) * N * pc;
+  size_t t2_off[scat::kRows1dMaxChildren + 1] = {0};
+  {
+    size_t used = 0;
+    for (int j2 = 1; j2 < J; ++j2) {
+      t2_off[j2] = used;
+      used += static_cast<size_t>(j2) * Q * (N >> h.res(j2));
+    }
+  }
   for (int j1 = 0; j1 < J; ++j1) {
     const int r1 = h.res(j1);
     const int Mc1 = N2 >> r1;
@@ -2210,30 +2259,33 @@ scat_status forward_1d(scat_plan *p, const float *in, float *out, long p0, long 
     scat::Rows1dArgs ch;
     ch.n = 0;
     if (lp) ch.c[ch.n++] = low_child(r1, ChanMap{Q, Q, 0, 1 + j1 * Q});
-    float2 *tj[scat::kRows1dMaxChildren];
-    size_t t_used = 0;
     for (int j2 = j1 + 1; kids && j2 < J; ++j2) {
       const int r2 = h.res(j2);
-      tj[j2] = tape ? tape->base + tape->y2_off.at({j1, j2}) * pc : T + t_used * pc;
-      t_used += static_cast<size_t>(Q) * (N >> r2);
-      ch.c[ch.n++] = scat::Rows1dChild{tab + p->psi2_off[{r1, j2}], tj[j2], r2 - r1, N >> r2,
-                                       ChanMap{1, 1, 0, 0}, 0};
+      if (tape != nullptr) {
+        ch.c[ch.n++] = scat::Rows1dChild{tab + p->psi2_off[{r1, j2}], tape->base + tape->y2_off.at({j1, j2}) * pc,
+                                         r2 - r1, N >> r2, ChanMap{1, 1, 0, 0}, 0};
+      } else {
+        // node (signal, k) of this octave is signal number (signal * j2 + j1) * Q + k of group j2
+        ch.c[ch.n++] = scat::Rows1dChild{tab + p->psi2_off[{r1, j2}], T2 + t2_off[j2] * pc, r2 - r1, N >> r2,
+                                         ChanMap{Q, Q, 0, j1 * Q}, j2 * Q};
+      }
     }
     SCAT_TRY(scat::launch_rows1d(U, pc * Q, N1, Mc1, ch, tw, tw_n, st));
-    if (!kids || tape != nullptr) continue;
-    const int octs = J - 1 - j1;
-    for (int j2 = j1 + 1; j2 < J; ++j2) {
-      const int r2 = h.res(j2);
-      const int Mc2 = N2 >> r2;
-      const int M2 = N >> r2;
-      SCAT_TRY(scat::launch_col(1, tj[j2], pc * Q, N1, Mc2, V, M2, nullptr, 0, nullptr, nullptr, none, K,
-                                tw, tw_n, st));
-      scat::Rows1dArgs lc;
-      lc.n = 1;
-      lc.c[0] = low_child(r2, ChanMap{Q, 1, octs, s2_base + (j2 - j1 - 1)});
-      SCAT_TRY(scat::launch_rows1d(V, pc * Q, N1, Mc2, lc, tw, tw_n, st));
-    }
-    s2_base += Q * octs;
+  }
+  // second order: per child octave j2 one column pass and one lowpass row pass over the nodes
+  // under all its parent octaves
+  for (int j2 = 1; tape == nullptr && h.max_order == 2 && j2 < J; ++j2) {
+    const int r2 = h.res(j2);
+    const int Mc2 = N2 >> r2;
+    const int M2 = N >> r2;
+    const long nodes = pc * j2 * Q;
+    SCAT_TRY(scat::launch_col(1, T2 + t2_off[j2] * pc, nodes, N1, Mc2, V, M2, nullptr, 0, nullptr, nullptr, none,
+                              K, tw, tw_n, st));
+    scat::Rows1dArgs lc;
+    lc.n = 1;
+    lc.c[0] = low_child(r2, ChanMap{j2 * Q, 1, 0, 1});
+    lc.c[0].chan_tab = p->d_chan1d + p->chan1d_off[j2];
+    SCAT_TRY(scat::launch_rows1d(V, nodes, N1, Mc2, lc, tw, tw_n, st));
   }
   // column half of the lowpass for channels 1 .. K-1 of every signal at once
   if (lp && K > 1)

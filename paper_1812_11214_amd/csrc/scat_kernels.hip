@@ -561,7 +561,8 @@ __global__ __launch_bounds__(256) void k_rows1d(const float2 *__restrict__ src, 
     long drow0 = row0;
     if (ch.K > 0) {
       const long node = row0 / Sr;
-      drow0 = ((node / ch.cm.G) * ch.K + chan_of(ch.cm, static_cast<int>(node % ch.cm.G))) * Sr + k1_0;
+      const int g = static_cast<int>(node % ch.cm.G);
+      drow0 = ((node / ch.cm.G) * ch.K + (ch.chan_tab != nullptr ? ch.chan_tab[g] : chan_of(ch.cm, g))) * Sr + k1_0;
     }
     float2 *dp = ch.dst + static_cast<size_t>(drow0) * m;
     for (int t = threadIdx.x; t < RB * m; t += blockDim.x) {
@@ -704,8 +705,10 @@ __global__ __launch_bounds__(256, 4) void k_rows1d_reg(const float2 *__restrict_
       if (t + T * i < m) slot[t + T * i] = p[i];
     wave_sync();
     long drow = row;
-    if (ch.K > 0)
-      drow = ((node / ch.cm.G) * ch.K + chan_of(ch.cm, static_cast<int>(node % ch.cm.G))) * Sr + k1;
+    if (ch.K > 0) {
+      const int g = static_cast<int>(node % ch.cm.G);
+      drow = ((node / ch.cm.G) * ch.K + (ch.chan_tab != nullptr ? ch.chan_tab[g] : chan_of(ch.cm, g))) * Sr + k1;
+    }
     float2 *dp = ch.dst + static_cast<size_t>(drow) * m;
     const int tws = Sc >> lgm;
     switch (lgm) {

@@ -73,6 +73,9 @@ struct Rows1dChild {
   // its own number (the lowpass children of a whole transform gathered channel-major)
   ChanMap cm;
   int K;
+  // null, or cm.G device words: the channel of node g comes from this table instead of cm's
+  // formula (nodes of several parent octaves in one launch)
+  const int *chan_tab;
 };
 struct Rows1dArgs {
   int n;
