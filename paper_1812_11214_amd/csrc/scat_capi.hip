@@ -312,12 +312,14 @@ Layout make_layout(const scat_plan &p, long batch, size_t budget = 0) {
     // level's; w: row-pass outputs of the lowpass for all K channels
     const size_t q = h.LQ;
     L.xh = n * c8;
-    // t: one octave's first-order row-pass outputs, then the grouped second-order ones
-    size_t vmost = 0;
-    const size_t kids = kids_elems_1d(h, n, &vmost);
-    L.t = std::max(t_elems_1d(h, n), q * n + kids) * c8;
-    L.u = q * n * c8;
-    L.v = second ? std::max(vmost, q * (n >> h.res(1))) * c8 : 0;
+    // t: the first-order row-pass outputs of all octaves, then the second-order ones grouped
+    // by child octave; u, v: their column spectra, laid out alike
+    const size_t kids = kids_elems_1d(h, n, nullptr);
+    size_t first = 0;
+    for (int j = 0; j < h.J; ++j) first += q * (n >> h.res(j));
+    L.t = (first + kids) * c8;
+    L.u = first * c8;
+    L.v = kids * c8;
     L.w = static_cast<size_t>(h.K) * (n >> h.res(h.J)) * c8;
   }
   if (p.padded) {
@@ -2225,26 +2227,98 @@ scat_status forward_1d(scat_plan *p, const float *in, float *out, long p0, long 
     SCAT_TRY(scat::launch_col(2, TL0, pc, N1, mc_out, nullptr, 0, nullptr, 0, nullptr, o,
                               ChanMap{1, 1, 0, 0}, K, tw, tw_n, st));
   }
-  // second-order row-pass outputs, grouped by child octave (behind one octave's first-order ones)
-  float2 *T2 = T + static_cast<size_t>(Q) * N * pc;
-  size_t t2_off[scat::kRows1dMaxChildren + 1] = {0};
-  {
-    size_t used = 0;
-    for (int j2 = 1; j2 < J; ++j2) {
-      t2_off[j2] = used;
-      used += static_cast<size_t>(j2) * Q * (N >> h.res(j2));
+  if (tape == nullptr) {
+    // Plain forward pass, breadth first: the row passes of all first-order octaves, ONE column
+    // pass over all of them (arrays that differ in their number of columns are segments of one
+    // launch), per octave one row pass over its spectra (lowpass + the wavelets of every coarser
+    // octave; the children are stored grouped by their own octave j2, node (signal, j1, k)),
+    // one column pass over all second-order nodes and one lowpass row pass per child octave.
+    size_t off1[scat::kRows1dMaxChildren + 1] = {0}, t2_off[scat::kRows1dMaxChildren + 1] = {0};
+    size_t tot1 = 0, tot2 = 0;
+    for (int j = 0; j < J; ++j) {
+      off1[j] = tot1;
+      tot1 += static_cast<size_t>(Q) * (N >> h.res(j));
     }
+    for (int j2 = 1; h.max_order == 2 && j2 < J; ++j2) {
+      t2_off[j2] = tot2;
+      tot2 += static_cast<size_t>(j2) * Q * (N >> h.res(j2));
+    }
+    float2 *T2 = T + tot1 * pc;
+    // column passes (mode 1 with the four-step twiddle) over a list of arrays
+    auto cols_pass = [&](const float2 *src, float2 *dst, const std::vector<scat::ColSeg> &all) -> scat_status {
+      std::vector<scat::ColSeg> together;
+      for (const scat::ColSeg &sg : all)
+        if (N1 == 256 && sg.Mc >= 16 && static_cast<int>(together.size()) < scat::kColMaxSegs) together.push_back(sg);
+      const bool merged = together.size() >= 2;
+      if (merged) SCAT_TRY(scat::launch_col_segs(src, dst, N1, together.data(), static_cast<int>(together.size()), tw, tw_n, st));
+      size_t taken = 0;
+      for (const scat::ColSeg &sg : all) {
+        if (merged && N1 == 256 && sg.Mc >= 16 && taken < together.size()) {
+          ++taken;
+          continue;
+        }
+        SCAT_TRY(scat::launch_col(1, src + sg.src_off, sg.nodes, N1, sg.Mc, dst + sg.uc_off, N1 * sg.Mc, nullptr, 0,
+                                  nullptr, nullptr, none, K, tw, tw_n, st));
+      }
+      return SCAT_OK;
+    };
+    std::vector<scat::ColSeg> segs;
+    for (int j1 = 0; j1 < J; ++j1) {
+      const int r1 = h.res(j1);
+      const unsigned long long *m1 = nullptr;
+      {
+        auto it = p->mask64_off.find({0, j1});
+        if (p->d_masks64 != nullptr && it != p->mask64_off.end() && r1 == j1) m1 = p->d_masks64 + it->second;
+      }
+      SCAT_TRY(scat::launch_mulfold_invrow(XH, tab + p->psi1_off[j1], T + off1[j1] * pc, pc, Q, N1, N2, 0, r1,
+                                           N >> r1, tw, tw_n, st, m1));
+      segs.push_back(scat::ColSeg{pc * Q, N2 >> r1, static_cast<long long>(off1[j1] * pc),
+                                  static_cast<long long>(off1[j1] * pc)});
+    }
+    SCAT_TRY(cols_pass(T, U, segs));
+    for (int j1 = 0; j1 < J; ++j1) {
+      const int r1 = h.res(j1);
+      scat::Rows1dArgs ch;
+      ch.n = 0;
+      ch.c[ch.n++] = low_child(r1, ChanMap{Q, Q, 0, 1 + j1 * Q});
+      for (int j2 = j1 + 1; h.max_order == 2 && j2 < J; ++j2) {
+        const int r2 = h.res(j2);
+        // node (signal, k) of this octave is signal number (signal * j2 + j1) * Q + k of group j2
+        ch.c[ch.n++] = scat::Rows1dChild{tab + p->psi2_off[{r1, j2}], T2 + t2_off[j2] * pc, r2 - r1, N >> r2,
+                                         ChanMap{Q, Q, 0, j1 * Q}, j2 * Q};
+      }
+      SCAT_TRY(scat::launch_rows1d(U + off1[j1] * pc, pc * Q, N1, N2 >> r1, ch, tw, tw_n, st));
+    }
+    if (h.max_order == 2 && J >= 2) {
+      segs.clear();
+      for (int j2 = 1; j2 < J; ++j2)
+        segs.push_back(scat::ColSeg{pc * j2 * Q, N2 >> h.res(j2), static_cast<long long>(t2_off[j2] * pc),
+                                    static_cast<long long>(t2_off[j2] * pc)});
+      SCAT_TRY(cols_pass(T2, V, segs));
+      for (int j2 = 1; j2 < J; ++j2) {
+        const int r2 = h.res(j2);
+        scat::Rows1dArgs lc;
+        lc.n = 1;
+        lc.c[0] = low_child(r2, ChanMap{j2 * Q, 1, 0, 1});
+        lc.c[0].chan_tab = p->d_chan1d + p->chan1d_off[j2];
+        SCAT_TRY(scat::launch_rows1d(V + t2_off[j2] * pc, pc * j2 * Q, N1, N2 >> r2, lc, tw, tw_n, st));
+      }
+    }
+    if (K > 1)
+      SCAT_TRY(scat::launch_col(2, TL, pc * (K - 1), N1, mc_out, nullptr, 0, nullptr, 0, nullptr, o,
+                                ChanMap{K - 1, K - 1, 0, 1}, K, tw, tw_n, st));
+    return SCAT_OK;
   }
+  // Taped pass: every node is taped as its row pass leaves it, before the inverse column
+  // transform, which the backward pass's column kernel does itself: the row pass writes
+  // straight into the tape, a leaf (no children below it) needs no column kernel here, and
+  // the column kernel of a node with children writes their spectra only.
   for (int j1 = 0; j1 < J; ++j1) {
     const int r1 = h.res(j1);
     const int Mc1 = N2 >> r1;
     const int M1 = N >> r1;
     const bool kids = h.max_order == 2 && j1 < J - 1;
-    // Taped pass: every node is taped as its row pass leaves it, before the inverse column
-    // transform, which the backward pass's column kernel does itself: the row pass writes
-    // straight into the tape, a leaf (no children below it) needs no column kernel here, and
-    // the column kernel of a node with children writes their spectra only.
-    float2 *t1 = tape ? tape->base + tape->y1_off[j1] * pc : T;
+    float2 *t1 = tape->base + tape->y1_off[j1] * pc;
     const unsigned long long *m1 = nullptr;
     {
       auto it = p->mask64_off.find({0, j1});
@@ -2252,45 +2326,18 @@ scat_status forward_1d(scat_plan *p, const float *in, float *out, long p0, long 
     }
     SCAT_TRY(scat::launch_mulfold_invrow(XH, tab + p->psi1_off[j1], t1, pc, Q, N1, N2, 0, r1, M1,
                                          tw, tw_n, st, m1));
-    if (tape != nullptr && !kids) continue;
+    if (!kids) continue;
     SCAT_TRY(scat::launch_col(1, t1, pc * Q, N1, Mc1, U, M1, nullptr, 0, nullptr, nullptr, none, K,
                               tw, tw_n, st));
-    // one pass over the rows of U: the lowpass and the wavelets of every coarser octave
     scat::Rows1dArgs ch;
     ch.n = 0;
-    if (lp) ch.c[ch.n++] = low_child(r1, ChanMap{Q, Q, 0, 1 + j1 * Q});
-    for (int j2 = j1 + 1; kids && j2 < J; ++j2) {
+    for (int j2 = j1 + 1; j2 < J; ++j2) {
       const int r2 = h.res(j2);
-      if (tape != nullptr) {
-        ch.c[ch.n++] = scat::Rows1dChild{tab + p->psi2_off[{r1, j2}], tape->base + tape->y2_off.at({j1, j2}) * pc,
-                                         r2 - r1, N >> r2, ChanMap{1, 1, 0, 0}, 0};
-      } else {
-        // node (signal, k) of this octave is signal number (signal * j2 + j1) * Q + k of group j2
-        ch.c[ch.n++] = scat::Rows1dChild{tab + p->psi2_off[{r1, j2}], T2 + t2_off[j2] * pc, r2 - r1, N >> r2,
-                                         ChanMap{Q, Q, 0, j1 * Q}, j2 * Q};
-      }
+      ch.c[ch.n++] = scat::Rows1dChild{tab + p->psi2_off[{r1, j2}], tape->base + tape->y2_off.at({j1, j2}) * pc,
+                                       r2 - r1, N >> r2, ChanMap{1, 1, 0, 0}, 0};
     }
     SCAT_TRY(scat::launch_rows1d(U, pc * Q, N1, Mc1, ch, tw, tw_n, st));
   }
-  // second order: per child octave j2 one column pass and one lowpass row pass over the nodes
-  // under all its parent octaves
-  for (int j2 = 1; tape == nullptr && h.max_order == 2 && j2 < J; ++j2) {
-    const int r2 = h.res(j2);
-    const int Mc2 = N2 >> r2;
-    const int M2 = N >> r2;
-    const long nodes = pc * j2 * Q;
-    SCAT_TRY(scat::launch_col(1, T2 + t2_off[j2] * pc, nodes, N1, Mc2, V, M2, nullptr, 0, nullptr, nullptr, none,
-                              K, tw, tw_n, st));
-    scat::Rows1dArgs lc;
-    lc.n = 1;
-    lc.c[0] = low_child(r2, ChanMap{j2 * Q, 1, 0, 1});
-    lc.c[0].chan_tab = p->d_chan1d + p->chan1d_off[j2];
-    SCAT_TRY(scat::launch_rows1d(V, nodes, N1, Mc2, lc, tw, tw_n, st));
-  }
-  // column half of the lowpass for channels 1 .. K-1 of every signal at once
-  if (lp && K > 1)
-    SCAT_TRY(scat::launch_col(2, TL, pc * (K - 1), N1, mc_out, nullptr, 0, nullptr, 0, nullptr, o,
-                              ChanMap{K - 1, K - 1, 0, 1}, K, tw, tw_n, st));
   return SCAT_OK;
 }
 

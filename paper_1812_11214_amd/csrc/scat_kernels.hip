@@ -790,20 +790,20 @@ __global__ void k_row_lowpass(const float *__restrict__ w, int m_r, int Mc, int 
 // along rows).  LM_R = compile-time lowpass length (8 or 32: the fold is done in registers
 // and the small inverse transform by 1 or 2 lanes per column) or 0 = any length (generic
 // tail through lds_fft).
+// (blk: the workgroup's number among those that work on this array of nodes)
 template <int MR, int MODE, int LM_R>
-__global__ __launch_bounds__(256) void k_col_fast(const void *__restrict__ src_v, int Mc, int TC,
-                                                  float2 *__restrict__ uc, int uc_half,
-                                                  int post_tw_m,
-                                                  const float *__restrict__ phi_rows, int m_r,
-                                                  float *__restrict__ w_out,
-                                                  const float2 *__restrict__ tw, int tw_n) {
+__device__ __forceinline__ void col_fast_body(unsigned blk, const void *__restrict__ src_v, int Mc, int TC,
+                                              float2 *__restrict__ uc, int uc_half, int post_tw_m,
+                                              const float *__restrict__ phi_rows, int m_r,
+                                              float *__restrict__ w_out,
+                                              const float2 *__restrict__ tw, int tw_n) {
   constexpr int E = MR > 256 ? 32 : 16, T = MR / E;
   extern __shared__ float2 lds[];
   const int KS = T * TC + 16;
   const int c = threadIdx.x % TC, t = threadIdx.x / TC;
   const int tiles = Mc / TC;
-  const int node = blockIdx.x / tiles;
-  const int c0 = (blockIdx.x % tiles) * TC;
+  const int node = blk / tiles;
+  const int c0 = (blk % tiles) * TC;
   const size_t plane = static_cast<size_t>(node) * MR * Mc;
   const int off0 = t * Mc + c0 + c;  // offset of this thread's first element in the plane
   const int step = T * Mc;
@@ -938,6 +938,68 @@ __global__ __launch_bounds__(256) void k_col_fast(const void *__restrict__ src_v
       wp[static_cast<size_t>(m) * Mc + cc] = low[idx].x;
     }
   }
+}
+
+template <int MR, int MODE, int LM_R>
+__global__ __launch_bounds__(256) void k_col_fast(const void *__restrict__ src_v, int Mc, int TC,
+                                                  float2 *__restrict__ uc, int uc_half,
+                                                  int post_tw_m,
+                                                  const float *__restrict__ phi_rows, int m_r,
+                                                  float *__restrict__ w_out,
+                                                  const float2 *__restrict__ tw, int tw_n) {
+  col_fast_body<MR, MODE, LM_R>(blockIdx.x, src_v, Mc, TC, uc, uc_half, post_tw_m, phi_rows, m_r, w_out, tw,
+                                tw_n);
+}
+
+// Mode 1 (inverse transform, modulus, forward transform, four-step twiddle: the 1-D cascade's
+// column pass) over several arrays of nodes that differ in their number of columns, in one
+// launch: workgroups first[s] .. first[s + 1] - 1 take segment s.
+struct ColSegsDev {
+  int n;
+  unsigned first[kColMaxSegs];
+  int Mc[kColMaxSegs];
+  long long src_off[kColMaxSegs], uc_off[kColMaxSegs];  // in elements from the common bases
+};
+template <int MR>
+__global__ __launch_bounds__(256) void k_col_fast_segs(const float2 *__restrict__ src,
+                                                       float2 *__restrict__ uc, ColSegsDev sg, int TC,
+                                                       const float2 *__restrict__ tw, int tw_n) {
+  int s = 0;
+#pragma unroll
+  for (int i = 1; i < kColMaxSegs; ++i)
+    if (i < sg.n && blockIdx.x >= sg.first[i]) s = i;
+  s = __builtin_amdgcn_readfirstlane(s);
+  const int Mc = sg.Mc[s];
+  col_fast_body<MR, 1, 0>(blockIdx.x - sg.first[s], src + sg.src_off[s], Mc, TC, uc + sg.uc_off[s], 0, MR * Mc,
+                          nullptr, 0, nullptr, tw, tw_n);
+}
+
+hipError_t launch_col_segs_impl(const float2 *src, float2 *uc, int Mr, const ColSeg *segs, int n, const float2 *tw,
+                                int tw_n, hipStream_t st) {
+  if (Mr != 256 || n < 1 || n > kColMaxSegs || tw_n % Mr != 0) return hipErrorInvalidValue;
+  constexpr int MR = 256, E = 16, T = MR / E, TC = 16;
+  ColSegsDev sg{};
+  sg.n = n;
+  long blocks = 0;
+  double pts = 0.0, cols = 0.0;
+  for (int i = 0; i < n; ++i) {
+    const long long m = static_cast<long long>(MR) * segs[i].Mc;
+    if (segs[i].nodes < 1 || segs[i].Mc < TC || segs[i].Mc % TC != 0 || tw_n % m != 0 || (m & (m - 1)) != 0)
+      return hipErrorInvalidValue;
+    sg.first[i] = static_cast<unsigned>(blocks);
+    sg.Mc[i] = segs[i].Mc;
+    sg.src_off[i] = segs[i].src_off;
+    sg.uc_off[i] = segs[i].uc_off;
+    blocks += segs[i].nodes * (segs[i].Mc / TC);
+    if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
+    pts += static_cast<double>(segs[i].nodes) * m;
+    cols += static_cast<double>(segs[i].nodes) * segs[i].Mc;
+  }
+  const size_t lds = static_cast<size_t>(E) * (T * TC + 16) * sizeof(float2);
+  Observe ob("k_col_fast_segs<256>", pts * 16, cols * 2 * fft_flops(MR) + 4.0 * pts, st);
+  hipLaunchKernelGGL((k_col_fast_segs<MR>), dim3(static_cast<unsigned>(blocks)), dim3(T * TC), lds, st, src, uc, sg,
+                     TC, tw, tw_n);
+  return hipGetLastError();
 }
 
 template <int MR>
@@ -1941,6 +2003,11 @@ hipError_t launch_mulfold_invrow(const float2 *src, const float *filt, float2 *d
   hipLaunchKernelGGL(k_mulfold_invrow, dim3(static_cast<unsigned>(blocks)), dim3(kThreads), lds, st,
                      src, filt, dst, F, Sr, Sc, fr, fc, RB, post_tw_m, tw, tw_n);
   return hipGetLastError();
+}
+
+hipError_t launch_col_segs(const float2 *src, float2 *uc, int Mr, const ColSeg *segs, int n, const float2 *tw,
+                           int tw_n, hipStream_t st) {
+  return launch_col_segs_impl(src, uc, Mr, segs, n, tw, tw_n, st);
 }
 
 hipError_t launch_col(int mode, const void *src, long nodes, int Mr, int Mc, float2 *uc,

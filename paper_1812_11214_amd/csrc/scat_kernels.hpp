@@ -60,6 +60,18 @@ hipError_t launch_col(int mode, const void *src, long nodes, int Mr, int Mc, flo
                       ChanMap cm, int K, const float2 *tw, int tw_n, hipStream_t st,
                       bool uc_half = false);
 
+// launch_col mode 1 with the four-step twiddle (post_tw_m = Mr * Mc) over up to kColMaxSegs
+// arrays of nodes in one launch: segment i holds `nodes` signals of Mr x Mc elements at
+// src + src_off and writes their column spectra to uc + uc_off (Mr = 256, Mc a multiple of 16).
+constexpr int kColMaxSegs = 8;
+struct ColSeg {
+  long nodes;
+  int Mc;
+  long long src_off, uc_off;
+};
+hipError_t launch_col_segs(const float2 *src, float2 *uc, int Mr, const ColSeg *segs, int n, const float2 *tw,
+                           int tw_n, hipStream_t st);
+
 // 1-D cascade: forward row FFT of src [nodes][Sr][Sc] (column spectra, left untouched) and,
 // for each child, filter product + fold of the row by 2^lg_fold + inverse row FFT + four-step
 // twiddle, stored to the child's dst [nodes][Sr][Sc >> lg_fold] (see k_rows1d).
