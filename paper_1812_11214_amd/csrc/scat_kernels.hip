@@ -636,7 +636,8 @@ __global__ __launch_bounds__(256, 4) void k_rows1d_reg(const float2 *__restrict_
   static_assert(E == 16 || T == 1, "short rows are held by one lane");
   constexpr bool ROWTW = T >= 4;
   constexpr int Sc = E * T, RPB = 256 / T;
-  constexpr int XS = (T == 1 ? E : E * (T + 1)) + (ROWTW ? 16 : 0);
+  // (an odd number of elements per row slot: the rows of a quarter wave start in different banks)
+  constexpr int XS = ((T == 1 ? E : E * (T + 1)) + (ROWTW ? 16 : 0)) | 1;
   constexpr int lgSc = (E == 4 ? 2 : E == 8 ? 3 : 4) + (T == 1 ? 0 : T == 2 ? 1 : T == 4 ? 2 : T == 8 ? 3 : 4);
   extern __shared__ float2 lds[];
   float2 *twl = lds;
@@ -1910,7 +1911,7 @@ template <int E, int T>
 hipError_t launch_rows1d_reg_t(const float2 *src, long rows, int Sr, const Rows1dArgs &a, double bytes,
                                double flops, const float2 *tw, int tw_n, hipStream_t st) {
   constexpr int Sc = E * T, RPB = 256 / T;
-  constexpr int XS = (T == 1 ? E : E * (T + 1)) + (T >= 4 ? 16 : 0);  // as in the kernel
+  constexpr int XS = ((T == 1 ? E : E * (T + 1)) + (T >= 4 ? 16 : 0)) | 1;  // as in the kernel
   const long blocks = (rows + RPB - 1) / RPB;
   if (blocks <= 0 || blocks > 0x7fffffffL) return hipErrorInvalidValue;
   const size_t lds = (static_cast<size_t>(Sc) + static_cast<size_t>(RPB) * XS) * sizeof(float2);
