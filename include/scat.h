@@ -166,6 +166,17 @@ scat_status scat_forward(scat_plan *plan, const float *in, float *out, long batc
                          void *stream);
 
 /*
+ * Grow the plan's scratch buffer now to what scat_forward (and, with with_backward != 0,
+ * scat_backward) needs for calls of up to `batch` planes, so that those calls neither
+ * allocate nor synchronise (paper, section 2 "Implementation": the transform is meant to sit
+ * inside a training or serving loop).  Synchronises the device if the buffer has to grow;
+ * must run on the plan's device with no call of this plan in flight.  The buffer never
+ * shrinks.  Errors: SCAT_ERR_NULL, SCAT_ERR_ARG (batch < 1), SCAT_ERR_DEVICE (host-only plan
+ * or wrong device), SCAT_ERR_ALLOC.
+ */
+scat_status scat_plan_reserve(scat_plan *plan, long batch, int with_backward);
+
+/*
  * scat_forward for callers that cannot allocate device memory (code under HIP graph capture,
  * serving loops and harnesses that forbid hipMalloc): same arguments, same result, but the
  * intermediate arrays live in a buffer of SCAT_STATIC_SCRATCH_MB MiB that is part of the

@@ -51,6 +51,8 @@ def lib():
     L.scat_forward.restype = ci
     L.scat_forward_static.argtypes = [vp, vp, vp, cl, vp]
     L.scat_forward_static.restype = ci
+    L.scat_plan_reserve.argtypes = [vp, cl, ci]
+    L.scat_plan_reserve.restype = ci
     L.scat_backward.argtypes = [vp, vp, vp, vp, cl, vp]
     L.scat_backward.restype = ci
     L.scat_plan_backward_workspace_bytes.argtypes = [vp, cl]
@@ -88,7 +90,7 @@ EXPORTS = ("scat_plan_create", "scat_plan_create_host", "scat_forward", "scat_pl
            "scat_plan_timing_begin", "scat_plan_timing_end", "scat_plan_timing_row",
            "scat_backward", "scat_plan_backward_workspace_bytes", "scat_plan_create_padded",
            "scat_plan_create_padded_host", "scat_plan_grid_shape", "scat_plan_create_ex",
-           "scat_forward_static")
+           "scat_forward_static", "scat_plan_reserve")
 
 
 def scat_status_string(status):
@@ -262,6 +264,13 @@ def scat_forward_static(plan, in_ptr, out_ptr, batch, stream_ptr=None):
         raise ScatError(st, "scat_forward_static")
 
 
+def scat_plan_reserve(plan, batch, with_backward=False):
+    """Grow the plan's scratch now so that later calls of up to `batch` planes do not allocate."""
+    st = lib().scat_plan_reserve(plan, int(batch), 1 if with_backward else 0)
+    if st != SCAT_OK:
+        raise ScatError(st, "scat_plan_reserve")
+
+
 class Scattering:
     """Owner of one plan.  `forward` takes a contiguous float32 CUDA tensor whose trailing
     dims equal `shape`; all leading dims are independent planes.  One or two sides: the Morlet
@@ -350,6 +359,9 @@ class Scattering:
 
     def backward_workspace_bytes(self, batch):
         return scat_plan_backward_workspace_bytes(self._plan, batch)
+
+    def reserve(self, batch, with_backward=False):
+        scat_plan_reserve(self._plan, batch, with_backward)
 
     def timing_begin(self, kernel_name=None):
         scat_plan_timing_begin(self._plan, kernel_name)

@@ -2499,6 +2499,18 @@ scat_status scat_forward(scat_plan *plan, const float *in, float *out, long batc
   return forward_chunks(plan, in, out, batch, lay, st);
 }
 
+scat_status scat_plan_reserve(scat_plan *plan, long batch, int with_backward) {
+  if (plan == nullptr) return SCAT_ERR_NULL;
+  if (batch < 1) return SCAT_ERR_ARG;
+  if (!plan->has_device) return SCAT_ERR_DEVICE;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev != plan->device) return SCAT_ERR_DEVICE;
+  size_t need = scat_plan_workspace_bytes(plan, batch);
+  if (with_backward) need = std::max(need, scat_plan_backward_workspace_bytes(plan, batch));
+  if (need <= plan->scratch_bytes) return SCAT_OK;
+  return ensure_scratch(plan, need);
+}
+
 scat_status scat_forward_static(scat_plan *plan, const float *in, float *out, long batch,
                                 void *stream) {
   if (plan == nullptr) return SCAT_ERR_NULL;

@@ -145,3 +145,17 @@ def test_backward_argument_errors_need_no_gpu():
     finally:
         for p in (one_d, tiny, big, ok):
             scat.scat_plan_destroy(p)
+
+
+def test_reserve_argument_errors_need_no_gpu():
+    """scat_plan_reserve: null plan, bad batch, and a host-only plan (no device to reserve on)."""
+    import paper_1812_11214_amd as scat
+    from paper_1812_11214_amd import binding
+    L = binding.lib()
+    ok = scat.scat_plan_create_host((64, 64), 2, 2)
+    try:
+        assert L.scat_plan_reserve(None, 4, 0) == 5   # SCAT_ERR_NULL
+        assert L.scat_plan_reserve(ok, 0, 0) == 1     # SCAT_ERR_ARG
+        assert L.scat_plan_reserve(ok, 4, 1) == 4     # SCAT_ERR_DEVICE: host-only plan
+    finally:
+        scat.scat_plan_destroy(ok)

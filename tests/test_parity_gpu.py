@@ -250,6 +250,34 @@ def test_stream_and_plan_independence():
         pb.close()
 
 
+def test_reserve_makes_later_calls_allocation_free():
+    """After scat_plan_reserve the forward and backward calls of that size leave the device's
+    free memory untouched, and give the results they give without it."""
+    import torch
+    rng = np.random.default_rng(23)
+    x = torch.from_numpy(rng.standard_normal((6, 64, 64)).astype(np.float32)).cuda()
+    a, b = scat.Scattering((64, 64), 3, 4), scat.Scattering((64, 64), 3, 4)
+    try:
+        ref = a.forward(x)
+        g = torch.ones_like(ref)
+        gref = a.backward(x, g)
+        out, gin = torch.empty_like(ref), torch.empty_like(x)
+        b.reserve(6, with_backward=True)
+        torch.cuda.synchronize()
+        free0 = torch.cuda.mem_get_info()[0]
+        b.forward(x, out=out)
+        b.backward(x, g, grad_in=gin)
+        torch.cuda.synchronize()
+        assert torch.cuda.mem_get_info()[0] == free0
+        assert torch.equal(out, ref) and torch.equal(gin, gref)
+        free1 = torch.cuda.mem_get_info()[0]   # (torch.equal above may have grown torch's own pool)
+        b.reserve(2)   # smaller: a no-op
+        assert torch.cuda.mem_get_info()[0] == free1
+    finally:
+        a.close()
+        b.close()
+
+
 def test_timing_api():
     import torch
     rng = np.random.default_rng(11)
