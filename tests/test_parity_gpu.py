@@ -110,6 +110,9 @@ def test_config3_512x512_sample():
     (64, 3, 2, 2), (256, 4, 1, 2), (1024, 5, 8, 2), (4096, 6, 8, 1), (8, 3, 1, 2), (2048, 2, 3, 2),
     # rows of 4096 points (n2 = 2^J): the row kernel's largest LDS tile
     (8192, 12, 1, 2), (1 << 18, 3, 2, 2),
+    # 256 rows: the column passes of several octaves as segments of one launch, narrow octaves
+    # (fewer than 16 columns) beside it; first order only; one octave
+    (65536, 4, 1, 2), (1 << 17, 9, 1, 2), (65536, 8, 2, 1), (65536, 1, 3, 2),
 ])
 def test_1d_shapes(n, J, Q, max_order):
     rng = np.random.default_rng(n + J + Q)
