@@ -369,13 +369,14 @@ size_t append_table(std::vector<float> &pool, const FilterTable &t, int dims, in
   return off;
 }
 
-// Activity words of the 256 threads of k_node<64, 2, P> for one table `ft` in that kernel's
+// Activity words of the threads of k_node<64, 2, P> (groups = 8: 256 threads) or k_node_pair
+// (groups = 16: 512 threads) for one table `ft` in those kernels'
 // layout [row][column block][column parity][column pair][component]: thread (st, cq) =
-// (tid / 32, tid % 32) takes source rows st + 8 i, i = 0 .. 7; bits 4 i + ac: the table values
+// (tid / 32, tid % 32) takes source rows st + groups i, i < 64 / groups; bits 4 i + ac: the table values
 // of the direct part of column block ac (both parities, all components) are not all negligible;
 // bits 4 i + 2 + ac: the same for the part it adds to the mirrored row (row 0: to row 64).
 // The index arithmetic is the kernel's own.
-void lane_words_64(const float *ft, int P, std::vector<unsigned> &out) {
+void lane_words_64(const float *ft, int P, int groups, std::vector<unsigned> &out) {
   const int S = 128;
   double peak = 0.0;
   for (size_t i = 0; i < static_cast<size_t>(P) * S * S; ++i) peak = std::max(peak, std::fabs(static_cast<double>(ft[i])));
@@ -385,11 +386,11 @@ void lane_words_64(const float *ft, int P, std::vector<unsigned> &out) {
       if (std::fabs(static_cast<double>(ft[static_cast<size_t>(entry) * P + q])) > thr) return true;
     return false;
   };
-  for (int tid = 0; tid < 256; ++tid) {
+  for (int tid = 0; tid < 32 * groups; ++tid) {
     const int cq = tid & 31, st = tid >> 5;
     unsigned w = 0;
-    for (int i = 0; i < 8; ++i) {
-      const int row = st + 8 * i;
+    for (int i = 0; i < 64 / groups; ++i) {
+      const int row = st + groups * i;
       const bool first = row == 0;
       const int row2 = first ? 64 : S - row;
       for (int ac = 0; ac < 2; ++ac)
@@ -697,14 +698,14 @@ scat_status upload(scat_plan *p) {
       if (side != 128) continue;  // tables of k_node<64, 2, 1>
       p->lane_mask_off[kv.first] = words.size();
       for (int l = 0; l < h.LQ; ++l)
-        lane_words_64(pool.data() + kv.second + static_cast<size_t>(l) * side * side, 1, words);
+        lane_words_64(pool.data() + kv.second + static_cast<size_t>(l) * side * side, 1, 8, words);
     }
     for (const auto &kv : p->poly_psi_off) {
       const int M = p->n1 / 2;
       if ((p->n1 >> kv.first) != M / 2 || M != 128) continue;  // tables of k_node<64, 2, 4>
       p->lane_mask_off[{-1, kv.first}] = words.size();
       for (int l = 0; l < h.LQ; ++l)
-        lane_words_64(pool.data() + kv.second + static_cast<size_t>(l) * 4 * M * M, 4, words);
+        lane_words_64(pool.data() + kv.second + static_cast<size_t>(l) * 4 * M * M, 4, h.LQ % 2 == 0 ? 16 : 8, words);
     }
     if (!words.empty()) {
       if (hipMalloc(&p->d_lane_masks, words.size() * sizeof(unsigned)) != hipSuccess) return SCAT_ERR_ALLOC;

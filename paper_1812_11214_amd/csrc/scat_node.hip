@@ -82,10 +82,15 @@ __device__ __forceinline__ void load_comps(float (&d)[P], const float *tab, int 
   }
 }
 
-template <int M, int A, int P, bool POLY, bool FULL>
-__global__ __launch_bounds__(M * M / 16, (P == 4 ? 3 : 4)) void k_node(NodeArgs a) {
+// NF = 2: one workgroup of 512 threads computes the nodes of TWO filters of one source (the
+// children of a polyphase parent, which are bound by their loads): the spectrum phase is shared
+// -- every source value is loaded once for both -- and each half of the workgroup then takes
+// one node through the other phases in an LDS area of its own.
+template <int M, int A, int P, bool POLY, bool FULL, int NF>
+__device__ __forceinline__ void node_body(const NodeArgs &a) {
   static_assert(!FULL || P == 1, "a full spectrum is one source");
   static_assert(M == 64, "128 x 128 nodes take k_node_half");
+  static_assert(NF == 1 || (NF == 2 && A == 2 && P == 4 && !POLY && !FULL), "pairs: four-component loader only");
   using SL = Slab<M, M>;
   // Row slots of 76 elements (rows 24 banks apart: conflict-free for the lanes of eight rows)
   // with an unpadded row exchange (16 x T elements): 39 KB per workgroup, FOUR workgroups per
@@ -96,22 +101,125 @@ __global__ __launch_bounds__(M * M / 16, (P == 4 ? 3 : 4)) void k_node(NodeArgs 
   static_assert(P == 1 || P == 4, "sources");
   static_assert(!POLY || P == 1, "a polyphase node reads a plain spectrum");
   extern __shared__ __attribute__((aligned(16))) float2 lds[];
-  float2 *area = lds;
-  float2 *wtab = lds + M * RS;
-  const int tid = threadIdx.x;
-  const int I = a.F * (POLY ? 4 : 1);
+  // (pairs: thread role `tid` and LDS area of the half-workgroup that owns one of the two nodes)
+  const int half = NF == 2 ? static_cast<int>(threadIdx.x) / NT : 0;
+  float2 *area = lds + half * (M * RS);
+  float2 *wtab = lds + NF * M * RS;
+  const int tid = NF == 2 ? static_cast<int>(threadIdx.x) % NT : static_cast<int>(threadIdx.x);
+  const int I = a.F * (POLY ? 4 : 1) / NF;
   const long bq = blockIdx.x >> 3;
   const long s = (blockIdx.x & 7) + 8 * (bq / I);
   const int item = static_cast<int>(bq % I);
   if (s >= a.NS) return;
-  const int f = POLY ? item >> 2 : item;
+  const int f = POLY ? item >> 2 : item * NF + half;
   const int pr = POLY ? (item >> 1) & 1 : 0, pc = POLY ? item & 1 : 0;
   // (no barrier here: the table is first read after the barrier that ends the spectrum phase,
   // and the workgroup's loads start without waiting for the twiddle fetch)
   SL::fill_twiddles(wtab, a.tw, a.tw_n, false);
   const int tw_step = a.tw_n / (2 * M);  // POLY only: table step of w = exp(-2 pi i / 2M)
 
-  if constexpr (A == 2 && !FULL) {
+  if constexpr (NF == 2) {
+    // ---- 1 for two filters at once: as below, with 16 row groups (thread = rows st + 16 i,
+    // i < 4) and every source value used for the tables of both filters f0 and f0 + 1.
+    const int ltid = threadIdx.x;
+    const int f0 = item * 2;
+    const float4 *src4 = reinterpret_cast<const float4 *>(a.src + static_cast<size_t>(s) * P * 65 * S);
+    const float *ft0 = a.filt + static_cast<size_t>(f0) * P * S * S;
+    const int cq = ltid & 31, st = ltid >> 5;
+    float2 z2[2][4][2];
+    unsigned am[2];
+    int zero_e[2];
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+      am[c] = a.lane_mask != nullptr ? a.lane_mask[static_cast<size_t>(f0 + c) * (2 * NT) + ltid] : ~0u;
+      zero_e[c] = (a.F - f0 - c) * S * S;  // from table f0 + c to the zeros behind the F tables
+    }
+    auto pick = [](bool on, int idx, int other) { return on ? idx : other; };
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row = st + 16 * i;
+      const bool first = i == 0 && st == 0;
+      const int row2 = first ? 64 : S - row;
+      const unsigned b0 = am[0] >> (4 * i), b1 = am[1] >> (4 * i);
+      float4 w[2][P], w2[2][P];
+#pragma unroll
+      for (int ac = 0; ac < 2; ++ac) {
+        const bool any_d = ((b0 | b1) >> ac) & 1u, any_m = ((b0 | b1) >> (2 + ac)) & 1u;
+        const int wc = pick(any_d || (any_m && !first), 32 * ac + cq, 0);
+#pragma unroll
+        for (int q = 0; q < P; ++q) w[ac][q] = src4[(q * 65 + row) * (S / 2) + wc];
+      }
+      if (i == 0) {
+        // row 0: its second part is row 64 itself, not a mirrored row
+#pragma unroll
+        for (int ac = 0; ac < 2; ++ac) {
+          const bool any_m = ((b0 | b1) >> (2 + ac)) & 1u;
+          const int wc = pick(any_m, 32 * ac + cq, 0);
+#pragma unroll
+          for (int q = 0; q < P; ++q) w2[ac][q] = first ? src4[(q * 65 + 64) * (S / 2) + wc] : w[ac][q];
+        }
+      }
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        const float *ft = ft0 + static_cast<size_t>(c) * P * S * S;
+        const unsigned bits = c == 0 ? b0 : b1;
+        float d[2][2][P], m[2][2][P];
+#pragma unroll
+        for (int ac = 0; ac < 2; ++ac) {
+          const bool on_d = (bits >> ac) & 1u, on_m = (bits >> (2 + ac)) & 1u;
+#pragma unroll
+          for (int e = 0; e < 2; ++e) {
+            const int idx = first ? 32 * ac + cq : (64 - 32 * ac - cq - e) & 63;
+            load_comps<P>(d[ac][e], ft, pick(on_d, ((row * 2 + ac) * 2 + e) * 32 + cq, zero_e[c]));
+            load_comps<P>(m[ac][e], ft, pick(on_m, ((row2 * 2 + (idx >> 5)) * 2 + e) * 32 + (idx & 31), zero_e[c]));
+          }
+        }
+        float4 zd = make_float4(0.f, 0.f, 0.f, 0.f), zs = zd;
+#pragma unroll
+        for (int ac = 0; ac < 2; ++ac) {
+          // s = (1, sc, -1, -sc), sc = -1 except for column 0
+          const float sc0 = first ? 1.f : (ac == 0 && cq == 0) ? 1.f : -1.f;
+          const float sc1 = first ? 1.f : -1.f;
+          const float sn = first ? 1.f : -1.f;
+          m[ac][0][1] *= sc0;
+          m[ac][0][2] *= sn;
+          m[ac][0][3] *= sn * sc0;
+          m[ac][1][1] *= sc1;
+          m[ac][1][2] *= sn;
+          m[ac][1][3] *= sn * sc1;
+#pragma unroll
+          for (int q = 0; q < P; ++q) {
+            const float4 wm = i == 0 ? w2[ac][q] : w[ac][q];
+            zd.x = fmaf(w[ac][q].x, d[ac][0][q], zd.x);
+            zd.y = fmaf(w[ac][q].y, d[ac][0][q], zd.y);
+            zd.z = fmaf(w[ac][q].z, d[ac][1][q], zd.z);
+            zd.w = fmaf(w[ac][q].w, d[ac][1][q], zd.w);
+            zs.x = fmaf(wm.x, m[ac][0][q], zs.x);
+            zs.y = fmaf(wm.y, m[ac][0][q], zs.y);
+            zs.z = fmaf(wm.z, m[ac][1][q], zs.z);
+            zs.w = fmaf(wm.w, m[ac][1][q], zs.w);
+          }
+        }
+        *reinterpret_cast<float4 *>(lds + c * (M * RS) + row * RS + 2 * cq) = zd;
+        const float cj = first ? 1.f : -1.f;
+        z2[c][i][0] = make_float2(zs.x, cj * zs.y);
+        z2[c][i][1] = make_float2(zs.z, cj * zs.w);
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int row = st + 16 * i;
+        const bool first = row == 0;
+        float2 *tr = lds + c * (M * RS) + (first ? 0 : M - row) * RS;
+        const int c0 = first ? 2 * cq : (M - 2 * cq) & (M - 1), c1 = first ? 2 * cq + 1 : M - 1 - 2 * cq;
+        float2 o0 = tr[c0], o1 = tr[c1];
+        tr[c0] = make_float2(o0.x + z2[c][i][0].x, o0.y + z2[c][i][0].y);
+        tr[c1] = make_float2(o1.x + z2[c][i][1].x, o1.y + z2[c][i][1].y);
+      }
+  } else if constexpr (A == 2 && !FULL) {
     // ---- 1 (source twice as large as the node). Every stored source row (0 .. 64, 128 columns)
     // is read once, by half a wavefront: a lane takes two adjacent columns of both column
     // blocks and of all P components (16-byte loads).  Row rho contributes to row rho of the
@@ -474,6 +582,15 @@ __global__ __launch_bounds__(M * M / 16, (P == 4 ? 3 : 4)) void k_node(NodeArgs 
     up[T * i] = val;
   }
 }
+
+template <int M, int A, int P, bool POLY, bool FULL>
+__global__ __launch_bounds__(M * M / 16, (P == 4 ? 3 : 4)) void k_node(NodeArgs a) {
+  node_body<M, A, P, POLY, FULL, 1>(a);
+}
+
+// Two 64 x 64 children of a polyphase parent per workgroup (78 KB of LDS, two workgroups and
+// sixteen waves per compute unit)
+__global__ __launch_bounds__(512, 4) void k_node_pair(NodeArgs a) { node_body<64, 2, 4, false, false, 2>(a); }
 
 // ------------------------------------------------------------------------------------
 // k_node for 128 x 128 nodes with HALF the workgroup: 512 threads hold the node in registers
@@ -944,8 +1061,11 @@ hipError_t launch_node_t(const NodeArgs &a, hipStream_t st) {
   // variant is bound by its loads and measured faster with THREE workgroups per compute unit
   // (fewer loads in flight): it asks for 44 KB.
   const size_t lds = P == 4 ? static_cast<size_t>(44) << 10 : (static_cast<size_t>(M) * 76 + 2 * M) * sizeof(float2);
-  const std::string name = (M == 128 ? "k_node_half<" : "k_node<64, ") + std::to_string(A) + ", " +
-                            std::to_string(P) + (POLY ? ", true" : ", false") + (FULL ? ", full>" : ">");
+  constexpr bool kPairs = M == 64 && A == 2 && P == 4 && !POLY && !FULL;  // two filters per workgroup
+  const bool pairs = kPairs && a.F % 2 == 0;
+  const std::string name = pairs ? std::string("k_node_pair")
+                                 : (M == 128 ? "k_node_half<" : "k_node<64, ") + std::to_string(A) + ", " +
+                                       std::to_string(P) + (POLY ? ", true" : ", false") + (FULL ? ", full>" : ">");
   const double items = static_cast<double>(a.NS) * I;
   const double pts = static_cast<double>(M) * M;
   LaunchScope obs(name.c_str(),
@@ -955,6 +1075,17 @@ hipError_t launch_node_t(const NodeArgs &a, hipStream_t st) {
                   items * ((a.uout ? 2 : 1) * fft2_flops(M) + fft2_flops(kOut) +
                            pts * (4.0 * P * A * A + 4.0 + 2.0) + fft2_flops(M) * (a.uout ? 0 : 1)),
                   st);
+  if constexpr (kPairs) {
+    if (pairs) {
+      // pairs of filters: half as many workgroups of twice the size
+      const size_t lds_p = (static_cast<size_t>(2) * M * 76 + 2 * M) * sizeof(float2);
+      static unsigned long long lds_ok = 0;
+      hipError_t e = allow_large_lds(reinterpret_cast<const void *>(k_node_pair), lds_ok);
+      if (e != hipSuccess) return e;
+      hipLaunchKernelGGL(k_node_pair, dim3(static_cast<unsigned>(blocks / 2)), dim3(512), lds_p, st, a);
+      return hipGetLastError();
+    }
+  }
   if constexpr (M == 128) {
     const size_t lds_h = (64 * 152 + 128 + 256 + 64) * sizeof(float2);
     static unsigned long long lds_ok = 0;
