@@ -1003,6 +1003,51 @@ hipError_t launch_col_segs_impl(const float2 *src, float2 *uc, int Mr, const Col
   return hipGetLastError();
 }
 
+// Mode 2 (the last step of the 1-D cascade: inverse column transform of the lowpassed rows,
+// real part to the output channel) with the transform in registers: nodes of MR = 256 rows
+// and TC <= 16 columns, 16 TC threads per node (thread = column c, rows t + 16 i), 16 / TC
+// nodes per workgroup.  src [nodes][MR][TC] complex; out[(p K + channel(g)) MR TC + row TC + c].
+template <int MR>
+__global__ __launch_bounds__(256) void k_col_out(const float2 *__restrict__ src, long nodes, int TC,
+                                                 float *__restrict__ out, ChanMap cm, int K,
+                                                 const float2 *__restrict__ tw, int tw_n) {
+  constexpr int E = 16, T = MR / E;
+  extern __shared__ float2 lds[];
+  const int per = T * TC;                      // threads per node
+  const int slot = threadIdx.x / per, l = threadIdx.x % per;
+  const int c = l % TC, t = l / TC;
+  const int KS = per + 16;
+  const long node_raw = static_cast<long>(blockIdx.x) * (256 / per) + slot;
+  const bool valid = node_raw < nodes;
+  const long node = valid ? node_raw : nodes - 1;  // idle slots redo the last node, unstored
+  float2 wt[E], v[E];
+  load_twiddles<E, T>(wt, t, tw, tw_n);
+  const float2 *sp = src + static_cast<size_t>(node) * MR * TC + t * TC + c;
+#pragma unroll
+  for (int i = 0; i < E; ++i) v[i] = sp[i * per];
+  fft_core<E, T, true>(v, t, lds + slot * E * KS + c, KS, TC, wt);
+  if (!valid) return;
+  const long p = node / cm.G;
+  const int g = static_cast<int>(node - p * cm.G);
+  float *op = out + (static_cast<size_t>(p) * K + chan_of(cm, g)) * MR * TC + t * TC + c;
+#pragma unroll
+  for (int i = 0; i < E; ++i) op[i * per] = v[i].x;
+}
+
+hipError_t launch_col_out(const float2 *src, long nodes, int Mc, float *out, ChanMap cm, int K,
+                          const float2 *tw, int tw_n, hipStream_t st) {
+  constexpr int MR = 256, E = 16, T = MR / E;
+  const int per = T * Mc;
+  const long blocks = (nodes + 256 / per - 1) / (256 / per);
+  if (blocks <= 0 || blocks > 0x7fffffffL) return hipErrorInvalidValue;
+  const size_t lds = static_cast<size_t>(256 / per) * E * (per + 16) * sizeof(float2);
+  const double pts = static_cast<double>(nodes) * MR * Mc;
+  Observe ob("k_col_out<256>", pts * 12, static_cast<double>(nodes) * Mc * fft_flops(MR), st);
+  hipLaunchKernelGGL((k_col_out<MR>), dim3(static_cast<unsigned>(blocks)), dim3(256), lds, st, src, nodes, Mc, out,
+                     cm, K, tw, tw_n);
+  return hipGetLastError();
+}
+
 template <int MR>
 hipError_t launch_col_fast_t(int mode, const void *src, long nodes, int Mc, float2 *uc, bool uc_half,
                              int post_tw_m, const float *phi_rows, int m_r, float *w_out,
@@ -2017,6 +2062,9 @@ hipError_t launch_col(int mode, const void *src, long nodes, int Mr, int Mc, flo
   if (uc_half && (mode == 2 || post_tw_m != 0 || Mr < 2)) return hipErrorInvalidValue;
   // register-resident variant: modes 0/1, column length 16*T with T | 16, at least 16
   // columns (4 without a lowpass tail), lowpass length dividing the column length
+  if (mode == 2 && Mr == 256 && (Mc == 1 || Mc == 2 || Mc == 4 || Mc == 8 || Mc == 16) && tw_n % Mr == 0 &&
+      out != nullptr && cm.G >= 1)
+    return launch_col_out(static_cast<const float2 *>(src), nodes, Mc, out, cm, K, tw, tw_n, st);
   if (mode != 2 && (Mc >= 16 || (Mc >= 4 && w_out == nullptr)) && tw_n % Mr == 0 &&
       (post_tw_m == 0 || !uc_half) &&
       (w_out == nullptr || (m_r >= 1 && m_r <= Mr))) {
