@@ -141,7 +141,7 @@ __device__ __forceinline__ void node_body(const NodeArgs &a) {
       const bool first = i == 0 && st == 0;
       const int row2 = first ? 64 : S - row;
       const unsigned b0 = am[0] >> (4 * i), b1 = am[1] >> (4 * i);
-      float4 w[2][P], w2[2][P];
+      float4 w[2][P];
 #pragma unroll
       for (int ac = 0; ac < 2; ++ac) {
         const bool any_d = ((b0 | b1) >> ac) & 1u, any_m = ((b0 | b1) >> (2 + ac)) & 1u;
@@ -149,32 +149,40 @@ __device__ __forceinline__ void node_body(const NodeArgs &a) {
 #pragma unroll
         for (int q = 0; q < P; ++q) w[ac][q] = src4[(q * 65 + row) * (S / 2) + wc];
       }
-      if (i == 0) {
-        // row 0: its second part is row 64 itself, not a mirrored row
-#pragma unroll
-        for (int ac = 0; ac < 2; ++ac) {
-          const bool any_m = ((b0 | b1) >> (2 + ac)) & 1u;
-          const int wc = pick(any_m, 32 * ac + cq, 0);
-#pragma unroll
-          for (int q = 0; q < P; ++q) w2[ac][q] = first ? src4[(q * 65 + 64) * (S / 2) + wc] : w[ac][q];
-        }
-      }
-#pragma unroll
-      for (int c = 0; c < 2; ++c) {
+      // Per filter: direct part (table row `row`) and second part (mirrored, table row S - row).
+      // Row 0 is special: its second part is row 64 itself, not a mirrored row, so in the first
+      // pass the lanes of row 0 fetch row 64 between the direct parts and the second parts of
+      // the two filters.
+      auto load_tab = [&](float (&tv)[2][2][P], int c, bool mirrored) {
         const float *ft = ft0 + static_cast<size_t>(c) * P * S * S;
-        const unsigned bits = c == 0 ? b0 : b1;
-        float d[2][2][P], m[2][2][P];
+        const unsigned bits = (c == 0 ? b0 : b1) >> (mirrored ? 2 : 0);
 #pragma unroll
         for (int ac = 0; ac < 2; ++ac) {
-          const bool on_d = (bits >> ac) & 1u, on_m = (bits >> (2 + ac)) & 1u;
+          const bool on = (bits >> ac) & 1u;
 #pragma unroll
           for (int e = 0; e < 2; ++e) {
             const int idx = first ? 32 * ac + cq : (64 - 32 * ac - cq - e) & 63;
-            load_comps<P>(d[ac][e], ft, pick(on_d, ((row * 2 + ac) * 2 + e) * 32 + cq, zero_e[c]));
-            load_comps<P>(m[ac][e], ft, pick(on_m, ((row2 * 2 + (idx >> 5)) * 2 + e) * 32 + (idx & 31), zero_e[c]));
+            const int entry = mirrored ? ((row2 * 2 + (idx >> 5)) * 2 + e) * 32 + (idx & 31)
+                                       : ((row * 2 + ac) * 2 + e) * 32 + cq;
+            load_comps<P>(tv[ac][e], ft, pick(on, entry, zero_e[c]));
           }
         }
-        float4 zd = make_float4(0.f, 0.f, 0.f, 0.f), zs = zd;
+      };
+      auto direct_part = [&](const float (&d)[2][2][P], int c) {
+        float4 zd = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int ac = 0; ac < 2; ++ac)
+#pragma unroll
+          for (int q = 0; q < P; ++q) {
+            zd.x = fmaf(w[ac][q].x, d[ac][0][q], zd.x);
+            zd.y = fmaf(w[ac][q].y, d[ac][0][q], zd.y);
+            zd.z = fmaf(w[ac][q].z, d[ac][1][q], zd.z);
+            zd.w = fmaf(w[ac][q].w, d[ac][1][q], zd.w);
+          }
+        *reinterpret_cast<float4 *>(lds + c * (M * RS) + row * RS + 2 * cq) = zd;
+      };
+      auto second_part = [&](float (&m)[2][2][P], int c) {
+        float4 zs = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
         for (int ac = 0; ac < 2; ++ac) {
           // s = (1, sc, -1, -sc), sc = -1 except for column 0
@@ -189,21 +197,46 @@ __device__ __forceinline__ void node_body(const NodeArgs &a) {
           m[ac][1][3] *= sn * sc1;
 #pragma unroll
           for (int q = 0; q < P; ++q) {
-            const float4 wm = i == 0 ? w2[ac][q] : w[ac][q];
-            zd.x = fmaf(w[ac][q].x, d[ac][0][q], zd.x);
-            zd.y = fmaf(w[ac][q].y, d[ac][0][q], zd.y);
-            zd.z = fmaf(w[ac][q].z, d[ac][1][q], zd.z);
-            zd.w = fmaf(w[ac][q].w, d[ac][1][q], zd.w);
-            zs.x = fmaf(wm.x, m[ac][0][q], zs.x);
-            zs.y = fmaf(wm.y, m[ac][0][q], zs.y);
-            zs.z = fmaf(wm.z, m[ac][1][q], zs.z);
-            zs.w = fmaf(wm.w, m[ac][1][q], zs.w);
+            zs.x = fmaf(w[ac][q].x, m[ac][0][q], zs.x);
+            zs.y = fmaf(w[ac][q].y, m[ac][0][q], zs.y);
+            zs.z = fmaf(w[ac][q].z, m[ac][1][q], zs.z);
+            zs.w = fmaf(w[ac][q].w, m[ac][1][q], zs.w);
           }
         }
-        *reinterpret_cast<float4 *>(lds + c * (M * RS) + row * RS + 2 * cq) = zd;
         const float cj = first ? 1.f : -1.f;
         z2[c][i][0] = make_float2(zs.x, cj * zs.y);
         z2[c][i][1] = make_float2(zs.z, cj * zs.w);
+      };
+      if (i == 0) {
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+          float d[2][2][P];
+          load_tab(d, c, false);
+          direct_part(d, c);
+        }
+        if (first) {
+#pragma unroll
+          for (int ac = 0; ac < 2; ++ac) {
+            const int wc = pick(((b0 | b1) >> (2 + ac)) & 1u, 32 * ac + cq, 0);
+#pragma unroll
+            for (int q = 0; q < P; ++q) w[ac][q] = src4[(q * 65 + 64) * (S / 2) + wc];
+          }
+        }
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+          float m[2][2][P];
+          load_tab(m, c, true);
+          second_part(m, c);
+        }
+      } else {
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+          float d[2][2][P], m[2][2][P];
+          load_tab(d, c, false);
+          load_tab(m, c, true);
+          direct_part(d, c);
+          second_part(m, c);
+        }
       }
     }
     __syncthreads();
