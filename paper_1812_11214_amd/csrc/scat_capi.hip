@@ -2245,13 +2245,20 @@ scat_status forward_1d(scat_plan *p, const float *in, float *out, long p0, long 
       tot2 += static_cast<size_t>(j2) * Q * (N >> h.res(j2));
     }
     float2 *T2 = T + tot1 * pc;
+    // The columns are real after the modulus: where every octave's shape allows it, the column
+    // passes write rows 0 .. N1/2 of each spectrum only (compactly, at the start of the node's
+    // place) and the row passes derive the other rows from them.
+    bool half = N1 == 32 || N1 == 64 || N1 == 128 || N1 == 256;
+    for (int j = 0; half && j < J; ++j) half = (N2 >> h.res(j)) >= 4 && scat::rows1d_half_supported(N1, N2 >> h.res(j));
     // column passes (mode 1 with the four-step twiddle) over a list of arrays
     auto cols_pass = [&](const float2 *src, float2 *dst, const std::vector<scat::ColSeg> &all) -> scat_status {
       std::vector<scat::ColSeg> together;
       for (const scat::ColSeg &sg : all)
         if (N1 == 256 && sg.Mc >= 16 && static_cast<int>(together.size()) < scat::kColMaxSegs) together.push_back(sg);
       const bool merged = together.size() >= 2;
-      if (merged) SCAT_TRY(scat::launch_col_segs(src, dst, N1, together.data(), static_cast<int>(together.size()), tw, tw_n, st));
+      if (merged)
+        SCAT_TRY(scat::launch_col_segs(src, dst, N1, together.data(), static_cast<int>(together.size()), half, tw,
+                                       tw_n, st));
       size_t taken = 0;
       for (const scat::ColSeg &sg : all) {
         if (merged && N1 == 256 && sg.Mc >= 16 && taken < together.size()) {
@@ -2259,7 +2266,7 @@ scat_status forward_1d(scat_plan *p, const float *in, float *out, long p0, long 
           continue;
         }
         SCAT_TRY(scat::launch_col(1, src + sg.src_off, sg.nodes, N1, sg.Mc, dst + sg.uc_off, N1 * sg.Mc, nullptr, 0,
-                                  nullptr, nullptr, none, K, tw, tw_n, st));
+                                  nullptr, nullptr, none, K, tw, tw_n, st, half));
       }
       return SCAT_OK;
     };
@@ -2288,7 +2295,7 @@ scat_status forward_1d(scat_plan *p, const float *in, float *out, long p0, long 
         ch.c[ch.n++] = scat::Rows1dChild{tab + p->psi2_off[{r1, j2}], T2 + t2_off[j2] * pc, r2 - r1, N >> r2,
                                          ChanMap{Q, Q, 0, j1 * Q}, j2 * Q};
       }
-      SCAT_TRY(scat::launch_rows1d(U + off1[j1] * pc, pc * Q, N1, N2 >> r1, ch, tw, tw_n, st));
+      SCAT_TRY(scat::launch_rows1d(U + off1[j1] * pc, pc * Q, N1, N2 >> r1, ch, tw, tw_n, st, half));
     }
     if (h.max_order == 2 && J >= 2) {
       segs.clear();
@@ -2302,7 +2309,7 @@ scat_status forward_1d(scat_plan *p, const float *in, float *out, long p0, long 
         lc.n = 1;
         lc.c[0] = low_child(r2, ChanMap{j2 * Q, 1, 0, 1});
         lc.c[0].chan_tab = p->d_chan1d + p->chan1d_off[j2];
-        SCAT_TRY(scat::launch_rows1d(V + t2_off[j2] * pc, pc * j2 * Q, N1, N2 >> r2, lc, tw, tw_n, st));
+        SCAT_TRY(scat::launch_rows1d(V + t2_off[j2] * pc, pc * j2 * Q, N1, N2 >> r2, lc, tw, tw_n, st, half));
       }
     }
     if (K > 1)

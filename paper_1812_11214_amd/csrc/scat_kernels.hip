@@ -629,7 +629,12 @@ __device__ __forceinline__ void rows1d_child_inv(float2 *slot, int t, int tw_ste
 }
 
 // (E = 16 points per lane; rows of 4 and 8 points: E = row length, T = 1.)
-template <int E, int T>
+// HALF: src holds rows 0 .. Sr/2 of every node only ([nodes][Sr/2+1][Sc], as the column pass
+// writes them for real columns).  Row Sr - k1 of the twiddled column spectra is the conjugate
+// of row k1 times exp(-2 pi i b / Sc), so its row transform is the stored row's, conjugated and
+// read backwards: X'[k2] = conj(X[Sc - 1 - k2]).  A row group therefore serves two rows of the
+// node from one load and one forward transform (rows 0 and Sr/2 have no partner).
+template <int E, int T, bool HALF>
 __global__ __launch_bounds__(256, 4) void k_rows1d_reg(const float2 *__restrict__ src, long rows,
                                                     int Sr, Rows1dArgs a,
                                                     const float2 *__restrict__ tw, int tw_n) {
@@ -647,8 +652,10 @@ __global__ __launch_bounds__(256, 4) void k_rows1d_reg(const float2 *__restrict_
   const long row_raw = static_cast<long>(blockIdx.x) * RPB + rl;
   const bool valid = row_raw < rows;
   const long row = valid ? row_raw : rows - 1;  // idle groups redo the last row, unstored
-  const long node = row / Sr;
-  const int k1 = static_cast<int>(row - node * Sr);
+  const int SrS = HALF ? Sr / 2 + 1 : Sr;        // stored rows of a node
+  const long node = row / SrS;
+  int k1 = static_cast<int>(row - node * SrS);
+  bool live = valid;
   float2 *slot = lds + Sc + rl * XS;
   float2 v[E];
   {
@@ -660,8 +667,30 @@ __global__ __launch_bounds__(256, 4) void k_rows1d_reg(const float2 *__restrict_
     for (int k = 0; k < E; ++k) wt[k] = twl[t * k];
     fft_core<E, T, false, true>(v, t, slot, T + 1, 1, wt);
   }
-  // exp(+2 pi i k1 i / (16 Sr)): the row's share of every child's four-step twiddle
   float2 *rowtw = ROWTW ? slot + XS - 16 : slot;
+#pragma unroll 1
+  for (int pass = 0; pass < (HALF ? 2 : 1); ++pass) {
+  if (HALF && pass == 1) {
+    // the partner row Sr - k1: spectrum conj(X[Sc - 1 - k2]); element t + T i comes from lane
+    // T - 1 - t of the row group, register E - 1 - i
+    live = live && k1 != 0 && 2 * k1 != Sr;
+    k1 = (Sr - k1) & (Sr - 1);  // (rows without a partner: unstored)
+    float2 u[E];
+#pragma unroll
+    for (int i = 0; i < E; ++i) {
+      const float2 x = v[E - 1 - i];
+      if (T > 1) {
+        const int from = (static_cast<int>(threadIdx.x) & 63 & ~(T - 1)) | (T - 1 - t);
+        u[i] = make_float2(__shfl(x.x, from), -__shfl(x.y, from));
+      } else {
+        u[i] = make_float2(x.x, -x.y);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < E; ++i) v[i] = u[i];
+    wave_sync();  // the first pass's reads of the row's twiddles are done
+  }
+  // exp(+2 pi i k1 i / (16 Sr)): the row's share of every child's four-step twiddle
   if (ROWTW) {
     // lane t fetches entries t, t + T, ... (T >= 4 lanes share the 16 entries)
     const int rstep = tw_n / (16 * Sr);
@@ -705,7 +734,7 @@ __global__ __launch_bounds__(256, 4) void k_rows1d_reg(const float2 *__restrict_
     for (int i = 0; i < E; ++i)
       if (t + T * i < m) slot[t + T * i] = p[i];
     wave_sync();
-    long drow = row;
+    long drow = node * Sr + k1;
     if (ch.K > 0) {
       const int g = static_cast<int>(node % ch.cm.G);
       drow = ((node / ch.cm.G) * ch.K + (ch.chan_tab != nullptr ? ch.chan_tab[g] : chan_of(ch.cm, g))) * Sr + k1;
@@ -714,20 +743,21 @@ __global__ __launch_bounds__(256, 4) void k_rows1d_reg(const float2 *__restrict_
     const int tws = Sc >> lgm;
     switch (lgm) {
       case 0:
-        if (t == 0 && valid) dp[0] = slot[0];
+        if (t == 0 && live) dp[0] = slot[0];
         break;
-      case 1: rows1d_child_inv<2, 1, ROWTW>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, valid, rowtw); break;
-      case 2: rows1d_child_inv<4, 1, ROWTW>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, valid, rowtw); break;
-      case 3: if (E >= 8) rows1d_child_inv<(E >= 8 ? 8 : 4), 1, ROWTW>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, valid, rowtw); break;
-      case 4: if (E >= 16) rows1d_child_inv<(E >= 16 ? 16 : 4), 1, ROWTW>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, valid, rowtw); break;
-      case 5: if (T >= 2) rows1d_child_inv<16, (T >= 2 ? 2 : 1), ROWTW>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, valid, rowtw); break;
-      case 6: if (T >= 4) rows1d_child_inv<16, (T >= 4 ? 4 : 1), ROWTW>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, valid, rowtw); break;
-      case 7: if (T >= 8) rows1d_child_inv<16, (T >= 8 ? 8 : 1), ROWTW>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, valid, rowtw); break;
-      case 8: if (T >= 16) rows1d_child_inv<16, (T >= 16 ? 16 : 1), ROWTW>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, valid, rowtw); break;
+      case 1: rows1d_child_inv<2, 1, ROWTW>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, live, rowtw); break;
+      case 2: rows1d_child_inv<4, 1, ROWTW>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, live, rowtw); break;
+      case 3: if (E >= 8) rows1d_child_inv<(E >= 8 ? 8 : 4), 1, ROWTW>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, live, rowtw); break;
+      case 4: if (E >= 16) rows1d_child_inv<(E >= 16 ? 16 : 4), 1, ROWTW>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, live, rowtw); break;
+      case 5: if (T >= 2) rows1d_child_inv<16, (T >= 2 ? 2 : 1), ROWTW>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, live, rowtw); break;
+      case 6: if (T >= 4) rows1d_child_inv<16, (T >= 4 ? 4 : 1), ROWTW>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, live, rowtw); break;
+      case 7: if (T >= 8) rows1d_child_inv<16, (T >= 8 ? 8 : 1), ROWTW>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, live, rowtw); break;
+      case 8: if (T >= 16) rows1d_child_inv<16, (T >= 16 ? 16 : 1), ROWTW>(slot, t, tws, twl, dp, k1, ch.post_tw_m, tw, tw_n, live, rowtw); break;
       default: break;
     }
     wave_sync();  // the slot is reused by the next child
   }
+  }  // pass
 }
 
 // ------------------------------------------------------------------------------------
@@ -826,7 +856,7 @@ __device__ __forceinline__ void col_fast_body(unsigned blk, const void *__restri
   }
   fft_core<E, T, false>(v, t, lds + c, KS, TC, wt);
   if (uc != nullptr) {
-    if (uc_half) {
+    if (uc_half && post_tw_m == 0) {
       // real input: rows above MR/2 are conjugates of stored ones; keep rows 0..MR/2 compactly
       float2 *up = uc + static_cast<size_t>(node) * (MR / 2 + 1) * Mc + off0;
 #pragma unroll
@@ -844,10 +874,14 @@ __device__ __forceinline__ void col_fast_body(unsigned blk, const void *__restri
         lds[idx] = tw[((i * (c0 + cc)) & bmask) * bstep];
       }
       __syncthreads();
-      float2 *up = uc + plane + off0;
+      // (uc_half: the column was real, so row MR - k of the twiddled result is the conjugate of
+      // row k times exp(-2 pi i b / Mc); rows 0 .. MR/2 are kept, compactly, and the row pass
+      // derives the others from them)
+      float2 *up = uc_half ? uc + static_cast<size_t>(node) * (MR / 2 + 1) * Mc + off0 : uc + plane + off0;
       const float2 wa = tw[((t * (c0 + c)) & (post_tw_m - 1)) * (tw_n / post_tw_m)];
 #pragma unroll
-      for (int i = 0; i < E; ++i) up[i * step] = cmul(v[i], cmul(wa, lds[i * TC + c]));
+      for (int i = 0; i < E; ++i)
+        if (!uc_half || t + T * i <= MR / 2) up[i * step] = cmul(v[i], cmul(wa, lds[i * TC + c]));
     } else if (post_tw_m > 0) {
       // four-step forward: times exp(-2 pi i k_r c / post_tw_m), k_r = t + T i, c the column
       float2 *up = uc + plane + off0;
@@ -964,19 +998,19 @@ struct ColSegsDev {
 template <int MR>
 __global__ __launch_bounds__(256) void k_col_fast_segs(const float2 *__restrict__ src,
                                                        float2 *__restrict__ uc, ColSegsDev sg, int TC,
-                                                       const float2 *__restrict__ tw, int tw_n) {
+                                                       int uc_half, const float2 *__restrict__ tw, int tw_n) {
   int s = 0;
 #pragma unroll
   for (int i = 1; i < kColMaxSegs; ++i)
     if (i < sg.n && blockIdx.x >= sg.first[i]) s = i;
   s = __builtin_amdgcn_readfirstlane(s);
   const int Mc = sg.Mc[s];
-  col_fast_body<MR, 1, 0>(blockIdx.x - sg.first[s], src + sg.src_off[s], Mc, TC, uc + sg.uc_off[s], 0, MR * Mc,
-                          nullptr, 0, nullptr, tw, tw_n);
+  col_fast_body<MR, 1, 0>(blockIdx.x - sg.first[s], src + sg.src_off[s], Mc, TC, uc + sg.uc_off[s], uc_half,
+                          MR * Mc, nullptr, 0, nullptr, tw, tw_n);
 }
 
-hipError_t launch_col_segs_impl(const float2 *src, float2 *uc, int Mr, const ColSeg *segs, int n, const float2 *tw,
-                                int tw_n, hipStream_t st) {
+hipError_t launch_col_segs_impl(const float2 *src, float2 *uc, int Mr, const ColSeg *segs, int n, bool uc_half,
+                                const float2 *tw, int tw_n, hipStream_t st) {
   if (Mr != 256 || n < 1 || n > kColMaxSegs || tw_n % Mr != 0) return hipErrorInvalidValue;
   constexpr int MR = 256, E = 16, T = MR / E, TC = 16;
   ColSegsDev sg{};
@@ -997,9 +1031,9 @@ hipError_t launch_col_segs_impl(const float2 *src, float2 *uc, int Mr, const Col
     cols += static_cast<double>(segs[i].nodes) * segs[i].Mc;
   }
   const size_t lds = static_cast<size_t>(E) * (T * TC + 16) * sizeof(float2);
-  Observe ob("k_col_fast_segs<256>", pts * 16, cols * 2 * fft_flops(MR) + 4.0 * pts, st);
+  Observe ob("k_col_fast_segs<256>", pts * (uc_half ? 12 : 16), cols * 2 * fft_flops(MR) + 4.0 * pts, st);
   hipLaunchKernelGGL((k_col_fast_segs<MR>), dim3(static_cast<unsigned>(blocks)), dim3(T * TC), lds, st, src, uc, sg,
-                     TC, tw, tw_n);
+                     TC, static_cast<int>(uc_half), tw, tw_n);
   return hipGetLastError();
 }
 
@@ -1053,8 +1087,9 @@ hipError_t launch_col_fast_t(int mode, const void *src, long nodes, int Mc, floa
                              int post_tw_m, const float *phi_rows, int m_r, float *w_out,
                              const float2 *tw, int tw_n, hipStream_t st) {
   constexpr int E = MR > 256 ? 32 : 16, T = MR / E;
-  if (post_tw_m > 0 && (uc_half || tw_n % post_tw_m != 0 || (post_tw_m & (post_tw_m - 1)) != 0))
-    return hipErrorInvalidValue;
+  if (post_tw_m > 0 && (tw_n % post_tw_m != 0 || (post_tw_m & (post_tw_m - 1)) != 0)) return hipErrorInvalidValue;
+  // half spectra with the four-step twiddle: the factored-twiddle path only (16 points per thread)
+  if (post_tw_m > 0 && uc_half && (E != 16 || post_tw_m != MR * Mc || mode != 1)) return hipErrorInvalidValue;
   int TC = 256 / T;
   if (TC < 16) TC = 16;
   if (TC > Mc) TC = Mc;
@@ -1954,7 +1989,7 @@ void set_launch_observer(LaunchObserver *o) { g_observer = o; }
 
 template <int E, int T>
 hipError_t launch_rows1d_reg_t(const float2 *src, long rows, int Sr, const Rows1dArgs &a, double bytes,
-                               double flops, const float2 *tw, int tw_n, hipStream_t st) {
+                               double flops, const float2 *tw, int tw_n, hipStream_t st, bool half) {
   constexpr int Sc = E * T, RPB = 256 / T;
   constexpr int XS = ((T == 1 ? E : E * (T + 1)) + (T >= 4 ? 16 : 0)) | 1;  // as in the kernel
   const long blocks = (rows + RPB - 1) / RPB;
@@ -1962,21 +1997,31 @@ hipError_t launch_rows1d_reg_t(const float2 *src, long rows, int Sr, const Rows1
   const size_t lds = (static_cast<size_t>(Sc) + static_cast<size_t>(RPB) * XS) * sizeof(float2);
   const std::string name = "k_rows1d_reg<" + std::to_string(E) + ", " + std::to_string(T) + ">";
   Observe ob(name.c_str(), bytes, flops, st);
-  hipLaunchKernelGGL((k_rows1d_reg<E, T>), dim3(static_cast<unsigned>(blocks)), dim3(256), lds, st, src,
-                     rows, Sr, a, tw, tw_n);
+  if (half)
+    hipLaunchKernelGGL((k_rows1d_reg<E, T, true>), dim3(static_cast<unsigned>(blocks)), dim3(256), lds, st, src,
+                       rows, Sr, a, tw, tw_n);
+  else
+    hipLaunchKernelGGL((k_rows1d_reg<E, T, false>), dim3(static_cast<unsigned>(blocks)), dim3(256), lds, st, src,
+                       rows, Sr, a, tw, tw_n);
   return hipGetLastError();
 }
 
+bool rows1d_half_supported(int Sr, int Sc) {
+  return Sr >= 4 && (Sr & (Sr - 1)) == 0 && (Sc == 4 || Sc == 8 || Sc == 16 || Sc == 32 || Sc == 64 || Sc == 128 || Sc == 256);
+}
+
 hipError_t launch_rows1d(const float2 *src, long nodes, int Sr, int Sc, const Rows1dArgs &a,
-                         const float2 *tw, int tw_n, hipStream_t st) {
+                         const float2 *tw, int tw_n, hipStream_t st, bool half_rows) {
   if (nodes <= 0 || a.n <= 0) return hipSuccess;
+  if (half_rows && !rows1d_half_supported(Sr, Sc)) return hipErrorInvalidValue;
   auto is_pow2 = [](int v) { return v > 0 && (v & (v - 1)) == 0; };
   if (a.n > kRows1dMaxChildren || !is_pow2(Sr) || !is_pow2(Sc) || Sc < 2 || Sc > kTileElems ||
       tw_n % Sc != 0)
     return hipErrorInvalidValue;
   int lgSc = 0;
   while ((1 << lgSc) < Sc) ++lgSc;
-  double bytes = static_cast<double>(nodes) * Sr * Sc * 8, flops = fft_flops(Sc);
+  const long rows_in = nodes * (half_rows ? Sr / 2 + 1 : Sr);  // stored source rows
+  double bytes = static_cast<double>(rows_in) * Sc * 8, flops = fft_flops(Sc) * (half_rows ? 0.5 : 1.0);
   for (int i = 0; i < a.n; ++i) {
     const Rows1dChild &c = a.c[i];
     if (c.filt == nullptr || c.dst == nullptr || c.lg_fold < 0 || c.lg_fold > lgSc ||
@@ -1989,13 +2034,13 @@ hipError_t launch_rows1d(const float2 *src, long nodes, int Sr, int Sc, const Ro
   }
   const double all_flops = static_cast<double>(nodes) * Sr * flops;
   switch (Sc) {
-    case 4: return launch_rows1d_reg_t<4, 1>(src, nodes * Sr, Sr, a, bytes, all_flops, tw, tw_n, st);
-    case 8: return launch_rows1d_reg_t<8, 1>(src, nodes * Sr, Sr, a, bytes, all_flops, tw, tw_n, st);
-    case 16: return launch_rows1d_reg_t<16, 1>(src, nodes * Sr, Sr, a, bytes, all_flops, tw, tw_n, st);
-    case 32: return launch_rows1d_reg_t<16, 2>(src, nodes * Sr, Sr, a, bytes, all_flops, tw, tw_n, st);
-    case 64: return launch_rows1d_reg_t<16, 4>(src, nodes * Sr, Sr, a, bytes, all_flops, tw, tw_n, st);
-    case 128: return launch_rows1d_reg_t<16, 8>(src, nodes * Sr, Sr, a, bytes, all_flops, tw, tw_n, st);
-    case 256: return launch_rows1d_reg_t<16, 16>(src, nodes * Sr, Sr, a, bytes, all_flops, tw, tw_n, st);
+    case 4: return launch_rows1d_reg_t<4, 1>(src, rows_in, Sr, a, bytes, all_flops, tw, tw_n, st, half_rows);
+    case 8: return launch_rows1d_reg_t<8, 1>(src, rows_in, Sr, a, bytes, all_flops, tw, tw_n, st, half_rows);
+    case 16: return launch_rows1d_reg_t<16, 1>(src, rows_in, Sr, a, bytes, all_flops, tw, tw_n, st, half_rows);
+    case 32: return launch_rows1d_reg_t<16, 2>(src, rows_in, Sr, a, bytes, all_flops, tw, tw_n, st, half_rows);
+    case 64: return launch_rows1d_reg_t<16, 4>(src, rows_in, Sr, a, bytes, all_flops, tw, tw_n, st, half_rows);
+    case 128: return launch_rows1d_reg_t<16, 8>(src, rows_in, Sr, a, bytes, all_flops, tw, tw_n, st, half_rows);
+    case 256: return launch_rows1d_reg_t<16, 16>(src, rows_in, Sr, a, bytes, all_flops, tw, tw_n, st, half_rows);
     default: break;
   }
   // other row lengths: spectrum rows and one child's rows side by side in LDS
@@ -2051,22 +2096,26 @@ hipError_t launch_mulfold_invrow(const float2 *src, const float *filt, float2 *d
   return hipGetLastError();
 }
 
-hipError_t launch_col_segs(const float2 *src, float2 *uc, int Mr, const ColSeg *segs, int n, const float2 *tw,
-                           int tw_n, hipStream_t st) {
-  return launch_col_segs_impl(src, uc, Mr, segs, n, tw, tw_n, st);
+hipError_t launch_col_segs(const float2 *src, float2 *uc, int Mr, const ColSeg *segs, int n, bool uc_half,
+                           const float2 *tw, int tw_n, hipStream_t st) {
+  return launch_col_segs_impl(src, uc, Mr, segs, n, uc_half, tw, tw_n, st);
 }
 
 hipError_t launch_col(int mode, const void *src, long nodes, int Mr, int Mc, float2 *uc,
                       int post_tw_m, const float *phi_rows, int m_r, float *w_out, float *out,
                       ChanMap cm, int K, const float2 *tw, int tw_n, hipStream_t st, bool uc_half) {
-  if (uc_half && (mode == 2 || post_tw_m != 0 || Mr < 2)) return hipErrorInvalidValue;
+  if (uc_half && (mode == 2 || Mr < 2)) return hipErrorInvalidValue;
+  // (with the four-step twiddle, half spectra are written by the register kernel only)
+  if (uc_half && post_tw_m != 0 &&
+      !(mode == 1 && (Mr == 32 || Mr == 64 || Mr == 128 || Mr == 256) && Mc >= 4 && w_out == nullptr &&
+        tw_n % Mr == 0 && post_tw_m == Mr * Mc))
+    return hipErrorInvalidValue;
   // register-resident variant: modes 0/1, column length 16*T with T | 16, at least 16
   // columns (4 without a lowpass tail), lowpass length dividing the column length
   if (mode == 2 && Mr == 256 && (Mc == 1 || Mc == 2 || Mc == 4 || Mc == 8 || Mc == 16) && tw_n % Mr == 0 &&
       out != nullptr && cm.G >= 1)
     return launch_col_out(static_cast<const float2 *>(src), nodes, Mc, out, cm, K, tw, tw_n, st);
   if (mode != 2 && (Mc >= 16 || (Mc >= 4 && w_out == nullptr)) && tw_n % Mr == 0 &&
-      (post_tw_m == 0 || !uc_half) &&
       (w_out == nullptr || (m_r >= 1 && m_r <= Mr))) {
     switch (Mr) {
       case 32: return launch_col_fast_t<32>(mode, src, nodes, Mc, uc, uc_half, post_tw_m, phi_rows, m_r, w_out, tw, tw_n, st);

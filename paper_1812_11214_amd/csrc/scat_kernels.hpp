@@ -69,8 +69,10 @@ struct ColSeg {
   int Mc;
   long long src_off, uc_off;
 };
-hipError_t launch_col_segs(const float2 *src, float2 *uc, int Mr, const ColSeg *segs, int n, const float2 *tw,
-                           int tw_n, hipStream_t st);
+// uc_half: the columns are real after the modulus, so only rows 0 .. Mr/2 of every node's
+// spectrum are written ([nodes][Mr/2+1][Mc] at uc + uc_off; launch_rows1d with half_rows reads them)
+hipError_t launch_col_segs(const float2 *src, float2 *uc, int Mr, const ColSeg *segs, int n, bool uc_half,
+                           const float2 *tw, int tw_n, hipStream_t st);
 
 // 1-D cascade: forward row FFT of src [nodes][Sr][Sc] (column spectra, left untouched) and,
 // for each child, filter product + fold of the row by 2^lg_fold + inverse row FFT + four-step
@@ -93,8 +95,12 @@ struct Rows1dArgs {
   int n;
   Rows1dChild c[kRows1dMaxChildren];
 };
+// half_rows: src holds rows 0 .. Sr/2 of every node only ([nodes][Sr/2+1][Sc], written by the
+// column pass with uc_half for real columns); the other rows are derived from them
+// (rows1d_half_supported: the row lengths for which that form exists)
+bool rows1d_half_supported(int Sr, int Sc);
 hipError_t launch_rows1d(const float2 *src, long nodes, int Sr, int Sc, const Rows1dArgs &a,
-                         const float2 *tw, int tw_n, hipStream_t st);
+                         const float2 *tw, int tw_n, hipStream_t st, bool half_rows = false);
 
 // Adjoint of launch_rows1d: dst [nodes][Sr][Sc] (= or +=) the inverse row FFT of
 // sum_c filt_c * tile(forward row FFT of child c), child rows of Sc >> lg_fold points (see
