@@ -113,6 +113,8 @@ def test_config3_512x512_sample():
     # 256 rows: the column passes of several octaves as segments of one launch, narrow octaves
     # (fewer than 16 columns) beside it; first order only; one octave
     (65536, 4, 1, 2), (1 << 17, 9, 1, 2), (65536, 8, 2, 1), (65536, 1, 3, 2),
+    # half spectra between the column and row passes with 128, 64 and 32 rows
+    (32768, 4, 2, 2), (8192, 3, 4, 2), (2048, 3, 1, 2),
 ])
 def test_1d_shapes(n, J, Q, max_order):
     rng = np.random.default_rng(n + J + Q)
