@@ -2252,16 +2252,18 @@ scat_status forward_1d(scat_plan *p, const float *in, float *out, long p0, long 
     for (int j = 0; half && j < J; ++j) half = (N2 >> h.res(j)) >= 4 && scat::rows1d_half_supported(N1, N2 >> h.res(j));
     // column passes (mode 1 with the four-step twiddle) over a list of arrays
     auto cols_pass = [&](const float2 *src, float2 *dst, const std::vector<scat::ColSeg> &all) -> scat_status {
+      // (half spectra: two columns per thread in the merged launch, tiles of 32 columns)
+      const int least = half ? 32 : 16;
       std::vector<scat::ColSeg> together;
       for (const scat::ColSeg &sg : all)
-        if (N1 == 256 && sg.Mc >= 16 && static_cast<int>(together.size()) < scat::kColMaxSegs) together.push_back(sg);
+        if (N1 == 256 && sg.Mc >= least && static_cast<int>(together.size()) < scat::kColMaxSegs) together.push_back(sg);
       const bool merged = together.size() >= 2;
       if (merged)
         SCAT_TRY(scat::launch_col_segs(src, dst, N1, together.data(), static_cast<int>(together.size()), half, tw,
                                        tw_n, st));
       size_t taken = 0;
       for (const scat::ColSeg &sg : all) {
-        if (merged && N1 == 256 && sg.Mc >= 16 && taken < together.size()) {
+        if (merged && N1 == 256 && sg.Mc >= least && taken < together.size()) {
           ++taken;
           continue;
         }

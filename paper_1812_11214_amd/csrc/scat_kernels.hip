@@ -1009,6 +1009,75 @@ __global__ __launch_bounds__(256) void k_col_fast_segs(const float2 *__restrict_
                           MR * Mc, nullptr, 0, nullptr, tw, tw_n);
 }
 
+// The same pass for half spectra with TWO adjacent columns per thread (16-byte loads and
+// stores): both are inverse-transformed, and since their moduli are real they go through ONE
+// forward transform as z = |a| + i |b|; the two spectra are taken apart again with the help of
+// row MR - k (through LDS): A[k] = (Z[k] + conj(Z[-k])) / 2, B[k] = -i (Z[k] - conj(Z[-k])) / 2.
+// Rows 0 .. MR/2 are written, with the four-step twiddle.  Tiles of 2 TC columns (Mc >= 32).
+template <int MR>
+__global__ __launch_bounds__(256) void k_col_pair_segs(const float2 *__restrict__ src,
+                                                       float2 *__restrict__ uc, ColSegsDev sg,
+                                                       const float2 *__restrict__ tw, int tw_n) {
+  constexpr int E = 16, T = MR / E, TC = 256 / T, KS = T * TC + 16;
+  extern __shared__ float2 lds[];
+  int sgi = 0;
+#pragma unroll
+  for (int i = 1; i < kColMaxSegs; ++i)
+    if (i < sg.n && blockIdx.x >= sg.first[i]) sgi = i;
+  sgi = __builtin_amdgcn_readfirstlane(sgi);
+  const int Mc = sg.Mc[sgi];
+  const unsigned blk = blockIdx.x - sg.first[sgi];
+  const int tiles = Mc / (2 * TC);
+  const int node = blk / tiles;
+  const int c0 = (blk % tiles) * (2 * TC);
+  const int cp = threadIdx.x % TC, t = threadIdx.x / TC;
+  const float2 *sp = src + sg.src_off[sgi] + static_cast<size_t>(node) * MR * Mc + t * Mc + c0 + 2 * cp;
+  const int step = T * Mc;
+  float2 wt[E];
+  load_twiddles<E, T>(wt, t, tw, tw_n);
+  float2 va[E], vb[E];
+#pragma unroll
+  for (int i = 0; i < E; ++i) {
+    const float4 x = *reinterpret_cast<const float4 *>(sp + i * step);
+    va[i] = make_float2(x.x, x.y);
+    vb[i] = make_float2(x.z, x.w);
+  }
+  fft_core<E, T, true>(va, t, lds + cp, KS, TC, wt);
+  fft_core<E, T, true>(vb, t, lds + cp, KS, TC, wt);
+#pragma unroll
+  for (int i = 0; i < E; ++i)
+    va[i] = make_float2(__builtin_amdgcn_sqrtf(va[i].x * va[i].x + va[i].y * va[i].y),
+                        __builtin_amdgcn_sqrtf(vb[i].x * vb[i].x + vb[i].y * vb[i].y));
+  fft_core<E, T, false>(va, t, lds + cp, KS, TC, wt);  // ends with a barrier: the area is free
+  // Z by rows for the partners, and behind it the column-dependent factors of the twiddle
+  // exp(-2 pi i i b / (16 Mc)), i < 16, for the tile's 2 TC columns
+  float2 *zt = lds, *ctw = lds + MR * TC;
+#pragma unroll
+  for (int i = 0; i < E; ++i) zt[(t + T * i) * TC + cp] = va[i];
+  const int M = MR * Mc;
+  const int bmask = 16 * Mc - 1, bstep = tw_n / (16 * Mc);
+  for (int idx = threadIdx.x; idx < 16 * 2 * TC; idx += 256) {
+    const int i = idx / (2 * TC), cc = idx - i * (2 * TC);
+    ctw[idx] = tw[((i * (c0 + cc)) & bmask) * bstep];
+  }
+  __syncthreads();
+  const int b0 = c0 + 2 * cp;
+  const int tstep = tw_n / M;
+  const float2 wa0 = tw[((t * b0) & (M - 1)) * tstep], wa1 = tw[((t * (b0 + 1)) & (M - 1)) * tstep];
+  float2 *up = uc + sg.uc_off[sgi] + static_cast<size_t>(node) * (MR / 2 + 1) * Mc + t * Mc + b0;
+#pragma unroll
+  for (int i = 0; i < E; ++i) {
+    const int r = t + T * i;
+    if (r > MR / 2) continue;
+    const float2 zk = va[i], zn = zt[((MR - r) & (MR - 1)) * TC + cp];
+    const float2 a = make_float2(0.5f * (zk.x + zn.x), 0.5f * (zk.y - zn.y));
+    const float2 b = make_float2(0.5f * (zk.y + zn.y), 0.5f * (zn.x - zk.x));
+    const float2 oa = cmul(a, cmul(wa0, ctw[i * (2 * TC) + 2 * cp]));
+    const float2 ob = cmul(b, cmul(wa1, ctw[i * (2 * TC) + 2 * cp + 1]));
+    *reinterpret_cast<float4 *>(up + i * step) = make_float4(oa.x, oa.y, ob.x, ob.y);
+  }
+}
+
 hipError_t launch_col_segs_impl(const float2 *src, float2 *uc, int Mr, const ColSeg *segs, int n, bool uc_half,
                                 const float2 *tw, int tw_n, hipStream_t st) {
   if (Mr != 256 || n < 1 || n > kColMaxSegs || tw_n % Mr != 0) return hipErrorInvalidValue;
@@ -1029,6 +1098,17 @@ hipError_t launch_col_segs_impl(const float2 *src, float2 *uc, int Mr, const Col
     if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
     pts += static_cast<double>(segs[i].nodes) * m;
     cols += static_cast<double>(segs[i].nodes) * segs[i].Mc;
+  }
+  bool pairs = uc_half;
+  for (int i = 0; i < n; ++i) pairs = pairs && segs[i].Mc % (2 * TC) == 0 && segs[i].src_off % 2 == 0 && segs[i].uc_off % 2 == 0;
+  if (pairs) {
+    // two columns per thread: half as many workgroups per segment
+    for (int i = 0; i < n; ++i) sg.first[i] /= 2;
+    const size_t lds_p = (static_cast<size_t>(MR) * TC + 16 * 2 * TC) * sizeof(float2);
+    Observe ob("k_col_pair_segs<256>", pts * 12, cols * 1.5 * fft_flops(MR) + 4.0 * pts, st);
+    hipLaunchKernelGGL((k_col_pair_segs<MR>), dim3(static_cast<unsigned>(blocks / 2)), dim3(256), lds_p, st, src, uc,
+                       sg, tw, tw_n);
+    return hipGetLastError();
   }
   const size_t lds = static_cast<size_t>(E) * (T * TC + 16) * sizeof(float2);
   Observe ob("k_col_fast_segs<256>", pts * (uc_half ? 12 : 16), cols * 2 * fft_flops(MR) + 4.0 * pts, st);
