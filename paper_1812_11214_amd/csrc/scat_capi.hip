@@ -2252,8 +2252,8 @@ scat_status forward_1d(scat_plan *p, const float *in, float *out, long p0, long 
     for (int j = 0; half && j < J; ++j) half = (N2 >> h.res(j)) >= 4 && scat::rows1d_half_supported(N1, N2 >> h.res(j));
     // column passes (mode 1 with the four-step twiddle) over a list of arrays
     auto cols_pass = [&](const float2 *src, float2 *dst, const std::vector<scat::ColSeg> &all) -> scat_status {
-      // (half spectra: two columns per thread in the merged launch, tiles of 32 columns)
-      const int least = half ? 32 : 16;
+      // (half spectra: two columns per thread in the merged launch, which also takes narrow arrays)
+      const int least = half ? 4 : 16;
       std::vector<scat::ColSeg> together;
       for (const scat::ColSeg &sg : all)
         if (N1 == 256 && sg.Mc >= least && static_cast<int>(together.size()) < scat::kColMaxSegs) together.push_back(sg);

@@ -994,6 +994,7 @@ struct ColSegsDev {
   unsigned first[kColMaxSegs];
   int Mc[kColMaxSegs];
   long long src_off[kColMaxSegs], uc_off[kColMaxSegs];  // in elements from the common bases
+  long long nodes[kColMaxSegs];                          // (read by k_col_pair_segs only)
 };
 template <int MR>
 __global__ __launch_bounds__(256) void k_col_fast_segs(const float2 *__restrict__ src,
@@ -1013,12 +1014,15 @@ __global__ __launch_bounds__(256) void k_col_fast_segs(const float2 *__restrict_
 // stores): both are inverse-transformed, and since their moduli are real they go through ONE
 // forward transform as z = |a| + i |b|; the two spectra are taken apart again with the help of
 // row MR - k (through LDS): A[k] = (Z[k] + conj(Z[-k])) / 2, B[k] = -i (Z[k] - conj(Z[-k])) / 2.
-// Rows 0 .. MR/2 are written, with the four-step twiddle.  Tiles of 2 TC columns (Mc >= 32).
+// Rows 0 .. MR/2 are written, with the four-step twiddle.  A tile is TCp = min(16, Mc / 2)
+// column pairs of one node, held by 16 TCp threads; narrow nodes (Mc < 32) are one tile each and
+// 16 / TCp of them share a workgroup, each with an LDS area of its own.
 template <int MR>
 __global__ __launch_bounds__(256) void k_col_pair_segs(const float2 *__restrict__ src,
                                                        float2 *__restrict__ uc, ColSegsDev sg,
                                                        const float2 *__restrict__ tw, int tw_n) {
-  constexpr int E = 16, T = MR / E, TC = 256 / T, KS = T * TC + 16;
+  constexpr int E = 16, T = MR / E;
+  static_assert(T == 16, "256 threads = 16 row lanes x up to 16 column pairs");
   extern __shared__ float2 lds[];
   int sgi = 0;
 #pragma unroll
@@ -1027,10 +1031,28 @@ __global__ __launch_bounds__(256) void k_col_pair_segs(const float2 *__restrict_
   sgi = __builtin_amdgcn_readfirstlane(sgi);
   const int Mc = sg.Mc[sgi];
   const unsigned blk = blockIdx.x - sg.first[sgi];
-  const int tiles = Mc / (2 * TC);
-  const int node = blk / tiles;
-  const int c0 = (blk % tiles) * (2 * TC);
-  const int cp = threadIdx.x % TC, t = threadIdx.x / TC;
+  const int TCp = Mc >= 32 ? 16 : Mc / 2;  // column pairs per tile
+  const int per = T * TCp;                 // threads per tile
+  const int slot = threadIdx.x / per, l = threadIdx.x % per;
+  const int cp = l % TCp, t = l / TCp;
+  long node;
+  int c0;
+  bool valid = true;
+  if (Mc >= 32) {
+    const int tiles = Mc / 32;
+    node = blk / tiles;
+    c0 = (blk % tiles) * 32;
+  } else {
+    const long node_raw = static_cast<long>(blk) * (256 / per) + slot;
+    valid = node_raw < sg.nodes[sgi];
+    node = valid ? node_raw : sg.nodes[sgi] - 1;  // idle tiles redo the last node, unstored
+    c0 = 0;
+  }
+  const int KS = per + 16;
+  // a tile's LDS area: the transforms' exchange (16 KS elements), later Z by rows (MR TCp) and the
+  // twiddle factors (32 TCp)
+  const int SA = 288 * TCp > 256 * TCp + 256 ? 288 * TCp : 256 * TCp + 256;
+  float2 *area = lds + slot * SA;
   const float2 *sp = src + sg.src_off[sgi] + static_cast<size_t>(node) * MR * Mc + t * Mc + c0 + 2 * cp;
   const int step = T * Mc;
   float2 wt[E];
@@ -1042,25 +1064,26 @@ __global__ __launch_bounds__(256) void k_col_pair_segs(const float2 *__restrict_
     va[i] = make_float2(x.x, x.y);
     vb[i] = make_float2(x.z, x.w);
   }
-  fft_core<E, T, true>(va, t, lds + cp, KS, TC, wt);
-  fft_core<E, T, true>(vb, t, lds + cp, KS, TC, wt);
+  fft_core<E, T, true>(va, t, area + cp, KS, TCp, wt);
+  fft_core<E, T, true>(vb, t, area + cp, KS, TCp, wt);
 #pragma unroll
   for (int i = 0; i < E; ++i)
     va[i] = make_float2(__builtin_amdgcn_sqrtf(va[i].x * va[i].x + va[i].y * va[i].y),
                         __builtin_amdgcn_sqrtf(vb[i].x * vb[i].x + vb[i].y * vb[i].y));
-  fft_core<E, T, false>(va, t, lds + cp, KS, TC, wt);  // ends with a barrier: the area is free
+  fft_core<E, T, false>(va, t, area + cp, KS, TCp, wt);  // ends with a barrier: the area is free
   // Z by rows for the partners, and behind it the column-dependent factors of the twiddle
-  // exp(-2 pi i i b / (16 Mc)), i < 16, for the tile's 2 TC columns
-  float2 *zt = lds, *ctw = lds + MR * TC;
+  // exp(-2 pi i i b / (16 Mc)), i < 16, for the tile's 2 TCp columns
+  float2 *zt = area, *ctw = area + MR * TCp;
 #pragma unroll
-  for (int i = 0; i < E; ++i) zt[(t + T * i) * TC + cp] = va[i];
+  for (int i = 0; i < E; ++i) zt[(t + T * i) * TCp + cp] = va[i];
   const int M = MR * Mc;
   const int bmask = 16 * Mc - 1, bstep = tw_n / (16 * Mc);
-  for (int idx = threadIdx.x; idx < 16 * 2 * TC; idx += 256) {
-    const int i = idx / (2 * TC), cc = idx - i * (2 * TC);
+  for (int idx = l; idx < 16 * 2 * TCp; idx += per) {
+    const int i = idx / (2 * TCp), cc = idx - i * (2 * TCp);
     ctw[idx] = tw[((i * (c0 + cc)) & bmask) * bstep];
   }
   __syncthreads();
+  if (!valid) return;
   const int b0 = c0 + 2 * cp;
   const int tstep = tw_n / M;
   const float2 wa0 = tw[((t * b0) & (M - 1)) * tstep], wa1 = tw[((t * (b0 + 1)) & (M - 1)) * tstep];
@@ -1069,11 +1092,11 @@ __global__ __launch_bounds__(256) void k_col_pair_segs(const float2 *__restrict_
   for (int i = 0; i < E; ++i) {
     const int r = t + T * i;
     if (r > MR / 2) continue;
-    const float2 zk = va[i], zn = zt[((MR - r) & (MR - 1)) * TC + cp];
+    const float2 zk = va[i], zn = zt[((MR - r) & (MR - 1)) * TCp + cp];
     const float2 a = make_float2(0.5f * (zk.x + zn.x), 0.5f * (zk.y - zn.y));
     const float2 b = make_float2(0.5f * (zk.y + zn.y), 0.5f * (zn.x - zk.x));
-    const float2 oa = cmul(a, cmul(wa0, ctw[i * (2 * TC) + 2 * cp]));
-    const float2 ob = cmul(b, cmul(wa1, ctw[i * (2 * TC) + 2 * cp + 1]));
+    const float2 oa = cmul(a, cmul(wa0, ctw[i * (2 * TCp) + 2 * cp]));
+    const float2 ob = cmul(b, cmul(wa1, ctw[i * (2 * TCp) + 2 * cp + 1]));
     *reinterpret_cast<float4 *>(up + i * step) = make_float4(oa.x, oa.y, ob.x, ob.y);
   }
 }
@@ -1086,6 +1109,34 @@ hipError_t launch_col_segs_impl(const float2 *src, float2 *uc, int Mr, const Col
   sg.n = n;
   long blocks = 0;
   double pts = 0.0, cols = 0.0;
+  bool pairs = uc_half;
+  for (int i = 0; i < n; ++i)
+    pairs = pairs && segs[i].Mc >= 4 && (segs[i].Mc & (segs[i].Mc - 1)) == 0 && segs[i].src_off % 2 == 0 &&
+            segs[i].uc_off % 2 == 0;
+  if (pairs) {
+    // two adjacent columns per thread; narrow nodes share a workgroup
+    size_t lds_p = 0;
+    for (int i = 0; i < n; ++i) {
+      const long long m = static_cast<long long>(MR) * segs[i].Mc;
+      if (segs[i].nodes < 1 || tw_n % m != 0) return hipErrorInvalidValue;
+      const int TCp = segs[i].Mc >= 32 ? 16 : segs[i].Mc / 2, NS = 16 / TCp;
+      const size_t SA = static_cast<size_t>(std::max(288 * TCp, 256 * TCp + 256));
+      lds_p = std::max(lds_p, NS * SA * sizeof(float2));
+      sg.first[i] = static_cast<unsigned>(blocks);
+      sg.Mc[i] = segs[i].Mc;
+      sg.src_off[i] = segs[i].src_off;
+      sg.uc_off[i] = segs[i].uc_off;
+      sg.nodes[i] = segs[i].nodes;
+      blocks += segs[i].Mc >= 32 ? segs[i].nodes * (segs[i].Mc / 32) : (segs[i].nodes + NS - 1) / NS;
+      if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
+      pts += static_cast<double>(segs[i].nodes) * m;
+      cols += static_cast<double>(segs[i].nodes) * segs[i].Mc;
+    }
+    Observe ob("k_col_pair_segs<256>", pts * 12, cols * 1.5 * fft_flops(MR) + 4.0 * pts, st);
+    hipLaunchKernelGGL((k_col_pair_segs<MR>), dim3(static_cast<unsigned>(blocks)), dim3(256), lds_p, st, src, uc, sg,
+                       tw, tw_n);
+    return hipGetLastError();
+  }
   for (int i = 0; i < n; ++i) {
     const long long m = static_cast<long long>(MR) * segs[i].Mc;
     if (segs[i].nodes < 1 || segs[i].Mc < TC || segs[i].Mc % TC != 0 || tw_n % m != 0 || (m & (m - 1)) != 0)
@@ -1098,17 +1149,6 @@ hipError_t launch_col_segs_impl(const float2 *src, float2 *uc, int Mr, const Col
     if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
     pts += static_cast<double>(segs[i].nodes) * m;
     cols += static_cast<double>(segs[i].nodes) * segs[i].Mc;
-  }
-  bool pairs = uc_half;
-  for (int i = 0; i < n; ++i) pairs = pairs && segs[i].Mc % (2 * TC) == 0 && segs[i].src_off % 2 == 0 && segs[i].uc_off % 2 == 0;
-  if (pairs) {
-    // two columns per thread: half as many workgroups per segment
-    for (int i = 0; i < n; ++i) sg.first[i] /= 2;
-    const size_t lds_p = (static_cast<size_t>(MR) * TC + 16 * 2 * TC) * sizeof(float2);
-    Observe ob("k_col_pair_segs<256>", pts * 12, cols * 1.5 * fft_flops(MR) + 4.0 * pts, st);
-    hipLaunchKernelGGL((k_col_pair_segs<MR>), dim3(static_cast<unsigned>(blocks / 2)), dim3(256), lds_p, st, src, uc,
-                       sg, tw, tw_n);
-    return hipGetLastError();
   }
   const size_t lds = static_cast<size_t>(E) * (T * TC + 16) * sizeof(float2);
   Observe ob("k_col_fast_segs<256>", pts * (uc_half ? 12 : 16), cols * 2 * fft_flops(MR) + 4.0 * pts, st);
