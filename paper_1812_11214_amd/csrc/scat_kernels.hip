@@ -1202,6 +1202,71 @@ hipError_t launch_col_out(const float2 *src, long nodes, int Mc, float *out, Cha
   return hipGetLastError();
 }
 
+// Mode 1 for nodes without children (no spectrum output, lowpass length 32) with TWO adjacent
+// columns per thread: 16-byte loads, both columns inverse-transformed, and their two real
+// moduli sent through the forward transform and the whole (linear, real-filter) lowpass tail as
+// ONE complex signal z = |a| + i |b|: the real part of the result is column a's lowpassed
+// column, the imaginary part column b's.  Tiles of 2 TC columns, TC = 256 / T.
+template <int MR>
+__global__ __launch_bounds__(256) void k_col_pair_low(const float2 *__restrict__ src, int Mc, int TC,
+                                                      const float *__restrict__ phi_rows,
+                                                      float *__restrict__ w_out,
+                                                      const float2 *__restrict__ tw, int tw_n) {
+  constexpr int E = 16, T = MR / E, LM = 32;
+  static_assert(T >= 4 && T <= 16, "64 to 256 rows");
+  extern __shared__ float2 lds[];
+  const int KS = T * TC + 16;
+  const int cp = threadIdx.x % TC, t = threadIdx.x / TC;
+  const int tiles = Mc / (2 * TC);
+  const int node = blockIdx.x / tiles;
+  const int c0 = (blockIdx.x % tiles) * (2 * TC);
+  const float2 *sp = src + static_cast<size_t>(node) * MR * Mc + t * Mc + c0 + 2 * cp;
+  const int step = T * Mc;
+  float2 wt[E];
+  load_twiddles<E, T>(wt, t, tw, tw_n);
+  float2 va[E], vb[E];
+#pragma unroll
+  for (int i = 0; i < E; ++i) {
+    const float4 x = *reinterpret_cast<const float4 *>(sp + i * step);
+    va[i] = make_float2(x.x, x.y);
+    vb[i] = make_float2(x.z, x.w);
+  }
+  fft_core<E, T, true>(va, t, lds + cp, KS, TC, wt);
+  fft_core<E, T, true>(vb, t, lds + cp, KS, TC, wt);
+#pragma unroll
+  for (int i = 0; i < E; ++i)
+    va[i] = make_float2(__builtin_amdgcn_sqrtf(va[i].x * va[i].x + va[i].y * va[i].y),
+                        __builtin_amdgcn_sqrtf(vb[i].x * vb[i].x + vb[i].y * vb[i].y));
+  fft_core<E, T, false>(va, t, lds + cp, KS, TC, wt);
+  // fold in registers: row t + T i lands on lowpass frequency t + T (i mod JT)
+  constexpr int JT = LM / T;
+  float2 fm[JT];
+#pragma unroll
+  for (int j = 0; j < JT; ++j) fm[j] = make_float2(0.f, 0.f);
+  const float *ph = phi_rows + t;
+#pragma unroll
+  for (int i = 0; i < E; ++i) {
+    const float f = ph[T * i];
+    fm[i % JT].x += va[i].x * f;
+    fm[i % JT].y += va[i].y * f;
+  }
+#pragma unroll
+  for (int j = 0; j < JT; ++j) lds[(t + T * j) * TC + cp] = fm[j];
+  __syncthreads();
+  if (static_cast<int>(threadIdx.x) < 4 * TC) {
+    // 4 lanes per column pair, 8 points each
+    const int tp = threadIdx.x & 3, cc = threadIdx.x >> 2;
+    float2 y[8], w2[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) y[i] = lds[(tp + 4 * i) * TC + cc];
+    load_twiddles<8, 4>(w2, tp, tw, tw_n);
+    fft_core<8, 4, true, true>(y, tp, lds + LM * TC + cc * 48, 5, 1, w2);
+    float *wp = w_out + static_cast<size_t>(node) * LM * Mc + c0 + 2 * cc;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) *reinterpret_cast<float2 *>(wp + (tp + 4 * i) * Mc) = y[i];
+  }
+}
+
 template <int MR>
 hipError_t launch_col_fast_t(int mode, const void *src, long nodes, int Mc, float2 *uc, bool uc_half,
                              int post_tw_m, const float *phi_rows, int m_r, float *w_out,
@@ -1218,6 +1283,28 @@ hipError_t launch_col_fast_t(int mode, const void *src, long nodes, int Mc, floa
   // lowpass tail variant: registers when the lowpass length is 32 or 8 and a multiple of T
   const int lm = (w_out && m_r == 32 && T <= 32 && tw_n >= 32) ? 32 : (w_out && m_r == 8 && T <= 8) ? 8 : 0;
   const int lm_t = (lm == 8 && MR > 128) ? 0 : lm;  // the template argument actually used
+  if constexpr (E == 16 && T >= 4) {
+    if (mode == 1 && uc == nullptr && lm == 32 && post_tw_m == 0 && Mc % (2 * TC) == 0 && T * TC == 256) {
+      // leaves: two columns per thread (see k_col_pair_low)
+      const long blocks2 = nodes * (Mc / (2 * TC));
+      if (blocks2 <= 0 || blocks2 > 0x7fffffffL) return hipErrorInvalidValue;
+      size_t words2 = static_cast<size_t>(E) * (T * TC + 16);
+      if (static_cast<size_t>(80) * TC > words2) words2 = static_cast<size_t>(80) * TC;
+      const size_t lds2 = words2 * sizeof(float2);
+      const std::string name2 = "k_col_pair_low<" + std::to_string(MR) + ">";
+      const double pts2 = static_cast<double>(nodes) * MR * Mc, cols2 = static_cast<double>(nodes) * Mc;
+      Observe ob(name2.c_str(), pts2 * 8 + cols2 * m_r * 4 + MR * 4.0,
+                 cols2 * (1.5 * fft_flops(MR) + fft_flops(m_r) + 2.0 * MR) + 4.0 * pts2, st);
+      static unsigned long long lds_ok2 = 0;
+      if (lds2 > 65536) {
+        hipError_t e = allow_large_lds(reinterpret_cast<const void *>(k_col_pair_low<MR>), lds_ok2);
+        if (e != hipSuccess) return e;
+      }
+      hipLaunchKernelGGL((k_col_pair_low<MR>), dim3(static_cast<unsigned>(blocks2)), dim3(256), lds2, st,
+                         static_cast<const float2 *>(src), Mc, TC, phi_rows, w_out, tw, tw_n);
+      return hipGetLastError();
+    }
+  }
   size_t words = static_cast<size_t>(E) * (T * TC + 16);
   if (lm_t == 0 && w_out) words += static_cast<size_t>(m_r) * TC;  // the generic tail's own area
   if (lm_t == 32 && static_cast<size_t>(80) * TC > words) words = static_cast<size_t>(80) * TC;
