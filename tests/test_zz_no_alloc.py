@@ -70,6 +70,16 @@ def test_static_second_plan_smaller_shape_and_1d():
         x1 = torch.from_numpy(rng.standard_normal((3, 4096)).astype(np.float32)).cuda()
         r, g = _both(one_d, x1, torch)
         _check(r, g)
+        # the 1-D workload's shape: one signal per pass through the static buffer (merged column
+        # passes, half spectra), three signals
+        long_1d = scat.Scattering((65536,), 6, 8)
+        try:
+            assert long_1d.workspace_bytes(1) <= binding.SCAT_STATIC_SCRATCH_MB << 20 < long_1d.workspace_bytes(3)
+            x2 = torch.from_numpy(workloads.planes(4, 3)).cuda()
+            r, g = _both(long_1d, x2, torch)
+            _check(r, g)
+        finally:
+            long_1d.close()
     finally:
         big.close()
         small.close()
