@@ -2337,8 +2337,11 @@ scat_status forward_1d(scat_plan *p, const float *in, float *out, long p0, long 
     SCAT_TRY(scat::launch_mulfold_invrow(XH, tab + p->psi1_off[j1], t1, pc, Q, N1, N2, 0, r1, M1,
                                          tw, tw_n, st, m1));
     if (!kids) continue;
+    // (half spectra between the two passes where the shapes allow it, as in the plain pass)
+    const bool half_t = (N1 == 32 || N1 == 64 || N1 == 128 || N1 == 256) && Mc1 >= 4 &&
+                        scat::rows1d_half_supported(N1, Mc1);
     SCAT_TRY(scat::launch_col(1, t1, pc * Q, N1, Mc1, U, M1, nullptr, 0, nullptr, nullptr, none, K,
-                              tw, tw_n, st));
+                              tw, tw_n, st, half_t));
     scat::Rows1dArgs ch;
     ch.n = 0;
     for (int j2 = j1 + 1; j2 < J; ++j2) {
@@ -2346,7 +2349,7 @@ scat_status forward_1d(scat_plan *p, const float *in, float *out, long p0, long 
       ch.c[ch.n++] = scat::Rows1dChild{tab + p->psi2_off[{r1, j2}], tape->base + tape->y2_off.at({j1, j2}) * pc,
                                        r2 - r1, N >> r2, ChanMap{1, 1, 0, 0}, 0};
     }
-    SCAT_TRY(scat::launch_rows1d(U, pc * Q, N1, Mc1, ch, tw, tw_n, st));
+    SCAT_TRY(scat::launch_rows1d(U, pc * Q, N1, Mc1, ch, tw, tw_n, st, half_t));
   }
   return SCAT_OK;
 }
