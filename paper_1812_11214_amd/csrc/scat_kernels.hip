@@ -1018,7 +1018,7 @@ __global__ __launch_bounds__(256) void k_col_fast_segs(const float2 *__restrict_
 // column pairs of one node, held by 16 TCp threads; narrow nodes (Mc < 32) are one tile each and
 // 16 / TCp of them share a workgroup, each with an LDS area of its own.
 template <int MR>
-__global__ __launch_bounds__(256) void k_col_pair_segs(const float2 *__restrict__ src,
+__global__ __launch_bounds__(256, 4) void k_col_pair_segs(const float2 *__restrict__ src,
                                                        float2 *__restrict__ uc, ColSegsDev sg,
                                                        const float2 *__restrict__ tw, int tw_n) {
   constexpr int E = 16, T = MR / E;
@@ -1053,10 +1053,13 @@ __global__ __launch_bounds__(256) void k_col_pair_segs(const float2 *__restrict_
   // twiddle factors (32 TCp)
   const int SA = 288 * TCp > 256 * TCp + 256 ? 288 * TCp : 256 * TCp + 256;
   float2 *area = lds + slot * SA;
+  // the transforms' twiddles exp(-2 pi i t k / MR) as a table in LDS, [k T + t], behind the tiles'
+  // areas (three transforms would otherwise hold sixteen of them in registers throughout)
+  float2 *wtab = lds + (256 / per) * SA;
+  for (int idx = threadIdx.x; idx < MR; idx += 256) wtab[idx] = tw[(idx / T) * (idx % T) * (tw_n / MR)];
+  __syncthreads();
   const float2 *sp = src + sg.src_off[sgi] + static_cast<size_t>(node) * MR * Mc + t * Mc + c0 + 2 * cp;
   const int step = T * Mc;
-  float2 wt[E];
-  load_twiddles<E, T>(wt, t, tw, tw_n);
   float2 va[E], vb[E];
 #pragma unroll
   for (int i = 0; i < E; ++i) {
@@ -1064,13 +1067,13 @@ __global__ __launch_bounds__(256) void k_col_pair_segs(const float2 *__restrict_
     va[i] = make_float2(x.x, x.y);
     vb[i] = make_float2(x.z, x.w);
   }
-  fft_core<E, T, true>(va, t, area + cp, KS, TCp, wt);
-  fft_core<E, T, true>(vb, t, area + cp, KS, TCp, wt);
+  fft_core_tab<E, T, true>(va, t, area + cp, KS, TCp, wtab + t, T);
+  fft_core_tab<E, T, true>(vb, t, area + cp, KS, TCp, wtab + t, T);
 #pragma unroll
   for (int i = 0; i < E; ++i)
     va[i] = make_float2(__builtin_amdgcn_sqrtf(va[i].x * va[i].x + va[i].y * va[i].y),
                         __builtin_amdgcn_sqrtf(vb[i].x * vb[i].x + vb[i].y * vb[i].y));
-  fft_core<E, T, false>(va, t, area + cp, KS, TCp, wt);  // ends with a barrier: the area is free
+  fft_core_tab<E, T, false>(va, t, area + cp, KS, TCp, wtab + t, T);  // ends with a barrier: the area is free
   // Z by rows for the partners, and behind it the column-dependent factors of the twiddle
   // exp(-2 pi i i b / (16 Mc)), i < 16, for the tile's 2 TCp columns
   float2 *zt = area, *ctw = area + MR * TCp;
@@ -1121,7 +1124,7 @@ hipError_t launch_col_segs_impl(const float2 *src, float2 *uc, int Mr, const Col
       if (segs[i].nodes < 1 || tw_n % m != 0) return hipErrorInvalidValue;
       const int TCp = segs[i].Mc >= 32 ? 16 : segs[i].Mc / 2, NS = 16 / TCp;
       const size_t SA = static_cast<size_t>(std::max(288 * TCp, 256 * TCp + 256));
-      lds_p = std::max(lds_p, NS * SA * sizeof(float2));
+      lds_p = std::max(lds_p, (NS * SA + MR) * sizeof(float2));
       sg.first[i] = static_cast<unsigned>(blocks);
       sg.Mc[i] = segs[i].Mc;
       sg.src_off[i] = segs[i].src_off;
@@ -1208,8 +1211,8 @@ hipError_t launch_col_out(const float2 *src, long nodes, int Mc, float *out, Cha
 // ONE complex signal z = |a| + i |b|: the real part of the result is column a's lowpassed
 // column, the imaginary part column b's.  Tiles of 2 TC columns, TC = 256 / T.
 template <int MR>
-__global__ __launch_bounds__(256) void k_col_pair_low(const float2 *__restrict__ src, int Mc, int TC,
-                                                      const float *__restrict__ phi_rows,
+__global__ __launch_bounds__(256, 4) void k_col_pair_low(const float2 *__restrict__ src, int Mc, int TC,
+                                                      int wtab_off, const float *__restrict__ phi_rows,
                                                       float *__restrict__ w_out,
                                                       const float2 *__restrict__ tw, int tw_n) {
   constexpr int E = 16, T = MR / E, LM = 32;
@@ -1222,8 +1225,10 @@ __global__ __launch_bounds__(256) void k_col_pair_low(const float2 *__restrict__
   const int c0 = (blockIdx.x % tiles) * (2 * TC);
   const float2 *sp = src + static_cast<size_t>(node) * MR * Mc + t * Mc + c0 + 2 * cp;
   const int step = T * Mc;
-  float2 wt[E];
-  load_twiddles<E, T>(wt, t, tw, tw_n);
+  // (the transforms' twiddles as a table in LDS behind the exchange area, [k T + t])
+  float2 *wtab = lds + wtab_off;
+  for (int idx = threadIdx.x; idx < MR; idx += 256) wtab[idx] = tw[(idx / T) * (idx % T) * (tw_n / MR)];
+  __syncthreads();
   float2 va[E], vb[E];
 #pragma unroll
   for (int i = 0; i < E; ++i) {
@@ -1231,13 +1236,13 @@ __global__ __launch_bounds__(256) void k_col_pair_low(const float2 *__restrict__
     va[i] = make_float2(x.x, x.y);
     vb[i] = make_float2(x.z, x.w);
   }
-  fft_core<E, T, true>(va, t, lds + cp, KS, TC, wt);
-  fft_core<E, T, true>(vb, t, lds + cp, KS, TC, wt);
+  fft_core_tab<E, T, true>(va, t, lds + cp, KS, TC, wtab + t, T);
+  fft_core_tab<E, T, true>(vb, t, lds + cp, KS, TC, wtab + t, T);
 #pragma unroll
   for (int i = 0; i < E; ++i)
     va[i] = make_float2(__builtin_amdgcn_sqrtf(va[i].x * va[i].x + va[i].y * va[i].y),
                         __builtin_amdgcn_sqrtf(vb[i].x * vb[i].x + vb[i].y * vb[i].y));
-  fft_core<E, T, false>(va, t, lds + cp, KS, TC, wt);
+  fft_core_tab<E, T, false>(va, t, lds + cp, KS, TC, wtab + t, T);
   // fold in registers: row t + T i lands on lowpass frequency t + T (i mod JT)
   constexpr int JT = LM / T;
   float2 fm[JT];
@@ -1290,7 +1295,7 @@ hipError_t launch_col_fast_t(int mode, const void *src, long nodes, int Mc, floa
       if (blocks2 <= 0 || blocks2 > 0x7fffffffL) return hipErrorInvalidValue;
       size_t words2 = static_cast<size_t>(E) * (T * TC + 16);
       if (static_cast<size_t>(80) * TC > words2) words2 = static_cast<size_t>(80) * TC;
-      const size_t lds2 = words2 * sizeof(float2);
+      const size_t lds2 = (words2 + MR) * sizeof(float2);  // + the twiddle table
       const std::string name2 = "k_col_pair_low<" + std::to_string(MR) + ">";
       const double pts2 = static_cast<double>(nodes) * MR * Mc, cols2 = static_cast<double>(nodes) * Mc;
       Observe ob(name2.c_str(), pts2 * 8 + cols2 * m_r * 4 + MR * 4.0,
@@ -1301,7 +1306,8 @@ hipError_t launch_col_fast_t(int mode, const void *src, long nodes, int Mc, floa
         if (e != hipSuccess) return e;
       }
       hipLaunchKernelGGL((k_col_pair_low<MR>), dim3(static_cast<unsigned>(blocks2)), dim3(256), lds2, st,
-                         static_cast<const float2 *>(src), Mc, TC, phi_rows, w_out, tw, tw_n);
+                         static_cast<const float2 *>(src), Mc, TC, static_cast<int>(words2), phi_rows, w_out, tw,
+                         tw_n);
       return hipGetLastError();
     }
   }
