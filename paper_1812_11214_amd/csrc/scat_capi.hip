@@ -228,15 +228,10 @@ size_t t_elems_1d(const scat::HostPlan &h, size_t n) {
 
 // 1-D forward pass (no tape): elements per signal of the second-order row-pass outputs, kept
 // for ALL parent octaves and grouped by child octave j2 (j2 * Q signals of n >> res(j2)
-// elements each), and of the largest such group (the column pass's output buffer V).
-size_t kids_elems_1d(const scat::HostPlan &h, size_t n, size_t *largest) {
-  size_t all = 0, most = 0;
-  for (int j2 = 1; h.max_order == 2 && j2 < h.J; ++j2) {
-    const size_t g = static_cast<size_t>(j2) * h.LQ * (n >> h.res(j2));
-    all += g;
-    most = std::max(most, g);
-  }
-  if (largest) *largest = most;
+// elements each).
+size_t kids_elems_1d(const scat::HostPlan &h, size_t n) {
+  size_t all = 0;
+  for (int j2 = 1; h.max_order == 2 && j2 < h.J; ++j2) all += static_cast<size_t>(j2) * h.LQ * (n >> h.res(j2));
   return all;
 }
 
@@ -314,7 +309,7 @@ Layout make_layout(const scat_plan &p, long batch, size_t budget = 0) {
     L.xh = n * c8;
     // t: the first-order row-pass outputs of all octaves, then the second-order ones grouped
     // by child octave; u, v: their column spectra, laid out alike
-    const size_t kids = kids_elems_1d(h, n, nullptr);
+    const size_t kids = kids_elems_1d(h, n);
     size_t first = 0;
     for (int j = 0; j < h.J; ++j) first += q * (n >> h.res(j));
     L.t = (first + kids) * c8;
