@@ -2220,8 +2220,10 @@ scat_status forward_1d(scat_plan *p, const float *in, float *out, long p0, long 
     }
     SCAT_TRY(scat::launch_mulfold_invrow(XH, tab + p->phi_off[0], TL0, pc, 1, N1, N2, 0, rJ, m_out,
                                          tw, tw_n, st, m0));
-    SCAT_TRY(scat::launch_col(2, TL0, pc, N1, mc_out, nullptr, 0, nullptr, 0, nullptr, o,
-                              ChanMap{1, 1, 0, 0}, K, tw, tw_n, st));
+    // (its column pass: with the other channels' at the end where that launch takes it along)
+    if (!(K > 1 && scat::col_out_tail_supported(N1, mc_out, tw_n)))
+      SCAT_TRY(scat::launch_col(2, TL0, pc, N1, mc_out, nullptr, 0, nullptr, 0, nullptr, o,
+                                ChanMap{1, 1, 0, 0}, K, tw, tw_n, st));
   }
   if (tape == nullptr) {
     // Plain forward pass, breadth first: the row passes of all first-order octaves, ONE column
@@ -2309,9 +2311,14 @@ scat_status forward_1d(scat_plan *p, const float *in, float *out, long p0, long 
         SCAT_TRY(scat::launch_rows1d(V + t2_off[j2] * pc, pc * j2 * Q, N1, N2 >> r2, lc, tw, tw_n, st, half));
       }
     }
-    if (K > 1)
-      SCAT_TRY(scat::launch_col(2, TL, pc * (K - 1), N1, mc_out, nullptr, 0, nullptr, 0, nullptr, o,
-                                ChanMap{K - 1, K - 1, 0, 1}, K, tw, tw_n, st));
+    if (K > 1) {
+      if (scat::col_out_tail_supported(N1, mc_out, tw_n))
+        SCAT_TRY(scat::launch_col_out_tail(TL, pc * (K - 1), pc, mc_out, o, ChanMap{K - 1, K - 1, 0, 1}, K, tw, tw_n,
+                                           st));
+      else
+        SCAT_TRY(scat::launch_col(2, TL, pc * (K - 1), N1, mc_out, nullptr, 0, nullptr, 0, nullptr, o,
+                                  ChanMap{K - 1, K - 1, 0, 1}, K, tw, tw_n, st));
+    }
     return SCAT_OK;
   }
   // Taped pass: every node is taped as its row pass leaves it, before the inverse column

@@ -1165,8 +1165,10 @@ hipError_t launch_col_segs_impl(const float2 *src, float2 *uc, int Mr, const Col
 // and TC <= 16 columns, 16 TC threads per node (thread = column c, rows t + 16 i), 16 / TC
 // nodes per workgroup.  src [nodes][MR][TC] complex; out[(p K + channel(g)) MR TC + row TC + c].
 template <int MR>
+// Nodes from `tail_from` on are channel 0 of signal node - tail_from (the order-0 coefficient,
+// whose rows are stored behind the others').
 __global__ __launch_bounds__(256) void k_col_out(const float2 *__restrict__ src, long nodes, int TC,
-                                                 float *__restrict__ out, ChanMap cm, int K,
+                                                 float *__restrict__ out, ChanMap cm, int K, long tail_from,
                                                  const float2 *__restrict__ tw, int tw_n) {
   constexpr int E = 16, T = MR / E;
   extern __shared__ float2 lds[];
@@ -1184,15 +1186,20 @@ __global__ __launch_bounds__(256) void k_col_out(const float2 *__restrict__ src,
   for (int i = 0; i < E; ++i) v[i] = sp[i * per];
   fft_core<E, T, true>(v, t, lds + slot * E * KS + c, KS, TC, wt);
   if (!valid) return;
-  const long p = node / cm.G;
-  const int g = static_cast<int>(node - p * cm.G);
-  float *op = out + (static_cast<size_t>(p) * K + chan_of(cm, g)) * MR * TC + t * TC + c;
+  long p = node / cm.G;
+  int chan = chan_of(cm, static_cast<int>(node - p * cm.G));
+  if (node >= tail_from) {
+    p = node - tail_from;
+    chan = 0;
+  }
+  float *op = out + (static_cast<size_t>(p) * K + chan) * MR * TC + t * TC + c;
 #pragma unroll
   for (int i = 0; i < E; ++i) op[i * per] = v[i].x;
 }
 
 hipError_t launch_col_out(const float2 *src, long nodes, int Mc, float *out, ChanMap cm, int K,
-                          const float2 *tw, int tw_n, hipStream_t st) {
+                          const float2 *tw, int tw_n, hipStream_t st, long tail_from = -1) {
+  if (tail_from < 0) tail_from = nodes;
   constexpr int MR = 256, E = 16, T = MR / E;
   const int per = T * Mc;
   const long blocks = (nodes + 256 / per - 1) / (256 / per);
@@ -1201,7 +1208,7 @@ hipError_t launch_col_out(const float2 *src, long nodes, int Mc, float *out, Cha
   const double pts = static_cast<double>(nodes) * MR * Mc;
   Observe ob("k_col_out<256>", pts * 12, static_cast<double>(nodes) * Mc * fft_flops(MR), st);
   hipLaunchKernelGGL((k_col_out<MR>), dim3(static_cast<unsigned>(blocks)), dim3(256), lds, st, src, nodes, Mc, out,
-                     cm, K, tw, tw_n);
+                     cm, K, tail_from, tw, tw_n);
   return hipGetLastError();
 }
 
@@ -2307,6 +2314,16 @@ hipError_t launch_mulfold_invrow(const float2 *src, const float *filt, float2 *d
   hipLaunchKernelGGL(k_mulfold_invrow, dim3(static_cast<unsigned>(blocks)), dim3(kThreads), lds, st,
                      src, filt, dst, F, Sr, Sc, fr, fc, RB, post_tw_m, tw, tw_n);
   return hipGetLastError();
+}
+
+bool col_out_tail_supported(int Mr, int Mc, int tw_n) {
+  return Mr == 256 && (Mc == 1 || Mc == 2 || Mc == 4 || Mc == 8 || Mc == 16) && tw_n % Mr == 0;
+}
+
+hipError_t launch_col_out_tail(const float2 *src, long nodes, long tail_nodes, int Mc, float *out, ChanMap cm, int K,
+                               const float2 *tw, int tw_n, hipStream_t st) {
+  if (!col_out_tail_supported(256, Mc, tw_n) || out == nullptr || cm.G < 1) return hipErrorInvalidValue;
+  return launch_col_out(src, nodes + tail_nodes, Mc, out, cm, K, tw, tw_n, st, nodes);
 }
 
 hipError_t launch_col_segs(const float2 *src, float2 *uc, int Mr, const ColSeg *segs, int n, bool uc_half,

@@ -74,6 +74,12 @@ struct ColSeg {
 hipError_t launch_col_segs(const float2 *src, float2 *uc, int Mr, const ColSeg *segs, int n, bool uc_half,
                            const float2 *tw, int tw_n, hipStream_t st);
 
+// launch_col mode 2 for 256-row nodes of Mc <= 16 columns, over `nodes` nodes mapped by cm and,
+// stored right behind them, `tail_nodes` nodes that are channel 0 of signals 0, 1, ...
+bool col_out_tail_supported(int Mr, int Mc, int tw_n);
+hipError_t launch_col_out_tail(const float2 *src, long nodes, long tail_nodes, int Mc, float *out, ChanMap cm, int K,
+                               const float2 *tw, int tw_n, hipStream_t st);
+
 // 1-D cascade: forward row FFT of src [nodes][Sr][Sc] (column spectra, left untouched) and,
 // for each child, filter product + fold of the row by 2^lg_fold + inverse row FFT + four-step
 // twiddle, stored to the child's dst [nodes][Sr][Sc >> lg_fold] (see k_rows1d).
