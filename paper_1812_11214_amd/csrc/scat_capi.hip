@@ -2210,16 +2210,27 @@ scat_status forward_1d(scat_plan *p, const float *in, float *out, long p0, long 
 
   SCAT_TRY(scat::launch_col(0, x, pc, N1, N2, XH, N, nullptr, 0, nullptr, nullptr, none, K, tw,
                             tw_n, st));
-  SCAT_TRY(scat::launch_row_fwd(XH, pc * N1, N2, tw, tw_n, st));
+  // the row transform of x's column spectra: alone, or (plain pass, row lengths the register
+  // row kernel takes) by that kernel in place, with the lowpass of S0 as its one child
+  const bool s0_rides = lp && scat::rows1d_half_supported(N1, N2);
+  if (s0_rides) {
+    scat::Rows1dArgs xa;
+    xa.n = 1;
+    xa.c[0] = scat::Rows1dChild{tab + p->phi_off[0], TL0, rJ, m_out, ChanMap{1, 1, 0, 0}, 0};
+    xa.spec_out = XH;
+    SCAT_TRY(scat::launch_rows1d(XH, pc, N1, N2, xa, tw, tw_n, st));
+  } else {
+    SCAT_TRY(scat::launch_row_fwd(XH, pc * N1, N2, tw, tw_n, st));
+  }
   // S0
   if (lp) {
-    const unsigned long long *m0 = nullptr;
-    {
+    if (!s0_rides) {
+      const unsigned long long *m0 = nullptr;
       auto it = p->mask64_off.find({-1, J});
       if (p->d_masks64 != nullptr && it != p->mask64_off.end() && rJ == J) m0 = p->d_masks64 + it->second;
+      SCAT_TRY(scat::launch_mulfold_invrow(XH, tab + p->phi_off[0], TL0, pc, 1, N1, N2, 0, rJ, m_out,
+                                           tw, tw_n, st, m0));
     }
-    SCAT_TRY(scat::launch_mulfold_invrow(XH, tab + p->phi_off[0], TL0, pc, 1, N1, N2, 0, rJ, m_out,
-                                         tw, tw_n, st, m0));
     // (its column pass: with the other channels' at the end where that launch takes it along)
     if (!(K > 1 && scat::col_out_tail_supported(N1, mc_out, tw_n)))
       SCAT_TRY(scat::launch_col(2, TL0, pc, N1, mc_out, nullptr, 0, nullptr, 0, nullptr, o,

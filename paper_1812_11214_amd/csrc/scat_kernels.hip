@@ -666,6 +666,11 @@ __global__ __launch_bounds__(256, 4) void k_rows1d_reg(const float2 *__restrict_
 #pragma unroll
     for (int k = 0; k < E; ++k) wt[k] = twl[t * k];
     fft_core<E, T, false, true>(v, t, slot, T + 1, 1, wt);
+    if (!HALF && a.spec_out != nullptr && valid) {
+      float2 *op = a.spec_out + static_cast<size_t>(row) * Sc + t;
+#pragma unroll
+      for (int i = 0; i < E; ++i) op[T * i] = v[i];
+    }
   }
   float2 *rowtw = ROWTW ? slot + XS - 16 : slot;
 #pragma unroll 1
@@ -2234,6 +2239,7 @@ hipError_t launch_rows1d(const float2 *src, long nodes, int Sr, int Sc, const Ro
                          const float2 *tw, int tw_n, hipStream_t st, bool half_rows) {
   if (nodes <= 0 || a.n <= 0) return hipSuccess;
   if (half_rows && !rows1d_half_supported(Sr, Sc)) return hipErrorInvalidValue;
+  if (a.spec_out != nullptr && (half_rows || !rows1d_half_supported(Sr, Sc))) return hipErrorInvalidValue;
   auto is_pow2 = [](int v) { return v > 0 && (v & (v - 1)) == 0; };
   if (a.n > kRows1dMaxChildren || !is_pow2(Sr) || !is_pow2(Sc) || Sc < 2 || Sc > kTileElems ||
       tw_n % Sc != 0)

@@ -100,6 +100,9 @@ struct Rows1dChild {
 struct Rows1dArgs {
   int n;
   Rows1dChild c[kRows1dMaxChildren];
+  // null, or where the forward row spectra themselves are stored ([nodes][Sr][Sc]; may be the
+  // source: in place).  Register kernel with all rows stored only.
+  float2 *spec_out = nullptr;
 };
 // half_rows: src holds rows 0 .. Sr/2 of every node only ([nodes][Sr/2+1][Sc], written by the
 // column pass with uc_half for real columns); the other rows are derived from them
