@@ -67,6 +67,17 @@ __device__ __forceinline__ void nt_store(float2 *p, float2 v) {
   __builtin_nontemporal_store(v.y, &p->y);
 }
 
+// The same for two adjacent complex values (16 bytes)
+typedef float scat_v4f __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void nt_store4(float2 *p, float4 v) {
+  scat_v4f x = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(x, reinterpret_cast<scat_v4f *>(p));
+}
+__device__ __forceinline__ float4 nt_load4(const float2 *p) {
+  const scat_v4f x = __builtin_nontemporal_load(reinterpret_cast<const scat_v4f *>(p));
+  return make_float4(x.x, x.y, x.z, x.w);
+}
+
 // Streaming load: the value is read exactly once.
 __device__ __forceinline__ float2 nt_load(const float2 *p) {
   return make_float2(__builtin_nontemporal_load(&p->x), __builtin_nontemporal_load(&p->y));
@@ -1068,7 +1079,7 @@ __global__ __launch_bounds__(256, 4) void k_col_pair_segs(const float2 *__restri
   float2 va[E], vb[E];
 #pragma unroll
   for (int i = 0; i < E; ++i) {
-    const float4 x = *reinterpret_cast<const float4 *>(sp + i * step);
+    const float4 x = nt_load4(sp + i * step);
     va[i] = make_float2(x.x, x.y);
     vb[i] = make_float2(x.z, x.w);
   }
@@ -1105,7 +1116,7 @@ __global__ __launch_bounds__(256, 4) void k_col_pair_segs(const float2 *__restri
     const float2 b = make_float2(0.5f * (zk.y + zn.y), 0.5f * (zn.x - zk.x));
     const float2 oa = cmul(a, cmul(wa0, ctw[i * (2 * TCp) + 2 * cp]));
     const float2 ob = cmul(b, cmul(wa1, ctw[i * (2 * TCp) + 2 * cp + 1]));
-    *reinterpret_cast<float4 *>(up + i * step) = make_float4(oa.x, oa.y, ob.x, ob.y);
+    nt_store4(up + i * step, make_float4(oa.x, oa.y, ob.x, ob.y));
   }
 }
 
