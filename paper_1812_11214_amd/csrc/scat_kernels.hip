@@ -672,7 +672,7 @@ __global__ __launch_bounds__(256, 4) void k_rows1d_reg(const float2 *__restrict_
   {
     const float2 *sp = src + static_cast<size_t>(row) * Sc + t;
 #pragma unroll
-    for (int i = 0; i < E; ++i) v[i] = sp[T * i];
+    for (int i = 0; i < E; ++i) v[i] = a.spec_out != nullptr ? sp[T * i] : nt_load(sp + T * i);
     float2 wt[E];
 #pragma unroll
     for (int k = 0; k < E; ++k) wt[k] = twl[t * k];
