@@ -384,6 +384,12 @@ __global__ __launch_bounds__(E == 32 ? 128 : 256) void k_mulfold_reg(
   fft_core<E, T, true, true>(v, t, lds + rl * (T == 1 ? E : E * (T + 1)), T + 1, 1, wt);
   if (!valid) return;
   float2 *dp = dst + ((static_cast<size_t>(s_idx) * F + f_idx) * Mr + qr) * M + t;
+  // (non-temporal where a row's T lanes write whole cache lines: the output is read much later,
+  // by another kernel; for partial lines it measured slower)
+  auto put = [](float2 *q, float2 val) {
+    if constexpr (T >= 16) nt_store(q, val);
+    else *q = val;
+  };
   if (post_tw_m > 0 && E == 16 && T >= 4 && post_tw_m == Mr * M) {
     // exp(+2 pi i qr b / (Mr M)), b = t + T i, factors into exp(2 pi i qr t / (Mr M)) (one
     // table read per lane) and exp(2 pi i qr i / (16 Mr)): 16 values per row, fetched by the
@@ -399,7 +405,7 @@ __global__ __launch_bounds__(E == 32 ? 128 : 256) void k_mulfold_reg(
       for (int i = 0; i < E; ++i) {
         float2 wb = slot[i];
         wb.y = -wb.y;
-        dp[T * i] = cmul(v[i], cmul(wa, wb));
+        put(dp + T * i, cmul(v[i], cmul(wa, wb)));
       }
     }
   } else if (post_tw_m > 0) {
@@ -409,11 +415,11 @@ __global__ __launch_bounds__(E == 32 ? 128 : 256) void k_mulfold_reg(
       const int e = static_cast<int>((static_cast<long long>(qr) * (t + T * i)) & (post_tw_m - 1));
       float2 w = tw[e * step];
       w.y = -w.y;
-      dp[T * i] = cmul(v[i], w);
+      put(dp + T * i, cmul(v[i], w));
     }
   } else {
 #pragma unroll
-    for (int i = 0; i < E; ++i) dp[T * i] = v[i];
+    for (int i = 0; i < E; ++i) put(dp + T * i, v[i]);
   }
 }
 
@@ -1199,7 +1205,7 @@ __global__ __launch_bounds__(256) void k_col_out(const float2 *__restrict__ src,
   load_twiddles<E, T>(wt, t, tw, tw_n);
   const float2 *sp = src + static_cast<size_t>(node) * MR * TC + t * TC + c;
 #pragma unroll
-  for (int i = 0; i < E; ++i) v[i] = sp[i * per];
+  for (int i = 0; i < E; ++i) v[i] = nt_load(sp + i * per);
   fft_core<E, T, true>(v, t, lds + slot * E * KS + c, KS, TC, wt);
   if (!valid) return;
   long p = node / cm.G;
@@ -1255,7 +1261,7 @@ __global__ __launch_bounds__(256, 4) void k_col_pair_low(const float2 *__restric
   float2 va[E], vb[E];
 #pragma unroll
   for (int i = 0; i < E; ++i) {
-    const float4 x = *reinterpret_cast<const float4 *>(sp + i * step);
+    const float4 x = nt_load4(sp + i * step);  // (read once)
     va[i] = make_float2(x.x, x.y);
     vb[i] = make_float2(x.z, x.w);
   }
