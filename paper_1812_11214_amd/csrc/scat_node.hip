@@ -590,7 +590,7 @@ __device__ __forceinline__ void node_body(const NodeArgs &a) {
                        kOut * kOut;
     }
 #pragma unroll
-    for (int j = 0; j < OPV; ++j) op[(OPV * ng + j) * kOut + mc] = acc[j];
+    for (int j = 0; j < OPV; ++j) __builtin_nontemporal_store(acc[j], op + (OPV * ng + j) * kOut + mc);  // (never read here)
   }
   if (a.uout == nullptr) return;
 
@@ -1008,7 +1008,7 @@ __global__ __launch_bounds__(512, 4) void k_node_half(NodeArgs a) {
                        kOut * kOut;
     }
 #pragma unroll
-    for (int j = 0; j < OPV; ++j) op[(OPV * ng + j) * kOut + mc] = acc[j];
+    for (int j = 0; j < OPV; ++j) __builtin_nontemporal_store(acc[j], op + (OPV * ng + j) * kOut + mc);  // (never read here)
   }
   if (a.uout == nullptr) return;
 
