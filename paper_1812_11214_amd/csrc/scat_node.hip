@@ -1049,7 +1049,16 @@ __global__ __launch_bounds__(512, 4) void k_node_half(NodeArgs a) {
     for (int i = 0; i < 16; ++i) {
       float2 val = vh[0][i];
       if (POLY) val = c_mul(val, w2m[(wbase + pc * T * i) & (2 * M - 1)]);
-      up[T * i] = val;
+      if constexpr (POLY) {
+        // the first octave's spectra (0.8 GB per launch) are read by a later launch, from
+        // memory in any case: kept out of the caches' way, the parents' own reads of the
+        // image's spectrum and of the tables hit more often (the later octaves' spectra fit
+        // the last-level cache and are stored the plain way)
+        __builtin_nontemporal_store(val.x, &up[T * i].x);
+        __builtin_nontemporal_store(val.y, &up[T * i].y);
+      } else {
+        up[T * i] = val;
+      }
     }
   }
   if (tid < T) {
