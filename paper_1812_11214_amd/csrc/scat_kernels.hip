@@ -2237,7 +2237,7 @@ hipError_t launch_rows1d_reg_t(const float2 *src, long rows, int Sr, const Rows1
   const long blocks = (rows + RPB - 1) / RPB;
   if (blocks <= 0 || blocks > 0x7fffffffL) return hipErrorInvalidValue;
   const size_t lds = (static_cast<size_t>(Sc) + static_cast<size_t>(RPB) * XS) * sizeof(float2);
-  const std::string name = "k_rows1d_reg<" + std::to_string(E) + ", " + std::to_string(T) + ">";
+  const std::string name = "k_rows1d_reg<" + std::to_string(E) + ", " + std::to_string(T) + (half ? ", true>" : ", false>");
   Observe ob(name.c_str(), bytes, flops, st);
   if (half)
     hipLaunchKernelGGL((k_rows1d_reg<E, T, true>), dim3(static_cast<unsigned>(blocks)), dim3(256), lds, st, src,
